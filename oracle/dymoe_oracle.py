@@ -1,0 +1,226 @@
+"""numpy-facing wrapper of the C oracle (oracle/dymoe_oracle.c).
+
+Test infrastructure only.  Every function takes and returns numpy arrays;
+bf16 / fp16 tensors travel as uint16 bit patterns.  The arithmetic lives in
+the C file; this module only marshals arguments.
+"""
+import ctypes as C
+
+import numpy as np
+
+from . import build as _build
+
+_lib = C.CDLL(_build.build())
+
+_u16p = C.POINTER(C.c_uint16)
+_u8p = C.POINTER(C.c_uint8)
+_i32p = C.POINTER(C.c_int32)
+_f64p = C.POINTER(C.c_double)
+_f32p = C.POINTER(C.c_float)
+
+
+def _ptr(a, typ):
+    return a.ctypes.data_as(typ) if a is not None else typ()
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+_lib.oracle_f32_to_f16.restype = C.c_uint16
+_lib.oracle_f32_to_f16.argtypes = [C.c_float]
+_lib.oracle_f16_to_f32.restype = C.c_float
+_lib.oracle_f16_to_f32.argtypes = [C.c_uint16]
+_lib.oracle_bf16_to_f32.restype = C.c_float
+_lib.oracle_bf16_to_f32.argtypes = [C.c_uint16]
+_lib.oracle_retention_ratio.restype = C.c_double
+_lib.oracle_retention_ratio.argtypes = [C.c_int, C.c_int, C.c_double]
+_lib.oracle_depth_schedule.restype = C.c_int
+_lib.oracle_depth_schedule.argtypes = [C.c_int, C.c_int, C.c_double, C.c_int]
+_lib.oracle_route_topk.restype = C.c_int
+_lib.oracle_route_topk.argtypes = [_u16p, _u16p, _f32p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                   C.c_int, _i32p, _f64p, _f64p, _f64p]
+_lib.oracle_token_score_norm.restype = None
+_lib.oracle_token_score_norm.argtypes = [_u16p, C.c_int, C.c_int, _f64p]
+_lib.oracle_expert_importance_prefill.restype = C.c_int
+_lib.oracle_expert_importance_prefill.argtypes = [_i32p, _f64p, C.c_int, C.c_int, C.c_int,
+                                                  C.c_int, _i32p, _i32p, _u8p]
+_lib.oracle_expert_importance_decode.restype = None
+_lib.oracle_expert_importance_decode.argtypes = [_f64p, C.c_int, C.c_int, _f64p]
+_lib.oracle_assign_precision.restype = C.c_int
+_lib.oracle_assign_precision.argtypes = [_f64p, _i32p, C.c_int, C.c_int, _i32p, _u8p, C.c_int,
+                                         _u8p, _i32p]
+_lib.oracle_quantize_pack.restype = C.c_int
+_lib.oracle_quantize_pack.argtypes = [_u16p, C.c_long, C.c_long, C.c_int, C.c_int, _u8p, _u16p,
+                                      _u16p]
+_lib.oracle_dequantize.restype = None
+_lib.oracle_dequantize.argtypes = [_u8p, _u16p, _u16p, C.c_long, C.c_long, C.c_int, C.c_int,
+                                   _f64p]
+_pp = C.POINTER(C.c_void_p)
+_lib.oracle_moe_ffn_mixed.restype = C.c_int
+_lib.oracle_moe_ffn_mixed.argtypes = [_u16p, _i32p, _f64p, _u8p, _pp, _pp, _pp, _pp, C.c_int,
+                                      C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _f64p]
+
+
+def f32_to_f16(v: float) -> int:
+    return int(_lib.oracle_f32_to_f16(float(v)))
+
+
+def f16_to_f32(bits: int) -> float:
+    return float(_lib.oracle_f16_to_f32(int(bits)))
+
+
+def bf16_to_f32(bits: int) -> float:
+    return float(_lib.oracle_bf16_to_f32(int(bits)))
+
+
+def retention_ratio(layer, n_layers, lam):
+    return float(_lib.oracle_retention_ratio(layer, n_layers, lam))
+
+
+def depth_schedule(layer, n_layers, lam, M):
+    return int(_lib.oracle_depth_schedule(layer, n_layers, lam, M))
+
+
+def route_topk(x_bits, wg_bits, bias, k, renorm=True):
+    """x [T,H], wg [E,H] as bf16 bit patterns (uint16); bias [E] float32 or None.
+    Returns idx [T,k] int32, w [T,k] f64, probs [T,E] f64, logits [T,E] f64."""
+    x = _c(x_bits, np.uint16)
+    wg = _c(wg_bits, np.uint16)
+    T, H = x.shape
+    E = wg.shape[0]
+    assert wg.shape[1] == H
+    b = _c(bias, np.float32) if bias is not None else None
+    idx = np.zeros((T, k), np.int32)
+    w = np.zeros((T, k), np.float64)
+    probs = np.zeros((T, E), np.float64)
+    logits = np.zeros((T, E), np.float64)
+    rc = _lib.oracle_route_topk(_ptr(x, _u16p), _ptr(wg, _u16p), _ptr(b, _f32p), T, H, E, k,
+                                1 if renorm else 0, _ptr(idx, _i32p), _ptr(w, _f64p),
+                                _ptr(probs, _f64p), _ptr(logits, _f64p))
+    if rc != 0:
+        raise ValueError("oracle_route_topk rc=%d" % rc)
+    return idx, w, probs, logits
+
+
+def token_score_norm(x_bits):
+    x = _c(x_bits, np.uint16)
+    T, H = x.shape
+    s = np.zeros(T, np.float64)
+    _lib.oracle_token_score_norm(_ptr(x, _u16p), T, H, _ptr(s, _f64p))
+    return s
+
+
+def expert_importance_prefill(idx, score, E, k_hh):
+    """Returns importance [E] int32, load [E] int32, heavy [T] uint8."""
+    idx = _c(idx, np.int32)
+    T, k = idx.shape
+    score = _c(score, np.float64)
+    assert score.shape == (T,)
+    imp = np.zeros(E, np.int32)
+    load = np.zeros(E, np.int32)
+    heavy = np.zeros(max(T, 1), np.uint8)
+    rc = _lib.oracle_expert_importance_prefill(_ptr(idx, _i32p), _ptr(score, _f64p), T, E, k,
+                                               k_hh, _ptr(imp, _i32p), _ptr(load, _i32p),
+                                               _ptr(heavy, _u8p))
+    if rc != 0:
+        raise ValueError("oracle_expert_importance_prefill rc=%d" % rc)
+    return imp, load, heavy[:T]
+
+
+def expert_importance_decode(probs):
+    probs = _c(probs, np.float64)
+    T, E = probs.shape
+    imp = np.zeros(E, np.float64)
+    _lib.oracle_expert_importance_decode(_ptr(probs, _f64p), T, E, _ptr(imp, _f64p))
+    return imp
+
+
+def assign_precision(importance, load, tier_count, tier_bits, floor_bits=0):
+    """Returns bits [E] uint8, rank [E] int32."""
+    imp = _c(importance, np.float64)
+    E = imp.shape[0]
+    ld = _c(load, np.int32) if load is not None else None
+    tc = _c(tier_count, np.int32)
+    tb = _c(tier_bits, np.uint8)
+    bits = np.zeros(E, np.uint8)
+    rank = np.zeros(E, np.int32)
+    rc = _lib.oracle_assign_precision(_ptr(imp, _f64p), _ptr(ld, _i32p), E, len(tc),
+                                      _ptr(tc, _i32p), _ptr(tb, _u8p), floor_bits,
+                                      _ptr(bits, _u8p), _ptr(rank, _i32p))
+    if rc != 0:
+        raise ValueError("oracle_assign_precision rc=%d" % rc)
+    return bits, rank
+
+
+def quantize_pack(w_bits, bits, group=64):
+    """w [N,K] bf16 bit patterns.  Returns codes [N,K*bits/8] uint8,
+    scale [N,K/group] and zero [N,K/group] as fp16 bit patterns (uint16)."""
+    w = _c(w_bits, np.uint16)
+    N, K = w.shape
+    codes = np.zeros((N, K * bits // 8), np.uint8)
+    scale = np.zeros((N, K // group), np.uint16)
+    zero = np.zeros((N, K // group), np.uint16)
+    rc = _lib.oracle_quantize_pack(_ptr(w, _u16p), N, K, bits, group, _ptr(codes, _u8p),
+                                   _ptr(scale, _u16p), _ptr(zero, _u16p))
+    if rc != 0:
+        raise ValueError("oracle_quantize_pack rc=%d" % rc)
+    return codes, scale, zero
+
+
+def dequantize(codes, scale, zero, bits, group=64):
+    codes = _c(codes, np.uint8)
+    scale = _c(scale, np.uint16)
+    zero = _c(zero, np.uint16)
+    N = codes.shape[0]
+    K = codes.shape[1] * 8 // bits
+    out = np.zeros((N, K), np.float64)
+    _lib.oracle_dequantize(_ptr(codes, _u8p), _ptr(scale, _u16p), _ptr(zero, _u16p), N, K, bits,
+                           group, _ptr(out, _f64p))
+    return out
+
+
+def moe_ffn_mixed(x_bits, idx, w, bits, experts, group=64):
+    """experts: list of E dicts; expert e holds, for the precision bits[e],
+    either 'w' = (W1,W3,W2) bf16 bit arrays, or 'q' = three (codes, scale, zero)
+    triples as produced by quantize_pack.  Returns y [T,H] f64."""
+    x = _c(x_bits, np.uint16)
+    idx = _c(idx, np.int32)
+    w = _c(w, np.float64)
+    bits = _c(bits, np.uint8)
+    T, H = x.shape
+    k = idx.shape[1]
+    E = len(experts)
+    keep = []
+    tabs = [(C.c_void_p * (3 * E))() for _ in range(4)]
+    F = None
+    for e, ex in enumerate(experts):
+        b = int(bits[e])
+        if b == 16:
+            mats = [_c(m, np.uint16) for m in ex["w"]]
+            keep.append(mats)
+            F = mats[0].shape[0]
+            assert mats[0].shape == (F, H) and mats[1].shape == (F, H) and mats[2].shape == (H, F)
+            for i in range(3):
+                tabs[0][3 * e + i] = mats[i].ctypes.data
+        elif b in (8, 4, 2):
+            for i in range(3):
+                cd, sc, zr = ex["q"][i] if "q" in ex else ex["q%d" % b][i]
+                cd, sc, zr = _c(cd, np.uint8), _c(sc, np.uint16), _c(zr, np.uint16)
+                keep.append((cd, sc, zr))
+                tabs[1][3 * e + i] = cd.ctypes.data
+                tabs[2][3 * e + i] = sc.ctypes.data
+                tabs[3][3 * e + i] = zr.ctypes.data
+                if i == 0:
+                    F = cd.shape[0]
+        elif b != 0:
+            raise ValueError("bits[%d]=%d" % (e, b))
+    if F is None:
+        raise ValueError("no expert with a non-zero precision")
+    y = np.zeros((T, H), np.float64)
+    rc = _lib.oracle_moe_ffn_mixed(_ptr(x, _u16p), _ptr(idx, _i32p), _ptr(w, _f64p),
+                                   _ptr(bits, _u8p), tabs[0], tabs[1], tabs[2], tabs[3], T, H, F,
+                                   E, k, group, _ptr(y, _f64p))
+    if rc != 0:
+        raise ValueError("oracle_moe_ffn_mixed rc=%d" % rc)
+    return y

@@ -1,0 +1,475 @@
+"""Pins for the CPU oracle: closed forms, invariants, brute force and special
+cases that reduce to a numpy routine.  None of these re-types the oracle's own
+formula; each is chosen so that a dropped term, a wrong sign or index, or a
+transposed operand in the oracle fails at least one of them."""
+import itertools
+import os
+from decimal import Decimal, getcontext
+
+import numpy as np
+import pytest
+
+from oracle import dymoe_oracle as O
+from paper_2603_19172_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def bf16(a):
+    return synth.f32_to_bf16_bits(np.asarray(a, np.float32))
+
+
+def widen(b):
+    return synth.bf16_bits_to_f32(b).astype(np.float64)
+
+
+# --------------------------------------------------------------------- formats
+
+def test_fp16_conversion_matches_numpy():
+    rng = np.random.default_rng(1)
+    vals = np.concatenate([
+        rng.standard_normal(4000).astype(np.float32) * np.float32(0.02),
+        rng.standard_normal(2000).astype(np.float32) * np.float32(1e-6),   # fp16 subnormals
+        rng.standard_normal(2000).astype(np.float32) * np.float32(3e4),    # near overflow
+        np.array([0.0, -0.0, 65504.0, 65519.99, 65520.0, 1e9, -1e9, 2.0 ** -24, 2.0 ** -25,
+                  1.5 * 2.0 ** -25, 2.0 ** -14, 2.0 ** -14 - 2.0 ** -26, 1.0 + 2.0 ** -11,
+                  1.0 + 3 * 2.0 ** -11, 1e-45], np.float32),
+    ])
+    with np.errstate(over="ignore"):
+        ref = vals.astype(np.float16).view(np.uint16)
+    got = np.array([O.f32_to_f16(v) for v in vals], np.uint16)
+    assert np.array_equal(ref, got)
+    # and back, over every finite fp16 bit pattern
+    allh = np.arange(0, 0x10000, dtype=np.uint32).astype(np.uint16)
+    fin = np.isfinite(allh.view(np.float16))
+    back = np.array([O.f16_to_f32(int(h)) for h in allh[fin]], np.float32)
+    assert np.array_equal(back.view(np.uint32), allh[fin].view(np.float16).astype(np.float32).view(np.uint32))
+
+
+def test_bf16_widening():
+    assert O.bf16_to_f32(0x3F80) == 1.0
+    assert O.bf16_to_f32(0xC000) == -2.0
+    assert O.bf16_to_f32(0x3C00) == 2.0 ** -7
+
+
+# --------------------------------------------------------------------- routing
+
+def _route_inputs(T, H, E, seed, bias=False):
+    rng = np.random.default_rng(seed)
+    x = bf16(rng.standard_normal((T, H)))
+    wg = bf16(rng.standard_normal((E, H)) * 0.1)
+    b = rng.standard_normal(E).astype(np.float32) if bias else None
+    return x, wg, b
+
+
+def test_route_hand_example():
+    # x = (1, 2); experts (1,0), (0,1), (1,1), (0,0): logits 1, 2, 3, 0
+    x = bf16([[1.0, 2.0]])
+    wg = bf16([[1, 0], [0, 1], [1, 1], [0, 0]])
+    idx, w, p, lg = O.route_topk(x, wg, None, k=2, renorm=True)
+    assert lg.tolist() == [[1.0, 2.0, 3.0, 0.0]]
+    den = np.e ** 1 + np.e ** 2 + np.e ** 3 + 1.0
+    assert np.allclose(p[0], np.array([np.e, np.e ** 2, np.e ** 3, 1.0]) / den, rtol=1e-14)
+    assert idx.tolist() == [[2, 1]]
+    # renormalised over the two chosen: e^3/(e^3+e^2) = 1/(1+1/e)
+    assert np.allclose(w[0], [1 / (1 + np.e ** -1), 1 / (1 + np.e)], rtol=1e-14)
+    _, w2, _, _ = O.route_topk(x, wg, None, k=2, renorm=False)
+    assert np.allclose(w2[0], p[0][[2, 1]], rtol=1e-15)
+
+
+def test_route_against_numpy_sort_and_brute_force():
+    for seed, (T, H, E, k, bias) in enumerate([(5, 32, 8, 2, False), (7, 64, 6, 3, True),
+                                               (3, 16, 40, 8, True)]):
+        x, wg, b = _route_inputs(T, H, E, seed, bias)
+        idx, w, p, lg = O.route_topk(x, wg, b, k=k, renorm=True)
+        ref_l = widen(x) @ widen(wg).T + (b.astype(np.float64) if b is not None else 0.0)
+        assert np.allclose(lg, ref_l, rtol=1e-12, atol=1e-12)
+        assert np.allclose(p.sum(1), 1.0, rtol=1e-13)
+        assert np.allclose(w.sum(1), 1.0, rtol=1e-13)
+        order = np.argsort(-lg, axis=1, kind="stable")[:, :k]
+        assert np.array_equal(order, idx)
+        # softmax is monotone in the logit and shift invariant
+        assert np.allclose(np.log(p) - np.log(p[:, :1]), lg - lg[:, :1], atol=1e-11)
+        if E <= 8:  # brute force: the chosen set maximises the total probability
+            for t in range(T):
+                best = max(itertools.combinations(range(E), k), key=lambda s: p[t, list(s)].sum())
+                assert set(best) == set(idx[t].tolist())
+
+
+def test_route_ties_and_permutation():
+    # two identical experts: the lower index comes first
+    x = bf16([[1.0, -1.0, 0.5, 2.0]])
+    row = [0.5, 0.25, 1.0, 0.125]          # logit 1; the zero row has logit 0
+    wg = bf16([row, [0, 0, 0, 0], row])
+    idx, w, p, _ = O.route_topk(x, wg, None, k=2)
+    assert idx.tolist() == [[0, 2]]
+    assert w[0, 0] == w[0, 1] == 0.5
+    idx, _, _, _ = O.route_topk(x, bf16([[0, 0, 0, 0], row, row, [0, 0, 0, 0]]), None, k=3)
+    assert idx.tolist() == [[1, 2, 0]]
+    # permuting the experts permutes the indices
+    x, wg, b = _route_inputs(6, 48, 8, 11, True)
+    idx, w, p, lg = O.route_topk(x, wg, b, k=3)
+    perm = np.random.default_rng(3).permutation(8)
+    idx2, w2, p2, _ = O.route_topk(x, wg[perm], b[perm], k=3)
+    assert np.array_equal(perm[idx2], idx)
+    assert np.allclose(w2, w, rtol=1e-13)
+    assert np.allclose(p2, p[:, perm], rtol=1e-13)
+
+
+# ------------------------------------------------------------------ importance
+
+def test_importance_hand_example():
+    # 4 tokens, 3 experts, top-2 routing; scores make tokens 2 and 0 the heavy hitters
+    idx = np.array([[0, 1], [1, 2], [2, 0], [1, 0]], np.int32)
+    score = np.array([5.0, 1.0, 9.0, 2.0])
+    imp, load, heavy = O.expert_importance_prefill(idx, score, E=3, k_hh=2)
+    assert heavy.tolist() == [1, 0, 1, 0]
+    assert imp.tolist() == [2, 1, 1]      # token0 -> {0,1}, token2 -> {2,0}
+    assert load.tolist() == [3, 3, 2]
+    # score ties go to the lower token index
+    imp, _, heavy = O.expert_importance_prefill(idx, np.array([1.0, 1.0, 1.0, 1.0]), E=3, k_hh=1)
+    assert heavy.tolist() == [1, 0, 0, 0] and imp.tolist() == [1, 1, 0]
+
+
+def test_importance_invariants_and_bincount():
+    rng = np.random.default_rng(5)
+    T, E, k, k_hh = 200, 16, 4, 17
+    idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    score = rng.standard_normal(T) ** 2
+    imp, load, heavy = O.expert_importance_prefill(idx, score, E=E, k_hh=k_hh)
+    assert imp.sum() == k * k_hh and load.sum() == k * T and heavy.sum() == k_hh
+    assert np.array_equal(load, np.bincount(idx.ravel(), minlength=E))
+    top = np.argsort(-score, kind="stable")[:k_hh]
+    assert set(np.nonzero(heavy)[0].tolist()) == set(top.tolist())
+    assert np.array_equal(imp, np.bincount(idx[top].ravel(), minlength=E))
+    # every token heavy: importance is the token-frequency count (total load)
+    imp_all, load_all, _ = O.expert_importance_prefill(idx, score, E=E, k_hh=T)
+    assert np.array_equal(imp_all, load_all)
+    imp0, _, _ = O.expert_importance_prefill(idx, score, E=E, k_hh=0)
+    assert imp0.sum() == 0
+
+
+def test_importance_decode_is_gate_score():
+    p = np.array([[0.1, 0.6, 0.3]])
+    assert np.array_equal(O.expert_importance_decode(p), p[0])
+    p2 = np.array([[0.1, 0.6, 0.3], [0.5, 0.2, 0.3]])
+    assert np.allclose(O.expert_importance_decode(p2), [0.3, 0.4, 0.3], rtol=1e-15)
+
+
+def test_token_score_norm():
+    rng = np.random.default_rng(2)
+    x = bf16(rng.standard_normal((9, 130)) * 3)
+    assert np.allclose(O.token_score_norm(x), np.linalg.norm(widen(x), axis=1), rtol=1e-14)
+
+
+# -------------------------------------------------------------------- schedule
+
+def _dec_cos(x: Decimal) -> Decimal:
+    # Taylor series at 60 digits; independent of libm
+    getcontext().prec = 60
+    term, s, n = Decimal(1), Decimal(1), 0
+    while abs(term) > Decimal(10) ** -55:
+        n += 2
+        term = -term * x * x / (n * (n - 1))
+        s += term
+    return s
+
+
+PI = Decimal("3.14159265358979323846264338327950288419716939937510582097494")
+
+
+def test_schedule_golden_tables():
+    for line in open(os.path.join(GOLDEN, "schedule_tables.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = line.split()
+        L, M, lam = int(f[0]), int(f[1]), float(f[2])
+        want = [int(v) for v in f[3:]]
+        assert [O.depth_schedule(l, L, lam, M) for l in range(L)] == want, line
+
+
+def test_schedule_closed_forms():
+    for L in (2, 5, 32, 48):
+        for lam in (0.0, 0.25, 0.5, 0.8, 1.0):
+            r = [O.retention_ratio(l, L, lam) for l in range(L)]
+            assert r[0] == 1.0 and abs(r[-1] - lam) < 1e-15
+            assert all(r[i] >= r[i + 1] - 1e-15 for i in range(L - 1))
+            assert abs(sum(r) / L - (1 + lam) / 2) < 1e-13   # cosine term is odd about the middle
+    assert O.retention_ratio(0, 1, 0.3) == 1.0
+    # slow start: the first quarter of a 32-layer stack keeps > 92% at lambda = 0.5
+    assert O.retention_ratio(8, 32, 0.5) > 0.92
+
+
+def test_schedule_against_high_precision_ceiling():
+    getcontext().prec = 60
+    for L in (4, 7, 13, 32, 61):
+        for M in (8, 60, 128):
+            for lam_s in ("0.5", "0.8", "0.25", "0.9"):
+                lam = Decimal(lam_s)
+                for l in range(L):
+                    c = _dec_cos(PI * l / (L - 1))
+                    v = ((1 - lam) * (c + 1) / 2 + lam) * M
+                    near = v.quantize(Decimal(1))
+                    exact = int(near) if abs(v - near) < Decimal("1e-40") else int(v.to_integral_value(rounding="ROUND_CEILING"))
+                    exact = min(max(exact, 1), M)
+                    assert O.depth_schedule(l, L, float(lam), M) == exact, (L, M, lam_s, l)
+
+
+def test_schedule_rejects_bad_arguments():
+    assert O.depth_schedule(4, 4, 0.5, 8) < 0
+    assert O.depth_schedule(0, 4, 1.5, 8) < 0
+    assert O.depth_schedule(0, 4, 0.5, 0) < 0
+
+
+# ------------------------------------------------------------------ assignment
+
+def test_assign_hand_example():
+    imp = [3, 7, 3, 0, 7, 1]
+    load = [10, 2, 12, 5, 9, 5]
+    bits, rank = O.assign_precision(imp, load, tier_count=[1, 2, 3], tier_bits=[16, 4, 2])
+    # order: e4 (7, load 9), e1 (7, load 2), e2 (3, load 12), e0 (3, load 10), e5, e3
+    assert rank.tolist() == [3, 1, 2, 5, 0, 4]
+    assert bits.tolist() == [2, 4, 4, 2, 16, 2]
+    bits, _ = O.assign_precision(imp, load, [1, 2, 3], [16, 4, 2], floor_bits=4)
+    assert bits.tolist() == [4, 4, 4, 4, 16, 4]
+    # full ties fall back to the expert index
+    bits, rank = O.assign_precision([1, 1, 1], [2, 2, 2], [1, 1, 1], [16, 4, 0])
+    assert rank.tolist() == [0, 1, 2] and bits.tolist() == [16, 4, 0]
+    with pytest.raises(ValueError):
+        O.assign_precision(imp, load, [1, 2, 2], [16, 4, 2])
+
+
+def test_assign_invariants():
+    rng = np.random.default_rng(8)
+    E = 128
+    imp = rng.integers(0, 6, E)
+    load = rng.integers(0, 50, E)
+    tc, tb = [13, 39, 76], [16, 4, 2]
+    bits, rank = O.assign_precision(imp, load, tc, tb)
+    assert sorted(rank.tolist()) == list(range(E))
+    assert [(bits == b).sum() for b in tb] == tc
+    # monotone: strictly more important never gets fewer bits
+    for a in range(E):
+        for b in range(E):
+            if imp[a] > imp[b]:
+                assert bits[a] >= bits[b]
+    # reference ordering by lexsort (last key is primary)
+    order = np.lexsort((np.arange(E), -load, -imp))
+    assert np.array_equal(np.argsort(rank), order)
+    # permutation equivariance (keys made distinct so that the index tie-break is idle)
+    imp_d = imp * 1000 + rng.permutation(E)
+    bits_d, _ = O.assign_precision(imp_d, load, tc, tb)
+    perm = rng.permutation(E)
+    bits_p, _ = O.assign_precision(imp_d[perm], load[perm], tc, tb)
+    assert np.array_equal(bits_p, bits_d[perm])
+    # paper mode: two tiers, t_l critical experts
+    t = O.depth_schedule(20, 32, 0.5, E)
+    b2, _ = O.assign_precision(imp_d, load, [t, E - t], [4, 2])
+    assert (b2 == 4).sum() == t and set(np.argsort(-imp_d)[:t].tolist()) == set(np.nonzero(b2 == 4)[0].tolist())
+
+
+# ---------------------------------------------------------------- quantization
+
+def _unpack(codes, bits):
+    """Brute-force bit unpacking, one code at a time."""
+    N, B = codes.shape
+    per = 8 // bits
+    out = np.zeros((N, B * per), np.int64)
+    for n in range(N):
+        for j in range(B):
+            byte = int(codes[n, j])
+            for i in range(per):
+                out[n, j * per + i] = (byte >> (bits * i)) & ((1 << bits) - 1)
+    return out
+
+
+def f16(bits_arr):
+    return np.asarray(bits_arr, np.uint16).view(np.float16).astype(np.float64)
+
+
+def test_pack_hand_bytes():
+    # one group, scale 1, zero 0 -> codes are the values themselves
+    row4 = np.array([[1, 2, 3, 4] + [0] * 59 + [15]], np.float32)
+    codes, sc, zr = O.quantize_pack(bf16(row4), 4)
+    assert f16(sc)[0, 0] == 1.0 and f16(zr)[0, 0] == 0.0
+    assert codes[0, :2].tolist() == [0x21, 0x43] and codes[0, 31] == 0xF0
+    row2 = np.array([[1, 2, 3, 0] + [0] * 59 + [3]], np.float32)
+    codes, sc, zr = O.quantize_pack(bf16(row2), 2)
+    assert f16(sc)[0, 0] == 1.0 and f16(zr)[0, 0] == 0.0
+    assert codes[0, 0] == 0x39 and codes[0, 15] == 0xC0
+
+
+def test_quantize_exact_cases():
+    g = np.tile(np.arange(16, dtype=np.float32), 4)[None, :]
+    codes, sc, zr = O.quantize_pack(bf16(g), 4)
+    assert f16(sc)[0, 0] == 1.0 and f16(zr)[0, 0] == 0.0
+    assert np.array_equal(_unpack(codes, 4)[0], g[0].astype(np.int64))
+    assert np.array_equal(O.dequantize(codes, sc, zr, 4), g.astype(np.float64))
+    codes, sc, zr = O.quantize_pack(bf16(g), 2)
+    assert f16(sc)[0, 0] == 5.0
+    assert _unpack(codes, 2)[0, :16].tolist() == [0, 0, 0, 1, 1, 1, 1, 1, 2, 2, 2, 2, 2, 3, 3, 3]
+    # shifted and negative: zero = group minimum
+    g2 = g * 0.5 - 3.0
+    codes, sc, zr = O.quantize_pack(bf16(g2), 4)
+    assert f16(sc)[0, 0] == 0.5 and f16(zr)[0, 0] == -3.0
+    assert np.array_equal(O.dequantize(codes, sc, zr, 4), g2.astype(np.float64))
+    # constant and all-zero groups: scale 0, codes 0, decode exact
+    for v in (0.0, 0.75, -1.5):
+        c = np.full((2, 128), v, np.float32)
+        for b in (2, 4):
+            codes, sc, zr = O.quantize_pack(bf16(c), b)
+            assert not codes.any() and not sc.any()
+            assert np.array_equal(O.dequantize(codes, sc, zr, b), c.astype(np.float64))
+    # ties round to even: values 0, .5, 1.5, 2.5 with scale 1 (max 15)
+    t = np.zeros((1, 64), np.float32)
+    t[0, :5] = [0.5, 1.5, 2.5, 3.5, 15.0]
+    codes, sc, zr = O.quantize_pack(bf16(t), 4)
+    assert _unpack(codes, 4)[0, :5].tolist() == [0, 2, 2, 4, 15]
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_quantize_round_trip_bound_and_independent_codes(bits):
+    cfg = synth.CONFIGS["tiny"]
+    w = synth.expert_weights(cfg, 0)[0]                    # [512,256] ~ N(0, 0.02)
+    qmax = (1 << bits) - 1
+    codes, sc, zr = O.quantize_pack(w, bits)
+    q = _unpack(codes, bits)
+    wf = widen(w)
+    N, K = wf.shape
+    G = K // 64
+    s = np.repeat(f16(sc), 64, axis=1)
+    m = np.repeat(f16(zr), 64, axis=1)
+    grp = wf.reshape(N, G, 64)
+    # stored zero is the group minimum (bf16 values of this size are fp16-exact)
+    assert np.array_equal(f16(zr), grp.min(2))
+    # stored scale is fp16((max-min)/qmax): numpy's own rounding of the exact quotient
+    assert np.array_equal(f16(sc), ((grp.max(2) - grp.min(2)) / qmax).astype(np.float32).astype(np.float16).astype(np.float64))
+    # dequantised values come from s*q + m
+    deq = O.dequantize(codes, sc, zr, bits)
+    assert np.array_equal(deq, s * q + m)
+    # round-to-nearest error bound, min -> 0, max -> qmax
+    assert np.all(np.abs(wf - deq) <= 0.5 * s * (1 + 2.0 ** -18))
+    assert np.all(q.reshape(N, G, 64)[np.arange(N)[:, None], np.arange(G)[None, :], grp.argmin(2)] == 0)
+    assert np.all(q.reshape(N, G, 64)[np.arange(N)[:, None], np.arange(G)[None, :], grp.argmax(2)] == qmax)
+    # codes equal the fp64 rounding except within 1e-5 of a .5 tie
+    exact = (wf - m) / s
+    clear = np.abs(exact - np.floor(exact) - 0.5) > 1e-5
+    assert clear.mean() > 0.99
+    assert np.array_equal(q[clear], np.clip(np.rint(exact), 0, qmax).astype(np.int64)[clear])
+
+
+def test_quantize_subnormal_scale_and_ragged_group_rejection():
+    # range so small that the fp16 scale is subnormal
+    w = np.zeros((1, 64), np.float32)
+    w[0, 1] = 2.0 ** -20
+    codes, sc, zr = O.quantize_pack(bf16(w), 4)
+    s = f16(sc)[0, 0]
+    assert 0 < s < 2.0 ** -14
+    # 2^-20 / 15 lies between 1 and 2 fp16 subnormal units and rounds to 1 unit, so the
+    # largest element (16 units) saturates at code 15; the upper clamp is what keeps it legal
+    assert s == 2.0 ** -24
+    q = _unpack(codes, 4)[0]
+    assert q[1] == 15 and q.sum() == 15
+    assert O.dequantize(codes, sc, zr, 4)[0, 1] == 15 * 2.0 ** -24
+    with pytest.raises(ValueError):
+        O.quantize_pack(bf16(np.zeros((1, 96), np.float32)), 4, group=64)
+
+
+# ------------------------------------------------------------------------- FFN
+
+def _silu(a):
+    return a / (1.0 + np.exp(-a))
+
+
+def _tiny_layer(E=4, T=5, H=64, F=128, k=2, seed=0):
+    rng = np.random.default_rng(seed)
+    x = bf16(rng.standard_normal((T, H)))
+    ws = [[bf16(rng.standard_normal(s) * 0.05) for s in ((F, H), (F, H), (H, F))] for _ in range(E)]
+    idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    g = rng.random((T, k)) + 0.1
+    g /= g.sum(1, keepdims=True)
+    return x, ws, idx, g
+
+
+def _numpy_moe(x, mats64, idx, g, skip=()):
+    """MoE with fp64 weight matrices through numpy matmul."""
+    xf = widen(x)
+    T, H = xf.shape
+    y = np.zeros((T, H))
+    for t in range(T):
+        for s in range(idx.shape[1]):
+            e = int(idx[t, s])
+            if e in skip:
+                continue
+            w1, w3, w2 = mats64[e]
+            y[t] += g[t, s] * (w2 @ (_silu(w1 @ xf[t]) * (w3 @ xf[t])))
+    return y
+
+
+def test_ffn_all_bf16_is_plain_moe_and_dense_mlp():
+    x, ws, idx, g = _tiny_layer()
+    E = len(ws)
+    y = O.moe_ffn_mixed(x, idx, g, np.full(E, 16, np.uint8), [{"w": w} for w in ws])
+    ref = _numpy_moe(x, [[widen(m) for m in w] for w in ws], idx, g)
+    assert np.allclose(y, ref, rtol=1e-11, atol=1e-13)
+    # one expert, k = 1, weight 1: a dense SwiGLU MLP
+    idx1 = np.zeros((x.shape[0], 1), np.int32)
+    y1 = O.moe_ffn_mixed(x, idx1, np.ones((x.shape[0], 1)), np.array([16], np.uint8), [{"w": ws[0]}])
+    w1, w3, w2 = [widen(m) for m in ws[0]]
+    xf = widen(x)
+    assert np.allclose(y1, (_silu(xf @ w1.T) * (xf @ w3.T)) @ w2.T, rtol=1e-11, atol=1e-13)
+
+
+def test_ffn_mixed_precisions_use_dequantised_weights():
+    x, ws, idx, g = _tiny_layer(E=4, seed=3)
+    bits = np.array([16, 4, 2, 4], np.uint8)
+    experts, mats = [], []
+    for e, w in enumerate(ws):
+        if bits[e] == 16:
+            experts.append({"w": w})
+            mats.append([widen(m) for m in w])
+        else:
+            q = [O.quantize_pack(m, int(bits[e])) for m in w]
+            experts.append({"q": q})
+            # weights rebuilt from brute-force unpacked codes, not from the oracle's dequantiser
+            mats.append([np.repeat(f16(sc), 64, 1) * _unpack(cd, int(bits[e])) + np.repeat(f16(zr), 64, 1)
+                         for cd, sc, zr in q])
+    y = O.moe_ffn_mixed(x, idx, g, bits, experts)
+    ref = _numpy_moe(x, mats, idx, g)
+    assert np.allclose(y, ref, rtol=1e-11, atol=1e-13)
+    # int2 is visibly different from bf16, so the precision switch is live
+    y16 = O.moe_ffn_mixed(x, idx, g, np.full(4, 16, np.uint8), [{"w": w} for w in ws])
+    assert np.abs(y - y16).max() > 1e-3 * np.abs(y16).max()
+
+
+def test_ffn_zero_bit_skip_linearity_and_zero_gate():
+    x, ws, idx, g = _tiny_layer(E=4, seed=5)
+    experts = [{"w": w} for w in ws]
+    mats = [[widen(m) for m in w] for w in ws]
+    bits = np.array([16, 0, 16, 16], np.uint8)
+    y = O.moe_ffn_mixed(x, idx, g, bits, experts)
+    assert np.allclose(y, _numpy_moe(x, mats, idx, g, skip={1}), rtol=1e-11, atol=1e-13)
+    # linear in the gate weights
+    all16 = np.full(4, 16, np.uint8)
+    ya = O.moe_ffn_mixed(x, idx, g, all16, experts)
+    yb = O.moe_ffn_mixed(x, idx, 3.0 * g, all16, experts)
+    assert np.allclose(yb, 3.0 * ya, rtol=1e-12)
+    # W1 = 0 -> silu(0) = 0 -> y = 0
+    zeroed = [{"w": [np.zeros_like(w[0]), w[1], w[2]]} for w in ws]
+    assert not O.moe_ffn_mixed(x, idx, g, all16, zeroed).any()
+
+
+def test_synth_configs_shapes():
+    cfg = synth.CONFIGS["tiny"]
+    x, heavy = synth.activations(cfg)
+    assert x.shape == (16, 256) and x.dtype == np.uint16 and heavy.size == 0
+    c3 = synth.scaled(synth.CONFIGS["mixtral_prefill"], H=128, F=256)
+    x3, heavy3 = synth.activations(c3)
+    n = np.linalg.norm(widen(x3), axis=1)
+    assert heavy3.size == 26 and set(np.argsort(-n)[:26].tolist()) == set(heavy3.tolist())
+    wg, bias = synth.router(synth.CONFIGS["fine_grained"])
+    assert wg.shape == (128, 2048) and bias.shape == (128,) and bias.max() == 0.0
+    assert abs(widen(wg).std() - 0.02) < 1e-3
+    # same key, same bytes
+    assert np.array_equal(synth.expert_weights(cfg, 3)[2], synth.expert_weights(cfg, 3)[2])
+    assert sum(synth.CONFIGS["fine_grained"].tier_count) == 128

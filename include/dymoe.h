@@ -1,0 +1,219 @@
+/*
+ * libdymoe: one Mixture-of-Experts layer under dynamic mixed precision
+ * (DyMoE), hand-written HIP for AMD gfx950, behind a plain C ABI.
+ *
+ * Pipeline of one layer (paper Sec. 4.1, steps 1-4 of the system overview):
+ *   dymoe_route_topk        router gating and top-k
+ *   dymoe_expert_importance per-expert importance (prefill: heavy-hitter token
+ *                           load; decode: gate score)
+ *   dymoe_assign_precision  importance- and depth-based bit-width per expert
+ *   dymoe_quantize_pack /   group-wise quantize-and-pack of expert weights
+ *   dymoe_quantize_experts
+ *   dymoe_moe_ffn_mixed     dequant-fused SwiGLU expert FFN over experts of
+ *                           differing precisions
+ *
+ * Conventions that hold for every call unless a comment says otherwise:
+ *  - Every pointer is a DEVICE pointer; arguments marked "host" are host
+ *    pointers that are read before the call returns.
+ *  - The caller allocates and owns every buffer.  The library never allocates
+ *    or frees device memory and keeps no pointer after the call returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue work and return without synchronising; nothing is read
+ *    back to the host, so the five steps chain on one stream with no host
+ *    round trip.
+ *  - bf16 and fp16 tensors are raw 16-bit patterns.  Matrices are row-major
+ *    with the contraction ("in") dimension contiguous: W1, W3 are [F,H],
+ *    W2 is [H,F], the router weight is [E,H].
+ *  - Return value: 0 on success, a negative DYMOE_E* code otherwise.
+ *    Arguments are validated before any GPU work is issued; a failing call
+ *    has enqueued nothing.
+ */
+#ifndef DYMOE_H
+#define DYMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DYMOE_OK 0
+#define DYMOE_EINVAL (-1)  /* bad argument: null pointer, bad size, bad bit width, misaligned */
+#define DYMOE_ENOSPC (-2)  /* workspace too small */
+#define DYMOE_EHIP (-3)    /* a HIP runtime call failed */
+#define DYMOE_ENOTSUP (-4) /* valid in principle, outside what the kernels cover */
+#define DYMOE_ENOCTX (-5)  /* context is NULL (checked after the other arguments) */
+
+#define DYMOE_PHASE_PREFILL 0
+#define DYMOE_PHASE_DECODE 1
+
+/* out_dtype of dymoe_moe_ffn_mixed */
+#define DYMOE_OUT_BF16 0
+#define DYMOE_OUT_F32 1
+
+/* path of dymoe_moe_ffn_mixed */
+#define DYMOE_PATH_AUTO 0
+#define DYMOE_PATH_GEMV 1  /* bandwidth-bound dequant GEMV per (token, expert) pair */
+#define DYMOE_PATH_GEMM 2  /* tokens grouped by expert, MFMA grouped GEMM */
+
+#define DYMOE_MAX_TIERS 8
+#define DYMOE_MAX_EXPERTS 1024
+
+typedef struct dymoe_ctx dymoe_ctx; /* opaque; holds the device ordinal and its properties */
+
+/*
+ * One expert's weights in every precision the caller has materialised.
+ * Index 0, 1, 2 of each array = W1 (gate, [F,H]), W3 (up, [F,H]), W2 (down, [H,F]).
+ * w: bf16.  q4/q2: packed codes as written by dymoe_quantize_pack; s4, z4, s2, z2:
+ * fp16 scale and zero, one per group of `group` columns ([rows, cols/group]).
+ * Entries for precisions that are never selected may be NULL.
+ * The table lives in device memory ([E] of these).
+ */
+typedef struct {
+    const void* w[3];
+    uint8_t* q4[3];
+    void* s4[3];
+    void* z4[3];
+    uint8_t* q2[3];
+    void* s2[3];
+    void* z2[3];
+} dymoe_expert_fmt;
+
+/* Create / destroy a context bound to HIP device `device`.  Host calls. */
+int dymoe_create(dymoe_ctx** out, int device);
+void dymoe_destroy(dymoe_ctx* ctx);
+
+/* Static, human-readable text of an error code. */
+const char* dymoe_strerror(int code);
+
+/* Bytes of workspace dymoe_moe_ffn_mixed needs for these sizes (either path).
+ * Pure host function; returns 0 for invalid sizes. */
+size_t dymoe_workspace_bytes(int T, int H, int F, int E, int k);
+
+/*
+ * Router gating and top-k (paper Sec. 2.1; gate form of Sec. 4.4.1:
+ * g = Softmax(h W_g), selection = TopK_k(g)).
+ *   logit[t,e] = sum_h x[t,h] * wg[e,h] (+ bias[e]),  fp32 accumulation
+ *   probs[t,:] = softmax over all E experts
+ *   idx[t,0..k) = the k experts with the largest logit, descending, ties to
+ *                 the lower index;  w[t,j] = probs[t, idx[t,j]], divided by
+ *                 their sum when renorm != 0.
+ * x [T,H] bf16, wg [E,H] bf16, bias [E] fp32 or NULL,
+ * idx [T,k] int32, w [T,k] fp32, probs [T,E] fp32 or NULL.
+ * Limits: 1 <= k <= E <= DYMOE_MAX_EXPERTS, H multiple of 8, H <= 16384.
+ */
+int dymoe_route_topk(dymoe_ctx* ctx, const void* x, const void* wg, const float* bias,
+                     int T, int H, int E, int k, int renorm,
+                     int32_t* idx, float* w, float* probs, void* stream);
+
+/*
+ * Activation-norm token score s_t = ||x_t||_2 (fp32).  Stand-in for the
+ * attention-derived token importance of paper Sec. 4.2.1 (first equation),
+ * which needs an attention block that is outside this layer.
+ * x [T,H] bf16, score [T] fp32.  H multiple of 8.
+ */
+int dymoe_token_score_norm(dymoe_ctx* ctx, const void* x, int T, int H, float* score,
+                           void* stream);
+
+/*
+ * Per-expert importance (paper Sec. 4.2).
+ * phase = DYMOE_PHASE_PREFILL (Sec. 4.2.1): T_imp = the k_hh tokens with the
+ *   largest token_score (ties to the lower token index);
+ *   importance[e] (int32) = number of (token, slot) pairs with token in T_imp and
+ *   idx[token,slot] = e;  load[e] (int32) = that count over all tokens (also the
+ *   token-frequency count of Sec. 4.4.1).  token_score [T] fp32 is required,
+ *   probs is ignored.
+ * phase = DYMOE_PHASE_DECODE (Sec. 4.2.2): importance[e] (fp32) = probs[0,e],
+ *   the gating score; for T > 1 the mean over the T tokens.  load as above.
+ *   probs [T,E] fp32 is required, token_score and k_hh are ignored.
+ * idx [T,k] int32 with values in [0,E); entries outside that range are skipped.
+ * importance [E] (4 bytes per entry, type by phase), load [E] int32.
+ */
+int dymoe_expert_importance(dymoe_ctx* ctx, int phase, const int32_t* idx, const float* probs,
+                            const float* token_score, int T, int E, int k, int k_hh,
+                            void* importance, int32_t* load, void* stream);
+
+/*
+ * Depth-aware retention schedule (paper Sec. 4.3), pure host function:
+ *   r(l) = (1 - lambda) * (cos(pi * l / (L-1)) + 1) / 2 + lambda,  l = 0..L-1
+ *   t_l  = ceil(r(l) * M), clamped to [1, M]  (L = 1 gives r = 1)
+ * Returns t_l, or DYMOE_EINVAL for layer outside [0,L), lambda outside [0,1],
+ * M < 1 or L < 1.
+ */
+int dymoe_depth_schedule(int layer, int n_layers, double lambda, int M);
+
+/*
+ * Bit-width per expert (paper Sec. 1, Sec. 4.3, Sec. 5: the top-t_l experts by
+ * importance are critical and keep high precision, the rest get low precision
+ * or 0 bits = skipped).  Generalised to an ordered tier table.
+ * Experts are ranked by (importance descending, load descending, index
+ * ascending); rank positions [0,c0) get tier_bits[0], the next c1 get
+ * tier_bits[1], ...; then bits[e] = max(tier bits, floor_bits).
+ * importance [E]: int32 for DYMOE_PHASE_PREFILL, fp32 for DYMOE_PHASE_DECODE.
+ * load [E] int32 or NULL.  tier_count / tier_bits: HOST arrays of n_tiers
+ * entries (1 <= n_tiers <= DYMOE_MAX_TIERS), counts >= 0 summing to E, bits in
+ * {0,2,4,16}.  bits [E] uint8, rank [E] int32 (position of expert e) or NULL.
+ * The two-tier paper mode is tier_count = {t_l, E - t_l}.
+ */
+int dymoe_assign_precision(dymoe_ctx* ctx, int phase, const void* importance,
+                           const int32_t* load, int E, int n_tiers,
+                           const int32_t* tier_count, const uint8_t* tier_bits, int floor_bits,
+                           uint8_t* bits, int32_t* rank, void* stream);
+
+/*
+ * Group-wise asymmetric quantize-and-pack of one matrix (the paper, Sec. 5,
+ * quantizes expert weights only and leaves the base quantizer exchangeable;
+ * this is round-to-nearest with the group minimum as zero point).
+ * For every row and every group of `group` consecutive columns, in binary32
+ * with one correctly rounded operation per step:
+ *   lo = min, hi = max over the group
+ *   zero  = fp16(lo)                     m = (float)zero
+ *   scale = fp16((hi - lo) / (2^bits-1)) s = (float)scale
+ *   inv   = s > 0 ? 1/s : 0
+ *   q     = clamp(rint((w - m) * inv), 0, 2^bits-1)
+ * Codes are packed little-endian along the row: code j of a byte sits at bit
+ * bits*j (int4: byte = q[2i] | q[2i+1]<<4; int2: four codes per byte).
+ * The dequantised weight is s*q + m.
+ * w [N,K] bf16 (finite, magnitude within fp16 range), codes [N, K*bits/8],
+ * scale and zero [N, K/group] fp16.  bits in {2,4}; group = 64; K multiple of
+ * group; w and codes 16-byte aligned.
+ */
+int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits, int group,
+                        uint8_t* codes, void* scale, void* zero, void* stream);
+
+/*
+ * Device-driven quantization of a layer's experts, so that the precision
+ * decision never travels to the host: for each expert e with bits[e] in {2,4}
+ * (and load[e] > 0 when load is given), quantize table[e].w[0..3) at bits[e]
+ * into table[e].q4/s4/z4 or q2/s2/z2 (same arithmetic and layout as
+ * dymoe_quantize_pack).  Experts at 16 or 0 bits are left untouched.
+ * table [E] device, bits [E] uint8 device, load [E] int32 device or NULL.
+ */
+int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const uint8_t* bits,
+                           const int32_t* load, int E, int H, int F, int group, void* stream);
+
+/*
+ * Mixed-precision SwiGLU expert FFN (paper Sec. 4.1: the executor runs the
+ * layer on a unified mixed-precision weight set; Sec. 1: a 0-bit expert is
+ * skipped):
+ *   y[t,:] = sum_{slot<k} w[t,slot] * W2_e( silu(W1_e x_t) * (W3_e x_t) ),
+ *   e = idx[t,slot], each expert's weights taken at bits[e]: 16 = table[e].w,
+ *   4 / 2 = the dequantised q4 / q2 codes, 0 = term omitted (no renormalising).
+ * x [T,H] bf16, idx [T,k] int32, w [T,k] fp32, bits [E] uint8, table [E].
+ * y [T,H] bf16 (DYMOE_OUT_BF16) or fp32 (DYMOE_OUT_F32); every row is written.
+ * path: DYMOE_PATH_AUTO picks GEMV for few tokens per expert, GEMM otherwise.
+ * workspace: at least dymoe_workspace_bytes(T,H,F,E,k) bytes, 256-byte aligned;
+ * contents are scratch.  Limits: group = 64; H, F multiples of 64;
+ * GEMV path H <= 8192; GEMM path H, F multiples of 128; E <= DYMOE_MAX_EXPERTS.
+ * Activations and the SwiGLU intermediate must stay inside fp16 range.
+ */
+int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w,
+                        const uint8_t* bits, const dymoe_expert_fmt* table,
+                        int T, int H, int F, int E, int k, int group, int out_dtype, int path,
+                        void* y, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYMOE_H */

@@ -1,0 +1,252 @@
+"""Thin ctypes binding of libdymoe.so (see include/dymoe.h for the contract).
+
+Argument marshalling only: every step of the MoE layer runs in the HIP
+library.  Device buffers are torch tensors (torch is used for device memory
+and streams only); each function takes tensors, checks dtype / contiguity and
+passes raw device pointers and sizes through the C ABI.  There is no fallback:
+if the shared library is missing, importing this module raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdymoe.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libdymoe.so is not built: run `python -m paper_2603_19172_amd.build` "
+        "(there is no CPU or PyTorch fallback for the DyMoE kernels)")
+
+lib = C.CDLL(LIB_PATH)
+
+OK, EINVAL, ENOSPC, EHIP, ENOTSUP, ENOCTX = 0, -1, -2, -3, -4, -5
+PHASE_PREFILL, PHASE_DECODE = 0, 1
+OUT_BF16, OUT_F32 = 0, 1
+PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
+
+# every symbol include/dymoe.h declares
+EXPORTS = [
+    "dymoe_create", "dymoe_destroy", "dymoe_strerror", "dymoe_workspace_bytes",
+    "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_expert_importance",
+    "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
+    "dymoe_quantize_experts", "dymoe_moe_ffn_mixed",
+]
+
+
+class ExpertFmt(C.Structure):
+    """Mirror of dymoe_expert_fmt."""
+    _fields_ = [("w", C.c_void_p * 3), ("q4", C.c_void_p * 3), ("s4", C.c_void_p * 3),
+                ("z4", C.c_void_p * 3), ("q2", C.c_void_p * 3), ("s2", C.c_void_p * 3),
+                ("z2", C.c_void_p * 3)]
+
+
+_vp, _i, _l, _sz, _d = C.c_void_p, C.c_int, C.c_long, C.c_size_t, C.c_double
+lib.dymoe_create.restype = _i
+lib.dymoe_create.argtypes = [C.POINTER(_vp), _i]
+lib.dymoe_destroy.restype = None
+lib.dymoe_destroy.argtypes = [_vp]
+lib.dymoe_strerror.restype = C.c_char_p
+lib.dymoe_strerror.argtypes = [_i]
+lib.dymoe_workspace_bytes.restype = _sz
+lib.dymoe_workspace_bytes.argtypes = [_i] * 5
+lib.dymoe_route_topk.restype = _i
+lib.dymoe_route_topk.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
+lib.dymoe_token_score_norm.restype = _i
+lib.dymoe_token_score_norm.argtypes = [_vp, _vp, _i, _i, _vp, _vp]
+lib.dymoe_expert_importance.restype = _i
+lib.dymoe_expert_importance.argtypes = [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp]
+lib.dymoe_depth_schedule.restype = _i
+lib.dymoe_depth_schedule.argtypes = [_i, _i, _d, _i]
+lib.dymoe_assign_precision.restype = _i
+lib.dymoe_assign_precision.argtypes = [_vp, _i, _vp, _vp, _i, _i, _vp, _vp, _i, _vp, _vp, _vp]
+lib.dymoe_quantize_pack.restype = _i
+lib.dymoe_quantize_pack.argtypes = [_vp, _vp, _l, _l, _i, _i, _vp, _vp, _vp, _vp]
+lib.dymoe_quantize_experts.restype = _i
+lib.dymoe_quantize_experts.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]
+lib.dymoe_moe_ffn_mixed.restype = _i
+lib.dymoe_moe_ffn_mixed.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i,
+                                    _vp, _vp, _sz, _vp]
+
+
+class DymoeError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (where, strerror(code), code))
+
+
+def strerror(code: int) -> str:
+    return lib.dymoe_strerror(int(code)).decode()
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise DymoeError(rc, where)
+
+
+def _ptr(t, dtype=None):
+    """Device pointer of a tensor (None -> NULL); ints pass through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("expected %s, got %s" % (dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def workspace_bytes(T, H, F, E, k) -> int:
+    return int(lib.dymoe_workspace_bytes(T, H, F, E, k))
+
+
+def depth_schedule(layer, n_layers, lam, M) -> int:
+    return int(lib.dymoe_depth_schedule(layer, n_layers, float(lam), M))
+
+
+class Context:
+    """Owns a dymoe_ctx.  All methods enqueue on `stream` (default: torch's current)."""
+
+    def __init__(self, device: int = 0):
+        h = _vp()
+        _check(lib.dymoe_create(C.byref(h), device), "dymoe_create")
+        self._h = h
+        self.device = device
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib.dymoe_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    # -- S1
+    def route_topk(self, x, wg, bias, k, renorm=True, probs=True, stream=None):
+        T, H = x.shape
+        E = wg.shape[0]
+        dev = x.device
+        idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+        w = torch.empty((T, k), dtype=torch.float32, device=dev)
+        p = torch.empty((T, E), dtype=torch.float32, device=dev) if probs else None
+        _check(lib.dymoe_route_topk(self._h, _ptr(x, torch.bfloat16), _ptr(wg, torch.bfloat16),
+                                    _ptr(bias, torch.float32), T, H, E, k, 1 if renorm else 0,
+                                    _ptr(idx), _ptr(w), _ptr(p), _stream(stream)),
+               "dymoe_route_topk")
+        return idx, w, p
+
+    def token_score_norm(self, x, stream=None):
+        T, H = x.shape
+        s = torch.empty((T,), dtype=torch.float32, device=x.device)
+        _check(lib.dymoe_token_score_norm(self._h, _ptr(x, torch.bfloat16), T, H, _ptr(s),
+                                          _stream(stream)), "dymoe_token_score_norm")
+        return s
+
+    # -- S2
+    def expert_importance(self, phase, idx, E, probs=None, token_score=None, k_hh=0, stream=None):
+        T, k = idx.shape
+        dev = idx.device
+        imp = torch.empty((E,), dtype=torch.int32 if phase == PHASE_PREFILL else torch.float32,
+                          device=dev)
+        load = torch.empty((E,), dtype=torch.int32, device=dev)
+        _check(lib.dymoe_expert_importance(self._h, phase, _ptr(idx, torch.int32),
+                                           _ptr(probs, torch.float32),
+                                           _ptr(token_score, torch.float32), T, E, k, k_hh,
+                                           _ptr(imp), _ptr(load), _stream(stream)),
+               "dymoe_expert_importance")
+        return imp, load
+
+    # -- S3
+    def assign_precision(self, phase, importance, load, tier_count, tier_bits, floor_bits=0,
+                         stream=None):
+        E = importance.shape[0]
+        dev = importance.device
+        n = len(tier_count)
+        tc = (C.c_int32 * n)(*[int(v) for v in tier_count])
+        tb = (C.c_uint8 * n)(*[int(v) for v in tier_bits])
+        bits = torch.empty((E,), dtype=torch.uint8, device=dev)
+        rank = torch.empty((E,), dtype=torch.int32, device=dev)
+        want = torch.int32 if phase == PHASE_PREFILL else torch.float32
+        _check(lib.dymoe_assign_precision(self._h, phase, _ptr(importance, want),
+                                          _ptr(load, torch.int32), E, n,
+                                          C.cast(tc, _vp), C.cast(tb, _vp), floor_bits,
+                                          _ptr(bits), _ptr(rank), _stream(stream)),
+               "dymoe_assign_precision")
+        return bits, rank
+
+    # -- S4
+    def quantize_pack(self, w, bits, group=64, out=None, stream=None):
+        N, K = w.shape
+        dev = w.device
+        if out is None:
+            codes = torch.empty((N, K * bits // 8), dtype=torch.uint8, device=dev)
+            scale = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+            zero = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+        else:
+            codes, scale, zero = out
+        _check(lib.dymoe_quantize_pack(self._h, _ptr(w, torch.bfloat16), N, K, bits, group,
+                                       _ptr(codes, torch.uint8), _ptr(scale, torch.float16),
+                                       _ptr(zero, torch.float16), _stream(stream)),
+               "dymoe_quantize_pack")
+        return codes, scale, zero
+
+    def quantize_experts(self, table, bits, load, E, H, F, group=64, stream=None):
+        _check(lib.dymoe_quantize_experts(self._h, _ptr(table), _ptr(bits, torch.uint8),
+                                          _ptr(load, torch.int32), E, H, F, group,
+                                          _stream(stream)), "dymoe_quantize_experts")
+
+    # -- S5
+    def moe_ffn_mixed(self, x, idx, w, bits, table, F, out_dtype=OUT_BF16, path=PATH_AUTO,
+                      group=64, y=None, workspace=None, stream=None):
+        T, H = x.shape
+        k = idx.shape[1]
+        E = bits.shape[0]
+        dev = x.device
+        if y is None:
+            y = torch.empty((T, H), dtype=torch.bfloat16 if out_dtype == OUT_BF16 else torch.float32,
+                            device=dev)
+        if workspace is None:
+            workspace = torch.empty((workspace_bytes(T, H, F, E, k),), dtype=torch.uint8, device=dev)
+        _check(lib.dymoe_moe_ffn_mixed(self._h, _ptr(x, torch.bfloat16), _ptr(idx, torch.int32),
+                                       _ptr(w, torch.float32), _ptr(bits, torch.uint8), _ptr(table),
+                                       T, H, F, E, k, group, out_dtype, path, _ptr(y),
+                                       _ptr(workspace, torch.uint8), workspace.numel(),
+                                       _stream(stream)), "dymoe_moe_ffn_mixed")
+        return y
+
+
+def make_expert_table(experts, device):
+    """Build the device-resident dymoe_expert_fmt[E] from per-expert dicts of
+    tensors: 'w' = [W1,W3,W2] bf16 and/or 'q4' / 'q2' = three (codes, scale,
+    zero) triples.  Returns (table tensor, keepalive list); the caller keeps
+    both alive while the table is in use."""
+    E = len(experts)
+    arr = (ExpertFmt * E)()
+    keep = []
+    for e, ex in enumerate(experts):
+        if ex.get("w") is not None:
+            for i in range(3):
+                arr[e].w[i] = _ptr(ex["w"][i], torch.bfloat16)
+            keep.append(ex["w"])
+        for b in (4, 2):
+            trip = ex.get("q%d" % b)
+            if trip is None:
+                continue
+            for i in range(3):
+                cd, sc, zr = trip[i]
+                getattr(arr[e], "q%d" % b)[i] = _ptr(cd, torch.uint8)
+                getattr(arr[e], "s%d" % b)[i] = _ptr(sc, torch.float16)
+                getattr(arr[e], "z%d" % b)[i] = _ptr(zr, torch.float16)
+            keep.append(trip)
+    raw = bytes(arr)
+    host = torch.frombuffer(bytearray(raw), dtype=torch.uint8)
+    table = host.to(device)
+    return table, keep

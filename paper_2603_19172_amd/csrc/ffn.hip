@@ -1,0 +1,42 @@
+// dymoe_moe_ffn_mixed: argument checks and the choice between the decode
+// (GEMV) and prefill (grouped GEMM) paths.
+#include "common.hpp"
+#include "ffn_layout.hpp"
+
+namespace dymoe {
+int ffn_gemv_launch(const void* x, const int32_t* idx, const float* w, const uint8_t* bits,
+                    const dymoe_expert_fmt* table, int T, int H, int F, int E, int k,
+                    int out_dtype, void* y, void* workspace, hipStream_t st);
+int ffn_gemm_launch(const void* x, const int32_t* idx, const float* w, const uint8_t* bits,
+                    const dymoe_expert_fmt* table, int T, int H, int F, int E, int k,
+                    int out_dtype, void* y, void* workspace, hipStream_t st);
+}  // namespace dymoe
+
+extern "C" int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t* idx,
+                                   const float* w, const uint8_t* bits,
+                                   const dymoe_expert_fmt* table, int T, int H, int F, int E,
+                                   int k, int group, int out_dtype, int path, void* y,
+                                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    DYMOE_REQUIRE(x && idx && w && bits && table && y && workspace);
+    DYMOE_REQUIRE(T >= 0 && H > 0 && F > 0 && E > 0 && k > 0 && k <= E);
+    DYMOE_REQUIRE(group > 0 && H % group == 0 && F % group == 0);
+    DYMOE_REQUIRE(out_dtype == DYMOE_OUT_BF16 || out_dtype == DYMOE_OUT_F32);
+    DYMOE_REQUIRE(path == DYMOE_PATH_AUTO || path == DYMOE_PATH_GEMV || path == DYMOE_PATH_GEMM);
+    DYMOE_REQUIRE(dymoe_aligned(x, 16) && dymoe_aligned(y, 16) && dymoe_aligned(workspace, 256));
+    if (group != 64 || E > DYMOE_MAX_EXPERTS) return DYMOE_ENOTSUP;
+    if ((long)T * k > 0x7fffffffL / 4) return DYMOE_ENOTSUP;
+    if (workspace_bytes < dymoe::ffn_layout(T, H, F, E, k).total) return DYMOE_ENOSPC;
+    const bool gemm_ok = (H % 128 == 0) && (F % 128 == 0);
+    const bool gemv_ok = (H <= 4 * dymoe::kSeg) && ((long)T * k <= 65535);
+    if (path == DYMOE_PATH_AUTO) path = (T <= 4 || !gemm_ok) ? DYMOE_PATH_GEMV : DYMOE_PATH_GEMM;
+    if (path == DYMOE_PATH_GEMV && !gemv_ok) return DYMOE_ENOTSUP;
+    if (path == DYMOE_PATH_GEMM && !gemm_ok) return DYMOE_ENOTSUP;
+    if (!ctx) return DYMOE_ENOCTX;
+    if (T == 0) return DYMOE_OK;
+    if (path == DYMOE_PATH_GEMV)
+        return dymoe::ffn_gemv_launch(x, idx, w, bits, table, T, H, F, E, k, out_dtype, y, workspace,
+                                      (hipStream_t)stream);
+    return dymoe::ffn_gemm_launch(x, idx, w, bits, table, T, H, F, E, k, out_dtype, y, workspace,
+                                  (hipStream_t)stream);
+}

@@ -1,0 +1,185 @@
+// Expert importance (heavy-hitter token load / gate score) and the
+// importance-ranked bit-width assignment.  Both are tiny: integer histograms
+// and an E x E ranking, sized for one or a few workgroups.
+#include "common.hpp"
+
+namespace dymoe {
+
+constexpr int kImpThreads = 256;
+
+// zero-fill without hipMemsetAsync (the calls may be captured into a graph)
+__global__ void zero_i32_kernel(int32_t* a, int32_t* b, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        a[i] = 0;
+        if (b) b[i] = 0;
+    }
+}
+
+// Prefill: a token is a heavy hitter when fewer than k_hh tokens precede it in
+// the order (score descending, token index ascending).  Each thread ranks one
+// token against all T scores staged through LDS, then adds its k routed
+// experts to the load histogram and, if heavy, to the importance histogram.
+// with_importance = 0: only the load histogram (decode phase).
+__global__ __launch_bounds__(kImpThreads) void importance_prefill_kernel(
+    const int32_t* __restrict__ idx, const float* __restrict__ score, int T, int E, int k,
+    int k_hh, int with_importance, int32_t* __restrict__ importance, int32_t* __restrict__ load)
+{
+    __shared__ float tile[kImpThreads];
+    const int t = blockIdx.x * kImpThreads + threadIdx.x;
+    bool heavy = false;
+    if (with_importance) {
+        const float mine = (t < T) ? score[t] : 0.0f;
+        int before = 0;
+        for (int base = 0; base < T; base += kImpThreads) {
+            const int u = base + threadIdx.x;
+            tile[threadIdx.x] = (u < T) ? score[u] : 0.0f;
+            __syncthreads();
+            const int n = min(kImpThreads, T - base);
+            for (int j = 0; j < n; j++) {
+                const float s = tile[j];
+                before += (s > mine || (s == mine && base + j < t)) ? 1 : 0;
+            }
+            __syncthreads();
+        }
+        heavy = (t < T) && before < k_hh;
+    }
+    if (t < T) {
+        for (int s = 0; s < k; s++) {
+            const int e = idx[(size_t)t * k + s];
+            if (e < 0 || e >= E) continue;
+            atomicAdd(&load[e], 1);
+            if (heavy) atomicAdd(&importance[e], 1);
+        }
+    }
+}
+
+// Decode: importance[e] = mean over the step's tokens of the gate score
+__global__ void importance_decode_kernel(const float* __restrict__ probs, int T, int E,
+                                         float* __restrict__ importance)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    float s = 0.0f;
+    for (int t = 0; t < T; t++) s += probs[(size_t)t * E + e];
+    importance[e] = (T == 1) ? s : s / (float)T;
+}
+
+struct TierTable {
+    int n;
+    int32_t count[DYMOE_MAX_TIERS];
+    uint8_t bits[DYMOE_MAX_TIERS];
+};
+
+// One workgroup; thread e counts the experts that precede expert e in the
+// order (importance desc, load desc, index asc) -> rank -> tier -> bits.
+template <typename ImpT>
+__global__ __launch_bounds__(DYMOE_MAX_EXPERTS) void assign_precision_kernel(
+    const ImpT* __restrict__ importance, const int32_t* __restrict__ load, int E, TierTable tiers,
+    int floor_bits, uint8_t* __restrict__ bits, int32_t* __restrict__ rank)
+{
+    __shared__ ImpT s_imp[DYMOE_MAX_EXPERTS];
+    __shared__ int32_t s_load[DYMOE_MAX_EXPERTS];
+    const int e = threadIdx.x;
+    if (e < E) {
+        s_imp[e] = importance[e];
+        s_load[e] = load ? load[e] : 0;
+    }
+    __syncthreads();
+    if (e >= E) return;
+    const ImpT mi = s_imp[e];
+    const int32_t ml = s_load[e];
+    int pos = 0;
+    for (int j = 0; j < E; j++) {
+        const ImpT oi = s_imp[j];
+        const int32_t ol = s_load[j];
+        const bool first = (oi > mi) || (oi == mi && (ol > ml || (ol == ml && j < e)));
+        pos += first ? 1 : 0;
+    }
+    int tier = 0, upto = tiers.count[0];
+    while (pos >= upto && tier + 1 < tiers.n) {
+        tier++;
+        upto += tiers.count[tier];
+    }
+    int b = tiers.bits[tier];
+    if (b < floor_bits) b = floor_bits;
+    bits[e] = (uint8_t)b;
+    if (rank) rank[e] = pos;
+}
+
+}  // namespace dymoe
+
+extern "C" {
+
+int dymoe_expert_importance(dymoe_ctx* ctx, int phase, const int32_t* idx, const float* probs,
+                            const float* token_score, int T, int E, int k, int k_hh,
+                            void* importance, int32_t* load, void* stream)
+{
+    DYMOE_REQUIRE(idx && importance && load);
+    DYMOE_REQUIRE(phase == DYMOE_PHASE_PREFILL || phase == DYMOE_PHASE_DECODE);
+    DYMOE_REQUIRE(T >= 0 && E > 0 && k > 0 && k <= E);
+    if (phase == DYMOE_PHASE_PREFILL) DYMOE_REQUIRE(token_score && k_hh >= 0 && k_hh <= T);
+    else DYMOE_REQUIRE(probs != nullptr);
+    if (E > DYMOE_MAX_EXPERTS) return DYMOE_ENOTSUP;
+    if (!ctx) return DYMOE_ENOCTX;
+    hipStream_t st = (hipStream_t)stream;
+    const bool prefill = phase == DYMOE_PHASE_PREFILL;
+    hipLaunchKernelGGL(dymoe::zero_i32_kernel, dim3((E + 255) / 256), dim3(256), 0, st, load,
+                       prefill ? (int32_t*)importance : (int32_t*)nullptr, E);
+    DYMOE_HIP_LAUNCH_CHECK();
+    if (T > 0) {
+        const unsigned blocks = (unsigned)((T + dymoe::kImpThreads - 1) / dymoe::kImpThreads);
+        hipLaunchKernelGGL(dymoe::importance_prefill_kernel, dim3(blocks), dim3(dymoe::kImpThreads),
+                           0, st, idx, token_score, T, E, k, k_hh, prefill ? 1 : 0,
+                           (int32_t*)importance, load);
+        DYMOE_HIP_LAUNCH_CHECK();
+    }
+    if (!prefill) {
+        hipLaunchKernelGGL(dymoe::importance_decode_kernel, dim3((E + 255) / 256), dim3(256), 0, st,
+                           probs, T, E, (float*)importance);
+        DYMOE_HIP_LAUNCH_CHECK();
+    }
+    return DYMOE_OK;
+}
+
+int dymoe_assign_precision(dymoe_ctx* ctx, int phase, const void* importance,
+                           const int32_t* load, int E, int n_tiers,
+                           const int32_t* tier_count, const uint8_t* tier_bits, int floor_bits,
+                           uint8_t* bits, int32_t* rank, void* stream)
+{
+    DYMOE_REQUIRE(importance && tier_count && tier_bits && bits);
+    DYMOE_REQUIRE(phase == DYMOE_PHASE_PREFILL || phase == DYMOE_PHASE_DECODE);
+    DYMOE_REQUIRE(E > 0 && n_tiers >= 1 && n_tiers <= DYMOE_MAX_TIERS);
+    DYMOE_REQUIRE(floor_bits == 0 || floor_bits == 2 || floor_bits == 4 || floor_bits == 16);
+    dymoe::TierTable tt;
+    tt.n = n_tiers;
+    long total = 0;
+    for (int i = 0; i < DYMOE_MAX_TIERS; i++) {
+        tt.count[i] = 0;
+        tt.bits[i] = 0;
+    }
+    for (int i = 0; i < n_tiers; i++) {
+        const int b = tier_bits[i];
+        DYMOE_REQUIRE(tier_count[i] >= 0);
+        DYMOE_REQUIRE(b == 0 || b == 2 || b == 4 || b == 16);
+        tt.count[i] = tier_count[i];
+        tt.bits[i] = (uint8_t)b;
+        total += tier_count[i];
+    }
+    DYMOE_REQUIRE(total == E);
+    if (E > DYMOE_MAX_EXPERTS) return DYMOE_ENOTSUP;
+    if (!ctx) return DYMOE_ENOCTX;
+    hipStream_t st = (hipStream_t)stream;
+    const unsigned threads = (unsigned)(((E + 63) / 64) * 64);
+    if (phase == DYMOE_PHASE_PREFILL)
+        hipLaunchKernelGGL((dymoe::assign_precision_kernel<int32_t>), dim3(1), dim3(threads), 0, st,
+                           (const int32_t*)importance, load, E, tt, floor_bits, bits, rank);
+    else
+        hipLaunchKernelGGL((dymoe::assign_precision_kernel<float>), dim3(1), dim3(threads), 0, st,
+                           (const float*)importance, load, E, tt, floor_bits, bits, rank);
+    DYMOE_HIP_LAUNCH_CHECK();
+    return DYMOE_OK;
+}
+
+}  // extern "C"

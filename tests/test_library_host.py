@@ -1,0 +1,119 @@
+"""Host-side checks of libdymoe.so that need no GPU: the library loads, exports
+every symbol the header declares, validates arguments before touching the
+device, and its host-side depth schedule agrees with the paper's closed forms."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import dymoe_oracle as O
+from paper_2603_19172_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = 0x10000  # a non-null, 64 KiB aligned dummy "pointer"; never dereferenced by validation
+
+
+def test_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "dymoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(dymoe_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B.lib, name), name
+
+
+def test_strerror_and_workspace():
+    assert B.strerror(0) == "success"
+    for code in (-1, -2, -3, -4, -5):
+        assert B.strerror(code) and "unknown" not in B.strerror(code)
+    assert "unknown" in B.strerror(-99)
+    assert B.workspace_bytes(0, 0, 0, 0, 0) == 0
+    assert B.workspace_bytes(4, 256, 512, 8, 9) == 0
+    small = B.workspace_bytes(16, 256, 512, 8, 2)
+    big = B.workspace_bytes(512, 4096, 14336, 8, 2)
+    assert 0 < small < big and big % 256 == 0
+    # holds the fp32 intermediate of every (token, expert) pair
+    assert big >= 512 * 2 * 14336 * 4
+
+
+def test_depth_schedule_matches_golden_and_oracle():
+    for line in open(os.path.join(ROOT, "tests", "golden", "schedule_tables.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = line.split()
+        L, M, lam = int(f[0]), int(f[1]), float(f[2])
+        assert [B.depth_schedule(l, L, lam, M) for l in range(L)] == [int(v) for v in f[3:]]
+    for L in (1, 2, 7, 32, 48):
+        for M in (8, 60, 128):
+            for lam in (0.0, 0.3, 0.5, 0.75, 0.8, 1.0):
+                for l in range(L):
+                    assert B.depth_schedule(l, L, lam, M) == O.depth_schedule(l, L, lam, M)
+    assert B.depth_schedule(4, 4, 0.5, 8) == B.EINVAL
+    assert B.depth_schedule(0, 4, -0.1, 8) == B.EINVAL
+    assert B.depth_schedule(0, 0, 0.5, 8) == B.EINVAL
+    assert B.depth_schedule(0, 4, 0.5, 0) == B.EINVAL
+    # mean retained fraction over the stack is (1 + lambda)/2 up to the ceilings
+    L, M = 32, 128
+    mean = sum(B.depth_schedule(l, L, 0.5, M) for l in range(L)) / (L * M)
+    assert 0.75 <= mean < 0.75 + 1.0 / M
+
+
+def test_argument_validation_happens_before_any_device_work():
+    lib = B.lib
+    # route: valid arguments but no context -> ENOCTX; bad ones -> EINVAL / ENOTSUP first
+    assert lib.dymoe_route_topk(None, P, P, None, 4, 256, 8, 2, 1, P, P, P, None) == B.ENOCTX
+    assert lib.dymoe_route_topk(None, None, P, None, 4, 256, 8, 2, 1, P, P, P, None) == B.EINVAL
+    assert lib.dymoe_route_topk(None, P, P, None, 4, 256, 8, 9, 1, P, P, P, None) == B.EINVAL
+    assert lib.dymoe_route_topk(None, P, P, None, 4, 252, 8, 2, 1, P, P, P, None) == B.EINVAL
+    assert lib.dymoe_route_topk(None, P + 2, P, None, 4, 256, 8, 2, 1, P, P, P, None) == B.EINVAL
+    assert lib.dymoe_route_topk(None, P, P, None, 4, 256, 2048, 2, 1, P, P, P, None) == B.ENOTSUP
+    assert lib.dymoe_token_score_norm(None, P, 4, 256, P, None) == B.ENOCTX
+    assert lib.dymoe_token_score_norm(None, P, 4, 250, P, None) == B.EINVAL
+    # importance
+    assert lib.dymoe_expert_importance(None, 0, P, None, P, 16, 8, 2, 3, P, P, None) == B.ENOCTX
+    assert lib.dymoe_expert_importance(None, 0, P, None, None, 16, 8, 2, 3, P, P, None) == B.EINVAL
+    assert lib.dymoe_expert_importance(None, 0, P, None, P, 16, 8, 2, 17, P, P, None) == B.EINVAL
+    assert lib.dymoe_expert_importance(None, 1, P, None, None, 1, 8, 2, 0, P, P, None) == B.EINVAL
+    assert lib.dymoe_expert_importance(None, 7, P, P, P, 1, 8, 2, 0, P, P, None) == B.EINVAL
+    # assignment: host tier tables are read during validation
+    tc = (C.c_int32 * 3)(2, 3, 3)
+    tb = (C.c_uint8 * 3)(16, 4, 2)
+    tcp, tbp = C.cast(tc, C.c_void_p), C.cast(tb, C.c_void_p)
+    assert lib.dymoe_assign_precision(None, 0, P, P, 8, 3, tcp, tbp, 0, P, P, None) == B.ENOCTX
+    assert lib.dymoe_assign_precision(None, 0, P, P, 9, 3, tcp, tbp, 0, P, P, None) == B.EINVAL
+    assert lib.dymoe_assign_precision(None, 0, P, P, 8, 3, tcp, tbp, 3, P, P, None) == B.EINVAL
+    bad = (C.c_uint8 * 3)(16, 5, 2)
+    assert lib.dymoe_assign_precision(None, 0, P, P, 8, 3, tcp, C.cast(bad, C.c_void_p), 0, P, P, None) == B.EINVAL
+    assert lib.dymoe_assign_precision(None, 0, P, P, 8, 9, tcp, tbp, 0, P, P, None) == B.EINVAL
+    # quantize
+    assert lib.dymoe_quantize_pack(None, P, 8, 256, 4, 64, P, P, P, None) == B.ENOCTX
+    assert lib.dymoe_quantize_pack(None, P, 8, 256, 3, 64, P, P, P, None) == B.EINVAL
+    assert lib.dymoe_quantize_pack(None, P, 8, 200, 4, 64, P, P, P, None) == B.EINVAL
+    assert lib.dymoe_quantize_pack(None, P, 8, 256, 4, 32, P, P, P, None) == B.ENOTSUP
+    assert lib.dymoe_quantize_pack(None, P + 8, 8, 256, 4, 64, P, P, P, None) == B.EINVAL
+    assert lib.dymoe_quantize_experts(None, P, P, None, 8, 256, 512, 64, None) == B.ENOCTX
+    assert lib.dymoe_quantize_experts(None, P, P, None, 8, 250, 512, 64, None) == B.EINVAL
+    # ffn
+    ws = B.workspace_bytes(16, 256, 512, 8, 2)
+    ffn = lib.dymoe_moe_ffn_mixed
+    assert ffn(None, P, P, P, P, P, 16, 256, 512, 8, 2, 64, 0, 0, P, P, ws, None) == B.ENOCTX
+    assert ffn(None, P, P, P, P, P, 16, 256, 512, 8, 2, 64, 0, 0, P, P, ws - 1, None) == B.ENOSPC
+    assert ffn(None, P, P, P, P, P, 16, 256, 512, 8, 2, 64, 5, 0, P, P, ws, None) == B.EINVAL
+    assert ffn(None, P, P, P, P, P, 16, 256, 512, 8, 2, 64, 0, 7, P, P, ws, None) == B.EINVAL
+    assert ffn(None, P, P, P, P, None, 16, 256, 512, 8, 2, 64, 0, 0, P, P, ws, None) == B.EINVAL
+    assert ffn(None, P, P, P, P, P, 16, 256, 500, 8, 2, 64, 0, 0, P, P, ws, None) == B.EINVAL
+    # shapes the MFMA path cannot take when it is asked for explicitly
+    ws2 = B.workspace_bytes(16, 192, 512, 8, 2)
+    assert ffn(None, P, P, P, P, P, 16, 192, 512, 8, 2, 64, 0, 2, P, P, ws2, None) == B.ENOTSUP
+    assert ffn(None, P, P, P, P, P, 16, 192, 512, 8, 2, 64, 0, 0, P, P, ws2, None) == B.ENOCTX
+
+
+def test_create_without_gpu_reports_error():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    h = C.c_void_p()
+    assert B.lib.dymoe_create(C.byref(h), 0) == B.EHIP and not h.value
+    with pytest.raises(B.DymoeError):
+        B.Context(0)

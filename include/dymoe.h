@@ -26,7 +26,8 @@
  *    W2 is [H,F], the router weight is [E,H].
  *  - Return value: 0 on success, a negative DYMOE_E* code otherwise.
  *    Arguments are validated before any GPU work is issued; a failing call
- *    has enqueued nothing.
+ *    has enqueued nothing.  A tensor with zero rows (T = 0, N = 0) may be
+ *    passed as NULL; such a call is a successful no-op.
  */
 #ifndef DYMOE_H
 #define DYMOE_H

@@ -18,8 +18,9 @@ extern "C" int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t*
                                    int k, int group, int out_dtype, int path, void* y,
                                    void* workspace, size_t workspace_bytes, void* stream)
 {
-    DYMOE_REQUIRE(x && idx && w && bits && table && y && workspace);
     DYMOE_REQUIRE(T >= 0 && H > 0 && F > 0 && E > 0 && k > 0 && k <= E);
+    DYMOE_REQUIRE(bits && table && workspace);
+    if (T > 0) DYMOE_REQUIRE(x && idx && w && y);  // empty step: nothing to read or write
     DYMOE_REQUIRE(group > 0 && H % group == 0 && F % group == 0);
     DYMOE_REQUIRE(out_dtype == DYMOE_OUT_BF16 || out_dtype == DYMOE_OUT_F32);
     DYMOE_REQUIRE(path == DYMOE_PATH_AUTO || path == DYMOE_PATH_GEMV || path == DYMOE_PATH_GEMM);

@@ -116,11 +116,15 @@ int dymoe_expert_importance(dymoe_ctx* ctx, int phase, const int32_t* idx, const
                             const float* token_score, int T, int E, int k, int k_hh,
                             void* importance, int32_t* load, void* stream)
 {
-    DYMOE_REQUIRE(idx && importance && load);
+    DYMOE_REQUIRE(importance && load);
     DYMOE_REQUIRE(phase == DYMOE_PHASE_PREFILL || phase == DYMOE_PHASE_DECODE);
     DYMOE_REQUIRE(T >= 0 && E > 0 && k > 0 && k <= E);
-    if (phase == DYMOE_PHASE_PREFILL) DYMOE_REQUIRE(token_score && k_hh >= 0 && k_hh <= T);
-    else DYMOE_REQUIRE(probs != nullptr);
+    if (phase == DYMOE_PHASE_PREFILL) DYMOE_REQUIRE(k_hh >= 0 && k_hh <= T);
+    if (T > 0) {
+        DYMOE_REQUIRE(idx != nullptr);
+        if (phase == DYMOE_PHASE_PREFILL) DYMOE_REQUIRE(token_score != nullptr);
+        else DYMOE_REQUIRE(probs != nullptr);
+    }
     if (E > DYMOE_MAX_EXPERTS) return DYMOE_ENOTSUP;
     if (!ctx) return DYMOE_ENOCTX;
     hipStream_t st = (hipStream_t)stream;

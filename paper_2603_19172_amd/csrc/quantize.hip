@@ -130,15 +130,15 @@ extern "C" {
 int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits, int group,
                         uint8_t* codes, void* scale, void* zero, void* stream)
 {
-    DYMOE_REQUIRE(w && codes && scale && zero);
     DYMOE_REQUIRE(N >= 0 && K > 0);
     DYMOE_REQUIRE(bits == 2 || bits == 4);
     DYMOE_REQUIRE(group > 0 && K % group == 0);
+    if (N == 0) return (group != 64) ? DYMOE_ENOTSUP : (ctx ? DYMOE_OK : DYMOE_ENOCTX);  // nothing to read or write
+    DYMOE_REQUIRE(w && codes && scale && zero);
     DYMOE_REQUIRE(dymoe_aligned(w, 16) && dymoe_aligned(codes, 4) && dymoe_aligned(scale, 2) &&
                   dymoe_aligned(zero, 2));
     if (group != 64) return DYMOE_ENOTSUP;
     if (!ctx) return DYMOE_ENOCTX;
-    if (N == 0) return DYMOE_OK;
     const long n_chunks = N * K / 8;
     const long per_block = dymoe::kQThreads * dymoe::kQUnroll;
     const long blocks = (n_chunks + per_block - 1) / per_block;

@@ -157,10 +157,10 @@ int dymoe_route_topk(dymoe_ctx* ctx, const void* x, const void* wg, const float*
                      int T, int H, int E, int k, int renorm,
                      int32_t* idx, float* w, float* probs, void* stream)
 {
-    DYMOE_REQUIRE(x && wg && idx && w);
     DYMOE_REQUIRE(T >= 0 && H > 0 && E > 0 && k > 0 && k <= E);
     DYMOE_REQUIRE(H % 8 == 0);
-    DYMOE_REQUIRE(dymoe_aligned(x, 16) && dymoe_aligned(wg, 16));
+    DYMOE_REQUIRE(wg != nullptr && dymoe_aligned(wg, 16));
+    if (T > 0) DYMOE_REQUIRE(x && idx && w && dymoe_aligned(x, 16));  // empty step: nothing to read or write
     if (E > DYMOE_MAX_EXPERTS || H > 16384) return DYMOE_ENOTSUP;
     if (!ctx) return DYMOE_ENOCTX;
     if (T == 0) return DYMOE_OK;
@@ -176,9 +176,8 @@ int dymoe_route_topk(dymoe_ctx* ctx, const void* x, const void* wg, const float*
 
 int dymoe_token_score_norm(dymoe_ctx* ctx, const void* x, int T, int H, float* score, void* stream)
 {
-    DYMOE_REQUIRE(x && score);
     DYMOE_REQUIRE(T >= 0 && H > 0 && H % 8 == 0);
-    DYMOE_REQUIRE(dymoe_aligned(x, 16));
+    if (T > 0) DYMOE_REQUIRE(x && score && dymoe_aligned(x, 16));
     if (!ctx) return DYMOE_ENOCTX;
     if (T == 0) return DYMOE_OK;
     const unsigned blocks = (unsigned)((T + 3) / 4);

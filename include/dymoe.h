@@ -214,6 +214,23 @@ int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t* idx, const
                         int T, int H, int F, int E, int k, int group, int out_dtype, int path,
                         void* y, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Per-kernel timing (diagnostic; the paper reports only end-to-end latency,
+ * Sec. 6.1 "Key Metrics", so these serve the roofline accounting).
+ * dymoe_timing_enable: launches of the kernels whose bit is set in kernel_mask
+ * (bit i = kernel id i, ids 0..11 in the order route, token_norm, importance,
+ * assign, quantize, gemv_phase1, gemv_phase2, gemv_combine, plan, gemm1, gemm2,
+ * gemm_combine) are bracketed by HIP events on the launch stream; 0 switches
+ * timing off.  Either way, records not yet read are dropped.
+ * dymoe_timing_read: waits for the recorded launches of `kernel`, returns
+ * their summed duration in milliseconds and their count (host pointers).
+ * Do not enable timing while the stream is being captured into a graph.
+ * dymoe_kernel_name: the kernel's name as a profiler shows it, NULL if unknown.
+ */
+int dymoe_timing_enable(dymoe_ctx* ctx, unsigned kernel_mask);
+int dymoe_timing_read(dymoe_ctx* ctx, int kernel, double* total_ms, int* launches);
+const char* dymoe_kernel_name(int kernel);
+
 #ifdef __cplusplus
 }
 #endif

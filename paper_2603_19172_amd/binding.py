@@ -32,7 +32,11 @@ EXPORTS = [
     "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_expert_importance",
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
     "dymoe_quantize_experts", "dymoe_moe_ffn_mixed",
+    "dymoe_timing_enable", "dymoe_timing_read", "dymoe_kernel_name",
 ]
+
+KERNELS = ["route", "token_norm", "importance", "assign", "quantize", "gemv_phase1",
+           "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine"]
 
 
 class ExpertFmt(C.Structure):
@@ -68,6 +72,14 @@ lib.dymoe_quantize_experts.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]
 lib.dymoe_moe_ffn_mixed.restype = _i
 lib.dymoe_moe_ffn_mixed.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i,
                                     _vp, _vp, _sz, _vp]
+
+
+lib.dymoe_timing_enable.restype = _i
+lib.dymoe_timing_enable.argtypes = [_vp, C.c_uint]
+lib.dymoe_timing_read.restype = _i
+lib.dymoe_timing_read.argtypes = [_vp, _i, C.POINTER(_d), C.POINTER(_i)]
+lib.dymoe_kernel_name.restype = C.c_char_p
+lib.dymoe_kernel_name.argtypes = [_i]
 
 
 class DymoeError(RuntimeError):
@@ -128,6 +140,18 @@ class Context:
 
     def __del__(self):
         self.close()
+
+    def timing_enable(self, kernels=()):
+        mask = 0
+        for name in kernels:
+            mask |= 1 << KERNELS.index(name)
+        _check(lib.dymoe_timing_enable(self._h, mask), "dymoe_timing_enable")
+
+    def timing_read(self, kernel):
+        ms, n = _d(0.0), _i(0)
+        _check(lib.dymoe_timing_read(self._h, KERNELS.index(kernel), C.byref(ms), C.byref(n)),
+               "dymoe_timing_read")
+        return ms.value, n.value
 
     # -- S1
     def route_topk(self, x, wg, bias, k, renorm=True, probs=True, stream=None):

@@ -19,11 +19,73 @@ int dymoe_create(dymoe_ctx** out, int device)
     if (!c) return DYMOE_EHIP;
     c->device = device;
     c->num_cu = prop.multiProcessorCount;
+    c->timing_mask = 0;
     *out = c;
     return DYMOE_OK;
 }
 
-void dymoe_destroy(dymoe_ctx* ctx) { delete ctx; }
+static void drop_timed(dymoe_ctx* ctx)
+{
+    for (auto& t : ctx->timed) {
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+    }
+    ctx->timed.clear();
+}
+
+void dymoe_destroy(dymoe_ctx* ctx)
+{
+    if (!ctx) return;
+    drop_timed(ctx);
+    delete ctx;
+}
+
+int dymoe_timing_enable(dymoe_ctx* ctx, unsigned kernel_mask)
+{
+    if (!ctx) return DYMOE_ENOCTX;
+    DYMOE_REQUIRE((kernel_mask >> DYMOE_K_COUNT) == 0);
+    drop_timed(ctx);
+    ctx->timing_mask = kernel_mask;
+    return DYMOE_OK;
+}
+
+int dymoe_timing_read(dymoe_ctx* ctx, int kernel, double* total_ms, int* launches)
+{
+    DYMOE_REQUIRE(kernel >= 0 && kernel < DYMOE_K_COUNT && total_ms && launches);
+    if (!ctx) return DYMOE_ENOCTX;
+    double sum = 0.0;
+    int n = 0;
+    for (auto& t : ctx->timed) {
+        if (t.kernel != kernel) continue;
+        if (hipEventSynchronize(t.stop) != hipSuccess) return DYMOE_EHIP;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, t.start, t.stop) != hipSuccess) return DYMOE_EHIP;
+        sum += (double)ms;
+        n++;
+    }
+    *total_ms = sum;
+    *launches = n;
+    return DYMOE_OK;
+}
+
+const char* dymoe_kernel_name(int kernel)
+{
+    switch (kernel) {
+    case DYMOE_K_ROUTE: return "route_kernel";
+    case DYMOE_K_TOKEN_NORM: return "token_norm_kernel";
+    case DYMOE_K_IMPORTANCE: return "importance_prefill_kernel";
+    case DYMOE_K_ASSIGN: return "assign_precision_kernel";
+    case DYMOE_K_QUANTIZE: return "quantize_experts_kernel";
+    case DYMOE_K_GEMV_PHASE1: return "gemv_phase1_kernel";
+    case DYMOE_K_GEMV_PHASE2: return "gemv_phase2_kernel";
+    case DYMOE_K_GEMV_COMBINE: return "gemv_combine_kernel";
+    case DYMOE_K_PLAN: return "plan_kernel";
+    case DYMOE_K_GEMM1: return "gemm_kernel<1>";
+    case DYMOE_K_GEMM2: return "gemm_kernel<2>";
+    case DYMOE_K_GEMM_COMBINE: return "gemm_combine_kernel";
+    default: return nullptr;
+    }
+}
 
 const char* dymoe_strerror(int code)
 {

@@ -6,9 +6,65 @@
 
 #include "dymoe.h"
 
+#include <vector>
+
+// kernel ids of the per-kernel timing facility (dymoe_timing_*)
+enum {
+    DYMOE_K_ROUTE = 0,
+    DYMOE_K_TOKEN_NORM,
+    DYMOE_K_IMPORTANCE,
+    DYMOE_K_ASSIGN,
+    DYMOE_K_QUANTIZE,
+    DYMOE_K_GEMV_PHASE1,
+    DYMOE_K_GEMV_PHASE2,
+    DYMOE_K_GEMV_COMBINE,
+    DYMOE_K_PLAN,
+    DYMOE_K_GEMM1,
+    DYMOE_K_GEMM2,
+    DYMOE_K_GEMM_COMBINE,
+    DYMOE_K_COUNT
+};
+
+struct dymoe_timed_launch {
+    int kernel;
+    hipEvent_t start, stop;
+};
+
 struct dymoe_ctx {
     int device;
     int num_cu;
+    unsigned timing_mask;                    // bit i set: time launches of kernel i
+    std::vector<dymoe_timed_launch> timed;   // recorded, not yet read
+};
+
+// Brackets one kernel launch with HIP events on the launch stream when the
+// context asks for that kernel to be timed; otherwise does nothing.
+struct dymoe_kernel_timer {
+    dymoe_ctx* ctx;
+    hipStream_t st;
+    dymoe_timed_launch rec;
+    bool on;
+    dymoe_kernel_timer(dymoe_ctx* c, int kernel, hipStream_t s) : ctx(c), st(s), on(false)
+    {
+        if (!c || !(c->timing_mask & (1u << kernel))) return;
+        rec.kernel = kernel;
+        if (hipEventCreate(&rec.start) != hipSuccess) return;
+        if (hipEventCreate(&rec.stop) != hipSuccess) {
+            (void)hipEventDestroy(rec.start);
+            return;
+        }
+        on = hipEventRecord(rec.start, st) == hipSuccess;
+        if (!on) {
+            (void)hipEventDestroy(rec.start);
+            (void)hipEventDestroy(rec.stop);
+        }
+    }
+    ~dymoe_kernel_timer()
+    {
+        if (!on) return;
+        (void)hipEventRecord(rec.stop, st);
+        ctx->timed.push_back(rec);
+    }
 };
 
 #define DYMOE_REQUIRE(cond) \

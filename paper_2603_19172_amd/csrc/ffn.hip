@@ -4,10 +4,10 @@
 #include "ffn_layout.hpp"
 
 namespace dymoe {
-int ffn_gemv_launch(const void* x, const int32_t* idx, const float* w, const uint8_t* bits,
+int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w, const uint8_t* bits,
                     const dymoe_expert_fmt* table, int T, int H, int F, int E, int k,
                     int out_dtype, void* y, void* workspace, hipStream_t st);
-int ffn_gemm_launch(const void* x, const int32_t* idx, const float* w, const uint8_t* bits,
+int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w, const uint8_t* bits,
                     const dymoe_expert_fmt* table, int T, int H, int F, int E, int k,
                     int out_dtype, void* y, void* workspace, hipStream_t st);
 }  // namespace dymoe
@@ -36,8 +36,8 @@ extern "C" int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t*
     if (!ctx) return DYMOE_ENOCTX;
     if (T == 0) return DYMOE_OK;
     if (path == DYMOE_PATH_GEMV)
-        return dymoe::ffn_gemv_launch(x, idx, w, bits, table, T, H, F, E, k, out_dtype, y, workspace,
+        return dymoe::ffn_gemv_launch(ctx, x, idx, w, bits, table, T, H, F, E, k, out_dtype, y, workspace,
                                       (hipStream_t)stream);
-    return dymoe::ffn_gemm_launch(x, idx, w, bits, table, T, H, F, E, k, out_dtype, y, workspace,
+    return dymoe::ffn_gemm_launch(ctx, x, idx, w, bits, table, T, H, F, E, k, out_dtype, y, workspace,
                                   (hipStream_t)stream);
 }

@@ -389,7 +389,7 @@ __global__ __launch_bounds__(256) void gemv_combine_kernel(
     else reinterpret_cast<uint16_t*>(y)[i] = (uint16_t)f32_to_bf16_bits(acc);
 }
 
-int ffn_gemv_launch(const void* x, const int32_t* idx, const float* w, const uint8_t* bits,
+int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w, const uint8_t* bits,
                     const dymoe_expert_fmt* table, int T, int H, int F, int E, int k,
                     int out_dtype, void* y, void* workspace, hipStream_t st)
 {
@@ -402,6 +402,8 @@ int ffn_gemv_launch(const void* x, const int32_t* idx, const float* w, const uin
     const int rows1 = 32, rows2 = 64;
     const dim3 g1((unsigned)((F + rows1 - 1) / rows1), (unsigned)P);
     const uint16_t* xb = (const uint16_t*)x;
+    {
+    dymoe_kernel_timer timer(ctx, DYMOE_K_GEMV_PHASE1, st);
     switch (nseg1) {
     case 1: hipLaunchKernelGGL((gemv_phase1_kernel<1>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
     case 2: hipLaunchKernelGGL((gemv_phase1_kernel<2>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
@@ -409,12 +411,17 @@ int ffn_gemv_launch(const void* x, const int32_t* idx, const float* w, const uin
     case 4: hipLaunchKernelGGL((gemv_phase1_kernel<4>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
     default: return DYMOE_ENOTSUP;
     }
+    }
     DYMOE_HIP_LAUNCH_CHECK();
     const dim3 g2((unsigned)((H + rows2 - 1) / rows2), (unsigned)nseg2, (unsigned)P);
+    {
+    dymoe_kernel_timer timer(ctx, DYMOE_K_GEMV_PHASE2, st);
     hipLaunchKernelGGL(gemv_phase2_kernel, g2, dim3(kGvThreads), 0, st, hbuf, idx, bits, table, H, F,
                        E, rows2, nseg2, part);
+    }
     DYMOE_HIP_LAUNCH_CHECK();
     const long n = (long)T * H;
+    dymoe_kernel_timer timer(ctx, DYMOE_K_GEMV_COMBINE, st);
     hipLaunchKernelGGL(gemv_combine_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part,
                        idx, w, bits, T, H, E, k, nseg2, out_dtype, y);
     DYMOE_HIP_LAUNCH_CHECK();

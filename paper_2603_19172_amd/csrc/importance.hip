@@ -134,6 +134,7 @@ int dymoe_expert_importance(dymoe_ctx* ctx, int phase, const int32_t* idx, const
     DYMOE_HIP_LAUNCH_CHECK();
     if (T > 0) {
         const unsigned blocks = (unsigned)((T + dymoe::kImpThreads - 1) / dymoe::kImpThreads);
+        dymoe_kernel_timer timer(ctx, DYMOE_K_IMPORTANCE, st);
         hipLaunchKernelGGL(dymoe::importance_prefill_kernel, dim3(blocks), dim3(dymoe::kImpThreads),
                            0, st, idx, token_score, T, E, k, k_hh, prefill ? 1 : 0,
                            (int32_t*)importance, load);
@@ -176,6 +177,7 @@ int dymoe_assign_precision(dymoe_ctx* ctx, int phase, const void* importance,
     if (!ctx) return DYMOE_ENOCTX;
     hipStream_t st = (hipStream_t)stream;
     const unsigned threads = (unsigned)(((E + 63) / 64) * 64);
+    dymoe_kernel_timer timer(ctx, DYMOE_K_ASSIGN, st);
     if (phase == DYMOE_PHASE_PREFILL)
         hipLaunchKernelGGL((dymoe::assign_precision_kernel<int32_t>), dim3(1), dim3(threads), 0, st,
                            (const int32_t*)importance, load, E, tt, floor_bits, bits, rank);

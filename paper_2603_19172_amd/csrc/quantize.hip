@@ -143,6 +143,7 @@ int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits,
     const long per_block = dymoe::kQThreads * dymoe::kQUnroll;
     const long blocks = (n_chunks + per_block - 1) / per_block;
     if (blocks > 0x7fffffffL) return DYMOE_ENOTSUP;
+    dymoe_kernel_timer timer(ctx, DYMOE_K_QUANTIZE, (hipStream_t)stream);
     hipLaunchKernelGGL(dymoe::quantize_pack_kernel, dim3((unsigned)blocks), dim3(dymoe::kQThreads), 0,
                        (hipStream_t)stream, (const uint16_t*)w, n_chunks, bits, codes,
                        (uint16_t*)scale, (uint16_t*)zero);
@@ -162,6 +163,7 @@ int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const 
     const long per_block = dymoe::kQThreads * dymoe::kQUnroll;
     const long blocks = (n_chunks + per_block - 1) / per_block;
     if (blocks > 0x7fffffffL) return DYMOE_ENOTSUP;
+    dymoe_kernel_timer timer(ctx, DYMOE_K_QUANTIZE, (hipStream_t)stream);
     hipLaunchKernelGGL(dymoe::quantize_experts_kernel, dim3((unsigned)blocks, (unsigned)(3 * E)),
                        dim3(dymoe::kQThreads), 0, (hipStream_t)stream, table, bits, load, H, F);
     DYMOE_HIP_LAUNCH_CHECK();

@@ -136,12 +136,13 @@ __global__ __launch_bounds__(256) void token_norm_kernel(const uint16_t* __restr
 }
 
 template <int TW, int NCH>
-static int launch_route(const void* x, const void* wg, const float* bias, int T, int H, int E,
+static int launch_route(dymoe_ctx* ctx, const void* x, const void* wg, const float* bias, int T, int H, int E,
                         int k, int renorm, int32_t* idx, float* w, float* probs, hipStream_t st)
 {
     const int tokens_per_block = kRouteWaves * TW;
     const unsigned blocks = (unsigned)((T + tokens_per_block - 1) / tokens_per_block);
     const size_t smem = ((size_t)kRouteWaves * TW * E + (size_t)kRouteWaves * k) * sizeof(float);
+    dymoe_kernel_timer timer(ctx, DYMOE_K_ROUTE, st);
     hipLaunchKernelGGL((route_kernel<TW, NCH>), dim3(blocks), dim3(kRouteWaves * kWave), smem, st,
                        (const uint16_t*)x, (const uint16_t*)wg, bias, T, H, E, k, renorm, idx, w,
                        probs);
@@ -168,10 +169,10 @@ int dymoe_route_topk(dymoe_ctx* ctx, const void* x, const void* wg, const float*
     // tokens per wavefront chosen so that their activations fit in 128 VGPRs;
     // few tokens: one per wavefront, to spread over more compute units
     if (H <= 4096 && T >= 1024 && E <= 256)
-        return dymoe::launch_route<4, 8>(x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
-    if (H <= 4096) return dymoe::launch_route<1, 8>(x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
-    if (H <= 8192) return dymoe::launch_route<1, 16>(x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
-    return dymoe::launch_route<1, 32>(x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
+        return dymoe::launch_route<4, 8>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
+    if (H <= 4096) return dymoe::launch_route<1, 8>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
+    if (H <= 8192) return dymoe::launch_route<1, 16>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
+    return dymoe::launch_route<1, 32>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
 }
 
 int dymoe_token_score_norm(dymoe_ctx* ctx, const void* x, int T, int H, float* score, void* stream)
@@ -181,6 +182,7 @@ int dymoe_token_score_norm(dymoe_ctx* ctx, const void* x, int T, int H, float* s
     if (!ctx) return DYMOE_ENOCTX;
     if (T == 0) return DYMOE_OK;
     const unsigned blocks = (unsigned)((T + 3) / 4);
+    dymoe_kernel_timer timer(ctx, DYMOE_K_TOKEN_NORM, (hipStream_t)stream);
     hipLaunchKernelGGL(dymoe::token_norm_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
                        (const uint16_t*)x, T, H, score);
     DYMOE_HIP_LAUNCH_CHECK();

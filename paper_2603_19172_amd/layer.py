@@ -1,0 +1,107 @@
+"""One MoE layer with every buffer pre-allocated, so that a step is nothing but
+the five libdymoe calls enqueued back to back on one stream (no allocation, no
+host read-back): route -> importance -> precision -> quantize -> FFN.
+
+Argument marshalling only; all arithmetic is in libdymoe.so.
+"""
+import ctypes as C
+
+import torch
+
+from . import binding as B
+
+
+class ExpertStore:
+    """Device-resident weights of a layer's experts: the bf16 originals plus
+    output buffers for the int4 and int2 formats, and the dymoe_expert_fmt table
+    that points at them."""
+
+    def __init__(self, w_bf16, H, F, device, group=64):
+        # w_bf16: list over experts of [W1 [F,H], W3 [F,H], W2 [H,F]] bf16 tensors on `device`
+        self.E = len(w_bf16)
+        self.H, self.F = H, F
+        self.w = w_bf16
+        self.q = {}
+        for b in (4, 2):
+            self.q[b] = [[(torch.empty((n, k * b // 8), dtype=torch.uint8, device=device),
+                           torch.empty((n, k // group), dtype=torch.float16, device=device),
+                           torch.empty((n, k // group), dtype=torch.float16, device=device))
+                          for n, k in ((F, H), (F, H), (H, F))] for _ in range(self.E)]
+        experts = [{"w": self.w[e], "q4": self.q[4][e], "q2": self.q[2][e]} for e in range(self.E)]
+        self.table, self._keep = B.make_expert_table(experts, device)
+
+    def clone(self):
+        return ExpertStore([[m.clone() for m in ex] for ex in self.w], self.H, self.F,
+                           self.table.device)
+
+
+class MoELayer:
+    def __init__(self, ctx, T, H, F, E, k, phase, tier_count, tier_bits, k_hh=0, floor_bits=0,
+                 out_dtype=B.OUT_BF16, path=B.PATH_AUTO, device="cuda:0", group=64):
+        self.ctx, self.T, self.H, self.F, self.E, self.k = ctx, T, H, F, E, k
+        self.phase = B.PHASE_PREFILL if phase == "prefill" else B.PHASE_DECODE
+        self.k_hh, self.floor_bits, self.out_dtype, self.path, self.group = k_hh, floor_bits, out_dtype, path, group
+        n = len(tier_count)
+        self._tc = (C.c_int32 * n)(*[int(v) for v in tier_count])
+        self._tb = (C.c_uint8 * n)(*[int(v) for v in tier_bits])
+        self._nt = n
+        dev = device
+        self.idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+        self.gate = torch.empty((T, k), dtype=torch.float32, device=dev)
+        self.probs = torch.empty((T, E), dtype=torch.float32, device=dev)
+        self.score = torch.empty((T,), dtype=torch.float32, device=dev)
+        self.imp = torch.empty((E,), dtype=torch.int32 if self.phase == B.PHASE_PREFILL else torch.float32, device=dev)
+        self.load = torch.empty((E,), dtype=torch.int32, device=dev)
+        self.bits = torch.empty((E,), dtype=torch.uint8, device=dev)
+        self.rank = torch.empty((E,), dtype=torch.int32, device=dev)
+        self.y = torch.empty((T, H), dtype=torch.bfloat16 if out_dtype == B.OUT_BF16 else torch.float32, device=dev)
+        self.ws_bytes = B.workspace_bytes(T, H, F, E, k)
+        self.ws = torch.empty((self.ws_bytes,), dtype=torch.uint8, device=dev)
+
+    # the individual steps; each is one C call
+    def route(self, x, wg, bias, st):
+        B._check(B.lib.dymoe_route_topk(self.ctx._h, x.data_ptr(), wg.data_ptr(),
+                                        bias.data_ptr() if bias is not None else None, self.T, self.H,
+                                        self.E, self.k, 1, self.idx.data_ptr(), self.gate.data_ptr(),
+                                        self.probs.data_ptr(), st), "dymoe_route_topk")
+
+    def importance(self, x, st):
+        if self.phase == B.PHASE_PREFILL:
+            B._check(B.lib.dymoe_token_score_norm(self.ctx._h, x.data_ptr(), self.T, self.H,
+                                                  self.score.data_ptr(), st), "dymoe_token_score_norm")
+        B._check(B.lib.dymoe_expert_importance(self.ctx._h, self.phase, self.idx.data_ptr(),
+                                               self.probs.data_ptr(), self.score.data_ptr(), self.T,
+                                               self.E, self.k, self.k_hh, self.imp.data_ptr(),
+                                               self.load.data_ptr(), st), "dymoe_expert_importance")
+
+    def assign(self, st):
+        B._check(B.lib.dymoe_assign_precision(self.ctx._h, self.phase, self.imp.data_ptr(),
+                                              self.load.data_ptr(), self.E, self._nt,
+                                              C.cast(self._tc, C.c_void_p), C.cast(self._tb, C.c_void_p),
+                                              self.floor_bits, self.bits.data_ptr(),
+                                              self.rank.data_ptr(), st), "dymoe_assign_precision")
+
+    def quantize(self, store, st):
+        B._check(B.lib.dymoe_quantize_experts(self.ctx._h, store.table.data_ptr(), self.bits.data_ptr(),
+                                              self.load.data_ptr(), self.E, self.H, self.F, self.group,
+                                              st), "dymoe_quantize_experts")
+
+    def ffn(self, x, store, st):
+        B._check(B.lib.dymoe_moe_ffn_mixed(self.ctx._h, x.data_ptr(), self.idx.data_ptr(),
+                                           self.gate.data_ptr(), self.bits.data_ptr(),
+                                           store.table.data_ptr(), self.T, self.H, self.F, self.E,
+                                           self.k, self.group, self.out_dtype, self.path,
+                                           self.y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, st),
+                 "dymoe_moe_ffn_mixed")
+
+    def step(self, x, wg, bias, store, quantize=True, stream=None):
+        """The whole hot path for one batch.  quantize=False assumes the formats
+        the assignment selects are already materialised in `store`."""
+        st = B._stream(stream)
+        self.route(x, wg, bias, st)
+        self.importance(x, st)
+        self.assign(st)
+        if quantize:
+            self.quantize(store, st)
+        self.ffn(x, store, st)
+        return self.y

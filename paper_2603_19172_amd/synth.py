@@ -77,8 +77,12 @@ def _rng(config_id: int, tensor_id: int) -> np.random.Generator:
 def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
     """Round float32 to bf16 (nearest even), returned as uint16 bit patterns."""
     u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
-    r = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
-    return ((u + r) >> np.uint32(16)).astype(np.uint16)
+    r = u >> np.uint32(16)
+    r &= np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u
+    # the rounded value is the high half of each little-endian word
+    return np.ascontiguousarray(r.view(np.uint16).reshape(u.shape + (2,))[..., 1])
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -118,8 +122,25 @@ def router(cfg: MoEConfig) -> Tuple[np.ndarray, Optional[np.ndarray]]:
     return wg, bias
 
 
+def expert_matrix(cfg: MoEConfig, e: int, i: int) -> np.ndarray:
+    """Matrix i (0: W1 [F,H], 1: W3 [F,H], 2: W2 [H,F]) of expert e, bf16 bits ~ N(0, weight_std)."""
+    shape = (cfg.F, cfg.H) if i < 2 else (cfg.H, cfg.F)
+    return normal_bf16(cfg.config_id, _TID_EXPERT + 3 * e + i, shape, cfg.weight_std)
+
+
 def expert_weights(cfg: MoEConfig, e: int) -> List[np.ndarray]:
     """[W1 [F,H], W3 [F,H], W2 [H,F]] bf16 bits ~ N(0, weight_std)."""
-    shapes = [(cfg.F, cfg.H), (cfg.F, cfg.H), (cfg.H, cfg.F)]
-    return [normal_bf16(cfg.config_id, _TID_EXPERT + 3 * e + i, shapes[i], cfg.weight_std)
-            for i in range(3)]
+    return [expert_matrix(cfg, e, i) for i in range(3)]
+
+
+def expert_weights_many(cfg: MoEConfig, experts, workers: int = 8):
+    """{e: [W1, W3, W2]} for several experts, drawn on a thread pool (every
+    matrix has its own key, so the bytes do not depend on the schedule)."""
+    from concurrent.futures import ThreadPoolExecutor
+    jobs = [(e, i) for e in experts for i in range(3)]
+    with ThreadPoolExecutor(max_workers=max(1, workers)) as pool:
+        mats = list(pool.map(lambda j: expert_matrix(cfg, j[0], j[1]), jobs))
+    out = {}
+    for (e, i), m in zip(jobs, mats):
+        out.setdefault(e, [None, None, None])[i] = m
+    return out

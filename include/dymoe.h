@@ -15,8 +15,9 @@
  * Conventions that hold for every call unless a comment says otherwise:
  *  - Every pointer is a DEVICE pointer; arguments marked "host" are host
  *    pointers that are read before the call returns.
- *  - The caller allocates and owns every buffer.  The library never allocates
- *    or frees device memory and keeps no pointer after the call returns.
+ *  - The caller allocates and owns every buffer.  Apart from the context's
+ *    own scratch (dymoe_create / dymoe_destroy) the library never allocates or
+ *    frees device memory and keeps no pointer after the call returns.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls enqueue work and return without synchronising; nothing is read
  *    back to the host, so the five steps chain on one stream with no host
@@ -61,7 +62,10 @@ extern "C" {
 #define DYMOE_MAX_TIERS 8
 #define DYMOE_MAX_EXPERTS 1024
 
-typedef struct dymoe_ctx dymoe_ctx; /* opaque; holds the device ordinal and its properties */
+/* opaque; holds the device ordinal, its properties and 64 KiB of device scratch
+ * that dymoe_create allocates and dymoe_destroy frees (work lists).  Calls that
+ * share a context must be issued on one stream, or be ordered by the caller. */
+typedef struct dymoe_ctx dymoe_ctx;
 
 /*
  * One expert's weights in every precision the caller has materialised.
@@ -190,6 +194,7 @@ int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits,
  * into table[e].q4/s4/z4 or q2/s2/z2 (same arithmetic and layout as
  * dymoe_quantize_pack).  Experts at 16 or 0 bits are left untouched.
  * table [E] device, bits [E] uint8 device, load [E] int32 device or NULL.
+ * Weight and code pointers in the table must be 16-byte aligned.
  */
 int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const uint8_t* bits,
                            const int32_t* load, int E, int H, int F, int group, void* stream);
@@ -220,7 +225,8 @@ int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t* idx, const
  * dymoe_timing_enable: launches of the kernels whose bit is set in kernel_mask
  * (bit i = kernel id i, ids 0..11 in the order route, token_norm, importance,
  * assign, quantize, gemv_phase1, gemv_phase2, gemv_combine, plan, gemm1, gemm2,
- * gemm_combine) are bracketed by HIP events on the launch stream; 0 switches
+ * gemm_combine) carry a start and a stop HIP event on the dispatch itself, so
+ * the interval is the kernel's execution time on the launch stream; 0 switches
  * timing off.  Either way, records not yet read are dropped.
  * dymoe_timing_read: waits for the recorded launches of `kernel`, returns
  * their summed duration in milliseconds and their count (host pointers).

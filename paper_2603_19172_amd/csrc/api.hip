@@ -20,6 +20,15 @@ int dymoe_create(dymoe_ctx** out, int device)
     c->device = device;
     c->num_cu = prop.multiProcessorCount;
     c->timing_mask = 0;
+    c->scratch = nullptr;
+    int prev = 0;
+    bool ok = hipGetDevice(&prev) == hipSuccess && hipSetDevice(device) == hipSuccess;
+    ok = ok && hipMalloc(&c->scratch, kDymoeScratchBytes) == hipSuccess;
+    (void)hipSetDevice(prev);
+    if (!ok) {
+        delete c;
+        return DYMOE_EHIP;
+    }
     *out = c;
     return DYMOE_OK;
 }
@@ -37,6 +46,7 @@ void dymoe_destroy(dymoe_ctx* ctx)
 {
     if (!ctx) return;
     drop_timed(ctx);
+    if (ctx->scratch) (void)hipFree(ctx->scratch);
     delete ctx;
 }
 

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "dymoe.h"
@@ -33,39 +34,36 @@ struct dymoe_timed_launch {
 struct dymoe_ctx {
     int device;
     int num_cu;
+    void* scratch;                           // small device buffer owned by the context (worklists)
     unsigned timing_mask;                    // bit i set: time launches of kernel i
     std::vector<dymoe_timed_launch> timed;   // recorded, not yet read
 };
 
-// Brackets one kernel launch with HIP events on the launch stream when the
-// context asks for that kernel to be timed; otherwise does nothing.
-struct dymoe_kernel_timer {
-    dymoe_ctx* ctx;
-    hipStream_t st;
-    dymoe_timed_launch rec;
-    bool on;
-    dymoe_kernel_timer(dymoe_ctx* c, int kernel, hipStream_t s) : ctx(c), st(s), on(false)
-    {
-        if (!c || !(c->timing_mask & (1u << kernel))) return;
-        rec.kernel = kernel;
-        if (hipEventCreate(&rec.start) != hipSuccess) return;
-        if (hipEventCreate(&rec.stop) != hipSuccess) {
+// Launch a kernel.  When the context asks for this kernel to be timed, the
+// launch carries a start and a stop event on the dispatch itself
+// (hipExtLaunchKernelGGL), so the recorded interval is the kernel's own
+// execution time on the launch stream, with no marker packets around it.
+template <typename... KArgs, typename... Args>
+inline void dymoe_launch(dymoe_ctx* ctx, int kernel_id, void (*kernel)(KArgs...), dim3 grid, dim3 block,
+                         size_t smem, hipStream_t st, Args&&... args)
+{
+    if (ctx && ((ctx->timing_mask >> kernel_id) & 1u)) {
+        dymoe_timed_launch rec;
+        rec.kernel = kernel_id;
+        if (hipEventCreate(&rec.start) == hipSuccess) {
+            if (hipEventCreate(&rec.stop) == hipSuccess) {
+                hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)smem, st, rec.start, rec.stop, 0,
+                                      static_cast<KArgs>(args)...);
+                ctx->timed.push_back(rec);
+                return;
+            }
             (void)hipEventDestroy(rec.start);
-            return;
-        }
-        on = hipEventRecord(rec.start, st) == hipSuccess;
-        if (!on) {
-            (void)hipEventDestroy(rec.start);
-            (void)hipEventDestroy(rec.stop);
         }
     }
-    ~dymoe_kernel_timer()
-    {
-        if (!on) return;
-        (void)hipEventRecord(rec.stop, st);
-        ctx->timed.push_back(rec);
-    }
-};
+    hipLaunchKernelGGL(kernel, grid, block, (uint32_t)smem, st, static_cast<KArgs>(args)...);
+}
+
+constexpr size_t kDymoeScratchBytes = 64 * 1024;
 
 #define DYMOE_REQUIRE(cond) \
     do {                    \

@@ -491,8 +491,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const uint16_t* xb = (const uint16_t*)x;
 
     {
-        dymoe_kernel_timer timer(ctx, DYMOE_K_PLAN, st);
-        hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, idx, bits, P, E, kGemmTileM, plan);
+        dymoe_launch(ctx, DYMOE_K_PLAN, plan_kernel, dim3(1), dim3(1024), 0, st, idx, bits, P, E, kGemmTileM, plan);
     }
     DYMOE_HIP_LAUNCH_CHECK();
     const long n8 = (long)T * H / 8;
@@ -501,21 +500,18 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const int max_tiles = P / kGemmTileM + E;
     const dim3 g1((unsigned)((F + 127) / 128), (unsigned)max_tiles);
     {
-        dymoe_kernel_timer timer(ctx, DYMOE_K_GEMM1, st);
-        hipLaunchKernelGGL((gemm_kernel<1>), g1, dim3(kGmThreads), 0, st, xb, xh, (const uint16_t*)nullptr,
+        dymoe_launch(ctx, DYMOE_K_GEMM1, (gemm_kernel<1>), g1, dim3(kGmThreads), 0, st, xb, xh, (const uint16_t*)nullptr,
                            bits, table, plan, P, E, k, H, F, hbuf, (float*)nullptr);
     }
     DYMOE_HIP_LAUNCH_CHECK();
     const dim3 g2((unsigned)((H + 255) / 256), (unsigned)max_tiles);
     {
-        dymoe_kernel_timer timer(ctx, DYMOE_K_GEMM2, st);
-        hipLaunchKernelGGL((gemm_kernel<2>), g2, dim3(kGmThreads), 0, st, xb, xh, hbuf, bits, table, plan,
+        dymoe_launch(ctx, DYMOE_K_GEMM2, (gemm_kernel<2>), g2, dim3(kGmThreads), 0, st, xb, xh, hbuf, bits, table, plan,
                            P, E, k, H, F, (uint16_t*)nullptr, opair);
     }
     DYMOE_HIP_LAUNCH_CHECK();
     const long n4 = (long)T * (H / 4);
-    dymoe_kernel_timer timer(ctx, DYMOE_K_GEMM_COMBINE, st);
-    hipLaunchKernelGGL(gemm_combine_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, opair,
+    dymoe_launch(ctx, DYMOE_K_GEMM_COMBINE, gemm_combine_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, opair,
                        idx, w, bits, T, H, E, k, out_dtype, y);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;

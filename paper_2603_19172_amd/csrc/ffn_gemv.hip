@@ -10,6 +10,11 @@
 //               or fp32 FMA (phase 2, fp32 intermediate)
 //   int4 rows : one 16-byte load per lane and segment (32 codes = half a group)
 //   int2 rows : one  8-byte load per lane and segment (32 codes = half a group)
+// The row loop is software pipelined: the loads of the next batch of rows are
+// issued before the current batch is reduced, and every load is unconditional
+// (lanes past the end of a row re-read the row's tail against zero
+// activations) so that the loop body is straight-line code.
+//
 // Quantised codes are turned into fp16 without integer->float conversions:
 // OR-ing a code field into the mantissa of 2^n (n chosen so that the field's
 // lowest bit weighs 1) gives the fp16 number 2^n + q.  The dot product with
@@ -25,6 +30,29 @@ namespace dymoe {
 
 constexpr int kGvThreads = 256;
 constexpr int kGvWaves = kGvThreads / kWave;
+
+// ------------------------------------------------------------------ reductions
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_get(float v)
+{
+    // lanes whose row is masked out, or whose source lane does not exist, read 0
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, true));
+}
+
+// sum over the 64 lanes, returned in every lane
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+    v += dpp_get<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v += dpp_get<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v += dpp_get<0x141, 0xF>(v);   // row_half_mirror
+    v += dpp_get<0x140, 0xF>(v);   // row_mirror: every lane of a row holds the row's sum
+    v += dpp_get<0x142, 0xA>(v);   // row_bcast15 into rows 1 and 3
+    v += dpp_get<0x143, 0xC>(v);   // row_bcast31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+// ------------------------------------------------------------------ activations
 
 // 32 activations of one lane (quantised layouts), as fp16 pairs ordered for
 // the code extraction below, plus the two per-lane constants.
@@ -117,6 +145,14 @@ __device__ __forceinline__ float dot_q2(const uint2 c, const LaneX& lx)
     return acc;
 }
 
+// activations of one lane for bf16 rows: NSEG x 4 chunks of 8, packed bf16 pairs
+template <int NSEG>
+struct LaneXB {
+    uint4 r[NSEG][4];
+};
+
+// ------------------------------------------------------------------ weight rows
+
 struct ExpertMat {
     const uint16_t* w;      // bf16
     const uint8_t* q;       // packed codes at the expert's precision
@@ -140,32 +176,128 @@ __device__ __forceinline__ ExpertMat pick_mat(const dymoe_expert_fmt& ex, int ma
     return m;
 }
 
-// per-lane partial of one quantised row over NSEG segments of a K-column row
+// what one lane loads of one row: NSEG segments starting at column seg0 * 2048
+template <int BITS, int NSEG> struct RowRegs;
+template <int NSEG> struct RowRegs<16, NSEG> { uint4 c[NSEG][4]; };
+template <int NSEG> struct RowRegs<4, NSEG> { uint4 c[NSEG]; uint16_t s[NSEG], z[NSEG]; };
+template <int NSEG> struct RowRegs<2, NSEG> { uint2 c[NSEG]; uint16_t s[NSEG], z[NSEG]; };
+
+// Issue the loads of row `row` (K columns).  Lanes past the end of the row
+// re-read its tail: finite weights against zero activations add nothing.
 template <int BITS, int NSEG>
-__device__ __forceinline__ float qrow_partial(const ExpertMat& m, long row, int K, int lane,
-                                              const LaneX (&lx)[NSEG])
+__device__ __forceinline__ void load_row(const ExpertMat& m, long row, int K, int seg0, int lane,
+                                         RowRegs<BITS, NSEG>& rr)
 {
-    const long G = K >> 6;
-    const uint8_t* codes = m.q + row * ((long)K * BITS / 8);
+    if constexpr (BITS == 16) {
+        const uint16_t* base = m.w + row * K;
+#pragma unroll
+        for (int s = 0; s < NSEG; s++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int col = min((seg0 + s) * kSeg + (j * kWave + lane) * 8, K - 8);
+                rr.c[s][j] = *reinterpret_cast<const uint4*>(base + col);
+            }
+    } else {
+        const long G = K >> 6;
+        const uint8_t* codes = m.q + row * ((long)K * BITS / 8);
+#pragma unroll
+        for (int s = 0; s < NSEG; s++) {
+            const int col0 = min((seg0 + s) * kSeg + 32 * lane, K - 32);
+            if constexpr (BITS == 4) rr.c[s] = *reinterpret_cast<const uint4*>(codes + (col0 >> 1));
+            else rr.c[s] = *reinterpret_cast<const uint2*>(codes + (col0 >> 2));
+            rr.s[s] = m.s[row * G + (col0 >> 6)];
+            rr.z[s] = m.z[row * G + (col0 >> 6)];
+        }
+    }
+}
+
+// per-lane partial dot product of a loaded quantised row
+template <int BITS, int NSEG>
+__device__ __forceinline__ float dot_row_q(const RowRegs<BITS, NSEG>& rr, const LaneX (&lx)[NSEG])
+{
     float part = 0.0f;
 #pragma unroll
     for (int s = 0; s < NSEG; s++) {
-        const int col0 = s * kSeg + 32 * lane;
-        if (col0 < K) {
-            const long g = row * G + (col0 >> 6);
-            const float sc = h2f(f16_from_bits(m.s[g]));
-            const float zr = h2f(f16_from_bits(m.z[g]));
-            float acc;
-            if (BITS == 4) acc = dot_q4(*reinterpret_cast<const uint4*>(codes + (col0 >> 1)), lx[s]);
-            else acc = dot_q2(*reinterpret_cast<const uint2*>(codes + (col0 >> 2)), lx[s]);
-            part += sc * (acc - lx[s].xoff) + zr * lx[s].xsum;
-        }
+        float acc;
+        if constexpr (BITS == 4) acc = dot_q4(rr.c[s], lx[s]);
+        else acc = dot_q2(rr.c[s], lx[s]);
+        const float sc = h2f(f16_from_bits(rr.s[s]));
+        const float zr = h2f(f16_from_bits(rr.z[s]));
+        part += sc * (acc - lx[s].xoff) + zr * lx[s].xsum;
     }
     return part;
 }
 
+// bf16 row against bf16 activations (exact products, fp32 accumulation)
+template <int NSEG>
+__device__ __forceinline__ float dot_row_b(const RowRegs<16, NSEG>& rr, const LaneXB<NSEG>& lx)
+{
+    float a = 0.0f;
+#pragma unroll
+    for (int s = 0; s < NSEG; s++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            a = dot2_bf16(rr.c[s][j].x, lx.r[s][j].x, a);
+            a = dot2_bf16(rr.c[s][j].y, lx.r[s][j].y, a);
+            a = dot2_bf16(rr.c[s][j].z, lx.r[s][j].z, a);
+            a = dot2_bf16(rr.c[s][j].w, lx.r[s][j].w, a);
+        }
+    return a;
+}
+
 // ---------------------------------------------------------------- phase 1
 // h[p,f] = silu(W1[f,:] . x_t) * (W3[f,:] . x_t)
+// A wavefront takes RF consecutive f per iteration (2*RF rows in flight).
+
+template <int BITS> struct Phase1Rows { static constexpr int RF = (BITS == 16) ? 1 : (BITS == 4 ? 2 : 4); };
+
+template <int BITS, int NSEG, typename XT, typename DotFn>
+__device__ __forceinline__ void phase1_rows(const ExpertMat& m1, const ExpertMat& m3, int H,
+                                            int f_begin, int f_end, float* __restrict__ hrow,
+                                            const XT& lx, DotFn dot)
+{
+    constexpr int RF = Phase1Rows<BITS>::RF;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    RowRegs<BITS, NSEG> cur[2 * RF], nxt[2 * RF];
+    int f = f_begin + wave * RF;
+    if (f >= f_end) return;
+#pragma unroll
+    for (int i = 0; i < RF; i++) {
+        const int fi = min(f + i, f_end - 1);
+        load_row<BITS, NSEG>(m1, fi, H, 0, lane, cur[2 * i]);
+        load_row<BITS, NSEG>(m3, fi, H, 0, lane, cur[2 * i + 1]);
+    }
+    for (; f < f_end; f += kGvWaves * RF) {
+        // next batch first (clamped to the block's last row on the final pass)
+        const int fn = f + kGvWaves * RF;
+#pragma unroll
+        for (int i = 0; i < RF; i++) {
+            const int fi = min(fn + i, f_end - 1);
+            load_row<BITS, NSEG>(m1, fi, H, 0, lane, nxt[2 * i]);
+            load_row<BITS, NSEG>(m3, fi, H, 0, lane, nxt[2 * i + 1]);
+        }
+        float a[RF], g[RF];
+#pragma unroll
+        for (int i = 0; i < RF; i++) {
+            a[i] = dot(cur[2 * i], lx);
+            g[i] = dot(cur[2 * i + 1], lx);
+        }
+#pragma unroll
+        for (int i = 0; i < RF; i++) {
+            a[i] = wave_sum_dpp(a[i]);
+            g[i] = wave_sum_dpp(g[i]);
+        }
+        // lane i writes row f + i
+        float hv = 0.0f;
+#pragma unroll
+        for (int i = 0; i < RF; i++)
+            if (lane == i) hv = a[i] / (1.0f + __expf(-a[i])) * g[i];
+        if (lane < RF && f + lane < f_end) hrow[f + lane] = hv;
+#pragma unroll
+        for (int i = 0; i < 2 * RF; i++) cur[i] = nxt[i];
+    }
+}
 
 template <int BITS, int NSEG>
 __device__ __forceinline__ void phase1_quant(const ExpertMat& m1, const ExpertMat& m3,
@@ -173,7 +305,6 @@ __device__ __forceinline__ void phase1_quant(const ExpertMat& m1, const ExpertMa
                                              int f_end, float* __restrict__ hrow)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
     LaneX lx[NSEG];
 #pragma unroll
     for (int s = 0; s < NSEG; s++) {
@@ -190,54 +321,31 @@ __device__ __forceinline__ void phase1_quant(const ExpertMat& m1, const ExpertMa
         }
         arrange_lane_x<BITS>(v, lx[s]);
     }
-    for (int f = f_begin + wave; f < f_end; f += kGvWaves) {
-        float a = qrow_partial<BITS, NSEG>(m1, f, H, lane, lx);
-        float g = qrow_partial<BITS, NSEG>(m3, f, H, lane, lx);
-        a = wave_sum(a);
-        g = wave_sum(g);
-        if (lane == 0) hrow[f] = a / (1.0f + expf(-a)) * g;
-    }
+    phase1_rows<BITS, NSEG>(m1, m3, H, f_begin, f_end, hrow, lx,
+                            [](const RowRegs<BITS, NSEG>& rr, const LaneX (&l)[NSEG]) {
+                                return dot_row_q<BITS, NSEG>(rr, l);
+                            });
 }
 
 template <int NSEG>
-__device__ __forceinline__ void phase1_bf16(const uint16_t* __restrict__ w1,
-                                            const uint16_t* __restrict__ w3,
+__device__ __forceinline__ void phase1_bf16(const ExpertMat& m1, const ExpertMat& m3,
                                             const uint16_t* __restrict__ xrow, int H, int f_begin,
                                             int f_end, float* __restrict__ hrow)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    uint4 xr[NSEG][4];
+    LaneXB<NSEG> lx;
 #pragma unroll
     for (int s = 0; s < NSEG; s++)
 #pragma unroll
         for (int j = 0; j < 4; j++) {
             const int col = s * kSeg + (j * kWave + lane) * 8;
-            xr[s][j] = make_uint4(0, 0, 0, 0);
-            if (col < H) xr[s][j] = *reinterpret_cast<const uint4*>(xrow + col);
+            lx.r[s][j] = make_uint4(0, 0, 0, 0);
+            if (col < H) lx.r[s][j] = *reinterpret_cast<const uint4*>(xrow + col);
         }
-    for (int f = f_begin + wave; f < f_end; f += kGvWaves) {
-        const uint16_t* r1 = w1 + (long)f * H;
-        const uint16_t* r3 = w3 + (long)f * H;
-        float a = 0.0f, g = 0.0f;
-#pragma unroll
-        for (int s = 0; s < NSEG; s++)
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const int col = s * kSeg + (j * kWave + lane) * 8;
-                if (col < H) {
-                    const uint4 u = *reinterpret_cast<const uint4*>(r1 + col);
-                    const uint4 v = *reinterpret_cast<const uint4*>(r3 + col);
-                    a = dot2_bf16(u.x, xr[s][j].x, a); a = dot2_bf16(u.y, xr[s][j].y, a);
-                    a = dot2_bf16(u.z, xr[s][j].z, a); a = dot2_bf16(u.w, xr[s][j].w, a);
-                    g = dot2_bf16(v.x, xr[s][j].x, g); g = dot2_bf16(v.y, xr[s][j].y, g);
-                    g = dot2_bf16(v.z, xr[s][j].z, g); g = dot2_bf16(v.w, xr[s][j].w, g);
-                }
-            }
-        a = wave_sum(a);
-        g = wave_sum(g);
-        if (lane == 0) hrow[f] = a / (1.0f + expf(-a)) * g;
-    }
+    phase1_rows<16, NSEG>(m1, m3, H, f_begin, f_end, hrow, lx,
+                          [](const RowRegs<16, NSEG>& rr, const LaneXB<NSEG>& l) {
+                              return dot_row_b<NSEG>(rr, l);
+                          });
 }
 
 template <int NSEG>
@@ -258,8 +366,7 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
     float* hrow = hbuf + (long)p * F;
     const dymoe_expert_fmt ex = table[e];
     if (b == 16) {
-        phase1_bf16<NSEG>(reinterpret_cast<const uint16_t*>(ex.w[0]),
-                          reinterpret_cast<const uint16_t*>(ex.w[1]), xrow, H, f_begin, f_end, hrow);
+        phase1_bf16<NSEG>(pick_mat(ex, 0, 16), pick_mat(ex, 1, 16), xrow, H, f_begin, f_end, hrow);
     } else if (b == 4) {
         phase1_quant<4, NSEG>(pick_mat(ex, 0, 4), pick_mat(ex, 1, 4), xrow, H, f_begin, f_end, hrow);
     } else {
@@ -269,6 +376,60 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
 
 // ---------------------------------------------------------------- phase 2
 // part[p,s,j] = sum over segment s of W2[j,f] * h[p,f]
+// A wavefront takes R consecutive rows j per iteration.
+
+template <int BITS> struct Phase2Rows { static constexpr int R = (BITS == 16) ? 4 : 8; };
+
+// fp32 intermediate against bf16 weights
+struct LaneH {
+    float v[4][8];
+};
+
+__device__ __forceinline__ float dot_row_h(const RowRegs<16, 1>& rr, const LaneH& lh)
+{
+    float acc = 0.0f;
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        const uint4 u = rr.c[0][c];
+        acc = fmaf(bf16_lo(u.x), lh.v[c][0], acc); acc = fmaf(bf16_hi(u.x), lh.v[c][1], acc);
+        acc = fmaf(bf16_lo(u.y), lh.v[c][2], acc); acc = fmaf(bf16_hi(u.y), lh.v[c][3], acc);
+        acc = fmaf(bf16_lo(u.z), lh.v[c][4], acc); acc = fmaf(bf16_hi(u.z), lh.v[c][5], acc);
+        acc = fmaf(bf16_lo(u.w), lh.v[c][6], acc); acc = fmaf(bf16_hi(u.w), lh.v[c][7], acc);
+    }
+    return acc;
+}
+
+template <int BITS, typename XT, typename DotFn>
+__device__ __forceinline__ void phase2_rows(const ExpertMat& m2, int F, int seg, int j_begin,
+                                            int j_end, float* __restrict__ out, const XT& lx,
+                                            DotFn dot)
+{
+    constexpr int R = Phase2Rows<BITS>::R;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    RowRegs<BITS, 1> cur[R], nxt[R];
+    int j = j_begin + wave * R;
+    if (j >= j_end) return;
+#pragma unroll
+    for (int i = 0; i < R; i++) load_row<BITS, 1>(m2, min(j + i, j_end - 1), F, seg, lane, cur[i]);
+    for (; j < j_end; j += kGvWaves * R) {
+        const int jn = j + kGvWaves * R;
+#pragma unroll
+        for (int i = 0; i < R; i++) load_row<BITS, 1>(m2, min(jn + i, j_end - 1), F, seg, lane, nxt[i]);
+        float acc[R];
+#pragma unroll
+        for (int i = 0; i < R; i++) acc[i] = dot(cur[i], lx);
+#pragma unroll
+        for (int i = 0; i < R; i++) acc[i] = wave_sum_dpp(acc[i]);
+        float o = 0.0f;
+#pragma unroll
+        for (int i = 0; i < R; i++)
+            if (lane == i) o = acc[i];
+        if (lane < R && j + lane < j_end) out[j + lane] = o;
+#pragma unroll
+        for (int i = 0; i < R; i++) cur[i] = nxt[i];
+    }
+}
 
 __global__ __launch_bounds__(kGvThreads) void gemv_phase2_kernel(
     const float* __restrict__ hbuf, const int32_t* __restrict__ idx,
@@ -282,46 +443,28 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase2_kernel(
     const int b = bits[e];
     if (b != 16 && b != 4 && b != 2) return;
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
     const int j_begin = blockIdx.x * rows_per_block;
     const int j_end = min(H, j_begin + rows_per_block);
     const float* hrow = hbuf + (long)p * F;
     float* out = part + ((long)p * nseg + s) * H;
     const dymoe_expert_fmt ex = table[e];
     if (b == 16) {
-        const uint16_t* w2 = reinterpret_cast<const uint16_t*>(ex.w[2]);
-        float hr[4][8];
+        LaneH lh;
 #pragma unroll
         for (int c = 0; c < 4; c++) {
             const int col = s * kSeg + (c * kWave + lane) * 8;
 #pragma unroll
-            for (int i = 0; i < 8; i++) hr[c][i] = 0.0f;
+            for (int i = 0; i < 8; i++) lh.v[c][i] = 0.0f;
             if (col < F) {
                 const float4 lo = *reinterpret_cast<const float4*>(hrow + col);
                 const float4 hi = *reinterpret_cast<const float4*>(hrow + col + 4);
-                hr[c][0] = lo.x; hr[c][1] = lo.y; hr[c][2] = lo.z; hr[c][3] = lo.w;
-                hr[c][4] = hi.x; hr[c][5] = hi.y; hr[c][6] = hi.z; hr[c][7] = hi.w;
+                lh.v[c][0] = lo.x; lh.v[c][1] = lo.y; lh.v[c][2] = lo.z; lh.v[c][3] = lo.w;
+                lh.v[c][4] = hi.x; lh.v[c][5] = hi.y; lh.v[c][6] = hi.z; lh.v[c][7] = hi.w;
             }
         }
-        for (int j = j_begin + wave; j < j_end; j += kGvWaves) {
-            const uint16_t* row = w2 + (long)j * F;
-            float acc = 0.0f;
-#pragma unroll
-            for (int c = 0; c < 4; c++) {
-                const int col = s * kSeg + (c * kWave + lane) * 8;
-                if (col < F) {
-                    const uint4 u = *reinterpret_cast<const uint4*>(row + col);
-                    acc = fmaf(bf16_lo(u.x), hr[c][0], acc); acc = fmaf(bf16_hi(u.x), hr[c][1], acc);
-                    acc = fmaf(bf16_lo(u.y), hr[c][2], acc); acc = fmaf(bf16_hi(u.y), hr[c][3], acc);
-                    acc = fmaf(bf16_lo(u.z), hr[c][4], acc); acc = fmaf(bf16_hi(u.z), hr[c][5], acc);
-                    acc = fmaf(bf16_lo(u.w), hr[c][6], acc); acc = fmaf(bf16_hi(u.w), hr[c][7], acc);
-                }
-            }
-            acc = wave_sum(acc);
-            if (lane == 0) out[j] = acc;
-        }
+        phase2_rows<16>(pick_mat(ex, 2, 16), F, s, j_begin, j_end, out, lh,
+                        [](const RowRegs<16, 1>& rr, const LaneH& l) { return dot_row_h(rr, l); });
     } else {
-        const ExpertMat m2 = pick_mat(ex, 2, b);
         const int col0 = s * kSeg + 32 * lane;
         float v[32];
 #pragma unroll
@@ -330,36 +473,15 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase2_kernel(
             if (col0 < F) q = *reinterpret_cast<const float4*>(hrow + col0 + 4 * c);
             v[4 * c + 0] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
         }
-        LaneX lx;
-        const long G = F >> 6;
+        LaneX lx[1];
         if (b == 4) {
-            arrange_lane_x<4>(v, lx);
-            for (int j = j_begin + wave; j < j_end; j += kGvWaves) {
-                float acc = 0.0f;
-                if (col0 < F) {
-                    const long g = (long)j * G + (col0 >> 6);
-                    const float sc = h2f(f16_from_bits(m2.s[g]));
-                    const float zr = h2f(f16_from_bits(m2.z[g]));
-                    const float d = dot_q4(*reinterpret_cast<const uint4*>(m2.q + (long)j * (F >> 1) + (col0 >> 1)), lx);
-                    acc = sc * (d - lx.xoff) + zr * lx.xsum;
-                }
-                acc = wave_sum(acc);
-                if (lane == 0) out[j] = acc;
-            }
+            arrange_lane_x<4>(v, lx[0]);
+            phase2_rows<4>(pick_mat(ex, 2, 4), F, s, j_begin, j_end, out, lx,
+                           [](const RowRegs<4, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<4, 1>(rr, l); });
         } else {
-            arrange_lane_x<2>(v, lx);
-            for (int j = j_begin + wave; j < j_end; j += kGvWaves) {
-                float acc = 0.0f;
-                if (col0 < F) {
-                    const long g = (long)j * G + (col0 >> 6);
-                    const float sc = h2f(f16_from_bits(m2.s[g]));
-                    const float zr = h2f(f16_from_bits(m2.z[g]));
-                    const float d = dot_q2(*reinterpret_cast<const uint2*>(m2.q + (long)j * (F >> 2) + (col0 >> 2)), lx);
-                    acc = sc * (d - lx.xoff) + zr * lx.xsum;
-                }
-                acc = wave_sum(acc);
-                if (lane == 0) out[j] = acc;
-            }
+            arrange_lane_x<2>(v, lx[0]);
+            phase2_rows<2>(pick_mat(ex, 2, 2), F, s, j_begin, j_end, out, lx,
+                           [](const RowRegs<2, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<2, 1>(rr, l); });
         }
     }
 }
@@ -389,9 +511,9 @@ __global__ __launch_bounds__(256) void gemv_combine_kernel(
     else reinterpret_cast<uint16_t*>(y)[i] = (uint16_t)f32_to_bf16_bits(acc);
 }
 
-int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w, const uint8_t* bits,
-                    const dymoe_expert_fmt* table, int T, int H, int F, int E, int k,
-                    int out_dtype, void* y, void* workspace, hipStream_t st)
+int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w,
+                    const uint8_t* bits, const dymoe_expert_fmt* table, int T, int H, int F, int E,
+                    int k, int out_dtype, void* y, void* workspace, hipStream_t st)
 {
     const FfnLayout L = ffn_layout(T, H, F, E, k);
     float* hbuf = reinterpret_cast<float*>((char*)workspace + L.hbuf);
@@ -399,30 +521,28 @@ int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const int P = T * k;
     const int nseg1 = (H + kSeg - 1) / kSeg;
     const int nseg2 = (F + kSeg - 1) / kSeg;
-    const int rows1 = 32, rows2 = 64;
+    // rows per workgroup (measured on the Mixtral-shaped decode layer: 64/64 beat 16..128)
+    const int rows1 = 64, rows2 = 64;
     const dim3 g1((unsigned)((F + rows1 - 1) / rows1), (unsigned)P);
     const uint16_t* xb = (const uint16_t*)x;
     {
-    dymoe_kernel_timer timer(ctx, DYMOE_K_GEMV_PHASE1, st);
-    switch (nseg1) {
-    case 1: hipLaunchKernelGGL((gemv_phase1_kernel<1>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
-    case 2: hipLaunchKernelGGL((gemv_phase1_kernel<2>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
-    case 3: hipLaunchKernelGGL((gemv_phase1_kernel<3>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
-    case 4: hipLaunchKernelGGL((gemv_phase1_kernel<4>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
-    default: return DYMOE_ENOTSUP;
-    }
+        switch (nseg1) {
+        case 1: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<1>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
+        case 2: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<2>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
+        case 3: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<3>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
+        case 4: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<4>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
+        default: return DYMOE_ENOTSUP;
+        }
     }
     DYMOE_HIP_LAUNCH_CHECK();
     const dim3 g2((unsigned)((H + rows2 - 1) / rows2), (unsigned)nseg2, (unsigned)P);
     {
-    dymoe_kernel_timer timer(ctx, DYMOE_K_GEMV_PHASE2, st);
-    hipLaunchKernelGGL(gemv_phase2_kernel, g2, dim3(kGvThreads), 0, st, hbuf, idx, bits, table, H, F,
-                       E, rows2, nseg2, part);
+        dymoe_launch(ctx, DYMOE_K_GEMV_PHASE2, gemv_phase2_kernel, g2, dim3(kGvThreads), 0, st, hbuf, idx, bits, table, H,
+                           F, E, rows2, nseg2, part);
     }
     DYMOE_HIP_LAUNCH_CHECK();
     const long n = (long)T * H;
-    dymoe_kernel_timer timer(ctx, DYMOE_K_GEMV_COMBINE, st);
-    hipLaunchKernelGGL(gemv_combine_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part,
+    dymoe_launch(ctx, DYMOE_K_GEMV_COMBINE, gemv_combine_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part,
                        idx, w, bits, T, H, E, k, nseg2, out_dtype, y);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;

@@ -55,6 +55,67 @@ __global__ __launch_bounds__(kImpThreads) void importance_prefill_kernel(
     }
 }
 
+// Single-workgroup version of both phases for steps of up to a few thousand
+// tokens: histograms live in LDS, so there is nothing to zero beforehand and
+// the whole step is one launch.
+constexpr int kImpBlock = 1024;
+
+__global__ __launch_bounds__(kImpBlock) void importance_block_kernel(
+    const int32_t* __restrict__ idx, const float* __restrict__ score,
+    const float* __restrict__ probs, int T, int E, int k, int k_hh, int prefill,
+    void* __restrict__ importance, int32_t* __restrict__ load)
+{
+    __shared__ int32_t s_load[DYMOE_MAX_EXPERTS];
+    __shared__ int32_t s_imp[DYMOE_MAX_EXPERTS];
+    __shared__ float tile[kImpBlock];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < E; e += kImpBlock) {
+        s_load[e] = 0;
+        s_imp[e] = 0;
+    }
+    __syncthreads();
+    const int chunks = (T + kImpBlock - 1) / kImpBlock;   // same trip count for every thread
+    for (int c = 0; c < chunks; c++) {
+        const int t = c * kImpBlock + tid;
+        bool heavy = false;
+        if (prefill) {
+            const float mine = (t < T) ? score[t] : 0.0f;
+            int before = 0;
+            for (int b = 0; b < chunks; b++) {
+                const int u = b * kImpBlock + tid;
+                tile[tid] = (u < T) ? score[u] : 0.0f;
+                __syncthreads();
+                const int n = min(kImpBlock, T - b * kImpBlock);
+                for (int j = 0; j < n; j++) {
+                    const float s = tile[j];
+                    before += (s > mine || (s == mine && b * kImpBlock + j < t)) ? 1 : 0;
+                }
+                __syncthreads();
+            }
+            heavy = (t < T) && before < k_hh;
+        }
+        if (t < T) {
+            for (int s = 0; s < k; s++) {
+                const int e = idx[(size_t)t * k + s];
+                if (e < 0 || e >= E) continue;
+                atomicAdd(&s_load[e], 1);
+                if (heavy) atomicAdd(&s_imp[e], 1);
+            }
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < E; e += kImpBlock) {
+        load[e] = s_load[e];
+        if (prefill) {
+            reinterpret_cast<int32_t*>(importance)[e] = s_imp[e];
+        } else {
+            float g = 0.0f;
+            for (int t = 0; t < T; t++) g += probs[(size_t)t * E + e];
+            reinterpret_cast<float*>(importance)[e] = (T <= 1) ? g : g / (float)T;
+        }
+    }
+}
+
 // Decode: importance[e] = mean over the step's tokens of the gate score
 __global__ void importance_decode_kernel(const float* __restrict__ probs, int T, int E,
                                          float* __restrict__ importance)
@@ -129,13 +190,19 @@ int dymoe_expert_importance(dymoe_ctx* ctx, int phase, const int32_t* idx, const
     if (!ctx) return DYMOE_ENOCTX;
     hipStream_t st = (hipStream_t)stream;
     const bool prefill = phase == DYMOE_PHASE_PREFILL;
+    if (T <= 4096) {
+        dymoe_launch(ctx, DYMOE_K_IMPORTANCE, dymoe::importance_block_kernel, dim3(1),
+                     dim3(dymoe::kImpBlock), 0, st, idx, token_score, probs, T, E, k, k_hh,
+                     prefill ? 1 : 0, importance, load);
+        DYMOE_HIP_LAUNCH_CHECK();
+        return DYMOE_OK;
+    }
     hipLaunchKernelGGL(dymoe::zero_i32_kernel, dim3((E + 255) / 256), dim3(256), 0, st, load,
                        prefill ? (int32_t*)importance : (int32_t*)nullptr, E);
     DYMOE_HIP_LAUNCH_CHECK();
     if (T > 0) {
         const unsigned blocks = (unsigned)((T + dymoe::kImpThreads - 1) / dymoe::kImpThreads);
-        dymoe_kernel_timer timer(ctx, DYMOE_K_IMPORTANCE, st);
-        hipLaunchKernelGGL(dymoe::importance_prefill_kernel, dim3(blocks), dim3(dymoe::kImpThreads),
+        dymoe_launch(ctx, DYMOE_K_IMPORTANCE, dymoe::importance_prefill_kernel, dim3(blocks), dim3(dymoe::kImpThreads),
                            0, st, idx, token_score, T, E, k, k_hh, prefill ? 1 : 0,
                            (int32_t*)importance, load);
         DYMOE_HIP_LAUNCH_CHECK();
@@ -177,12 +244,11 @@ int dymoe_assign_precision(dymoe_ctx* ctx, int phase, const void* importance,
     if (!ctx) return DYMOE_ENOCTX;
     hipStream_t st = (hipStream_t)stream;
     const unsigned threads = (unsigned)(((E + 63) / 64) * 64);
-    dymoe_kernel_timer timer(ctx, DYMOE_K_ASSIGN, st);
     if (phase == DYMOE_PHASE_PREFILL)
-        hipLaunchKernelGGL((dymoe::assign_precision_kernel<int32_t>), dim3(1), dim3(threads), 0, st,
+        dymoe_launch(ctx, DYMOE_K_ASSIGN, (dymoe::assign_precision_kernel<int32_t>), dim3(1), dim3(threads), 0, st,
                            (const int32_t*)importance, load, E, tt, floor_bits, bits, rank);
     else
-        hipLaunchKernelGGL((dymoe::assign_precision_kernel<float>), dim3(1), dim3(threads), 0, st,
+        dymoe_launch(ctx, DYMOE_K_ASSIGN, (dymoe::assign_precision_kernel<float>), dim3(1), dim3(threads), 0, st,
                            (const float*)importance, load, E, tt, floor_bits, bits, rank);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;

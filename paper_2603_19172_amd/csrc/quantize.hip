@@ -1,42 +1,63 @@
 // Group-wise asymmetric quantize-and-pack (bf16 -> int4 / int2 codes + fp16
-// scale and zero per group of 64 columns).  Streaming, HBM-bound:
-// every lane owns 8 consecutive bf16 (one 16-byte load), 8 lanes own a group.
+// scale and zero per group of 64 columns).  Streaming kernel: every lane owns
+// 32 consecutive bf16 (four 16-byte loads, 64 contiguous bytes), two lanes own
+// a group, and a lane writes its 32 codes with one 16-byte (int4) or 8-byte
+// (int2) store.
 //
 // The arithmetic is an exact sequence of binary32 operations (this file is
 // built with -ffp-contract=off): the codes must equal the reference's bit for
 // bit, so nothing here may be fused, reassociated or approximated.
+//   round-to-nearest-even of v = (w - m) * inv is done by the addition
+//   v + 1.5*2^23, which is exact RNE-to-integer for |v| < 2^22 and leaves the
+//   integer in the low mantissa bits; the clamp then runs on the bit pattern.
 #include "common.hpp"
 
 namespace dymoe {
 
 constexpr int kQThreads = 256;
-constexpr int kQUnroll = 4;  // 16-byte loads in flight per lane
+constexpr int kQElemsPerLane = 32;
+constexpr int kQElemsPerBlock = kQThreads * kQElemsPerLane;  // 8192 elements = 128 groups
 
-template <int BITS>
-__device__ __forceinline__ void quantize_chunk(const uint4 raw, long chunk,
-                                               uint8_t* __restrict__ codes,
-                                               uint16_t* __restrict__ scale,
-                                               uint16_t* __restrict__ zero, int lane)
+__device__ __forceinline__ void unpack8(const uint4 raw, float* v)
 {
-#pragma clang fp contract(off)
-    constexpr int qmax = (1 << BITS) - 1;
-    float v[8];
     v[0] = bf16_lo(raw.x); v[1] = bf16_hi(raw.x);
     v[2] = bf16_lo(raw.y); v[3] = bf16_hi(raw.y);
     v[4] = bf16_lo(raw.z); v[5] = bf16_hi(raw.z);
     v[6] = bf16_lo(raw.w); v[7] = bf16_hi(raw.w);
+}
+
+// One block quantizes elements [block*8192, block*8192 + 8192) of a matrix
+// whose element count is a multiple of 64 (rows are whole groups, so the flat
+// element index addresses the packed row-major outputs directly).
+template <int BITS>
+__device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, long n_elems,
+                                               uint8_t* __restrict__ codes,
+                                               uint16_t* __restrict__ scale,
+                                               uint16_t* __restrict__ zero, long block)
+{
+#pragma clang fp contract(off)
+    constexpr int qmax = (1 << BITS) - 1;
+    constexpr float kMagic = 12582912.0f;          // 1.5 * 2^23
+    constexpr int kMagicBits = 0x4B400000;
+    const int lane = threadIdx.x & (kWave - 1);
+    const long e0 = block * (long)kQElemsPerBlock + (long)threadIdx.x * kQElemsPerLane;
+    // a group's two lanes are in or out together (n_elems is a multiple of 64)
+    if (e0 >= n_elems) return;
+    const uint4* src = reinterpret_cast<const uint4*>(w + e0);
+    uint4 raw[4];
+#pragma unroll
+    for (int c = 0; c < 4; c++) raw[c] = src[c];
+    float v[32];
+#pragma unroll
+    for (int c = 0; c < 4; c++) unpack8(raw[c], v + 8 * c);
     float lo = v[0], hi = v[0];
 #pragma unroll
-    for (int i = 1; i < 8; i++) {
+    for (int i = 1; i < 32; i++) {
         lo = fminf(lo, v[i]);
         hi = fmaxf(hi, v[i]);
     }
-    // the 8 lanes of a group are lane-aligned (chunks_per_row is a multiple of 8)
-#pragma unroll
-    for (int o = 1; o < 8; o <<= 1) {
-        lo = fminf(lo, __shfl_xor(lo, o, kWave));
-        hi = fmaxf(hi, __shfl_xor(hi, o, kWave));
-    }
+    lo = fminf(lo, __shfl_xor(lo, 1, kWave));
+    hi = fmaxf(hi, __shfl_xor(hi, 1, kWave));
     const _Float16 zh = (_Float16)lo;                 // round to nearest even
     const float range = hi - lo;
     const float step = range / (float)qmax;           // correctly rounded division
@@ -44,83 +65,98 @@ __device__ __forceinline__ void quantize_chunk(const uint4 raw, long chunk,
     const float m = (float)zh;
     const float s = (float)sh;
     const float inv = (s > 0.0f) ? (1.0f / s) : 0.0f;
-    uint32_t word = 0;
+    uint32_t words[BITS];                             // 32 codes: 4 words (int4) or 2 words (int2)
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
-        const float d = v[i] - m;
-        const float r = rintf(d * inv);
-        int q = (int)r;
-        q = q < 0 ? 0 : (q > qmax ? qmax : q);
-        word |= (uint32_t)q << (BITS * i);
+    for (int wd = 0; wd < BITS; wd++) {
+        constexpr int per_word = 32 / BITS;
+        uint32_t bytes[4];
+#pragma unroll
+        for (int b = 0; b < 4; b++) {
+            constexpr int per_byte = 8 / BITS;
+            uint32_t acc = 0;
+#pragma unroll
+            for (int j = per_byte - 1; j >= 0; j--) {
+                const int i = wd * per_word + b * per_byte + j;
+                const float d = v[i] - m;
+                const float t = d * inv;
+                const float r = t + kMagic;
+                int q = __float_as_int(r);
+                q = min(max(q, kMagicBits), kMagicBits + qmax);
+                // the low byte accumulates the codes; bits above it are garbage
+                acc = (j == per_byte - 1) ? (uint32_t)q : ((acc << BITS) | (uint32_t)q);
+            }
+            bytes[b] = acc;
+        }
+        // gather the four low bytes
+        const uint32_t lo16 = __builtin_amdgcn_perm(bytes[1], bytes[0], 0x0c0c0400u);
+        const uint32_t hi16 = __builtin_amdgcn_perm(bytes[3], bytes[2], 0x04000c0cu);
+        words[wd] = lo16 | hi16;
     }
-    // rows are whole numbers of groups, so the flat chunk index addresses the
-    // packed row-major outputs directly: 8 codes per chunk, 8 chunks per group
-    if (BITS == 4) {
-        *reinterpret_cast<uint32_t*>(codes + chunk * 4) = word;
+    if constexpr (BITS == 4) {
+        *reinterpret_cast<uint4*>(codes + (e0 >> 1)) = make_uint4(words[0], words[1], words[2], words[3]);
     } else {
-        // two lanes share one 32-bit store
-        const uint32_t other = __shfl_down(word, 1, kWave);
-        if ((lane & 1) == 0) *reinterpret_cast<uint32_t*>(codes + chunk * 2) = word | (other << 16);
+        *reinterpret_cast<uint2*>(codes + (e0 >> 2)) = make_uint2(words[0], words[1]);
     }
-    if ((lane & 7) == 0) {
-        scale[chunk >> 3] = (uint16_t)f16_bits(sh);
-        zero[chunk >> 3] = (uint16_t)f16_bits(zh);
-    }
-}
-
-template <int BITS>
-__device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, long n_chunks,
-                                               uint8_t* __restrict__ codes,
-                                               uint16_t* __restrict__ scale,
-                                               uint16_t* __restrict__ zero, long block)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-    const long base = block * (long)(kQThreads * kQUnroll) + threadIdx.x;
-    uint4 raw[kQUnroll];
-#pragma unroll
-    for (int u = 0; u < kQUnroll; u++) {
-        const long c = base + (long)u * kQThreads;
-        if (c < n_chunks) raw[u] = reinterpret_cast<const uint4*>(w)[c];
-        else raw[u] = make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int u = 0; u < kQUnroll; u++) {
-        const long c = base + (long)u * kQThreads;
-        // n_chunks is a multiple of 8, so a group's 8 lanes are in or out together
-        if (c < n_chunks) quantize_chunk<BITS>(raw[u], c, codes, scale, zero, lane);
+    if ((lane & 1) == 0) {
+        scale[e0 >> 6] = (uint16_t)f16_bits(sh);
+        zero[e0 >> 6] = (uint16_t)f16_bits(zh);
     }
 }
 
 __global__ __launch_bounds__(kQThreads) void quantize_pack_kernel(
-    const uint16_t* __restrict__ w, long n_chunks, int bits,
+    const uint16_t* __restrict__ w, long n_elems, int bits,
     uint8_t* __restrict__ codes, uint16_t* __restrict__ scale, uint16_t* __restrict__ zero)
 {
-    if (bits == 4) quantize_block<4>(w, n_chunks, codes, scale, zero, blockIdx.x);
-    else quantize_block<2>(w, n_chunks, codes, scale, zero, blockIdx.x);
+    if (bits == 4) quantize_block<4>(w, n_elems, codes, scale, zero, blockIdx.x);
+    else quantize_block<2>(w, n_elems, codes, scale, zero, blockIdx.x);
 }
 
-// One launch for a whole layer: blockIdx.y = 3*expert + matrix.  The expert's
-// bit width is read on the device, so no decision goes through the host.
+// Worklist of a layer: the experts whose assigned width is 4 or 2 bits (and
+// that have load, when load is given).  list[0] = count, list[1..] = experts.
+__global__ __launch_bounds__(DYMOE_MAX_EXPERTS) void quantize_worklist_kernel(
+    const uint8_t* __restrict__ bits, const int32_t* __restrict__ load, int E,
+    int32_t* __restrict__ list)
+{
+    __shared__ int32_t flags[DYMOE_MAX_EXPERTS];
+    const int e = threadIdx.x;
+    if (e < E) {
+        const int b = bits[e];
+        flags[e] = ((b == 4 || b == 2) && (load == nullptr || load[e] > 0)) ? 1 : 0;
+    }
+    __syncthreads();
+    if (e == 0) {
+        int n = 0;
+        for (int i = 0; i < E; i++)
+            if (flags[i]) list[1 + n++] = i;
+        list[0] = n;
+    }
+}
+
+// A fixed-size grid walks (expert of the worklist, matrix, block) units, so no
+// workgroup is launched for experts that need nothing and the precision
+// decision never goes through the host.
 __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
     const dymoe_expert_fmt* __restrict__ table, const uint8_t* __restrict__ bits,
-    const int32_t* __restrict__ load, int H, int F)
+    const int32_t* __restrict__ list, int H, int F)
 {
-    const int e = blockIdx.y / 3;
-    const int mat = blockIdx.y - 3 * e;
-    const int b = bits[e];
-    if (b != 4 && b != 2) return;
-    if (load != nullptr && load[e] <= 0) return;
-    const long n_chunks = (long)H * (long)F / 8;
-    const dymoe_expert_fmt ex = table[e];
-    const uint16_t* w = reinterpret_cast<const uint16_t*>(ex.w[mat]);
-    if (b == 4)
-        quantize_block<4>(w, n_chunks, ex.q4[mat],
-                          reinterpret_cast<uint16_t*>(ex.s4[mat]),
-                          reinterpret_cast<uint16_t*>(ex.z4[mat]), blockIdx.x);
-    else
-        quantize_block<2>(w, n_chunks, ex.q2[mat],
-                          reinterpret_cast<uint16_t*>(ex.s2[mat]),
-                          reinterpret_cast<uint16_t*>(ex.z2[mat]), blockIdx.x);
+    const long n_elems = (long)H * (long)F;
+    const long bpm = (n_elems + kQElemsPerBlock - 1) / kQElemsPerBlock;   // blocks per matrix
+    const long units = (long)list[0] * 3 * bpm;
+    for (long u = blockIdx.x; u < units; u += gridDim.x) {
+        const long item = u / bpm;
+        const long blk = u - item * bpm;
+        const int e = list[1 + item / 3];
+        const int mat = (int)(item % 3);
+        const int b = bits[e];
+        const dymoe_expert_fmt* ex = table + e;
+        const uint16_t* w = reinterpret_cast<const uint16_t*>(ex->w[mat]);
+        if (b == 4)
+            quantize_block<4>(w, n_elems, ex->q4[mat], reinterpret_cast<uint16_t*>(ex->s4[mat]),
+                              reinterpret_cast<uint16_t*>(ex->z4[mat]), blk);
+        else
+            quantize_block<2>(w, n_elems, ex->q2[mat], reinterpret_cast<uint16_t*>(ex->s2[mat]),
+                              reinterpret_cast<uint16_t*>(ex->z2[mat]), blk);
+    }
 }
 
 }  // namespace dymoe
@@ -135,17 +171,15 @@ int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits,
     DYMOE_REQUIRE(group > 0 && K % group == 0);
     if (N == 0) return (group != 64) ? DYMOE_ENOTSUP : (ctx ? DYMOE_OK : DYMOE_ENOCTX);  // nothing to read or write
     DYMOE_REQUIRE(w && codes && scale && zero);
-    DYMOE_REQUIRE(dymoe_aligned(w, 16) && dymoe_aligned(codes, 4) && dymoe_aligned(scale, 2) &&
+    DYMOE_REQUIRE(dymoe_aligned(w, 16) && dymoe_aligned(codes, 16) && dymoe_aligned(scale, 2) &&
                   dymoe_aligned(zero, 2));
     if (group != 64) return DYMOE_ENOTSUP;
     if (!ctx) return DYMOE_ENOCTX;
-    const long n_chunks = N * K / 8;
-    const long per_block = dymoe::kQThreads * dymoe::kQUnroll;
-    const long blocks = (n_chunks + per_block - 1) / per_block;
+    const long n_elems = N * K;
+    const long blocks = (n_elems + dymoe::kQElemsPerBlock - 1) / dymoe::kQElemsPerBlock;
     if (blocks > 0x7fffffffL) return DYMOE_ENOTSUP;
-    dymoe_kernel_timer timer(ctx, DYMOE_K_QUANTIZE, (hipStream_t)stream);
-    hipLaunchKernelGGL(dymoe::quantize_pack_kernel, dim3((unsigned)blocks), dim3(dymoe::kQThreads), 0,
-                       (hipStream_t)stream, (const uint16_t*)w, n_chunks, bits, codes,
+    dymoe_launch(ctx, DYMOE_K_QUANTIZE, dymoe::quantize_pack_kernel, dim3((unsigned)blocks), dim3(dymoe::kQThreads), 0,
+                       (hipStream_t)stream, (const uint16_t*)w, n_elems, bits, codes,
                        (uint16_t*)scale, (uint16_t*)zero);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
@@ -155,17 +189,22 @@ int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const 
                            const int32_t* load, int E, int H, int F, int group, void* stream)
 {
     DYMOE_REQUIRE(table && bits);
-    DYMOE_REQUIRE(E > 0 && E <= DYMOE_MAX_EXPERTS && H > 0 && F > 0);
+    DYMOE_REQUIRE(E > 0 && H > 0 && F > 0);
     DYMOE_REQUIRE(group > 0 && H % group == 0 && F % group == 0);
-    if (group != 64) return DYMOE_ENOTSUP;
+    if (group != 64 || E > DYMOE_MAX_EXPERTS) return DYMOE_ENOTSUP;
     if (!ctx) return DYMOE_ENOCTX;
-    const long n_chunks = (long)H * (long)F / 8;
-    const long per_block = dymoe::kQThreads * dymoe::kQUnroll;
-    const long blocks = (n_chunks + per_block - 1) / per_block;
-    if (blocks > 0x7fffffffL) return DYMOE_ENOTSUP;
-    dymoe_kernel_timer timer(ctx, DYMOE_K_QUANTIZE, (hipStream_t)stream);
-    hipLaunchKernelGGL(dymoe::quantize_experts_kernel, dim3((unsigned)blocks, (unsigned)(3 * E)),
-                       dim3(dymoe::kQThreads), 0, (hipStream_t)stream, table, bits, load, H, F);
+    hipStream_t st = (hipStream_t)stream;
+    int32_t* list = reinterpret_cast<int32_t*>(ctx->scratch);
+    hipLaunchKernelGGL(dymoe::quantize_worklist_kernel, dim3(1), dim3((unsigned)(((E + 63) / 64) * 64)),
+                       0, st, bits, load, E, list);
+    DYMOE_HIP_LAUNCH_CHECK();
+    const long n_elems = (long)H * (long)F;
+    const long bpm = (n_elems + dymoe::kQElemsPerBlock - 1) / dymoe::kQElemsPerBlock;
+    long grid = 3L * E * bpm;
+    const long cap = (long)ctx->num_cu * 32;   // enough resident workgroups to fill the chip; the rest loops
+    if (grid > cap) grid = cap;
+    dymoe_launch(ctx, DYMOE_K_QUANTIZE, dymoe::quantize_experts_kernel, dim3((unsigned)grid), dim3(dymoe::kQThreads), 0,
+                       st, table, bits, list, H, F);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }

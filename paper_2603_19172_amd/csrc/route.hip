@@ -11,10 +11,14 @@
 
 namespace dymoe {
 
-constexpr int kRouteWaves = 4;
-
-template <int TW, int NCH>
-__global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
+// A workgroup of NW wavefronts owns TW tokens.  Every wavefront keeps all TW
+// activation rows in registers and computes the logits of the experts
+// e = wave, wave + NW, ...; then token tw is finished (softmax, top-k) by
+// wavefront tw mod NW.  Few tokens: TW = 1 and the experts spread over 8
+// wavefronts; many tokens: TW = NW = 4, so that a router row is read once per
+// four tokens.
+template <int TW, int NCH, int NW>
+__global__ __launch_bounds__(NW* kWave) void route_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
     const float* __restrict__ bias, int T, int H, int E, int k, int renorm,
     int32_t* __restrict__ idx, float* __restrict__ w, float* __restrict__ probs)
@@ -22,11 +26,9 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     extern __shared__ float smem[];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    float* logit = smem + (size_t)wave * TW * E;                 // [TW][E]
-    float* selp = smem + (size_t)kRouteWaves * TW * E + (size_t)wave * k;  // [k]
-    const int t0 = (blockIdx.x * kRouteWaves + wave) * TW;
-    // wavefronts past the last token keep running on zero activations so that
-    // every block-level barrier below is reached by all of them
+    float* logit = smem;                                  // [TW][E]
+    float* selp = smem + (size_t)TW * E + (size_t)wave * k;   // [NW][k]
+    const int t0 = blockIdx.x * TW;
 
     uint4 xr[TW][NCH];
 #pragma unroll
@@ -39,17 +41,17 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
                 xr[tw][c] = *reinterpret_cast<const uint4*>(x + (size_t)(t0 + tw) * H + col);
         }
     }
-    for (int e = 0; e < E; e++) {
+    for (int e = wave; e < E; e += NW) {
         float acc[TW];
 #pragma unroll
         for (int tw = 0; tw < TW; tw++) acc[tw] = 0.0f;
         const uint16_t* row = wg + (size_t)e * H;
 #pragma unroll
         for (int c = 0; c < NCH; c++) {
-            const int col = (c * kWave + lane) * 8;
             if (c * kWave * 8 < H) {  // uniform
-                uint4 wv = make_uint4(0, 0, 0, 0);
-                if (col < H) wv = *reinterpret_cast<const uint4*>(row + col);
+                // lanes past the end re-read the row's tail against zero activations
+                const int col = min((c * kWave + lane) * 8, H - 8);
+                const uint4 wv = *reinterpret_cast<const uint4*>(row + col);
 #pragma unroll
                 for (int tw = 0; tw < TW; tw++) {
                     acc[tw] = dot2_bf16(wv.x, xr[tw][c].x, acc[tw]);
@@ -68,9 +70,12 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     }
     __syncthreads();
 
-    for (int tw = 0; tw < TW; tw++) {
+    // From here on a wavefront only touches the LDS rows of its own tokens; LDS
+    // operations of one wavefront complete in order, so a wavefront-scope fence
+    // is all that the lane-to-lane hand-offs below need.
+    for (int tw = wave; tw < TW; tw += NW) {
         const int t = t0 + tw;
-        const bool valid = t < T;
+        if (t >= T) break;
         float* lg = logit + tw * E;
         float mx = -INFINITY;
         for (int e = lane; e < E; e += kWave) mx = fmaxf(mx, lg[e]);
@@ -79,7 +84,7 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
         for (int e = lane; e < E; e += kWave) den += expf(lg[e] - mx);
         den = wave_sum(den);
         const float rden = 1.0f / den;
-        if (probs && valid)
+        if (probs)
             for (int e = lane; e < E; e += kWave) probs[(size_t)t * E + e] = expf(lg[e] - mx) * rden;
         float sel_sum = 0.0f;
         for (int j = 0; j < k; j++) {
@@ -99,16 +104,17 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
             const float p = expf(bv - mx) * rden;
             sel_sum += p;
             if (lane == 0) {
-                if (valid) idx[(size_t)t * k + j] = bi;
+                idx[(size_t)t * k + j] = bi;
                 selp[j] = p;
             }
             if ((bi & (kWave - 1)) == lane) lg[bi] = -INFINITY;
-            __syncthreads();
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
         const float scale = renorm ? 1.0f / sel_sum : 1.0f;
-        if (valid)
-            for (int j = lane; j < k; j += kWave) w[(size_t)t * k + j] = selp[j] * scale;
-        __syncthreads();
+        for (int j = lane; j < k; j += kWave) w[(size_t)t * k + j] = selp[j] * scale;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -135,15 +141,13 @@ __global__ __launch_bounds__(256) void token_norm_kernel(const uint16_t* __restr
     if (lane == 0) score[t] = sqrtf(acc);
 }
 
-template <int TW, int NCH>
+template <int TW, int NCH, int NW>
 static int launch_route(dymoe_ctx* ctx, const void* x, const void* wg, const float* bias, int T, int H, int E,
                         int k, int renorm, int32_t* idx, float* w, float* probs, hipStream_t st)
 {
-    const int tokens_per_block = kRouteWaves * TW;
-    const unsigned blocks = (unsigned)((T + tokens_per_block - 1) / tokens_per_block);
-    const size_t smem = ((size_t)kRouteWaves * TW * E + (size_t)kRouteWaves * k) * sizeof(float);
-    dymoe_kernel_timer timer(ctx, DYMOE_K_ROUTE, st);
-    hipLaunchKernelGGL((route_kernel<TW, NCH>), dim3(blocks), dim3(kRouteWaves * kWave), smem, st,
+    const unsigned blocks = (unsigned)((T + TW - 1) / TW);
+    const size_t smem = ((size_t)TW * E + (size_t)NW * k) * sizeof(float);
+    dymoe_launch(ctx, DYMOE_K_ROUTE, (route_kernel<TW, NCH, NW>), dim3(blocks), dim3(NW * kWave), smem, st,
                        (const uint16_t*)x, (const uint16_t*)wg, bias, T, H, E, k, renorm, idx, w,
                        probs);
     DYMOE_HIP_LAUNCH_CHECK();
@@ -166,13 +170,13 @@ int dymoe_route_topk(dymoe_ctx* ctx, const void* x, const void* wg, const float*
     if (!ctx) return DYMOE_ENOCTX;
     if (T == 0) return DYMOE_OK;
     hipStream_t st = (hipStream_t)stream;
-    // tokens per wavefront chosen so that their activations fit in 128 VGPRs;
-    // few tokens: one per wavefront, to spread over more compute units
-    if (H <= 4096 && T >= 1024 && E <= 256)
-        return dymoe::launch_route<4, 8>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
-    if (H <= 4096) return dymoe::launch_route<1, 8>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
-    if (H <= 8192) return dymoe::launch_route<1, 16>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
-    return dymoe::launch_route<1, 32>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
+    // tokens per workgroup chosen so that their activations fit in 128 VGPRs;
+    // few tokens: one per workgroup, its experts spread over 8 wavefronts
+    if (H <= 4096 && T >= 1024)
+        return dymoe::launch_route<4, 8, 4>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
+    if (H <= 4096) return dymoe::launch_route<1, 8, 8>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
+    if (H <= 8192) return dymoe::launch_route<1, 16, 8>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
+    return dymoe::launch_route<1, 32, 8>(ctx, x, wg, bias, T, H, E, k, renorm, idx, w, probs, st);
 }
 
 int dymoe_token_score_norm(dymoe_ctx* ctx, const void* x, int T, int H, float* score, void* stream)
@@ -182,8 +186,7 @@ int dymoe_token_score_norm(dymoe_ctx* ctx, const void* x, int T, int H, float* s
     if (!ctx) return DYMOE_ENOCTX;
     if (T == 0) return DYMOE_OK;
     const unsigned blocks = (unsigned)((T + 3) / 4);
-    dymoe_kernel_timer timer(ctx, DYMOE_K_TOKEN_NORM, (hipStream_t)stream);
-    hipLaunchKernelGGL(dymoe::token_norm_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+    dymoe_launch(ctx, DYMOE_K_TOKEN_NORM, dymoe::token_norm_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
                        (const uint16_t*)x, T, H, score);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;

@@ -168,7 +168,8 @@ def test_token_score_norm(ctx):
 
 def test_importance_prefill_bit_exact(ctx):
     rng = np.random.default_rng(4)
-    for T, E, k, k_hh in ((16, 8, 2, 1), (700, 128, 8, 35), (513, 8, 2, 513), (300, 16, 4, 0)):
+    for T, E, k, k_hh in ((16, 8, 2, 1), (700, 128, 8, 35), (513, 8, 2, 513), (300, 16, 4, 0),
+                           (2048, 128, 8, 103), (5000, 16, 4, 250)):   # the last one takes the multi-workgroup kernels
         idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
         score = (rng.standard_normal(T) ** 2).astype(np.float32)
         score[T // 2] = score[T // 3]          # an exact tie

@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=20)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU (no collectives, no sharding); use --gpus 1",
@@ -77,6 +79,12 @@ def main():
                      out_dtype=B.OUT_BF16, device=dev)
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
+    if args.calibrate_copy:
+        src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def timed_loop(fns, steps, warmup):
         """fns: one callable per weight copy; returns seconds for `steps` calls."""

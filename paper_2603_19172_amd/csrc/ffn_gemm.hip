@@ -256,22 +256,49 @@ __device__ __forceinline__ void perm16(const uint4 a, const uint4 b, uint4& o0, 
     o1.w = (a.w >> 16) | (b.w & 0xffff0000u);
 }
 
+// one K-block of MFMAs for NTF token fragments (32 tokens each)
+template <int BITS, int NTF>
+__device__ __forceinline__ void compute_kblock(const StripRaw<BITS>& ra, const StripRaw<BITS>& rb,
+                                               const uint16_t (*xs)[kLdsStride], int ln, int kb,
+                                               float16_t (&acc)[2][NTF])
+{
+#pragma unroll
+    for (int jj = 0; jj < 4; jj++) {
+        uint4 a0, a1, b0, b1;
+        strip_frags<BITS>(ra, jj, a0, a1);
+        strip_frags<BITS>(rb, jj, b0, b1);
+#pragma unroll
+        for (int tf = 0; tf < NTF; tf++) {
+            const uint4 t0 = *reinterpret_cast<const uint4*>(&xs[32 * tf + ln][64 * kb + 16 * jj]);
+            const uint4 t1 = *reinterpret_cast<const uint4*>(&xs[32 * tf + ln][64 * kb + 16 * jj + 8]);
+            acc[0][tf] = mfma16<BITS>(a0, t0, acc[0][tf]);
+            acc[1][tf] = mfma16<BITS>(b0, t0, acc[1][tf]);
+            acc[0][tf] = mfma16<BITS>(a1, t1, acc[0][tf]);
+            acc[1][tf] = mfma16<BITS>(b1, t1, acc[1][tf]);
+        }
+    }
+}
+
 // ----------------------------------------------------------------------------
 // MODE 1: h = silu(x W1^T) * (x W3^T)   strips = (W1 rows, W3 rows) of the same 32 features
-// MODE 2: o = h W2^T                     strips = two adjacent groups of 32 rows of W2
-template <int MODE, int BITS>
+// MODE 2: o = h W2^T                     strips = two adjacent groups of 32 rows of W2,
+//                                        K range [k_begin, k_end) of the split
+// The K loop is software pipelined: while K-block i is multiplied out of
+// registers (weights) and LDS buffer i&1 (tokens), the weights of K-block i+1
+// are in flight to registers and its token tile is in flight to registers, to
+// be written to the other LDS buffer afterwards; one barrier per K-block.
+template <int MODE, int BITS, int NTF>
 __device__ __forceinline__ void gemm_tile(
     const uint16_t* __restrict__ act,   // MODE 1: [T,H] activations (gathered); MODE 2: [P,F] intermediate
     const int32_t* __restrict__ perm, int k_route, const dymoe_expert_fmt& ex, int K, int N,
-    int row0, int rows, int nblock, uint16_t* __restrict__ hout, float* __restrict__ oout,
-    uint16_t (*xs)[kLdsStride])
+    int k_begin, int k_end, int row0, int rows, int nblock, uint16_t* __restrict__ hout,
+    float* __restrict__ oout, uint16_t (*xs)[kGemmTileM][kLdsStride])
 {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     const int ln = lane & 31;
     const int kb = lane >> 5;
-    const int ntf = (rows + 31) >> 5;
 
     // strips of this wavefront
     long n_a, n_b;
@@ -294,77 +321,88 @@ __device__ __forceinline__ void gemm_tile(
     if (!strip_ok[0]) n_a = 0;
     if (!strip_ok[1]) n_b = 0;
 
-    float16_t acc[2][4];
+    float16_t acc[2][NTF];
 #pragma unroll
     for (int s = 0; s < 2; s++)
 #pragma unroll
-        for (int tf = 0; tf < 4; tf++)
+        for (int tf = 0; tf < NTF; tf++)
 #pragma unroll
             for (int i = 0; i < 16; i++) acc[s][tf][i] = 0.0f;
 
     // staging role: thread -> (row, half) of the token tile
     const int srow = tid >> 1;
     const int shalf = tid & 1;
-    const uint16_t* src_row = nullptr;
-    if (srow < rows) {
-        if (MODE == 1) src_row = act + (long)(perm[row0 + srow] / k_route) * K;
-        else src_row = act + (long)(row0 + srow) * K;
-    }
+    // tile rows past the expert's last token re-read its last token: their
+    // products are computed and dropped, and the loop stays branch-free
+    const int srow_c = min(srow, rows - 1);
+    const uint16_t* src_row;
+    if (MODE == 1) src_row = act + (long)(perm[row0 + srow_c] / k_route) * K;
+    else src_row = act + (long)(row0 + srow_c) * K;
+    uint4 xv[8];
+    auto load_x = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+            xv[i] = *reinterpret_cast<const uint4*>(src_row + k0 + 64 * shalf + 8 * i);
+    };
+    auto store_x = [&](int buf) {
+        uint4* dst = reinterpret_cast<uint4*>(&xs[buf][srow][64 * shalf]);
+        if constexpr (BITS == 16) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) dst[i] = xv[i];
+        } else if constexpr (BITS == 4) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) dst[i] = perm8(xv[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                uint4 o0, o1;
+                perm16(xv[2 * i], xv[2 * i + 1], o0, o1);
+                dst[2 * i] = o0;
+                dst[2 * i + 1] = o1;
+            }
+        }
+    };
 
-    for (int k0 = 0; k0 < K; k0 += kBK) {
-        __syncthreads();  // previous tile fully consumed
-        {
-            uint4 v[8];
-#pragma unroll
-            for (int i = 0; i < 8; i++) {
-                v[i] = make_uint4(0, 0, 0, 0);
-                if (src_row) v[i] = *reinterpret_cast<const uint4*>(src_row + k0 + 64 * shalf + 8 * i);
-            }
-            uint4* dst = reinterpret_cast<uint4*>(&xs[srow][64 * shalf]);
-            if (BITS == 16) {
-#pragma unroll
-                for (int i = 0; i < 8; i++) dst[i] = v[i];
-            } else if (BITS == 4) {
-#pragma unroll
-                for (int i = 0; i < 8; i++) dst[i] = perm8(v[i]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    uint4 o0, o1;
-                    perm16(v[2 * i], v[2 * i + 1], o0, o1);
-                    dst[2 * i] = o0;
-                    dst[2 * i + 1] = o1;
-                }
-            }
-        }
-        StripRaw<BITS> ra, rb;
-        load_strip<BITS>(ma, n_a, kb, k0, K, ra);
-        load_strip<BITS>(mb, n_b, kb, k0, K, rb);
+    // Two register sets (0 / 1) take turns, so no value is ever copied from a
+    // "next" to a "current" register: a copy would have to wait for the loads
+    // it copies.  The scheduler fences keep the prefetch loads at the top of
+    // each half-step, ahead of the MFMA work that hides their latency.
+    StripRaw<BITS> ra0, rb0, ra1, rb1;
+    load_x(k_begin);
+    load_strip<BITS>(ma, n_a, kb, k_begin, K, ra0);
+    load_strip<BITS>(mb, n_b, kb, k_begin, K, rb0);
+    store_x(0);
+    __syncthreads();
+    for (int k0 = k_begin; k0 < k_end; k0 += 2 * kBK) {
+        // half-step A: prefetch block k0 + BK into set 1, multiply set 0 from LDS buffer 0
+        // (past the end the prefetch re-reads the last block instead of branching)
+        const int k1 = min(k0 + kBK, k_end - kBK);
+        load_x(k1);
+        load_strip<BITS>(ma, n_a, kb, k1, K, ra1);
+        load_strip<BITS>(mb, n_b, kb, k1, K, rb1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_kblock<BITS, NTF>(ra0, rb0, xs[0], ln, kb, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        store_x(1);
         __syncthreads();
-#pragma unroll
-        for (int jj = 0; jj < 4; jj++) {
-            uint4 a0, a1, b0, b1;
-            strip_frags<BITS>(ra, jj, a0, a1);
-            strip_frags<BITS>(rb, jj, b0, b1);
-#pragma unroll
-            for (int tf = 0; tf < 4; tf++) {
-                if (tf < ntf) {
-                    const uint4 t0 = *reinterpret_cast<const uint4*>(&xs[32 * tf + ln][64 * kb + 16 * jj]);
-                    const uint4 t1 = *reinterpret_cast<const uint4*>(&xs[32 * tf + ln][64 * kb + 16 * jj + 8]);
-                    acc[0][tf] = mfma16<BITS>(a0, t0, acc[0][tf]);
-                    acc[1][tf] = mfma16<BITS>(b0, t0, acc[1][tf]);
-                    acc[0][tf] = mfma16<BITS>(a1, t1, acc[0][tf]);
-                    acc[1][tf] = mfma16<BITS>(b1, t1, acc[1][tf]);
-                }
-            }
-        }
+        if (k0 + kBK >= k_end) break;   // odd number of K-blocks
+        // half-step B: prefetch block k0 + 2 BK into set 0, multiply set 1 from LDS buffer 1
+        const int k2 = min(k0 + 2 * kBK, k_end - kBK);
+        load_x(k2);
+        load_strip<BITS>(ma, n_a, kb, k2, K, ra0);
+        load_strip<BITS>(mb, n_b, kb, k2, K, rb0);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_kblock<BITS, NTF>(ra1, rb1, xs[1], ln, kb, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        store_x(0);
+        __syncthreads();
     }
 
     // epilogue.  D layout: lane (ln, kb), register i -> weight row 8*(i/4) + 4*kb + i%4, token ln
 #pragma unroll
-    for (int tf = 0; tf < 4; tf++) {
+    for (int tf = 0; tf < NTF; tf++) {
         const int trow = 32 * tf + ln;
-        if (tf < ntf && trow < rows) {
+        if (trow < rows) {
             if (MODE == 1) {
                 if (strip_ok[0]) {
                     const int f0 = nblock * (32 * kGmWaves) + wave * 32;
@@ -376,7 +414,7 @@ __device__ __forceinline__ void gemm_tile(
                         for (int i = 0; i < 4; i++) {
                             const float a = acc[0][tf][4 * g + i];
                             const float u = acc[1][tf][4 * g + i];
-                            hv[i] = a / (1.0f + __expf(-a)) * u;
+                            hv[i] = a * __builtin_amdgcn_rcpf(1.0f + __expf(-a)) * u;
                         }
                         uint2 pk;
                         if (BITS == 16) {
@@ -419,7 +457,8 @@ __global__ __launch_bounds__(kGmThreads) void gemm_kernel(
     const dymoe_expert_fmt* __restrict__ table, const int32_t* __restrict__ plan, int P, int E,
     int k_route, int H, int F, uint16_t* __restrict__ hbuf_out, float* __restrict__ opair)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t xs[kGemmTileM][kLdsStride];
+    extern __shared__ __attribute__((aligned(16))) uint16_t xs_raw[];
+    uint16_t (*xs)[kGemmTileM][kLdsStride] = reinterpret_cast<uint16_t (*)[kGemmTileM][kLdsStride]>(xs_raw);
     const PlanPtrs pp = plan_ptrs(const_cast<int32_t*>(plan), E, P);
     const int tile = blockIdx.y;
     if (tile >= pp.ntiles[0]) return;
@@ -430,22 +469,51 @@ __global__ __launch_bounds__(kGmThreads) void gemm_kernel(
     const dymoe_expert_fmt ex = table[e];
     const int K = (MODE == 1) ? H : F;
     const int N = (MODE == 1) ? F : H;
-    if (b == 16) {
-        gemm_tile<MODE, 16>(MODE == 1 ? x_bf16 : hbuf_in, pp.perm, k_route, ex, K, N, row0, rows,
-                            blockIdx.x, hbuf_out, opair, xs);
-    } else if (b == 4) {
-        gemm_tile<MODE, 4>(MODE == 1 ? x_f16 : hbuf_in, pp.perm, k_route, ex, K, N, row0, rows,
-                           blockIdx.x, hbuf_out, opair, xs);
-    } else {
-        gemm_tile<MODE, 2>(MODE == 1 ? x_f16 : hbuf_in, pp.perm, k_route, ex, K, N, row0, rows,
-                           blockIdx.x, hbuf_out, opair, xs);
+    // split-K (MODE 2 only): blockIdx.z takes K-blocks [z*per, (z+1)*per) and its own output slab
+    const int nkb = K / kBK;
+    const int per = (nkb + (int)gridDim.z - 1) / (int)gridDim.z;
+    const int k_begin = (int)blockIdx.z * per * kBK;
+    const int k_end = min(K, k_begin + per * kBK);
+    float* oz = opair + (size_t)blockIdx.z * (size_t)P * (size_t)N;
+    if (k_begin >= k_end) {
+        // a split with no K-blocks still owns its slab: write zeros
+        if (MODE == 2) {
+            for (int i = threadIdx.x; i < rows * 64; i += kGmThreads) {
+                const int r = i >> 6, c = (blockIdx.x * 64 + (i & 63)) * 4;
+                if (c < N) *reinterpret_cast<float4*>(oz + (size_t)pp.perm[row0 + r] * N + c) = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        return;
     }
+    const uint16_t* act = (MODE != 1) ? hbuf_in : (b == 16 ? x_bf16 : x_f16);
+    const int ntf = (rows + 31) >> 5;
+    // one instantiation per (precision, number of 32-token fragments): the
+    // accumulators then sit in fixed registers for the whole K loop
+#define DYMOE_TILE(BITS_, NTF_)                                                                      \
+    gemm_tile<MODE, BITS_, NTF_>(act, pp.perm, k_route, ex, K, N, k_begin, k_end, row0, rows,        \
+                                 blockIdx.x, hbuf_out, oz, xs)
+#define DYMOE_TILE_NTF(BITS_)                     \
+    switch (ntf) {                                \
+    case 1: DYMOE_TILE(BITS_, 1); break;          \
+    case 2: DYMOE_TILE(BITS_, 2); break;          \
+    case 3: DYMOE_TILE(BITS_, 3); break;          \
+    default: DYMOE_TILE(BITS_, 4); break;         \
+    }
+    if (b == 16) {
+        DYMOE_TILE_NTF(16)
+    } else if (b == 4) {
+        DYMOE_TILE_NTF(4)
+    } else {
+        DYMOE_TILE_NTF(2)
+    }
+#undef DYMOE_TILE_NTF
+#undef DYMOE_TILE
 }
 
 // y[t,j] = sum_slot w[t,slot] * o[pair,j]  (pairs of skipped experts omitted)
 __global__ __launch_bounds__(256) void gemm_combine_kernel(
     const float* __restrict__ opair, const int32_t* __restrict__ idx, const float* __restrict__ w,
-    const uint8_t* __restrict__ bits, int T, int H, int E, int k, int out_dtype,
+    const uint8_t* __restrict__ bits, int T, int H, int E, int k, int splits, int out_dtype,
     void* __restrict__ y)
 {
     const long i4 = (long)blockIdx.x * 256 + threadIdx.x;  // groups of 4 columns
@@ -461,7 +529,11 @@ __global__ __launch_bounds__(256) void gemm_combine_kernel(
         const int b = bits[e];
         if (b != 16 && b != 4 && b != 2) continue;
         const float g = w[p];
-        const float4 o = *reinterpret_cast<const float4*>(opair + (long)p * H + j);
+        float4 o = *reinterpret_cast<const float4*>(opair + (long)p * H + j);
+        for (int z = 1; z < splits; z++) {
+            const float4 oz = *reinterpret_cast<const float4*>(opair + ((long)z * T * k + p) * H + j);
+            o.x += oz.x; o.y += oz.y; o.z += oz.z; o.w += oz.w;
+        }
         acc.x = fmaf(g, o.x, acc.x);
         acc.y = fmaf(g, o.y, acc.y);
         acc.z = fmaf(g, o.z, acc.z);
@@ -497,22 +569,39 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const long n8 = (long)T * H / 8;
     hipLaunchKernelGGL(to_f16_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st, xb, n8, xh);
     DYMOE_HIP_LAUNCH_CHECK();
+    // two token-tile buffers in LDS: more than the 64 KiB a kernel gets by default
+    constexpr size_t kLdsBytes = 2 * sizeof(uint16_t) * kGemmTileM * kLdsStride;
+    static bool lds_attr_set = false;
+    if (!lds_attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes) != hipSuccess)
+            return DYMOE_EHIP;
+        lds_attr_set = true;
+    }
     const int max_tiles = P / kGemmTileM + E;
     const dim3 g1((unsigned)((F + 127) / 128), (unsigned)max_tiles);
-    {
-        dymoe_launch(ctx, DYMOE_K_GEMM1, (gemm_kernel<1>), g1, dim3(kGmThreads), 0, st, xb, xh, (const uint16_t*)nullptr,
-                           bits, table, plan, P, E, k, H, F, hbuf, (float*)nullptr);
-    }
+    dymoe_launch(ctx, DYMOE_K_GEMM1, (gemm_kernel<1>), g1, dim3(kGmThreads), kLdsBytes, st, xb, xh,
+                 (const uint16_t*)nullptr, bits, table, plan, P, E, k, H, F, hbuf, (float*)nullptr);
     DYMOE_HIP_LAUNCH_CHECK();
-    const dim3 g2((unsigned)((H + 255) / 256), (unsigned)max_tiles);
-    {
-        dymoe_launch(ctx, DYMOE_K_GEMM2, (gemm_kernel<2>), g2, dim3(kGmThreads), 0, st, xb, xh, hbuf, bits, table, plan,
-                           P, E, k, H, F, (uint16_t*)nullptr, opair);
-    }
+    // The down projection has few output tiles (H/256 per token tile): split K so
+    // that the launch still covers the chip.  Each split writes its own slab of
+    // per-pair outputs; the combine kernel adds the slabs in a fixed order.
+    const int nblk2 = (H + 255) / 256;
+    const long est_blocks = (long)nblk2 * ((long)P / kGemmTileM + (E < P ? E : P) / 2 + 1);
+    int splits = (int)((2L * ctx->num_cu + est_blocks - 1) / est_blocks);
+    const int max_splits = (F + kSeg - 1) / kSeg;     // slabs the workspace holds
+    if (splits > max_splits) splits = max_splits;
+    if (splits > 4) splits = 4;
+    if (splits < 1) splits = 1;
+    const dim3 g2((unsigned)nblk2, (unsigned)max_tiles, (unsigned)splits);
+    dymoe_launch(ctx, DYMOE_K_GEMM2, (gemm_kernel<2>), g2, dim3(kGmThreads), kLdsBytes, st, xb, xh, hbuf,
+                 bits, table, plan, P, E, k, H, F, (uint16_t*)nullptr, opair);
     DYMOE_HIP_LAUNCH_CHECK();
     const long n4 = (long)T * (H / 4);
     dymoe_launch(ctx, DYMOE_K_GEMM_COMBINE, gemm_combine_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, opair,
-                       idx, w, bits, T, H, E, k, out_dtype, y);
+                       idx, w, bits, T, H, E, k, splits, out_dtype, y);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }

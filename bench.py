@@ -70,7 +70,7 @@ def main():
     x_np, _ = synth.activations(cfg)
     wg_np, bias_np = synth.router(cfg)
     ctx = B.Context(0)
-    stores = [ExpertStore([[bf16(m) for m in host_w[e]] for e in range(E)], H, F, dev)]
+    stores = [ExpertStore([[bf16(m) for m in host_w[e]] for e in range(E)], H, F, dev, ctx=ctx)]
     for _ in range(LAYER_COPIES - 1):
         stores.append(stores[0].clone())
     x = bf16(x_np)

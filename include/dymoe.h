@@ -59,6 +59,10 @@ extern "C" {
 #define DYMOE_PATH_GEMV 1  /* bandwidth-bound dequant GEMV per (token, expert) pair */
 #define DYMOE_PATH_GEMM 2  /* tokens grouped by expert, MFMA grouped GEMM */
 
+/* layout of packed expert weights (codes + scale/zero, and the bf16 tile copy) */
+#define DYMOE_LAYOUT_ROWMAJOR 0 /* as dymoe_quantize_pack writes: what the GEMV path reads */
+#define DYMOE_LAYOUT_TILE 1     /* 32-row x 128-column tiles: what the GEMM path reads */
+
 #define DYMOE_MAX_TIERS 8
 #define DYMOE_MAX_EXPERTS 1024
 
@@ -70,13 +74,30 @@ typedef struct dymoe_ctx dymoe_ctx;
 /*
  * One expert's weights in every precision the caller has materialised.
  * Index 0, 1, 2 of each array = W1 (gate, [F,H]), W3 (up, [F,H]), W2 (down, [H,F]).
- * w: bf16.  q4/q2: packed codes as written by dymoe_quantize_pack; s4, z4, s2, z2:
- * fp16 scale and zero, one per group of `group` columns ([rows, cols/group]).
+ * w: bf16, row-major.  q4/q2: packed codes; s4, z4, s2, z2: fp16 scale and zero,
+ * one per group of 64 columns.  wt: optional copy of w in the tile layout
+ * (dymoe_pack_tiles), read by the GEMM path for 16-bit experts; when NULL that
+ * path reads w row by row (slower).
  * Entries for precisions that are never selected may be NULL.
  * The table lives in device memory ([E] of these).
+ *
+ * Two layouts of a packed [N,K] matrix exist, with the same bytes in a
+ * different order (N multiple of 32 and K multiple of 128 for the tile one):
+ *  DYMOE_LAYOUT_ROWMAJOR  codes [N, K*bits/8], scale and zero [N, K/64].
+ *  DYMOE_LAYOUT_TILE      tiles of 32 rows x 128 columns, tile (nt, kt) at index
+ *    nt*(K/128)+kt.  "Lane" l = 32*kb + r of a tile owns row 32*nt+r, columns
+ *    128*kt+64*kb .. +64 (one quantisation group).  bf16: 8 KiB per tile, the
+ *    lane's chunk j (8 columns, 16 bytes) at byte j*1024 + l*16.  int4: 2 KiB
+ *    of codes per tile, the lane's chunk c (32 codes) at byte c*1024 + l*16.
+ *    int2: 1 KiB per tile, the lane's 64 codes at byte l*16.  Codes inside a
+ *    chunk are packed as in the row-major layout.  scale / zero: 64 fp16 per
+ *    tile, the lane's at index l.
+ * The GEMV path of dymoe_moe_ffn_mixed reads q4/q2 row-major, the GEMM path
+ * reads them tiled: quantize with the layout of the path that will run.
  */
 typedef struct {
     const void* w[3];
+    const void* wt[3];
     uint8_t* q4[3];
     void* s4[3];
     void* z4[3];
@@ -191,13 +212,22 @@ int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits,
  * Device-driven quantization of a layer's experts, so that the precision
  * decision never travels to the host: for each expert e with bits[e] in {2,4}
  * (and load[e] > 0 when load is given), quantize table[e].w[0..3) at bits[e]
- * into table[e].q4/s4/z4 or q2/s2/z2 (same arithmetic and layout as
- * dymoe_quantize_pack).  Experts at 16 or 0 bits are left untouched.
+ * into table[e].q4/s4/z4 or q2/s2/z2 (same arithmetic as dymoe_quantize_pack;
+ * layout = DYMOE_LAYOUT_ROWMAJOR or DYMOE_LAYOUT_TILE, the latter needs H and F
+ * multiples of 128).  Experts at 16 or 0 bits are left untouched.
  * table [E] device, bits [E] uint8 device, load [E] int32 device or NULL.
  * Weight and code pointers in the table must be 16-byte aligned.
  */
 int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const uint8_t* bits,
-                           const int32_t* load, int E, int H, int F, int group, void* stream);
+                           const int32_t* load, int E, int H, int F, int group, int layout,
+                           void* stream);
+
+/*
+ * bf16 row-major [N,K] -> bf16 tile layout (see dymoe_expert_fmt), a pure
+ * permutation done once when an expert's weights are loaded.  N multiple of
+ * 32, K multiple of 128; w and tiles 16-byte aligned, distinct buffers.
+ */
+int dymoe_pack_tiles(dymoe_ctx* ctx, const void* w, long N, long K, void* tiles, void* stream);
 
 /*
  * Mixed-precision SwiGLU expert FFN (paper Sec. 4.1: the executor runs the
@@ -208,7 +238,9 @@ int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const 
  *   4 / 2 = the dequantised q4 / q2 codes, 0 = term omitted (no renormalising).
  * x [T,H] bf16, idx [T,k] int32, w [T,k] fp32, bits [E] uint8, table [E].
  * y [T,H] bf16 (DYMOE_OUT_BF16) or fp32 (DYMOE_OUT_F32); every row is written.
- * path: DYMOE_PATH_AUTO picks GEMV for few tokens per expert, GEMM otherwise.
+ * path: DYMOE_PATH_AUTO picks GEMV for T <= 4 (or when the sizes rule out the
+ * GEMM), GEMM otherwise.  GEMV reads q4/q2 in DYMOE_LAYOUT_ROWMAJOR, GEMM in
+ * DYMOE_LAYOUT_TILE.
  * workspace: at least dymoe_workspace_bytes(T,H,F,E,k) bytes, 256-byte aligned;
  * contents are scratch.  Limits: group = 64; H, F multiples of 64;
  * GEMV path H <= 8192; GEMM path H, F multiples of 128; E <= DYMOE_MAX_EXPERTS.

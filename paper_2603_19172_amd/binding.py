@@ -25,13 +25,14 @@ OK, EINVAL, ENOSPC, EHIP, ENOTSUP, ENOCTX = 0, -1, -2, -3, -4, -5
 PHASE_PREFILL, PHASE_DECODE = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
 PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
+LAYOUT_ROWMAJOR, LAYOUT_TILE = 0, 1
 
 # every symbol include/dymoe.h declares
 EXPORTS = [
     "dymoe_create", "dymoe_destroy", "dymoe_strerror", "dymoe_workspace_bytes",
     "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_expert_importance",
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
-    "dymoe_quantize_experts", "dymoe_moe_ffn_mixed",
+    "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_moe_ffn_mixed",
     "dymoe_timing_enable", "dymoe_timing_read", "dymoe_kernel_name",
 ]
 
@@ -41,7 +42,7 @@ KERNELS = ["route", "token_norm", "importance", "assign", "quantize", "gemv_phas
 
 class ExpertFmt(C.Structure):
     """Mirror of dymoe_expert_fmt."""
-    _fields_ = [("w", C.c_void_p * 3), ("q4", C.c_void_p * 3), ("s4", C.c_void_p * 3),
+    _fields_ = [("w", C.c_void_p * 3), ("wt", C.c_void_p * 3), ("q4", C.c_void_p * 3), ("s4", C.c_void_p * 3),
                 ("z4", C.c_void_p * 3), ("q2", C.c_void_p * 3), ("s2", C.c_void_p * 3),
                 ("z2", C.c_void_p * 3)]
 
@@ -68,7 +69,9 @@ lib.dymoe_assign_precision.argtypes = [_vp, _i, _vp, _vp, _i, _i, _vp, _vp, _i, 
 lib.dymoe_quantize_pack.restype = _i
 lib.dymoe_quantize_pack.argtypes = [_vp, _vp, _l, _l, _i, _i, _vp, _vp, _vp, _vp]
 lib.dymoe_quantize_experts.restype = _i
-lib.dymoe_quantize_experts.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]
+lib.dymoe_quantize_experts.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]
+lib.dymoe_pack_tiles.restype = _i
+lib.dymoe_pack_tiles.argtypes = [_vp, _vp, _l, _l, _vp, _vp]
 lib.dymoe_moe_ffn_mixed.restype = _i
 lib.dymoe_moe_ffn_mixed.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i,
                                     _vp, _vp, _sz, _vp]
@@ -222,10 +225,18 @@ class Context:
                "dymoe_quantize_pack")
         return codes, scale, zero
 
-    def quantize_experts(self, table, bits, load, E, H, F, group=64, stream=None):
+    def quantize_experts(self, table, bits, load, E, H, F, group=64, layout=LAYOUT_ROWMAJOR,
+                         stream=None):
         _check(lib.dymoe_quantize_experts(self._h, _ptr(table), _ptr(bits, torch.uint8),
-                                          _ptr(load, torch.int32), E, H, F, group,
+                                          _ptr(load, torch.int32), E, H, F, group, layout,
                                           _stream(stream)), "dymoe_quantize_experts")
+
+    def pack_tiles(self, w, stream=None):
+        N, K = w.shape
+        out = torch.empty_like(w)
+        _check(lib.dymoe_pack_tiles(self._h, _ptr(w, torch.bfloat16), N, K, _ptr(out),
+                                    _stream(stream)), "dymoe_pack_tiles")
+        return out
 
     # -- S5
     def moe_ffn_mixed(self, x, idx, w, bits, table, F, out_dtype=OUT_BF16, path=PATH_AUTO,
@@ -260,6 +271,10 @@ def make_expert_table(experts, device):
             for i in range(3):
                 arr[e].w[i] = _ptr(ex["w"][i], torch.bfloat16)
             keep.append(ex["w"])
+        if ex.get("wt") is not None:
+            for i in range(3):
+                arr[e].wt[i] = _ptr(ex["wt"][i], torch.bfloat16)
+            keep.append(ex["wt"])
         for b in (4, 2):
             trip = ex.get("q%d" % b)
             if trip is None:

@@ -1,18 +1,24 @@
 // Prefill path of the mixed-precision SwiGLU expert FFN: tokens grouped by
 // expert, one MFMA grouped GEMM per projection, all experts in one launch.
 //
-// Tile: up to 128 token rows of one expert x (4 wavefronts x 2 strips of 32
-// weight rows), K-blocks of 128.  Weights never touch LDS: the MFMA A operand
-// of lane (r, kb) is 8 consecutive k of weight row r, so every lane loads its
-// own row's bytes straight from HBM (bf16: as is; int4 / int2: packed codes,
-// turned into fp16 in registers).  The contraction order inside a K-block is
-// permuted so that one lane's 64 k (one quantisation group) are contiguous in
-// memory; the token tile in LDS is stored in the matching order.
-//   bf16 experts: v_mfma_f32_32x32x16_bf16 on the bf16 activations
-//   int4 / int2 : v_mfma_f32_32x32x16_f16 on an fp16 copy of the activations,
-//                 weights dequantised as fma(q, s, m) in packed fp16
-// Code fields become fp16 numbers by OR-ing them into the mantissa of 2^n
-// (n such that the field's lowest bit weighs one), then subtracting 2^n.
+// Work unit: up to 128 token rows of one expert x (8 wavefronts x 2 strips of
+// 32 weight rows), K walked in tiles of 128.
+//  * Weights never touch LDS.  They are stored in 32 x 128 tiles whose byte
+//    order is the MFMA A-operand order (lane (r, kb) owns row r, columns
+//    64 kb .. 64 kb + 64, one quantisation group), so every load instruction of
+//    a wavefront reads 1 KiB of contiguous memory straight into the registers
+//    the MFMA consumes (bf16) or the dequantiser consumes (int4 / int2).
+//  * The token tile is shared by the 8 wavefronts through a double-buffered
+//    LDS tile; it is copied from a 16-bit copy of the activations that is
+//    already in the column order the code fields come out of a dword, so
+//    staging is a plain copy.
+//  * bf16 experts: v_mfma_f32_32x32x16_bf16 on the bf16 activations.
+//    int4 / int2 experts: v_mfma_f32_32x32x16_f16 on an fp16 copy of the
+//    activations; weights become fp16 in registers: a code field OR-ed into the
+//    mantissa of 2^n (n such that the field's lowest bit weighs one) is the
+//    number 2^n + q; subtracting 2^n is exact; then one packed fma(q, s, m).
+//  * Two wavefronts share a SIMD, so one's global-load and LDS waits are
+//    covered by the other's MFMA work.
 #include <math.h>
 
 #include "common.hpp"
@@ -20,10 +26,10 @@
 
 namespace dymoe {
 
-constexpr int kGmThreads = 256;
-constexpr int kGmWaves = 4;
-constexpr int kBK = 128;            // K-block
-constexpr int kLdsStride = 136;     // 16-bit elements per LDS row (128 + pad, keeps b128 reads conflict free)
+constexpr int kGmThreads = 512;
+constexpr int kGmWaves = 8;
+constexpr int kBK = 128;            // K-tile
+constexpr int kLdsStride = 136;     // 16-bit elements per LDS row (128 + pad keeps 16-byte reads conflict free)
 
 // ----------------------------------------------------------------------------
 // plan: counting sort of the (token, slot) pairs by expert + tile list
@@ -103,137 +109,9 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
     }
 }
 
-// fp16 copy of the bf16 activations (exact inside fp16's normal range)
-__global__ __launch_bounds__(256) void to_f16_kernel(const uint16_t* __restrict__ x, long n8,
-                                                     uint16_t* __restrict__ out)
-{
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n8) return;
-    const uint4 v = reinterpret_cast<const uint4*>(x)[i];
-    uint4 o;
-    o.x = pack_half2(bf16_lo(v.x), bf16_hi(v.x));
-    o.y = pack_half2(bf16_lo(v.y), bf16_hi(v.y));
-    o.z = pack_half2(bf16_lo(v.z), bf16_hi(v.z));
-    o.w = pack_half2(bf16_lo(v.w), bf16_hi(v.w));
-    reinterpret_cast<uint4*>(out)[i] = o;
-}
-
-// ----------------------------------------------------------------------------
-// weight strips
-
-template <int BITS> struct StripRaw;
-template <> struct StripRaw<16> { uint4 r[8]; };
-template <> struct StripRaw<4> { uint4 r[2]; uint32_t s2, m2; };
-template <> struct StripRaw<2> { uint4 r[1]; uint32_t s2, m2; };
-
-struct MatPtr {
-    const uint16_t* w;
-    const uint8_t* q;
-    const uint16_t* s;
-    const uint16_t* z;
-};
-
-__device__ __forceinline__ MatPtr mat_ptr(const dymoe_expert_fmt& ex, int mat, int b)
-{
-    MatPtr m;
-    m.w = reinterpret_cast<const uint16_t*>(ex.w[mat]);
-    m.q = (b == 4) ? ex.q4[mat] : ex.q2[mat];
-    m.s = reinterpret_cast<const uint16_t*>((b == 4) ? ex.s4[mat] : ex.s2[mat]);
-    m.z = reinterpret_cast<const uint16_t*>((b == 4) ? ex.z4[mat] : ex.z2[mat]);
-    return m;
-}
-
-// lane (n, kb) of a strip loads k in [k0 + 64 kb, k0 + 64 kb + 64) of weight row n
-template <int BITS>
-__device__ __forceinline__ void load_strip(const MatPtr& m, long n, int kb, int k0, int K,
-                                           StripRaw<BITS>& raw)
-{
-    const int kk = k0 + 64 * kb;
-    if constexpr (BITS == 16) {
-        const uint4* src = reinterpret_cast<const uint4*>(m.w + n * K + kk);
-#pragma unroll
-        for (int j = 0; j < 8; j++) raw.r[j] = src[j];
-    } else if constexpr (BITS == 4) {
-        const uint4* src = reinterpret_cast<const uint4*>(m.q + n * (long)(K >> 1) + (kk >> 1));
-        StripRaw<4>& r4 = raw;
-        r4.r[0] = src[0];
-        r4.r[1] = src[1];
-        const long g = n * (long)(K >> 6) + (kk >> 6);
-        const uint32_t s = m.s[g], z = m.z[g];
-        r4.s2 = s | (s << 16);
-        r4.m2 = z | (z << 16);
-    } else {
-        const uint4* src = reinterpret_cast<const uint4*>(m.q + n * (long)(K >> 2) + (kk >> 2));
-        StripRaw<2>& r2 = raw;
-        r2.r[0] = src[0];
-        const long g = n * (long)(K >> 6) + (kk >> 6);
-        const uint32_t s = m.s[g], z = m.z[g];
-        r2.s2 = s | (s << 16);
-        r2.m2 = z | (z << 16);
-    }
-}
-
-__device__ __forceinline__ uint32_t deq_pair(uint32_t biased, uint32_t bias2, uint32_t s2, uint32_t m2)
-{
-    const half2_t q = __builtin_bit_cast(half2_t, biased) - __builtin_bit_cast(half2_t, bias2);  // exact
-    const half2_t r = __builtin_elementwise_fma(q, __builtin_bit_cast(half2_t, s2),
-                                                __builtin_bit_cast(half2_t, m2));
-    return __builtin_bit_cast(uint32_t, r);
-}
-
-// A fragments of MFMA sub-steps 2*jj and 2*jj+1 (8 k each) of one strip
-template <int BITS>
-__device__ __forceinline__ void strip_frags(const StripRaw<BITS>& raw, int jj, uint4& f0, uint4& f1)
-{
-    if constexpr (BITS == 16) {
-        f0 = raw.r[2 * jj];
-        f1 = raw.r[2 * jj + 1];
-    } else if constexpr (BITS == 4) {
-        const StripRaw<4>& r = raw;
-        const uint4 q = r.r[jj >> 1];
-        const uint32_t w0 = (jj & 1) ? q.z : q.x;
-        const uint32_t w1 = (jj & 1) ? q.w : q.y;
-        // k order inside a fragment: 0,4,1,5,2,6,3,7
-        uint32_t v = w0, v8 = w0 >> 8;
-        f0.x = deq_pair((v & 0x000F000Fu) | 0x64006400u, 0x64006400u, r.s2, r.m2);
-        f0.y = deq_pair((v & 0x00F000F0u) | 0x54005400u, 0x54005400u, r.s2, r.m2);
-        f0.z = deq_pair((v8 & 0x000F000Fu) | 0x64006400u, 0x64006400u, r.s2, r.m2);
-        f0.w = deq_pair((v8 & 0x00F000F0u) | 0x54005400u, 0x54005400u, r.s2, r.m2);
-        v = w1; v8 = w1 >> 8;
-        f1.x = deq_pair((v & 0x000F000Fu) | 0x64006400u, 0x64006400u, r.s2, r.m2);
-        f1.y = deq_pair((v & 0x00F000F0u) | 0x54005400u, 0x54005400u, r.s2, r.m2);
-        f1.z = deq_pair((v8 & 0x000F000Fu) | 0x64006400u, 0x64006400u, r.s2, r.m2);
-        f1.w = deq_pair((v8 & 0x00F000F0u) | 0x54005400u, 0x54005400u, r.s2, r.m2);
-    } else {
-        const StripRaw<2>& r = raw;
-        const uint4 q = r.r[0];
-        const uint32_t v = (jj == 0) ? q.x : (jj == 1) ? q.y : (jj == 2) ? q.z : q.w;
-        const uint32_t v10 = v >> 10;
-        // 16 codes of the dword; k order 0,8,1,9,2,10,3,11 | 4,12,5,13,6,14,7,15
-        f0.x = deq_pair((v & 0x00030003u) | 0x64006400u, 0x64006400u, r.s2, r.m2);
-        f0.y = deq_pair((v & 0x000C000Cu) | 0x5C005C00u, 0x5C005C00u, r.s2, r.m2);
-        f0.z = deq_pair((v & 0x00300030u) | 0x54005400u, 0x54005400u, r.s2, r.m2);
-        f0.w = deq_pair((v & 0x00C000C0u) | 0x4C004C00u, 0x4C004C00u, r.s2, r.m2);
-        f1.x = deq_pair((v & 0x03000300u) | 0x44004400u, 0x44004400u, r.s2, r.m2);
-        f1.y = deq_pair((v10 & 0x00030003u) | 0x64006400u, 0x64006400u, r.s2, r.m2);
-        f1.z = deq_pair((v10 & 0x000C000Cu) | 0x5C005C00u, 0x5C005C00u, r.s2, r.m2);
-        f1.w = deq_pair((v10 & 0x00300030u) | 0x54005400u, 0x54005400u, r.s2, r.m2);
-    }
-}
-
-template <int BITS>
-__device__ __forceinline__ float16_t mfma16(const uint4 a, const uint4 b, const float16_t c)
-{
-    if constexpr (BITS == 16)
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                      __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a),
-                                                      __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
-}
-
-// reorder 8 (int4) or 16 (int2) consecutive 16-bit activations into the k
-// order in which the code fields come out of a dword
+// Column order in which the code fields of a dword come out of the mask-and-or
+// extraction: inside every 8 columns (int4) 0,4,1,5,2,6,3,7; inside every 16
+// columns (int2) 0,8,1,9,...,7,15.  Inputs are packed pairs of 16-bit values.
 __device__ __forceinline__ uint4 perm8(const uint4 v)
 {
     uint4 o;
@@ -256,11 +134,149 @@ __device__ __forceinline__ void perm16(const uint4 a, const uint4 b, uint4& o0, 
     o1.w = (a.w >> 16) | (b.w & 0xffff0000u);
 }
 
-// one K-block of MFMAs for NTF token fragments (32 tokens each)
+// Two fp16 copies of the bf16 activations (exact inside fp16's normal range),
+// one in each of the column orders above.  A thread converts 16 columns.
+__global__ __launch_bounds__(256) void prep_x_kernel(const uint16_t* __restrict__ x, long n16,
+                                                     uint16_t* __restrict__ xh4,
+                                                     uint16_t* __restrict__ xh2)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n16) return;
+    const uint4 a = reinterpret_cast<const uint4*>(x)[2 * i];
+    const uint4 b = reinterpret_cast<const uint4*>(x)[2 * i + 1];
+    uint4 ha, hb;
+    ha.x = pack_half2(bf16_lo(a.x), bf16_hi(a.x)); ha.y = pack_half2(bf16_lo(a.y), bf16_hi(a.y));
+    ha.z = pack_half2(bf16_lo(a.z), bf16_hi(a.z)); ha.w = pack_half2(bf16_lo(a.w), bf16_hi(a.w));
+    hb.x = pack_half2(bf16_lo(b.x), bf16_hi(b.x)); hb.y = pack_half2(bf16_lo(b.y), bf16_hi(b.y));
+    hb.z = pack_half2(bf16_lo(b.z), bf16_hi(b.z)); hb.w = pack_half2(bf16_lo(b.w), bf16_hi(b.w));
+    reinterpret_cast<uint4*>(xh4)[2 * i] = perm8(ha);
+    reinterpret_cast<uint4*>(xh4)[2 * i + 1] = perm8(hb);
+    uint4 o0, o1;
+    perm16(ha, hb, o0, o1);
+    reinterpret_cast<uint4*>(xh2)[2 * i] = o0;
+    reinterpret_cast<uint4*>(xh2)[2 * i + 1] = o1;
+}
+
+// ----------------------------------------------------------------------------
+// weight strips (32 rows x one K-tile of 128), as one lane holds them
+
+template <int BITS> struct StripRaw;
+template <> struct StripRaw<16> { uint4 r[8]; };
+template <> struct StripRaw<4> { uint4 r[2]; uint32_t s2, m2; };
+template <> struct StripRaw<2> { uint4 r[1]; uint32_t s2, m2; };
+
+struct MatPtr {
+    const uint16_t* w;    // bf16 row-major
+    const char* wt;       // bf16 tiles (may be null)
+    const char* q;        // packed codes, tile layout
+    const uint16_t* s;    // fp16 scale, tile layout
+    const uint16_t* z;    // fp16 zero, tile layout
+};
+
+__device__ __forceinline__ MatPtr mat_ptr(const dymoe_expert_fmt& ex, int mat, int b)
+{
+    MatPtr m;
+    m.w = reinterpret_cast<const uint16_t*>(ex.w[mat]);
+    m.wt = reinterpret_cast<const char*>(ex.wt[mat]);
+    m.q = reinterpret_cast<const char*>((b == 4) ? ex.q4[mat] : ex.q2[mat]);
+    m.s = reinterpret_cast<const uint16_t*>((b == 4) ? ex.s4[mat] : ex.s2[mat]);
+    m.z = reinterpret_cast<const uint16_t*>((b == 4) ? ex.z4[mat] : ex.z2[mat]);
+    return m;
+}
+
+// loads of tile (nt, kt) of a [N,K] matrix for this lane
+template <int BITS>
+__device__ __forceinline__ void load_strip(const MatPtr& m, long nt, int kt, int K, int lane,
+                                           StripRaw<BITS>& raw)
+{
+    const long tile = nt * (K >> 7) + kt;
+    if constexpr (BITS == 16) {
+        if (m.wt) {
+            const char* src = m.wt + tile * 8192 + lane * 16;
+#pragma unroll
+            for (int j = 0; j < 8; j++) raw.r[j] = *reinterpret_cast<const uint4*>(src + j * 1024);
+        } else {
+            const uint4* src = reinterpret_cast<const uint4*>(
+                m.w + (nt * 32 + (lane & 31)) * K + kt * 128 + 64 * (lane >> 5));
+#pragma unroll
+            for (int j = 0; j < 8; j++) raw.r[j] = src[j];
+        }
+    } else {
+        if constexpr (BITS == 4) {
+            const char* src = m.q + tile * 2048 + lane * 16;
+            raw.r[0] = *reinterpret_cast<const uint4*>(src);
+            raw.r[1] = *reinterpret_cast<const uint4*>(src + 1024);
+        } else {
+            raw.r[0] = *reinterpret_cast<const uint4*>(m.q + tile * 1024 + lane * 16);
+        }
+        const uint32_t s = m.s[tile * 64 + lane], z = m.z[tile * 64 + lane];
+        raw.s2 = s | (s << 16);
+        raw.m2 = z | (z << 16);
+    }
+}
+
+__device__ __forceinline__ uint32_t deq_pair(uint32_t biased, uint32_t bias2, uint32_t s2, uint32_t m2)
+{
+    const half2_t q = __builtin_bit_cast(half2_t, biased) - __builtin_bit_cast(half2_t, bias2);  // exact
+    const half2_t r = __builtin_elementwise_fma(q, __builtin_bit_cast(half2_t, s2),
+                                                __builtin_bit_cast(half2_t, m2));
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// A fragments of MFMA sub-steps 2*jj and 2*jj+1 (8 k each) of one strip
+template <int BITS>
+__device__ __forceinline__ void strip_frags(const StripRaw<BITS>& raw, int jj, uint4& f0, uint4& f1)
+{
+    if constexpr (BITS == 16) {
+        f0 = raw.r[2 * jj];
+        f1 = raw.r[2 * jj + 1];
+    } else if constexpr (BITS == 4) {
+        const uint4 q = raw.r[jj >> 1];
+        const uint32_t w0 = (jj & 1) ? q.z : q.x;
+        const uint32_t w1 = (jj & 1) ? q.w : q.y;
+        // k order inside a fragment: 0,4,1,5,2,6,3,7
+        uint32_t v = w0, v8 = w0 >> 8;
+        f0.x = deq_pair((v & 0x000F000Fu) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
+        f0.y = deq_pair((v & 0x00F000F0u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
+        f0.z = deq_pair((v8 & 0x000F000Fu) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
+        f0.w = deq_pair((v8 & 0x00F000F0u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
+        v = w1; v8 = w1 >> 8;
+        f1.x = deq_pair((v & 0x000F000Fu) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
+        f1.y = deq_pair((v & 0x00F000F0u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
+        f1.z = deq_pair((v8 & 0x000F000Fu) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
+        f1.w = deq_pair((v8 & 0x00F000F0u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
+    } else {
+        const uint4 q = raw.r[0];
+        const uint32_t v = (jj == 0) ? q.x : (jj == 1) ? q.y : (jj == 2) ? q.z : q.w;
+        const uint32_t v10 = v >> 10;
+        // 16 codes of the dword; k order 0,8,1,9,2,10,3,11 | 4,12,5,13,6,14,7,15
+        f0.x = deq_pair((v & 0x00030003u) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
+        f0.y = deq_pair((v & 0x000C000Cu) | 0x5C005C00u, 0x5C005C00u, raw.s2, raw.m2);
+        f0.z = deq_pair((v & 0x00300030u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
+        f0.w = deq_pair((v & 0x00C000C0u) | 0x4C004C00u, 0x4C004C00u, raw.s2, raw.m2);
+        f1.x = deq_pair((v & 0x03000300u) | 0x44004400u, 0x44004400u, raw.s2, raw.m2);
+        f1.y = deq_pair((v10 & 0x00030003u) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
+        f1.z = deq_pair((v10 & 0x000C000Cu) | 0x5C005C00u, 0x5C005C00u, raw.s2, raw.m2);
+        f1.w = deq_pair((v10 & 0x00300030u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ float16_t mfma16(const uint4 a, const uint4 b, const float16_t c)
+{
+    if constexpr (BITS == 16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                      __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a),
+                                                      __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+}
+
+// one K-tile of MFMAs for NTF token fragments (32 tokens each)
 template <int BITS, int NTF>
-__device__ __forceinline__ void compute_kblock(const StripRaw<BITS>& ra, const StripRaw<BITS>& rb,
-                                               const uint16_t (*xs)[kLdsStride], int ln, int kb,
-                                               float16_t (&acc)[2][NTF])
+__device__ __forceinline__ void compute_ktile(const StripRaw<BITS>& ra, const StripRaw<BITS>& rb,
+                                              const uint16_t (*xs)[kLdsStride], int ln, int kb,
+                                              float16_t (&acc)[2][NTF])
 {
 #pragma unroll
     for (int jj = 0; jj < 4; jj++) {
@@ -282,16 +298,12 @@ __device__ __forceinline__ void compute_kblock(const StripRaw<BITS>& ra, const S
 // ----------------------------------------------------------------------------
 // MODE 1: h = silu(x W1^T) * (x W3^T)   strips = (W1 rows, W3 rows) of the same 32 features
 // MODE 2: o = h W2^T                     strips = two adjacent groups of 32 rows of W2,
-//                                        K range [k_begin, k_end) of the split
-// The K loop is software pipelined: while K-block i is multiplied out of
-// registers (weights) and LDS buffer i&1 (tokens), the weights of K-block i+1
-// are in flight to registers and its token tile is in flight to registers, to
-// be written to the other LDS buffer afterwards; one barrier per K-block.
+//                                        K-tiles [kt_begin, kt_end) of the split
 template <int MODE, int BITS, int NTF>
 __device__ __forceinline__ void gemm_tile(
-    const uint16_t* __restrict__ act,   // MODE 1: [T,H] activations (gathered); MODE 2: [P,F] intermediate
+    const uint16_t* __restrict__ act,   // MODE 1: [T,K] activations (gathered); MODE 2: [P,K] intermediate
     const int32_t* __restrict__ perm, int k_route, const dymoe_expert_fmt& ex, int K, int N,
-    int k_begin, int k_end, int row0, int rows, int nblock, uint16_t* __restrict__ hout,
+    int kt_begin, int kt_end, int row0, int rows, int nblock, uint16_t* __restrict__ hout,
     float* __restrict__ oout, uint16_t (*xs)[kGemmTileM][kLdsStride])
 {
     const int tid = threadIdx.x;
@@ -300,26 +312,24 @@ __device__ __forceinline__ void gemm_tile(
     const int ln = lane & 31;
     const int kb = lane >> 5;
 
-    // strips of this wavefront
-    long n_a, n_b;
+    // strips of this wavefront (32-row tiles of the weight matrices)
+    long nt_a, nt_b;
     MatPtr ma, mb;
     bool strip_ok[2];
     if (MODE == 1) {
-        const int f0 = nblock * (32 * kGmWaves) + wave * 32;
-        n_a = n_b = f0 + ln;
+        nt_a = nt_b = (long)nblock * kGmWaves + wave;
         ma = mat_ptr(ex, 0, BITS);
         mb = mat_ptr(ex, 1, BITS);
-        strip_ok[0] = strip_ok[1] = f0 < N;
+        strip_ok[0] = strip_ok[1] = nt_a * 32 < N;
     } else {
-        const int j0 = nblock * (64 * kGmWaves) + wave * 64;
-        n_a = j0 + ln;
-        n_b = j0 + 32 + ln;
+        nt_a = ((long)nblock * kGmWaves + wave) * 2;
+        nt_b = nt_a + 1;
         ma = mb = mat_ptr(ex, 2, BITS);
-        strip_ok[0] = j0 < N;
-        strip_ok[1] = j0 + 32 < N;
+        strip_ok[0] = nt_a * 32 < N;
+        strip_ok[1] = nt_b * 32 < N;
     }
-    if (!strip_ok[0]) n_a = 0;
-    if (!strip_ok[1]) n_b = 0;
+    if (!strip_ok[0]) nt_a = 0;   // idle strips stream tile row 0; their results are dropped
+    if (!strip_ok[1]) nt_b = 0;
 
     float16_t acc[2][NTF];
 #pragma unroll
@@ -329,120 +339,161 @@ __device__ __forceinline__ void gemm_tile(
 #pragma unroll
             for (int i = 0; i < 16; i++) acc[s][tf][i] = 0.0f;
 
-    // staging role: thread -> (row, half) of the token tile
-    const int srow = tid >> 1;
-    const int shalf = tid & 1;
-    // tile rows past the expert's last token re-read its last token: their
-    // products are computed and dropped, and the loop stays branch-free
+    // staging role: thread -> (row, quarter) of the token tile.  Tile rows past
+    // the expert's last token re-read its last token: their products are
+    // computed and dropped, and the loop stays branch-free.
+    const int srow = tid >> 2;
+    const int sq = tid & 3;
     const int srow_c = min(srow, rows - 1);
     const uint16_t* src_row;
     if (MODE == 1) src_row = act + (long)(perm[row0 + srow_c] / k_route) * K;
     else src_row = act + (long)(row0 + srow_c) * K;
-    uint4 xv[8];
-    auto load_x = [&](int k0) {
+    src_row += 32 * sq;
+    uint4 xv[4];
+    auto load_x = [&](int kt) {
 #pragma unroll
-        for (int i = 0; i < 8; i++)
-            xv[i] = *reinterpret_cast<const uint4*>(src_row + k0 + 64 * shalf + 8 * i);
+        for (int i = 0; i < 4; i++) xv[i] = *reinterpret_cast<const uint4*>(src_row + kt * kBK + 8 * i);
     };
     auto store_x = [&](int buf) {
-        uint4* dst = reinterpret_cast<uint4*>(&xs[buf][srow][64 * shalf]);
-        if constexpr (BITS == 16) {
+        uint4* dst = reinterpret_cast<uint4*>(&xs[buf][srow][32 * sq]);
 #pragma unroll
-            for (int i = 0; i < 8; i++) dst[i] = xv[i];
-        } else if constexpr (BITS == 4) {
-#pragma unroll
-            for (int i = 0; i < 8; i++) dst[i] = perm8(xv[i]);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                uint4 o0, o1;
-                perm16(xv[2 * i], xv[2 * i + 1], o0, o1);
-                dst[2 * i] = o0;
-                dst[2 * i + 1] = o1;
-            }
-        }
+        for (int i = 0; i < 4; i++) dst[i] = xv[i];
     };
 
-    // Two register sets (0 / 1) take turns, so no value is ever copied from a
-    // "next" to a "current" register: a copy would have to wait for the loads
-    // it copies.  The scheduler fences keep the prefetch loads at the top of
-    // each half-step, ahead of the MFMA work that hides their latency.
-    StripRaw<BITS> ra0, rb0, ra1, rb1;
-    load_x(k_begin);
-    load_strip<BITS>(ma, n_a, kb, k_begin, K, ra0);
-    load_strip<BITS>(mb, n_b, kb, k_begin, K, rb0);
-    store_x(0);
-    __syncthreads();
-    for (int k0 = k_begin; k0 < k_end; k0 += 2 * kBK) {
-        // half-step A: prefetch block k0 + BK into set 1, multiply set 0 from LDS buffer 0
-        // (past the end the prefetch re-reads the last block instead of branching)
-        const int k1 = min(k0 + kBK, k_end - kBK);
-        load_x(k1);
-        load_strip<BITS>(ma, n_a, kb, k1, K, ra1);
-        load_strip<BITS>(mb, n_b, kb, k1, K, rb1);
-        __builtin_amdgcn_sched_barrier(0);
-        compute_kblock<BITS, NTF>(ra0, rb0, xs[0], ln, kb, acc);
-        __builtin_amdgcn_sched_barrier(0);
-        store_x(1);
-        __syncthreads();
-        if (k0 + kBK >= k_end) break;   // odd number of K-blocks
-        // half-step B: prefetch block k0 + 2 BK into set 0, multiply set 1 from LDS buffer 1
-        const int k2 = min(k0 + 2 * kBK, k_end - kBK);
-        load_x(k2);
-        load_strip<BITS>(ma, n_a, kb, k2, K, ra0);
-        load_strip<BITS>(mb, n_b, kb, k2, K, rb0);
-        __builtin_amdgcn_sched_barrier(0);
-        compute_kblock<BITS, NTF>(ra1, rb1, xs[1], ln, kb, acc);
-        __builtin_amdgcn_sched_barrier(0);
+    if constexpr (BITS == 16) {
+        // one register set: the next tile's weights are requested as soon as
+        // the MFMAs of the current one have been issued
+        StripRaw<16> ra, rb;
+        load_x(kt_begin);
+        load_strip<16>(ma, nt_a, kt_begin, K, lane, ra);
+        load_strip<16>(mb, nt_b, kt_begin, K, lane, rb);
         store_x(0);
         __syncthreads();
+        int buf = 0;
+        for (int kt = kt_begin; kt < kt_end; kt++) {
+            const int kn = min(kt + 1, kt_end - 1);
+            load_x(kn);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_ktile<16, NTF>(ra, rb, xs[buf], ln, kb, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            load_strip<16>(ma, nt_a, kn, K, lane, ra);
+            load_strip<16>(mb, nt_b, kn, K, lane, rb);
+            buf ^= 1;
+            store_x(buf);
+            __syncthreads();
+        }
+    } else {
+        // two register sets take turns, so the weights of tile kt+1 are in
+        // flight while tile kt is multiplied and no register is ever copied
+        StripRaw<BITS> ra0, rb0, ra1, rb1;
+        load_x(kt_begin);
+        load_strip<BITS>(ma, nt_a, kt_begin, K, lane, ra0);
+        load_strip<BITS>(mb, nt_b, kt_begin, K, lane, rb0);
+        store_x(0);
+        __syncthreads();
+        for (int kt = kt_begin; kt < kt_end; kt += 2) {
+            const int k1 = min(kt + 1, kt_end - 1);
+            load_x(k1);
+            load_strip<BITS>(ma, nt_a, k1, K, lane, ra1);
+            load_strip<BITS>(mb, nt_b, k1, K, lane, rb1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_ktile<BITS, NTF>(ra0, rb0, xs[0], ln, kb, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            store_x(1);
+            __syncthreads();
+            if (kt + 1 >= kt_end) break;   // odd number of K-tiles
+            const int k2 = min(kt + 2, kt_end - 1);
+            load_x(k2);
+            load_strip<BITS>(ma, nt_a, k2, K, lane, ra0);
+            load_strip<BITS>(mb, nt_b, k2, K, lane, rb0);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_ktile<BITS, NTF>(ra1, rb1, xs[1], ln, kb, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            store_x(0);
+            __syncthreads();
+        }
     }
 
     // epilogue.  D layout: lane (ln, kb), register i -> weight row 8*(i/4) + 4*kb + i%4, token ln
 #pragma unroll
     for (int tf = 0; tf < NTF; tf++) {
         const int trow = 32 * tf + ln;
-        if (trow < rows) {
-            if (MODE == 1) {
-                if (strip_ok[0]) {
-                    const int f0 = nblock * (32 * kGmWaves) + wave * 32;
-                    uint16_t* dst = hout + (long)(row0 + trow) * N + f0 + 4 * kb;
+        const bool row_ok = trow < rows;
+        if (MODE == 1) {
+            // SwiGLU; the 16-bit intermediate is written in the column order the
+            // down projection of this expert reads (see perm8 / perm16)
+            const long f0 = nt_a * 32;
+            uint16_t* dst = hout + (long)(row0 + min(trow, rows - 1)) * N + f0;
+            uint32_t pk[4][2];
 #pragma unroll
-                    for (int g = 0; g < 4; g++) {
-                        float hv[4];
+            for (int g = 0; g < 4; g++) {
+                float hv[4];
 #pragma unroll
-                        for (int i = 0; i < 4; i++) {
-                            const float a = acc[0][tf][4 * g + i];
-                            const float u = acc[1][tf][4 * g + i];
-                            hv[i] = a * __builtin_amdgcn_rcpf(1.0f + __expf(-a)) * u;
-                        }
-                        uint2 pk;
-                        if (BITS == 16) {
-                            pk.x = f32_to_bf16_bits(hv[0]) | (f32_to_bf16_bits(hv[1]) << 16);
-                            pk.y = f32_to_bf16_bits(hv[2]) | (f32_to_bf16_bits(hv[3]) << 16);
-                        } else {
-                            pk.x = pack_half2(hv[0], hv[1]);
-                            pk.y = pack_half2(hv[2], hv[3]);
-                        }
-                        *reinterpret_cast<uint2*>(dst + 8 * g) = pk;
-                    }
+                for (int i = 0; i < 4; i++) {
+                    const float a = acc[0][tf][4 * g + i];
+                    const float u = acc[1][tf][4 * g + i];
+                    hv[i] = a * __builtin_amdgcn_rcpf(1.0f + __expf(-a)) * u;
+                }
+                if constexpr (BITS == 16) {
+                    pk[g][0] = f32_to_bf16_bits(hv[0]) | (f32_to_bf16_bits(hv[1]) << 16);
+                    pk[g][1] = f32_to_bf16_bits(hv[2]) | (f32_to_bf16_bits(hv[3]) << 16);
+                } else {
+                    pk[g][0] = pack_half2(hv[0], hv[1]);
+                    pk[g][1] = pack_half2(hv[2], hv[3]);
+                }
+            }
+            if constexpr (BITS == 16) {
+                // features f0 + 8g + 4kb .. +4, natural order
+                if (row_ok && strip_ok[0]) {
+#pragma unroll
+                    for (int g = 0; g < 4; g++)
+                        *reinterpret_cast<uint2*>(dst + 8 * g + 4 * kb) = make_uint2(pk[g][0], pk[g][1]);
+                }
+            } else if constexpr (BITS == 4) {
+                // group of 8 features e0..e7: this lane holds e(4kb..4kb+3); stored order is
+                // e0,e4,e1,e5 | e2,e6,e3,e7: the two kb lanes trade one packed pair
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    const uint32_t send = kb ? pk[g][0] : pk[g][1];          // kb0 gives (e2,e3), kb1 gives (e4,e5)
+                    const uint32_t got = (uint32_t)__shfl_xor((int)send, 32, kWave);
+                    const uint32_t lo = kb ? got : pk[g][0];                 // kb0: (e0,e1)  kb1: (e2,e3)
+                    const uint32_t hi = kb ? pk[g][1] : got;                 // kb0: (e4,e5)  kb1: (e6,e7)
+                    const uint32_t o0 = (lo & 0xffffu) | (hi << 16);
+                    const uint32_t o1 = (lo >> 16) | (hi & 0xffff0000u);
+                    if (row_ok && strip_ok[0])
+                        *reinterpret_cast<uint2*>(dst + 8 * g + 4 * kb) = make_uint2(o0, o1);
                 }
             } else {
-                const int pair = perm[row0 + trow];
+                // group of 16 features = register groups (g, g+1), g even: this lane holds
+                // e(4kb+i) and e(8+4kb+i); stored order interleaves them at 8kb .. 8kb+7
+                if (row_ok && strip_ok[0]) {
 #pragma unroll
-                for (int s = 0; s < 2; s++) {
-                    if (strip_ok[s]) {
-                        const int j0 = nblock * (64 * kGmWaves) + wave * 64 + 32 * s;
-                        float* dst = oout + (long)pair * N + j0 + 4 * kb;
+                    for (int g = 0; g < 4; g += 2) {
+                        const uint32_t a01 = pk[g][0], a23 = pk[g][1], b01 = pk[g + 1][0], b23 = pk[g + 1][1];
+                        uint4 o;
+                        o.x = (a01 & 0xffffu) | (b01 << 16);
+                        o.y = (a01 >> 16) | (b01 & 0xffff0000u);
+                        o.z = (a23 & 0xffffu) | (b23 << 16);
+                        o.w = (a23 >> 16) | (b23 & 0xffff0000u);
+                        *reinterpret_cast<uint4*>(dst + 8 * g + 8 * kb) = o;
+                    }
+                }
+            }
+        } else if (row_ok) {
+            const int pair = perm[row0 + trow];
 #pragma unroll
-                        for (int g = 0; g < 4; g++) {
-                            float4 o;
-                            o.x = acc[s][tf][4 * g + 0];
-                            o.y = acc[s][tf][4 * g + 1];
-                            o.z = acc[s][tf][4 * g + 2];
-                            o.w = acc[s][tf][4 * g + 3];
-                            *reinterpret_cast<float4*>(dst + 8 * g) = o;
-                        }
+            for (int s = 0; s < 2; s++) {
+                if (strip_ok[s]) {
+                    const long j0 = (s ? nt_b : nt_a) * 32;
+                    float* dst = oout + (long)pair * N + j0 + 4 * kb;
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        float4 o;
+                        o.x = acc[s][tf][4 * g + 0];
+                        o.y = acc[s][tf][4 * g + 1];
+                        o.z = acc[s][tf][4 * g + 2];
+                        o.w = acc[s][tf][4 * g + 3];
+                        *reinterpret_cast<float4*>(dst + 8 * g) = o;
                     }
                 }
             }
@@ -452,10 +503,11 @@ __device__ __forceinline__ void gemm_tile(
 
 template <int MODE>
 __global__ __launch_bounds__(kGmThreads) void gemm_kernel(
-    const uint16_t* __restrict__ x_bf16, const uint16_t* __restrict__ x_f16,
-    const uint16_t* __restrict__ hbuf_in, const uint8_t* __restrict__ bits,
-    const dymoe_expert_fmt* __restrict__ table, const int32_t* __restrict__ plan, int P, int E,
-    int k_route, int H, int F, uint16_t* __restrict__ hbuf_out, float* __restrict__ opair)
+    const uint16_t* __restrict__ x_bf16, const uint16_t* __restrict__ x_h4,
+    const uint16_t* __restrict__ x_h2, const uint16_t* __restrict__ hbuf_in,
+    const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table,
+    const int32_t* __restrict__ plan, int P, int E, int k_route, int H, int F,
+    uint16_t* __restrict__ hbuf_out, float* __restrict__ opair)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t xs_raw[];
     uint16_t (*xs)[kGemmTileM][kLdsStride] = reinterpret_cast<uint16_t (*)[kGemmTileM][kLdsStride]>(xs_raw);
@@ -469,28 +521,30 @@ __global__ __launch_bounds__(kGmThreads) void gemm_kernel(
     const dymoe_expert_fmt ex = table[e];
     const int K = (MODE == 1) ? H : F;
     const int N = (MODE == 1) ? F : H;
-    // split-K (MODE 2 only): blockIdx.z takes K-blocks [z*per, (z+1)*per) and its own output slab
-    const int nkb = K / kBK;
-    const int per = (nkb + (int)gridDim.z - 1) / (int)gridDim.z;
-    const int k_begin = (int)blockIdx.z * per * kBK;
-    const int k_end = min(K, k_begin + per * kBK);
+    // split-K (MODE 2 only): blockIdx.z takes K-tiles [z*per, (z+1)*per) and its own output slab
+    const int nkt = K / kBK;
+    const int per = (nkt + (int)gridDim.z - 1) / (int)gridDim.z;
+    const int kt_begin = (int)blockIdx.z * per;
+    const int kt_end = min(nkt, kt_begin + per);
     float* oz = opair + (size_t)blockIdx.z * (size_t)P * (size_t)N;
-    if (k_begin >= k_end) {
-        // a split with no K-blocks still owns its slab: write zeros
+    if (kt_begin >= kt_end) {
+        // a split with no K-tiles still owns its slab: write zeros
         if (MODE == 2) {
-            for (int i = threadIdx.x; i < rows * 64; i += kGmThreads) {
-                const int r = i >> 6, c = (blockIdx.x * 64 + (i & 63)) * 4;
-                if (c < N) *reinterpret_cast<float4*>(oz + (size_t)pp.perm[row0 + r] * N + c) = make_float4(0.f, 0.f, 0.f, 0.f);
+            const int cols = 64 * kGmWaves;     // columns of this workgroup
+            for (int i = threadIdx.x; i < rows * (cols / 4); i += kGmThreads) {
+                const int r = i / (cols / 4), c = blockIdx.x * cols + (i % (cols / 4)) * 4;
+                if (c < N)
+                    *reinterpret_cast<float4*>(oz + (size_t)pp.perm[row0 + r] * N + c) = make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
         return;
     }
-    const uint16_t* act = (MODE != 1) ? hbuf_in : (b == 16 ? x_bf16 : x_f16);
+    const uint16_t* act = (MODE != 1) ? hbuf_in : (b == 16 ? x_bf16 : (b == 4 ? x_h4 : x_h2));
     const int ntf = (rows + 31) >> 5;
     // one instantiation per (precision, number of 32-token fragments): the
     // accumulators then sit in fixed registers for the whole K loop
 #define DYMOE_TILE(BITS_, NTF_)                                                                      \
-    gemm_tile<MODE, BITS_, NTF_>(act, pp.perm, k_route, ex, K, N, k_begin, k_end, row0, rows,        \
+    gemm_tile<MODE, BITS_, NTF_>(act, pp.perm, k_route, ex, K, N, kt_begin, kt_end, row0, rows,      \
                                  blockIdx.x, hbuf_out, oz, xs)
 #define DYMOE_TILE_NTF(BITS_)                     \
     switch (ntf) {                                \
@@ -510,7 +564,7 @@ __global__ __launch_bounds__(kGmThreads) void gemm_kernel(
 #undef DYMOE_TILE
 }
 
-// y[t,j] = sum_slot w[t,slot] * o[pair,j]  (pairs of skipped experts omitted)
+// y[t,j] = sum_slot w[t,slot] * (sum over K splits of o[z,pair,j])  (pairs of skipped experts omitted)
 __global__ __launch_bounds__(256) void gemm_combine_kernel(
     const float* __restrict__ opair, const int32_t* __restrict__ idx, const float* __restrict__ w,
     const uint8_t* __restrict__ bits, int T, int H, int E, int k, int splits, int out_dtype,
@@ -557,17 +611,16 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const int P = T * k;
     char* ws = (char*)workspace;
     uint16_t* hbuf = reinterpret_cast<uint16_t*>(ws + L.hbuf);   // [P,F] 16-bit
-    uint16_t* xh = reinterpret_cast<uint16_t*>(ws + L.xh);       // [T,H] fp16 copy of x
+    uint16_t* xh4 = reinterpret_cast<uint16_t*>(ws + L.xh);      // [T,H] fp16, int4 column order
+    uint16_t* xh2 = xh4 + round256((size_t)T * H * 2) / 2;       // [T,H] fp16, int2 column order
     float* opair = reinterpret_cast<float*>(ws + L.part);
     int32_t* plan = reinterpret_cast<int32_t*>(ws + L.plan);
     const uint16_t* xb = (const uint16_t*)x;
 
-    {
-        dymoe_launch(ctx, DYMOE_K_PLAN, plan_kernel, dim3(1), dim3(1024), 0, st, idx, bits, P, E, kGemmTileM, plan);
-    }
+    dymoe_launch(ctx, DYMOE_K_PLAN, plan_kernel, dim3(1), dim3(1024), 0, st, idx, bits, P, E, kGemmTileM, plan);
     DYMOE_HIP_LAUNCH_CHECK();
-    const long n8 = (long)T * H / 8;
-    hipLaunchKernelGGL(to_f16_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st, xb, n8, xh);
+    const long n16 = (long)T * H / 16;
+    hipLaunchKernelGGL(prep_x_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, xb, n16, xh4, xh2);
     DYMOE_HIP_LAUNCH_CHECK();
     // two token-tile buffers in LDS: more than the 64 KiB a kernel gets by default
     constexpr size_t kLdsBytes = 2 * sizeof(uint16_t) * kGemmTileM * kLdsStride;
@@ -581,27 +634,28 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
         lds_attr_set = true;
     }
     const int max_tiles = P / kGemmTileM + E;
-    const dim3 g1((unsigned)((F + 127) / 128), (unsigned)max_tiles);
-    dymoe_launch(ctx, DYMOE_K_GEMM1, (gemm_kernel<1>), g1, dim3(kGmThreads), kLdsBytes, st, xb, xh,
+    const int cols1 = 32 * kGmWaves, cols2 = 64 * kGmWaves;
+    const dim3 g1((unsigned)((F + cols1 - 1) / cols1), (unsigned)max_tiles);
+    dymoe_launch(ctx, DYMOE_K_GEMM1, (gemm_kernel<1>), g1, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2,
                  (const uint16_t*)nullptr, bits, table, plan, P, E, k, H, F, hbuf, (float*)nullptr);
     DYMOE_HIP_LAUNCH_CHECK();
-    // The down projection has few output tiles (H/256 per token tile): split K so
-    // that the launch still covers the chip.  Each split writes its own slab of
-    // per-pair outputs; the combine kernel adds the slabs in a fixed order.
-    const int nblk2 = (H + 255) / 256;
+    // The down projection has few output tiles: split K so that the launch
+    // still covers the chip.  Each split writes its own slab of per-pair
+    // outputs; the combine kernel adds the slabs in a fixed order.
+    const int nblk2 = (H + cols2 - 1) / cols2;
     const long est_blocks = (long)nblk2 * ((long)P / kGemmTileM + (E < P ? E : P) / 2 + 1);
     int splits = (int)((2L * ctx->num_cu + est_blocks - 1) / est_blocks);
     const int max_splits = (F + kSeg - 1) / kSeg;     // slabs the workspace holds
     if (splits > max_splits) splits = max_splits;
-    if (splits > 4) splits = 4;
+    if (splits > 8) splits = 8;
     if (splits < 1) splits = 1;
     const dim3 g2((unsigned)nblk2, (unsigned)max_tiles, (unsigned)splits);
-    dymoe_launch(ctx, DYMOE_K_GEMM2, (gemm_kernel<2>), g2, dim3(kGmThreads), kLdsBytes, st, xb, xh, hbuf,
+    dymoe_launch(ctx, DYMOE_K_GEMM2, (gemm_kernel<2>), g2, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2, hbuf,
                  bits, table, plan, P, E, k, H, F, (uint16_t*)nullptr, opair);
     DYMOE_HIP_LAUNCH_CHECK();
     const long n4 = (long)T * (H / 4);
     dymoe_launch(ctx, DYMOE_K_GEMM_COMBINE, gemm_combine_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, opair,
-                       idx, w, bits, T, H, E, k, splits, out_dtype, y);
+                 idx, w, bits, T, H, E, k, splits, out_dtype, y);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }

@@ -111,6 +111,101 @@ __global__ __launch_bounds__(kQThreads) void quantize_pack_kernel(
     else quantize_block<2>(w, n_elems, codes, scale, zero, blockIdx.x);
 }
 
+// Tile-layout variant: a lane owns a whole group (row 32*nt + r, columns
+// 128*kt + 64*kb .. +64 of tile (nt, kt), lane l = 32*kb + r): eight 16-byte
+// loads from the row-major bf16 matrix, no cross-lane step, and the codes,
+// scale and zero go to the lane's slots of the tile.  One wavefront per tile.
+template <int BITS>
+__device__ __forceinline__ void quantize_tile(const uint16_t* __restrict__ w, long K, long tile,
+                                              uint8_t* __restrict__ codes,
+                                              uint16_t* __restrict__ scale,
+                                              uint16_t* __restrict__ zero)
+{
+#pragma clang fp contract(off)
+    constexpr int qmax = (1 << BITS) - 1;
+    constexpr float kMagic = 12582912.0f;          // 1.5 * 2^23
+    constexpr int kMagicBits = 0x4B400000;
+    const int lane = threadIdx.x & (kWave - 1);
+    const long KT = K >> 7;
+    const long nt = tile / KT;
+    const long kt = tile - nt * KT;
+    const long row = nt * 32 + (lane & 31);
+    const long col = kt * 128 + 64 * (lane >> 5);
+    const uint4* src = reinterpret_cast<const uint4*>(w + row * K + col);
+    uint4 raw[8];
+#pragma unroll
+    for (int c = 0; c < 8; c++) raw[c] = src[c];
+    float v[64];
+#pragma unroll
+    for (int c = 0; c < 8; c++) unpack8(raw[c], v + 8 * c);
+    float lo = v[0], hi = v[0];
+#pragma unroll
+    for (int i = 1; i < 64; i++) {
+        lo = fminf(lo, v[i]);
+        hi = fmaxf(hi, v[i]);
+    }
+    const _Float16 zh = (_Float16)lo;                 // round to nearest even
+    const float range = hi - lo;
+    const float step = range / (float)qmax;           // correctly rounded division
+    const _Float16 sh = (_Float16)step;
+    const float m = (float)zh;
+    const float s = (float)sh;
+    const float inv = (s > 0.0f) ? (1.0f / s) : 0.0f;
+    constexpr int kWords = 2 * BITS;                  // 64 codes: 8 words (int4) or 4 words (int2)
+    uint32_t words[kWords];
+#pragma unroll
+    for (int wd = 0; wd < kWords; wd++) {
+        constexpr int per_word = 32 / BITS;
+        uint32_t bytes[4];
+#pragma unroll
+        for (int b = 0; b < 4; b++) {
+            constexpr int per_byte = 8 / BITS;
+            uint32_t acc = 0;
+#pragma unroll
+            for (int j = per_byte - 1; j >= 0; j--) {
+                const int i = wd * per_word + b * per_byte + j;
+                const float d = v[i] - m;
+                const float t = d * inv;
+                const float r = t + kMagic;
+                int q = __float_as_int(r);
+                q = min(max(q, kMagicBits), kMagicBits + qmax);
+                acc = (j == per_byte - 1) ? (uint32_t)q : ((acc << BITS) | (uint32_t)q);
+            }
+            bytes[b] = acc;
+        }
+        const uint32_t lo16 = __builtin_amdgcn_perm(bytes[1], bytes[0], 0x0c0c0400u);
+        const uint32_t hi16 = __builtin_amdgcn_perm(bytes[3], bytes[2], 0x04000c0cu);
+        words[wd] = lo16 | hi16;
+    }
+    if constexpr (BITS == 4) {
+        uint8_t* dst = codes + tile * 2048 + lane * 16;
+        *reinterpret_cast<uint4*>(dst) = make_uint4(words[0], words[1], words[2], words[3]);
+        *reinterpret_cast<uint4*>(dst + 1024) = make_uint4(words[4], words[5], words[6], words[7]);
+    } else {
+        *reinterpret_cast<uint4*>(codes + tile * 1024 + lane * 16) =
+            make_uint4(words[0], words[1], words[2], words[3]);
+    }
+    scale[tile * 64 + lane] = (uint16_t)f16_bits(sh);
+    zero[tile * 64 + lane] = (uint16_t)f16_bits(zh);
+}
+
+// bf16 row-major -> bf16 tiles: thread = (tile, chunk j, lane)
+__global__ __launch_bounds__(256) void pack_tiles_kernel(const uint16_t* __restrict__ w, long N,
+                                                         long K, uint16_t* __restrict__ tiles)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;     // one 16-byte chunk of the output
+    if (i >= N * K / 8) return;
+    const long tile = i >> 9;                                  // 512 chunks per tile
+    const int j = (int)((i >> 6) & 7);
+    const int lane = (int)(i & 63);
+    const long KT = K >> 7;
+    const long nt = tile / KT;
+    const long kt = tile - nt * KT;
+    const long row = nt * 32 + (lane & 31);
+    const long col = kt * 128 + 64 * (lane >> 5) + 8 * j;
+    reinterpret_cast<uint4*>(tiles)[i] = *reinterpret_cast<const uint4*>(w + row * K + col);
+}
+
 // Worklist of a layer: the experts whose assigned width is 4 or 2 bits (and
 // that have load, when load is given).  list[0] = count, list[1..] = experts.
 __global__ __launch_bounds__(DYMOE_MAX_EXPERTS) void quantize_worklist_kernel(
@@ -135,12 +230,15 @@ __global__ __launch_bounds__(DYMOE_MAX_EXPERTS) void quantize_worklist_kernel(
 // A fixed-size grid walks (expert of the worklist, matrix, block) units, so no
 // workgroup is launched for experts that need nothing and the precision
 // decision never goes through the host.
+template <int LAYOUT>
 __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
     const dymoe_expert_fmt* __restrict__ table, const uint8_t* __restrict__ bits,
     const int32_t* __restrict__ list, int H, int F)
 {
     const long n_elems = (long)H * (long)F;
-    const long bpm = (n_elems + kQElemsPerBlock - 1) / kQElemsPerBlock;   // blocks per matrix
+    // row-major: 8192 elements per block; tiles: 4 tiles (one per wavefront) = 16384 elements
+    constexpr long kPerBlock = (LAYOUT == DYMOE_LAYOUT_TILE) ? 4 * 4096 : kQElemsPerBlock;
+    const long bpm = (n_elems + kPerBlock - 1) / kPerBlock;               // blocks per matrix
     const long units = (long)list[0] * 3 * bpm;
     for (long u = blockIdx.x; u < units; u += gridDim.x) {
         const long item = u / bpm;
@@ -150,12 +248,20 @@ __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
         const int b = bits[e];
         const dymoe_expert_fmt* ex = table + e;
         const uint16_t* w = reinterpret_cast<const uint16_t*>(ex->w[mat]);
-        if (b == 4)
-            quantize_block<4>(w, n_elems, ex->q4[mat], reinterpret_cast<uint16_t*>(ex->s4[mat]),
-                              reinterpret_cast<uint16_t*>(ex->z4[mat]), blk);
-        else
-            quantize_block<2>(w, n_elems, ex->q2[mat], reinterpret_cast<uint16_t*>(ex->s2[mat]),
-                              reinterpret_cast<uint16_t*>(ex->z2[mat]), blk);
+        uint8_t* q = (b == 4) ? ex->q4[mat] : ex->q2[mat];
+        uint16_t* sc = reinterpret_cast<uint16_t*>((b == 4) ? ex->s4[mat] : ex->s2[mat]);
+        uint16_t* zr = reinterpret_cast<uint16_t*>((b == 4) ? ex->z4[mat] : ex->z2[mat]);
+        if constexpr (LAYOUT == DYMOE_LAYOUT_TILE) {
+            const long K = (mat == 2) ? F : H;
+            const long tile = blk * 4 + (threadIdx.x >> 6);
+            if (tile * 4096 < n_elems) {
+                if (b == 4) quantize_tile<4>(w, K, tile, q, sc, zr);
+                else quantize_tile<2>(w, K, tile, q, sc, zr);
+            }
+        } else {
+            if (b == 4) quantize_block<4>(w, n_elems, q, sc, zr, blk);
+            else quantize_block<2>(w, n_elems, q, sc, zr, blk);
+        }
     }
 }
 
@@ -186,11 +292,14 @@ int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits,
 }
 
 int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const uint8_t* bits,
-                           const int32_t* load, int E, int H, int F, int group, void* stream)
+                           const int32_t* load, int E, int H, int F, int group, int layout,
+                           void* stream)
 {
     DYMOE_REQUIRE(table && bits);
     DYMOE_REQUIRE(E > 0 && H > 0 && F > 0);
     DYMOE_REQUIRE(group > 0 && H % group == 0 && F % group == 0);
+    DYMOE_REQUIRE(layout == DYMOE_LAYOUT_ROWMAJOR || layout == DYMOE_LAYOUT_TILE);
+    if (layout == DYMOE_LAYOUT_TILE) DYMOE_REQUIRE(H % 128 == 0 && F % 128 == 0);
     if (group != 64 || E > DYMOE_MAX_EXPERTS) return DYMOE_ENOTSUP;
     if (!ctx) return DYMOE_ENOCTX;
     hipStream_t st = (hipStream_t)stream;
@@ -199,12 +308,33 @@ int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const 
                        0, st, bits, load, E, list);
     DYMOE_HIP_LAUNCH_CHECK();
     const long n_elems = (long)H * (long)F;
-    const long bpm = (n_elems + dymoe::kQElemsPerBlock - 1) / dymoe::kQElemsPerBlock;
+    const long per_block = (layout == DYMOE_LAYOUT_TILE) ? 4 * 4096 : dymoe::kQElemsPerBlock;
+    const long bpm = (n_elems + per_block - 1) / per_block;
     long grid = 3L * E * bpm;
     const long cap = (long)ctx->num_cu * 32;   // enough resident workgroups to fill the chip; the rest loops
     if (grid > cap) grid = cap;
-    dymoe_launch(ctx, DYMOE_K_QUANTIZE, dymoe::quantize_experts_kernel, dim3((unsigned)grid), dim3(dymoe::kQThreads), 0,
-                       st, table, bits, list, H, F);
+    if (layout == DYMOE_LAYOUT_TILE)
+        dymoe_launch(ctx, DYMOE_K_QUANTIZE, dymoe::quantize_experts_kernel<DYMOE_LAYOUT_TILE>,
+                     dim3((unsigned)grid), dim3(dymoe::kQThreads), 0, st, table, bits, list, H, F);
+    else
+        dymoe_launch(ctx, DYMOE_K_QUANTIZE, dymoe::quantize_experts_kernel<DYMOE_LAYOUT_ROWMAJOR>,
+                     dim3((unsigned)grid), dim3(dymoe::kQThreads), 0, st, table, bits, list, H, F);
+    DYMOE_HIP_LAUNCH_CHECK();
+    return DYMOE_OK;
+}
+
+int dymoe_pack_tiles(dymoe_ctx* ctx, const void* w, long N, long K, void* tiles, void* stream)
+{
+    DYMOE_REQUIRE(N >= 0 && K > 0 && N % 32 == 0 && K % 128 == 0);
+    if (N == 0) return ctx ? DYMOE_OK : DYMOE_ENOCTX;
+    DYMOE_REQUIRE(w && tiles && w != tiles);
+    DYMOE_REQUIRE(dymoe_aligned(w, 16) && dymoe_aligned(tiles, 16));
+    if (!ctx) return DYMOE_ENOCTX;
+    const long chunks = N * K / 8;
+    const long blocks = (chunks + 255) / 256;
+    if (blocks > 0x7fffffffL) return DYMOE_ENOTSUP;
+    hipLaunchKernelGGL(dymoe::pack_tiles_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                       (hipStream_t)stream, (const uint16_t*)w, N, K, (uint16_t*)tiles);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }

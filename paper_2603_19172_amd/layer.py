@@ -16,23 +16,29 @@ class ExpertStore:
     output buffers for the int4 and int2 formats, and the dymoe_expert_fmt table
     that points at them."""
 
-    def __init__(self, w_bf16, H, F, device, group=64):
-        # w_bf16: list over experts of [W1 [F,H], W3 [F,H], W2 [H,F]] bf16 tensors on `device`
+    def __init__(self, w_bf16, H, F, device, group=64, ctx=None, w_tiles=None):
+        # w_bf16: list over experts of [W1 [F,H], W3 [F,H], W2 [H,F]] bf16 tensors on `device`.
+        # With a context, a tile-layout copy of the bf16 weights is made for the GEMM path.
         self.E = len(w_bf16)
         self.H, self.F = H, F
         self.w = w_bf16
+        self.wt = w_tiles
+        if self.wt is None and ctx is not None and H % 128 == 0 and F % 128 == 0:
+            self.wt = [[ctx.pack_tiles(m) for m in ex] for ex in w_bf16]
         self.q = {}
         for b in (4, 2):
             self.q[b] = [[(torch.empty((n, k * b // 8), dtype=torch.uint8, device=device),
                            torch.empty((n, k // group), dtype=torch.float16, device=device),
                            torch.empty((n, k // group), dtype=torch.float16, device=device))
                           for n, k in ((F, H), (F, H), (H, F))] for _ in range(self.E)]
-        experts = [{"w": self.w[e], "q4": self.q[4][e], "q2": self.q[2][e]} for e in range(self.E)]
+        experts = [{"w": self.w[e], "wt": self.wt[e] if self.wt is not None else None,
+                    "q4": self.q[4][e], "q2": self.q[2][e]} for e in range(self.E)]
         self.table, self._keep = B.make_expert_table(experts, device)
 
     def clone(self):
+        wt = [[m.clone() for m in ex] for ex in self.wt] if self.wt is not None else None
         return ExpertStore([[m.clone() for m in ex] for ex in self.w], self.H, self.F,
-                           self.table.device)
+                           self.table.device, w_tiles=wt)
 
 
 class MoELayer:
@@ -55,6 +61,9 @@ class MoELayer:
         self.bits = torch.empty((E,), dtype=torch.uint8, device=dev)
         self.rank = torch.empty((E,), dtype=torch.int32, device=dev)
         self.y = torch.empty((T, H), dtype=torch.bfloat16 if out_dtype == B.OUT_BF16 else torch.float32, device=dev)
+        # the FFN path and the layout of the packed weights go together
+        gemm = path == B.PATH_GEMM or (path == B.PATH_AUTO and T > 4 and H % 128 == 0 and F % 128 == 0)
+        self.layout = B.LAYOUT_TILE if gemm else B.LAYOUT_ROWMAJOR
         self.ws_bytes = B.workspace_bytes(T, H, F, E, k)
         self.ws = torch.empty((self.ws_bytes,), dtype=torch.uint8, device=dev)
 
@@ -84,7 +93,7 @@ class MoELayer:
     def quantize(self, store, st):
         B._check(B.lib.dymoe_quantize_experts(self.ctx._h, store.table.data_ptr(), self.bits.data_ptr(),
                                               self.load.data_ptr(), self.E, self.H, self.F, self.group,
-                                              st), "dymoe_quantize_experts")
+                                              self.layout, st), "dymoe_quantize_experts")
 
     def ffn(self, x, store, st):
         B._check(B.lib.dymoe_moe_ffn_mixed(self.ctx._h, x.data_ptr(), self.idx.data_ptr(),

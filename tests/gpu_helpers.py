@@ -40,6 +40,40 @@ def empty_q(F, H, bits):
     return out
 
 
+def tiles_from_rowmajor(codes, scale, zero, bits):
+    """Row-major packed matrix -> the library's 32x128 tile layout (a pure
+    permutation of bytes; see include/dymoe.h)."""
+    N = codes.shape[0]
+    K = codes.shape[1] * 8 // bits
+    NT, KT = N // 32, K // 128
+    if bits == 4:     # row bytes: (kt, kb, c, 16) -> tile (c, kb, r, 16)
+        t = codes.reshape(NT, 32, KT, 2, 2, 16).transpose(0, 2, 4, 3, 1, 5)
+    else:             # row bytes: (kt, kb, 16) -> tile (kb, r, 16)
+        t = codes.reshape(NT, 32, KT, 2, 16).transpose(0, 2, 3, 1, 4)
+    sz = lambda a: np.ascontiguousarray(a.reshape(NT, 32, KT, 2).transpose(0, 2, 3, 1)).reshape(N, K // 64)
+    return np.ascontiguousarray(t).reshape(codes.shape), sz(scale), sz(zero)
+
+
+def rowmajor_from_tiles(codes, scale, zero, bits):
+    N = codes.shape[0]
+    K = codes.shape[1] * 8 // bits
+    NT, KT = N // 32, K // 128
+    if bits == 4:
+        t = codes.reshape(NT, KT, 2, 2, 32, 16).transpose(0, 4, 1, 3, 2, 5)
+    else:
+        t = codes.reshape(NT, KT, 2, 32, 16).transpose(0, 3, 1, 2, 4)
+    sz = lambda a: np.ascontiguousarray(a.reshape(NT, KT, 2, 32).transpose(0, 3, 1, 2)).reshape(N, K // 64)
+    return np.ascontiguousarray(t).reshape(codes.shape), sz(scale), sz(zero)
+
+
+def bf16_tiles_from_rowmajor(w):
+    """bf16 bit patterns [N,K] -> tile layout: row elements (kt, kb, j, 8) -> tile (j, kb, r, 8)."""
+    N, K = w.shape
+    NT, KT = N // 32, K // 128
+    t = w.reshape(NT, 32, KT, 2, 8, 8).transpose(0, 2, 4, 3, 1, 5)
+    return np.ascontiguousarray(t).reshape(N, K)
+
+
 def rel_err_per_token(y: np.ndarray, ref: np.ndarray) -> float:
     """max over tokens of max_j |y - ref| / rms_j(ref[t])."""
     rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))

@@ -8,8 +8,10 @@ import torch
 from oracle import dymoe_oracle as O
 from paper_2603_19172_amd import binding as B
 from paper_2603_19172_amd import synth
-from gpu_helpers import (DEV, bits_of, empty_q, margin_ok, oracle_quantize_expert,
-                         rel_err_per_token, to_bf16, to_f16, upload_q)
+from gpu_helpers import (DEV, bf16_tiles_from_rowmajor, bits_of, empty_q, margin_ok,
+                         oracle_quantize_expert, rel_err_per_token, rowmajor_from_tiles,
+                         tiles_from_rowmajor, to_bf16, to_f16, upload_q)
+from paper_2603_19172_amd.layer import ExpertStore, MoELayer
 
 pytestmark = pytest.mark.gpu
 
@@ -73,7 +75,8 @@ def test_quantize_pack_empty_and_deterministic(ctx):
     assert all(torch.equal(x, y) for x, y in zip(a, b))
 
 
-def test_quantize_experts_follows_device_bits(ctx):
+@pytest.mark.parametrize("layout", [B.LAYOUT_ROWMAJOR, B.LAYOUT_TILE])
+def test_quantize_experts_follows_device_bits(ctx, layout):
     cfg = synth.CONFIGS["tiny"]
     E, H, F = 4, cfg.H, cfg.F
     mats = [synth.expert_weights(cfg, e) for e in range(E)]
@@ -86,18 +89,46 @@ def test_quantize_experts_follows_device_bits(ctx):
     table, keep = B.make_expert_table(experts, DEV)
     bits = torch.tensor([4, 16, 2, 4], dtype=torch.uint8, device=DEV)
     load = torch.tensor([3, 5, 1, 0], dtype=torch.int32, device=DEV)
-    ctx.quantize_experts(table, bits, load, E, H, F)
+    ctx.quantize_experts(table, bits, load, E, H, F, layout=layout)
     sync()
     for e, b in ((0, 4), (2, 2)):
         for i in range(3):
             rc, rs, rz = O.quantize_pack(mats[e][i], b)
             cd, sc, zr = experts[e]["q%d" % b][i]
-            assert np.array_equal(cd.cpu().numpy(), rc)
-            assert np.array_equal(bits_of(sc), rs) and np.array_equal(bits_of(zr), rz)
+            got = (cd.cpu().numpy(), bits_of(sc), bits_of(zr))
+            if layout == B.LAYOUT_TILE:      # same bytes, tile order: undo the permutation
+                got = rowmajor_from_tiles(*got, b)
+            assert np.array_equal(got[0], rc)
+            assert np.array_equal(got[1], rs) and np.array_equal(got[2], rz)
     # untouched: 16-bit expert, the unselected precision, and the expert with no load
     for e, b in ((1, 4), (1, 2), (0, 2), (2, 4), (3, 4), (3, 2)):
         for cd, sc, zr in experts[e]["q%d" % b]:
             assert (cd == 0xAB).all() and (sc == -1.0).all()
+
+
+def test_tile_layout_helpers_and_pack_tiles(ctx):
+    rng = np.random.default_rng(3)
+    for bits in (4, 2):
+        cd = rng.integers(0, 256, (64, 256 * bits // 8), dtype=np.uint8)
+        sc = rng.integers(0, 65536, (64, 4), dtype=np.uint16)
+        zr = rng.integers(0, 65536, (64, 4), dtype=np.uint16)
+        t = tiles_from_rowmajor(cd, sc, zr, bits)
+        back = rowmajor_from_tiles(*t, bits)
+        assert all(np.array_equal(a, b) for a, b in zip(back, (cd, sc, zr)))
+        # lane 32*kb + r of tile (nt, kt) holds row 32*nt + r, columns 128*kt + 64*kb .. +64
+        nt, kt, kb, r = 1, 1, 1, 5
+        tile_bytes = 128 * 32 * bits // 8
+        lane = 32 * kb + r
+        flat = t[0].reshape(-1)
+        base = (nt * 2 + kt) * tile_bytes + lane * 16
+        row = cd[32 * nt + r]
+        col_byte = (128 * kt + 64 * kb) * bits // 8
+        assert np.array_equal(flat[base:base + 16], row[col_byte:col_byte + 16])
+        assert t[1].reshape(-1)[(nt * 2 + kt) * 64 + lane] == sc[32 * nt + r, 2 * kt + kb]
+    w = synth.expert_weights(synth.CONFIGS["tiny"], 0)[2]      # [256, 512]
+    got = ctx.pack_tiles(to_bf16(w))
+    sync()
+    assert np.array_equal(bits_of(got), bf16_tiles_from_rowmajor(w))
 
 
 # --------------------------------------------------------------------- route
@@ -222,9 +253,10 @@ def test_assign_precision_bit_exact(ctx):
 
 # ----------------------------------------------------------------------- FFN
 
-def build_layer(cfg, bits_np, experts_needed=None):
+def build_layer(cfg, bits_np, experts_needed=None, path=B.PATH_GEMV):
     """Host weights, oracle-quantised copies at each expert's precision, and the
-    device table holding exactly those formats."""
+    device table holding exactly those formats, in the layout `path` reads."""
+    tiled = path == B.PATH_GEMM
     E = cfg.E
     host, dev = [], []
     for e in range(E):
@@ -236,11 +268,14 @@ def build_layer(cfg, bits_np, experts_needed=None):
         mats = synth.expert_weights(cfg, e)
         if b == 16:
             host.append({"w": mats})
-            dev.append({"w": [to_bf16(m) for m in mats]})
+            d = {"w": [to_bf16(m) for m in mats]}
+            if tiled:
+                d["wt"] = [to_bf16(bf16_tiles_from_rowmajor(m)) for m in mats]
+            dev.append(d)
         else:
             q = oracle_quantize_expert(mats, b)
             host.append({"q": q})
-            dev.append({"q%d" % b: upload_q(q)})
+            dev.append({"q%d" % b: upload_q([tiles_from_rowmajor(*t, b) for t in q] if tiled else q)})
     table, keep = B.make_expert_table(dev, DEV)
     return host, dev, table, keep
 
@@ -276,7 +311,7 @@ def test_ffn_tiny_every_precision(ctx, path):
     for bits_np in (np.array([16, 4, 2, 16, 4, 2, 4, 2], np.uint8),
                     np.full(8, 16, np.uint8), np.full(8, 4, np.uint8), np.full(8, 2, np.uint8),
                     np.array([16, 0, 2, 4, 0, 2, 4, 16], np.uint8)):
-        host, dev, table, keep = build_layer(cfg, bits_np)
+        host, dev, table, keep = build_layer(cfg, bits_np, path=path)
         ref = oracle_ffn(cfg, x, idx, w, bits_np, host)
         y = run_ffn(ctx, cfg, x, idx, w, bits_np, table, path)
         err = rel_err_per_token(y, ref)
@@ -313,12 +348,17 @@ def test_ffn_gemm_ragged_tiles(ctx):
     w = w.astype(np.float32)
     assert (idx != 3).all()
     bits_np = np.array([16, 4, 2, 4], np.uint8)
-    host, dev, table, keep = build_layer(cfg, bits_np)
+    host, dev, table, keep = build_layer(cfg, bits_np, path=B.PATH_GEMM)
     ref = oracle_ffn(cfg, x, idx, w, bits_np, host)
     y = run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM)
     err = rel_err_per_token(y, ref)
     print("gemm ragged err=%.3e" % err)
     assert err <= FFN_TOL
+    # a 16-bit expert without a tile copy is read row by row: same result
+    dev[0].pop("wt")
+    table2, keep2 = B.make_expert_table(dev, DEV)
+    y3 = run_ffn(ctx, cfg, x, idx, w, bits_np, table2, B.PATH_GEMM)
+    assert np.array_equal(y, y3)
     # AUTO takes the same path for this many tokens
     y2 = run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_AUTO)
     assert np.array_equal(y, y2)
@@ -357,18 +397,15 @@ def test_chained_layer_tiny(ctx):
         b = int(rbits[e])
         host.append({"w": mats[e]} if b == 16 else {"q": oracle_quantize_expert(mats[e], b)})
     ref = O.moe_ffn_mixed(x, ridx, rw, rbits, host)
-    # device chain
+    # device chain: the pre-allocated layer runner, AUTO path (16 tokens -> grouped GEMM, tile layout)
     xt = to_bf16(x)
-    experts = [{"w": [to_bf16(m) for m in mats[e]], "q4": empty_q(cfg.F, cfg.H, 4),
-                "q2": empty_q(cfg.F, cfg.H, 2)} for e in range(cfg.E)]
-    table, keep = B.make_expert_table(experts, DEV)
-    idx, w, p = ctx.route_topk(xt, to_bf16(wg), None, cfg.k)
-    score = ctx.token_score_norm(xt)
-    imp, load = ctx.expert_importance(B.PHASE_PREFILL, idx, cfg.E, token_score=score, k_hh=cfg.k_hh)
-    bits, rank = ctx.assign_precision(B.PHASE_PREFILL, imp, load, cfg.tier_count, cfg.tier_bits)
-    ctx.quantize_experts(table, bits, load, cfg.E, cfg.H, cfg.F)
-    y = ctx.moe_ffn_mixed(xt, idx, w, bits, table, cfg.F, out_dtype=B.OUT_F32)
+    store = ExpertStore([[to_bf16(m) for m in mats[e]] for e in range(cfg.E)], cfg.H, cfg.F, DEV, ctx=ctx)
+    layer = MoELayer(ctx, cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, "prefill", cfg.tier_count, cfg.tier_bits,
+                     k_hh=cfg.k_hh, out_dtype=B.OUT_F32, device=DEV)
+    assert layer.layout == B.LAYOUT_TILE
+    y = layer.step(xt, to_bf16(wg), None, store)
     sync()
+    idx, imp, load, bits = layer.idx, layer.imp, layer.load, layer.bits
     assert np.array_equal(idx.cpu().numpy(), ridx)
     assert np.array_equal(imp.cpu().numpy(), rimp) and np.array_equal(load.cpu().numpy(), rload)
     assert np.array_equal(bits.cpu().numpy(), rbits)

@@ -92,8 +92,15 @@ def test_argument_validation_happens_before_any_device_work():
     assert lib.dymoe_quantize_pack(None, P, 8, 200, 4, 64, P, P, P, None) == B.EINVAL
     assert lib.dymoe_quantize_pack(None, P, 8, 256, 4, 32, P, P, P, None) == B.ENOTSUP
     assert lib.dymoe_quantize_pack(None, P + 8, 8, 256, 4, 64, P, P, P, None) == B.EINVAL
-    assert lib.dymoe_quantize_experts(None, P, P, None, 8, 256, 512, 64, None) == B.ENOCTX
-    assert lib.dymoe_quantize_experts(None, P, P, None, 8, 250, 512, 64, None) == B.EINVAL
+    assert lib.dymoe_quantize_experts(None, P, P, None, 8, 256, 512, 64, 0, None) == B.ENOCTX
+    assert lib.dymoe_quantize_experts(None, P, P, None, 8, 256, 512, 64, 1, None) == B.ENOCTX
+    assert lib.dymoe_quantize_experts(None, P, P, None, 8, 250, 512, 64, 0, None) == B.EINVAL
+    assert lib.dymoe_quantize_experts(None, P, P, None, 8, 256, 512, 64, 2, None) == B.EINVAL
+    assert lib.dymoe_quantize_experts(None, P, P, None, 8, 192, 512, 64, 1, None) == B.EINVAL   # tiles need multiples of 128
+    assert lib.dymoe_pack_tiles(None, P, 64, 256, 2 * P, None) == B.ENOCTX
+    assert lib.dymoe_pack_tiles(None, P, 48, 256, 2 * P, None) == B.EINVAL
+    assert lib.dymoe_pack_tiles(None, P, 64, 192, 2 * P, None) == B.EINVAL
+    assert lib.dymoe_pack_tiles(None, P, 64, 256, P, None) == B.EINVAL                          # in place
     # ffn
     ws = B.workspace_bytes(16, 256, 512, 8, 2)
     ffn = lib.dymoe_moe_ffn_mixed

@@ -272,26 +272,47 @@ __device__ __forceinline__ float16_t mfma16(const uint4 a, const uint4 b, const 
                                                       __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
 }
 
-// one K-tile of MFMAs for NTF token fragments (32 tokens each)
+// one K-tile of MFMAs for NTF token fragments (32 tokens each).  The token
+// fragments are read from LDS one step ahead of the MFMAs that use them, and
+// the weight fragments of the next sub-step pair are built while the MFMAs of
+// the current one run.
 template <int BITS, int NTF>
 __device__ __forceinline__ void compute_ktile(const StripRaw<BITS>& ra, const StripRaw<BITS>& rb,
                                               const uint16_t (*xs)[kLdsStride], int ln, int kb,
                                               float16_t (&acc)[2][NTF])
 {
+    const uint16_t* base = &xs[ln][64 * kb];
+    auto frag = [&](int step) {   // step = jj * NTF + tf
+        const int jj = step / NTF, tf = step - jj * NTF;
+        return reinterpret_cast<const uint4*>(base + (32 * tf) * kLdsStride + 16 * jj);
+    };
+    uint4 a0, a1, b0, b1;
+    strip_frags<BITS>(ra, 0, a0, a1);
+    strip_frags<BITS>(rb, 0, b0, b1);
+    uint4 t0 = frag(0)[0], t1 = frag(0)[1];
 #pragma unroll
     for (int jj = 0; jj < 4; jj++) {
-        uint4 a0, a1, b0, b1;
-        strip_frags<BITS>(ra, jj, a0, a1);
-        strip_frags<BITS>(rb, jj, b0, b1);
+        uint4 na0 = a0, na1 = a1, nb0 = b0, nb1 = b1;
 #pragma unroll
         for (int tf = 0; tf < NTF; tf++) {
-            const uint4 t0 = *reinterpret_cast<const uint4*>(&xs[32 * tf + ln][64 * kb + 16 * jj]);
-            const uint4 t1 = *reinterpret_cast<const uint4*>(&xs[32 * tf + ln][64 * kb + 16 * jj + 8]);
+            const int step = jj * NTF + tf;
+            uint4 n0 = t0, n1 = t1;
+            if (step + 1 < 4 * NTF) {
+                n0 = frag(step + 1)[0];
+                n1 = frag(step + 1)[1];
+            }
             acc[0][tf] = mfma16<BITS>(a0, t0, acc[0][tf]);
             acc[1][tf] = mfma16<BITS>(b0, t0, acc[1][tf]);
             acc[0][tf] = mfma16<BITS>(a1, t1, acc[0][tf]);
             acc[1][tf] = mfma16<BITS>(b1, t1, acc[1][tf]);
+            if (tf == 0 && jj < 3) {   // next weight fragments, behind the first MFMAs of this pair
+                strip_frags<BITS>(ra, jj + 1, na0, na1);
+                strip_frags<BITS>(rb, jj + 1, nb0, nb1);
+            }
+            t0 = n0;
+            t1 = n1;
         }
+        a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
     }
 }
 

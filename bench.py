@@ -8,8 +8,9 @@ the assignment sends to int4 / int2 -> dequant-fused SwiGLU expert FFN.
 Headline (`value`): tokens/s of that full step on the Mixtral-8x7B-shaped decode
 layer (batch 1).  The same JSON line also carries the FFN alone with the
 selected formats already resident, the 512-token prefill of the same layer, the
-roofline of the dominant kernel (timed with HIP events on the launch stream by
-the library's per-kernel timers) and the CPU oracle timed on this host.
+roofline of the dominant kernel (timed with HIP events attached to its
+dispatches by the library's per-kernel timers, over the same steps launched
+eagerly right after the timed region) and the CPU oracle timed on this host.
 
   python bench.py --gpus 1 --steps 200 --warmup 20
 """
@@ -43,7 +44,8 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one 1 GiB device copy (a kernel of known traffic, to scale profiler byte counters)")
+                    help="also run dymoe_pack_tiles on a 1 GiB bf16 matrix: a plain permuting copy kernel of known "
+                         "traffic (1 GiB read, 1 GiB written), to scale a profiler's byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU (no collectives, no sharding); use --gpus 1",
@@ -80,9 +82,9 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
     if args.calibrate_copy:
-        src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
+        src = torch.zeros((32768, 16384), dtype=torch.bfloat16, device=dev)
+        for _ in range(3):
+            dst = ctx.pack_tiles(src)
         torch.cuda.synchronize()
         del src, dst
 
@@ -150,9 +152,18 @@ def main():
     dominant = max(alg_bytes, key=lambda n: kt[n][0])
     dom_us = kt[dominant][0]
     achieved = alg_bytes[dominant] / (dom_us * 1e-6) / 1e9 if dom_us > 0 else 0.0
-    roofline = {"kernel": B.lib.dymoe_kernel_name(B.KERNELS.index(dominant)).decode(),
+    kname = B.lib.dymoe_kernel_name(B.KERNELS.index(dominant)).decode()
+    # HBM bytes per launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by the
+    # same counters' reading for a copy kernel of known size); written down from the
+    # profiling runs documented under profiles/, null when no such file is there
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("mixtral_decode", {}).get(kname)
+    roofline = {"kernel": kname,
                 "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": alg_bytes[dominant], "avg_launch_us": round(dom_us, 2)}
     kernels_report = {}
     for name in kernels:

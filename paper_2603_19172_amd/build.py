@@ -29,7 +29,8 @@ SOURCES = ["api.hip", "route.hip", "importance.hip", "quantize.hip", "ffn.hip", 
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *COMMON, *PER_FILE.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = os.environ.get("DYMOE_EXTRA_HIPCC", "").split()      # e.g. -D knobs while tuning
+    cmd = ["hipcc", *COMMON, *PER_FILE.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -184,37 +184,6 @@ __device__ __forceinline__ MatPtr mat_ptr(const dymoe_expert_fmt& ex, int mat, i
     return m;
 }
 
-// loads of tile (nt, kt) of a [N,K] matrix for this lane
-template <int BITS>
-__device__ __forceinline__ void load_strip(const MatPtr& m, long nt, int kt, int K, int lane,
-                                           StripRaw<BITS>& raw)
-{
-    const long tile = nt * (K >> 7) + kt;
-    if constexpr (BITS == 16) {
-        if (m.wt) {
-            const char* src = m.wt + tile * 8192 + lane * 16;
-#pragma unroll
-            for (int j = 0; j < 8; j++) raw.r[j] = *reinterpret_cast<const uint4*>(src + j * 1024);
-        } else {
-            const uint4* src = reinterpret_cast<const uint4*>(
-                m.w + (nt * 32 + (lane & 31)) * K + kt * 128 + 64 * (lane >> 5));
-#pragma unroll
-            for (int j = 0; j < 8; j++) raw.r[j] = src[j];
-        }
-    } else {
-        if constexpr (BITS == 4) {
-            const char* src = m.q + tile * 2048 + lane * 16;
-            raw.r[0] = *reinterpret_cast<const uint4*>(src);
-            raw.r[1] = *reinterpret_cast<const uint4*>(src + 1024);
-        } else {
-            raw.r[0] = *reinterpret_cast<const uint4*>(m.q + tile * 1024 + lane * 16);
-        }
-        const uint32_t s = m.s[tile * 64 + lane], z = m.z[tile * 64 + lane];
-        raw.s2 = s | (s << 16);
-        raw.m2 = z | (z << 16);
-    }
-}
-
 __device__ __forceinline__ uint32_t deq_pair(uint32_t biased, uint32_t bias2, uint32_t s2, uint32_t m2)
 {
     const half2_t q = __builtin_bit_cast(half2_t, biased) - __builtin_bit_cast(half2_t, bias2);  // exact
@@ -272,48 +241,129 @@ __device__ __forceinline__ float16_t mfma16(const uint4 a, const uint4 b, const 
                                                       __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
 }
 
-// one K-tile of MFMAs for NTF token fragments (32 tokens each).  The token
-// fragments are read from LDS one step ahead of the MFMAs that use them, and
-// the weight fragments of the next sub-step pair are built while the MFMAs of
-// the current one run.
+// address of this lane's slice of tile (nt, kt)
+struct StripSrc {
+    const char* p;        // bf16 tiles, or packed codes (tile layout), at this lane's 16 bytes of tile 0
+    const uint16_t* s;    // scale / zero at this lane's slot of tile 0 (quantised only)
+    const uint16_t* z;
+    const uint16_t* w;    // bf16 row-major fallback: this lane's row and column half (null when tiles exist)
+    long tile_row;        // nt * (K / 128)
+    int K;
+};
+
+template <int BITS>
+__device__ __forceinline__ StripSrc strip_src(const MatPtr& m, long nt, int K, int lane)
+{
+    StripSrc src;
+    src.tile_row = nt * (K >> 7);
+    src.K = K;
+    src.w = nullptr;
+    src.s = m.s + lane;
+    src.z = m.z + lane;
+    if constexpr (BITS == 16) {
+        src.p = m.wt ? m.wt + lane * 16 : nullptr;
+        if (!m.wt) src.w = m.w + (nt * 32 + (lane & 31)) * K + 64 * (lane >> 5);
+    } else {
+        src.p = m.q + lane * 16;
+    }
+    return src;
+}
+
+// chunk c of the lane's slice of K-tile kt: bf16 c = 0..7 (8 columns each),
+// int4 c = 0..1 (32 codes each), int2 c = 0 (64 codes)
+template <int BITS>
+__device__ __forceinline__ uint4 load_chunk(const StripSrc& src, int kt, int c)
+{
+    if constexpr (BITS == 16) {
+        if (src.p) return *reinterpret_cast<const uint4*>(src.p + (src.tile_row + kt) * 8192 + c * 1024);
+        return *reinterpret_cast<const uint4*>(src.w + kt * 128 + 8 * c);
+    } else if constexpr (BITS == 4) {
+        return *reinterpret_cast<const uint4*>(src.p + (src.tile_row + kt) * 2048 + c * 1024);
+    } else {
+        return *reinterpret_cast<const uint4*>(src.p + (src.tile_row + kt) * 1024);
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void load_scale_zero(const StripSrc& src, int kt, StripRaw<BITS>& raw)
+{
+    if constexpr (BITS != 16) {
+        const uint32_t s = src.s[(src.tile_row + kt) * 64], z = src.z[(src.tile_row + kt) * 64];
+        raw.s2 = s | (s << 16);
+        raw.m2 = z | (z << 16);
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void load_strip(const StripSrc& src, int kt, StripRaw<BITS>& raw)
+{
+    constexpr int kChunks = (BITS == 16) ? 8 : (BITS == 4 ? 2 : 1);
+#pragma unroll
+    for (int c = 0; c < kChunks; c++) raw.r[c] = load_chunk<BITS>(src, kt, c);
+    load_scale_zero<BITS>(src, kt, raw);
+}
+
+// One K-tile of MFMAs for NTF token fragments (32 tokens each), and, woven into
+// it, the loads of the next K-tile: every weight register is refilled as soon as
+// the last MFMA that reads it has been issued, so the next tile's weights are in
+// flight during this tile's arithmetic without a second set of registers.
 template <int BITS, int NTF>
-__device__ __forceinline__ void compute_ktile(const StripRaw<BITS>& ra, const StripRaw<BITS>& rb,
+__device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>& rb,
+                                              const StripSrc& sa, const StripSrc& sb, int kt_next,
                                               const uint16_t (*xs)[kLdsStride], int ln, int kb,
                                               float16_t (&acc)[2][NTF])
 {
     const uint16_t* base = &xs[ln][64 * kb];
-    auto frag = [&](int step) {   // step = jj * NTF + tf
-        const int jj = step / NTF, tf = step - jj * NTF;
-        return reinterpret_cast<const uint4*>(base + (32 * tf) * kLdsStride + 16 * jj);
-    };
-    uint4 a0, a1, b0, b1;
-    strip_frags<BITS>(ra, 0, a0, a1);
-    strip_frags<BITS>(rb, 0, b0, b1);
-    uint4 t0 = frag(0)[0], t1 = frag(0)[1];
 #pragma unroll
     for (int jj = 0; jj < 4; jj++) {
-        uint4 na0 = a0, na1 = a1, nb0 = b0, nb1 = b1;
+        uint4 a0, a1, b0, b1;
+        strip_frags<BITS>(ra, jj, a0, a1);
+        strip_frags<BITS>(rb, jj, b0, b1);
 #pragma unroll
         for (int tf = 0; tf < NTF; tf++) {
-            const int step = jj * NTF + tf;
-            uint4 n0 = t0, n1 = t1;
-            if (step + 1 < 4 * NTF) {
-                n0 = frag(step + 1)[0];
-                n1 = frag(step + 1)[1];
-            }
+            const uint4* t = reinterpret_cast<const uint4*>(base + (32 * tf) * kLdsStride + 16 * jj);
+            const uint4 t0 = t[0], t1 = t[1];
             acc[0][tf] = mfma16<BITS>(a0, t0, acc[0][tf]);
             acc[1][tf] = mfma16<BITS>(b0, t0, acc[1][tf]);
             acc[0][tf] = mfma16<BITS>(a1, t1, acc[0][tf]);
             acc[1][tf] = mfma16<BITS>(b1, t1, acc[1][tf]);
-            if (tf == 0 && jj < 3) {   // next weight fragments, behind the first MFMAs of this pair
-                strip_frags<BITS>(ra, jj + 1, na0, na1);
-                strip_frags<BITS>(rb, jj + 1, nb0, nb1);
-            }
-            t0 = n0;
-            t1 = n1;
         }
-        a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+        if constexpr (BITS == 16) {
+            ra.r[2 * jj] = load_chunk<16>(sa, kt_next, 2 * jj);
+            ra.r[2 * jj + 1] = load_chunk<16>(sa, kt_next, 2 * jj + 1);
+            rb.r[2 * jj] = load_chunk<16>(sb, kt_next, 2 * jj);
+            rb.r[2 * jj + 1] = load_chunk<16>(sb, kt_next, 2 * jj + 1);
+        } else if constexpr (BITS == 4) {
+            if (jj & 1) {
+                ra.r[jj >> 1] = load_chunk<4>(sa, kt_next, jj >> 1);
+                rb.r[jj >> 1] = load_chunk<4>(sb, kt_next, jj >> 1);
+            }
+        }
     }
+    if constexpr (BITS == 2) {
+        ra.r[0] = load_chunk<2>(sa, kt_next, 0);
+        rb.r[0] = load_chunk<2>(sb, kt_next, 0);
+    }
+    load_scale_zero<BITS>(sa, kt_next, ra);
+    load_scale_zero<BITS>(sb, kt_next, rb);
+}
+
+// the 64 bytes of the token tile one thread moves from global memory to LDS
+struct XTile {
+    uint4 v[4];
+};
+
+__device__ __forceinline__ void load_x(XTile& x, const uint16_t* __restrict__ src_row, int kt)
+{
+#pragma unroll
+    for (int i = 0; i < 4; i++) x.v[i] = *reinterpret_cast<const uint4*>(src_row + kt * kBK + 8 * i);
+}
+
+__device__ __forceinline__ void store_x(const XTile& x, uint16_t (*xs)[kLdsStride], int srow, int sq)
+{
+    uint4* dst = reinterpret_cast<uint4*>(&xs[srow][32 * sq]);
+#pragma unroll
+    for (int i = 0; i < 4; i++) dst[i] = x.v[i];
 }
 
 // ----------------------------------------------------------------------------
@@ -370,69 +420,26 @@ __device__ __forceinline__ void gemm_tile(
     if (MODE == 1) src_row = act + (long)(perm[row0 + srow_c] / k_route) * K;
     else src_row = act + (long)(row0 + srow_c) * K;
     src_row += 32 * sq;
-    uint4 xv[4];
-    auto load_x = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) xv[i] = *reinterpret_cast<const uint4*>(src_row + kt * kBK + 8 * i);
-    };
-    auto store_x = [&](int buf) {
-        uint4* dst = reinterpret_cast<uint4*>(&xs[buf][srow][32 * sq]);
-#pragma unroll
-        for (int i = 0; i < 4; i++) dst[i] = xv[i];
-    };
-
-    if constexpr (BITS == 16) {
-        // one register set: the next tile's weights are requested as soon as
-        // the MFMAs of the current one have been issued
-        StripRaw<16> ra, rb;
-        load_x(kt_begin);
-        load_strip<16>(ma, nt_a, kt_begin, K, lane, ra);
-        load_strip<16>(mb, nt_b, kt_begin, K, lane, rb);
-        store_x(0);
+    XTile xv;
+    // K loop: the next token tile travels global -> registers -> other LDS
+    // buffer around the MFMAs; the next weights are requested inside them.
+    const StripSrc sa = strip_src<BITS>(ma, nt_a, K, lane);
+    const StripSrc sb = strip_src<BITS>(mb, nt_b, K, lane);
+    StripRaw<BITS> ra, rb;
+    load_x(xv, src_row, kt_begin);
+    load_strip<BITS>(sa, kt_begin, ra);
+    load_strip<BITS>(sb, kt_begin, rb);
+    store_x(xv, xs[0], srow, sq);
+    __syncthreads();
+    int buf = 0;
+    for (int kt = kt_begin; kt < kt_end; kt++) {
+        // past the end the prefetches re-read the last tile instead of branching
+        const int kn = min(kt + 1, kt_end - 1);
+        load_x(xv, src_row, kn);
+        compute_ktile<BITS, NTF>(ra, rb, sa, sb, kn, xs[buf], ln, kb, acc);
+        buf ^= 1;
+        store_x(xv, xs[buf], srow, sq);
         __syncthreads();
-        int buf = 0;
-        for (int kt = kt_begin; kt < kt_end; kt++) {
-            const int kn = min(kt + 1, kt_end - 1);
-            load_x(kn);
-            __builtin_amdgcn_sched_barrier(0);
-            compute_ktile<16, NTF>(ra, rb, xs[buf], ln, kb, acc);
-            __builtin_amdgcn_sched_barrier(0);
-            load_strip<16>(ma, nt_a, kn, K, lane, ra);
-            load_strip<16>(mb, nt_b, kn, K, lane, rb);
-            buf ^= 1;
-            store_x(buf);
-            __syncthreads();
-        }
-    } else {
-        // two register sets take turns, so the weights of tile kt+1 are in
-        // flight while tile kt is multiplied and no register is ever copied
-        StripRaw<BITS> ra0, rb0, ra1, rb1;
-        load_x(kt_begin);
-        load_strip<BITS>(ma, nt_a, kt_begin, K, lane, ra0);
-        load_strip<BITS>(mb, nt_b, kt_begin, K, lane, rb0);
-        store_x(0);
-        __syncthreads();
-        for (int kt = kt_begin; kt < kt_end; kt += 2) {
-            const int k1 = min(kt + 1, kt_end - 1);
-            load_x(k1);
-            load_strip<BITS>(ma, nt_a, k1, K, lane, ra1);
-            load_strip<BITS>(mb, nt_b, k1, K, lane, rb1);
-            __builtin_amdgcn_sched_barrier(0);
-            compute_ktile<BITS, NTF>(ra0, rb0, xs[0], ln, kb, acc);
-            __builtin_amdgcn_sched_barrier(0);
-            store_x(1);
-            __syncthreads();
-            if (kt + 1 >= kt_end) break;   // odd number of K-tiles
-            const int k2 = min(kt + 2, kt_end - 1);
-            load_x(k2);
-            load_strip<BITS>(ma, nt_a, k2, K, lane, ra0);
-            load_strip<BITS>(mb, nt_b, k2, K, lane, rb0);
-            __builtin_amdgcn_sched_barrier(0);
-            compute_ktile<BITS, NTF>(ra1, rb1, xs[1], ln, kb, acc);
-            __builtin_amdgcn_sched_barrier(0);
-            store_x(0);
-            __syncthreads();
-        }
     }
 
     // epilogue.  D layout: lane (ln, kb), register i -> weight row 8*(i/4) + 4*kb + i%4, token ln

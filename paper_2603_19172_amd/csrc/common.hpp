@@ -87,6 +87,37 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
+// A pointer fetched from the expert table carries no address space, so a plain
+// dereference becomes a flat instruction, which also occupies the LDS counter and
+// makes every wait on LDS data wait on weight loads as well.  All table pointers
+// are device memory: these helpers access them as such.
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+#define DYMOE_GLOBAL __attribute__((address_space(1)))
+
+// (HIP's uint2/uint4 are classes whose copy goes through a generic reference, so
+// 8- and 16-byte values are moved as native vectors and converted afterwards.)
+template <typename T>
+__device__ __forceinline__ T load_global(const void* p)
+{
+    if constexpr (sizeof(T) == 16) {
+        const u32x4_t v = *(const DYMOE_GLOBAL u32x4_t*)p;
+        return __builtin_bit_cast(T, v);
+    } else if constexpr (sizeof(T) == 8) {
+        const u32x2_t v = *(const DYMOE_GLOBAL u32x2_t*)p;
+        return __builtin_bit_cast(T, v);
+    } else {
+        return *(const DYMOE_GLOBAL T*)p;
+    }
+}
+template <typename T>
+__device__ __forceinline__ void store_global(void* p, T v)
+{
+    if constexpr (sizeof(T) == 16) *(DYMOE_GLOBAL u32x4_t*)p = __builtin_bit_cast(u32x4_t, v);
+    else if constexpr (sizeof(T) == 8) *(DYMOE_GLOBAL u32x2_t*)p = __builtin_bit_cast(u32x2_t, v);
+    else *(DYMOE_GLOBAL T*)p = v;
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 __device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }

@@ -241,30 +241,36 @@ __device__ __forceinline__ float16_t mfma16(const uint4 a, const uint4 b, const 
                                                       __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
 }
 
-// address of this lane's slice of tile (nt, kt)
+// address of this lane's slice of the K-tiles of one 32-row strip
 struct StripSrc {
-    const char* p;        // bf16 tiles, or packed codes (tile layout), at this lane's 16 bytes of tile 0
-    const uint16_t* s;    // scale / zero at this lane's slot of tile 0 (quantised only)
+    const char* p;        // this lane's first 16 bytes of K-tile 0 (bf16 tiles or rows, or packed codes)
+    const uint16_t* s;    // scale / zero at this lane's slot of K-tile 0 (quantised only)
     const uint16_t* z;
-    const uint16_t* w;    // bf16 row-major fallback: this lane's row and column half (null when tiles exist)
-    long tile_row;        // nt * (K / 128)
-    int K;
+    int kt_stride;        // bytes from one K-tile to the next
+    int c_stride;         // bytes from one 16-byte chunk of the lane's slice to the next
 };
 
 template <int BITS>
 __device__ __forceinline__ StripSrc strip_src(const MatPtr& m, long nt, int K, int lane)
 {
     StripSrc src;
-    src.tile_row = nt * (K >> 7);
-    src.K = K;
-    src.w = nullptr;
-    src.s = m.s + lane;
-    src.z = m.z + lane;
+    const long tile_row = nt * (K >> 7);
+    src.s = m.s + tile_row * 64 + lane;
+    src.z = m.z + tile_row * 64 + lane;
     if constexpr (BITS == 16) {
-        src.p = m.wt ? m.wt + lane * 16 : nullptr;
-        if (!m.wt) src.w = m.w + (nt * 32 + (lane & 31)) * K + 64 * (lane >> 5);
+        if (m.wt) {          // tiles: chunk c of every lane sits in one 1 KiB run
+            src.p = m.wt + tile_row * 8192 + lane * 16;
+            src.kt_stride = 8192;
+            src.c_stride = 1024;
+        } else {             // rows: the lane's 64 columns are contiguous
+            src.p = reinterpret_cast<const char*>(m.w + (nt * 32 + (lane & 31)) * K + 64 * (lane >> 5));
+            src.kt_stride = 256;
+            src.c_stride = 16;
+        }
     } else {
-        src.p = m.q + lane * 16;
+        src.p = m.q + tile_row * (BITS == 4 ? 2048 : 1024) + lane * 16;
+        src.kt_stride = (BITS == 4) ? 2048 : 1024;
+        src.c_stride = 1024;
     }
     return src;
 }
@@ -274,21 +280,17 @@ __device__ __forceinline__ StripSrc strip_src(const MatPtr& m, long nt, int K, i
 template <int BITS>
 __device__ __forceinline__ uint4 load_chunk(const StripSrc& src, int kt, int c)
 {
-    if constexpr (BITS == 16) {
-        if (src.p) return *reinterpret_cast<const uint4*>(src.p + (src.tile_row + kt) * 8192 + c * 1024);
-        return *reinterpret_cast<const uint4*>(src.w + kt * 128 + 8 * c);
-    } else if constexpr (BITS == 4) {
-        return *reinterpret_cast<const uint4*>(src.p + (src.tile_row + kt) * 2048 + c * 1024);
-    } else {
-        return *reinterpret_cast<const uint4*>(src.p + (src.tile_row + kt) * 1024);
-    }
+    if constexpr (BITS == 16) return load_global<uint4>(src.p + (long)kt * src.kt_stride + c * src.c_stride);
+    else if constexpr (BITS == 4) return load_global<uint4>(src.p + (long)kt * 2048 + c * 1024);
+    else return load_global<uint4>(src.p + (long)kt * 1024);
 }
 
 template <int BITS>
 __device__ __forceinline__ void load_scale_zero(const StripSrc& src, int kt, StripRaw<BITS>& raw)
 {
     if constexpr (BITS != 16) {
-        const uint32_t s = src.s[(src.tile_row + kt) * 64], z = src.z[(src.tile_row + kt) * 64];
+        const uint32_t s = load_global<uint16_t>(src.s + kt * 64);
+        const uint32_t z = load_global<uint16_t>(src.z + kt * 64);
         raw.s2 = s | (s << 16);
         raw.m2 = z | (z << 16);
     }

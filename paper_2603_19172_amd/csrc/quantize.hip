@@ -43,10 +43,9 @@ __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, l
     const long e0 = block * (long)kQElemsPerBlock + (long)threadIdx.x * kQElemsPerLane;
     // a group's two lanes are in or out together (n_elems is a multiple of 64)
     if (e0 >= n_elems) return;
-    const uint4* src = reinterpret_cast<const uint4*>(w + e0);
     uint4 raw[4];
 #pragma unroll
-    for (int c = 0; c < 4; c++) raw[c] = src[c];
+    for (int c = 0; c < 4; c++) raw[c] = load_global<uint4>(w + e0 + 8 * c);
     float v[32];
 #pragma unroll
     for (int c = 0; c < 4; c++) unpack8(raw[c], v + 8 * c);
@@ -93,13 +92,13 @@ __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, l
         words[wd] = lo16 | hi16;
     }
     if constexpr (BITS == 4) {
-        *reinterpret_cast<uint4*>(codes + (e0 >> 1)) = make_uint4(words[0], words[1], words[2], words[3]);
+        store_global(codes + (e0 >> 1), make_uint4(words[0], words[1], words[2], words[3]));
     } else {
-        *reinterpret_cast<uint2*>(codes + (e0 >> 2)) = make_uint2(words[0], words[1]);
+        store_global(codes + (e0 >> 2), make_uint2(words[0], words[1]));
     }
     if ((lane & 1) == 0) {
-        scale[e0 >> 6] = (uint16_t)f16_bits(sh);
-        zero[e0 >> 6] = (uint16_t)f16_bits(zh);
+        store_global(scale + (e0 >> 6), (uint16_t)f16_bits(sh));
+        store_global(zero + (e0 >> 6), (uint16_t)f16_bits(zh));
     }
 }
 
@@ -131,10 +130,9 @@ __device__ __forceinline__ void quantize_tile(const uint16_t* __restrict__ w, lo
     const long kt = tile - nt * KT;
     const long row = nt * 32 + (lane & 31);
     const long col = kt * 128 + 64 * (lane >> 5);
-    const uint4* src = reinterpret_cast<const uint4*>(w + row * K + col);
     uint4 raw[8];
 #pragma unroll
-    for (int c = 0; c < 8; c++) raw[c] = src[c];
+    for (int c = 0; c < 8; c++) raw[c] = load_global<uint4>(w + row * K + col + 8 * c);
     float v[64];
 #pragma unroll
     for (int c = 0; c < 8; c++) unpack8(raw[c], v + 8 * c);
@@ -179,14 +177,13 @@ __device__ __forceinline__ void quantize_tile(const uint16_t* __restrict__ w, lo
     }
     if constexpr (BITS == 4) {
         uint8_t* dst = codes + tile * 2048 + lane * 16;
-        *reinterpret_cast<uint4*>(dst) = make_uint4(words[0], words[1], words[2], words[3]);
-        *reinterpret_cast<uint4*>(dst + 1024) = make_uint4(words[4], words[5], words[6], words[7]);
+        store_global(dst, make_uint4(words[0], words[1], words[2], words[3]));
+        store_global(dst + 1024, make_uint4(words[4], words[5], words[6], words[7]));
     } else {
-        *reinterpret_cast<uint4*>(codes + tile * 1024 + lane * 16) =
-            make_uint4(words[0], words[1], words[2], words[3]);
+        store_global(codes + tile * 1024 + lane * 16, make_uint4(words[0], words[1], words[2], words[3]));
     }
-    scale[tile * 64 + lane] = (uint16_t)f16_bits(sh);
-    zero[tile * 64 + lane] = (uint16_t)f16_bits(zh);
+    store_global(scale + tile * 64 + lane, (uint16_t)f16_bits(sh));
+    store_global(zero + tile * 64 + lane, (uint16_t)f16_bits(zh));
 }
 
 // bf16 row-major -> bf16 tiles: thread = (tile, chunk j, lane)

@@ -44,8 +44,9 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run dymoe_pack_tiles on a 1 GiB bf16 matrix: a plain permuting copy kernel of known "
-                         "traffic (1 GiB read, 1 GiB written), to scale a profiler's byte counters")
+                    help="also run dymoe_pack_tiles on a 1 GiB bf16 matrix: a permuting copy of known traffic "
+                         "(1 GiB read in 32-byte pieces, 1 GiB written), a second reference for a profiler's "
+                         "byte counters beside the plain stream copy that every run makes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU (no collectives, no sharding); use --gpus 1",
@@ -81,12 +82,24 @@ def main():
                      out_dtype=B.OUT_BF16, device=dev)
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
+    # plain copy of 1 GiB: the copy rate this machine sustains, and a known quantity
+    # of traffic for a profiler's byte counters
+    src = torch.zeros((1 << 30,), dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        ctx.stream_copy(src, dst)
+    ctx.timing_enable(["stream_copy"])
+    for _ in range(10):
+        ctx.stream_copy(src, dst)
+    ms, n = ctx.timing_read("stream_copy")
+    ctx.timing_enable([])
+    copy_gbps = 2.0 * src.numel() * n / (ms * 1e-3) / 1e9
     if args.calibrate_copy:
-        src = torch.zeros((32768, 16384), dtype=torch.bfloat16, device=dev)
+        src2 = src.view(torch.bfloat16).view(32768, 16384)
         for _ in range(3):
-            dst = ctx.pack_tiles(src)
-        torch.cuda.synchronize()
-        del src, dst
+            ctx.pack_tiles(src2)
+    torch.cuda.synchronize()
+    del src, dst
 
     def timed_loop(fns, steps, warmup):
         """fns: one callable per weight copy; returns seconds for `steps` calls."""
@@ -184,6 +197,12 @@ def main():
                    "active_experts": active, "active_bits": active_bits, "launch": launch_mode,
                    "weight_copies_rotated": LAYER_COPIES, "setup_s": round(setup_s, 1)},
         "roofline": roofline,
+        "hot_path_hbm": {"algorithmic_bytes_per_step": sum(alg_bytes.values()),
+                         "GBps": round(sum(alg_bytes.values()) / (ms_per_step * 1e-3) / 1e9, 1),
+                         "frac_hbm": round(sum(alg_bytes.values()) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                         "stream_copy_GBps": round(copy_gbps, 1),
+                         "note": "all kernels of a step and the gaps between them over the step's algorithmic "
+                                 "bytes; stream_copy_GBps is a plain 1 GiB copy (read + write bytes) on this GPU"},
         "kernels": kernels_report,
         "decode_ffn_only": {"tokens_per_s": round(cfg.T * args.steps / sec_ffn, 1),
                             "us_per_step": round(sec_ffn / args.steps * 1e6, 2),
@@ -233,31 +252,39 @@ def main():
     # ---------------------------------------------------------------- CPU oracle on this host
     if not args.skip_cpu:
         from oracle import dymoe_oracle as O
+        def oracle_step():
+            ridx, rw, rp, rl = O.route_topk(x_np, wg_np, bias_np, k)
+            rimp = O.expert_importance_decode(rp)
+            rload = np.bincount(ridx.ravel(), minlength=E).astype(np.int32)
+            rbits, _ = O.assign_precision(rimp, rload, cfg.tier_count, cfg.tier_bits)
+            experts = []
+            for e in range(E):
+                b = int(rbits[e])
+                if e not in ridx[0]:
+                    experts.append({})
+                elif b == 16:
+                    experts.append({"w": host_w[e]})
+                else:
+                    experts.append({"q": [O.quantize_pack(m, b) for m in host_w[e]]})
+            ob = rbits.copy()
+            for e in range(E):
+                if e not in ridx[0]:
+                    ob[e] = 0
+            return ridx, rbits, O.moe_ffn_mixed(x_np, ridx, rw, ob, experts)
+
+        # whole steps, repeated until about 10 s of oracle work have been timed
         t0 = time.perf_counter()
-        ridx, rw, rp, rl = O.route_topk(x_np, wg_np, bias_np, k)
-        rimp = O.expert_importance_decode(rp)
-        rload = np.bincount(ridx.ravel(), minlength=E).astype(np.int32)
-        rbits, _ = O.assign_precision(rimp, rload, cfg.tier_count, cfg.tier_bits)
-        experts = []
-        for e in range(E):
-            b = int(rbits[e])
-            if e not in ridx[0]:
-                experts.append({})
-            elif b == 16:
-                experts.append({"w": host_w[e]})
-            else:
-                experts.append({"q": [O.quantize_pack(m, b) for m in host_w[e]]})
-        ob = rbits.copy()
-        for e in range(E):
-            if e not in ridx[0]:
-                ob[e] = 0
-        ref = O.moe_ffn_mixed(x_np, ridx, rw, ob, experts)
+        cpu_steps = 0
+        while cpu_steps < 64 and (cpu_steps == 0 or time.perf_counter() - t0 < 10.0):
+            ridx, rbits, ref = oracle_step()
+            cpu_steps += 1
         cpu_s = time.perf_counter() - t0
         rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))
         err = float((np.abs(y_gpu - ref) / rms).max())
-        out["cpu_baseline"] = {"value": round(cfg.T / cpu_s, 4), "unit": "tokens/s", "cores": 1,
+        out["cpu_baseline"] = {"value": round(cfg.T * cpu_steps / cpu_s, 4), "unit": "tokens/s", "cores": 1,
                                "kind": "oracle",
-                               "sample": "one full step (1 token): route, importance, assignment, quantize-pack of the active int4 expert, FFN over the 2 active experts; %.1f s" % cpu_s,
+                               "sample": "%d full steps of 1 token each (route, importance, assignment, quantize-pack of the active "
+                                         "int4 expert, FFN over the 2 active experts), %.1f s in all" % (cpu_steps, cpu_s),
                                "host_cpus": os.cpu_count()}
         out["parity_vs_oracle"] = {"topk_equal": bool(np.array_equal(idx_host, ridx)),
                                    "bits_equal": bool(np.array_equal(bits_host, rbits)),

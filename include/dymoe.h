@@ -252,12 +252,24 @@ int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t* idx, const
                         void* y, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Measurement aid, not a step of the method: copies `bytes` (a multiple of
+ * 16; src and dst 16-byte aligned device pointers that do not overlap) with
+ * the access pattern of the weight-streaming kernels (16 bytes per lane,
+ * 1 KiB per wavefront instruction).  Its traffic is exactly `bytes` read and
+ * `bytes` written, which gives a profiler's HBM byte counters a known
+ * quantity to be scaled by, and the rate it reaches is the copy rate the
+ * machine sustains, the practical ceiling beside the 8 TB/s on the data sheet
+ * (the paper's own evaluation reports latency only, Sec. 6.1 "Key Metrics").
+ */
+int dymoe_stream_copy(dymoe_ctx* ctx, const void* src, void* dst, size_t bytes, void* stream);
+
+/*
  * Per-kernel timing (diagnostic; the paper reports only end-to-end latency,
  * Sec. 6.1 "Key Metrics", so these serve the roofline accounting).
  * dymoe_timing_enable: launches of the kernels whose bit is set in kernel_mask
- * (bit i = kernel id i, ids 0..11 in the order route, token_norm, importance,
+ * (bit i = kernel id i, ids 0..12 in the order route, token_norm, importance,
  * assign, quantize, gemv_phase1, gemv_phase2, gemv_combine, plan, gemm1, gemm2,
- * gemm_combine) carry a start and a stop HIP event on the dispatch itself, so
+ * gemm_combine, stream_copy) carry a start and a stop HIP event on the dispatch itself, so
  * the interval is the kernel's execution time on the launch stream; 0 switches
  * timing off.  Either way, records not yet read are dropped.
  * dymoe_timing_read: waits for the recorded launches of `kernel`, returns

@@ -32,12 +32,12 @@ EXPORTS = [
     "dymoe_create", "dymoe_destroy", "dymoe_strerror", "dymoe_workspace_bytes",
     "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_expert_importance",
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
-    "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_moe_ffn_mixed",
+    "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_moe_ffn_mixed", "dymoe_stream_copy",
     "dymoe_timing_enable", "dymoe_timing_read", "dymoe_kernel_name",
 ]
 
 KERNELS = ["route", "token_norm", "importance", "assign", "quantize", "gemv_phase1",
-           "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine"]
+           "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine", "stream_copy"]
 
 
 class ExpertFmt(C.Structure):
@@ -56,6 +56,8 @@ lib.dymoe_strerror.restype = C.c_char_p
 lib.dymoe_strerror.argtypes = [_i]
 lib.dymoe_workspace_bytes.restype = _sz
 lib.dymoe_workspace_bytes.argtypes = [_i] * 5
+lib.dymoe_stream_copy.restype = _i
+lib.dymoe_stream_copy.argtypes = [_vp, _vp, _vp, _sz, _vp]
 lib.dymoe_route_topk.restype = _i
 lib.dymoe_route_topk.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
 lib.dymoe_token_score_norm.restype = _i
@@ -237,6 +239,14 @@ class Context:
         _check(lib.dymoe_pack_tiles(self._h, _ptr(w, torch.bfloat16), N, K, _ptr(out),
                                     _stream(stream)), "dymoe_pack_tiles")
         return out
+
+    def stream_copy(self, src, dst, stream=None):
+        """Plain copy of src's bytes into dst (same byte count): a measurement aid."""
+        n = src.numel() * src.element_size()
+        if n != dst.numel() * dst.element_size():
+            raise ValueError("stream_copy: byte counts differ")
+        _check(lib.dymoe_stream_copy(self._h, _ptr(src), _ptr(dst), n, _stream(stream)), "dymoe_stream_copy")
+        return dst
 
     # -- S5
     def moe_ffn_mixed(self, x, idx, w, bits, table, F, out_dtype=OUT_BF16, path=PATH_AUTO,

@@ -5,7 +5,42 @@
 #include "common.hpp"
 #include "ffn_layout.hpp"
 
+namespace dymoe {
+
+// Plain copy, 16 bytes per lane, every wavefront instruction moving 1 KiB of
+// contiguous memory: the access pattern of the weight-streaming kernels, with
+// exactly known traffic.
+__global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restrict__ src,
+                                                          uint4* __restrict__ dst, long n16)
+{
+    const long i = (long)blockIdx.x * 1024 + threadIdx.x;
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++)
+        if (i + 256 * u < n16) v[u] = src[i + 256 * u];
+#pragma unroll
+    for (int u = 0; u < 4; u++)
+        if (i + 256 * u < n16) dst[i + 256 * u] = v[u];
+}
+
+}  // namespace dymoe
+
 extern "C" {
+
+int dymoe_stream_copy(dymoe_ctx* ctx, const void* src, void* dst, size_t bytes, void* stream)
+{
+    DYMOE_REQUIRE(bytes % 16 == 0);
+    if (bytes == 0) return DYMOE_OK;
+    DYMOE_REQUIRE(src != nullptr && dst != nullptr && dymoe_aligned(src, 16) && dymoe_aligned(dst, 16));
+    if (!ctx) return DYMOE_ENOCTX;
+    const long n16 = (long)(bytes / 16);
+    const long blocks = (n16 + 1023) / 1024;
+    DYMOE_REQUIRE(blocks <= 0x7fffffffL);
+    dymoe_launch(ctx, DYMOE_K_STREAM_COPY, dymoe::stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                 (hipStream_t)stream, (const uint4*)src, (uint4*)dst, n16);
+    DYMOE_HIP_LAUNCH_CHECK();
+    return DYMOE_OK;
+}
 
 int dymoe_create(dymoe_ctx** out, int device)
 {
@@ -93,6 +128,7 @@ const char* dymoe_kernel_name(int kernel)
     case DYMOE_K_GEMM1: return "gemm_kernel<1>";
     case DYMOE_K_GEMM2: return "gemm_kernel<2>";
     case DYMOE_K_GEMM_COMBINE: return "gemm_combine_kernel";
+    case DYMOE_K_STREAM_COPY: return "stream_copy_kernel";
     default: return nullptr;
     }
 }

@@ -413,3 +413,16 @@ def test_chained_layer_tiny(ctx):
     err = rel_err_per_token(y.cpu().numpy().astype(np.float64), ref)
     print("chained tiny err=%.3e" % err)
     assert err <= FFN_TOL
+
+
+# ------------------------------------------------------------------ measurement aid
+
+@pytest.mark.parametrize("nbytes", [0, 16, 16 * 1024 * 3 + 48, 8 << 20])
+def test_stream_copy_copies_every_byte(ctx, nbytes):
+    g = torch.Generator().manual_seed(5)
+    src = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, generator=g).to(DEV)
+    dst = torch.zeros((nbytes + 64,), dtype=torch.uint8, device=DEV)
+    ctx.stream_copy(src, dst[:nbytes])
+    sync()
+    assert torch.equal(dst[:nbytes], src)
+    assert int(dst[nbytes:].sum()) == 0        # nothing written past the end

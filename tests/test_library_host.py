@@ -101,6 +101,12 @@ def test_argument_validation_happens_before_any_device_work():
     assert lib.dymoe_pack_tiles(None, P, 48, 256, 2 * P, None) == B.EINVAL
     assert lib.dymoe_pack_tiles(None, P, 64, 192, 2 * P, None) == B.EINVAL
     assert lib.dymoe_pack_tiles(None, P, 64, 256, P, None) == B.EINVAL                          # in place
+    # stream copy
+    assert lib.dymoe_stream_copy(None, P, 2 * P, 1024, None) == B.ENOCTX
+    assert lib.dymoe_stream_copy(None, P, 2 * P, 1000, None) == B.EINVAL
+    assert lib.dymoe_stream_copy(None, P + 4, 2 * P, 1024, None) == B.EINVAL
+    assert lib.dymoe_stream_copy(None, None, 2 * P, 1024, None) == B.EINVAL
+    assert lib.dymoe_stream_copy(None, None, None, 0, None) == B.OK
     # ffn
     ws = B.workspace_bytes(16, 256, 512, 8, 2)
     ffn = lib.dymoe_moe_ffn_mixed

@@ -33,7 +33,7 @@ constexpr int kLdsStride = 136;     // 16-bit elements per LDS row (128 + pad ke
 
 // ----------------------------------------------------------------------------
 // plan: counting sort of the (token, slot) pairs by expert + tile list
-// ints: counts[E] | offsets[E+1] | cursor[E] | ntiles (8 ints) | perm[P] | tiles[4*max_tiles]
+// ints: counts[E] | offsets[E+1] | cursor[E] | ntiles (8 ints) | perm[P] | tiles[4*max_tiles] | draft[4*max_tiles]
 struct PlanPtrs {
     int32_t* counts;
     int32_t* offsets;
@@ -57,11 +57,14 @@ __host__ __device__ inline PlanPtrs plan_ptrs(int32_t* base, int E, int P)
 
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ idx,
                                                     const uint8_t* __restrict__ bits, int P, int E,
-                                                    int tile_m, int32_t* __restrict__ plan)
+                                                    int tile_m, int max_tiles,
+                                                    int32_t* __restrict__ plan)
 {
     __shared__ int32_t s_count[DYMOE_MAX_EXPERTS];
     __shared__ int32_t s_off[DYMOE_MAX_EXPERTS + 1];
+    __shared__ int s_nt;
     const PlanPtrs pp = plan_ptrs(plan, E, P);
+    int32_t* draft = pp.tiles + 4 * (size_t)max_tiles;   // tiles in expert order, before sorting
     for (int e = threadIdx.x; e < E; e += blockDim.x) s_count[e] = 0;
     __syncthreads();
     for (int p = threadIdx.x; p < P; p += blockDim.x) {
@@ -77,11 +80,15 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
         for (int e = 0; e < E; e++) {
             s_off[e] = run;
             const int c = s_count[e];
+            const int b = bits[e];
             for (int m0 = 0; m0 < c; m0 += tile_m) {
-                pp.tiles[4 * nt + 0] = e;
-                pp.tiles[4 * nt + 1] = run + m0;
-                pp.tiles[4 * nt + 2] = min(tile_m, c - m0);
-                pp.tiles[4 * nt + 3] = 0;
+                const int rows = min(tile_m, c - m0);
+                draft[4 * nt + 0] = e;
+                draft[4 * nt + 1] = run + m0;
+                draft[4 * nt + 2] = rows;
+                // cost key: 32-token fragments first (MFMA work), then quantised before bf16
+                // (dequantisation costs the same whatever the number of tokens)
+                draft[4 * nt + 3] = 4 * ((rows + 31) >> 5) + (b == 4 ? 2 : (b == 2 ? 1 : 0));
                 nt++;
             }
             run += c;
@@ -89,8 +96,25 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
         s_off[E] = run;
         pp.ntiles[0] = nt;
         pp.ntiles[1] = run;
+        s_nt = nt;
     }
     __syncthreads();
+    // Longest first: workgroups are dispatched in tile order, so the cheap tiles
+    // (few tokens) fill the end of the launch instead of stretching it.
+    // Rank by counting, (key descending, position ascending): a permutation.
+    const int nt_all = s_nt;
+    for (int i = threadIdx.x; i < nt_all; i += blockDim.x) {
+        const int key = draft[4 * i + 3];
+        int pos = 0;
+        for (int j = 0; j < nt_all; j++) {
+            const int kj = draft[4 * j + 3];
+            pos += (kj > key || (kj == key && j < i)) ? 1 : 0;
+        }
+        pp.tiles[4 * pos + 0] = draft[4 * i + 0];
+        pp.tiles[4 * pos + 1] = draft[4 * i + 1];
+        pp.tiles[4 * pos + 2] = draft[4 * i + 2];
+        pp.tiles[4 * pos + 3] = key;
+    }
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         pp.counts[e] = s_count[e];
         pp.offsets[e] = s_off[e];
@@ -647,7 +671,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     int32_t* plan = reinterpret_cast<int32_t*>(ws + L.plan);
     const uint16_t* xb = (const uint16_t*)x;
 
-    dymoe_launch(ctx, DYMOE_K_PLAN, plan_kernel, dim3(1), dim3(1024), 0, st, idx, bits, P, E, kGemmTileM, plan);
+    dymoe_launch(ctx, DYMOE_K_PLAN, plan_kernel, dim3(1), dim3(1024), 0, st, idx, bits, P, E, kGemmTileM, L.max_tiles, plan);
     DYMOE_HIP_LAUNCH_CHECK();
     const long n16 = (long)T * H / 16;
     hipLaunchKernelGGL(prep_x_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, xb, n16, xh4, xh2);

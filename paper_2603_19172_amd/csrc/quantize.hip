@@ -204,24 +204,31 @@ __global__ __launch_bounds__(256) void pack_tiles_kernel(const uint16_t* __restr
 }
 
 // Worklist of a layer: the experts whose assigned width is 4 or 2 bits (and
-// that have load, when load is given).  list[0] = count, list[1..] = experts.
-__global__ __launch_bounds__(DYMOE_MAX_EXPERTS) void quantize_worklist_kernel(
-    const uint8_t* __restrict__ bits, const int32_t* __restrict__ load, int E,
-    int32_t* __restrict__ list)
+// that have load, when load is given), in ascending order.  Every workgroup
+// builds its own copy in LDS with its first wavefront (ballot + prefix count),
+// so no separate launch and no global buffer is needed.  Returns the count.
+__device__ __forceinline__ int build_worklist(const uint8_t* __restrict__ bits,
+                                              const int32_t* __restrict__ load, int E,
+                                              int16_t* list, int* count)
 {
-    __shared__ int32_t flags[DYMOE_MAX_EXPERTS];
-    const int e = threadIdx.x;
-    if (e < E) {
-        const int b = bits[e];
-        flags[e] = ((b == 4 || b == 2) && (load == nullptr || load[e] > 0)) ? 1 : 0;
+    if (threadIdx.x < kWave) {
+        const int lane = threadIdx.x;
+        int n = 0;
+        for (int base = 0; base < E; base += kWave) {
+            const int e = base + lane;
+            bool need = false;
+            if (e < E) {
+                const int b = bits[e];
+                need = (b == 4 || b == 2) && (load == nullptr || load[e] > 0);
+            }
+            const unsigned long long mask = __ballot(need);
+            if (need) list[n + __popcll(mask & ((1ull << lane) - 1ull))] = (int16_t)e;
+            n += __popcll(mask);
+        }
+        if (lane == 0) *count = n;
     }
     __syncthreads();
-    if (e == 0) {
-        int n = 0;
-        for (int i = 0; i < E; i++)
-            if (flags[i]) list[1 + n++] = i;
-        list[0] = n;
-    }
+    return *count;
 }
 
 // A fixed-size grid walks (expert of the worklist, matrix, block) units, so no
@@ -230,17 +237,20 @@ __global__ __launch_bounds__(DYMOE_MAX_EXPERTS) void quantize_worklist_kernel(
 template <int LAYOUT>
 __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
     const dymoe_expert_fmt* __restrict__ table, const uint8_t* __restrict__ bits,
-    const int32_t* __restrict__ list, int H, int F)
+    const int32_t* __restrict__ load, int E, int H, int F)
 {
+    __shared__ int16_t list[DYMOE_MAX_EXPERTS];
+    __shared__ int n_list;
+    const int n_work = build_worklist(bits, load, E, list, &n_list);
     const long n_elems = (long)H * (long)F;
     // row-major: 8192 elements per block; tiles: 4 tiles (one per wavefront) = 16384 elements
     constexpr long kPerBlock = (LAYOUT == DYMOE_LAYOUT_TILE) ? 4 * 4096 : kQElemsPerBlock;
     const long bpm = (n_elems + kPerBlock - 1) / kPerBlock;               // blocks per matrix
-    const long units = (long)list[0] * 3 * bpm;
+    const long units = (long)n_work * 3 * bpm;
     for (long u = blockIdx.x; u < units; u += gridDim.x) {
         const long item = u / bpm;
         const long blk = u - item * bpm;
-        const int e = list[1 + item / 3];
+        const int e = list[item / 3];
         const int mat = (int)(item % 3);
         const int b = bits[e];
         const dymoe_expert_fmt* ex = table + e;
@@ -300,10 +310,6 @@ int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const 
     if (group != 64 || E > DYMOE_MAX_EXPERTS) return DYMOE_ENOTSUP;
     if (!ctx) return DYMOE_ENOCTX;
     hipStream_t st = (hipStream_t)stream;
-    int32_t* list = reinterpret_cast<int32_t*>(ctx->scratch);
-    hipLaunchKernelGGL(dymoe::quantize_worklist_kernel, dim3(1), dim3((unsigned)(((E + 63) / 64) * 64)),
-                       0, st, bits, load, E, list);
-    DYMOE_HIP_LAUNCH_CHECK();
     const long n_elems = (long)H * (long)F;
     const long per_block = (layout == DYMOE_LAYOUT_TILE) ? 4 * 4096 : dymoe::kQElemsPerBlock;
     const long bpm = (n_elems + per_block - 1) / per_block;
@@ -312,10 +318,10 @@ int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const 
     if (grid > cap) grid = cap;
     if (layout == DYMOE_LAYOUT_TILE)
         dymoe_launch(ctx, DYMOE_K_QUANTIZE, dymoe::quantize_experts_kernel<DYMOE_LAYOUT_TILE>,
-                     dim3((unsigned)grid), dim3(dymoe::kQThreads), 0, st, table, bits, list, H, F);
+                     dim3((unsigned)grid), dim3(dymoe::kQThreads), 0, st, table, bits, load, E, H, F);
     else
         dymoe_launch(ctx, DYMOE_K_QUANTIZE, dymoe::quantize_experts_kernel<DYMOE_LAYOUT_ROWMAJOR>,
-                     dim3((unsigned)grid), dim3(dymoe::kQThreads), 0, st, table, bits, list, H, F);
+                     dim3((unsigned)grid), dim3(dymoe::kQThreads), 0, st, table, bits, load, E, H, F);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }

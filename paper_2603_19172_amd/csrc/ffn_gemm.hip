@@ -11,7 +11,9 @@
 //  * The token tile is shared by the 8 wavefronts through a double-buffered
 //    LDS tile; it is copied from a 16-bit copy of the activations that is
 //    already in the column order the code fields come out of a dword, so
-//    staging is a plain copy.
+//    staging is a plain copy: global memory -> LDS directly
+//    (global_load_lds_dwordx4), stored swizzled so that the operand reads are
+//    free of bank conflicts without padding.
 //  * bf16 experts: v_mfma_f32_32x32x16_bf16 on the bf16 activations.
 //    int4 / int2 experts: v_mfma_f32_32x32x16_f16 on an fp16 copy of the
 //    activations; weights become fp16 in registers: a code field OR-ed into the
@@ -29,7 +31,7 @@ namespace dymoe {
 constexpr int kGmThreads = 512;
 constexpr int kGmWaves = 8;
 constexpr int kBK = 128;            // K-tile
-constexpr int kLdsStride = 136;     // 16-bit elements per LDS row (128 + pad keeps 16-byte reads conflict free)
+constexpr int kXsBufBytes = kGemmTileM * kBK * 2;   // one token tile in LDS: 128 rows x 256 bytes, no padding
 
 // ----------------------------------------------------------------------------
 // plan: counting sort of the (token, slot) pairs by expert + tile list
@@ -329,6 +331,13 @@ __device__ __forceinline__ void load_strip(const StripSrc& src, int kt, StripRaw
     load_scale_zero<BITS>(src, kt, raw);
 }
 
+// 16 bytes of LDS at a byte address
+__device__ __forceinline__ uint4 lds_read16(uint32_t addr)
+{
+    const u32x4_t v = *(const __attribute__((address_space(3))) u32x4_t*)(uintptr_t)addr;
+    return __builtin_bit_cast(uint4, v);
+}
+
 // One K-tile of MFMAs for NTF token fragments (32 tokens each), and, woven into
 // it, the loads of the next K-tile: every weight register is refilled as soon as
 // the last MFMA that reads it has been issued, so the next tile's weights are in
@@ -336,19 +345,20 @@ __device__ __forceinline__ void load_strip(const StripSrc& src, int kt, StripRaw
 template <int BITS, int NTF>
 __device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>& rb,
                                               const StripSrc& sa, const StripSrc& sb, int kt_next,
-                                              const uint16_t (*xs)[kLdsStride], int ln, int kb,
-                                              float16_t (&acc)[2][NTF])
+                                              uint32_t xa, float16_t (&acc)[2][NTF])
 {
-    const uint16_t* base = &xs[ln][64 * kb];
 #pragma unroll
     for (int jj = 0; jj < 4; jj++) {
         uint4 a0, a1, b0, b1;
         strip_frags<BITS>(ra, jj, a0, a1);
         strip_frags<BITS>(rb, jj, b0, b1);
+        // the lane's two 16-byte chunks of this step, at their swizzled places
+        const uint32_t x0 = xa ^ (uint32_t)(jj << 5);
+        const uint32_t x1 = x0 ^ 16u;
 #pragma unroll
         for (int tf = 0; tf < NTF; tf++) {
-            const uint4* t = reinterpret_cast<const uint4*>(base + (32 * tf) * kLdsStride + 16 * jj);
-            const uint4 t0 = t[0], t1 = t[1];
+            const uint4 t0 = lds_read16(x0 + tf * (32 * kBK * 2));
+            const uint4 t1 = lds_read16(x1 + tf * (32 * kBK * 2));
             acc[0][tf] = mfma16<BITS>(a0, t0, acc[0][tf]);
             acc[1][tf] = mfma16<BITS>(b0, t0, acc[1][tf]);
             acc[0][tf] = mfma16<BITS>(a1, t1, acc[0][tf]);
@@ -374,22 +384,56 @@ __device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>
     load_scale_zero<BITS>(sb, kt_next, rb);
 }
 
-// the 64 bytes of the token tile one thread moves from global memory to LDS
-struct XTile {
-    uint4 v[4];
-};
-
-__device__ __forceinline__ void load_x(XTile& x, const uint16_t* __restrict__ src_row, int kt)
+// Global-memory instructions compute_ktile issues per call (every one of them
+// unconditional): the token-tile copies below are older than all of them, so
+// "at most this many memory operations still in flight" means the copies landed.
+template <int BITS>
+constexpr int ktile_loads()
 {
-#pragma unroll
-    for (int i = 0; i < 4; i++) x.v[i] = *reinterpret_cast<const uint4*>(src_row + kt * kBK + 8 * i);
+    return BITS == 16 ? 16 : (BITS == 4 ? 8 : 6);
 }
 
-__device__ __forceinline__ void store_x(const XTile& x, uint16_t (*xs)[kLdsStride], int srow, int sq)
+// ----------------------------------------------------------------------------
+// Token tile: global memory -> LDS without passing through registers.
+//
+// global_load_lds_dwordx4 writes the 16 bytes a lane fetched to
+// LDS[M0 + 16 * lane]: one instruction fills 1 KiB = 4 tile rows of 256 bytes.
+// The lane chooses WHAT it fetches, so the tile is stored swizzled for free:
+// row r keeps its 16-byte chunk c at chunk position c ^ (r & 15).  The MFMA
+// operand reads (lane = row, fixed c) then fall on 16 different chunk
+// positions for 16 consecutive rows, i.e. on all banks once.
+// Wavefront w fills rows 32 i + 4 w .. + 3 (i = 0 .. NTF-1); a thread's rows
+// all have the same r & 15, hence the same source chunk.
+// The instruction is issued from inline assembly so that the compiler does not
+// make every later LDS read wait for it; completion is awaited explicitly
+// (wait_tile_copies) before the workgroup barrier that publishes the tile.
+__device__ __forceinline__ void lds_copy16(const void* g, uint32_t lds_addr_lane0)
 {
-    uint4* dst = reinterpret_cast<uint4*>(&xs[srow][32 * sq]);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr_lane0), "v"(g)
+                 : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_tile_copies()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+template <int NTF>
+struct XStage {
+    const char* src[NTF];   // this thread's 16 bytes of K-tile 0 in each of its rows
+    uint32_t lds;           // LDS address of lane 0's slot of the wavefront's first unit, buffer 0
+};
+
+template <int NTF>
+__device__ __forceinline__ void copy_tile(const XStage<NTF>& st, int kt, int buf)
+{
 #pragma unroll
-    for (int i = 0; i < 4; i++) dst[i] = x.v[i];
+    for (int i = 0; i < NTF; i++)
+        lds_copy16(st.src[i] + (long)kt * (kBK * 2), st.lds + buf * kXsBufBytes + i * (32 * kBK * 2));
 }
 
 // ----------------------------------------------------------------------------
@@ -401,7 +445,7 @@ __device__ __forceinline__ void gemm_tile(
     const uint16_t* __restrict__ act,   // MODE 1: [T,K] activations (gathered); MODE 2: [P,K] intermediate
     const int32_t* __restrict__ perm, int k_route, const dymoe_expert_fmt& ex, int K, int N,
     int kt_begin, int kt_end, int row0, int rows, int nblock, uint16_t* __restrict__ hout,
-    float* __restrict__ oout, uint16_t (*xs)[kGemmTileM][kLdsStride])
+    float* __restrict__ oout, uint32_t xs_base)
 {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -436,36 +480,44 @@ __device__ __forceinline__ void gemm_tile(
 #pragma unroll
             for (int i = 0; i < 16; i++) acc[s][tf][i] = 0.0f;
 
-    // staging role: thread -> (row, quarter) of the token tile.  Tile rows past
-    // the expert's last token re-read its last token: their products are
-    // computed and dropped, and the loop stays branch-free.
-    const int srow = tid >> 2;
-    const int sq = tid & 3;
-    const int srow_c = min(srow, rows - 1);
-    const uint16_t* src_row;
-    if (MODE == 1) src_row = act + (long)(perm[row0 + srow_c] / k_route) * K;
-    else src_row = act + (long)(row0 + srow_c) * K;
-    src_row += 32 * sq;
-    XTile xv;
-    // K loop: the next token tile travels global -> registers -> other LDS
-    // buffer around the MFMAs; the next weights are requested inside them.
+    // staging role: rows 32 i + 4 wave + lane / 16, physical chunk lane % 16.
+    // Tile rows past the expert's last token re-read its last token: their
+    // products are computed and dropped, and the loop stays branch-free.
+    XStage<NTF> stage;
+    {
+        const int rb = 4 * wave + (lane >> 4);
+        const int chunk = (lane & 15) ^ (rb & 15);
+#pragma unroll
+        for (int i = 0; i < NTF; i++) {
+            const int r = min(32 * i + rb, rows - 1);
+            const long src_row = (MODE == 1) ? (long)(perm[row0 + r] / k_route) : (long)(row0 + r);
+            stage.src[i] = reinterpret_cast<const char*>(act + src_row * K) + 16 * chunk;
+        }
+        stage.lds = __builtin_amdgcn_readfirstlane(xs_base + wave * 1024);
+    }
+    // operand reads: lane (ln, kb) reads row 32 tf + ln, chunks 8 kb + 2 jj (+1)
+    uint32_t xa = xs_base + ln * (kBK * 2) + (((uint32_t)kb << 7) ^ ((uint32_t)(ln & 15) << 4));
+
+    // K loop: the next token tile is copied into the other LDS buffer while this
+    // one is multiplied; the next weights are requested inside the MFMA sequence.
     const StripSrc sa = strip_src<BITS>(ma, nt_a, K, lane);
     const StripSrc sb = strip_src<BITS>(mb, nt_b, K, lane);
     StripRaw<BITS> ra, rb;
-    load_x(xv, src_row, kt_begin);
+    copy_tile<NTF>(stage, kt_begin, 0);
     load_strip<BITS>(sa, kt_begin, ra);
     load_strip<BITS>(sb, kt_begin, rb);
-    store_x(xv, xs[0], srow, sq);
+    wait_tile_copies<0>();
     __syncthreads();
     int buf = 0;
     for (int kt = kt_begin; kt < kt_end; kt++) {
         // past the end the prefetches re-read the last tile instead of branching
         const int kn = min(kt + 1, kt_end - 1);
-        load_x(xv, src_row, kn);
-        compute_ktile<BITS, NTF>(ra, rb, sa, sb, kn, xs[buf], ln, kb, acc);
-        buf ^= 1;
-        store_x(xv, xs[buf], srow, sq);
+        copy_tile<NTF>(stage, kn, buf ^ 1);
+        compute_ktile<BITS, NTF>(ra, rb, sa, sb, kn, xa, acc);
+        wait_tile_copies<ktile_loads<BITS>()>();
         __syncthreads();
+        buf ^= 1;
+        xa ^= (uint32_t)kXsBufBytes;
     }
 
     // epilogue.  D layout: lane (ln, kb), register i -> weight row 8*(i/4) + 4*kb + i%4, token ln
@@ -563,8 +615,9 @@ __global__ __launch_bounds__(kGmThreads) void gemm_kernel(
     const int32_t* __restrict__ plan, int P, int E, int k_route, int H, int F,
     uint16_t* __restrict__ hbuf_out, float* __restrict__ opair)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t xs_raw[];
-    uint16_t (*xs)[kGemmTileM][kLdsStride] = reinterpret_cast<uint16_t (*)[kGemmTileM][kLdsStride]>(xs_raw);
+    // two token-tile buffers; the swizzle and the buffer toggle work on address bits
+    extern __shared__ __attribute__((aligned(65536))) uint16_t xs_raw[];
+    const uint32_t xs = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)xs_raw;
     const PlanPtrs pp = plan_ptrs(const_cast<int32_t*>(plan), E, P);
     const int tile = blockIdx.y;
     if (tile >= pp.ntiles[0]) return;
@@ -677,7 +730,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     hipLaunchKernelGGL(prep_x_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, xb, n16, xh4, xh2);
     DYMOE_HIP_LAUNCH_CHECK();
     // two token-tile buffers in LDS: more than the 64 KiB a kernel gets by default
-    constexpr size_t kLdsBytes = 2 * sizeof(uint16_t) * kGemmTileM * kLdsStride;
+    constexpr size_t kLdsBytes = 2 * (size_t)kXsBufBytes;
     static bool lds_attr_set = false;
     if (!lds_attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<1>),

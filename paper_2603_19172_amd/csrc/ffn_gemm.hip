@@ -315,10 +315,22 @@ template <int BITS>
 __device__ __forceinline__ void load_scale_zero(const StripSrc& src, int kt, StripRaw<BITS>& raw)
 {
     if constexpr (BITS != 16) {
-        const uint32_t s = load_global<uint16_t>(src.s + kt * 64);
-        const uint32_t z = load_global<uint16_t>(src.z + kt * 64);
-        raw.s2 = s | (s << 16);
-        raw.m2 = z | (z << 16);
+        // the 16-bit values as loaded; adopt_strip() duplicates them into both halves
+        raw.s2 = load_global<uint16_t>(src.s + kt * 64);
+        raw.m2 = load_global<uint16_t>(src.z + kt * 64);
+    }
+}
+
+// Make a freshly loaded strip the current one.  Touching the loaded values is
+// left to this point, a whole K-tile after the request, so nothing waits for a
+// load right after issuing it.
+template <int BITS>
+__device__ __forceinline__ void adopt_strip(StripRaw<BITS>& cur, const StripRaw<BITS>& next)
+{
+    cur = next;
+    if constexpr (BITS != 16) {
+        cur.s2 |= cur.s2 << 16;
+        cur.m2 |= cur.m2 << 16;
     }
 }
 
@@ -338,15 +350,23 @@ __device__ __forceinline__ uint4 lds_read16(uint32_t addr)
     return __builtin_bit_cast(uint4, v);
 }
 
-// One K-tile of MFMAs for NTF token fragments (32 tokens each), and, woven into
-// it, the loads of the next K-tile: every weight register is refilled as soon as
-// the last MFMA that reads it has been issued, so the next tile's weights are in
-// flight during this tile's arithmetic without a second set of registers.
+// One K-tile of MFMAs for NTF token fragments (32 tokens each).
+// bf16 (64 registers of raw weights per K-tile): the loads of the next K-tile
+// are woven into the sequence; every weight register is refilled as soon as
+// the last MFMA that reads it has been issued, so the next tile's weights are
+// in flight during three quarters of this tile's arithmetic without a second
+// set of registers.  The scheduling barriers keep that order (without them the
+// scheduler gathers the loads at the end of the tile, where their latency is
+// exposed): VALU, SALU and LDS reads may move across them, MFMAs and global
+// loads may not.
+// int4 / int2 (10 / 6 registers per strip): the next tile's codes were already
+// requested into a second register set before this call; nothing to load here.
 template <int BITS, int NTF>
 __device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>& rb,
                                               const StripSrc& sa, const StripSrc& sb, int kt_next,
                                               uint32_t xa, float16_t (&acc)[2][NTF])
 {
+    constexpr int kPinMask = 0x2 | 0x4 | 0x100;
 #pragma unroll
     for (int jj = 0; jj < 4; jj++) {
         uint4 a0, a1, b0, b1;
@@ -365,27 +385,18 @@ __device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>
             acc[1][tf] = mfma16<BITS>(b1, t1, acc[1][tf]);
         }
         if constexpr (BITS == 16) {
+            __builtin_amdgcn_sched_barrier(kPinMask);
             ra.r[2 * jj] = load_chunk<16>(sa, kt_next, 2 * jj);
             ra.r[2 * jj + 1] = load_chunk<16>(sa, kt_next, 2 * jj + 1);
             rb.r[2 * jj] = load_chunk<16>(sb, kt_next, 2 * jj);
             rb.r[2 * jj + 1] = load_chunk<16>(sb, kt_next, 2 * jj + 1);
-        } else if constexpr (BITS == 4) {
-            if (jj & 1) {
-                ra.r[jj >> 1] = load_chunk<4>(sa, kt_next, jj >> 1);
-                rb.r[jj >> 1] = load_chunk<4>(sb, kt_next, jj >> 1);
-            }
+            __builtin_amdgcn_sched_barrier(kPinMask);
         }
     }
-    if constexpr (BITS == 2) {
-        ra.r[0] = load_chunk<2>(sa, kt_next, 0);
-        rb.r[0] = load_chunk<2>(sb, kt_next, 0);
-    }
-    load_scale_zero<BITS>(sa, kt_next, ra);
-    load_scale_zero<BITS>(sb, kt_next, rb);
 }
 
-// Global-memory instructions compute_ktile issues per call (every one of them
-// unconditional): the token-tile copies below are older than all of them, so
+// Global-memory instructions issued per K-tile after the token-tile copies
+// (every one of them unconditional): the copies are older than all of them, so
 // "at most this many memory operations still in flight" means the copies landed.
 template <int BITS>
 constexpr int ktile_loads()
@@ -420,6 +431,11 @@ __device__ __forceinline__ void wait_tile_copies()
 {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+    // the same wait once more in a form the compiler's own bookkeeping reads
+    // (vmcnt = N, no wait on the export and LDS/scalar counters): it then knows
+    // that older loads have completed and does not wait for them again later,
+    // when such a wait would also cover copies issued in between
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
 template <int NTF>
@@ -506,6 +522,8 @@ __device__ __forceinline__ void gemm_tile(
     copy_tile<NTF>(stage, kt_begin, 0);
     load_strip<BITS>(sa, kt_begin, ra);
     load_strip<BITS>(sb, kt_begin, rb);
+    adopt_strip<BITS>(ra, ra);
+    adopt_strip<BITS>(rb, rb);
     wait_tile_copies<0>();
     __syncthreads();
     int buf = 0;
@@ -513,7 +531,20 @@ __device__ __forceinline__ void gemm_tile(
         // past the end the prefetches re-read the last tile instead of branching
         const int kn = min(kt + 1, kt_end - 1);
         copy_tile<NTF>(stage, kn, buf ^ 1);
-        compute_ktile<BITS, NTF>(ra, rb, sa, sb, kn, xa, acc);
+        if constexpr (BITS == 16) {
+            compute_ktile<BITS, NTF>(ra, rb, sa, sb, kn, xa, acc);
+        } else {
+            StripRaw<BITS> na, nb;
+            load_strip<BITS>(sa, kn, na);
+            load_strip<BITS>(sb, kn, nb);
+            __builtin_amdgcn_sched_barrier(0);   // keep the requests up here, a whole tile ahead of their use
+            compute_ktile<BITS, NTF>(ra, rb, sa, sb, kn, xa, acc);
+            adopt_strip<BITS>(ra, na);
+            adopt_strip<BITS>(rb, nb);
+            // finish the hand-over here, not after the next tile's requests
+            // (a wait placed there would also wait for the copies just issued)
+            __builtin_amdgcn_sched_barrier(0);
+        }
         wait_tile_copies<ktile_loads<BITS>()>();
         __syncthreads();
         buf ^= 1;

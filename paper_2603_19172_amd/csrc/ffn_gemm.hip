@@ -1,14 +1,14 @@
 // Prefill path of the mixed-precision SwiGLU expert FFN: tokens grouped by
 // expert, one MFMA grouped GEMM per projection, all experts in one launch.
 //
-// Work unit: up to 128 token rows of one expert x (8 wavefronts x 2 strips of
+// Work unit: up to 128 token rows of one expert x (4 wavefronts x 2 strips of
 // 32 weight rows), K walked in tiles of 128.
 //  * Weights never touch LDS.  They are stored in 32 x 128 tiles whose byte
 //    order is the MFMA A-operand order (lane (r, kb) owns row r, columns
 //    64 kb .. 64 kb + 64, one quantisation group), so every load instruction of
 //    a wavefront reads 1 KiB of contiguous memory straight into the registers
 //    the MFMA consumes (bf16) or the dequantiser consumes (int4 / int2).
-//  * The token tile is shared by the 8 wavefronts through a double-buffered
+//  * The token tile is shared by the 4 wavefronts through a double-buffered
 //    LDS tile; it is copied from a 16-bit copy of the activations that is
 //    already in the column order the code fields come out of a dword, so
 //    staging is a plain copy: global memory -> LDS directly
@@ -19,8 +19,10 @@
 //    activations; weights become fp16 in registers: a code field OR-ed into the
 //    mantissa of 2^n (n such that the field's lowest bit weighs one) is the
 //    number 2^n + q; subtracting 2^n is exact; then one packed fma(q, s, m).
-//  * Two wavefronts share a SIMD, so one's global-load and LDS waits are
-//    covered by the other's MFMA work.
+//  * A workgroup is four wavefronts, one per SIMD, and two workgroups share a
+//    compute unit: the two wavefronts of a SIMD belong to different workgroups,
+//    so one's barrier, waits, prologue and epilogue are covered by the other's
+//    MFMA work.
 #include <math.h>
 
 #include "common.hpp"
@@ -28,8 +30,8 @@
 
 namespace dymoe {
 
-constexpr int kGmThreads = 512;
-constexpr int kGmWaves = 8;
+constexpr int kGmThreads = 256;
+constexpr int kGmWaves = 4;         // one per SIMD; two workgroups share a compute unit
 constexpr int kBK = 128;            // K-tile
 constexpr int kXsBufBytes = kGemmTileM * kBK * 2;   // one token tile in LDS: 128 rows x 256 bytes, no padding
 
@@ -88,9 +90,10 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
                 draft[4 * nt + 0] = e;
                 draft[4 * nt + 1] = run + m0;
                 draft[4 * nt + 2] = rows;
-                // cost key: 32-token fragments first (MFMA work), then quantised before bf16
-                // (dequantisation costs the same whatever the number of tokens)
-                draft[4 * nt + 3] = 4 * ((rows + 31) >> 5) + (b == 4 ? 2 : (b == 2 ? 1 : 0));
+                // cost key, roughly the time a workgroup spends on the tile: streaming (bf16)
+                // or dequantising (int4, int2) the weights costs the same whatever the number
+                // of tokens; the MFMA work grows with the 32-token fragments
+                draft[4 * nt + 3] = (b == 16 ? 100 : (b == 4 ? 61 : 60)) + 10 * ((rows + 31) >> 5);
                 nt++;
             }
             run += c;
@@ -210,6 +213,16 @@ __device__ __forceinline__ MatPtr mat_ptr(const dymoe_expert_fmt& ex, int mat, i
     return m;
 }
 
+// (v & mask) | magic in one instruction.  With literal operands the compiler has
+// to emit two (the three-operand form takes no literals), so the mask is handed
+// over in a scalar register and the magic number in a vector register.
+__device__ __forceinline__ uint32_t and_or(uint32_t v, uint32_t mask, uint32_t magic)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "s"(mask), "v"(magic));
+    return r;
+}
+
 __device__ __forceinline__ uint32_t deq_pair(uint32_t biased, uint32_t bias2, uint32_t s2, uint32_t m2)
 {
     const half2_t q = __builtin_bit_cast(half2_t, biased) - __builtin_bit_cast(half2_t, bias2);  // exact
@@ -231,28 +244,28 @@ __device__ __forceinline__ void strip_frags(const StripRaw<BITS>& raw, int jj, u
         const uint32_t w1 = (jj & 1) ? q.w : q.y;
         // k order inside a fragment: 0,4,1,5,2,6,3,7
         uint32_t v = w0, v8 = w0 >> 8;
-        f0.x = deq_pair((v & 0x000F000Fu) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
-        f0.y = deq_pair((v & 0x00F000F0u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
-        f0.z = deq_pair((v8 & 0x000F000Fu) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
-        f0.w = deq_pair((v8 & 0x00F000F0u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
+        f0.x = deq_pair(and_or(v, 0x000F000Fu, 0x64006400u), 0x64006400u, raw.s2, raw.m2);
+        f0.y = deq_pair(and_or(v, 0x00F000F0u, 0x54005400u), 0x54005400u, raw.s2, raw.m2);
+        f0.z = deq_pair(and_or(v8, 0x000F000Fu, 0x64006400u), 0x64006400u, raw.s2, raw.m2);
+        f0.w = deq_pair(and_or(v8, 0x00F000F0u, 0x54005400u), 0x54005400u, raw.s2, raw.m2);
         v = w1; v8 = w1 >> 8;
-        f1.x = deq_pair((v & 0x000F000Fu) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
-        f1.y = deq_pair((v & 0x00F000F0u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
-        f1.z = deq_pair((v8 & 0x000F000Fu) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
-        f1.w = deq_pair((v8 & 0x00F000F0u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
+        f1.x = deq_pair(and_or(v, 0x000F000Fu, 0x64006400u), 0x64006400u, raw.s2, raw.m2);
+        f1.y = deq_pair(and_or(v, 0x00F000F0u, 0x54005400u), 0x54005400u, raw.s2, raw.m2);
+        f1.z = deq_pair(and_or(v8, 0x000F000Fu, 0x64006400u), 0x64006400u, raw.s2, raw.m2);
+        f1.w = deq_pair(and_or(v8, 0x00F000F0u, 0x54005400u), 0x54005400u, raw.s2, raw.m2);
     } else {
         const uint4 q = raw.r[0];
         const uint32_t v = (jj == 0) ? q.x : (jj == 1) ? q.y : (jj == 2) ? q.z : q.w;
         const uint32_t v10 = v >> 10;
         // 16 codes of the dword; k order 0,8,1,9,2,10,3,11 | 4,12,5,13,6,14,7,15
-        f0.x = deq_pair((v & 0x00030003u) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
-        f0.y = deq_pair((v & 0x000C000Cu) | 0x5C005C00u, 0x5C005C00u, raw.s2, raw.m2);
-        f0.z = deq_pair((v & 0x00300030u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
-        f0.w = deq_pair((v & 0x00C000C0u) | 0x4C004C00u, 0x4C004C00u, raw.s2, raw.m2);
-        f1.x = deq_pair((v & 0x03000300u) | 0x44004400u, 0x44004400u, raw.s2, raw.m2);
-        f1.y = deq_pair((v10 & 0x00030003u) | 0x64006400u, 0x64006400u, raw.s2, raw.m2);
-        f1.z = deq_pair((v10 & 0x000C000Cu) | 0x5C005C00u, 0x5C005C00u, raw.s2, raw.m2);
-        f1.w = deq_pair((v10 & 0x00300030u) | 0x54005400u, 0x54005400u, raw.s2, raw.m2);
+        f0.x = deq_pair(and_or(v, 0x00030003u, 0x64006400u), 0x64006400u, raw.s2, raw.m2);
+        f0.y = deq_pair(and_or(v, 0x000C000Cu, 0x5C005C00u), 0x5C005C00u, raw.s2, raw.m2);
+        f0.z = deq_pair(and_or(v, 0x00300030u, 0x54005400u), 0x54005400u, raw.s2, raw.m2);
+        f0.w = deq_pair(and_or(v, 0x00C000C0u, 0x4C004C00u), 0x4C004C00u, raw.s2, raw.m2);
+        f1.x = deq_pair(and_or(v, 0x03000300u, 0x44004400u), 0x44004400u, raw.s2, raw.m2);
+        f1.y = deq_pair(and_or(v10, 0x00030003u, 0x64006400u), 0x64006400u, raw.s2, raw.m2);
+        f1.z = deq_pair(and_or(v10, 0x000C000Cu, 0x5C005C00u), 0x5C005C00u, raw.s2, raw.m2);
+        f1.w = deq_pair(and_or(v10, 0x00300030u, 0x54005400u), 0x54005400u, raw.s2, raw.m2);
     }
 }
 
@@ -350,47 +363,61 @@ __device__ __forceinline__ uint4 lds_read16(uint32_t addr)
     return __builtin_bit_cast(uint4, v);
 }
 
-// One K-tile of MFMAs for NTF token fragments (32 tokens each).
+// The token operands of one MFMA step (two 16-byte chunks of one row).
+struct XOps {
+    uint4 t0, t1;
+};
+
+// Quarters JJ0 .. JJ1-1 of one K-tile of MFMAs for NTF token fragments (32 tokens each).
+// A step is one (quarter, fragment) pair: four MFMAs on two LDS chunks.  The
+// chunks of step s+1 are requested before the MFMAs of step s are issued, so the
+// LDS latency hides behind arithmetic; the operands of a tile's first step come
+// in through `ops`.  Scheduling barriers keep this order.
 // bf16 (64 registers of raw weights per K-tile): the loads of the next K-tile
 // are woven into the sequence; every weight register is refilled as soon as
 // the last MFMA that reads it has been issued, so the next tile's weights are
 // in flight during three quarters of this tile's arithmetic without a second
-// set of registers.  The scheduling barriers keep that order (without them the
-// scheduler gathers the loads at the end of the tile, where their latency is
-// exposed): VALU, SALU and LDS reads may move across them, MFMAs and global
-// loads may not.
+// set of registers.
 // int4 / int2 (10 / 6 registers per strip): the next tile's codes were already
 // requested into a second register set before this call; nothing to load here.
-template <int BITS, int NTF>
+template <int BITS, int NTF, int JJ0, int JJ1>
 __device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>& rb,
                                               const StripSrc& sa, const StripSrc& sb, int kt_next,
-                                              uint32_t xa, float16_t (&acc)[2][NTF])
+                                              uint32_t xa, XOps& ops, float16_t (&acc)[2][NTF])
 {
-    constexpr int kPinMask = 0x2 | 0x4 | 0x100;
+    constexpr int kStepMask = 0x2 | 0x4;            // VALU and SALU may cross; MFMA, LDS and global accesses may not
 #pragma unroll
-    for (int jj = 0; jj < 4; jj++) {
+    for (int jj = JJ0; jj < JJ1; jj++) {
         uint4 a0, a1, b0, b1;
         strip_frags<BITS>(ra, jj, a0, a1);
         strip_frags<BITS>(rb, jj, b0, b1);
-        // the lane's two 16-byte chunks of this step, at their swizzled places
-        const uint32_t x0 = xa ^ (uint32_t)(jj << 5);
-        const uint32_t x1 = x0 ^ 16u;
 #pragma unroll
         for (int tf = 0; tf < NTF; tf++) {
-            const uint4 t0 = lds_read16(x0 + tf * (32 * kBK * 2));
-            const uint4 t1 = lds_read16(x1 + tf * (32 * kBK * 2));
-            acc[0][tf] = mfma16<BITS>(a0, t0, acc[0][tf]);
-            acc[1][tf] = mfma16<BITS>(b0, t0, acc[1][tf]);
-            acc[0][tf] = mfma16<BITS>(a1, t1, acc[0][tf]);
-            acc[1][tf] = mfma16<BITS>(b1, t1, acc[1][tf]);
+            // next step: next fragment, else next quarter (nothing after the tile's last step)
+            const bool wrap = (tf == NTF - 1);
+            const bool last = wrap && jj == 3;
+            const int njj = wrap ? jj + 1 : jj;
+            const int ntf = wrap ? 0 : tf + 1;
+            XOps nxt = ops;
+            if (!last) {
+                const uint32_t x0 = (xa ^ (uint32_t)(njj << 5)) + ntf * (32 * kBK * 2);
+                nxt.t0 = lds_read16(x0);
+                nxt.t1 = lds_read16(x0 ^ 16u);
+            }
+            __builtin_amdgcn_sched_barrier(kStepMask);
+            acc[0][tf] = mfma16<BITS>(a0, ops.t0, acc[0][tf]);
+            acc[1][tf] = mfma16<BITS>(b0, ops.t0, acc[1][tf]);
+            acc[0][tf] = mfma16<BITS>(a1, ops.t1, acc[0][tf]);
+            acc[1][tf] = mfma16<BITS>(b1, ops.t1, acc[1][tf]);
+            ops = nxt;
+            __builtin_amdgcn_sched_barrier(kStepMask);
         }
         if constexpr (BITS == 16) {
-            __builtin_amdgcn_sched_barrier(kPinMask);
             ra.r[2 * jj] = load_chunk<16>(sa, kt_next, 2 * jj);
             ra.r[2 * jj + 1] = load_chunk<16>(sa, kt_next, 2 * jj + 1);
             rb.r[2 * jj] = load_chunk<16>(sb, kt_next, 2 * jj);
             rb.r[2 * jj + 1] = load_chunk<16>(sb, kt_next, 2 * jj + 1);
-            __builtin_amdgcn_sched_barrier(kPinMask);
+            __builtin_amdgcn_sched_barrier(kStepMask);
         }
     }
 }
@@ -418,11 +445,12 @@ constexpr int ktile_loads()
 // The instruction is issued from inline assembly so that the compiler does not
 // make every later LDS read wait for it; completion is awaited explicitly
 // (wait_tile_copies) before the workgroup barrier that publishes the tile.
-__device__ __forceinline__ void lds_copy16(const void* g, uint32_t lds_addr_lane0)
+__device__ __forceinline__ void lds_copy16(const char* base, uint32_t lane_offset, uint32_t lds_addr_lane0)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+    // base is the same for the whole wavefront (scalar registers), lane_offset an unsigned 32-bit byte offset
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_addr_lane0), "v"(g)
+                 : "s"(lds_addr_lane0), "v"(lane_offset), "s"(base)
                  : "memory");
 }
 
@@ -438,18 +466,23 @@ __device__ __forceinline__ void wait_tile_copies()
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+constexpr int kRowsPerCopy = 4 * kGmWaves;      // tile rows the workgroup fills with one instruction per wavefront
+
 template <int NTF>
 struct XStage {
-    const char* src[NTF];   // this thread's 16 bytes of K-tile 0 in each of its rows
-    uint32_t lds;           // LDS address of lane 0's slot of the wavefront's first unit, buffer 0
+    static constexpr int kCopies = 32 * NTF / kRowsPerCopy;
+    const char* base;            // start of the activation matrix (the same in every lane)
+    uint32_t off[kCopies];       // byte offset of this thread's 16 bytes of K-tile 0 in each of its rows
+    uint32_t lds;                // LDS address of lane 0's slot of the wavefront's first unit, buffer 0
 };
 
 template <int NTF>
 __device__ __forceinline__ void copy_tile(const XStage<NTF>& st, int kt, int buf)
 {
+    const char* base = st.base + (long)kt * (kBK * 2);
 #pragma unroll
-    for (int i = 0; i < NTF; i++)
-        lds_copy16(st.src[i] + (long)kt * (kBK * 2), st.lds + buf * kXsBufBytes + i * (32 * kBK * 2));
+    for (int i = 0; i < XStage<NTF>::kCopies; i++)
+        lds_copy16(base, st.off[i], st.lds + buf * kXsBufBytes + i * (kRowsPerCopy * kBK * 2));
 }
 
 // ----------------------------------------------------------------------------
@@ -496,7 +529,7 @@ __device__ __forceinline__ void gemm_tile(
 #pragma unroll
             for (int i = 0; i < 16; i++) acc[s][tf][i] = 0.0f;
 
-    // staging role: rows 32 i + 4 wave + lane / 16, physical chunk lane % 16.
+    // staging role: rows 16 i + 4 wave + lane / 16, physical chunk lane % 16.
     // Tile rows past the expert's last token re-read its last token: their
     // products are computed and dropped, and the loop stays branch-free.
     XStage<NTF> stage;
@@ -504,18 +537,22 @@ __device__ __forceinline__ void gemm_tile(
         const int rb = 4 * wave + (lane >> 4);
         const int chunk = (lane & 15) ^ (rb & 15);
 #pragma unroll
-        for (int i = 0; i < NTF; i++) {
-            const int r = min(32 * i + rb, rows - 1);
+        for (int i = 0; i < XStage<NTF>::kCopies; i++) {
+            const int r = min(kRowsPerCopy * i + rb, rows - 1);
             const long src_row = (MODE == 1) ? (long)(perm[row0 + r] / k_route) : (long)(row0 + r);
-            stage.src[i] = reinterpret_cast<const char*>(act + src_row * K) + 16 * chunk;
+            stage.off[i] = (uint32_t)(src_row * K * 2 + 16 * chunk);     // < 4 GiB, checked by the launcher
         }
+        stage.base = reinterpret_cast<const char*>(act);
         stage.lds = __builtin_amdgcn_readfirstlane(xs_base + wave * 1024);
     }
     // operand reads: lane (ln, kb) reads row 32 tf + ln, chunks 8 kb + 2 jj (+1)
-    uint32_t xa = xs_base + ln * (kBK * 2) + (((uint32_t)kb << 7) ^ ((uint32_t)(ln & 15) << 4));
+    const uint32_t xa0 = xs_base + ln * (kBK * 2) + (((uint32_t)kb << 7) ^ ((uint32_t)(ln & 15) << 4));
+    uint32_t xa = xa0;
 
-    // K loop: the next token tile is copied into the other LDS buffer while this
-    // one is multiplied; the next weights are requested inside the MFMA sequence.
+    // K loop over two LDS buffers: the next token tile is copied into the other
+    // buffer while this one is multiplied.  The two workgroups of a compute unit
+    // run independently, so one's barrier, prologue and epilogue overlap the
+    // other's arithmetic.
     const StripSrc sa = strip_src<BITS>(ma, nt_a, K, lane);
     const StripSrc sb = strip_src<BITS>(mb, nt_b, K, lane);
     StripRaw<BITS> ra, rb;
@@ -526,19 +563,22 @@ __device__ __forceinline__ void gemm_tile(
     adopt_strip<BITS>(rb, rb);
     wait_tile_copies<0>();
     __syncthreads();
-    int buf = 0;
+    int buf = 0;          // buffer of tile kt
     for (int kt = kt_begin; kt < kt_end; kt++) {
         // past the end the prefetches re-read the last tile instead of branching
         const int kn = min(kt + 1, kt_end - 1);
         copy_tile<NTF>(stage, kn, buf ^ 1);
-        if constexpr (BITS == 16) {
-            compute_ktile<BITS, NTF>(ra, rb, sa, sb, kn, xa, acc);
-        } else {
-            StripRaw<BITS> na, nb;
+        StripRaw<BITS> na, nb;
+        if constexpr (BITS != 16) {
             load_strip<BITS>(sa, kn, na);
             load_strip<BITS>(sb, kn, nb);
             __builtin_amdgcn_sched_barrier(0);   // keep the requests up here, a whole tile ahead of their use
-            compute_ktile<BITS, NTF>(ra, rb, sa, sb, kn, xa, acc);
+        }
+        XOps ops;             // operands of the first step
+        ops.t0 = lds_read16(xa);
+        ops.t1 = lds_read16(xa ^ 16u);
+        compute_ktile<BITS, NTF, 0, 4>(ra, rb, sa, sb, kn, xa, ops, acc);
+        if constexpr (BITS != 16) {
             adopt_strip<BITS>(ra, na);
             adopt_strip<BITS>(rb, nb);
             // finish the hand-over here, not after the next tile's requests
@@ -639,7 +679,7 @@ __device__ __forceinline__ void gemm_tile(
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kGmThreads) void gemm_kernel(
+__global__ __launch_bounds__(kGmThreads, 2) void gemm_kernel(
     const uint16_t* __restrict__ x_bf16, const uint16_t* __restrict__ x_h4,
     const uint16_t* __restrict__ x_h2, const uint16_t* __restrict__ hbuf_in,
     const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table,
@@ -747,6 +787,8 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
 {
     const FfnLayout L = ffn_layout(T, H, F, E, k);
     const int P = T * k;
+    // the token-tile copies address a row through an unsigned 32-bit byte offset
+    if ((size_t)T * H * 2 >= ((size_t)1 << 32) || (size_t)P * F * 2 >= ((size_t)1 << 32)) return DYMOE_ENOTSUP;
     char* ws = (char*)workspace;
     uint16_t* hbuf = reinterpret_cast<uint16_t*>(ws + L.hbuf);   // [P,F] 16-bit
     uint16_t* xh4 = reinterpret_cast<uint16_t*>(ws + L.xh);      // [T,H] fp16, int4 column order
@@ -760,7 +802,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const long n16 = (long)T * H / 16;
     hipLaunchKernelGGL(prep_x_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, xb, n16, xh4, xh2);
     DYMOE_HIP_LAUNCH_CHECK();
-    // two token-tile buffers in LDS: more than the 64 KiB a kernel gets by default
+    // two token-tile buffers in LDS
     constexpr size_t kLdsBytes = 2 * (size_t)kXsBufBytes;
     static bool lds_attr_set = false;
     if (!lds_attr_set) {
@@ -782,7 +824,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     // outputs; the combine kernel adds the slabs in a fixed order.
     const int nblk2 = (H + cols2 - 1) / cols2;
     const long est_blocks = (long)nblk2 * ((long)P / kGemmTileM + (E < P ? E : P) / 2 + 1);
-    int splits = (int)((2L * ctx->num_cu + est_blocks - 1) / est_blocks);
+    int splits = (int)((4L * ctx->num_cu + est_blocks - 1) / est_blocks);
     const int max_splits = (F + kSeg - 1) / kSeg;     // slabs the workspace holds
     if (splits > max_splits) splits = max_splits;
     if (splits > 8) splits = 8;

@@ -145,7 +145,7 @@ def main():
     ffn_bytes = sum(3.0 * H * F * bytes_per_weight(b) for b in active_bits)
 
     # ---------------------------------------------------------------- per-kernel timing (eager, HIP events)
-    kernels = ["route", "importance", "assign", "quantize", "gemv_phase1", "gemv_phase2", "gemv_combine"]
+    kernels = ["decode_front", "quantize", "gemv_phase1", "gemv_phase2", "gemv_combine"]
     ctx.timing_enable(kernels)
     n_timed = min(args.steps, 100)
     for i in range(n_timed):

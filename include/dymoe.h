@@ -64,6 +64,7 @@ extern "C" {
 #define DYMOE_LAYOUT_TILE 1     /* 32-row x 128-column tiles: what the GEMM path reads */
 
 #define DYMOE_MAX_TIERS 8
+#define DYMOE_FRONT_MAX_TOKENS 16   /* tokens per step of dymoe_decode_front */
 #define DYMOE_MAX_EXPERTS 1024
 
 /* opaque; holds the device ordinal, its properties and 64 KiB of device scratch
@@ -188,6 +189,22 @@ int dymoe_assign_precision(dymoe_ctx* ctx, int phase, const void* importance,
                            uint8_t* bits, int32_t* rank, void* stream);
 
 /*
+ * Decode-step front end: dymoe_route_topk, dymoe_expert_importance (decode
+ * phase: importance = gate score, Sec. 4.2.2 Eq. 3) and dymoe_assign_precision
+ * (Sec. 4.3, Sec. 5) in ONE launch, for steps of 1 <= T <= DYMOE_FRONT_MAX_TOKENS
+ * tokens, where three dependent launches of microseconds each would cost more
+ * than their work.  Arguments have the meaning, layout and limits they have in
+ * the three calls (importance: [E] fp32; probs may be NULL; rank may be NULL;
+ * tier_count / tier_bits: host arrays read before the launch), and every
+ * output is bit for bit what the three calls in turn produce.
+ */
+int dymoe_decode_front(dymoe_ctx* ctx, const void* x, const void* wg, const float* bias,
+                       int T, int H, int E, int k, int renorm, int n_tiers,
+                       const int32_t* tier_count, const uint8_t* tier_bits, int floor_bits,
+                       int32_t* idx, float* w, float* probs, float* importance, int32_t* load,
+                       uint8_t* bits, int32_t* rank, void* stream);
+
+/*
  * Group-wise asymmetric quantize-and-pack of one matrix (the paper, Sec. 5,
  * quantizes expert weights only and leaves the base quantizer exchangeable;
  * this is round-to-nearest with the group minimum as zero point).
@@ -267,9 +284,9 @@ int dymoe_stream_copy(dymoe_ctx* ctx, const void* src, void* dst, size_t bytes, 
  * Per-kernel timing (diagnostic; the paper reports only end-to-end latency,
  * Sec. 6.1 "Key Metrics", so these serve the roofline accounting).
  * dymoe_timing_enable: launches of the kernels whose bit is set in kernel_mask
- * (bit i = kernel id i, ids 0..12 in the order route, token_norm, importance,
+ * (bit i = kernel id i, ids 0..13 in the order route, token_norm, importance,
  * assign, quantize, gemv_phase1, gemv_phase2, gemv_combine, plan, gemm1, gemm2,
- * gemm_combine, stream_copy) carry a start and a stop HIP event on the dispatch itself, so
+ * gemm_combine, stream_copy, decode_front) carry a start and a stop HIP event on the dispatch itself, so
  * the interval is the kernel's execution time on the launch stream; 0 switches
  * timing off.  Either way, records not yet read are dropped.
  * dymoe_timing_read: waits for the recorded launches of `kernel`, returns

@@ -23,6 +23,7 @@ lib = C.CDLL(LIB_PATH)
 
 OK, EINVAL, ENOSPC, EHIP, ENOTSUP, ENOCTX = 0, -1, -2, -3, -4, -5
 PHASE_PREFILL, PHASE_DECODE = 0, 1
+FRONT_MAX_TOKENS = 16
 OUT_BF16, OUT_F32 = 0, 1
 PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
 LAYOUT_ROWMAJOR, LAYOUT_TILE = 0, 1
@@ -33,11 +34,12 @@ EXPORTS = [
     "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_expert_importance",
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
     "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_moe_ffn_mixed", "dymoe_stream_copy",
+    "dymoe_decode_front",
     "dymoe_timing_enable", "dymoe_timing_read", "dymoe_kernel_name",
 ]
 
 KERNELS = ["route", "token_norm", "importance", "assign", "quantize", "gemv_phase1",
-           "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine", "stream_copy"]
+           "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine", "stream_copy", "decode_front"]
 
 
 class ExpertFmt(C.Structure):
@@ -56,6 +58,9 @@ lib.dymoe_strerror.restype = C.c_char_p
 lib.dymoe_strerror.argtypes = [_i]
 lib.dymoe_workspace_bytes.restype = _sz
 lib.dymoe_workspace_bytes.argtypes = [_i] * 5
+lib.dymoe_decode_front.restype = _i
+lib.dymoe_decode_front.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _i,
+                                   _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.dymoe_stream_copy.restype = _i
 lib.dymoe_stream_copy.argtypes = [_vp, _vp, _vp, _sz, _vp]
 lib.dymoe_route_topk.restype = _i
@@ -139,7 +144,8 @@ class Context:
         self.device = device
 
     def close(self):
-        if getattr(self, "_h", None):
+        # at interpreter shutdown the module globals may already be gone
+        if getattr(self, "_h", None) and lib is not None:
             lib.dymoe_destroy(self._h)
             self._h = None
 
@@ -210,6 +216,29 @@ class Context:
                                           _ptr(bits), _ptr(rank), _stream(stream)),
                "dymoe_assign_precision")
         return bits, rank
+
+    # -- S1 + S2 + S3 of a decode step in one launch
+    def decode_front(self, x, wg, bias, k, tier_count, tier_bits, floor_bits=0, renorm=True,
+                     stream=None):
+        T, H = x.shape
+        E = wg.shape[0]
+        dev = x.device
+        n = len(tier_count)
+        tc = (C.c_int32 * n)(*[int(v) for v in tier_count])
+        tb = (C.c_uint8 * n)(*[int(v) for v in tier_bits])
+        idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+        w = torch.empty((T, k), dtype=torch.float32, device=dev)
+        probs = torch.empty((T, E), dtype=torch.float32, device=dev)
+        imp = torch.empty((E,), dtype=torch.float32, device=dev)
+        load = torch.empty((E,), dtype=torch.int32, device=dev)
+        bits = torch.empty((E,), dtype=torch.uint8, device=dev)
+        rank = torch.empty((E,), dtype=torch.int32, device=dev)
+        _check(lib.dymoe_decode_front(self._h, _ptr(x, torch.bfloat16), _ptr(wg, torch.bfloat16),
+                                      _ptr(bias, torch.float32), T, H, E, k, 1 if renorm else 0, n,
+                                      C.cast(tc, _vp), C.cast(tb, _vp), floor_bits, _ptr(idx), _ptr(w),
+                                      _ptr(probs), _ptr(imp), _ptr(load), _ptr(bits), _ptr(rank),
+                                      _stream(stream)), "dymoe_decode_front")
+        return idx, w, probs, imp, load, bits, rank
 
     # -- S4
     def quantize_pack(self, w, bits, group=64, out=None, stream=None):

@@ -129,6 +129,7 @@ const char* dymoe_kernel_name(int kernel)
     case DYMOE_K_GEMM2: return "gemm_kernel<2>";
     case DYMOE_K_GEMM_COMBINE: return "gemm_combine_kernel";
     case DYMOE_K_STREAM_COPY: return "stream_copy_kernel";
+    case DYMOE_K_DECODE_FRONT: return "decode_front_kernel";
     default: return nullptr;
     }
 }

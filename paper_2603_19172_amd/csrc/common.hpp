@@ -24,6 +24,7 @@ enum {
     DYMOE_K_GEMM2,
     DYMOE_K_GEMM_COMBINE,
     DYMOE_K_STREAM_COPY,
+    DYMOE_K_DECODE_FRONT,
     DYMOE_K_COUNT
 };
 

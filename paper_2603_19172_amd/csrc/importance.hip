@@ -2,6 +2,7 @@
 // importance-ranked bit-width assignment.  Both are tiny: integer histograms
 // and an E x E ranking, sized for one or a few workgroups.
 #include "common.hpp"
+#include "assign.hpp"
 
 namespace dymoe {
 
@@ -127,14 +128,7 @@ __global__ void importance_decode_kernel(const float* __restrict__ probs, int T,
     importance[e] = (T == 1) ? s : s / (float)T;
 }
 
-struct TierTable {
-    int n;
-    int32_t count[DYMOE_MAX_TIERS];
-    uint8_t bits[DYMOE_MAX_TIERS];
-};
-
-// One workgroup; thread e counts the experts that precede expert e in the
-// order (importance desc, load desc, index asc) -> rank -> tier -> bits.
+// One workgroup; thread e ranks expert e.
 template <typename ImpT>
 __global__ __launch_bounds__(DYMOE_MAX_EXPERTS) void assign_precision_kernel(
     const ImpT* __restrict__ importance, const int32_t* __restrict__ load, int E, TierTable tiers,
@@ -149,24 +143,7 @@ __global__ __launch_bounds__(DYMOE_MAX_EXPERTS) void assign_precision_kernel(
     }
     __syncthreads();
     if (e >= E) return;
-    const ImpT mi = s_imp[e];
-    const int32_t ml = s_load[e];
-    int pos = 0;
-    for (int j = 0; j < E; j++) {
-        const ImpT oi = s_imp[j];
-        const int32_t ol = s_load[j];
-        const bool first = (oi > mi) || (oi == mi && (ol > ml || (ol == ml && j < e)));
-        pos += first ? 1 : 0;
-    }
-    int tier = 0, upto = tiers.count[0];
-    while (pos >= upto && tier + 1 < tiers.n) {
-        tier++;
-        upto += tiers.count[tier];
-    }
-    int b = tiers.bits[tier];
-    if (b < floor_bits) b = floor_bits;
-    bits[e] = (uint8_t)b;
-    if (rank) rank[e] = pos;
+    assign_one<ImpT>(e, E, s_imp, s_load, tiers, floor_bits, bits, rank);
 }
 
 }  // namespace dymoe
@@ -225,21 +202,7 @@ int dymoe_assign_precision(dymoe_ctx* ctx, int phase, const void* importance,
     DYMOE_REQUIRE(E > 0 && n_tiers >= 1 && n_tiers <= DYMOE_MAX_TIERS);
     DYMOE_REQUIRE(floor_bits == 0 || floor_bits == 2 || floor_bits == 4 || floor_bits == 16);
     dymoe::TierTable tt;
-    tt.n = n_tiers;
-    long total = 0;
-    for (int i = 0; i < DYMOE_MAX_TIERS; i++) {
-        tt.count[i] = 0;
-        tt.bits[i] = 0;
-    }
-    for (int i = 0; i < n_tiers; i++) {
-        const int b = tier_bits[i];
-        DYMOE_REQUIRE(tier_count[i] >= 0);
-        DYMOE_REQUIRE(b == 0 || b == 2 || b == 4 || b == 16);
-        tt.count[i] = tier_count[i];
-        tt.bits[i] = (uint8_t)b;
-        total += tier_count[i];
-    }
-    DYMOE_REQUIRE(total == E);
+    DYMOE_REQUIRE(dymoe::make_tier_table(E, n_tiers, tier_count, tier_bits, tt) == DYMOE_OK);
     if (E > DYMOE_MAX_EXPERTS) return DYMOE_ENOTSUP;
     if (!ctx) return DYMOE_ENOCTX;
     hipStream_t st = (hipStream_t)stream;

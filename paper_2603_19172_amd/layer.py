@@ -103,13 +103,27 @@ class MoELayer:
                                            self.y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, st),
                  "dymoe_moe_ffn_mixed")
 
-    def step(self, x, wg, bias, store, quantize=True, stream=None):
+    def front(self, x, wg, bias, st):
+        """S1 + S2 + S3 of a small decode step in one launch."""
+        B._check(B.lib.dymoe_decode_front(self.ctx._h, x.data_ptr(), wg.data_ptr(),
+                                          bias.data_ptr() if bias is not None else None, self.T, self.H,
+                                          self.E, self.k, 1, self._nt, C.cast(self._tc, C.c_void_p),
+                                          C.cast(self._tb, C.c_void_p), self.floor_bits,
+                                          self.idx.data_ptr(), self.gate.data_ptr(), self.probs.data_ptr(),
+                                          self.imp.data_ptr(), self.load.data_ptr(), self.bits.data_ptr(),
+                                          self.rank.data_ptr(), st), "dymoe_decode_front")
+
+    def step(self, x, wg, bias, store, quantize=True, stream=None, fused_front=True):
         """The whole hot path for one batch.  quantize=False assumes the formats
-        the assignment selects are already materialised in `store`."""
+        the assignment selects are already materialised in `store`.  Small decode
+        steps take the single-launch front end unless fused_front is False."""
         st = B._stream(stream)
-        self.route(x, wg, bias, st)
-        self.importance(x, st)
-        self.assign(st)
+        if fused_front and self.phase == B.PHASE_DECODE and self.T <= B.FRONT_MAX_TOKENS:
+            self.front(x, wg, bias, st)
+        else:
+            self.route(x, wg, bias, st)
+            self.importance(x, st)
+            self.assign(st)
         if quantize:
             self.quantize(store, st)
         self.ffn(x, store, st)

@@ -415,6 +415,43 @@ def test_chained_layer_tiny(ctx):
     assert err <= FFN_TOL
 
 
+# ------------------------------------------------------------------ fused decode front end
+
+@pytest.mark.parametrize("T,H,E,k,tiers", [(1, 256, 8, 2, (2, 3, 3)), (1, 4096, 8, 2, (1, 3, 4)),
+                                            (3, 512, 128, 8, (13, 39, 76)), (16, 6144, 40, 4, (4, 12, 24))])
+def test_decode_front_equals_the_three_calls_and_the_oracle(ctx, T, H, E, k, tiers):
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=T, H=H, E=E, k=k, phase="decode", config_id=70 + T)
+    x, _ = synth.activations(cfg)
+    wg, _ = synth.router(cfg)
+    bias = (np.linspace(-0.3, 0.3, E).astype(np.float32)) if E > 8 else None
+    xd, wgd = to_bf16(x), to_bf16(wg)
+    bd = torch.from_numpy(bias).to(DEV) if bias is not None else None
+    tier_bits = (16, 4, 2)
+    idx, w, p, imp, load, bits, rank = ctx.decode_front(xd, wgd, bd, k, tiers, tier_bits)
+    sync()
+    # bit for bit the same as the stand-alone entry points
+    idx2, w2, p2 = ctx.route_topk(xd, wgd, bd, k)
+    imp2, load2 = ctx.expert_importance(B.PHASE_DECODE, idx2, E, probs=p2)
+    bits2, rank2 = ctx.assign_precision(B.PHASE_DECODE, imp2, load2, tiers, tier_bits)
+    sync()
+    for a, b in ((idx, idx2), (w, w2), (p, p2), (imp, imp2), (load, load2), (bits, bits2), (rank, rank2)):
+        assert torch.equal(a, b)
+    # and the oracle's decisions
+    ridx, rw, rp, rl = O.route_topk(x, wg, bias, k)
+    ok = margin_ok(rl, k)
+    assert ok.sum() >= max(1, T - 1)
+    assert np.array_equal(idx.cpu().numpy()[ok], ridx[ok])
+    assert np.allclose(w.cpu().numpy()[ok], rw[ok], rtol=2e-4, atol=1e-7)
+    rimp = O.expert_importance_decode(rp)
+    assert np.allclose(imp.cpu().numpy(), rimp, rtol=1e-5)
+    rload = np.bincount(idx.cpu().numpy().ravel(), minlength=E).astype(np.int32)
+    assert np.array_equal(load.cpu().numpy(), rload)
+    # rank on the GPU's own fp32 importance (floating point decides an integer: same precision both sides)
+    rbits, rrank = O.assign_precision(imp.cpu().numpy().astype(np.float64), rload, tiers, tier_bits)
+    assert np.array_equal(bits.cpu().numpy(), rbits)
+    assert np.array_equal(rank.cpu().numpy(), rrank)
+
+
 # ------------------------------------------------------------------ measurement aid
 
 @pytest.mark.parametrize("nbytes", [0, 16, 16 * 1024 * 3 + 48, 8 << 20])

@@ -101,6 +101,15 @@ def test_argument_validation_happens_before_any_device_work():
     assert lib.dymoe_pack_tiles(None, P, 48, 256, 2 * P, None) == B.EINVAL
     assert lib.dymoe_pack_tiles(None, P, 64, 192, 2 * P, None) == B.EINVAL
     assert lib.dymoe_pack_tiles(None, P, 64, 256, P, None) == B.EINVAL                          # in place
+    # fused decode front end
+    df = lib.dymoe_decode_front
+    assert df(None, P, P, None, 1, 256, 8, 2, 1, 3, tcp, tbp, 0, P, P, P, P, P, P, P, None) == B.ENOCTX
+    assert df(None, P, P, None, 0, 256, 8, 2, 1, 3, tcp, tbp, 0, P, P, P, P, P, P, P, None) == B.EINVAL
+    assert df(None, P, P, None, B.FRONT_MAX_TOKENS + 1, 256, 8, 2, 1, 3, tcp, tbp, 0, P, P, P, P, P, P, P, None) == B.EINVAL
+    assert df(None, P, P, None, 1, 256, 9, 2, 1, 3, tcp, tbp, 0, P, P, P, P, P, P, P, None) == B.EINVAL   # tiers sum to 8
+    assert df(None, P, P, None, 1, 256, 8, 2, 1, 3, tcp, tbp, 3, P, P, P, P, P, P, P, None) == B.EINVAL
+    assert df(None, P, P, None, 1, 256, 8, 2, 1, 3, tcp, tbp, 0, P, P, None, P, P, P, None, None) == B.ENOCTX  # probs, rank optional
+    assert df(None, P, P, None, 1, 256, 8, 2, 1, 3, tcp, tbp, 0, P, P, P, None, P, P, P, None) == B.EINVAL
     # stream copy
     assert lib.dymoe_stream_copy(None, P, 2 * P, 1024, None) == B.ENOCTX
     assert lib.dymoe_stream_copy(None, P, 2 * P, 1000, None) == B.EINVAL

@@ -415,6 +415,34 @@ def test_chained_layer_tiny(ctx):
     assert err <= FFN_TOL
 
 
+def test_ffn_gemv_combine_is_deterministic_over_many_launches(ctx):
+    """The down projection's last-arriving workgroup sums the partial results in a
+    fixed order: whichever it is, the output bits are the same."""
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=3, H=1024, F=4096, E=4, k=2, config_id=81)
+    x, _ = synth.activations(cfg)
+    hw = {e: synth.expert_weights(cfg, e) for e in range(cfg.E)}
+    store = ExpertStore([[to_bf16(m) for m in hw[e]] for e in range(cfg.E)], cfg.H, cfg.F, DEV)
+    bits_np = np.array([16, 4, 2, 4], dtype=np.uint8)
+    bits = torch.from_numpy(bits_np).to(DEV)
+    ones = torch.ones((cfg.E,), dtype=torch.int32, device=DEV)
+    ctx.quantize_experts(store.table, bits, ones, cfg.E, cfg.H, cfg.F)
+    idx_np = np.array([[0, 1], [2, 3], [1, 0]], dtype=np.int32)
+    w_np = np.array([[0.6, 0.4], [0.3, 0.7], [0.5, 0.5]], dtype=np.float32)
+    idx, w = torch.from_numpy(idx_np).to(DEV), torch.from_numpy(w_np).to(DEV)
+    xd = to_bf16(x)
+    first = ctx.moe_ffn_mixed(xd, idx, w, bits, store.table, cfg.F, out_dtype=B.OUT_F32, path=B.PATH_GEMV).clone()
+    sync()
+    for _ in range(200):
+        y = ctx.moe_ffn_mixed(xd, idx, w, bits, store.table, cfg.F, out_dtype=B.OUT_F32, path=B.PATH_GEMV)
+        assert torch.equal(y, first)
+    experts = []
+    for e in range(cfg.E):
+        b = int(bits_np[e])
+        experts.append({"w": hw[e]} if b == 16 else {"q": [O.quantize_pack(m, b) for m in hw[e]]})
+    ref = O.moe_ffn_mixed(x, idx_np, w_np.astype(np.float64), bits_np, experts)
+    assert rel_err_per_token(first.cpu().numpy(), ref) <= FFN_TOL
+
+
 # ------------------------------------------------------------------ fused decode front end
 
 @pytest.mark.parametrize("T,H,E,k,tiers", [(1, 256, 8, 2, (2, 3, 3)), (1, 4096, 8, 2, (1, 3, 4)),

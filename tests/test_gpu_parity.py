@@ -416,8 +416,8 @@ def test_chained_layer_tiny(ctx):
 
 
 def test_ffn_gemv_combine_is_deterministic_over_many_launches(ctx):
-    """The down projection's last-arriving workgroup sums the partial results in a
-    fixed order: whichever it is, the output bits are the same."""
+    """Partial sums of the segments and of the token's experts are added in a fixed
+    order: every launch gives the same bits."""
     cfg = synth.scaled(synth.CONFIGS["tiny"], T=3, H=1024, F=4096, E=4, k=2, config_id=81)
     x, _ = synth.activations(cfg)
     hw = {e: synth.expert_weights(cfg, e) for e in range(cfg.E)}
@@ -441,6 +441,63 @@ def test_ffn_gemv_combine_is_deterministic_over_many_launches(ctx):
         experts.append({"w": hw[e]} if b == 16 else {"q": [O.quantize_pack(m, b) for m in hw[e]]})
     ref = O.moe_ffn_mixed(x, idx_np, w_np.astype(np.float64), bits_np, experts)
     assert rel_err_per_token(first.cpu().numpy(), ref) <= FFN_TOL
+
+
+# ------------------------------------------------------------------ the paper's own modes
+
+@pytest.mark.parametrize("low_bits", [2, 0])
+@pytest.mark.parametrize("phase", ["prefill", "decode"])
+def test_paper_modes_depth_schedule_4_2_and_4_0(ctx, low_bits, phase):
+    """Sec. 5: "4/2" keeps the Critical experts of a layer in 4 bits and drops the
+    Sub-critical ones to 2 bits, "4/0" skips them; Sec. 4.3: the number of
+    Critical experts of layer l is t_l = ceil(r(l) * M) with the cosine retention
+    (L = 4, M = 8, lambda = 0.5: t = 8, 7, 5, 4).  Every layer of the stack runs
+    the whole chain on the device and is compared with the oracle's chain."""
+    L, lam = 4, 0.5
+    base = synth.CONFIGS["tiny"]
+    T = base.T if phase == "prefill" else 1
+    expected_t = [8, 7, 5, 4]
+    for layer_no in range(L):
+        # the first seed of the layer whose top-(k+1) logits are separated by more than 1e-4 in every token
+        for seed in range(100 * (layer_no + 1), 100 * (layer_no + 1) + 50):
+            cfg = synth.scaled(base, T=T, phase=phase, config_id=seed)
+            x, _ = synth.activations(cfg)
+            wg, _ = synth.router(cfg)
+            if margin_ok(O.route_topk(x, wg, None, cfg.k)[3], cfg.k).all():
+                break
+        t_l = B.depth_schedule(layer_no, L, lam, cfg.E)
+        assert t_l == expected_t[layer_no]
+        tiers, tier_bits = (t_l, cfg.E - t_l), (4, low_bits)
+        mats = [synth.expert_weights(cfg, e) for e in range(cfg.E)]
+        # oracle chain
+        ridx, rw, rp, rl = O.route_topk(x, wg, None, cfg.k)
+        assert margin_ok(rl, cfg.k).all()
+        if phase == "prefill":
+            rimp, rload, _ = O.expert_importance_prefill(ridx, O.token_score_norm(x), cfg.E, cfg.k_hh)
+        else:
+            rimp = O.expert_importance_decode(rp)
+            rload = np.bincount(ridx.ravel(), minlength=cfg.E).astype(np.int32)
+        # device chain
+        store = ExpertStore([[to_bf16(m) for m in mats[e]] for e in range(cfg.E)], cfg.H, cfg.F, DEV, ctx=ctx)
+        layer = MoELayer(ctx, cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, phase, tiers, tier_bits,
+                         k_hh=cfg.k_hh, out_dtype=B.OUT_F32, device=DEV)
+        y = layer.step(to_bf16(x), to_bf16(wg), None, store)
+        sync()
+        assert np.array_equal(layer.idx.cpu().numpy(), ridx)
+        imp_for_rank = rimp if phase == "prefill" else layer.imp.cpu().numpy().astype(np.float64)
+        if phase == "decode":
+            assert np.allclose(imp_for_rank, rimp, rtol=1e-5)
+        rbits, _ = O.assign_precision(imp_for_rank, rload, tiers, tier_bits)
+        assert np.array_equal(layer.bits.cpu().numpy(), rbits)
+        assert int((rbits == 4).sum()) == t_l and int((rbits == low_bits).sum()) == cfg.E - t_l
+        host = [({"q": oracle_quantize_expert(mats[e], int(rbits[e]))} if rbits[e] else {}) for e in range(cfg.E)]
+        ref = O.moe_ffn_mixed(x, ridx, rw, rbits, host)
+        err = rel_err_per_token(y.cpu().numpy().astype(np.float64), ref)
+        assert err <= FFN_TOL, (layer_no, err)
+        if low_bits == 0 and t_l < cfg.E:
+            # a token routed only to skipped experts yields exactly zero
+            dead = np.isin(ridx, np.nonzero(rbits == 0)[0]).all(axis=1)
+            assert np.all(y.cpu().numpy()[dead] == 0.0)
 
 
 # ------------------------------------------------------------------ fused decode front end

@@ -69,12 +69,16 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
     __shared__ int s_nt;
     const PlanPtrs pp = plan_ptrs(plan, E, P);
     int32_t* draft = pp.tiles + 4 * (size_t)max_tiles;   // tiles in expert order, before sorting
-    for (int e = threadIdx.x; e < E; e += blockDim.x) s_count[e] = 0;
+    __shared__ uint8_t s_bits[DYMOE_MAX_EXPERTS];
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        s_count[e] = 0;
+        s_bits[e] = bits[e];
+    }
     __syncthreads();
     for (int p = threadIdx.x; p < P; p += blockDim.x) {
         const int e = idx[p];
         if (e < 0 || e >= E) continue;
-        const int b = bits[e];
+        const int b = s_bits[e];
         if (b != 16 && b != 4 && b != 2) continue;
         atomicAdd(&s_count[e], 1);
     }
@@ -84,7 +88,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
         for (int e = 0; e < E; e++) {
             s_off[e] = run;
             const int c = s_count[e];
-            const int b = bits[e];
+            const int b = s_bits[e];
             for (int m0 = 0; m0 < c; m0 += tile_m) {
                 const int rows = min(tile_m, c - m0);
                 draft[4 * nt + 0] = e;
@@ -131,7 +135,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
     for (int p = threadIdx.x; p < P; p += blockDim.x) {
         const int e = idx[p];
         if (e < 0 || e >= E) continue;
-        const int b = bits[e];
+        const int b = s_bits[e];
         if (b != 16 && b != 4 && b != 2) continue;
         const int pos = s_off[e] + atomicAdd(&s_count[e], 1);
         pp.perm[pos] = p;

@@ -1,6 +1,8 @@
 // Expert importance (heavy-hitter token load / gate score) and the
 // importance-ranked bit-width assignment.  Both are tiny: integer histograms
 // and an E x E ranking, sized for one or a few workgroups.
+#include <math.h>
+
 #include "common.hpp"
 #include "assign.hpp"
 
@@ -20,14 +22,21 @@ __global__ void zero_i32_kernel(int32_t* a, int32_t* b, int n)
 
 // Prefill: a token is a heavy hitter when fewer than k_hh tokens precede it in
 // the order (score descending, token index ascending).  Each thread ranks one
-// token against all T scores staged through LDS, then adds its k routed
-// experts to the load histogram and, if heavy, to the importance histogram.
-// with_importance = 0: only the load histogram (decode phase).
+// token against all T scores staged through LDS (four per read), then adds its
+// k routed experts to the workgroup's LDS histograms (load and, if heavy,
+// importance); the workgroup adds its non-zero bins to the global ones, which
+// the caller has zeroed.  with_importance = 0: only the load histogram (decode).
 __global__ __launch_bounds__(kImpThreads) void importance_prefill_kernel(
     const int32_t* __restrict__ idx, const float* __restrict__ score, int T, int E, int k,
     int k_hh, int with_importance, int32_t* __restrict__ importance, int32_t* __restrict__ load)
 {
-    __shared__ float tile[kImpThreads];
+    __shared__ __attribute__((aligned(16))) float tile[kImpThreads];
+    __shared__ int32_t s_load[DYMOE_MAX_EXPERTS];
+    __shared__ int32_t s_imp[DYMOE_MAX_EXPERTS];
+    for (int e = threadIdx.x; e < E; e += kImpThreads) {
+        s_load[e] = 0;
+        s_imp[e] = 0;
+    }
     const int t = blockIdx.x * kImpThreads + threadIdx.x;
     bool heavy = false;
     if (with_importance) {
@@ -35,24 +44,36 @@ __global__ __launch_bounds__(kImpThreads) void importance_prefill_kernel(
         int before = 0;
         for (int base = 0; base < T; base += kImpThreads) {
             const int u = base + threadIdx.x;
-            tile[threadIdx.x] = (u < T) ? score[u] : 0.0f;
+            // slots past the end hold -inf at an index past every token: never counted
+            tile[threadIdx.x] = (u < T) ? score[u] : -INFINITY;
             __syncthreads();
-            const int n = min(kImpThreads, T - base);
-            for (int j = 0; j < n; j++) {
-                const float s = tile[j];
-                before += (s > mine || (s == mine && base + j < t)) ? 1 : 0;
+#pragma unroll 4
+            for (int j = 0; j < kImpThreads; j += 4) {
+                const float4 s4 = *reinterpret_cast<const float4*>(tile + j);
+                const int u0 = base + j;
+                before += (s4.x > mine || (s4.x == mine && u0 + 0 < t)) ? 1 : 0;
+                before += (s4.y > mine || (s4.y == mine && u0 + 1 < t)) ? 1 : 0;
+                before += (s4.z > mine || (s4.z == mine && u0 + 2 < t)) ? 1 : 0;
+                before += (s4.w > mine || (s4.w == mine && u0 + 3 < t)) ? 1 : 0;
             }
             __syncthreads();
         }
         heavy = (t < T) && before < k_hh;
+    } else {
+        __syncthreads();
     }
     if (t < T) {
         for (int s = 0; s < k; s++) {
             const int e = idx[(size_t)t * k + s];
             if (e < 0 || e >= E) continue;
-            atomicAdd(&load[e], 1);
-            if (heavy) atomicAdd(&importance[e], 1);
+            atomicAdd(&s_load[e], 1);
+            if (heavy) atomicAdd(&s_imp[e], 1);
         }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kImpThreads) {
+        if (s_load[e]) atomicAdd(&load[e], s_load[e]);
+        if (with_importance && s_imp[e]) atomicAdd(&importance[e], s_imp[e]);
     }
 }
 
@@ -167,7 +188,7 @@ int dymoe_expert_importance(dymoe_ctx* ctx, int phase, const int32_t* idx, const
     if (!ctx) return DYMOE_ENOCTX;
     hipStream_t st = (hipStream_t)stream;
     const bool prefill = phase == DYMOE_PHASE_PREFILL;
-    if (T <= 4096) {
+    if (T <= 512) {      // one workgroup ranks T tokens against T scores: quadratic, so only for short steps
         dymoe_launch(ctx, DYMOE_K_IMPORTANCE, dymoe::importance_block_kernel, dim3(1),
                      dim3(dymoe::kImpBlock), 0, st, idx, token_score, probs, T, E, k, k_hh,
                      prefill ? 1 : 0, importance, load);

@@ -269,6 +269,44 @@ int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t* idx, const
                         void* y, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Host-resident experts (Sec. 4.4.1, Phase-Adaptive Prefetcher): the weights a
+ * later layer is predicted to need are copied from pinned host memory into
+ * device buffers on a side stream while the compute stream works on the current
+ * layer.  Which experts to fetch is decided with the calls above: Eq. 6 applies
+ * the NEXT layer's router to the current hidden state (dymoe_route_topk with
+ * that layer's wg); decode prefetches its top-t experts (Eq. 8: call it with
+ * k = t); prefill counts the predicted activations per expert (Eq. 7: the load
+ * histogram of dymoe_expert_importance) and takes the t most frequent
+ * (dymoe_assign_precision with tiers (t, E - t) marks them).
+ *
+ * dymoe_prefetch_submit: enqueue on side_stream the copy of `bytes` from
+ * host_pinned_src (pinned host memory, owned by the caller, must stay valid and
+ * unchanged until the copy has completed) to dev_dst (device), followed by an
+ * event; *event_out receives the event (opaque, owned by the caller until
+ * dymoe_prefetch_release).  bytes == 0 records only the event.  Does not block.
+ * dymoe_prefetch_wait: work enqueued on compute_stream after this call starts
+ * only when the copy behind `event` has completed.  Does not block the host.
+ * dymoe_prefetch_done: 1 if the copy has completed, 0 if not yet (host query).
+ * dymoe_prefetch_release: destroy the event (its copy may still be running).
+ * Errors: DYMOE_EINVAL, DYMOE_ENOCTX, DYMOE_EHIP.
+ */
+int dymoe_prefetch_submit(dymoe_ctx* ctx, const void* host_pinned_src, void* dev_dst, size_t bytes,
+                          void* side_stream, void** event_out);
+int dymoe_prefetch_wait(dymoe_ctx* ctx, void* event, void* compute_stream);
+int dymoe_prefetch_done(dymoe_ctx* ctx, void* event);
+int dymoe_prefetch_release(dymoe_ctx* ctx, void* event);
+
+/*
+ * Glue between the layers of an expert-only stack (not from the paper, which
+ * runs whole transformer blocks): v = h[t,:] + alpha * y[t,:], h_out[t,:] =
+ * bf16(v / rms(v)), fp32 arithmetic (fma, then sum of squares by lane and a
+ * cross-lane sum).  h, h_out: [T,H] bf16 (may alias); y: [T,H] bf16 or fp32
+ * (y_dtype = DYMOE_OUT_BF16 / DYMOE_OUT_F32).  A row of zeros stays zero.
+ */
+int dymoe_residual_rmsnorm(dymoe_ctx* ctx, const void* h, const void* y, int y_dtype, float alpha,
+                           int T, int H, void* h_out, void* stream);
+
+/*
  * Measurement aid, not a step of the method: copies `bytes` (a multiple of
  * 16; src and dst 16-byte aligned device pointers that do not overlap) with
  * the access pattern of the weight-streaming kernels (16 bytes per lane,

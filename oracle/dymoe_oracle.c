@@ -507,3 +507,39 @@ int oracle_moe_ffn_mixed(const uint16_t* x, const int32_t* idx, const double* w,
     free(xd);
     return rc;
 }
+
+/* ------------------------------------------------------------------ */
+/* Glue between the layers of an expert-only stack (not from the paper, which  */
+/* runs whole transformer blocks): v = h + alpha * y, out = bf16(v / rms(v)),   */
+/* in fp64, rounded once to bf16 (nearest even, through binary32).  A row of    */
+/* zeros stays zero.                                                            */
+/* ------------------------------------------------------------------ */
+
+static uint16_t f64_to_bf16_rne(double d)
+{
+    float f = (float)d;
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    u = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (uint16_t)u;
+}
+
+uint16_t oracle_f64_to_bf16(double d) { return f64_to_bf16_rne(d); }
+
+void oracle_residual_rmsnorm(const uint16_t* h, const double* y, double alpha, int T, int H,
+                             uint16_t* out)
+{
+    for (int t = 0; t < T; t++) {
+        double ss = 0.0;
+        for (int j = 0; j < H; j++) {
+            double v = (double)bf16_to_f32(h[(size_t)t * H + j]) + alpha * y[(size_t)t * H + j];
+            ss += v * v;
+        }
+        double rms = sqrt(ss / (double)H);
+        for (int j = 0; j < H; j++) {
+            double v = (double)bf16_to_f32(h[(size_t)t * H + j]) + alpha * y[(size_t)t * H + j];
+            out[(size_t)t * H + j] = f64_to_bf16_rne(rms > 0.0 ? v / rms : 0.0);
+        }
+    }
+}
+

@@ -224,3 +224,63 @@ def moe_ffn_mixed(x_bits, idx, w, bits, experts, group=64):
     if rc != 0:
         raise ValueError("oracle_moe_ffn_mixed rc=%d" % rc)
     return y
+
+
+_lib.oracle_f64_to_bf16.restype = C.c_uint16
+_lib.oracle_f64_to_bf16.argtypes = [C.c_double]
+_lib.oracle_residual_rmsnorm.restype = None
+_lib.oracle_residual_rmsnorm.argtypes = [_u16p, _f64p, C.c_double, C.c_int, C.c_int, _u16p]
+
+
+def f64_to_bf16(v: float) -> int:
+    return int(_lib.oracle_f64_to_bf16(float(v)))
+
+
+def residual_rmsnorm(h_bits, y, alpha=1.0):
+    """h [T,H] bf16 bits, y [T,H] f64 -> bf16 bits of (h + alpha*y) / rms(h + alpha*y)."""
+    h = _c(h_bits, np.uint16)
+    y = _c(y, np.float64)
+    T, H = h.shape
+    out = np.zeros((T, H), np.uint16)
+    _lib.oracle_residual_rmsnorm(_ptr(h, _u16p), _ptr(y, _f64p), float(alpha), T, H, _ptr(out, _u16p))
+    return out
+
+
+def decode_stack(h0_bits, routers, expert_matrices, k, tier_count, tier_bits, floor_bits, alpha,
+                 predict_t=0):
+    """A stack of expert layers on one token (composition of the functions above,
+    no arithmetic of its own): per layer gating, decode importance, assignment
+    (with the layer's floor), quantisation of the active experts to their
+    assigned width, FFN, residual + normalisation.
+    routers: list of wg [E,H] bf16 bits; expert_matrices(layer, e) -> (W1, W3, W2) bf16 bits.
+    Returns (final h bits, per-layer list of (idx, bits of idx, logits, importance),
+    per-layer predicted top-t experts of the NEXT layer from this layer's input)."""
+    h = _c(h0_bits, np.uint16)
+    log, preds = [], []
+    for l, wg in enumerate(routers):
+        E = wg.shape[0]
+        idx, w, probs, logits = route_topk(h, wg, None, k)
+        if predict_t and l + 1 < len(routers):
+            pidx, _, _, _ = route_topk(h, routers[l + 1], None, predict_t)
+            preds.append([int(v) for v in pidx[0]])
+        imp = expert_importance_decode(probs)
+        load = np.bincount(idx.ravel(), minlength=E).astype(np.int32)
+        bits, _ = assign_precision(imp, load, tier_count, tier_bits, floor_bits[l] if floor_bits else 0)
+        experts = []
+        use_bits = np.zeros(E, np.uint8)
+        for e in range(E):
+            b = int(bits[e])
+            if e not in idx[0] or b == 0:
+                experts.append({})
+                continue
+            use_bits[e] = b
+            mats = expert_matrices(l, e)
+            experts.append({"w": mats} if b == 16 else {"q": [quantize_pack(m, b) for m in mats]})
+        if use_bits.any():
+            y = moe_ffn_mixed(h, idx, w, use_bits, experts)
+        else:
+            y = np.zeros(h.shape, np.float64)
+        log.append((idx.copy(), bits[idx[0]].copy(), logits.copy(), imp.copy()))
+        h = residual_rmsnorm(h, y, alpha)
+    return h, log, preds
+

@@ -34,7 +34,8 @@ EXPORTS = [
     "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_expert_importance",
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
     "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_moe_ffn_mixed", "dymoe_stream_copy",
-    "dymoe_decode_front",
+    "dymoe_decode_front", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
+    "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
     "dymoe_timing_enable", "dymoe_timing_read", "dymoe_kernel_name",
 ]
 
@@ -61,6 +62,16 @@ lib.dymoe_workspace_bytes.argtypes = [_i] * 5
 lib.dymoe_decode_front.restype = _i
 lib.dymoe_decode_front.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _i,
                                    _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.dymoe_prefetch_submit.restype = _i
+lib.dymoe_prefetch_submit.argtypes = [_vp, _vp, _vp, _sz, _vp, C.POINTER(_vp)]
+lib.dymoe_prefetch_wait.restype = _i
+lib.dymoe_prefetch_wait.argtypes = [_vp, _vp, _vp]
+lib.dymoe_prefetch_done.restype = _i
+lib.dymoe_prefetch_done.argtypes = [_vp, _vp]
+lib.dymoe_prefetch_release.restype = _i
+lib.dymoe_prefetch_release.argtypes = [_vp, _vp]
+lib.dymoe_residual_rmsnorm.restype = _i
+lib.dymoe_residual_rmsnorm.argtypes = [_vp, _vp, _vp, _i, C.c_float, _i, _i, _vp, _vp]
 lib.dymoe_stream_copy.restype = _i
 lib.dymoe_stream_copy.argtypes = [_vp, _vp, _vp, _sz, _vp]
 lib.dymoe_route_topk.restype = _i
@@ -267,6 +278,34 @@ class Context:
         out = torch.empty_like(w)
         _check(lib.dymoe_pack_tiles(self._h, _ptr(w, torch.bfloat16), N, K, _ptr(out),
                                     _stream(stream)), "dymoe_pack_tiles")
+        return out
+
+    # -- host-resident experts
+    def prefetch_submit(self, host_ptr, dev_ptr, nbytes, side_stream):
+        ev = _vp()
+        _check(lib.dymoe_prefetch_submit(self._h, host_ptr, dev_ptr, nbytes, side_stream, C.byref(ev)),
+               "dymoe_prefetch_submit")
+        return ev
+
+    def prefetch_wait(self, ev, compute_stream):
+        _check(lib.dymoe_prefetch_wait(self._h, ev, compute_stream), "dymoe_prefetch_wait")
+
+    def prefetch_done(self, ev):
+        r = lib.dymoe_prefetch_done(self._h, ev)
+        if r < 0:
+            _check(r, "dymoe_prefetch_done")
+        return bool(r)
+
+    def prefetch_release(self, ev):
+        _check(lib.dymoe_prefetch_release(self._h, ev), "dymoe_prefetch_release")
+
+    def residual_rmsnorm(self, h, y, alpha=1.0, out=None, stream=None):
+        T, H = h.shape
+        if out is None:
+            out = torch.empty_like(h)
+        yd = OUT_BF16 if y.dtype == torch.bfloat16 else OUT_F32
+        _check(lib.dymoe_residual_rmsnorm(self._h, _ptr(h, torch.bfloat16), _ptr(y), yd, float(alpha), T, H,
+                                          _ptr(out, torch.bfloat16), _stream(stream)), "dymoe_residual_rmsnorm")
         return out
 
     def stream_copy(self, src, dst, stream=None):

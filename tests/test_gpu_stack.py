@@ -1,0 +1,127 @@
+"""GPU tests of the host-resident expert stack: the side-stream copy calls, the
+residual + normalisation glue kernel, and a small stack of layers decoded with
+and without look-ahead prefetch against the oracle's composition."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dymoe_oracle as O
+from paper_2603_19172_amd import binding as B
+from paper_2603_19172_amd import synth
+from paper_2603_19172_amd.stack import DecodeStack, HostExpertPool
+from gpu_helpers import DEV, bits_of, margin_ok, to_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.Context(0)
+    yield c
+    c.close()
+
+
+def test_prefetch_copy_is_ordered_before_the_compute_stream(ctx):
+    n = 8 << 20
+    g = torch.Generator().manual_seed(11)
+    host = torch.randint(0, 256, (n,), dtype=torch.uint8, generator=g).pin_memory()
+    dev = torch.zeros((n,), dtype=torch.uint8, device=DEV)
+    out = torch.zeros_like(dev)
+    side = torch.cuda.Stream()
+    cs = torch.cuda.current_stream()
+    ev = ctx.prefetch_submit(host.data_ptr(), dev.data_ptr(), n, side.cuda_stream)
+    ctx.prefetch_wait(ev, cs.cuda_stream)
+    ctx.stream_copy(dev, out)            # on the compute stream: must see the copied bytes
+    torch.cuda.synchronize()
+    assert ctx.prefetch_done(ev)
+    ctx.prefetch_release(ev)
+    assert torch.equal(out.cpu(), host)
+    # an empty copy still gives an event that completes
+    ev = ctx.prefetch_submit(None, None, 0, side.cuda_stream)
+    torch.cuda.synchronize()
+    assert ctx.prefetch_done(ev)
+    ctx.prefetch_release(ev)
+
+
+@pytest.mark.parametrize("T,H,alpha", [(1, 256, 1.0), (5, 4096, 0.125), (3, 264, 0.5)])
+def test_residual_rmsnorm_against_the_oracle(ctx, T, H, alpha):
+    rng = np.random.default_rng(3)
+    h = synth.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))
+    y = (2.0 * rng.standard_normal((T, H))).astype(np.float32)
+    h[T - 1] = 0
+    y[T - 1] = 0.0                                   # a zero row stays zero
+    ref = O.residual_rmsnorm(h, y.astype(np.float64), alpha)
+    for yt in (torch.from_numpy(y).to(DEV), to_bf16(synth.f32_to_bf16_bits(y))):
+        yref = ref if yt.dtype == torch.float32 else O.residual_rmsnorm(
+            h, synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(y)).astype(np.float64), alpha)
+        out = ctx.residual_rmsnorm(to_bf16(h), yt, alpha)
+        torch.cuda.synchronize()
+        got = bits_of(out).astype(np.int64)
+        # fp32 arithmetic on the device, fp64 in the oracle: at most one bf16 step apart
+        assert np.abs(got - yref.astype(np.int64)).max() <= 1
+        assert (got[T - 1] == 0).all()
+
+
+def _small_stack(ctx, L, n_slots, prefetch, seed0):
+    H, F, E, k = 256, 512, 8, 2
+    cfgs = [synth.scaled(synth.CONFIGS["tiny"], T=1, phase="decode", config_id=seed0 + l) for l in range(L)]
+    routers_np = [synth.router(c)[0] for c in cfgs]
+    n_pool = 12
+    pool_cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=seed0 + 50)
+    mats = {i: synth.expert_weights(pool_cfg, i) for i in range(n_pool)}
+    pool = HostExpertPool(H, F, E, n_pool, lambda i: mats[i])
+    floor = [4] + [0] * (L - 2) + [4]
+    stack = DecodeStack(ctx, H, F, E, k, [to_bf16(r) for r in routers_np], pool, n_slots, (1, 3, 4), (16, 4, 2),
+                        floor_bits=floor, prefetch_t=2, prefetch=prefetch, alpha=0.25, device=DEV)
+    expert_matrices = lambda l, e: mats[pool.entry(l, e)]
+    return stack, routers_np, expert_matrices, floor, cfgs[0]
+
+
+def test_stack_decode_matches_the_oracle_and_prefetch_changes_nothing(ctx):
+    L, steps = 4, 3
+    outs, traces, stats = {}, {}, {}
+    for prefetch in (False, True):
+        stack, routers_np, expert_matrices, floor, cfg0 = _small_stack(ctx, L, 4, prefetch, 300)
+        hs = []
+        for s in range(steps):
+            x, _ = synth.activations(synth.scaled(cfg0, config_id=400 + s))
+            hs.append((x, stack.step(to_bf16(x)).clone()))
+        stack.close()
+        outs[prefetch], traces[prefetch], stats[prefetch] = hs, stack.trace, dict(stack.stats)
+    # look-ahead copies change when the weights arrive, never what is computed
+    for (x0, a), (x1, b) in zip(outs[False], outs[True]):
+        assert torch.equal(a, b)
+    assert traces[False] == traces[True]
+    for st in stats.values():
+        assert st["miss"] + st.get("hit_resident", 0) + st.get("hit_prefetched", 0) == L * 2 * steps
+    assert stats[False].get("hit_prefetched", 0) == 0 and stats[False].get("prefetch_issued", 0) == 0
+    assert stats[True]["prefetch_issued"] > 0
+    assert stats[True]["miss"] <= stats[False]["miss"]
+    # against the oracle's composition of its own functions
+    checked = 0
+    for s, (x, h_dev) in enumerate(outs[True]):
+        ref_h, log, preds = O.decode_stack(x, routers_np, expert_matrices, 2, (1, 3, 4), (16, 4, 2), floor, 0.25,
+                                           predict_t=2)
+        if not all(margin_ok(lg, 2).all() for (_, _, lg, _) in log):
+            continue                     # a near tie somewhere in the stack: decisions may legitimately differ
+        checked += 1
+        for l, (idx, bts, _, _) in enumerate(log):
+            assert traces[True][s][l] == (tuple(int(v) for v in idx[0]), tuple(int(v) for v in bts))
+        got = synth.bf16_bits_to_f32(bits_of(h_dev)).astype(np.float64)
+        want = synth.bf16_bits_to_f32(ref_h).astype(np.float64)
+        # unit-RMS rows; the FFN tolerance (2e-2 of a row's RMS, scaled by alpha) accumulates over the layers
+        assert np.abs(got - want).max() <= 2e-2
+    assert checked >= 1
+
+
+def test_stack_with_room_for_everything_copies_each_expert_once(ctx):
+    L, steps = 3, 4
+    stack, _, _, _, cfg0 = _small_stack(ctx, L, 3 * 8, True, 500)
+    for s in range(steps):
+        x, _ = synth.activations(synth.scaled(cfg0, config_id=600 + s))
+        stack.step(to_bf16(x))
+    stack.close()
+    st = stack.stats
+    copies = st["bytes_copied"] // stack.pool.nbytes
+    assert copies == len(stack.where) <= L * 8          # nothing was ever evicted
+    assert st["miss"] + st.get("prefetch_issued", 0) == copies

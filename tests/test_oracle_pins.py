@@ -473,3 +473,37 @@ def test_synth_configs_shapes():
     # same key, same bytes
     assert np.array_equal(synth.expert_weights(cfg, 3)[2], synth.expert_weights(cfg, 3)[2])
     assert sum(synth.CONFIGS["fine_grained"].tier_count) == 128
+
+
+# ------------------------------------------------------------------ stack glue (not from the paper)
+
+def test_bf16_rounding_of_the_stack_glue():
+    # ties go to the even mantissa; the next representable value is 2^-7 above 1
+    assert O.f64_to_bf16(1.0) == 0x3F80
+    assert O.f64_to_bf16(1.0 + 2.0 ** -8) == 0x3F80          # tie -> even (down)
+    assert O.f64_to_bf16(1.0 + 3 * 2.0 ** -8) == 0x3F82      # tie -> even (up)
+    assert O.f64_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -20) == 0x3F81
+    assert O.f64_to_bf16(-2.5) == 0xC020
+    assert O.f64_to_bf16(0.0) == 0
+
+
+def test_residual_rmsnorm_closed_forms():
+    # (1, 2, -2, 0) has RMS 1.5 -> (2/3, 4/3, -4/3, 0), written here as bf16 bit patterns
+    h = np.array([[0x3F80, 0x4000, 0xC000, 0x0000]], dtype=np.uint16)
+    out = O.residual_rmsnorm(h, np.zeros((1, 4)), 1.0)
+    assert out.tolist() == [[0x3F2B, 0x3FAB, 0xBFAB, 0x0000]]
+    # y enters scaled by alpha: h = 0, y = (4, 0, 0, 0), alpha = 0.5 -> v = (2, 0, 0, 0), RMS 1 -> (2, 0, 0, 0)
+    z = np.zeros((1, 4), dtype=np.uint16)
+    assert O.residual_rmsnorm(z, np.array([[4.0, 0, 0, 0]]), 0.5).tolist() == [[0x4000, 0, 0, 0]]
+    # scale invariance: multiplying h and y by 4 changes nothing; a zero row stays zero
+    rng = np.random.default_rng(5)
+    hb = synth.f32_to_bf16_bits(rng.standard_normal((3, 64)).astype(np.float32))
+    y = rng.standard_normal((3, 64))
+    hb[2] = 0
+    y[2] = 0.0
+    a = O.residual_rmsnorm(hb, y, 0.25)
+    h4 = synth.f32_to_bf16_bits(4.0 * synth.bf16_bits_to_f32(hb))
+    assert np.array_equal(a, O.residual_rmsnorm(h4, 4.0 * y, 0.25))
+    assert (a[2] == 0).all()
+    rms = np.sqrt((synth.bf16_bits_to_f32(a[:2]).astype(np.float64) ** 2).mean(axis=1))
+    assert np.allclose(rms, 1.0, atol=2e-3)

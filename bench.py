@@ -41,6 +41,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--skip-prefill", action="store_true")
+    ap.add_argument("--stack-steps", type=int, default=0,
+                    help="also decode this many steps through a 32-layer stack with the experts in pinned host "
+                         "memory (BASELINE configs[4]); off by default: the run is bound by the host link")
+    ap.add_argument("--stack-slots", type=str, default="47,256",
+                    help="device slot counts to try (47 slots of 506 MB are a 24 GB budget; 256 holds every expert)")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -289,6 +294,46 @@ def main():
         out["parity_vs_oracle"] = {"topk_equal": bool(np.array_equal(idx_host, ridx)),
                                    "bits_equal": bool(np.array_equal(bits_host, rbits)),
                                    "ffn_max_err_over_rms_bf16_out": round(err, 5)}
+    # ---------------------------------------------------------------- 32-layer stack, experts in host memory
+    if args.stack_steps > 0:
+        from paper_2603_19172_amd.stack import DecodeStack, HostExpertPool
+        L, n_pool = 32, 16
+        for st_ in stores[1:]:
+            del st_
+        pool = HostExpertPool(H, F, E, n_pool, lambda i: host_w[i % E] if i < E else
+                              synth.expert_weights(synth.scaled(cfg, config_id=50), i % E))
+        routers = [bf16(synth.router(synth.scaled(cfg, config_id=100 + l))[0]) for l in range(L)]
+        floor = [4 if (l < 4 or l >= L - 4) else 2 for l in range(L)]
+        xs = [bf16(synth.activations(synth.scaled(cfg, config_id=200 + s))[0]) for s in range(args.stack_steps)]
+        results = []
+        for n_slots in [int(v) for v in args.stack_slots.split(",")]:
+            for prefetch in (False, True):
+                stack = DecodeStack(ctx, H, F, E, k, routers, pool, n_slots, cfg.tier_count, cfg.tier_bits,
+                                    floor_bits=floor, prefetch_t=2, prefetch=prefetch, alpha=0.125, device=dev)
+                stack.step(xs[0])                 # warm-up step (fills the slots it can)
+                torch.cuda.synchronize()
+                stack.stats.clear()
+                t0 = time.perf_counter()
+                for s in range(args.stack_steps):
+                    stack.step(xs[s])
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+                stack.close()
+                stt = stack.stats
+                uses = stt["miss"] + stt["hit_resident"] + stt["hit_prefetched"]
+                results.append({"slots": n_slots, "slot_bytes_GB": round(n_slots * (pool.nbytes * 1.4375) / 1e9, 1),
+                                "prefetch": prefetch, "steps_per_s": round(args.stack_steps / dt, 3),
+                                "ms_per_layer": round(dt / args.stack_steps / L * 1e3, 3),
+                                "expert_uses": uses, "miss": stt["miss"], "hit_resident": stt["hit_resident"],
+                                "hit_prefetched": stt["hit_prefetched"], "prefetch_issued": stt["prefetch_issued"],
+                                "prefetch_wasted": stt["prefetch_wasted"],
+                                "host_link_GBps": round(stt["bytes_copied"] / dt / 1e9, 1)})
+                del stack
+                torch.cuda.empty_cache()
+        out["stack_decode"] = {"workload": "32 Mixtral-shaped layers, 1 token per step, bf16 experts in pinned host memory "
+                                           "(16 distinct experts shared by the 256 layer-experts), tiers 1/3/4 with an int4 "
+                                           "floor in the first and last 4 layers, quantised on arrival, look-ahead t=2",
+                               "steps": args.stack_steps, "runs": results}
     print(json.dumps(out))
 
 

@@ -188,7 +188,7 @@ int dymoe_expert_importance(dymoe_ctx* ctx, int phase, const int32_t* idx, const
     if (!ctx) return DYMOE_ENOCTX;
     hipStream_t st = (hipStream_t)stream;
     const bool prefill = phase == DYMOE_PHASE_PREFILL;
-    if (T <= 512) {      // one workgroup ranks T tokens against T scores: quadratic, so only for short steps
+    if (T <= 256) {      // one workgroup ranks T tokens against T scores: quadratic, so only for short steps
         dymoe_launch(ctx, DYMOE_K_IMPORTANCE, dymoe::importance_block_kernel, dim3(1),
                      dim3(dymoe::kImpBlock), 0, st, idx, token_score, probs, T, E, k, k_hh,
                      prefill ? 1 : 0, importance, load);

@@ -44,8 +44,8 @@ def main():
     ap.add_argument("--stack-steps", type=int, default=0,
                     help="also decode this many steps through a 32-layer stack with the experts in pinned host "
                          "memory (BASELINE configs[4]); off by default: the run is bound by the host link")
-    ap.add_argument("--stack-slots", type=str, default="47,256",
-                    help="device slot counts to try (47 slots of 506 MB are a 24 GB budget; 256 holds every expert)")
+    ap.add_argument("--stack-budget-gb", type=float, default=24.0,
+                    help="device bytes set aside for expert slots in the stack run")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -298,18 +298,30 @@ def main():
     if args.stack_steps > 0:
         from paper_2603_19172_amd.stack import DecodeStack, HostExpertPool
         L, n_pool = 32, 16
-        for st_ in stores[1:]:
-            del st_
+        del stores[1:]
+        torch.cuda.empty_cache()
         pool = HostExpertPool(H, F, E, n_pool, lambda i: host_w[i % E] if i < E else
                               synth.expert_weights(synth.scaled(cfg, config_id=50), i % E))
+        pool.add_quantised(ctx, dev)
         routers = [bf16(synth.router(synth.scaled(cfg, config_id=100 + l))[0]) for l in range(L)]
         floor = [4 if (l < 4 or l >= L - 4) else 2 for l in range(L)]
         xs = [bf16(synth.activations(synth.scaled(cfg, config_id=200 + s))[0]) for s in range(args.stack_steps)]
+        gb = {b: pool.nbytes[b] / 1e9 for b in (16, 4, 2)}
+        budget = float(args.stack_budget_gb)
+        # one byte budget, two ways of spending it: bf16 slots that also hold what the device quantiser
+        # writes, or slots of the three formats (a quarter / half / quarter of the bytes)
+        # the paper's "4/2" mode: t_l Critical experts in 4 bits (cosine depth schedule, lambda = 0.5), the rest in 2
+        paper_tiers = [(B.depth_schedule(l, L, 0.5, E), E - B.depth_schedule(l, L, 0.5, E)) for l in range(L)]
+        plans = [("bf16", int(budget / (gb[16] + gb[4] + gb[2])), "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
+                 ("assigned", {16: int(0.25 * budget / gb[16]), 4: int(0.5 * budget / gb[4]),
+                               2: int(0.25 * budget / gb[2])}, "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
+                 ("assigned", {4: int(0.75 * budget / gb[4]), 2: int(0.25 * budget / gb[2])},
+                  "4/2 with the cosine depth schedule", paper_tiers, (4, 2), None)]
         results = []
-        for n_slots in [int(v) for v in args.stack_slots.split(",")]:
+        for transfer, slots, tier_name, tcount, tbits, flr in plans:
             for prefetch in (False, True):
-                stack = DecodeStack(ctx, H, F, E, k, routers, pool, n_slots, cfg.tier_count, cfg.tier_bits,
-                                    floor_bits=floor, prefetch_t=2, prefetch=prefetch, alpha=0.125, device=dev)
+                stack = DecodeStack(ctx, H, F, E, k, routers, pool, slots, tcount, tbits,
+                                    floor_bits=flr, prefetch=prefetch, transfer=transfer, alpha=0.125, device=dev)
                 stack.step(xs[0])                 # warm-up step (fills the slots it can)
                 torch.cuda.synchronize()
                 stack.stats.clear()
@@ -320,20 +332,21 @@ def main():
                 dt = time.perf_counter() - t0
                 stack.close()
                 stt = stack.stats
-                uses = stt["miss"] + stt["hit_resident"] + stt["hit_prefetched"]
-                results.append({"slots": n_slots, "slot_bytes_GB": round(n_slots * (pool.nbytes * 1.4375) / 1e9, 1),
-                                "prefetch": prefetch, "steps_per_s": round(args.stack_steps / dt, 3),
+                results.append({"transfer": transfer, "tiers": tier_name, "slots": slots, "prefetch": prefetch,
+                                "steps_per_s": round(args.stack_steps / dt, 3),
                                 "ms_per_layer": round(dt / args.stack_steps / L * 1e3, 3),
-                                "expert_uses": uses, "miss": stt["miss"], "hit_resident": stt["hit_resident"],
-                                "hit_prefetched": stt["hit_prefetched"], "prefetch_issued": stt["prefetch_issued"],
-                                "prefetch_wasted": stt["prefetch_wasted"],
+                                "expert_uses": stt["miss"] + stt["promote"] + stt["hit_resident"] + stt["hit_prefetched"],
+                                "miss": stt["miss"], "promote": stt["promote"], "hit_resident": stt["hit_resident"],
+                                "hit_prefetched": stt["hit_prefetched"], "reused_higher": stt["reused_higher"],
+                                "prefetch_issued": stt["prefetch_issued"], "prefetch_wasted": stt["prefetch_wasted"],
+                                "GB_moved_per_step": round(stt["bytes_copied"] / args.stack_steps / 1e9, 2),
                                 "host_link_GBps": round(stt["bytes_copied"] / dt / 1e9, 1)})
                 del stack
                 torch.cuda.empty_cache()
-        out["stack_decode"] = {"workload": "32 Mixtral-shaped layers, 1 token per step, bf16 experts in pinned host memory "
-                                           "(16 distinct experts shared by the 256 layer-experts), tiers 1/3/4 with an int4 "
-                                           "floor in the first and last 4 layers, quantised on arrival, look-ahead t=2",
-                               "steps": args.stack_steps, "runs": results}
+        out["stack_decode"] = {"workload": "32 Mixtral-shaped layers, 1 token per step, experts in pinned host memory "
+                                           "(16 distinct experts shared by the 256 layer-experts), look-ahead of the next layer's 2 "
+                                           "experts; the 1/3/4 tiers carry an int4 floor in the first and last 4 layers",
+                               "device_budget_GB": budget, "steps": args.stack_steps, "runs": results}
     print(json.dumps(out))
 
 

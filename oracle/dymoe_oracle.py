@@ -247,12 +247,14 @@ def residual_rmsnorm(h_bits, y, alpha=1.0):
 
 
 def decode_stack(h0_bits, routers, expert_matrices, k, tier_count, tier_bits, floor_bits, alpha,
-                 predict_t=0):
+                 predict_t=0, run_bits=None):
     """A stack of expert layers on one token (composition of the functions above,
     no arithmetic of its own): per layer gating, decode importance, assignment
     (with the layer's floor), quantisation of the active experts to their
     assigned width, FFN, residual + normalisation.
     routers: list of wg [E,H] bf16 bits; expert_matrices(layer, e) -> (W1, W3, W2) bf16 bits.
+    run_bits: None, or per layer a dict {expert: bits} naming the precision an active expert is
+    actually run at (a cache may hold, and then reuse, a higher precision than the assigned one).
     Returns (final h bits, per-layer list of (idx, bits of idx, logits, importance),
     per-layer predicted top-t experts of the NEXT layer from this layer's input)."""
     h = _c(h0_bits, np.uint16)
@@ -273,6 +275,8 @@ def decode_stack(h0_bits, routers, expert_matrices, k, tier_count, tier_bits, fl
             if e not in idx[0] or b == 0:
                 experts.append({})
                 continue
+            if run_bits is not None:
+                b = int(run_bits[l].get(e, b))
             use_bits[e] = b
             mats = expert_matrices(l, e)
             experts.append({"w": mats} if b == 16 else {"q": [quantize_pack(m, b) for m in mats]})

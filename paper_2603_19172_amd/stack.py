@@ -2,16 +2,21 @@
 resident in pinned HOST memory (paper Sec. 4.4: dynamic expert orchestration).
 
 Per layer the compute stream runs the hot path of `layer.py`; the experts it
-needs are brought into a small set of device slots, on demand or ahead of time:
-the next layer's router applied to the current hidden state (Sec. 4.4.1 Eq. 6)
-names the t experts to prefetch (Eq. 8), and their bf16 weights are copied on a
-side stream (dymoe_prefetch_submit / dymoe_prefetch_wait) while the current
-layer computes.  Experts arrive as bf16 and are quantised on the device to the
-width the precision assignment asks for (S4 on arrival).
+needs are brought into device slots, on demand or ahead of time: the next
+layer's router applied to the current hidden state (Sec. 4.4.1 Eq. 6) names the
+experts to prefetch (Eq. 8), which are copied on a side stream
+(dymoe_prefetch_submit / dymoe_prefetch_wait) while the current layer computes.
+
+Two ways of moving an expert:
+  transfer="bf16"      the bf16 weights travel and are quantised on the device
+                       to the width the precision assignment asks for;
+  transfer="assigned"  the host also holds the int4 and int2 formats (made once
+                       by the device quantiser) and the format the assignment
+                       asks for travels: fewer bytes on the host link, and the
+                       mixed-precision cache of Sec. 4.4.2 decides what stays.
 
 Host control flow and bookkeeping only; every arithmetic step runs in
-libdymoe.so.  The device slots are a plain LRU cache keyed by (layer, expert);
-the paper's mixed-precision cache rules are not modelled here.
+libdymoe.so.
 """
 import collections
 import ctypes as C
@@ -19,180 +24,238 @@ import ctypes as C
 import torch
 
 from . import binding as B
+from .cache import MixedPrecisionCache
 from .layer import MoELayer
 
 FMT_BYTES = C.sizeof(B.ExpertFmt)
 
 
+def quant_layout(H, F, bits, group=64):
+    """Byte offsets of a quantised expert stored as one block: for each matrix
+    codes | scale | zero.  Returns ([(codes, scale, zero)] * 3, total bytes)."""
+    offs, pos = [], 0
+    for n, kk in ((F, H), (F, H), (H, F)):
+        codes, sz = n * kk * bits // 8, n * (kk // group) * 2
+        offs.append((pos, pos + codes, pos + codes + sz))
+        pos += codes + 2 * sz
+    return offs, pos
+
+
 class HostExpertPool:
-    """bf16 expert weights in pinned host memory.  To bound memory and set-up
-    time, `n_pool` distinct experts are drawn and (layer, expert) maps to entry
-    (layer * E + expert) mod n_pool.  One entry is W1 [F,H] | W3 [F,H] | W2 [H,F]
-    back to back, so an expert moves with a single copy."""
+    """Expert weights in pinned host memory.  To bound memory and set-up time,
+    `n_pool` distinct experts are drawn and (layer, expert) maps to entry
+    (layer * E + expert) mod n_pool.  A bf16 entry is W1 [F,H] | W3 [F,H] |
+    W2 [H,F] back to back, so an expert moves with a single copy."""
 
     def __init__(self, H, F, E, n_pool, matrices):
         # matrices(i) -> [W1, W3, W2] as uint16 numpy arrays (bf16 bits) of pool entry i
         self.H, self.F, self.E, self.n_pool = H, F, E, n_pool
         self.elems = 3 * H * F
-        self.nbytes = 2 * self.elems
-        self.buf = torch.empty((n_pool, self.elems), dtype=torch.int16, pin_memory=True)
-        view = self.buf.numpy()
+        self.nbytes = {16: 2 * self.elems}
+        self.buf = {16: torch.empty((n_pool, 2 * self.elems), dtype=torch.uint8, pin_memory=True)}
+        view = self.buf[16].numpy().view("int16")
         for i in range(n_pool):
             w1, w3, w2 = matrices(i)
             view[i, :H * F] = w1.reshape(-1).view("int16")
             view[i, H * F:2 * H * F] = w3.reshape(-1).view("int16")
             view[i, 2 * H * F:] = w2.reshape(-1).view("int16")
 
+    def add_quantised(self, ctx, device):
+        """int4 and int2 copies of every entry, made by the device quantiser and kept in pinned host memory."""
+        H, F = self.H, self.F
+        wdev = torch.empty((self.elems,), dtype=torch.bfloat16, device=device)
+        for b in (4, 2):
+            offs, total = quant_layout(H, F, b)
+            self.nbytes[b] = total
+            self.buf[b] = torch.empty((self.n_pool, total), dtype=torch.uint8, pin_memory=True)
+            stage = torch.empty((total,), dtype=torch.uint8, device=device)
+            for i in range(self.n_pool):
+                wdev.view(torch.uint8).copy_(self.buf[16][i], non_blocking=True)
+                for m, (n, kk) in enumerate(((F, H), (F, H), (H, F))):
+                    w = wdev[m * H * F:(m + 1) * H * F].view(n, kk)
+                    co, so, zo = offs[m]
+                    B._check(B.lib.dymoe_quantize_pack(ctx._h, w.data_ptr(), n, kk, b, 64, stage.data_ptr() + co,
+                                                       stage.data_ptr() + so, stage.data_ptr() + zo,
+                                                       torch.cuda.current_stream().cuda_stream), "dymoe_quantize_pack")
+                self.buf[b][i].copy_(stage, non_blocking=True)
+            torch.cuda.synchronize()
+
     def entry(self, layer, e):
         return (layer * self.E + e) % self.n_pool
 
-    def host_ptr(self, layer, e):
-        return self.buf.data_ptr() + self.entry(layer, e) * self.nbytes
+    def host_ptr(self, layer, e, fmt=16):
+        return self.buf[fmt].data_ptr() + self.entry(layer, e) * self.nbytes[fmt]
 
 
 class _Slot:
-    """Device buffers of one resident expert."""
+    """Device buffers of one resident expert in one transferred format.  A bf16
+    slot of the "bf16" transfer mode also carries the buffers the device
+    quantiser writes."""
 
-    def __init__(self, H, F, device, group=64):
-        self.w = torch.empty((3 * H * F,), dtype=torch.bfloat16, device=device)
-        self.q = {}
-        for b in (4, 2):
-            self.q[b] = [(torch.empty((n, kk * b // 8), dtype=torch.uint8, device=device),
-                          torch.empty((n, kk // group), dtype=torch.float16, device=device),
-                          torch.empty((n, kk // group), dtype=torch.float16, device=device))
-                         for n, kk in ((F, H), (F, H), (H, F))]
+    def __init__(self, H, F, fmt_bits, device, with_quant_buffers):
         fmt = B.ExpertFmt()
-        base = self.w.data_ptr()
-        for i in range(3):
-            fmt.w[i] = base + i * H * F * 2
-            for b in (4, 2):
-                cd, sc, zr = self.q[b][i]
-                getattr(fmt, "q%d" % b)[i] = cd.data_ptr()
-                getattr(fmt, "s%d" % b)[i] = sc.data_ptr()
-                getattr(fmt, "z%d" % b)[i] = zr.data_ptr()
+        self.fmt_bits = fmt_bits
+        if fmt_bits == 16:
+            self.buf = torch.empty((6 * H * F,), dtype=torch.uint8, device=device)
+            for i in range(3):
+                fmt.w[i] = self.buf.data_ptr() + i * H * F * 2
+            self.qbuf = {}
+            if with_quant_buffers:
+                for b in (4, 2):
+                    offs, total = quant_layout(H, F, b)
+                    self.qbuf[b] = torch.empty((total,), dtype=torch.uint8, device=device)
+                    self._point(fmt, b, self.qbuf[b].data_ptr(), offs)
+        else:
+            offs, total = quant_layout(H, F, fmt_bits)
+            self.buf = torch.empty((total,), dtype=torch.uint8, device=device)
+            self._point(fmt, fmt_bits, self.buf.data_ptr(), offs)
         self.fmt = torch.frombuffer(bytearray(bytes(fmt)), dtype=torch.uint8).pin_memory()
-        self.key = None          # (layer, expert) held
         self.copy_event = None   # event of a copy not yet waited for on the compute stream
         self.last_use = None     # torch event: the compute stream has finished reading the slot
         self.prefetched = False  # filled ahead of time and not used yet
 
+    @staticmethod
+    def _point(fmt, b, base, offs):
+        for i in range(3):
+            co, so, zo = offs[i]
+            getattr(fmt, "q%d" % b)[i] = base + co
+            getattr(fmt, "s%d" % b)[i] = base + so
+            getattr(fmt, "z%d" % b)[i] = base + zo
+
 
 class DecodeStack:
-    def __init__(self, ctx, H, F, E, k, routers, pool, n_slots, tier_count, tier_bits,
-                 floor_bits=None, prefetch_t=2, prefetch=True, alpha=0.125, device="cuda:0"):
-        """routers: list over layers of wg [E,H] bf16 device tensors.  floor_bits: per-layer
-        floor of the assignment (list) or None.  prefetch_t: experts fetched ahead per layer (Eq. 8)."""
-        if n_slots < k + (prefetch_t if prefetch else 0):
-            raise ValueError("need at least k + prefetch_t slots")
+    def __init__(self, ctx, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
+                 prefetch=True, transfer="bf16", alpha=0.125, device="cuda:0"):
+        """routers: list over layers of wg [E,H] bf16 device tensors.  slots: number of bf16 slots
+        (transfer="bf16") or {16: n, 4: n, 2: n} (transfer="assigned").  floor_bits: per-layer floor
+        of the assignment (list) or None.  tier_count: one tuple for every layer, or a list of
+        per-layer tuples (e.g. (t_l, E - t_l) from the depth schedule of Sec. 4.3).  With prefetch,
+        the k experts the next layer is predicted to route to are fetched ahead (Eq. 8 with t = k)."""
+        if transfer not in ("bf16", "assigned"):
+            raise ValueError("transfer must be 'bf16' or 'assigned'")
         self.ctx, self.H, self.F, self.E, self.k = ctx, H, F, E, k
         self.L = len(routers)
-        self.routers, self.pool = routers, pool
+        self.routers, self.pool, self.transfer = routers, pool, transfer
         self.floor = list(floor_bits) if floor_bits is not None else [0] * self.L
-        self.t, self.prefetch, self.alpha = prefetch_t, prefetch, alpha
-        self.dev = device
-        self.layer = MoELayer(ctx, 1, H, F, E, k, "decode", tier_count, tier_bits, out_dtype=B.OUT_F32,
+        self.prefetch, self.alpha, self.dev = prefetch, alpha, device
+        counts = {16: int(slots)} if transfer == "bf16" else {b: int(slots.get(b, 0)) for b in (16, 4, 2)}
+        need = k * (2 if prefetch else 1)
+        if any(0 < n < need for n in counts.values()) or not any(counts.values()):
+            raise ValueError("every configured pool needs at least %d slots" % need)
+        self.cache = MixedPrecisionCache(counts)
+        self.slots = {(b, i): _Slot(H, F, b, device, transfer == "bf16") for b, n in counts.items() for i in range(n)}
+        per_layer = isinstance(tier_count[0], (tuple, list))
+        self.tiers = [tuple(tc) for tc in tier_count] if per_layer else [tuple(tier_count)] * self.L
+        if len(self.tiers) != self.L or any(len(tc) != len(tier_bits) for tc in self.tiers):
+            raise ValueError("tier_count: one tuple, or one per layer, as long as tier_bits")
+        self.tier_arrays = [(C.c_int32 * len(tc))(*[int(v) for v in tc]) for tc in self.tiers]
+        mk = lambda: MoELayer(ctx, 1, H, F, E, k, "decode", self.tiers[0], tier_bits, out_dtype=B.OUT_F32,
                               path=B.PATH_GEMV, device=device)
-        self.slots = [_Slot(H, F, device) for _ in range(n_slots)]
-        self.lru = collections.OrderedDict((i, None) for i in range(n_slots))   # slot ids, oldest first
-        self.where = {}                                                        # (layer, e) -> slot id
+        self.layer, self.ahead = mk(), mk()     # buffers of the current layer, and of the look-ahead prediction
         self.tables = torch.zeros((self.L, E, FMT_BYTES), dtype=torch.uint8, device=device)
-        self.table_slot = {}                                                   # (layer, e) -> slot id written in the table
-        self.pred = torch.empty((1, max(1, prefetch_t)), dtype=torch.int32, device=device)
-        self.pred_w = torch.empty((1, max(1, prefetch_t)), dtype=torch.float32, device=device)
+        self.table_slot = {}                    # (layer, e) -> slot written in the table
         self.h = [torch.empty((1, H), dtype=torch.bfloat16, device=device) for _ in range(2)]
         self.side = torch.cuda.Stream(device=device)
-        self.host_idx = torch.empty((1, k), dtype=torch.int32).pin_memory()
-        self.host_bits = torch.empty((E,), dtype=torch.uint8).pin_memory()
-        self.host_pred = torch.empty((1, max(1, prefetch_t)), dtype=torch.int32).pin_memory()
+        pin = lambda shape, dt: torch.empty(shape, dtype=dt).pin_memory()
+        self.host_idx, self.host_bits = pin((1, k), torch.int32), pin((E,), torch.uint8)
+        self.host_pidx, self.host_pbits = pin((1, k), torch.int32), pin((E,), torch.uint8)
         self.stats = collections.Counter()
-        self.trace = []     # per step and layer: (idx, bits of the active experts)
+        self.trace = []     # per step and layer: (experts, assigned bits, bits they were run at)
 
-    # -- residency
-    def _touch(self, sid):
-        self.lru.move_to_end(sid)
-
-    def _fill(self, key, protect, ahead):
-        """Bring expert `key` into a slot (evicting the least recently used one
-        outside `protect`), by a copy on the side stream.  Returns the slot id."""
-        sid = next(s for s in self.lru if s not in protect)
-        slot = self.slots[sid]
-        if slot.key is not None:
-            self.where.pop(slot.key, None)
-            if slot.prefetched:
-                self.stats["prefetch_wasted"] += 1
+    def _fill(self, act, key, ahead):
+        """Copy the format `act.load_bits` of expert `key` into the slot the cache chose, on the side stream."""
+        slot = self.slots[act.slot]
+        if slot.prefetched:
+            self.stats["prefetch_wasted"] += 1
         if slot.copy_event is not None:           # an unused earlier copy: same stream, ordered before this one
             self.ctx.prefetch_release(slot.copy_event)
         if slot.last_use is not None:             # the compute stream may still be reading the old content
             self.side.wait_event(slot.last_use)
         layer, e = key
-        slot.copy_event = self.ctx.prefetch_submit(self.pool.host_ptr(layer, e), slot.w.data_ptr(),
-                                                   self.pool.nbytes, self.side.cuda_stream)
-        slot.key, slot.prefetched = key, ahead
-        self.where[key] = sid
-        self._touch(sid)
-        self.stats["bytes_copied"] += self.pool.nbytes
-        return sid
+        nbytes = self.pool.nbytes[act.load_bits]
+        slot.copy_event = self.ctx.prefetch_submit(self.pool.host_ptr(layer, e, act.load_bits), slot.buf.data_ptr(),
+                                                   nbytes, self.side.cuda_stream)
+        slot.prefetched = ahead
+        self.stats["bytes_copied"] += nbytes
+        self.stats["copies_%d" % act.load_bits] += 1
 
     def step(self, h0):
         """One decode step through all layers.  h0: [1,H] bf16 on the device.  Returns the final hidden state."""
-        lay, ctx = self.layer, self.ctx
+        lay, nxt_lay, ctx = self.layer, self.ahead, self.ctx
         cs = torch.cuda.current_stream()
         st = cs.cuda_stream
         h = self.h[0]
         h.copy_(h0)
         step_trace = []
         for l in range(self.L):
-            lay.floor_bits = self.floor[l]
+            lay.floor_bits, lay._tc = self.floor[l], self.tier_arrays[l]
             lay.front(h, self.routers[l], None, st)
             look = self.prefetch and l + 1 < self.L
-            if look:     # Eq. 6: the next layer's router on the current hidden state; Eq. 8: its top t
-                B._check(B.lib.dymoe_route_topk(ctx._h, h.data_ptr(), self.routers[l + 1].data_ptr(), None, 1,
-                                                self.H, self.E, self.t, 1, self.pred.data_ptr(),
-                                                self.pred_w.data_ptr(), None, st), "dymoe_route_topk")
-                self.host_pred.copy_(self.pred, non_blocking=True)
+            if look:     # Eq. 6: the next layer's router (and precision rule) on the current hidden state
+                nxt_lay.floor_bits, nxt_lay._tc = self.floor[l + 1], self.tier_arrays[l + 1]
+                nxt_lay.front(h, self.routers[l + 1], None, st)
+                self.host_pidx.copy_(nxt_lay.idx, non_blocking=True)
+                self.host_pbits.copy_(nxt_lay.bits, non_blocking=True)
             self.host_idx.copy_(lay.idx, non_blocking=True)
             self.host_bits.copy_(lay.bits, non_blocking=True)
             cs.synchronize()
             active = [int(e) for e in self.host_idx[0].tolist()]
             abits = [int(self.host_bits[e]) for e in active]
-            step_trace.append((tuple(active), tuple(abits)))
-            need = [e for e, b in zip(active, abits) if b != 0]
-            # this layer's experts: resident, arriving, or fetched now (the resident ones are
+            want = lambda b: 16 if self.transfer == "bf16" else b
+            need = [(e, b) for e, b in zip(active, abits) if b != 0]
+            # this layer's experts: resident, arriving, or fetched now (what is already resident is
             # protected first, so that fetching one expert cannot evict another one of the layer)
-            used = set(self.where[(l, e)] for e in need if (l, e) in self.where)
-            for e in need:
+            protect = set()
+            for e, b in need:
+                if self.cache.covers((l, e), want(b)):
+                    protect.add(self.cache.resident((l, e)))
+            used_bits = dict(zip(active, abits))
+            override = False
+            for e, b in need:
                 key = (l, e)
-                sid = self.where.get(key)
-                if sid is None:
-                    sid = self._fill(key, used, ahead=False)
-                    self.stats["miss"] += 1
+                act = self.cache.request(key, want(b), protect)
+                protect.add(act.slot)
+                slot = self.slots[act.slot]
+                if act.load_bits:
+                    self._fill(act, key, ahead=False)
+                    self.stats[act.kind] += 1
                 else:
-                    self.stats["hit_prefetched" if self.slots[sid].prefetched else "hit_resident"] += 1
-                    self._touch(sid)
-                used.add(sid)
-                slot = self.slots[sid]
+                    self.stats["hit_prefetched" if slot.prefetched else "hit_resident"] += 1
                 slot.prefetched = False
                 if slot.copy_event is not None:
                     ctx.prefetch_wait(slot.copy_event, st)
                     ctx.prefetch_release(slot.copy_event)
                     slot.copy_event = None
-                if self.table_slot.get(key) != sid:
+                if self.table_slot.get(key) != act.slot:
                     self.tables[l, e].copy_(slot.fmt, non_blocking=True)
-                    self.table_slot[key] = sid
+                    self.table_slot[key] = act.slot
+                if self.transfer == "assigned" and act.use_bits != b:     # Conservative Reuse: run at the resident precision
+                    self.host_bits[e] = act.use_bits
+                    used_bits[e] = act.use_bits
+                    override = True
+                    self.stats["reused_higher"] += 1
+            if override:
+                lay.bits.copy_(self.host_bits, non_blocking=True)
+            step_trace.append((tuple(active), tuple(abits), tuple(used_bits[e] for e in active)))
             # the next layer's predicted experts, copied while this layer computes
             if look:
-                protect = set(used)
-                for e in [int(v) for v in self.host_pred[0].tolist()]:
+                for e in [int(v) for v in self.host_pidx[0].tolist()]:
+                    pb = int(self.host_pbits[e])
                     key = (l + 1, e)
-                    sid = self.where.get(key)
-                    if sid is None:
-                        sid = self._fill(key, protect, ahead=True)
-                        self.stats["prefetch_issued"] += 1
-                    protect.add(sid)
+                    if pb == 0:
+                        continue
+                    if self.cache.covers(key, want(pb)):
+                        protect.add(self.cache.resident(key))
+                        continue
+                    act = self.cache.request(key, want(pb), protect)
+                    protect.add(act.slot)
+                    self._fill(act, key, ahead=True)
+                    self.stats["prefetch_issued"] += 1
             table = self.tables[l]
-            B._check(B.lib.dymoe_quantize_experts(ctx._h, table.data_ptr(), lay.bits.data_ptr(), lay.load.data_ptr(),
-                                                  self.E, self.H, self.F, 64, B.LAYOUT_ROWMAJOR, st),
-                     "dymoe_quantize_experts")
+            if self.transfer == "bf16":      # S4 on arrival
+                B._check(B.lib.dymoe_quantize_experts(ctx._h, table.data_ptr(), lay.bits.data_ptr(),
+                                                      lay.load.data_ptr(), self.E, self.H, self.F, 64,
+                                                      B.LAYOUT_ROWMAJOR, st), "dymoe_quantize_experts")
             B._check(B.lib.dymoe_moe_ffn_mixed(ctx._h, h.data_ptr(), lay.idx.data_ptr(), lay.gate.data_ptr(),
                                                lay.bits.data_ptr(), table.data_ptr(), 1, self.H, self.F, self.E,
                                                self.k, 64, B.OUT_F32, B.PATH_GEMV, lay.y.data_ptr(),
@@ -203,8 +266,8 @@ class DecodeStack:
                      "dymoe_residual_rmsnorm")
             done = torch.cuda.Event()
             done.record(cs)
-            for sid in used:
-                self.slots[sid].last_use = done
+            for e, b in need:
+                self.slots[self.cache.resident((l, e))].last_use = done
             h = nxt
         self.trace.append(step_trace)
         self.stats["steps"] += 1
@@ -212,7 +275,7 @@ class DecodeStack:
 
     def close(self):
         torch.cuda.synchronize()
-        for slot in self.slots:
+        for slot in self.slots.values():
             if slot.copy_event is not None:
                 self.ctx.prefetch_release(slot.copy_event)
                 slot.copy_event = None

@@ -62,19 +62,45 @@ def test_residual_rmsnorm_against_the_oracle(ctx, T, H, alpha):
         assert (got[T - 1] == 0).all()
 
 
-def _small_stack(ctx, L, n_slots, prefetch, seed0):
+def _small_stack(ctx, L, slots, prefetch, seed0, transfer="bf16", pool=None):
     H, F, E, k = 256, 512, 8, 2
     cfgs = [synth.scaled(synth.CONFIGS["tiny"], T=1, phase="decode", config_id=seed0 + l) for l in range(L)]
     routers_np = [synth.router(c)[0] for c in cfgs]
     n_pool = 12
     pool_cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=seed0 + 50)
     mats = {i: synth.expert_weights(pool_cfg, i) for i in range(n_pool)}
-    pool = HostExpertPool(H, F, E, n_pool, lambda i: mats[i])
+    if pool is None:
+        pool = HostExpertPool(H, F, E, n_pool, lambda i: mats[i])
+        if transfer == "assigned":
+            pool.add_quantised(ctx, DEV)
     floor = [4] + [0] * (L - 2) + [4]
-    stack = DecodeStack(ctx, H, F, E, k, [to_bf16(r) for r in routers_np], pool, n_slots, (1, 3, 4), (16, 4, 2),
-                        floor_bits=floor, prefetch_t=2, prefetch=prefetch, alpha=0.25, device=DEV)
+    stack = DecodeStack(ctx, H, F, E, k, [to_bf16(r) for r in routers_np], pool, slots, (1, 3, 4), (16, 4, 2),
+                        floor_bits=floor, prefetch=prefetch, transfer=transfer, alpha=0.25, device=DEV)
     expert_matrices = lambda l, e: mats[pool.entry(l, e)]
     return stack, routers_np, expert_matrices, floor, cfgs[0]
+
+
+def _uses(st):
+    return st.get("miss", 0) + st.get("promote", 0) + st.get("hit_resident", 0) + st.get("hit_prefetched", 0)
+
+
+def _check_against_oracle(outs, trace, routers_np, expert_matrices, floor):
+    checked = 0
+    for s, (x, h_dev) in enumerate(outs):
+        run_bits = [dict(zip(ex, used)) for (ex, _, used) in trace[s]]
+        ref_h, log, _ = O.decode_stack(x, routers_np, expert_matrices, 2, (1, 3, 4), (16, 4, 2), floor, 0.25,
+                                       run_bits=run_bits)
+        if not all(margin_ok(lg, 2).all() for (_, _, lg, _) in log):
+            continue                     # a near tie somewhere in the stack: decisions may legitimately differ
+        checked += 1
+        for l, (idx, bts, _, _) in enumerate(log):
+            assert trace[s][l][0] == tuple(int(v) for v in idx[0])
+            assert trace[s][l][1] == tuple(int(v) for v in bts)            # the assignment itself
+        got = synth.bf16_bits_to_f32(bits_of(h_dev)).astype(np.float64)
+        want = synth.bf16_bits_to_f32(ref_h).astype(np.float64)
+        # unit-RMS rows; the FFN tolerance (2e-2 of a row's RMS, scaled by alpha) accumulates over the layers
+        assert np.abs(got - want).max() <= 2e-2
+    assert checked >= 1
 
 
 def test_stack_decode_matches_the_oracle_and_prefetch_changes_nothing(ctx):
@@ -93,25 +119,11 @@ def test_stack_decode_matches_the_oracle_and_prefetch_changes_nothing(ctx):
         assert torch.equal(a, b)
     assert traces[False] == traces[True]
     for st in stats.values():
-        assert st["miss"] + st.get("hit_resident", 0) + st.get("hit_prefetched", 0) == L * 2 * steps
+        assert _uses(st) == L * 2 * steps
     assert stats[False].get("hit_prefetched", 0) == 0 and stats[False].get("prefetch_issued", 0) == 0
     assert stats[True]["prefetch_issued"] > 0
     assert stats[True]["miss"] <= stats[False]["miss"]
-    # against the oracle's composition of its own functions
-    checked = 0
-    for s, (x, h_dev) in enumerate(outs[True]):
-        ref_h, log, preds = O.decode_stack(x, routers_np, expert_matrices, 2, (1, 3, 4), (16, 4, 2), floor, 0.25,
-                                           predict_t=2)
-        if not all(margin_ok(lg, 2).all() for (_, _, lg, _) in log):
-            continue                     # a near tie somewhere in the stack: decisions may legitimately differ
-        checked += 1
-        for l, (idx, bts, _, _) in enumerate(log):
-            assert traces[True][s][l] == (tuple(int(v) for v in idx[0]), tuple(int(v) for v in bts))
-        got = synth.bf16_bits_to_f32(bits_of(h_dev)).astype(np.float64)
-        want = synth.bf16_bits_to_f32(ref_h).astype(np.float64)
-        # unit-RMS rows; the FFN tolerance (2e-2 of a row's RMS, scaled by alpha) accumulates over the layers
-        assert np.abs(got - want).max() <= 2e-2
-    assert checked >= 1
+    _check_against_oracle(outs[True], traces[True], routers_np, expert_matrices, floor)
 
 
 def test_stack_with_room_for_everything_copies_each_expert_once(ctx):
@@ -122,6 +134,30 @@ def test_stack_with_room_for_everything_copies_each_expert_once(ctx):
         stack.step(to_bf16(x))
     stack.close()
     st = stack.stats
-    copies = st["bytes_copied"] // stack.pool.nbytes
-    assert copies == len(stack.where) <= L * 8          # nothing was ever evicted
+    copies = st["bytes_copied"] // stack.pool.nbytes[16]
+    assert copies == len(stack.cache.where) <= L * 8          # nothing was ever evicted
     assert st["miss"] + st.get("prefetch_issued", 0) == copies
+
+
+def test_stack_moving_the_assigned_format_follows_the_cache_rules(ctx):
+    """transfer="assigned": the int4 / int2 / bf16 format the assignment asks for travels; an expert
+    resident at a higher precision is run at that precision (Conservative Reuse), which the
+    oracle is told through run_bits; everything else is the oracle's own chain."""
+    L, steps = 4, 6
+    slots = {16: 4, 4: 4, 2: 4}
+    stack, routers_np, expert_matrices, floor, cfg0 = _small_stack(ctx, L, slots, True, 700, transfer="assigned")
+    outs = []
+    for s in range(steps):
+        x, _ = synth.activations(synth.scaled(cfg0, config_id=800 + (s % 3)))     # tokens come back: reuse happens
+        outs.append((x, stack.step(to_bf16(x)).clone()))
+    stack.close()
+    st = stack.stats
+    assert _uses(st) == L * 2 * steps
+    # bytes on the link: only the formats asked for, never more than bf16 for everything
+    moved = sum(st.get("copies_%d" % b, 0) * stack.pool.nbytes[b] for b in (16, 4, 2))
+    assert moved == st["bytes_copied"]
+    assert st["copies_4"] + st["copies_2"] > 0
+    for step in stack.trace:
+        for (ex, assigned, used) in step:
+            assert all(u >= a for a, u in zip(assigned, used))       # never run below the assigned precision
+    _check_against_oracle(outs, stack.trace, routers_np, expert_matrices, floor)

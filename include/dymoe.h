@@ -15,9 +15,9 @@
  * Conventions that hold for every call unless a comment says otherwise:
  *  - Every pointer is a DEVICE pointer; arguments marked "host" are host
  *    pointers that are read before the call returns.
- *  - The caller allocates and owns every buffer.  Apart from the context's
- *    own scratch (dymoe_create / dymoe_destroy) the library never allocates or
- *    frees device memory and keeps no pointer after the call returns.
+ *  - The caller allocates and owns every buffer.  The library never allocates
+ *    or frees device memory and keeps no pointer after the call returns
+ *    (dymoe_prefetch_submit creates an event that the caller releases).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls enqueue work and return without synchronising; nothing is read
  *    back to the host, so the five steps chain on one stream with no host
@@ -67,16 +67,17 @@ extern "C" {
 #define DYMOE_FRONT_MAX_TOKENS 16   /* tokens per step of dymoe_decode_front */
 #define DYMOE_MAX_EXPERTS 1024
 
-/* opaque; holds the device ordinal, its properties and 64 KiB of device scratch
- * that dymoe_create allocates and dymoe_destroy frees (work lists).  Calls that
- * share a context must be issued on one stream, or be ordered by the caller. */
+/* opaque; holds the device ordinal, its properties and the records of the
+ * per-kernel timing facility.  It owns no device memory.  Calls that share a
+ * context must come from one host thread at a time. */
 typedef struct dymoe_ctx dymoe_ctx;
 
 /*
  * One expert's weights in every precision the caller has materialised.
  * Index 0, 1, 2 of each array = W1 (gate, [F,H]), W3 (up, [F,H]), W2 (down, [H,F]).
- * w: bf16, row-major.  q4/q2: packed codes; s4, z4, s2, z2: fp16 scale and zero,
- * one per group of 64 columns.  wt: optional copy of w in the tile layout
+ * w: bf16, row-major.  q8/q4/q2: packed codes; s8, z8, s4, z4, s2, z2: fp16 scale
+ * and zero, one per group of 64 columns (the 8-bit state is the top of the
+ * paper's precision spectrum, Sec. 1).  wt: optional copy of w in the tile layout
  * (dymoe_pack_tiles), read by the GEMM path for 16-bit experts; when NULL that
  * path reads w row by row (slower).
  * Entries for precisions that are never selected may be NULL.
@@ -90,11 +91,13 @@ typedef struct dymoe_ctx dymoe_ctx;
  *    128*kt+64*kb .. +64 (one quantisation group).  bf16: 8 KiB per tile, the
  *    lane's chunk j (8 columns, 16 bytes) at byte j*1024 + l*16.  int4: 2 KiB
  *    of codes per tile, the lane's chunk c (32 codes) at byte c*1024 + l*16.
- *    int2: 1 KiB per tile, the lane's 64 codes at byte l*16.  Codes inside a
+ *    int2: 1 KiB per tile, the lane's 64 codes at byte l*16.  int8: 4 KiB per
+ *    tile, the lane's chunk c (16 codes) at byte c*1024 + l*16.  Codes inside a
  *    chunk are packed as in the row-major layout.  scale / zero: 64 fp16 per
  *    tile, the lane's at index l.
- * The GEMV path of dymoe_moe_ffn_mixed reads q4/q2 row-major, the GEMM path
+ * The GEMV path of dymoe_moe_ffn_mixed reads the codes row-major, the GEMM path
  * reads them tiled: quantize with the layout of the path that will run.
+ * (q8/s8/z8 were added after the other fields and sit at the end.)
  */
 typedef struct {
     const void* w[3];
@@ -105,6 +108,9 @@ typedef struct {
     uint8_t* q2[3];
     void* s2[3];
     void* z2[3];
+    uint8_t* q8[3];
+    void* s8[3];
+    void* z8[3];
 } dymoe_expert_fmt;
 
 /* Create / destroy a context bound to HIP device `device`.  Host calls. */
@@ -180,7 +186,7 @@ int dymoe_depth_schedule(int layer, int n_layers, double lambda, int M);
  * importance [E]: int32 for DYMOE_PHASE_PREFILL, fp32 for DYMOE_PHASE_DECODE.
  * load [E] int32 or NULL.  tier_count / tier_bits: HOST arrays of n_tiers
  * entries (1 <= n_tiers <= DYMOE_MAX_TIERS), counts >= 0 summing to E, bits in
- * {0,2,4,16}.  bits [E] uint8, rank [E] int32 (position of expert e) or NULL.
+ * {0,2,4,8,16}.  bits [E] uint8, rank [E] int32 (position of expert e) or NULL.
  * The two-tier paper mode is tier_count = {t_l, E - t_l}.
  */
 int dymoe_assign_precision(dymoe_ctx* ctx, int phase, const void* importance,
@@ -216,10 +222,10 @@ int dymoe_decode_front(dymoe_ctx* ctx, const void* x, const void* wg, const floa
  *   inv   = s > 0 ? 1/s : 0
  *   q     = clamp(rint((w - m) * inv), 0, 2^bits-1)
  * Codes are packed little-endian along the row: code j of a byte sits at bit
- * bits*j (int4: byte = q[2i] | q[2i+1]<<4; int2: four codes per byte).
+ * bits*j (int4: byte = q[2i] | q[2i+1]<<4; int2: four codes per byte; int8: one).
  * The dequantised weight is s*q + m.
  * w [N,K] bf16 (finite, magnitude within fp16 range), codes [N, K*bits/8],
- * scale and zero [N, K/group] fp16.  bits in {2,4}; group = 64; K multiple of
+ * scale and zero [N, K/group] fp16.  bits in {2,4,8}; group = 64; K multiple of
  * group; w and codes 16-byte aligned.
  */
 int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits, int group,
@@ -227,9 +233,9 @@ int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits,
 
 /*
  * Device-driven quantization of a layer's experts, so that the precision
- * decision never travels to the host: for each expert e with bits[e] in {2,4}
+ * decision never travels to the host: for each expert e with bits[e] in {2,4,8}
  * (and load[e] > 0 when load is given), quantize table[e].w[0..3) at bits[e]
- * into table[e].q4/s4/z4 or q2/s2/z2 (same arithmetic as dymoe_quantize_pack;
+ * into table[e].q8/s8/z8, q4/s4/z4 or q2/s2/z2 (same arithmetic as dymoe_quantize_pack;
  * layout = DYMOE_LAYOUT_ROWMAJOR or DYMOE_LAYOUT_TILE, the latter needs H and F
  * multiples of 128).  Experts at 16 or 0 bits are left untouched.
  * table [E] device, bits [E] uint8 device, load [E] int32 device or NULL.
@@ -252,11 +258,11 @@ int dymoe_pack_tiles(dymoe_ctx* ctx, const void* w, long N, long K, void* tiles,
  * skipped):
  *   y[t,:] = sum_{slot<k} w[t,slot] * W2_e( silu(W1_e x_t) * (W3_e x_t) ),
  *   e = idx[t,slot], each expert's weights taken at bits[e]: 16 = table[e].w,
- *   4 / 2 = the dequantised q4 / q2 codes, 0 = term omitted (no renormalising).
+ *   8 / 4 / 2 = the dequantised q8 / q4 / q2 codes, 0 = term omitted (no renormalising).
  * x [T,H] bf16, idx [T,k] int32, w [T,k] fp32, bits [E] uint8, table [E].
  * y [T,H] bf16 (DYMOE_OUT_BF16) or fp32 (DYMOE_OUT_F32); every row is written.
  * path: DYMOE_PATH_AUTO picks GEMV for T <= 4 (or when the sizes rule out the
- * GEMM), GEMM otherwise.  GEMV reads q4/q2 in DYMOE_LAYOUT_ROWMAJOR, GEMM in
+ * GEMM), GEMM otherwise.  GEMV reads the codes in DYMOE_LAYOUT_ROWMAJOR, GEMM in
  * DYMOE_LAYOUT_TILE.
  * workspace: at least dymoe_workspace_bytes(T,H,F,E,k) bytes, 256-byte aligned;
  * contents are scratch.  Limits: group = 64; H, F multiples of 64;
@@ -327,7 +333,7 @@ int dymoe_stream_copy(dymoe_ctx* ctx, const void* src, void* dst, size_t bytes, 
  * gemm_combine, stream_copy, decode_front) carry a start and a stop HIP event on the dispatch itself, so
  * the interval is the kernel's execution time on the launch stream; 0 switches
  * timing off.  Either way, records not yet read are dropped.
- * dymoe_timing_read: waits for the recorded launches of `kernel`, returns
+ * dymoe_timing_read: waits for the recorded launches of `kernel`, drops their records and returns
  * their summed duration in milliseconds and their count (host pointers).
  * Do not enable timing while the stream is being captured into a graph.
  * dymoe_kernel_name: the kernel's name as a profiler shows it, NULL if unknown.

@@ -47,7 +47,8 @@ class ExpertFmt(C.Structure):
     """Mirror of dymoe_expert_fmt."""
     _fields_ = [("w", C.c_void_p * 3), ("wt", C.c_void_p * 3), ("q4", C.c_void_p * 3), ("s4", C.c_void_p * 3),
                 ("z4", C.c_void_p * 3), ("q2", C.c_void_p * 3), ("s2", C.c_void_p * 3),
-                ("z2", C.c_void_p * 3)]
+                ("z2", C.c_void_p * 3), ("q8", C.c_void_p * 3), ("s8", C.c_void_p * 3),
+                ("z8", C.c_void_p * 3)]
 
 
 _vp, _i, _l, _sz, _d = C.c_void_p, C.c_int, C.c_long, C.c_size_t, C.c_double
@@ -338,7 +339,7 @@ class Context:
 
 def make_expert_table(experts, device):
     """Build the device-resident dymoe_expert_fmt[E] from per-expert dicts of
-    tensors: 'w' = [W1,W3,W2] bf16 and/or 'q4' / 'q2' = three (codes, scale,
+    tensors: 'w' = [W1,W3,W2] bf16 and/or 'q8' / 'q4' / 'q2' = three (codes, scale,
     zero) triples.  Returns (table tensor, keepalive list); the caller keeps
     both alive while the table is in use."""
     E = len(experts)
@@ -353,7 +354,7 @@ def make_expert_table(experts, device):
             for i in range(3):
                 arr[e].wt[i] = _ptr(ex["wt"][i], torch.bfloat16)
             keep.append(ex["wt"])
-        for b in (4, 2):
+        for b in (8, 4, 2):
             trip = ex.get("q%d" % b)
             if trip is None:
                 continue

@@ -1,7 +1,7 @@
 """Mixed-precision expert cache (paper Sec. 4.4.2): host-side bookkeeping only.
 
 The device memory set aside for experts is divided into slots of three sizes,
-one pool per stored format (16, 4 or 2 bits per weight); each pool is kept in
+one pool per stored format (16, 8, 4 or 2 bits per weight); each pool is kept in
 least-recently-used order.  The three rules of the paper:
 
   No Duplication        an expert is resident in at most one format;
@@ -17,7 +17,7 @@ the expert at.  No GPU call is made here.
 """
 import collections
 
-FORMATS = (16, 4, 2)
+FORMATS = (16, 8, 4, 2)
 
 
 class Action:
@@ -38,7 +38,7 @@ class Action:
 
 class MixedPrecisionCache:
     def __init__(self, slots):
-        """slots: {16: n16, 4: n4, 2: n2} slot counts per format."""
+        """slots: {16: n16, 8: n8, 4: n4, 2: n2} slot counts per format (missing: none)."""
         self.capacity = {b: int(slots.get(b, 0)) for b in FORMATS}
         # per format: slot index -> key (None when free), least recently used first
         self.pool = {b: collections.OrderedDict((i, None) for i in range(self.capacity[b])) for b in FORMATS}

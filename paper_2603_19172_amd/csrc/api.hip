@@ -55,15 +55,6 @@ int dymoe_create(dymoe_ctx** out, int device)
     c->device = device;
     c->num_cu = prop.multiProcessorCount;
     c->timing_mask = 0;
-    c->scratch = nullptr;
-    int prev = 0;
-    bool ok = hipGetDevice(&prev) == hipSuccess && hipSetDevice(device) == hipSuccess;
-    ok = ok && hipMalloc(&c->scratch, kDymoeScratchBytes) == hipSuccess;
-    (void)hipSetDevice(prev);
-    if (!ok) {
-        delete c;
-        return DYMOE_EHIP;
-    }
     *out = c;
     return DYMOE_OK;
 }
@@ -81,7 +72,6 @@ void dymoe_destroy(dymoe_ctx* ctx)
 {
     if (!ctx) return;
     drop_timed(ctx);
-    if (ctx->scratch) (void)hipFree(ctx->scratch);
     delete ctx;
 }
 
@@ -100,17 +90,25 @@ int dymoe_timing_read(dymoe_ctx* ctx, int kernel, double* total_ms, int* launche
     if (!ctx) return DYMOE_ENOCTX;
     double sum = 0.0;
     int n = 0;
+    std::vector<dymoe_timed_launch> rest;
+    int rc = DYMOE_OK;
     for (auto& t : ctx->timed) {
-        if (t.kernel != kernel) continue;
-        if (hipEventSynchronize(t.stop) != hipSuccess) return DYMOE_EHIP;
+        if (t.kernel != kernel) {
+            rest.push_back(t);
+            continue;
+        }
         float ms = 0.0f;
-        if (hipEventElapsedTime(&ms, t.start, t.stop) != hipSuccess) return DYMOE_EHIP;
+        if (hipEventSynchronize(t.stop) != hipSuccess || hipEventElapsedTime(&ms, t.start, t.stop) != hipSuccess)
+            rc = DYMOE_EHIP;
         sum += (double)ms;
         n++;
+        (void)hipEventDestroy(t.start);      // a record is read once
+        (void)hipEventDestroy(t.stop);
     }
+    ctx->timed.swap(rest);
     *total_ms = sum;
     *launches = n;
-    return DYMOE_OK;
+    return rc;
 }
 
 const char* dymoe_kernel_name(int kernel)

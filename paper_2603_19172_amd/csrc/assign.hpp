@@ -25,7 +25,7 @@ inline int make_tier_table(int E, int n_tiers, const int32_t* tier_count, const 
     for (int i = 0; i < n_tiers; i++) {
         const int b = tier_bits[i];
         if (tier_count[i] < 0) return DYMOE_EINVAL;
-        if (!(b == 0 || b == 2 || b == 4 || b == 16)) return DYMOE_EINVAL;
+        if (!(b == 0 || b == 2 || b == 4 || b == 8 || b == 16)) return DYMOE_EINVAL;
         tt.count[i] = tier_count[i];
         tt.bits[i] = (uint8_t)b;
         total += tier_count[i];

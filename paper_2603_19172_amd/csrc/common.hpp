@@ -36,7 +36,6 @@ struct dymoe_timed_launch {
 struct dymoe_ctx {
     int device;
     int num_cu;
-    void* scratch;                           // small device buffer owned by the context (worklists)
     unsigned timing_mask;                    // bit i set: time launches of kernel i
     std::vector<dymoe_timed_launch> timed;   // recorded, not yet read
 };
@@ -64,8 +63,6 @@ inline void dymoe_launch(dymoe_ctx* ctx, int kernel_id, void (*kernel)(KArgs...)
     }
     hipLaunchKernelGGL(kernel, grid, block, (uint32_t)smem, st, static_cast<KArgs>(args)...);
 }
-
-constexpr size_t kDymoeScratchBytes = 64 * 1024;
 
 #define DYMOE_REQUIRE(cond) \
     do {                    \

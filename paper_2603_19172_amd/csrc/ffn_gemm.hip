@@ -79,7 +79,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
         const int e = idx[p];
         if (e < 0 || e >= E) continue;
         const int b = s_bits[e];
-        if (b != 16 && b != 4 && b != 2) continue;
+        if (b != 16 && b != 8 && b != 4 && b != 2) continue;
         atomicAdd(&s_count[e], 1);
     }
     __syncthreads();
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
                 // cost key, roughly the time a workgroup spends on the tile: streaming (bf16)
                 // or dequantising (int4, int2) the weights costs the same whatever the number
                 // of tokens; the MFMA work grows with the 32-token fragments
-                draft[4 * nt + 3] = (b == 16 ? 100 : (b == 4 ? 61 : 60)) + 10 * ((rows + 31) >> 5);
+                draft[4 * nt + 3] = (b == 16 ? 100 : (b == 2 ? 60 : 61)) + 10 * ((rows + 31) >> 5);
                 nt++;
             }
             run += c;
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
         const int e = idx[p];
         if (e < 0 || e >= E) continue;
         const int b = s_bits[e];
-        if (b != 16 && b != 4 && b != 2) continue;
+        if (b != 16 && b != 8 && b != 4 && b != 2) continue;
         const int pos = s_off[e] + atomicAdd(&s_count[e], 1);
         pp.perm[pos] = p;
     }
@@ -167,11 +167,13 @@ __device__ __forceinline__ void perm16(const uint4 a, const uint4 b, uint4& o0, 
     o1.w = (a.w >> 16) | (b.w & 0xffff0000u);
 }
 
-// Two fp16 copies of the bf16 activations (exact inside fp16's normal range),
-// one in each of the column orders above.  A thread converts 16 columns.
+// Three fp16 copies of the bf16 activations (exact inside fp16's normal range):
+// one in each of the column orders above and one in the natural order (int8
+// codes come out of a dword in order).  A thread converts 16 columns.
 __global__ __launch_bounds__(256) void prep_x_kernel(const uint16_t* __restrict__ x, long n16,
                                                      uint16_t* __restrict__ xh4,
-                                                     uint16_t* __restrict__ xh2)
+                                                     uint16_t* __restrict__ xh2,
+                                                     uint16_t* __restrict__ xh8)
 {
     const long i = (long)blockIdx.x * 256 + threadIdx.x;
     if (i >= n16) return;
@@ -188,6 +190,8 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const uint16_t* __restrict_
     perm16(ha, hb, o0, o1);
     reinterpret_cast<uint4*>(xh2)[2 * i] = o0;
     reinterpret_cast<uint4*>(xh2)[2 * i + 1] = o1;
+    reinterpret_cast<uint4*>(xh8)[2 * i] = ha;
+    reinterpret_cast<uint4*>(xh8)[2 * i + 1] = hb;
 }
 
 // ----------------------------------------------------------------------------
@@ -195,6 +199,7 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const uint16_t* __restrict_
 
 template <int BITS> struct StripRaw;
 template <> struct StripRaw<16> { uint4 r[8]; };
+template <> struct StripRaw<8> { uint4 r[4]; uint32_t s2, m2; };
 template <> struct StripRaw<4> { uint4 r[2]; uint32_t s2, m2; };
 template <> struct StripRaw<2> { uint4 r[1]; uint32_t s2, m2; };
 
@@ -211,9 +216,9 @@ __device__ __forceinline__ MatPtr mat_ptr(const dymoe_expert_fmt& ex, int mat, i
     MatPtr m;
     m.w = reinterpret_cast<const uint16_t*>(ex.w[mat]);
     m.wt = reinterpret_cast<const char*>(ex.wt[mat]);
-    m.q = reinterpret_cast<const char*>((b == 4) ? ex.q4[mat] : ex.q2[mat]);
-    m.s = reinterpret_cast<const uint16_t*>((b == 4) ? ex.s4[mat] : ex.s2[mat]);
-    m.z = reinterpret_cast<const uint16_t*>((b == 4) ? ex.z4[mat] : ex.z2[mat]);
+    m.q = reinterpret_cast<const char*>((b == 8) ? ex.q8[mat] : (b == 4) ? ex.q4[mat] : ex.q2[mat]);
+    m.s = reinterpret_cast<const uint16_t*>((b == 8) ? ex.s8[mat] : (b == 4) ? ex.s4[mat] : ex.s2[mat]);
+    m.z = reinterpret_cast<const uint16_t*>((b == 8) ? ex.z8[mat] : (b == 4) ? ex.z4[mat] : ex.z2[mat]);
     return m;
 }
 
@@ -242,6 +247,17 @@ __device__ __forceinline__ void strip_frags(const StripRaw<BITS>& raw, int jj, u
     if constexpr (BITS == 16) {
         f0 = raw.r[2 * jj];
         f1 = raw.r[2 * jj + 1];
+    } else if constexpr (BITS == 8) {
+        // 16 codes, one per byte, in k order: a byte b becomes the fp16 number 1024 + b
+        const uint4 q = raw.r[jj];
+        f0.x = deq_pair(__builtin_amdgcn_perm(0x64646464u, q.x, 0x04010400u), 0x64006400u, raw.s2, raw.m2);
+        f0.y = deq_pair(__builtin_amdgcn_perm(0x64646464u, q.x, 0x04030402u), 0x64006400u, raw.s2, raw.m2);
+        f0.z = deq_pair(__builtin_amdgcn_perm(0x64646464u, q.y, 0x04010400u), 0x64006400u, raw.s2, raw.m2);
+        f0.w = deq_pair(__builtin_amdgcn_perm(0x64646464u, q.y, 0x04030402u), 0x64006400u, raw.s2, raw.m2);
+        f1.x = deq_pair(__builtin_amdgcn_perm(0x64646464u, q.z, 0x04010400u), 0x64006400u, raw.s2, raw.m2);
+        f1.y = deq_pair(__builtin_amdgcn_perm(0x64646464u, q.z, 0x04030402u), 0x64006400u, raw.s2, raw.m2);
+        f1.z = deq_pair(__builtin_amdgcn_perm(0x64646464u, q.w, 0x04010400u), 0x64006400u, raw.s2, raw.m2);
+        f1.w = deq_pair(__builtin_amdgcn_perm(0x64646464u, q.w, 0x04030402u), 0x64006400u, raw.s2, raw.m2);
     } else if constexpr (BITS == 4) {
         const uint4 q = raw.r[jj >> 1];
         const uint32_t w0 = (jj & 1) ? q.z : q.x;
@@ -311,19 +327,20 @@ __device__ __forceinline__ StripSrc strip_src(const MatPtr& m, long nt, int K, i
             src.c_stride = 16;
         }
     } else {
-        src.p = m.q + tile_row * (BITS == 4 ? 2048 : 1024) + lane * 16;
-        src.kt_stride = (BITS == 4) ? 2048 : 1024;
+        src.p = m.q + tile_row * (512 * BITS) + lane * 16;      // 32 x 128 codes of BITS bits: 512 * BITS bytes per tile
+        src.kt_stride = 512 * BITS;
         src.c_stride = 1024;
     }
     return src;
 }
 
 // chunk c of the lane's slice of K-tile kt: bf16 c = 0..7 (8 columns each),
-// int4 c = 0..1 (32 codes each), int2 c = 0 (64 codes)
+// int8 c = 0..3 (16 codes each), int4 c = 0..1 (32 codes each), int2 c = 0 (64 codes)
 template <int BITS>
 __device__ __forceinline__ uint4 load_chunk(const StripSrc& src, int kt, int c)
 {
     if constexpr (BITS == 16) return load_global<uint4>(src.p + (long)kt * src.kt_stride + c * src.c_stride);
+    else if constexpr (BITS == 8) return load_global<uint4>(src.p + (long)kt * 4096 + c * 1024);
     else if constexpr (BITS == 4) return load_global<uint4>(src.p + (long)kt * 2048 + c * 1024);
     else return load_global<uint4>(src.p + (long)kt * 1024);
 }
@@ -354,7 +371,7 @@ __device__ __forceinline__ void adopt_strip(StripRaw<BITS>& cur, const StripRaw<
 template <int BITS>
 __device__ __forceinline__ void load_strip(const StripSrc& src, int kt, StripRaw<BITS>& raw)
 {
-    constexpr int kChunks = (BITS == 16) ? 8 : (BITS == 4 ? 2 : 1);
+    constexpr int kChunks = (BITS == 16) ? 8 : (BITS == 8 ? 4 : (BITS == 4 ? 2 : 1));
 #pragma unroll
     for (int c = 0; c < kChunks; c++) raw.r[c] = load_chunk<BITS>(src, kt, c);
     load_scale_zero<BITS>(src, kt, raw);
@@ -382,6 +399,8 @@ struct XOps {
 // the last MFMA that reads it has been issued, so the next tile's weights are
 // in flight during three quarters of this tile's arithmetic without a second
 // set of registers.
+// int8 (16 registers of codes per strip): refilled in place like bf16; only the
+// scale and zero of the next tile wait in registers of their own.
 // int4 / int2 (10 / 6 registers per strip): the next tile's codes were already
 // requested into a second register set before this call; nothing to load here.
 template <int BITS, int NTF, int JJ0, int JJ1>
@@ -422,6 +441,10 @@ __device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>
             rb.r[2 * jj] = load_chunk<16>(sb, kt_next, 2 * jj);
             rb.r[2 * jj + 1] = load_chunk<16>(sb, kt_next, 2 * jj + 1);
             __builtin_amdgcn_sched_barrier(kStepMask);
+        } else if constexpr (BITS == 8) {
+            ra.r[jj] = load_chunk<8>(sa, kt_next, jj);
+            rb.r[jj] = load_chunk<8>(sb, kt_next, jj);
+            __builtin_amdgcn_sched_barrier(kStepMask);
         }
     }
 }
@@ -432,7 +455,7 @@ __device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>
 template <int BITS>
 constexpr int ktile_loads()
 {
-    return BITS == 16 ? 16 : (BITS == 4 ? 8 : 6);
+    return BITS == 16 ? 16 : (BITS == 8 ? 12 : (BITS == 4 ? 8 : 6));
 }
 
 // ----------------------------------------------------------------------------
@@ -573,7 +596,7 @@ __device__ __forceinline__ void gemm_tile(
         const int kn = min(kt + 1, kt_end - 1);
         copy_tile<NTF>(stage, kn, buf ^ 1);
         StripRaw<BITS> na, nb;
-        if constexpr (BITS != 16) {
+        if constexpr (BITS != 16 && BITS != 8) {
             load_strip<BITS>(sa, kn, na);
             load_strip<BITS>(sb, kn, nb);
             __builtin_amdgcn_sched_barrier(0);   // keep the requests up here, a whole tile ahead of their use
@@ -581,8 +604,24 @@ __device__ __forceinline__ void gemm_tile(
         XOps ops;             // operands of the first step
         ops.t0 = lds_read16(xa);
         ops.t1 = lds_read16(xa ^ 16u);
-        compute_ktile<BITS, NTF, 0, 4>(ra, rb, sa, sb, kn, xa, ops, acc);
-        if constexpr (BITS != 16) {
+        if constexpr (BITS == 8) {
+            // the next tile's scale and zero are requested after the first quarter's
+            // refills: a wait for a refilled register then never reaches back to
+            // the copies issued at the top of the tile before a quarter has passed
+            compute_ktile<BITS, NTF, 0, 1>(ra, rb, sa, sb, kn, xa, ops, acc);
+            load_scale_zero<BITS>(sa, kn, na);
+            load_scale_zero<BITS>(sb, kn, nb);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_ktile<BITS, NTF, 1, 4>(ra, rb, sa, sb, kn, xa, ops, acc);
+            ra.s2 = na.s2 | (na.s2 << 16);
+            ra.m2 = na.m2 | (na.m2 << 16);
+            rb.s2 = nb.s2 | (nb.s2 << 16);
+            rb.m2 = nb.m2 | (nb.m2 << 16);
+            __builtin_amdgcn_sched_barrier(0);
+        } else {
+            compute_ktile<BITS, NTF, 0, 4>(ra, rb, sa, sb, kn, xa, ops, acc);
+        }
+        if constexpr (BITS != 16 && BITS != 8) {
             adopt_strip<BITS>(ra, na);
             adopt_strip<BITS>(rb, nb);
             // finish the hand-over here, not after the next tile's requests
@@ -623,7 +662,7 @@ __device__ __forceinline__ void gemm_tile(
                     pk[g][1] = pack_half2(hv[2], hv[3]);
                 }
             }
-            if constexpr (BITS == 16) {
+            if constexpr (BITS == 16 || BITS == 8) {
                 // features f0 + 8g + 4kb .. +4, natural order
                 if (row_ok && strip_ok[0]) {
 #pragma unroll
@@ -685,7 +724,8 @@ __device__ __forceinline__ void gemm_tile(
 template <int MODE>
 __global__ __launch_bounds__(kGmThreads, 2) void gemm_kernel(
     const uint16_t* __restrict__ x_bf16, const uint16_t* __restrict__ x_h4,
-    const uint16_t* __restrict__ x_h2, const uint16_t* __restrict__ hbuf_in,
+    const uint16_t* __restrict__ x_h2, const uint16_t* __restrict__ x_h8,
+    const uint16_t* __restrict__ hbuf_in,
     const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table,
     const int32_t* __restrict__ plan, int P, int E, int k_route, int H, int F,
     uint16_t* __restrict__ hbuf_out, float* __restrict__ opair)
@@ -721,7 +761,7 @@ __global__ __launch_bounds__(kGmThreads, 2) void gemm_kernel(
         }
         return;
     }
-    const uint16_t* act = (MODE != 1) ? hbuf_in : (b == 16 ? x_bf16 : (b == 4 ? x_h4 : x_h2));
+    const uint16_t* act = (MODE != 1) ? hbuf_in : (b == 16 ? x_bf16 : (b == 8 ? x_h8 : (b == 4 ? x_h4 : x_h2)));
     const int ntf = (rows + 31) >> 5;
     // one instantiation per (precision, number of 32-token fragments): the
     // accumulators then sit in fixed registers for the whole K loop
@@ -737,6 +777,8 @@ __global__ __launch_bounds__(kGmThreads, 2) void gemm_kernel(
     }
     if (b == 16) {
         DYMOE_TILE_NTF(16)
+    } else if (b == 8) {
+        DYMOE_TILE_NTF(8)
     } else if (b == 4) {
         DYMOE_TILE_NTF(4)
     } else {
@@ -763,7 +805,7 @@ __global__ __launch_bounds__(256) void gemm_combine_kernel(
         const int e = idx[p];
         if (e < 0 || e >= E) continue;
         const int b = bits[e];
-        if (b != 16 && b != 4 && b != 2) continue;
+        if (b != 16 && b != 8 && b != 4 && b != 2) continue;
         const float g = w[p];
         float4 o = *reinterpret_cast<const float4*>(opair + (long)p * H + j);
         for (int z = 1; z < splits; z++) {
@@ -797,6 +839,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     uint16_t* hbuf = reinterpret_cast<uint16_t*>(ws + L.hbuf);   // [P,F] 16-bit
     uint16_t* xh4 = reinterpret_cast<uint16_t*>(ws + L.xh);      // [T,H] fp16, int4 column order
     uint16_t* xh2 = xh4 + round256((size_t)T * H * 2) / 2;       // [T,H] fp16, int2 column order
+    uint16_t* xh8 = xh2 + round256((size_t)T * H * 2) / 2;       // [T,H] fp16, natural column order (int8)
     float* opair = reinterpret_cast<float*>(ws + L.part);
     int32_t* plan = reinterpret_cast<int32_t*>(ws + L.plan);
     const uint16_t* xb = (const uint16_t*)x;
@@ -804,7 +847,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     dymoe_launch(ctx, DYMOE_K_PLAN, plan_kernel, dim3(1), dim3(1024), 0, st, idx, bits, P, E, kGemmTileM, L.max_tiles, plan);
     DYMOE_HIP_LAUNCH_CHECK();
     const long n16 = (long)T * H / 16;
-    hipLaunchKernelGGL(prep_x_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, xb, n16, xh4, xh2);
+    hipLaunchKernelGGL(prep_x_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, xb, n16, xh4, xh2, xh8);
     DYMOE_HIP_LAUNCH_CHECK();
     // two token-tile buffers in LDS
     constexpr size_t kLdsBytes = 2 * (size_t)kXsBufBytes;
@@ -820,7 +863,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const int max_tiles = P / kGemmTileM + E;
     const int cols1 = 32 * kGmWaves, cols2 = 64 * kGmWaves;
     const dim3 g1((unsigned)((F + cols1 - 1) / cols1), (unsigned)max_tiles);
-    dymoe_launch(ctx, DYMOE_K_GEMM1, (gemm_kernel<1>), g1, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2,
+    dymoe_launch(ctx, DYMOE_K_GEMM1, (gemm_kernel<1>), g1, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2, xh8,
                  (const uint16_t*)nullptr, bits, table, plan, P, E, k, H, F, hbuf, (float*)nullptr);
     DYMOE_HIP_LAUNCH_CHECK();
     // The down projection has few output tiles: split K so that the launch
@@ -834,7 +877,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     if (splits > 8) splits = 8;
     if (splits < 1) splits = 1;
     const dim3 g2((unsigned)nblk2, (unsigned)max_tiles, (unsigned)splits);
-    dymoe_launch(ctx, DYMOE_K_GEMM2, (gemm_kernel<2>), g2, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2, hbuf,
+    dymoe_launch(ctx, DYMOE_K_GEMM2, (gemm_kernel<2>), g2, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2, xh8, hbuf,
                  bits, table, plan, P, E, k, H, F, (uint16_t*)nullptr, opair);
     DYMOE_HIP_LAUNCH_CHECK();
     const long n4 = (long)T * (H / 4);

@@ -8,6 +8,7 @@
 // memory traffic of the loop.
 //   bf16 rows : 4 x 16-byte loads per lane and segment, bf16 dot2 (phase 1)
 //               or fp32 FMA (phase 2, fp32 intermediate)
+//   int8 rows : two 16-byte loads per lane and segment (32 codes = half a group)
 //   int4 rows : one 16-byte load per lane and segment (32 codes = half a group)
 //   int2 rows : one  8-byte load per lane and segment (32 codes = half a group)
 // The row loop is software pipelined: the loads of the next batch of rows are
@@ -77,7 +78,15 @@ __device__ __forceinline__ void arrange_lane_x(const float* v, LaneX& lx)
     }
     lx.xsum = sum;
     float off = 0.0f;
-    if (BITS == 4) {
+    if (BITS == 8) {
+        // dword d holds codes 4d..4d+3, one per byte; pairs (b0,b1) and (b2,b3), all offset by 1024
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            half2_t pr = {hv[2 * i], hv[2 * i + 1]};
+            lx.r[i] = __builtin_bit_cast(uint32_t, pr);
+        }
+        off = 1024.0f * sum;
+    } else if (BITS == 4) {
         // dword d holds codes 8d..8d+7 in nibbles 0..7
         // pairs: (n0,n4)+1024, (n1,n5)+64, (n2,n6)+1024, (n3,n7)+64
 #pragma unroll
@@ -145,6 +154,19 @@ __device__ __forceinline__ float dot_q2(const uint2 c, const LaneX& lx)
     return acc;
 }
 
+// the same over the lane's 32 int8 codes (two uint4): a byte b becomes the fp16 number 1024 + b
+__device__ __forceinline__ float dot_q8(const uint4 c0, const uint4 c1, const LaneX& lx)
+{
+    const uint32_t w[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+    float acc = 0.0f;
+#pragma unroll
+    for (int d = 0; d < 8; d++) {
+        acc = dot2_f16(__builtin_amdgcn_perm(0x64646464u, w[d], 0x04010400u), lx.r[2 * d], acc);
+        acc = dot2_f16(__builtin_amdgcn_perm(0x64646464u, w[d], 0x04030402u), lx.r[2 * d + 1], acc);
+    }
+    return acc;
+}
+
 // activations of one lane for bf16 rows: NSEG x 4 chunks of 8, packed bf16 pairs
 template <int NSEG>
 struct LaneXB {
@@ -164,7 +186,11 @@ __device__ __forceinline__ ExpertMat pick_mat(const dymoe_expert_fmt& ex, int ma
 {
     ExpertMat m;
     m.w = reinterpret_cast<const uint16_t*>(ex.w[mat]);
-    if (b == 4) {
+    if (b == 8) {
+        m.q = ex.q8[mat];
+        m.s = reinterpret_cast<const uint16_t*>(ex.s8[mat]);
+        m.z = reinterpret_cast<const uint16_t*>(ex.z8[mat]);
+    } else if (b == 4) {
         m.q = ex.q4[mat];
         m.s = reinterpret_cast<const uint16_t*>(ex.s4[mat]);
         m.z = reinterpret_cast<const uint16_t*>(ex.z4[mat]);
@@ -181,6 +207,7 @@ template <int BITS, int NSEG> struct RowRegs;
 template <int NSEG> struct RowRegs<16, NSEG> { uint4 c[NSEG][4]; };
 template <int NSEG> struct RowRegs<4, NSEG> { uint4 c[NSEG]; uint16_t s[NSEG], z[NSEG]; };
 template <int NSEG> struct RowRegs<2, NSEG> { uint2 c[NSEG]; uint16_t s[NSEG], z[NSEG]; };
+template <int NSEG> struct RowRegs<8, NSEG> { uint4 c[NSEG][2]; uint16_t s[NSEG], z[NSEG]; };
 
 // Issue the loads of row `row` (K columns).  Lanes past the end of the row
 // re-read its tail: finite weights against zero activations add nothing.
@@ -203,7 +230,10 @@ __device__ __forceinline__ void load_row(const ExpertMat& m, long row, int K, in
 #pragma unroll
         for (int s = 0; s < NSEG; s++) {
             const int col0 = min((seg0 + s) * kSeg + 32 * lane, K - 32);
-            if constexpr (BITS == 4) rr.c[s] = load_global<uint4>(codes + (col0 >> 1));
+            if constexpr (BITS == 8) {
+                rr.c[s][0] = load_global<uint4>(codes + col0);
+                rr.c[s][1] = load_global<uint4>(codes + col0 + 16);
+            } else if constexpr (BITS == 4) rr.c[s] = load_global<uint4>(codes + (col0 >> 1));
             else rr.c[s] = load_global<uint2>(codes + (col0 >> 2));
             rr.s[s] = load_global<uint16_t>(m.s + row * G + (col0 >> 6));
             rr.z[s] = load_global<uint16_t>(m.z + row * G + (col0 >> 6));
@@ -219,7 +249,8 @@ __device__ __forceinline__ float dot_row_q(const RowRegs<BITS, NSEG>& rr, const 
 #pragma unroll
     for (int s = 0; s < NSEG; s++) {
         float acc;
-        if constexpr (BITS == 4) acc = dot_q4(rr.c[s], lx[s]);
+        if constexpr (BITS == 8) acc = dot_q8(rr.c[s][0], rr.c[s][1], lx[s]);
+        else if constexpr (BITS == 4) acc = dot_q4(rr.c[s], lx[s]);
         else acc = dot_q2(rr.c[s], lx[s]);
         const float sc = h2f(f16_from_bits(rr.s[s]));
         const float zr = h2f(f16_from_bits(rr.z[s]));
@@ -249,7 +280,7 @@ __device__ __forceinline__ float dot_row_b(const RowRegs<16, NSEG>& rr, const La
 // h[p,f] = silu(W1[f,:] . x_t) * (W3[f,:] . x_t)
 // A wavefront takes RF consecutive f per iteration (2*RF rows in flight).
 
-template <int BITS> struct Phase1Rows { static constexpr int RF = (BITS == 16) ? 1 : (BITS == 4 ? 2 : 4); };
+template <int BITS> struct Phase1Rows { static constexpr int RF = (BITS == 16) ? 1 : (BITS == 2 ? 4 : 2); };
 
 template <int BITS, int NSEG, typename XT, typename DotFn>
 __device__ __forceinline__ void phase1_rows(const ExpertMat& m1, const ExpertMat& m3, int H,
@@ -358,7 +389,7 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
     const int e = idx[p];
     if (e < 0 || e >= E) return;
     const int b = bits[e];
-    if (b != 16 && b != 4 && b != 2) return;
+    if (b != 16 && b != 8 && b != 4 && b != 2) return;
     const int t = p / k;
     const int f_begin = blockIdx.x * rows_per_block;
     const int f_end = min(F, f_begin + rows_per_block);
@@ -367,6 +398,8 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
     const dymoe_expert_fmt ex = table[e];
     if (b == 16) {
         phase1_bf16<NSEG>(pick_mat(ex, 0, 16), pick_mat(ex, 1, 16), xrow, H, f_begin, f_end, hrow);
+    } else if (b == 8) {
+        phase1_quant<8, NSEG>(pick_mat(ex, 0, 8), pick_mat(ex, 1, 8), xrow, H, f_begin, f_end, hrow);
     } else if (b == 4) {
         phase1_quant<4, NSEG>(pick_mat(ex, 0, 4), pick_mat(ex, 1, 4), xrow, H, f_begin, f_end, hrow);
     } else {
@@ -378,7 +411,7 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
 // part[p,s,j] = sum over segment s of W2[j,f] * h[p,f]
 // A wavefront takes R consecutive rows j per iteration.
 
-template <int BITS> struct Phase2Rows { static constexpr int R = (BITS == 16) ? 4 : 8; };
+template <int BITS> struct Phase2Rows { static constexpr int R = (BITS == 16 || BITS == 8) ? 4 : 8; };
 
 // fp32 intermediate against bf16 weights
 struct LaneH {
@@ -441,7 +474,7 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase2_kernel(
     const int e = idx[p];
     if (e < 0 || e >= E) return;
     const int b = bits[e];
-    if (b != 16 && b != 4 && b != 2) return;
+    if (b != 16 && b != 8 && b != 4 && b != 2) return;
     const int lane = threadIdx.x & (kWave - 1);
     const int j_begin = blockIdx.x * rows_per_block;
     const int j_end = min(H, j_begin + rows_per_block);
@@ -474,7 +507,11 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase2_kernel(
             v[4 * c + 0] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
         }
         LaneX lx[1];
-        if (b == 4) {
+        if (b == 8) {
+            arrange_lane_x<8>(v, lx[0]);
+            phase2_rows<8>(pick_mat(ex, 2, 8), F, s, j_begin, j_end, out, lx,
+                           [](const RowRegs<8, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<8, 1>(rr, l); });
+        } else if (b == 4) {
             arrange_lane_x<4>(v, lx[0]);
             phase2_rows<4>(pick_mat(ex, 2, 4), F, s, j_begin, j_end, out, lx,
                            [](const RowRegs<4, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<4, 1>(rr, l); });
@@ -502,7 +539,7 @@ __global__ __launch_bounds__(256) void gemv_combine_kernel(
         const int e = idx[p];
         if (e < 0 || e >= E) continue;
         const int b = bits[e];
-        if (b != 16 && b != 4 && b != 2) continue;
+        if (b != 16 && b != 8 && b != 4 && b != 2) continue;
         float o = 0.0f;
         for (int s = 0; s < nseg; s++) o += part[((long)p * nseg + s) * H + j];
         acc = fmaf(w[p], o, acc);

@@ -13,7 +13,7 @@ constexpr int kPlanTileMin = 32;  // sizing granularity of the tile list
 struct FfnLayout {
     size_t hbuf;    // [P,F] SwiGLU intermediate: fp32 (GEMV) or 16-bit (GEMM)
     size_t part;    // GEMV: [P,nseg,H] fp32 partial sums; GEMM: [P,H] fp32 per-pair outputs
-    size_t xh;      // GEMM: two [T,H] fp16 copies of the activations (int4 / int2 column order)
+    size_t xh;      // GEMM: three [T,H] fp16 copies of the activations (int4 / int2 / natural column order)
     size_t plan;    // int32: counts[E], offsets[E+1], cursor[E], ntiles, perm[P], tiles[4*maxtiles], draft[4*maxtiles]
     size_t total;
     int max_tiles;
@@ -30,7 +30,7 @@ static inline FfnLayout ffn_layout(int T, int H, int F, int E, int k)
     L.hbuf = 0;
     L.part = L.hbuf + round256(P * (size_t)F * 4);
     L.xh = L.part + round256(P * nseg * (size_t)H * 4);
-    L.plan = L.xh + 2 * round256((size_t)T * (size_t)H * 2);
+    L.plan = L.xh + 3 * round256((size_t)T * (size_t)H * 2);
     size_t plan_ints = (size_t)E + ((size_t)E + 1) + (size_t)E + 8 + P + 8 * (size_t)L.max_tiles;
     L.total = L.plan + round256(plan_ints * 4);
     return L;

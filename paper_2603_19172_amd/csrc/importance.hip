@@ -221,7 +221,7 @@ int dymoe_assign_precision(dymoe_ctx* ctx, int phase, const void* importance,
     DYMOE_REQUIRE(importance && tier_count && tier_bits && bits);
     DYMOE_REQUIRE(phase == DYMOE_PHASE_PREFILL || phase == DYMOE_PHASE_DECODE);
     DYMOE_REQUIRE(E > 0 && n_tiers >= 1 && n_tiers <= DYMOE_MAX_TIERS);
-    DYMOE_REQUIRE(floor_bits == 0 || floor_bits == 2 || floor_bits == 4 || floor_bits == 16);
+    DYMOE_REQUIRE(floor_bits == 0 || floor_bits == 2 || floor_bits == 4 || floor_bits == 8 || floor_bits == 16);
     dymoe::TierTable tt;
     DYMOE_REQUIRE(dymoe::make_tier_table(E, n_tiers, tier_count, tier_bits, tt) == DYMOE_OK);
     if (E > DYMOE_MAX_EXPERTS) return DYMOE_ENOTSUP;

@@ -64,7 +64,7 @@ __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, l
     const float m = (float)zh;
     const float s = (float)sh;
     const float inv = (s > 0.0f) ? (1.0f / s) : 0.0f;
-    uint32_t words[BITS];                             // 32 codes: 4 words (int4) or 2 words (int2)
+    uint32_t words[BITS];                             // 32 codes: 8 words (int8), 4 (int4) or 2 (int2)
 #pragma unroll
     for (int wd = 0; wd < BITS; wd++) {
         constexpr int per_word = 32 / BITS;
@@ -91,7 +91,10 @@ __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, l
         const uint32_t hi16 = __builtin_amdgcn_perm(bytes[3], bytes[2], 0x04000c0cu);
         words[wd] = lo16 | hi16;
     }
-    if constexpr (BITS == 4) {
+    if constexpr (BITS == 8) {
+        store_global(codes + e0, make_uint4(words[0], words[1], words[2], words[3]));
+        store_global(codes + e0 + 16, make_uint4(words[4], words[5], words[6], words[7]));
+    } else if constexpr (BITS == 4) {
         store_global(codes + (e0 >> 1), make_uint4(words[0], words[1], words[2], words[3]));
     } else {
         store_global(codes + (e0 >> 2), make_uint2(words[0], words[1]));
@@ -106,7 +109,8 @@ __global__ __launch_bounds__(kQThreads) void quantize_pack_kernel(
     const uint16_t* __restrict__ w, long n_elems, int bits,
     uint8_t* __restrict__ codes, uint16_t* __restrict__ scale, uint16_t* __restrict__ zero)
 {
-    if (bits == 4) quantize_block<4>(w, n_elems, codes, scale, zero, blockIdx.x);
+    if (bits == 8) quantize_block<8>(w, n_elems, codes, scale, zero, blockIdx.x);
+    else if (bits == 4) quantize_block<4>(w, n_elems, codes, scale, zero, blockIdx.x);
     else quantize_block<2>(w, n_elems, codes, scale, zero, blockIdx.x);
 }
 
@@ -149,7 +153,7 @@ __device__ __forceinline__ void quantize_tile(const uint16_t* __restrict__ w, lo
     const float m = (float)zh;
     const float s = (float)sh;
     const float inv = (s > 0.0f) ? (1.0f / s) : 0.0f;
-    constexpr int kWords = 2 * BITS;                  // 64 codes: 8 words (int4) or 4 words (int2)
+    constexpr int kWords = 2 * BITS;                  // 64 codes: 16 words (int8), 8 (int4) or 4 (int2)
     uint32_t words[kWords];
 #pragma unroll
     for (int wd = 0; wd < kWords; wd++) {
@@ -175,7 +179,12 @@ __device__ __forceinline__ void quantize_tile(const uint16_t* __restrict__ w, lo
         const uint32_t hi16 = __builtin_amdgcn_perm(bytes[3], bytes[2], 0x04000c0cu);
         words[wd] = lo16 | hi16;
     }
-    if constexpr (BITS == 4) {
+    if constexpr (BITS == 8) {
+        uint8_t* dst = codes + tile * 4096 + lane * 16;
+#pragma unroll
+        for (int c = 0; c < 4; c++)
+            store_global(dst + c * 1024, make_uint4(words[4 * c], words[4 * c + 1], words[4 * c + 2], words[4 * c + 3]));
+    } else if constexpr (BITS == 4) {
         uint8_t* dst = codes + tile * 2048 + lane * 16;
         store_global(dst, make_uint4(words[0], words[1], words[2], words[3]));
         store_global(dst + 1024, make_uint4(words[4], words[5], words[6], words[7]));
@@ -203,7 +212,7 @@ __global__ __launch_bounds__(256) void pack_tiles_kernel(const uint16_t* __restr
     reinterpret_cast<uint4*>(tiles)[i] = *reinterpret_cast<const uint4*>(w + row * K + col);
 }
 
-// Worklist of a layer: the experts whose assigned width is 4 or 2 bits (and
+// Worklist of a layer: the experts whose assigned width is 8, 4 or 2 bits (and
 // that have load, when load is given), in ascending order.  Every workgroup
 // builds its own copy in LDS with its first wavefront (ballot + prefix count),
 // so no separate launch and no global buffer is needed.  Returns the count.
@@ -219,7 +228,7 @@ __device__ __forceinline__ int build_worklist(const uint8_t* __restrict__ bits,
             bool need = false;
             if (e < E) {
                 const int b = bits[e];
-                need = (b == 4 || b == 2) && (load == nullptr || load[e] > 0);
+                need = (b == 8 || b == 4 || b == 2) && (load == nullptr || load[e] > 0);
             }
             const unsigned long long mask = __ballot(need);
             if (need) list[n + __popcll(mask & ((1ull << lane) - 1ull))] = (int16_t)e;
@@ -255,18 +264,20 @@ __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
         const int b = bits[e];
         const dymoe_expert_fmt* ex = table + e;
         const uint16_t* w = reinterpret_cast<const uint16_t*>(ex->w[mat]);
-        uint8_t* q = (b == 4) ? ex->q4[mat] : ex->q2[mat];
-        uint16_t* sc = reinterpret_cast<uint16_t*>((b == 4) ? ex->s4[mat] : ex->s2[mat]);
-        uint16_t* zr = reinterpret_cast<uint16_t*>((b == 4) ? ex->z4[mat] : ex->z2[mat]);
+        uint8_t* q = (b == 8) ? ex->q8[mat] : (b == 4) ? ex->q4[mat] : ex->q2[mat];
+        uint16_t* sc = reinterpret_cast<uint16_t*>((b == 8) ? ex->s8[mat] : (b == 4) ? ex->s4[mat] : ex->s2[mat]);
+        uint16_t* zr = reinterpret_cast<uint16_t*>((b == 8) ? ex->z8[mat] : (b == 4) ? ex->z4[mat] : ex->z2[mat]);
         if constexpr (LAYOUT == DYMOE_LAYOUT_TILE) {
             const long K = (mat == 2) ? F : H;
             const long tile = blk * 4 + (threadIdx.x >> 6);
             if (tile * 4096 < n_elems) {
-                if (b == 4) quantize_tile<4>(w, K, tile, q, sc, zr);
+                if (b == 8) quantize_tile<8>(w, K, tile, q, sc, zr);
+                else if (b == 4) quantize_tile<4>(w, K, tile, q, sc, zr);
                 else quantize_tile<2>(w, K, tile, q, sc, zr);
             }
         } else {
-            if (b == 4) quantize_block<4>(w, n_elems, q, sc, zr, blk);
+            if (b == 8) quantize_block<8>(w, n_elems, q, sc, zr, blk);
+            else if (b == 4) quantize_block<4>(w, n_elems, q, sc, zr, blk);
             else quantize_block<2>(w, n_elems, q, sc, zr, blk);
         }
     }
@@ -280,7 +291,7 @@ int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits,
                         uint8_t* codes, void* scale, void* zero, void* stream)
 {
     DYMOE_REQUIRE(N >= 0 && K > 0);
-    DYMOE_REQUIRE(bits == 2 || bits == 4);
+    DYMOE_REQUIRE(bits == 2 || bits == 4 || bits == 8);
     DYMOE_REQUIRE(group > 0 && K % group == 0);
     if (N == 0) return (group != 64) ? DYMOE_ENOTSUP : (ctx ? DYMOE_OK : DYMOE_ENOCTX);  // nothing to read or write
     DYMOE_REQUIRE(w && codes && scale && zero);

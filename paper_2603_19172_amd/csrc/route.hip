@@ -254,7 +254,7 @@ int dymoe_decode_front(dymoe_ctx* ctx, const void* x, const void* wg, const floa
     DYMOE_REQUIRE(H % 8 == 0);
     DYMOE_REQUIRE(x && wg && idx && w && importance && load && bits);
     DYMOE_REQUIRE(dymoe_aligned(x, 16) && dymoe_aligned(wg, 16));
-    DYMOE_REQUIRE(floor_bits == 0 || floor_bits == 2 || floor_bits == 4 || floor_bits == 16);
+    DYMOE_REQUIRE(floor_bits == 0 || floor_bits == 2 || floor_bits == 4 || floor_bits == 8 || floor_bits == 16);
     dymoe::TierTable tt;
     DYMOE_REQUIRE(dymoe::make_tier_table(E, n_tiers, tier_count, tier_bits, tt) == DYMOE_OK);
     if (E > DYMOE_MAX_EXPERTS || H > 16384) return DYMOE_ENOTSUP;

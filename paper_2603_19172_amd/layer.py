@@ -13,10 +13,10 @@ from . import binding as B
 
 class ExpertStore:
     """Device-resident weights of a layer's experts: the bf16 originals plus
-    output buffers for the int4 and int2 formats, and the dymoe_expert_fmt table
-    that points at them."""
+    output buffers for the quantised formats (int4 and int2; int8 when asked
+    for), and the dymoe_expert_fmt table that points at them."""
 
-    def __init__(self, w_bf16, H, F, device, group=64, ctx=None, w_tiles=None):
+    def __init__(self, w_bf16, H, F, device, group=64, ctx=None, w_tiles=None, formats=(4, 2)):
         # w_bf16: list over experts of [W1 [F,H], W3 [F,H], W2 [H,F]] bf16 tensors on `device`.
         # With a context, a tile-layout copy of the bf16 weights is made for the GEMM path.
         self.E = len(w_bf16)
@@ -25,20 +25,21 @@ class ExpertStore:
         self.wt = w_tiles
         if self.wt is None and ctx is not None and H % 128 == 0 and F % 128 == 0:
             self.wt = [[ctx.pack_tiles(m) for m in ex] for ex in w_bf16]
+        self.formats = tuple(formats)
         self.q = {}
-        for b in (4, 2):
+        for b in self.formats:
             self.q[b] = [[(torch.empty((n, k * b // 8), dtype=torch.uint8, device=device),
                            torch.empty((n, k // group), dtype=torch.float16, device=device),
                            torch.empty((n, k // group), dtype=torch.float16, device=device))
                           for n, k in ((F, H), (F, H), (H, F))] for _ in range(self.E)]
-        experts = [{"w": self.w[e], "wt": self.wt[e] if self.wt is not None else None,
-                    "q4": self.q[4][e], "q2": self.q[2][e]} for e in range(self.E)]
+        experts = [dict({"w": self.w[e], "wt": self.wt[e] if self.wt is not None else None},
+                        **{"q%d" % b: self.q[b][e] for b in self.formats}) for e in range(self.E)]
         self.table, self._keep = B.make_expert_table(experts, device)
 
     def clone(self):
         wt = [[m.clone() for m in ex] for ex in self.wt] if self.wt is not None else None
         return ExpertStore([[m.clone() for m in ex] for ex in self.w], self.H, self.F,
-                           self.table.device, w_tiles=wt)
+                           self.table.device, w_tiles=wt, formats=self.formats)
 
 
 class MoELayer:

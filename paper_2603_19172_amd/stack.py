@@ -10,7 +10,7 @@ experts to prefetch (Eq. 8), which are copied on a side stream
 Two ways of moving an expert:
   transfer="bf16"      the bf16 weights travel and are quantised on the device
                        to the width the precision assignment asks for;
-  transfer="assigned"  the host also holds the int4 and int2 formats (made once
+  transfer="assigned"  the host also holds the quantised formats (made once
                        by the device quantiser) and the format the assignment
                        asks for travels: fewer bytes on the host link, and the
                        mixed-precision cache of Sec. 4.4.2 decides what stays.
@@ -24,7 +24,7 @@ import ctypes as C
 import torch
 
 from . import binding as B
-from .cache import MixedPrecisionCache
+from .cache import FORMATS, MixedPrecisionCache
 from .layer import MoELayer
 
 FMT_BYTES = C.sizeof(B.ExpertFmt)
@@ -60,11 +60,12 @@ class HostExpertPool:
             view[i, H * F:2 * H * F] = w3.reshape(-1).view("int16")
             view[i, 2 * H * F:] = w2.reshape(-1).view("int16")
 
-    def add_quantised(self, ctx, device):
-        """int4 and int2 copies of every entry, made by the device quantiser and kept in pinned host memory."""
+    def add_quantised(self, ctx, device, formats=(4, 2)):
+        """Quantised copies (by default int4 and int2) of every entry, made by the device quantiser and
+        kept in pinned host memory."""
         H, F = self.H, self.F
         wdev = torch.empty((self.elems,), dtype=torch.bfloat16, device=device)
-        for b in (4, 2):
+        for b in formats:
             offs, total = quant_layout(H, F, b)
             self.nbytes[b] = total
             self.buf[b] = torch.empty((self.n_pool, total), dtype=torch.uint8, pin_memory=True)
@@ -89,10 +90,10 @@ class HostExpertPool:
 
 class _Slot:
     """Device buffers of one resident expert in one transferred format.  A bf16
-    slot of the "bf16" transfer mode also carries the buffers the device
-    quantiser writes."""
+    slot also carries a buffer for each of `quant_formats`, which the device
+    quantiser writes ("bf16" transfer mode)."""
 
-    def __init__(self, H, F, fmt_bits, device, with_quant_buffers):
+    def __init__(self, H, F, fmt_bits, device, quant_formats):
         fmt = B.ExpertFmt()
         self.fmt_bits = fmt_bits
         if fmt_bits == 16:
@@ -100,11 +101,10 @@ class _Slot:
             for i in range(3):
                 fmt.w[i] = self.buf.data_ptr() + i * H * F * 2
             self.qbuf = {}
-            if with_quant_buffers:
-                for b in (4, 2):
-                    offs, total = quant_layout(H, F, b)
-                    self.qbuf[b] = torch.empty((total,), dtype=torch.uint8, device=device)
-                    self._point(fmt, b, self.qbuf[b].data_ptr(), offs)
+            for b in quant_formats:
+                offs, total = quant_layout(H, F, b)
+                self.qbuf[b] = torch.empty((total,), dtype=torch.uint8, device=device)
+                self._point(fmt, b, self.qbuf[b].data_ptr(), offs)
         else:
             offs, total = quant_layout(H, F, fmt_bits)
             self.buf = torch.empty((total,), dtype=torch.uint8, device=device)
@@ -127,7 +127,7 @@ class DecodeStack:
     def __init__(self, ctx, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
                  prefetch=True, transfer="bf16", alpha=0.125, device="cuda:0"):
         """routers: list over layers of wg [E,H] bf16 device tensors.  slots: number of bf16 slots
-        (transfer="bf16") or {16: n, 4: n, 2: n} (transfer="assigned").  floor_bits: per-layer floor
+        (transfer="bf16") or {16: n, 8: n, 4: n, 2: n} (transfer="assigned"; formats left out get none).  floor_bits: per-layer floor
         of the assignment (list) or None.  tier_count: one tuple for every layer, or a list of
         per-layer tuples (e.g. (t_l, E - t_l) from the depth schedule of Sec. 4.3).  With prefetch,
         the k experts the next layer is predicted to route to are fetched ahead (Eq. 8 with t = k)."""
@@ -138,12 +138,14 @@ class DecodeStack:
         self.routers, self.pool, self.transfer = routers, pool, transfer
         self.floor = list(floor_bits) if floor_bits is not None else [0] * self.L
         self.prefetch, self.alpha, self.dev = prefetch, alpha, device
-        counts = {16: int(slots)} if transfer == "bf16" else {b: int(slots.get(b, 0)) for b in (16, 4, 2)}
+        counts = {16: int(slots)} if transfer == "bf16" else {b: int(slots.get(b, 0)) for b in FORMATS}
         need = k * (2 if prefetch else 1)
         if any(0 < n < need for n in counts.values()) or not any(counts.values()):
             raise ValueError("every configured pool needs at least %d slots" % need)
         self.cache = MixedPrecisionCache(counts)
-        self.slots = {(b, i): _Slot(H, F, b, device, transfer == "bf16") for b, n in counts.items() for i in range(n)}
+        # formats the device quantiser may be asked for when bf16 weights are moved
+        made = sorted({int(b) for b in list(tier_bits) + self.floor if int(b) in (8, 4, 2)}) if transfer == "bf16" else []
+        self.slots = {(b, i): _Slot(H, F, b, device, made) for b, n in counts.items() for i in range(n)}
         per_layer = isinstance(tier_count[0], (tuple, list))
         self.tiers = [tuple(tc) for tc in tier_count] if per_layer else [tuple(tier_count)] * self.L
         if len(self.tiers) != self.L or any(len(tc) != len(tier_bits) for tc in self.tiers):

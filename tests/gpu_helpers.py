@@ -46,10 +46,8 @@ def tiles_from_rowmajor(codes, scale, zero, bits):
     N = codes.shape[0]
     K = codes.shape[1] * 8 // bits
     NT, KT = N // 32, K // 128
-    if bits == 4:     # row bytes: (kt, kb, c, 16) -> tile (c, kb, r, 16)
-        t = codes.reshape(NT, 32, KT, 2, 2, 16).transpose(0, 2, 4, 3, 1, 5)
-    else:             # row bytes: (kt, kb, 16) -> tile (kb, r, 16)
-        t = codes.reshape(NT, 32, KT, 2, 16).transpose(0, 2, 3, 1, 4)
+    C = bits // 2     # 16-byte chunks per lane; row bytes: (kt, kb, c, 16) -> tile (c, kb, r, 16)
+    t = codes.reshape(NT, 32, KT, 2, C, 16).transpose(0, 2, 4, 3, 1, 5)
     sz = lambda a: np.ascontiguousarray(a.reshape(NT, 32, KT, 2).transpose(0, 2, 3, 1)).reshape(N, K // 64)
     return np.ascontiguousarray(t).reshape(codes.shape), sz(scale), sz(zero)
 
@@ -58,10 +56,8 @@ def rowmajor_from_tiles(codes, scale, zero, bits):
     N = codes.shape[0]
     K = codes.shape[1] * 8 // bits
     NT, KT = N // 32, K // 128
-    if bits == 4:
-        t = codes.reshape(NT, KT, 2, 2, 32, 16).transpose(0, 4, 1, 3, 2, 5)
-    else:
-        t = codes.reshape(NT, KT, 2, 32, 16).transpose(0, 3, 1, 2, 4)
+    C = bits // 2
+    t = codes.reshape(NT, KT, C, 2, 32, 16).transpose(0, 4, 1, 3, 2, 5)
     sz = lambda a: np.ascontiguousarray(a.reshape(NT, KT, 2, 32).transpose(0, 3, 1, 2)).reshape(N, K // 64)
     return np.ascontiguousarray(t).reshape(codes.shape), sz(scale), sz(zero)
 

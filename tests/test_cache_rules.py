@@ -76,3 +76,17 @@ def test_covers_predicts_the_outcome_of_a_request():
     c = MixedPrecisionCache({16: 1, 4: 1, 2: 1})
     c.request("a", 4)
     assert c.covers("a", 4) and c.covers("a", 2) and not c.covers("a", 16) and not c.covers("b", 2)
+
+
+def test_four_formats_form_one_ladder():
+    c = MixedPrecisionCache({16: 1, 8: 1, 4: 1, 2: 1})
+    run(c, [
+        ("a", 4, "miss", 4, None),
+        ("a", 8, "promote", 8, None),   # int4 dropped, int8 loaded
+        ("a", 4, "hit", 8, None),       # Conservative Reuse from the 8-bit copy
+        ("b", 8, "miss", 8, "a"),       # one 8-bit slot: a leaves
+        ("a", 2, "miss", 2, None),
+        ("a", 16, "promote", 16, None),
+        ("a", 8, "hit", 16, None),
+    ])
+    assert c.resident("b") == (8, 0) and c.resident("a") == (16, 0)

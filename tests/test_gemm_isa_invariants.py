@@ -128,4 +128,4 @@ def test_counted_waits_cover_the_tile_copies():
                 waited = True
             k += 1
         assert waited, "copy at line %d reaches a barrier without a wait for everything" % c[0]
-    assert checked >= 9          # 3 precisions x fragment counts x 2 projections
+    assert checked >= 32         # 4 precisions x 4 fragment counts x 2 projections

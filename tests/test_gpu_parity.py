@@ -40,7 +40,7 @@ def _check_quant(ctx, w_bits, bits):
     assert np.array_equal(bits_of(zr), rz)
 
 
-@pytest.mark.parametrize("bits", [4, 2])
+@pytest.mark.parametrize("bits", [8, 4, 2])
 def test_quantize_pack_bit_exact(ctx, bits):
     cfg = synth.CONFIGS["tiny"]
     mats = synth.expert_weights(cfg, 1)
@@ -78,20 +78,21 @@ def test_quantize_pack_empty_and_deterministic(ctx):
 @pytest.mark.parametrize("layout", [B.LAYOUT_ROWMAJOR, B.LAYOUT_TILE])
 def test_quantize_experts_follows_device_bits(ctx, layout):
     cfg = synth.CONFIGS["tiny"]
-    E, H, F = 4, cfg.H, cfg.F
+    E, H, F = 5, cfg.H, cfg.F
     mats = [synth.expert_weights(cfg, e) for e in range(E)]
     experts = []
     for e in range(E):
-        experts.append({"w": [to_bf16(m) for m in mats[e]], "q4": empty_q(F, H, 4), "q2": empty_q(F, H, 2)})
-        for b in (4, 2):
+        experts.append({"w": [to_bf16(m) for m in mats[e]], "q8": empty_q(F, H, 8), "q4": empty_q(F, H, 4),
+                        "q2": empty_q(F, H, 2)})
+        for b in (8, 4, 2):
             for cd, sc, zr in experts[e]["q%d" % b]:
                 cd.fill_(0xAB); sc.fill_(-1.0); zr.fill_(-1.0)
     table, keep = B.make_expert_table(experts, DEV)
-    bits = torch.tensor([4, 16, 2, 4], dtype=torch.uint8, device=DEV)
-    load = torch.tensor([3, 5, 1, 0], dtype=torch.int32, device=DEV)
+    bits = torch.tensor([4, 16, 2, 4, 8], dtype=torch.uint8, device=DEV)
+    load = torch.tensor([3, 5, 1, 0, 2], dtype=torch.int32, device=DEV)
     ctx.quantize_experts(table, bits, load, E, H, F, layout=layout)
     sync()
-    for e, b in ((0, 4), (2, 2)):
+    for e, b in ((0, 4), (2, 2), (4, 8)):
         for i in range(3):
             rc, rs, rz = O.quantize_pack(mats[e][i], b)
             cd, sc, zr = experts[e]["q%d" % b][i]
@@ -101,14 +102,14 @@ def test_quantize_experts_follows_device_bits(ctx, layout):
             assert np.array_equal(got[0], rc)
             assert np.array_equal(got[1], rs) and np.array_equal(got[2], rz)
     # untouched: 16-bit expert, the unselected precision, and the expert with no load
-    for e, b in ((1, 4), (1, 2), (0, 2), (2, 4), (3, 4), (3, 2)):
+    for e, b in ((1, 8), (1, 4), (1, 2), (0, 2), (0, 8), (2, 4), (3, 4), (3, 2), (4, 4), (4, 2)):
         for cd, sc, zr in experts[e]["q%d" % b]:
             assert (cd == 0xAB).all() and (sc == -1.0).all()
 
 
 def test_tile_layout_helpers_and_pack_tiles(ctx):
     rng = np.random.default_rng(3)
-    for bits in (4, 2):
+    for bits in (8, 4, 2):
         cd = rng.integers(0, 256, (64, 256 * bits // 8), dtype=np.uint8)
         sc = rng.integers(0, 65536, (64, 4), dtype=np.uint16)
         zr = rng.integers(0, 65536, (64, 4), dtype=np.uint16)
@@ -232,7 +233,8 @@ def test_assign_precision_bit_exact(ctx):
     rng = np.random.default_rng(9)
     cases = [(8, [2, 3, 3], [16, 4, 2], 0), (128, [13, 39, 76], [16, 4, 2], 0),
              (128, [13, 39, 76], [16, 4, 2], 4), (8, [4, 4], [4, 0], 0), (70, [70], [2], 0),
-             (1000, [100, 300, 600], [16, 4, 2], 2)]
+             (1000, [100, 300, 600], [16, 4, 2], 2), (16, [2, 3, 5, 6], [16, 8, 4, 2], 0),
+             (16, [4, 12], [8, 0], 0), (16, [2, 6, 8], [16, 4, 2], 8)]
     for E, tc, tb, floor in cases:
         imp = rng.integers(0, 5, E).astype(np.int32)
         load = rng.integers(0, 40, E).astype(np.int32)
@@ -310,7 +312,8 @@ def test_ffn_tiny_every_precision(ctx, path):
     idx, w = routed(cfg, x)
     for bits_np in (np.array([16, 4, 2, 16, 4, 2, 4, 2], np.uint8),
                     np.full(8, 16, np.uint8), np.full(8, 4, np.uint8), np.full(8, 2, np.uint8),
-                    np.array([16, 0, 2, 4, 0, 2, 4, 16], np.uint8)):
+                    np.array([16, 0, 2, 4, 0, 2, 4, 16], np.uint8),
+                    np.full(8, 8, np.uint8), np.array([8, 16, 2, 8, 4, 0, 8, 2], np.uint8)):
         host, dev, table, keep = build_layer(cfg, bits_np, path=path)
         ref = oracle_ffn(cfg, x, idx, w, bits_np, host)
         y = run_ffn(ctx, cfg, x, idx, w, bits_np, table, path)
@@ -328,13 +331,14 @@ def test_ffn_gemv_ragged_shapes(ctx):
                            tier_count=(E,))
         x, _ = synth.activations(cfg)
         idx, w = routed(cfg, x)
-        bits_np = np.array([16, 4, 2, 4][:E], np.uint8)
-        host, dev, table, keep = build_layer(cfg, bits_np)
-        ref = oracle_ffn(cfg, x, idx, w, bits_np, host)
-        y = run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMV)
-        err = rel_err_per_token(y, ref)
-        print("gemv ragged", (T, H, F, E, k), "err=%.3e" % err)
-        assert err <= FFN_TOL
+        for fmts in ([16, 4, 2, 4], [8, 2, 8, 16]):
+            bits_np = np.array(fmts[:E], np.uint8)
+            host, dev, table, keep = build_layer(cfg, bits_np)
+            ref = oracle_ffn(cfg, x, idx, w, bits_np, host)
+            y = run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMV)
+            err = rel_err_per_token(y, ref)
+            print("gemv ragged", (T, H, F, E, k), fmts[:E], "err=%.3e" % err)
+            assert err <= FFN_TOL
 
 
 def test_ffn_gemm_ragged_tiles(ctx):
@@ -362,6 +366,13 @@ def test_ffn_gemm_ragged_tiles(ctx):
     # AUTO takes the same path for this many tokens
     y2 = run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_AUTO)
     assert np.array_equal(y, y2)
+    # the same ragged tiles with 8-bit experts
+    bits_np = np.array([8, 2, 8, 4], np.uint8)
+    host, dev, table, keep = build_layer(cfg, bits_np, path=B.PATH_GEMM)
+    ref = oracle_ffn(cfg, x, idx, w, bits_np, host)
+    err = rel_err_per_token(run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM), ref)
+    print("gemm ragged, 8-bit experts err=%.3e" % err)
+    assert err <= FFN_TOL
 
 
 def test_ffn_zero_tokens_and_all_skipped(ctx):

@@ -62,7 +62,11 @@ def test_residual_rmsnorm_against_the_oracle(ctx, T, H, alpha):
         assert (got[T - 1] == 0).all()
 
 
-def _small_stack(ctx, L, slots, prefetch, seed0, transfer="bf16", pool=None):
+TIERS3 = ((1, 3, 4), (16, 4, 2))
+TIERS4 = ((1, 2, 2, 3), (16, 8, 4, 2))
+
+
+def _small_stack(ctx, L, slots, prefetch, seed0, transfer="bf16", pool=None, tiers=TIERS3):
     H, F, E, k = 256, 512, 8, 2
     cfgs = [synth.scaled(synth.CONFIGS["tiny"], T=1, phase="decode", config_id=seed0 + l) for l in range(L)]
     routers_np = [synth.router(c)[0] for c in cfgs]
@@ -72,9 +76,9 @@ def _small_stack(ctx, L, slots, prefetch, seed0, transfer="bf16", pool=None):
     if pool is None:
         pool = HostExpertPool(H, F, E, n_pool, lambda i: mats[i])
         if transfer == "assigned":
-            pool.add_quantised(ctx, DEV)
+            pool.add_quantised(ctx, DEV, formats=[b for b in tiers[1] if b != 16])
     floor = [4] + [0] * (L - 2) + [4]
-    stack = DecodeStack(ctx, H, F, E, k, [to_bf16(r) for r in routers_np], pool, slots, (1, 3, 4), (16, 4, 2),
+    stack = DecodeStack(ctx, H, F, E, k, [to_bf16(r) for r in routers_np], pool, slots, tiers[0], tiers[1],
                         floor_bits=floor, prefetch=prefetch, transfer=transfer, alpha=0.25, device=DEV)
     expert_matrices = lambda l, e: mats[pool.entry(l, e)]
     return stack, routers_np, expert_matrices, floor, cfgs[0]
@@ -84,11 +88,11 @@ def _uses(st):
     return st.get("miss", 0) + st.get("promote", 0) + st.get("hit_resident", 0) + st.get("hit_prefetched", 0)
 
 
-def _check_against_oracle(outs, trace, routers_np, expert_matrices, floor):
+def _check_against_oracle(outs, trace, routers_np, expert_matrices, floor, tiers=TIERS3):
     checked = 0
     for s, (x, h_dev) in enumerate(outs):
         run_bits = [dict(zip(ex, used)) for (ex, _, used) in trace[s]]
-        ref_h, log, _ = O.decode_stack(x, routers_np, expert_matrices, 2, (1, 3, 4), (16, 4, 2), floor, 0.25,
+        ref_h, log, _ = O.decode_stack(x, routers_np, expert_matrices, 2, tiers[0], tiers[1], floor, 0.25,
                                        run_bits=run_bits)
         if not all(margin_ok(lg, 2).all() for (_, _, lg, _) in log):
             continue                     # a near tie somewhere in the stack: decisions may legitimately differ
@@ -161,3 +165,24 @@ def test_stack_moving_the_assigned_format_follows_the_cache_rules(ctx):
         for (ex, assigned, used) in step:
             assert all(u >= a for a, u in zip(assigned, used))       # never run below the assigned precision
     _check_against_oracle(outs, stack.trace, routers_np, expert_matrices, floor)
+
+
+@pytest.mark.parametrize("transfer", ["bf16", "assigned"])
+def test_stack_with_an_8_bit_tier(ctx, transfer):
+    """Four tiers (16 / 8 / 4 / 2 bits): the 8-bit format is quantised on the device after a bf16
+    transfer, or travels as such and has a pool of its own in the cache."""
+    L, steps = 3, 4
+    slots = 4 if transfer == "bf16" else {16: 4, 8: 4, 4: 4, 2: 4}
+    stack, routers_np, expert_matrices, floor, cfg0 = _small_stack(ctx, L, slots, True, 900, transfer=transfer,
+                                                                   tiers=TIERS4)
+    outs = []
+    for s in range(steps):
+        x, _ = synth.activations(synth.scaled(cfg0, config_id=950 + (s % 3)))
+        outs.append((x, stack.step(to_bf16(x)).clone()))
+    stack.close()
+    assert _uses(stack.stats) == L * 2 * steps
+    assigned = [a for step in stack.trace for (_, bits, _) in step for a in bits]
+    assert 8 in assigned                                   # the tier is exercised
+    if transfer == "assigned":
+        assert stack.stats["copies_8"] > 0
+    _check_against_oracle(outs, stack.trace, routers_np, expert_matrices, floor, tiers=TIERS4)

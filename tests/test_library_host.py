@@ -88,6 +88,7 @@ def test_argument_validation_happens_before_any_device_work():
     assert lib.dymoe_assign_precision(None, 0, P, P, 8, 9, tcp, tbp, 0, P, P, None) == B.EINVAL
     # quantize
     assert lib.dymoe_quantize_pack(None, P, 8, 256, 4, 64, P, P, P, None) == B.ENOCTX
+    assert lib.dymoe_quantize_pack(None, P, 8, 256, 8, 64, P, P, P, None) == B.ENOCTX
     assert lib.dymoe_quantize_pack(None, P, 8, 256, 3, 64, P, P, P, None) == B.EINVAL
     assert lib.dymoe_quantize_pack(None, P, 8, 200, 4, 64, P, P, P, None) == B.EINVAL
     assert lib.dymoe_quantize_pack(None, P, 8, 256, 4, 32, P, P, P, None) == B.ENOTSUP

@@ -288,3 +288,55 @@ def decode_stack(h0_bits, routers, expert_matrices, k, tier_count, tier_bits, fl
         h = residual_rmsnorm(h, y, alpha)
     return h, log, preds
 
+
+
+def predicted_frequency(h_bits, wg_next, k, t):
+    """Sec. 4.4.1 Eq. 6 + Eq. 7: the next layer's router on the current hidden
+    states; c[e] = number of tokens whose predicted top-k holds expert e; the
+    t experts of highest c (ties: lower index; experts nobody asks for are left out).
+    Returns (c [E] int32, list of predicted experts, the predicted logits [T,E])."""
+    pidx, _, _, plogits = route_topk(h_bits, wg_next, None, k)
+    E = wg_next.shape[0]
+    c = np.bincount(pidx.ravel(), minlength=E).astype(np.int32)
+    order = sorted(range(E), key=lambda e: (-int(c[e]), e))
+    return c, [e for e in order[:t] if c[e] > 0], plogits
+
+
+def prefill_stack(h0_bits, routers, expert_matrices, k, k_hh, tier_count, tier_bits, floor_bits, alpha,
+                  predict_t=0, run_bits=None, token_score=None):
+    """A stack of expert layers on a batch of T tokens (composition of the
+    functions above): per layer gating, heavy-hitter importance (Eq. 2) with
+    one score per token for the whole stack (given, or the row norms of the
+    stack's input), assignment, quantisation of the loaded experts to their
+    assigned width, FFN, residual + normalisation; with predict_t, the experts
+    Eq. 7 would fetch ahead for the next layer.
+    tier_count: one tuple, or one per layer.  run_bits as in decode_stack.
+    Returns (final h bits, per-layer (idx, bits [E], logits, importance, load), per-layer predictions)."""
+    h = _c(h0_bits, np.uint16)
+    score = token_score_norm(h) if token_score is None else np.asarray(token_score, np.float64)
+    per_layer = isinstance(tier_count[0], (tuple, list))
+    log, preds = [], []
+    for l, wg in enumerate(routers):
+        E = wg.shape[0]
+        idx, w, probs, logits = route_topk(h, wg, None, k)
+        if predict_t and l + 1 < len(routers):
+            preds.append(predicted_frequency(h, routers[l + 1], k, predict_t))
+        imp, load, _ = expert_importance_prefill(idx, score, E, k_hh)
+        bits, _ = assign_precision(imp, load, tier_count[l] if per_layer else tier_count, tier_bits,
+                                   floor_bits[l] if floor_bits else 0)
+        experts = []
+        use_bits = np.zeros(E, np.uint8)
+        for e in range(E):
+            b = int(bits[e])
+            if load[e] == 0 or b == 0:
+                experts.append({})
+                continue
+            if run_bits is not None:
+                b = int(run_bits[l].get(e, b))
+            use_bits[e] = b
+            mats = expert_matrices(l, e)
+            experts.append({"w": mats} if b == 16 else {"q": [quantize_pack(m, b) for m in mats]})
+        y = moe_ffn_mixed(h, idx, w, use_bits, experts) if use_bits.any() else np.zeros(h.shape, np.float64)
+        log.append((idx.copy(), bits.copy(), logits.copy(), imp.copy(), load.copy()))
+        h = residual_rmsnorm(h, y, alpha)
+    return h, log, preds

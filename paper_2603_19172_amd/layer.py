@@ -75,12 +75,15 @@ class MoELayer:
                                         self.E, self.k, 1, self.idx.data_ptr(), self.gate.data_ptr(),
                                         self.probs.data_ptr(), st), "dymoe_route_topk")
 
-    def importance(self, x, st):
-        if self.phase == B.PHASE_PREFILL:
+    def importance(self, x, st, score=None):
+        """score: [T] fp32 token scores to rank the heavy hitters by (prefill); None: the row norms of x."""
+        if self.phase == B.PHASE_PREFILL and score is None:
             B._check(B.lib.dymoe_token_score_norm(self.ctx._h, x.data_ptr(), self.T, self.H,
                                                   self.score.data_ptr(), st), "dymoe_token_score_norm")
+        if score is None:
+            score = self.score
         B._check(B.lib.dymoe_expert_importance(self.ctx._h, self.phase, self.idx.data_ptr(),
-                                               self.probs.data_ptr(), self.score.data_ptr(), self.T,
+                                               self.probs.data_ptr(), score.data_ptr(), self.T,
                                                self.E, self.k, self.k_hh, self.imp.data_ptr(),
                                                self.load.data_ptr(), st), "dymoe_expert_importance")
 

@@ -1,11 +1,14 @@
-"""A stack of MoE expert layers decoding one token at a time with the experts
-resident in pinned HOST memory (paper Sec. 4.4: dynamic expert orchestration).
+"""A stack of MoE expert layers with the experts resident in pinned HOST memory
+(paper Sec. 4.4: dynamic expert orchestration), decoding one token at a time
+or prefilling a batch of tokens.
 
 Per layer the compute stream runs the hot path of `layer.py`; the experts it
 needs are brought into device slots, on demand or ahead of time: the next
-layer's router applied to the current hidden state (Sec. 4.4.1 Eq. 6) names the
-experts to prefetch (Eq. 8), which are copied on a side stream
-(dymoe_prefetch_submit / dymoe_prefetch_wait) while the current layer computes.
+layer's router applied to the current hidden states (Sec. 4.4.1 Eq. 6) names the
+experts to prefetch (decode: the token's own predicted experts, Eq. 8; prefill:
+the experts most tokens are predicted to ask for, Eq. 7), which are copied on a
+side stream (dymoe_prefetch_submit / dymoe_prefetch_wait) while the current
+layer computes.
 
 Two ways of moving an expert:
   transfer="bf16"      the bf16 weights travel and are quantised on the device
@@ -52,6 +55,7 @@ class HostExpertPool:
         self.H, self.F, self.E, self.n_pool = H, F, E, n_pool
         self.elems = 3 * H * F
         self.nbytes = {16: 2 * self.elems}
+        self.layout = B.LAYOUT_ROWMAJOR     # of the quantised formats, once made
         self.buf = {16: torch.empty((n_pool, 2 * self.elems), dtype=torch.uint8, pin_memory=True)}
         view = self.buf[16].numpy().view("int16")
         for i in range(n_pool):
@@ -60,24 +64,29 @@ class HostExpertPool:
             view[i, H * F:2 * H * F] = w3.reshape(-1).view("int16")
             view[i, 2 * H * F:] = w2.reshape(-1).view("int16")
 
-    def add_quantised(self, ctx, device, formats=(4, 2)):
+    def add_quantised(self, ctx, device, formats=(4, 2), layout=B.LAYOUT_ROWMAJOR):
         """Quantised copies (by default int4 and int2) of every entry, made by the device quantiser and
-        kept in pinned host memory."""
+        kept in pinned host memory, in the layout the FFN path that will read them expects (row-major for
+        the GEMV, tiles for the grouped GEMM)."""
         H, F = self.H, self.F
+        self.layout = layout
         wdev = torch.empty((self.elems,), dtype=torch.bfloat16, device=device)
+        st = torch.cuda.current_stream().cuda_stream
         for b in formats:
             offs, total = quant_layout(H, F, b)
             self.nbytes[b] = total
             self.buf[b] = torch.empty((self.n_pool, total), dtype=torch.uint8, pin_memory=True)
             stage = torch.empty((total,), dtype=torch.uint8, device=device)
+            fmt = B.ExpertFmt()
+            for m in range(3):
+                fmt.w[m] = wdev.data_ptr() + m * H * F * 2
+            _Slot._point(fmt, b, stage.data_ptr(), offs)
+            table = torch.frombuffer(bytearray(bytes(fmt)), dtype=torch.uint8).to(device)
+            want = torch.tensor([b], dtype=torch.uint8, device=device)
             for i in range(self.n_pool):
                 wdev.view(torch.uint8).copy_(self.buf[16][i], non_blocking=True)
-                for m, (n, kk) in enumerate(((F, H), (F, H), (H, F))):
-                    w = wdev[m * H * F:(m + 1) * H * F].view(n, kk)
-                    co, so, zo = offs[m]
-                    B._check(B.lib.dymoe_quantize_pack(ctx._h, w.data_ptr(), n, kk, b, 64, stage.data_ptr() + co,
-                                                       stage.data_ptr() + so, stage.data_ptr() + zo,
-                                                       torch.cuda.current_stream().cuda_stream), "dymoe_quantize_pack")
+                B._check(B.lib.dymoe_quantize_experts(ctx._h, table.data_ptr(), want.data_ptr(), None, 1, H, F, 64,
+                                                      layout, st), "dymoe_quantize_experts")
                 self.buf[b][i].copy_(stage, non_blocking=True)
             torch.cuda.synchronize()
 
@@ -123,23 +132,30 @@ class _Slot:
             getattr(fmt, "z%d" % b)[i] = base + zo
 
 
-class DecodeStack:
-    def __init__(self, ctx, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
-                 prefetch=True, transfer="bf16", alpha=0.125, device="cuda:0"):
-        """routers: list over layers of wg [E,H] bf16 device tensors.  slots: number of bf16 slots
-        (transfer="bf16") or {16: n, 8: n, 4: n, 2: n} (transfer="assigned"; formats left out get none).  floor_bits: per-layer floor
-        of the assignment (list) or None.  tier_count: one tuple for every layer, or a list of
-        per-layer tuples (e.g. (t_l, E - t_l) from the depth schedule of Sec. 4.3).  With prefetch,
-        the k experts the next layer is predicted to route to are fetched ahead (Eq. 8 with t = k)."""
+class ExpertStack:
+    def __init__(self, ctx, T, phase, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
+                 prefetch=True, transfer="bf16", alpha=0.125, k_hh=0, predict_t=None, device="cuda:0"):
+        """T tokens per step; phase "decode" (gate-score importance, Eq. 3; the k experts the next layer is
+        predicted to route the token to are fetched ahead, Eq. 8 with t = k) or "prefill" (heavy-hitter
+        importance over the k_hh highest-norm tokens, Eq. 2; the predict_t experts of highest predicted
+        token frequency are fetched ahead, Eq. 7).
+        routers: list over layers of wg [E,H] bf16 device tensors.  slots: number of bf16 slots
+        (transfer="bf16") or {16: n, 8: n, 4: n, 2: n} (transfer="assigned"; formats left out get none).
+        floor_bits: per-layer floor of the assignment (list) or None.  tier_count: one tuple for every
+        layer, or a list of per-layer tuples (e.g. (t_l, E - t_l) from the depth schedule of Sec. 4.3)."""
         if transfer not in ("bf16", "assigned"):
             raise ValueError("transfer must be 'bf16' or 'assigned'")
-        self.ctx, self.H, self.F, self.E, self.k = ctx, H, F, E, k
+        if phase not in ("decode", "prefill"):
+            raise ValueError("phase must be 'decode' or 'prefill'")
+        self.ctx, self.T, self.phase, self.H, self.F, self.E, self.k = ctx, T, phase, H, F, E, k
         self.L = len(routers)
         self.routers, self.pool, self.transfer = routers, pool, transfer
         self.floor = list(floor_bits) if floor_bits is not None else [0] * self.L
         self.prefetch, self.alpha, self.dev = prefetch, alpha, device
+        self.predict_t = int(predict_t) if predict_t is not None else k
         counts = {16: int(slots)} if transfer == "bf16" else {b: int(slots.get(b, 0)) for b in FORMATS}
-        need = k * (2 if prefetch else 1)
+        # a layer's experts are all resident while it runs, next to the ones fetched ahead
+        need = min(E, T * k) + (self.predict_t if prefetch else 0)
         if any(0 < n < need for n in counts.values()) or not any(counts.values()):
             raise ValueError("every configured pool needs at least %d slots" % need)
         self.cache = MixedPrecisionCache(counts)
@@ -151,18 +167,23 @@ class DecodeStack:
         if len(self.tiers) != self.L or any(len(tc) != len(tier_bits) for tc in self.tiers):
             raise ValueError("tier_count: one tuple, or one per layer, as long as tier_bits")
         self.tier_arrays = [(C.c_int32 * len(tc))(*[int(v) for v in tc]) for tc in self.tiers]
-        mk = lambda: MoELayer(ctx, 1, H, F, E, k, "decode", self.tiers[0], tier_bits, out_dtype=B.OUT_F32,
-                              path=B.PATH_GEMV, device=device)
+        path = B.PATH_GEMV if T == 1 else B.PATH_AUTO
+        mk = lambda: MoELayer(ctx, T, H, F, E, k, phase, self.tiers[0], tier_bits, k_hh=k_hh, out_dtype=B.OUT_F32,
+                              path=path, device=device)
         self.layer, self.ahead = mk(), mk()     # buffers of the current layer, and of the look-ahead prediction
+        if transfer == "assigned" and pool.layout != self.layer.layout:
+            raise ValueError("the pool's quantised formats are not in the layout the FFN path reads")
         self.tables = torch.zeros((self.L, E, FMT_BYTES), dtype=torch.uint8, device=device)
         self.table_slot = {}                    # (layer, e) -> slot written in the table
-        self.h = [torch.empty((1, H), dtype=torch.bfloat16, device=device) for _ in range(2)]
+        self.h = [torch.empty((T, H), dtype=torch.bfloat16, device=device) for _ in range(2)]
+        self.score = torch.empty((T,), dtype=torch.float32, device=device)
         self.side = torch.cuda.Stream(device=device)
         pin = lambda shape, dt: torch.empty(shape, dtype=dt).pin_memory()
-        self.host_idx, self.host_bits = pin((1, k), torch.int32), pin((E,), torch.uint8)
-        self.host_pidx, self.host_pbits = pin((1, k), torch.int32), pin((E,), torch.uint8)
+        self.host_idx, self.host_load, self.host_bits = pin((T, k), torch.int32), pin((E,), torch.int32), pin((E,), torch.uint8)
+        self.host_pidx, self.host_pload, self.host_pbits = pin((T, k), torch.int32), pin((E,), torch.int32), pin((E,), torch.uint8)
         self.stats = collections.Counter()
         self.trace = []     # per step and layer: (experts, assigned bits, bits they were run at)
+        self.predictions = []   # per step and layer (but the last): experts fetched ahead for the next layer
 
     def _fill(self, act, key, ahead):
         """Copy the format `act.load_bits` of expert `key` into the slot the cache chose, on the side stream."""
@@ -181,27 +202,52 @@ class DecodeStack:
         self.stats["bytes_copied"] += nbytes
         self.stats["copies_%d" % act.load_bits] += 1
 
-    def step(self, h0):
-        """One decode step through all layers.  h0: [1,H] bf16 on the device.  Returns the final hidden state."""
+    def _front(self, lay, h, wg, st):
+        """S1 + S2 + S3 into the buffers of `lay`."""
+        if self.phase == "decode" and self.T <= B.FRONT_MAX_TOKENS:
+            lay.front(h, wg, None, st)
+        else:
+            lay.route(h, wg, None, st)
+            lay.importance(h, st, score=self.score if self.phase == "prefill" else None)
+            lay.assign(st)
+
+    def step(self, h0, token_score=None):
+        """One step (T tokens) through all layers.  h0: [T,H] bf16 on the device.  Returns the final hidden states.
+        Prefill: token_score [T] fp32 ranks the heavy-hitter tokens in every layer (a token's score is a
+        property of the token, Sec. 4.2.1); None takes the row norms of h0 (the layers' own inputs are
+        normalised and carry no such signal)."""
         lay, nxt_lay, ctx = self.layer, self.ahead, self.ctx
         cs = torch.cuda.current_stream()
         st = cs.cuda_stream
         h = self.h[0]
         h.copy_(h0)
-        step_trace = []
+        if self.phase == "prefill":
+            if token_score is not None:
+                self.score.copy_(token_score)
+            else:
+                B._check(B.lib.dymoe_token_score_norm(ctx._h, h.data_ptr(), self.T, self.H, self.score.data_ptr(), st),
+                         "dymoe_token_score_norm")
+        step_trace, step_pred = [], []
         for l in range(self.L):
             lay.floor_bits, lay._tc = self.floor[l], self.tier_arrays[l]
-            lay.front(h, self.routers[l], None, st)
+            self._front(lay, h, self.routers[l], st)
             look = self.prefetch and l + 1 < self.L
-            if look:     # Eq. 6: the next layer's router (and precision rule) on the current hidden state
+            if look:     # Eq. 6: the next layer's router (and precision rule) on the current hidden states
                 nxt_lay.floor_bits, nxt_lay._tc = self.floor[l + 1], self.tier_arrays[l + 1]
-                nxt_lay.front(h, self.routers[l + 1], None, st)
-                self.host_pidx.copy_(nxt_lay.idx, non_blocking=True)
+                self._front(nxt_lay, h, self.routers[l + 1], st)
+                if self.T == 1:
+                    self.host_pidx.copy_(nxt_lay.idx, non_blocking=True)
+                self.host_pload.copy_(nxt_lay.load, non_blocking=True)
                 self.host_pbits.copy_(nxt_lay.bits, non_blocking=True)
-            self.host_idx.copy_(lay.idx, non_blocking=True)
+            if self.T == 1:
+                self.host_idx.copy_(lay.idx, non_blocking=True)
+            self.host_load.copy_(lay.load, non_blocking=True)
             self.host_bits.copy_(lay.bits, non_blocking=True)
             cs.synchronize()
-            active = [int(e) for e in self.host_idx[0].tolist()]
+            if self.T == 1:      # in routing order
+                active = [int(e) for e in self.host_idx[0].tolist()]
+            else:                # every expert some token was routed to
+                active = [e for e, c in enumerate(self.host_load.tolist()) if c > 0]
             abits = [int(self.host_bits[e]) for e in active]
             want = lambda b: 16 if self.transfer == "bf16" else b
             need = [(e, b) for e, b in zip(active, abits) if b != 0]
@@ -241,7 +287,14 @@ class DecodeStack:
             step_trace.append((tuple(active), tuple(abits), tuple(used_bits[e] for e in active)))
             # the next layer's predicted experts, copied while this layer computes
             if look:
-                for e in [int(v) for v in self.host_pidx[0].tolist()]:
+                if self.T == 1:      # Eq. 8: the token's own predicted experts
+                    ahead = [int(v) for v in self.host_pidx[0].tolist()][:self.predict_t]
+                else:                # Eq. 7: the experts most tokens are predicted to ask for
+                    freq = self.host_pload.tolist()
+                    order = sorted(range(self.E), key=lambda e: (-freq[e], e))
+                    ahead = [e for e in order[:self.predict_t] if freq[e] > 0]
+                step_pred.append(tuple(ahead))
+                for e in ahead:
                     pb = int(self.host_pbits[e])
                     key = (l + 1, e)
                     if pb == 0:
@@ -257,14 +310,14 @@ class DecodeStack:
             if self.transfer == "bf16":      # S4 on arrival
                 B._check(B.lib.dymoe_quantize_experts(ctx._h, table.data_ptr(), lay.bits.data_ptr(),
                                                       lay.load.data_ptr(), self.E, self.H, self.F, 64,
-                                                      B.LAYOUT_ROWMAJOR, st), "dymoe_quantize_experts")
+                                                      lay.layout, st), "dymoe_quantize_experts")
             B._check(B.lib.dymoe_moe_ffn_mixed(ctx._h, h.data_ptr(), lay.idx.data_ptr(), lay.gate.data_ptr(),
-                                               lay.bits.data_ptr(), table.data_ptr(), 1, self.H, self.F, self.E,
-                                               self.k, 64, B.OUT_F32, B.PATH_GEMV, lay.y.data_ptr(),
+                                               lay.bits.data_ptr(), table.data_ptr(), self.T, self.H, self.F, self.E,
+                                               self.k, 64, B.OUT_F32, lay.path, lay.y.data_ptr(),
                                                lay.ws.data_ptr(), lay.ws_bytes, st), "dymoe_moe_ffn_mixed")
             nxt = self.h[(l + 1) % 2]
             B._check(B.lib.dymoe_residual_rmsnorm(ctx._h, h.data_ptr(), lay.y.data_ptr(), B.OUT_F32,
-                                                  float(self.alpha), 1, self.H, nxt.data_ptr(), st),
+                                                  float(self.alpha), self.T, self.H, nxt.data_ptr(), st),
                      "dymoe_residual_rmsnorm")
             done = torch.cuda.Event()
             done.record(cs)
@@ -272,6 +325,7 @@ class DecodeStack:
                 self.slots[self.cache.resident((l, e))].last_use = done
             h = nxt
         self.trace.append(step_trace)
+        self.predictions.append(step_pred)
         self.stats["steps"] += 1
         return h
 
@@ -281,3 +335,23 @@ class DecodeStack:
             if slot.copy_event is not None:
                 self.ctx.prefetch_release(slot.copy_event)
                 slot.copy_event = None
+
+
+class DecodeStack(ExpertStack):
+    """One token per step (Sec. 4.2.2 importance, Eq. 8 prefetch)."""
+
+    def __init__(self, ctx, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
+                 prefetch=True, transfer="bf16", alpha=0.125, device="cuda:0"):
+        super().__init__(ctx, 1, "decode", H, F, E, k, routers, pool, slots, tier_count, tier_bits,
+                         floor_bits=floor_bits, prefetch=prefetch, transfer=transfer, alpha=alpha, device=device)
+
+
+class PrefillStack(ExpertStack):
+    """T tokens per step (Sec. 4.2.1 importance over the k_hh highest-norm tokens, Eq. 7 prefetch of
+    the predict_t most frequently predicted experts)."""
+
+    def __init__(self, ctx, T, H, F, E, k, k_hh, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
+                 prefetch=True, predict_t=None, transfer="bf16", alpha=0.125, device="cuda:0"):
+        super().__init__(ctx, T, "prefill", H, F, E, k, routers, pool, slots, tier_count, tier_bits,
+                         floor_bits=floor_bits, prefetch=prefetch, transfer=transfer, alpha=alpha, k_hh=k_hh,
+                         predict_t=predict_t if predict_t is not None else min(E, max(k, E // 2)), device=device)

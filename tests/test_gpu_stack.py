@@ -8,7 +8,7 @@ import torch
 from oracle import dymoe_oracle as O
 from paper_2603_19172_amd import binding as B
 from paper_2603_19172_amd import synth
-from paper_2603_19172_amd.stack import DecodeStack, HostExpertPool
+from paper_2603_19172_amd.stack import DecodeStack, HostExpertPool, PrefillStack
 from gpu_helpers import DEV, bits_of, margin_ok, to_bf16
 
 pytestmark = pytest.mark.gpu
@@ -186,3 +186,97 @@ def test_stack_with_an_8_bit_tier(ctx, transfer):
     if transfer == "assigned":
         assert stack.stats["copies_8"] > 0
     _check_against_oracle(outs, stack.trace, routers_np, expert_matrices, floor, tiers=TIERS4)
+
+
+# ------------------------------------------------------------------ prefill: Eq. 2 importance, Eq. 7 prefetch
+
+def _small_prefill_stack(ctx, T, L, slots, prefetch, seed0, transfer="bf16", predict_t=4, pool=None):
+    H, F, E, k, k_hh = 256, 512, 8, 2, 3
+    cfgs = [synth.scaled(synth.CONFIGS["tiny"], T=T, config_id=seed0 + l) for l in range(L)]
+    routers_np = [synth.router(c)[0] for c in cfgs]
+    n_pool = 12
+    pool_cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=seed0 + 50)
+    mats = {i: synth.expert_weights(pool_cfg, i) for i in range(n_pool)}
+    if pool is None:
+        pool = HostExpertPool(H, F, E, n_pool, lambda i: mats[i])
+        if transfer == "assigned":
+            pool.add_quantised(ctx, DEV, layout=B.LAYOUT_TILE)       # T > 4: the grouped GEMM reads tiles
+    floor = [4] + [0] * (L - 1)
+    stack = PrefillStack(ctx, T, H, F, E, k, k_hh, [to_bf16(r) for r in routers_np], pool, slots, (1, 3, 4),
+                         (16, 4, 2), floor_bits=floor, prefetch=prefetch, predict_t=predict_t, transfer=transfer,
+                         alpha=0.25, device=DEV)
+    return stack, routers_np, (lambda l, e: mats[pool.entry(l, e)]), floor, cfgs[0], k_hh
+
+
+def _check_prefill_against_oracle(outs, stack, routers_np, expert_matrices, floor, k_hh, predict_t):
+    checked = 0
+    for s, (x, h_dev) in enumerate(outs):
+        run_bits = [dict(zip(ex, used)) for (ex, _, used) in stack.trace[s]]
+        ref_h, log, preds = O.prefill_stack(x, routers_np, expert_matrices, 2, k_hh, (1, 3, 4), (16, 4, 2), floor,
+                                            0.25, predict_t=predict_t, run_bits=run_bits)
+        if not all(margin_ok(lg, 2).all() for (_, _, lg, _, _) in log):
+            continue                     # a near tie somewhere in the stack: decisions may legitimately differ
+        checked += 1
+        for l, (idx, bts, _, imp, load) in enumerate(log):
+            active = tuple(int(e) for e in np.nonzero(load)[0])
+            assert stack.trace[s][l][0] == active                               # Eq. 7's counts are exact integers
+            assert stack.trace[s][l][1] == tuple(int(bts[e]) for e in active)   # Eq. 2 importance -> assignment
+        if stack.prefetch:
+            # first layer: both sides predict from the same input, so Eq. 7's list is the same, in order
+            c, want, plg = preds[0]
+            if margin_ok(plg, 2).all():
+                assert list(stack.predictions[s][0]) == want
+            # deeper layers predict from the GPU's own hidden states (within the FFN tolerance of the
+            # oracle's): one token routed differently moves a count by one, so compare the sets where
+            # the counts at the cut are further apart than that
+            for l, (c, want, _) in enumerate(preds):
+                srt = sorted(c.tolist(), reverse=True)
+                if len(srt) > predict_t and srt[predict_t - 1] - srt[predict_t] < 2:
+                    continue
+                assert set(stack.predictions[s][l]) == set(want)
+        got = synth.bf16_bits_to_f32(bits_of(h_dev)).astype(np.float64)
+        want_h = synth.bf16_bits_to_f32(ref_h).astype(np.float64)
+        assert np.abs(got - want_h).max() <= 2e-2
+    assert checked >= 1
+
+
+@pytest.mark.parametrize("T", [24, 150])
+def test_prefill_stack_matches_the_oracle_and_prefetch_changes_nothing(ctx, T):
+    L, steps, predict_t = 3, 2, 4
+    outs, traces = {}, {}
+    for prefetch in (False, True):
+        stack, routers_np, expert_matrices, floor, cfg0, k_hh = _small_prefill_stack(ctx, T, L, 12, prefetch, 1100,
+                                                                                     predict_t=predict_t)
+        hs = []
+        for s in range(steps):
+            x, _ = synth.activations(synth.scaled(cfg0, config_id=1200 + s))
+            hs.append((x, stack.step(to_bf16(x)).clone()))
+        stack.close()
+        outs[prefetch], traces[prefetch] = hs, stack.trace
+        if prefetch:
+            assert stack.stats["prefetch_issued"] > 0 and stack.stats["hit_prefetched"] > 0
+            assert all(len(p) == predict_t for step in stack.predictions for p in step)
+            _check_prefill_against_oracle(hs, stack, routers_np, expert_matrices, floor, k_hh, predict_t)
+    for (x0, a), (x1, b) in zip(outs[False], outs[True]):
+        assert torch.equal(a, b)
+    assert traces[False] == traces[True]
+
+
+def test_prefill_stack_moving_the_assigned_format_in_tile_layout(ctx):
+    T, L, steps = 40, 3, 3
+    slots = {16: 12, 4: 12, 2: 12}
+    stack, routers_np, expert_matrices, floor, cfg0, k_hh = _small_prefill_stack(ctx, T, L, slots, True, 1300,
+                                                                                 transfer="assigned", predict_t=4)
+    outs = []
+    for s in range(steps):
+        x, _ = synth.activations(synth.scaled(cfg0, config_id=1400 + (s % 2)))
+        outs.append((x, stack.step(to_bf16(x)).clone()))
+    stack.close()
+    st = stack.stats
+    assert st["copies_4"] + st["copies_2"] > 0
+    moved = sum(st.get("copies_%d" % b, 0) * stack.pool.nbytes[b] for b in (16, 4, 2))
+    assert moved == st["bytes_copied"]
+    for step in stack.trace:
+        for (ex, assigned, used) in step:
+            assert all(u >= a for a, u in zip(assigned, used))
+    _check_prefill_against_oracle(outs, stack, routers_np, expert_matrices, floor, k_hh, 4)

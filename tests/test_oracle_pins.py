@@ -516,3 +516,28 @@ def test_residual_rmsnorm_closed_forms():
     assert (a[2] == 0).all()
     rms = np.sqrt((synth.bf16_bits_to_f32(a[:2]).astype(np.float64) ** 2).mean(axis=1))
     assert np.allclose(rms, 1.0, atol=2e-3)
+
+
+def test_predicted_frequency_counts_and_cut():
+    """Eq. 7: the counts are a histogram of the predicted top-k sets (sum = T k); the list is the t
+    largest counts, lower index first among equals, and never names an expert nobody asked for."""
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=12, config_id=31)
+    x, _ = synth.activations(cfg)
+    wg, _ = synth.router(cfg)
+    c, pred, lg = O.predicted_frequency(x, wg, 2, 3)
+    assert c.sum() == 12 * 2 and lg.shape == (12, 8)
+    top2 = np.argsort(-lg, axis=1, kind="stable")[:, :2]
+    assert np.array_equal(c, np.bincount(top2.ravel(), minlength=8))
+    assert pred == sorted(range(8), key=lambda e: (-c[e], e))[:3]
+    # one token, k = 2, t = 5: only the two experts it asks for
+    c1, pred1, lg1 = O.predicted_frequency(x[:1], wg, 2, 5)
+    assert sorted(pred1) == sorted(top2[0].tolist()) and c1.sum() == 2
+    # the first layer of the prefill composition: k_hh = T makes Eq. 2's importance the load itself
+    mats = synth.expert_weights(cfg, 0)
+    h, log, preds = O.prefill_stack(x, [wg, wg], lambda l, e: mats, 2, 12, (8,), (16,), None, 0.25, predict_t=3)
+    idx, bits, _, imp, load = log[0]
+    assert np.array_equal(imp, load) and load.sum() == 24 and (bits == 16).all()
+    assert preds[0][1] == pred and np.array_equal(preds[0][0], c)      # same router, same input
+    # identical experts, all 16-bit: the layer is a dense SwiGLU MLP with gate weights summing to one
+    y = O.moe_ffn_mixed(x, idx, np.full(idx.shape, 0.5), np.full(8, 16, np.uint8), [{"w": mats}] * 8)
+    assert np.array_equal(O.residual_rmsnorm(x, y, 0.25), O.prefill_stack(x, [wg], lambda l, e: mats, 2, 12, (8,), (16,), None, 0.25)[0])

@@ -340,3 +340,32 @@ def prefill_stack(h0_bits, routers, expert_matrices, k, k_hh, tier_count, tier_b
         log.append((idx.copy(), bits.copy(), logits.copy(), imp.copy(), load.copy()))
         h = residual_rmsnorm(h, y, alpha)
     return h, log, preds
+
+
+def _widen_bf16(bits):
+    """bf16 bit patterns -> the float32 values they denote (exact)."""
+    return (np.ascontiguousarray(bits, np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def token_score_attention(q_bits, k_bits, n_heads, n_kv_heads, causal=True, scale=None):
+    """Sec. 4.2.1, first equation: s_i = (1/Hh) sum_h a_i^(h), read as the attention
+    token i RECEIVES in head h averaged over the T queries: a_i^(h) = (1/T) sum_q P^(h)[q, i],
+    P^(h) = softmax over keys of q_q . k_i * scale (causal: keys after the query masked out).
+    q [T, n_heads, d], k [T, n_kv_heads, d] as bf16 bits; query head h reads key head
+    h // (n_heads / n_kv_heads).  fp64 throughout; returns s [T] (sums to 1)."""
+    q = _widen_bf16(q_bits).astype(np.float64)
+    k = _widen_bf16(k_bits).astype(np.float64)
+    T, Hh, d = q.shape
+    assert Hh == n_heads and k.shape == (T, n_kv_heads, d) and n_heads % n_kv_heads == 0
+    group = n_heads // n_kv_heads
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    s = np.zeros(T, np.float64)
+    visible = np.tril(np.ones((T, T), bool)) if causal else np.ones((T, T), bool)
+    for h in range(n_heads):
+        logits = (q[:, h, :] @ k[:, h // group, :].T) * scale          # [query, key]
+        logits = np.where(visible, logits, -np.inf)
+        p = np.exp(logits - logits.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        s += p.sum(axis=0)
+    return s / (n_heads * T)

@@ -144,3 +144,28 @@ def expert_weights_many(cfg: MoEConfig, experts, workers: int = 8):
     for (e, i), m in zip(jobs, mats):
         out.setdefault(e, [None, None, None])[i] = m
     return out
+
+
+_TID_ATTN = 5000  # + {0: queries, 1: keys, 2: per-head direction}
+
+
+def attention_inputs(cfg: MoEConfig, n_heads: int, n_kv_heads: int, head_dim: int, boost: float = 1.0):
+    """Queries [T, n_heads, d] and keys [T, n_kv_heads, d] ~ N(0,1) as bf16 bits, for the
+    attention-derived token score.  Every query carries a per-head direction u (|u| = sqrt(d)/2), and
+    the keys of the config's heavy-hitter tokens (the same seeded rows `activations` scales) carry
+    boost * u of their head as well, so that those tokens receive more attention, as heavy hitters do
+    in trained models.  Returns (q bits, k bits, heavy token indices)."""
+    T = cfg.T
+    rq = _rng(cfg.config_id, _TID_ATTN + 0)
+    rk = _rng(cfg.config_id, _TID_ATTN + 1)
+    ru = _rng(cfg.config_id, _TID_ATTN + 2)
+    q = rq.standard_normal((T, n_heads, head_dim), dtype=np.float32)
+    k = rk.standard_normal((T, n_kv_heads, head_dim), dtype=np.float32)
+    u = ru.standard_normal((n_kv_heads, head_dim), dtype=np.float32)
+    u *= (0.5 * np.sqrt(head_dim)) / np.linalg.norm(u, axis=1, keepdims=True)
+    group = n_heads // n_kv_heads
+    q += np.repeat(u, group, axis=0)[None, :, :]
+    _, heavy = activations(cfg)
+    if heavy.size:
+        k[heavy] += boost * u[None, :, :]
+    return f32_to_bf16_bits(q), f32_to_bf16_bits(k), heavy

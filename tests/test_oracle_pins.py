@@ -541,3 +541,71 @@ def test_predicted_frequency_counts_and_cut():
     # identical experts, all 16-bit: the layer is a dense SwiGLU MLP with gate weights summing to one
     y = O.moe_ffn_mixed(x, idx, np.full(idx.shape, 0.5), np.full(8, 16, np.uint8), [{"w": mats}] * 8)
     assert np.array_equal(O.residual_rmsnorm(x, y, 0.25), O.prefill_stack(x, [wg], lambda l, e: mats, 2, 12, (8,), (16,), None, 0.25)[0])
+
+
+# ---------------------------------------------------------------- attention-derived token score
+
+def _harmonic(n):
+    return sum(1.0 / j for j in range(1, n + 1))
+
+
+def test_attention_score_closed_forms():
+    rng = np.random.default_rng(5)
+    T, Hh, Hkv, d = 9, 4, 2, 16
+    k = bf16(rng.standard_normal((T, Hkv, d)))
+    zero_q = bf16(np.zeros((T, Hh, d)))
+    # all logits equal: every query spreads its unit of attention evenly over the keys it sees
+    s = O.token_score_attention(zero_q, k, Hh, Hkv, causal=False)
+    assert np.allclose(s, 1.0 / T, rtol=0, atol=1e-15)
+    s = O.token_score_attention(zero_q, k, Hh, Hkv, causal=True)
+    want = [(_harmonic(T) - _harmonic(i)) / T for i in range(T)]      # key i is seen by queries i..T-1, 1/(q+1) each
+    assert np.allclose(s, want, rtol=0, atol=1e-15)
+    # one key dominates: keys = 0 but key 3 = 40 e_0, queries = e_0; exp(-10) mass elsewhere
+    kk = np.zeros((T, 1, d), np.float32)
+    kk[3, 0, 0] = 40.0
+    qq = np.zeros((T, 2, d), np.float32)
+    qq[:, :, 0] = 1.0
+    s = O.token_score_attention(bf16(qq), bf16(kk), 2, 1, causal=False)       # scale 1/4: logit 10 at key 3
+    p3 = np.exp(10.0) / (np.exp(10.0) + (T - 1))
+    assert np.isclose(s[3], p3, rtol=1e-14) and np.allclose(np.delete(s, 3), (1 - p3) / (T - 1), rtol=1e-12)
+    # causal: queries before token 3 do not see it
+    s = O.token_score_attention(bf16(qq), bf16(kk), 2, 1, causal=True)
+    want3 = sum(np.exp(10.0) / (np.exp(10.0) + q) for q in range(3, T)) / T
+    assert np.isclose(s[3], want3, rtol=1e-14)
+
+
+def test_attention_score_invariants_and_brute_force():
+    rng = np.random.default_rng(6)
+    T, Hh, Hkv, d = 7, 4, 2, 8
+    q = bf16(rng.standard_normal((T, Hh, d)))
+    k = bf16(rng.standard_normal((T, Hkv, d)))
+    for causal in (False, True):
+        s = O.token_score_attention(q, k, Hh, Hkv, causal=causal)
+        assert np.isclose(s.sum(), 1.0, rtol=1e-14)                        # every query hands out one unit
+        # brute force, one probability at a time
+        qf, kf = widen(q), widen(k)
+        ref = np.zeros(T)
+        for h in range(Hh):
+            for i in range(T):
+                keys = range(i + 1) if causal else range(T)
+                lg = {j: float(np.dot(qf[i, h], kf[j, h // 2])) / np.sqrt(d) for j in keys}
+                z = sum(np.exp(v) for v in lg.values())
+                for j, v in lg.items():
+                    ref[j] += np.exp(v) / z / (Hh * T)
+        assert np.allclose(s, ref, rtol=1e-12)
+    # without a mask the score follows the keys when the tokens are permuted (queries are averaged over)
+    perm = rng.permutation(T)
+    s0 = O.token_score_attention(q, k, Hh, Hkv, causal=False)
+    s1 = O.token_score_attention(q[perm], k[perm], Hh, Hkv, causal=False)
+    assert np.allclose(s1, s0[perm], rtol=1e-13)
+    # a common shift of all keys of a head changes every logit of a row alike: softmax unchanged
+    s2 = O.token_score_attention(q, bf16(widen(k) * 2.0), Hh, Hkv, causal=True, scale=0.5 / np.sqrt(d))
+    assert np.allclose(s2, O.token_score_attention(q, k, Hh, Hkv, causal=True), rtol=1e-13)
+
+
+def test_attention_inputs_make_the_heavy_hitters_score_highest():
+    cfg = synth.scaled(synth.CONFIGS["mixtral_prefill"], T=256, k_hh=13, config_id=41)
+    q, k, heavy = synth.attention_inputs(cfg, 8, 2, 64, boost=1.5)
+    assert heavy.size == 13
+    s = O.token_score_attention(q, k, 8, 2, causal=False)
+    assert set(np.argsort(-s)[:13].tolist()) == set(heavy.tolist())

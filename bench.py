@@ -253,6 +253,28 @@ def main():
             "grouped_gemm_frac_mfma_bf16_peak": round(flops / (g_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4) if g_us > 0 else None,
             "kernels_us": {n: round(v[0] / max(v[1], 1) * 1e3, 1) for n, v in pk.items()},
         }
+        # the attention-derived token score of the same 512 tokens (32 query heads, 8 key heads of 128)
+        a_heads, a_kv, a_d = 32, 8, 128
+        aq_np, ak_np, _ = synth.attention_inputs(pcfg, a_heads, a_kv, a_d)
+        aq = torch.from_numpy(aq_np.view(np.int16)).to(dev).view(torch.bfloat16)
+        ak = torch.from_numpy(ak_np.view(np.int16)).to(dev).view(torch.bfloat16)
+        a_ws = torch.empty((int(B.lib.dymoe_attention_workspace_bytes(pcfg.T, a_heads)),), dtype=torch.uint8, device=dev)
+        a_out = torch.empty((pcfg.T,), dtype=torch.float32, device=dev)
+        for _ in range(3):
+            ctx.token_score_attention(aq, ak, causal=True, out=a_out, workspace=a_ws)
+        torch.cuda.synchronize()
+        ctx.timing_enable(["attn_stats", "attn_colsum"])
+        for _ in range(args.prefill_steps):
+            ctx.token_score_attention(aq, ak, causal=True, out=a_out, workspace=a_ws)
+        torch.cuda.synchronize()
+        ak_us = {n: ctx.timing_read(n) for n in ("attn_stats", "attn_colsum")}
+        ctx.timing_enable(())
+        a_us = sum(v[0] / max(v[1], 1) for v in ak_us.values()) * 1e3
+        a_flops = 2 * 2.0 * pcfg.T * (pcfg.T + 32) / 2 * a_d * a_heads     # two passes over the causal half (32-token tiles)
+        out["prefill_512"]["attention_token_score"] = {
+            "workload": "512 tokens, 32 query / 8 key heads of 128, causal",
+            "kernels_us": {n: round(v[0] / max(v[1], 1) * 1e3, 1) for n, v in ak_us.items()},
+            "TFLOPs": round(a_flops / (a_us * 1e-6) / 1e12, 1) if a_us > 0 else None}
 
     # ---------------------------------------------------------------- CPU oracle on this host
     if not args.skip_cpu:

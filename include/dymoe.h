@@ -142,12 +142,34 @@ int dymoe_route_topk(dymoe_ctx* ctx, const void* x, const void* wg, const float*
 
 /*
  * Activation-norm token score s_t = ||x_t||_2 (fp32).  Stand-in for the
- * attention-derived token importance of paper Sec. 4.2.1 (first equation),
- * which needs an attention block that is outside this layer.
+ * attention-derived token importance of paper Sec. 4.2.1 (first equation)
+ * where no attention block is at hand (see dymoe_token_score_attention).
  * x [T,H] bf16, score [T] fp32.  H multiple of 8.
  */
 int dymoe_token_score_norm(dymoe_ctx* ctx, const void* x, int T, int H, float* score,
                            void* stream);
+
+/*
+ * Attention-derived token score (paper Sec. 4.2.1, first equation):
+ *   s_i = (1/n_heads) sum_h a_i^(h),
+ * with a_i^(h) read as the attention token i RECEIVES in head h, averaged over
+ * the T queries: a_i^(h) = (1/T) sum_q P^(h)[q,i], P^(h) = softmax over keys of
+ * (q_q . k_i) * scale; causal = 1 masks the keys after the query.  The scores
+ * sum to 1.  Feed `score` to dymoe_expert_importance as token_score.
+ * q [T, n_heads, head_dim] bf16, k [T, n_kv_heads, head_dim] bf16 (token-major,
+ * as a fused QKV projection writes them), 16-byte aligned; query head h reads
+ * key head h / (n_heads / n_kv_heads).  scale > 0, or 0 for 1/sqrt(head_dim).
+ * score [T] fp32.  workspace: device, 256-byte aligned, at least
+ * dymoe_attention_workspace_bytes(T, n_heads) bytes (softmax statistics and
+ * per-head sums); owned by the caller, free for reuse when the call's work on
+ * `stream` has completed.  Deterministic (no atomics).
+ * Limits: head_dim 64 or 128 (others: DYMOE_ENOTSUP); n_heads multiple of
+ * n_kv_heads.  T = 0: nothing is read or written.
+ */
+size_t dymoe_attention_workspace_bytes(int T, int n_heads);
+int dymoe_token_score_attention(dymoe_ctx* ctx, const void* q, const void* k, int T, int n_heads,
+                                int n_kv_heads, int head_dim, float scale, int causal, float* score,
+                                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Per-expert importance (paper Sec. 4.2).
@@ -328,9 +350,9 @@ int dymoe_stream_copy(dymoe_ctx* ctx, const void* src, void* dst, size_t bytes, 
  * Per-kernel timing (diagnostic; the paper reports only end-to-end latency,
  * Sec. 6.1 "Key Metrics", so these serve the roofline accounting).
  * dymoe_timing_enable: launches of the kernels whose bit is set in kernel_mask
- * (bit i = kernel id i, ids 0..13 in the order route, token_norm, importance,
+ * (bit i = kernel id i, ids 0..15 in the order route, token_norm, importance,
  * assign, quantize, gemv_phase1, gemv_phase2, gemv_combine, plan, gemm1, gemm2,
- * gemm_combine, stream_copy, decode_front) carry a start and a stop HIP event on the dispatch itself, so
+ * gemm_combine, stream_copy, decode_front, attn_stats, attn_colsum) carry a start and a stop HIP event on the dispatch itself, so
  * the interval is the kernel's execution time on the launch stream; 0 switches
  * timing off.  Either way, records not yet read are dropped.
  * dymoe_timing_read: waits for the recorded launches of `kernel`, drops their records and returns

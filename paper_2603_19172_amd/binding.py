@@ -31,7 +31,8 @@ LAYOUT_ROWMAJOR, LAYOUT_TILE = 0, 1
 # every symbol include/dymoe.h declares
 EXPORTS = [
     "dymoe_create", "dymoe_destroy", "dymoe_strerror", "dymoe_workspace_bytes",
-    "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_expert_importance",
+    "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_attention_workspace_bytes",
+    "dymoe_token_score_attention", "dymoe_expert_importance",
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
     "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_moe_ffn_mixed", "dymoe_stream_copy",
     "dymoe_decode_front", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
@@ -40,7 +41,8 @@ EXPORTS = [
 ]
 
 KERNELS = ["route", "token_norm", "importance", "assign", "quantize", "gemv_phase1",
-           "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine", "stream_copy", "decode_front"]
+           "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine", "stream_copy", "decode_front",
+           "attn_stats", "attn_colsum"]
 
 
 class ExpertFmt(C.Structure):
@@ -73,6 +75,10 @@ lib.dymoe_prefetch_release.restype = _i
 lib.dymoe_prefetch_release.argtypes = [_vp, _vp]
 lib.dymoe_residual_rmsnorm.restype = _i
 lib.dymoe_residual_rmsnorm.argtypes = [_vp, _vp, _vp, _i, C.c_float, _i, _i, _vp, _vp]
+lib.dymoe_attention_workspace_bytes.restype = _sz
+lib.dymoe_attention_workspace_bytes.argtypes = [_i, _i]
+lib.dymoe_token_score_attention.restype = _i
+lib.dymoe_token_score_attention.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, C.c_float, _i, _vp, _vp, _sz, _vp]
 lib.dymoe_stream_copy.restype = _i
 lib.dymoe_stream_copy.argtypes = [_vp, _vp, _vp, _sz, _vp]
 lib.dymoe_route_topk.restype = _i
@@ -307,6 +313,21 @@ class Context:
         yd = OUT_BF16 if y.dtype == torch.bfloat16 else OUT_F32
         _check(lib.dymoe_residual_rmsnorm(self._h, _ptr(h, torch.bfloat16), _ptr(y), yd, float(alpha), T, H,
                                           _ptr(out, torch.bfloat16), _stream(stream)), "dymoe_residual_rmsnorm")
+        return out
+
+    def token_score_attention(self, q, k, causal=True, scale=0.0, out=None, workspace=None, stream=None):
+        """q [T, n_heads, d], k [T, n_kv_heads, d] bf16 -> score [T] fp32."""
+        T, n_heads, d = q.shape
+        n_kv = k.shape[1]
+        if out is None:
+            out = torch.empty((T,), dtype=torch.float32, device=q.device)
+        nb = int(lib.dymoe_attention_workspace_bytes(T, n_heads))
+        if workspace is None:
+            workspace = torch.empty((max(nb, 256),), dtype=torch.uint8, device=q.device)
+        _check(lib.dymoe_token_score_attention(self._h, _ptr(q, torch.bfloat16), _ptr(k, torch.bfloat16), T, n_heads,
+                                               n_kv, d, float(scale), 1 if causal else 0, _ptr(out, torch.float32),
+                                               _ptr(workspace, torch.uint8), workspace.numel(), _stream(stream)),
+               "dymoe_token_score_attention")
         return out
 
     def stream_copy(self, src, dst, stream=None):

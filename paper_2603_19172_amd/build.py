@@ -24,7 +24,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, 
 PER_FILE = {"quantize.hip": ["-ffp-contract=off"]}
 
 SOURCES = ["api.hip", "route.hip", "importance.hip", "quantize.hip", "ffn.hip", "ffn_gemv.hip",
-           "ffn_gemm.hip", "prefetch.hip"]
+           "ffn_gemm.hip", "prefetch.hip", "attention.hip"]
 
 
 def _compile(src: str) -> str:

@@ -128,6 +128,8 @@ const char* dymoe_kernel_name(int kernel)
     case DYMOE_K_GEMM_COMBINE: return "gemm_combine_kernel";
     case DYMOE_K_STREAM_COPY: return "stream_copy_kernel";
     case DYMOE_K_DECODE_FRONT: return "decode_front_kernel";
+    case DYMOE_K_ATTN_STATS: return "attn_rowstats_kernel";
+    case DYMOE_K_ATTN_COLSUM: return "attn_colsum_kernel";
     default: return nullptr;
     }
 }

@@ -25,6 +25,8 @@ enum {
     DYMOE_K_GEMM_COMBINE,
     DYMOE_K_STREAM_COPY,
     DYMOE_K_DECODE_FRONT,
+    DYMOE_K_ATTN_STATS,
+    DYMOE_K_ATTN_COLSUM,
     DYMOE_K_COUNT
 };
 

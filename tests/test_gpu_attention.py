@@ -1,0 +1,87 @@
+"""GPU parity of the attention-derived token score (paper Sec. 4.2.1, first
+equation) against the CPU oracle, and its hand-over to the importance step."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dymoe_oracle as O
+from paper_2603_19172_amd import binding as B
+from paper_2603_19172_amd import synth
+from gpu_helpers import DEV
+
+pytestmark = pytest.mark.gpu
+
+# fp32 accumulation of exact bf16 products over d <= 128 terms, v_exp_f32 on arguments of
+# magnitude <= ~40, sums of <= 2048 probabilities: a few 1e-6 relative on every score
+RTOL, ATOL = 2e-5, 1e-9
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.Context(0)
+    yield c
+    c.close()
+
+
+def _dev3(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def _run(ctx, q, k, causal, scale=0.0):
+    s = ctx.token_score_attention(_dev3(q), _dev3(k), causal=causal, scale=scale)
+    torch.cuda.synchronize()
+    return s.cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("T,Hh,Hkv,d", [(16, 2, 2, 64), (77, 4, 2, 128), (1, 2, 1, 64), (33, 3, 3, 64),
+                                        (160, 8, 2, 128), (512, 32, 8, 128)])
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_score_matches_the_oracle(ctx, T, Hh, Hkv, d, causal):
+    cfg = synth.scaled(synth.CONFIGS["mixtral_prefill"], T=T, k_hh=max(1, T // 20), config_id=60 + T)
+    q, k, heavy = synth.attention_inputs(cfg, Hh, Hkv, d, boost=1.0)
+    ref = O.token_score_attention(q, k, Hh, Hkv, causal=causal)
+    got = _run(ctx, q, k, causal)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref) / (np.abs(ref) + ATOL / RTOL)
+    print("T=%d heads=%d/%d d=%d causal=%d: max rel err %.2e, sum %.8f" % (T, Hh, Hkv, d, causal, err.max(), got.sum()))
+    assert np.allclose(got, ref, rtol=RTOL, atol=ATOL)
+    assert abs(got.sum() - 1.0) < 1e-5                      # every query hands out one unit of attention
+
+
+def test_attention_score_explicit_scale_and_determinism(ctx):
+    cfg = synth.scaled(synth.CONFIGS["mixtral_prefill"], T=200, k_hh=10, config_id=71)
+    q, k, _ = synth.attention_inputs(cfg, 4, 4, 64)
+    ref = O.token_score_attention(q, k, 4, 4, causal=True, scale=0.05)
+    a = _run(ctx, q, k, True, scale=0.05)
+    b = _run(ctx, q, k, True, scale=0.05)
+    assert np.allclose(a, ref, rtol=RTOL, atol=ATOL)
+    assert np.array_equal(a, b)                              # fixed summation order, no atomics
+
+
+def test_attention_score_uniform_closed_form(ctx):
+    T, Hh, d = 45, 2, 64
+    k = synth.normal_bf16(3, 9001, (T, Hh, d), 1.0)
+    q = np.zeros((T, Hh, d), np.uint16)
+    got = _run(ctx, q, k, True)
+    harm = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, T + 1))])
+    want = (harm[T] - harm[:T]) / T
+    assert np.allclose(got, want, rtol=1e-6)
+    assert np.allclose(_run(ctx, q, k, False), 1.0 / T, rtol=1e-6)
+
+
+def test_attention_score_feeds_the_importance_step(ctx):
+    """Eq. 1 -> Eq. 2: heavy hitters found by the attention they receive; the expert importance
+    computed from the device's scores equals the oracle's from its own."""
+    cfg = synth.scaled(synth.CONFIGS["mixtral_prefill"], T=256, k_hh=13, config_id=41)
+    q, k, heavy = synth.attention_inputs(cfg, 8, 2, 64, boost=1.5)
+    x, _ = synth.activations(cfg)
+    wg, bias = synth.router(cfg)
+    ridx, _, _, _ = O.route_topk(x, wg, bias, cfg.k)
+    rscore = O.token_score_attention(q, k, 8, 2, causal=False)
+    rimp, rload, rheavy = O.expert_importance_prefill(ridx, rscore, cfg.E, cfg.k_hh)
+    assert set(np.nonzero(rheavy)[0].tolist()) == set(heavy.tolist())
+    score = ctx.token_score_attention(_dev3(q), _dev3(k), causal=False)
+    idx = torch.from_numpy(ridx).to(DEV)
+    imp, load = ctx.expert_importance(B.PHASE_PREFILL, idx, cfg.E, k_hh=cfg.k_hh, token_score=score)
+    torch.cuda.synchronize()
+    assert np.array_equal(imp.cpu().numpy(), rimp) and np.array_equal(load.cpu().numpy(), rload)

@@ -111,6 +111,20 @@ def test_argument_validation_happens_before_any_device_work():
     assert df(None, P, P, None, 1, 256, 8, 2, 1, 3, tcp, tbp, 3, P, P, P, P, P, P, P, None) == B.EINVAL
     assert df(None, P, P, None, 1, 256, 8, 2, 1, 3, tcp, tbp, 0, P, P, None, P, P, P, None, None) == B.ENOCTX  # probs, rank optional
     assert df(None, P, P, None, 1, 256, 8, 2, 1, 3, tcp, tbp, 0, P, P, P, None, P, P, P, None) == B.EINVAL
+    # attention-derived token score
+    ta = lib.dymoe_token_score_attention
+    aw = int(lib.dymoe_attention_workspace_bytes(77, 8))
+    assert aw >= 77 * 8 * 12 and aw % 256 == 0 and lib.dymoe_attention_workspace_bytes(0, 8) == 0
+    assert ta(None, P, P, 77, 8, 2, 128, 0.0, 1, P, P, aw, None) == B.ENOCTX
+    assert ta(None, P, P, 77, 8, 2, 128, 0.0, 1, P, P, aw - 1, None) == B.ENOSPC
+    assert ta(None, P, P, 77, 8, 3, 128, 0.0, 1, P, P, aw, None) == B.EINVAL          # heads not a multiple of kv heads
+    assert ta(None, P, P, 77, 8, 2, 96, 0.0, 1, P, P, aw, None) == B.ENOTSUP
+    assert ta(None, P, P, 77, 8, 2, 100, 0.0, 1, P, P, aw, None) == B.EINVAL
+    assert ta(None, P, P, 77, 8, 2, 128, -1.0, 1, P, P, aw, None) == B.EINVAL
+    assert ta(None, P, P, 77, 8, 2, 128, 0.0, 2, P, P, aw, None) == B.EINVAL
+    assert ta(None, P + 2, P, 77, 8, 2, 128, 0.0, 1, P, P, aw, None) == B.EINVAL
+    assert ta(None, P, P, 77, 8, 2, 128, 0.0, 1, None, P, aw, None) == B.EINVAL
+    assert ta(None, None, None, 0, 8, 2, 128, 0.0, 1, None, None, 0, None) == B.ENOCTX   # T = 0 needs only a context
     # stream copy
     assert lib.dymoe_stream_copy(None, P, 2 * P, 1024, None) == B.ENOCTX
     assert lib.dymoe_stream_copy(None, P, 2 * P, 1000, None) == B.EINVAL

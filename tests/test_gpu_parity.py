@@ -375,6 +375,28 @@ def test_ffn_gemm_ragged_tiles(ctx):
     assert err <= FFN_TOL
 
 
+@pytest.mark.parametrize("loads,fmts", [((160, 129, 33, 8), (4, 2, 4, 2)), ((161, 1, 0, 168), (2, 16, 4, 4)),
+                                        ((320, 5, 150, 140), (4, 4, 8, 16))])
+def test_ffn_gemm_tile_boundaries(ctx, loads, fmts):
+    """Expert loads around the 128-token tile size: full tiles, remainders of 1, 5, 22, 32 and 33 tokens, an
+    expert with no token, in every format."""
+    T = sum(loads)
+    cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=23, T=T, H=256, F=384, E=4, k=1, tier_count=(4,))
+    x, _ = synth.activations(cfg)
+    rng = np.random.default_rng(23)
+    idx = np.repeat(np.arange(4, dtype=np.int32), loads)
+    rng.shuffle(idx)
+    idx = idx.reshape(T, 1)
+    w = (0.5 + rng.random((T, 1))).astype(np.float32)
+    bits_np = np.array(fmts, np.uint8)
+    host, dev, table, keep = build_layer(cfg, bits_np, path=B.PATH_GEMM)
+    ref = oracle_ffn(cfg, x, idx, w, bits_np, host)
+    y = run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM)
+    err = rel_err_per_token(y, ref)
+    print("gemm tile boundaries loads=%s bits=%s err=%.3e" % (loads, fmts, err))
+    assert err <= FFN_TOL
+
+
 def test_ffn_zero_tokens_and_all_skipped(ctx):
     cfg = synth.CONFIGS["tiny"]
     x, _ = synth.activations(cfg)

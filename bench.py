@@ -330,20 +330,25 @@ def main():
         xs = [bf16(synth.activations(synth.scaled(cfg, config_id=200 + s))[0]) for s in range(args.stack_steps)]
         gb = {b: pool.nbytes[b] / 1e9 for b in (16, 4, 2)}
         budget = float(args.stack_budget_gb)
-        # one byte budget, two ways of spending it: bf16 slots that also hold what the device quantiser
-        # writes, or slots of the three formats (a quarter / half / quarter of the bytes)
+        # one byte budget, spent three ways: bf16 slots that also hold what the device quantiser writes;
+        # fixed pools of the three formats (a quarter / half / quarter of the bytes); the library's
+        # byte-budget cache, whose blocks change hands between the formats as the demand shifts
         # the paper's "4/2" mode: t_l Critical experts in 4 bits (cosine depth schedule, lambda = 0.5), the rest in 2
         paper_tiers = [(B.depth_schedule(l, L, 0.5, E), E - B.depth_schedule(l, L, 0.5, E)) for l in range(L)]
         plans = [("bf16", int(budget / (gb[16] + gb[4] + gb[2])), "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
                  ("assigned", {16: int(0.25 * budget / gb[16]), 4: int(0.5 * budget / gb[4]),
                                2: int(0.25 * budget / gb[2])}, "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
+                 ("assigned", "budget", "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
                  ("assigned", {4: int(0.75 * budget / gb[4]), 2: int(0.25 * budget / gb[2])},
-                  "4/2 with the cosine depth schedule", paper_tiers, (4, 2), None)]
+                  "4/2 with the cosine depth schedule", paper_tiers, (4, 2), None),
+                 ("assigned", "budget", "4/2 with the cosine depth schedule", paper_tiers, (4, 2), None)]
         results = []
         for transfer, slots, tier_name, tcount, tbits, flr in plans:
             for prefetch in (False, True):
-                stack = DecodeStack(ctx, H, F, E, k, routers, pool, slots, tcount, tbits,
-                                    floor_bits=flr, prefetch=prefetch, transfer=transfer, alpha=0.125, device=dev)
+                by_budget = slots == "budget"
+                stack = DecodeStack(ctx, H, F, E, k, routers, pool, None if by_budget else slots, tcount, tbits,
+                                    floor_bits=flr, prefetch=prefetch, transfer=transfer, alpha=0.125, device=dev,
+                                    budget_bytes=int(budget * 1e9) if by_budget else None)
                 stack.step(xs[0])                 # warm-up step (fills the slots it can)
                 torch.cuda.synchronize()
                 stack.stats.clear()

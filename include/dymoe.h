@@ -347,6 +347,55 @@ int dymoe_residual_rmsnorm(dymoe_ctx* ctx, const void* h, const void* y, int y_d
 int dymoe_stream_copy(dymoe_ctx* ctx, const void* src, void* dst, size_t bytes, void* stream);
 
 /*
+ * Mixed-precision expert cache with one byte budget (paper Sec. 4.4.2): host-side
+ * bookkeeping for a caller that keeps experts in an arena of device memory.  No
+ * GPU call is made and no device memory is touched; all pointers are host pointers.
+ * Rules: No Duplication (an expert is resident in one format at most), Precision
+ * Promotion (a request above the resident precision loads the higher format and
+ * drops the lower one), Conservative Reuse (a request at or below the resident
+ * precision is a hit and the resident format is used).
+ * dymoe_cache_create: formats format_bits[i] in {2,4,8,16} (distinct), each with
+ *   the bytes one expert takes in it.  The arena is cut into blocks of the
+ *   largest slot size (rounded up to 256 bytes); a block serves one format at a
+ *   time and holds as many of its slots as fit.  DYMOE_ENOSPC: the budget holds
+ *   no block; DYMOE_ENOTSUP: more than DYMOE_CACHE_MAX_EVICT slots per block.
+ * dymoe_cache_request: the expert `key` is wanted at `want_bits`.  On return
+ *   out->offset is the byte offset of its slot in the arena, out->use_bits the
+ *   precision to run it at, out->load_bits the format the caller has to copy
+ *   into the slot (0: nothing), out->evicted[0..n_evicted) the keys that lost
+ *   their slots, out->dropped_offset the slot a promotion freed (else -1).
+ *   Room is taken from a free slot, a free block, or else the least recently
+ *   used of (a) the residents of the requested format and (b) whole blocks of
+ *   other formats (a block is as recent as its most recent resident); keys in
+ *   protect[0..n_protect) are never evicted.  DYMOE_ENOSPC: nothing evictable;
+ *   the cache is then unchanged.
+ * dymoe_cache_lookup: 1 and the resident format / offset, or 0.
+ */
+typedef struct dymoe_cache dymoe_cache;
+#define DYMOE_CACHE_MAX_FORMATS 4
+#define DYMOE_CACHE_MAX_EVICT 16
+#define DYMOE_CACHE_HIT 0
+#define DYMOE_CACHE_MISS 1
+#define DYMOE_CACHE_PROMOTE 2
+typedef struct {
+    int32_t kind;
+    int32_t use_bits;
+    int32_t load_bits;
+    int32_t n_evicted;
+    int64_t offset;
+    int64_t dropped_offset;
+    int64_t evicted[DYMOE_CACHE_MAX_EVICT];
+} dymoe_cache_action;
+int dymoe_cache_create(dymoe_cache** out, size_t budget_bytes, int n_formats, const int32_t* format_bits,
+                       const size_t* slot_bytes);
+void dymoe_cache_destroy(dymoe_cache* cache);
+int dymoe_cache_request(dymoe_cache* cache, int64_t key, int want_bits, const int64_t* protect, int n_protect,
+                        dymoe_cache_action* out);
+int dymoe_cache_lookup(const dymoe_cache* cache, int64_t key, int32_t* bits, int64_t* offset);
+size_t dymoe_cache_block_bytes(const dymoe_cache* cache);
+size_t dymoe_cache_bytes_resident(const dymoe_cache* cache);
+
+/*
  * Per-kernel timing (diagnostic; the paper reports only end-to-end latency,
  * Sec. 6.1 "Key Metrics", so these serve the roofline accounting).
  * dymoe_timing_enable: launches of the kernels whose bit is set in kernel_mask

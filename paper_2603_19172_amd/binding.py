@@ -37,6 +37,8 @@ EXPORTS = [
     "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_moe_ffn_mixed", "dymoe_stream_copy",
     "dymoe_decode_front", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
     "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
+    "dymoe_cache_create", "dymoe_cache_destroy", "dymoe_cache_request", "dymoe_cache_lookup",
+    "dymoe_cache_block_bytes", "dymoe_cache_bytes_resident",
     "dymoe_timing_enable", "dymoe_timing_read", "dymoe_kernel_name",
 ]
 
@@ -53,7 +55,29 @@ class ExpertFmt(C.Structure):
                 ("z8", C.c_void_p * 3)]
 
 
+CACHE_MAX_FORMATS, CACHE_MAX_EVICT = 4, 16
+CACHE_HIT, CACHE_MISS, CACHE_PROMOTE = 0, 1, 2
+
+
+class CacheAction(C.Structure):
+    """Mirror of dymoe_cache_action."""
+    _fields_ = [("kind", C.c_int32), ("use_bits", C.c_int32), ("load_bits", C.c_int32), ("n_evicted", C.c_int32),
+                ("offset", C.c_int64), ("dropped_offset", C.c_int64), ("evicted", C.c_int64 * CACHE_MAX_EVICT)]
+
+
 _vp, _i, _l, _sz, _d = C.c_void_p, C.c_int, C.c_long, C.c_size_t, C.c_double
+lib.dymoe_cache_create.restype = _i
+lib.dymoe_cache_create.argtypes = [C.POINTER(_vp), _sz, _i, _vp, _vp]
+lib.dymoe_cache_destroy.restype = None
+lib.dymoe_cache_destroy.argtypes = [_vp]
+lib.dymoe_cache_request.restype = _i
+lib.dymoe_cache_request.argtypes = [_vp, C.c_int64, _i, _vp, _i, C.POINTER(CacheAction)]
+lib.dymoe_cache_lookup.restype = _i
+lib.dymoe_cache_lookup.argtypes = [_vp, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_int64)]
+lib.dymoe_cache_block_bytes.restype = _sz
+lib.dymoe_cache_block_bytes.argtypes = [_vp]
+lib.dymoe_cache_bytes_resident.restype = _sz
+lib.dymoe_cache_bytes_resident.argtypes = [_vp]
 lib.dymoe_create.restype = _i
 lib.dymoe_create.argtypes = [C.POINTER(_vp), _i]
 lib.dymoe_destroy.restype = None

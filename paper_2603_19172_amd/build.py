@@ -24,11 +24,11 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, 
 PER_FILE = {"quantize.hip": ["-ffp-contract=off"]}
 
 SOURCES = ["api.hip", "route.hip", "importance.hip", "quantize.hip", "ffn.hip", "ffn_gemv.hip",
-           "ffn_gemm.hip", "prefetch.hip", "attention.hip"]
+           "ffn_gemm.hip", "prefetch.hip", "attention.hip", "expert_cache.cpp"]
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     extra = os.environ.get("DYMOE_EXTRA_HIPCC", "").split()      # e.g. -D knobs while tuning
     cmd = ["hipcc", *COMMON, *PER_FILE.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -1,0 +1,269 @@
+// Mixed-precision expert cache with one byte budget (paper Sec. 4.4.2).
+// Host-side bookkeeping only: no GPU call, no device memory.  The caller owns an
+// arena of `budget_bytes` of device memory and copies experts into the slots
+// this cache hands out (as byte offsets into that arena).
+//
+// The three rules of the paper:
+//   No Duplication       an expert is resident in at most one format;
+//   Precision Promotion  a request above the resident precision is a miss: the
+//                        higher format is loaded, the lower one dropped;
+//   Conservative Reuse   a request at or below the resident precision is a hit
+//                        and the resident (higher) format is used.
+//
+// One budget, several slot sizes: the arena is cut into blocks of the largest
+// slot size; a block belongs to one format at a time and holds as many slots of
+// that format as fit.  A request first takes a free slot of its format, then a
+// free block; otherwise it evicts the least recently used of
+//   (a) the unprotected residents of its own format, and
+//   (b) the blocks of other formats none of whose residents is protected, a
+//       block being as recent as its most recently used resident,
+// (a) on equal age.  Evicting a block frees all its slots and hands the block
+// over to the requesting format.
+#include "dymoe.h"
+
+#include <stdint.h>
+
+#include <algorithm>
+#include <new>
+#include <unordered_map>
+#include <vector>
+
+namespace {
+
+struct Resident {
+    int fmt;        // index into the format table
+    int block;
+    int slot;
+    uint64_t tick;  // time of last use
+};
+
+struct Block {
+    int fmt = -1;                 // -1: free
+    int used = 0;
+    std::vector<int64_t> keys;    // per slot: resident key, or kNoKey
+};
+
+constexpr int64_t kNoKey = INT64_MIN;
+
+}  // namespace
+
+struct dymoe_cache {
+    std::vector<int> bits;             // per format, descending precision not required
+    std::vector<size_t> slot_bytes;    // per format, rounded up to 256
+    std::vector<int> slots_per_block;
+    size_t block_bytes = 0;
+    std::vector<Block> blocks;
+    std::unordered_map<int64_t, Resident> where;
+    uint64_t clock = 0;
+
+    int format_of(int b) const
+    {
+        for (size_t i = 0; i < bits.size(); i++)
+            if (bits[i] == b) return (int)i;
+        return -1;
+    }
+    int64_t offset_of(const Resident& r) const
+    {
+        return (int64_t)((size_t)r.block * block_bytes + (size_t)r.slot * slot_bytes[r.fmt]);
+    }
+    void release(int64_t key)
+    {
+        auto it = where.find(key);
+        Block& b = blocks[it->second.block];
+        b.keys[it->second.slot] = kNoKey;
+        if (--b.used == 0) b.fmt = -1;
+        where.erase(it);
+    }
+    // a free slot of format f, or false
+    bool take_free(int f, int& block, int& slot)
+    {
+        for (size_t i = 0; i < blocks.size(); i++) {
+            Block& b = blocks[i];
+            if (b.fmt != f || b.used == slots_per_block[f]) continue;
+            for (int s = 0; s < slots_per_block[f]; s++)
+                if (b.keys[s] == kNoKey) {
+                    block = (int)i;
+                    slot = s;
+                    return true;
+                }
+        }
+        for (size_t i = 0; i < blocks.size(); i++) {
+            Block& b = blocks[i];
+            if (b.fmt != -1) continue;
+            b.fmt = f;
+            b.used = 0;
+            b.keys.assign((size_t)slots_per_block[f], kNoKey);
+            block = (int)i;
+            slot = 0;
+            return true;
+        }
+        return false;
+    }
+};
+
+extern "C" {
+
+int dymoe_cache_create(dymoe_cache** out, size_t budget_bytes, int n_formats, const int32_t* format_bits,
+                       const size_t* slot_bytes)
+{
+    if (!out || !format_bits || !slot_bytes) return DYMOE_EINVAL;
+    if (n_formats < 1 || n_formats > DYMOE_CACHE_MAX_FORMATS) return DYMOE_EINVAL;
+    dymoe_cache* c = new (std::nothrow) dymoe_cache;
+    if (!c) return DYMOE_EHIP;
+    size_t largest = 0;
+    for (int i = 0; i < n_formats; i++) {
+        const int b = format_bits[i];
+        bool dup = false;
+        for (int j = 0; j < i; j++) dup = dup || format_bits[j] == b;
+        if (!(b == 2 || b == 4 || b == 8 || b == 16) || dup || slot_bytes[i] == 0) {
+            delete c;
+            return DYMOE_EINVAL;
+        }
+        c->bits.push_back(b);
+        c->slot_bytes.push_back((slot_bytes[i] + 255) / 256 * 256);
+        largest = std::max(largest, c->slot_bytes.back());
+    }
+    c->block_bytes = largest;
+    for (int i = 0; i < n_formats; i++) {
+        const size_t n = largest / c->slot_bytes[i];
+        if (n > DYMOE_CACHE_MAX_EVICT) {          // an eviction is reported key by key
+            delete c;
+            return DYMOE_ENOTSUP;
+        }
+        c->slots_per_block.push_back((int)n);
+    }
+    const size_t n_blocks = budget_bytes / largest;
+    if (n_blocks == 0) {
+        delete c;
+        return DYMOE_ENOSPC;
+    }
+    c->blocks.resize(n_blocks);
+    *out = c;
+    return DYMOE_OK;
+}
+
+void dymoe_cache_destroy(dymoe_cache* c) { delete c; }
+
+size_t dymoe_cache_block_bytes(const dymoe_cache* c) { return c ? c->block_bytes : 0; }
+
+size_t dymoe_cache_bytes_resident(const dymoe_cache* c)
+{
+    if (!c) return 0;
+    size_t n = 0;
+    for (const auto& kv : c->where) n += c->slot_bytes[kv.second.fmt];
+    return n;
+}
+
+int dymoe_cache_lookup(const dymoe_cache* c, int64_t key, int32_t* bits, int64_t* offset)
+{
+    if (!c) return DYMOE_EINVAL;
+    auto it = c->where.find(key);
+    if (it == c->where.end()) return 0;
+    if (bits) *bits = c->bits[it->second.fmt];
+    if (offset) *offset = c->offset_of(it->second);
+    return 1;
+}
+
+int dymoe_cache_request(dymoe_cache* c, int64_t key, int want_bits, const int64_t* protect, int n_protect,
+                        dymoe_cache_action* out)
+{
+    if (!c || !out || n_protect < 0 || (n_protect > 0 && !protect) || key == kNoKey) return DYMOE_EINVAL;
+    const int f = c->format_of(want_bits);
+    if (f < 0) return DYMOE_EINVAL;
+    out->n_evicted = 0;
+    out->dropped_offset = -1;
+    c->clock++;
+    auto it = c->where.find(key);
+    if (it != c->where.end() && c->bits[it->second.fmt] >= want_bits) {      // Conservative Reuse, or an exact hit
+        it->second.tick = c->clock;
+        out->kind = DYMOE_CACHE_HIT;
+        out->use_bits = c->bits[it->second.fmt];
+        out->load_bits = 0;
+        out->offset = c->offset_of(it->second);
+        return DYMOE_OK;
+    }
+    auto is_protected = [&](int64_t k) {
+        for (int i = 0; i < n_protect; i++)
+            if (protect[i] == k) return true;
+        return false;
+    };
+    int block = -1, slot = -1;
+    const bool promote = it != c->where.end();
+    // Room is found before anything is changed, so that a request that cannot be served leaves the cache as it was.
+    if (!c->take_free(f, block, slot)) {
+        // (a) least recently used unprotected resident of the requested format
+        int64_t own = kNoKey;
+        uint64_t own_tick = UINT64_MAX;
+        for (const auto& kv : c->where)
+            if (kv.second.fmt == f && kv.first != key && kv.second.tick < own_tick && !is_protected(kv.first)) {
+                own = kv.first;
+                own_tick = kv.second.tick;
+            }
+        // (b) least recently used block of another format without a protected resident (nor the expert being promoted:
+        //     its slot is released below, by the promotion itself)
+        int other = -1;
+        uint64_t other_tick = UINT64_MAX;
+        for (size_t i = 0; i < c->blocks.size(); i++) {
+            const Block& b = c->blocks[i];
+            if (b.fmt < 0 || b.fmt == f) continue;
+            uint64_t newest = 0;
+            bool ok = true;
+            for (int64_t k : b.keys) {
+                if (k == kNoKey) continue;
+                if (k != key && is_protected(k)) ok = false;
+                if (k != key) newest = std::max(newest, c->where[k].tick);
+            }
+            if (ok && newest < other_tick) {
+                other = (int)i;
+                other_tick = newest;
+            }
+        }
+        if (own == kNoKey && other < 0) return DYMOE_ENOSPC;
+        if (own != kNoKey && own_tick <= other_tick) {
+            const Resident r = c->where[own];
+            out->evicted[out->n_evicted++] = own;
+            c->release(own);
+            block = r.block;
+            slot = r.slot;
+            Block& b = c->blocks[block];          // release() frees a block that became empty: claim it back
+            if (b.fmt == -1) {
+                b.fmt = f;
+                b.keys.assign((size_t)c->slots_per_block[f], kNoKey);
+            }
+        } else {
+            const std::vector<int64_t> keys = c->blocks[other].keys;
+            for (int64_t k : keys) {
+                if (k == kNoKey) continue;
+                if (k == key) {                   // the lower format of the expert being promoted
+                    out->dropped_offset = c->offset_of(c->where[k]);
+                    c->release(k);
+                    continue;
+                }
+                out->evicted[out->n_evicted++] = k;
+                c->release(k);
+            }
+            Block& b = c->blocks[other];
+            b.fmt = f;
+            b.used = 0;
+            b.keys.assign((size_t)c->slots_per_block[f], kNoKey);
+            block = other;
+            slot = 0;
+        }
+    }
+    if (promote && c->where.count(key)) {                                    // Precision Promotion: the lower format goes
+        out->dropped_offset = c->offset_of(c->where[key]);
+        c->release(key);                          // (a slot of another format, hence of another block than the new one)
+    }
+    Block& b = c->blocks[block];
+    b.keys[slot] = key;
+    b.used++;
+    Resident r{f, block, slot, c->clock};
+    c->where[key] = r;
+    out->kind = promote ? DYMOE_CACHE_PROMOTE : DYMOE_CACHE_MISS;
+    out->use_bits = want_bits;
+    out->load_bits = want_bits;
+    out->offset = c->offset_of(r);
+    return DYMOE_OK;
+}
+
+}  // extern "C"

@@ -27,7 +27,7 @@ import ctypes as C
 import torch
 
 from . import binding as B
-from .cache import FORMATS, MixedPrecisionCache
+from .cache import FORMATS, ByteBudgetCache, MixedPrecisionCache
 from .layer import MoELayer
 
 FMT_BYTES = C.sizeof(B.ExpertFmt)
@@ -102,26 +102,45 @@ class _Slot:
     slot also carries a buffer for each of `quant_formats`, which the device
     quantiser writes ("bf16" transfer mode)."""
 
-    def __init__(self, H, F, fmt_bits, device, quant_formats):
+    def __init__(self, H, F, fmt_bits, device, quant_formats, mem=None):
+        """mem: None (the slot allocates its buffers) or a uint8 view of the slot's bytes in an arena."""
         fmt = B.ExpertFmt()
         self.fmt_bits = fmt_bits
+        pos = 0
+
+        def take(nbytes):
+            nonlocal pos
+            if mem is None:
+                return torch.empty((nbytes,), dtype=torch.uint8, device=device)
+            view = mem[pos:pos + nbytes]
+            pos += (nbytes + 255) // 256 * 256
+            return view
+
         if fmt_bits == 16:
-            self.buf = torch.empty((6 * H * F,), dtype=torch.uint8, device=device)
+            self.buf = take(6 * H * F)
             for i in range(3):
                 fmt.w[i] = self.buf.data_ptr() + i * H * F * 2
             self.qbuf = {}
             for b in quant_formats:
                 offs, total = quant_layout(H, F, b)
-                self.qbuf[b] = torch.empty((total,), dtype=torch.uint8, device=device)
+                self.qbuf[b] = take(total)
                 self._point(fmt, b, self.qbuf[b].data_ptr(), offs)
         else:
             offs, total = quant_layout(H, F, fmt_bits)
-            self.buf = torch.empty((total,), dtype=torch.uint8, device=device)
+            self.buf = take(total)
             self._point(fmt, fmt_bits, self.buf.data_ptr(), offs)
         self.fmt = torch.frombuffer(bytearray(bytes(fmt)), dtype=torch.uint8).pin_memory()
         self.copy_event = None   # event of a copy not yet waited for on the compute stream
         self.last_use = None     # torch event: the compute stream has finished reading the slot
         self.prefetched = False  # filled ahead of time and not used yet
+
+    @staticmethod
+    def nbytes(H, F, fmt_bits, quant_formats):
+        """Bytes of a slot of this format inside an arena (pieces aligned to 256 bytes)."""
+        r = lambda n: (n + 255) // 256 * 256
+        if fmt_bits == 16:
+            return r(6 * H * F) + sum(r(quant_layout(H, F, b)[1]) for b in quant_formats)
+        return r(quant_layout(H, F, fmt_bits)[1])
 
     @staticmethod
     def _point(fmt, b, base, offs):
@@ -134,13 +153,16 @@ class _Slot:
 
 class ExpertStack:
     def __init__(self, ctx, T, phase, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
-                 prefetch=True, transfer="bf16", alpha=0.125, k_hh=0, predict_t=None, device="cuda:0"):
+                 prefetch=True, transfer="bf16", alpha=0.125, k_hh=0, predict_t=None, device="cuda:0",
+                 budget_bytes=None):
         """T tokens per step; phase "decode" (gate-score importance, Eq. 3; the k experts the next layer is
         predicted to route the token to are fetched ahead, Eq. 8 with t = k) or "prefill" (heavy-hitter
         importance over the k_hh highest-norm tokens, Eq. 2; the predict_t experts of highest predicted
         token frequency are fetched ahead, Eq. 7).
         routers: list over layers of wg [E,H] bf16 device tensors.  slots: number of bf16 slots
         (transfer="bf16") or {16: n, 8: n, 4: n, 2: n} (transfer="assigned"; formats left out get none).
+        budget_bytes: instead of `slots`, one byte budget of device memory shared by the formats (the
+        library's dymoe_cache_*).
         floor_bits: per-layer floor of the assignment (list) or None.  tier_count: one tuple for every
         layer, or a list of per-layer tuples (e.g. (t_l, E - t_l) from the depth schedule of Sec. 4.3)."""
         if transfer not in ("bf16", "assigned"):
@@ -153,15 +175,28 @@ class ExpertStack:
         self.floor = list(floor_bits) if floor_bits is not None else [0] * self.L
         self.prefetch, self.alpha, self.dev = prefetch, alpha, device
         self.predict_t = int(predict_t) if predict_t is not None else k
-        counts = {16: int(slots)} if transfer == "bf16" else {b: int(slots.get(b, 0)) for b in FORMATS}
         # a layer's experts are all resident while it runs, next to the ones fetched ahead
         need = min(E, T * k) + (self.predict_t if prefetch else 0)
-        if any(0 < n < need for n in counts.values()) or not any(counts.values()):
-            raise ValueError("every configured pool needs at least %d slots" % need)
-        self.cache = MixedPrecisionCache(counts)
         # formats the device quantiser may be asked for when bf16 weights are moved
         made = sorted({int(b) for b in list(tier_bits) + self.floor if int(b) in (8, 4, 2)}) if transfer == "bf16" else []
-        self.slots = {(b, i): _Slot(H, F, b, device, made) for b, n in counts.items() for i in range(n)}
+        self._slot_args = (H, F, device, made)
+        if budget_bytes is None:
+            counts = {16: int(slots)} if transfer == "bf16" else {b: int(slots.get(b, 0)) for b in FORMATS}
+            if any(0 < n < need for n in counts.values()) or not any(counts.values()):
+                raise ValueError("every configured pool needs at least %d slots" % need)
+            self.cache = MixedPrecisionCache(counts)
+            self.arena = None
+            self.slots = {(b, i): _Slot(H, F, b, device, made) for b, n in counts.items() for i in range(n)}
+        else:
+            held = (16,) if transfer == "bf16" else tuple(b for b in FORMATS if b in pool.nbytes)
+            sizes = {b: _Slot.nbytes(H, F, b, made) for b in held}
+            self.cache = ByteBudgetCache(int(budget_bytes), sizes)
+            n_blocks = int(budget_bytes) // self.cache.block_bytes
+            if n_blocks * (self.cache.block_bytes // max(sizes.values())) < need:
+                raise ValueError("the budget holds fewer than %d experts of the largest format" % need)
+            self.arena = torch.empty((n_blocks * self.cache.block_bytes,), dtype=torch.uint8, device=device)
+            self._slot_bytes = sizes
+            self.slots = {}                         # (format, offset) -> _Slot, made when first handed out
         per_layer = isinstance(tier_count[0], (tuple, list))
         self.tiers = [tuple(tc) for tc in tier_count] if per_layer else [tuple(tier_count)] * self.L
         if len(self.tiers) != self.L or any(len(tc) != len(tier_bits) for tc in self.tiers):
@@ -185,9 +220,30 @@ class ExpertStack:
         self.trace = []     # per step and layer: (experts, assigned bits, bits they were run at)
         self.predictions = []   # per step and layer (but the last): experts fetched ahead for the next layer
 
+    def _slot(self, name):
+        slot = self.slots.get(name)
+        if slot is None:        # byte-budget mode: a view of the arena
+            bits, off = name
+            H, F, device, made = self._slot_args
+            slot = self.slots[name] = _Slot(H, F, bits, device, made, mem=self.arena[off:off + self._slot_bytes[bits]])
+        return slot
+
     def _fill(self, act, key, ahead):
         """Copy the format `act.load_bits` of expert `key` into the slot the cache chose, on the side stream."""
-        slot = self.slots[act.slot]
+        slot = self._slot(act.slot)
+        for name in act.freed:                    # slots given up whose memory the new one may overlap
+            old = self.slots.get(name)
+            if old is None:
+                continue
+            if old.prefetched:
+                self.stats["prefetch_wasted"] += 1
+                old.prefetched = False
+            if old.copy_event is not None:        # same stream: the old copy is ordered before the new one
+                self.ctx.prefetch_release(old.copy_event)
+                old.copy_event = None
+            if old.last_use is not None:
+                self.side.wait_event(old.last_use)
+                old.last_use = None
         if slot.prefetched:
             self.stats["prefetch_wasted"] += 1
         if slot.copy_event is not None:           # an unused earlier copy: same stream, ordered before this one
@@ -263,7 +319,7 @@ class ExpertStack:
                 key = (l, e)
                 act = self.cache.request(key, want(b), protect)
                 protect.add(act.slot)
-                slot = self.slots[act.slot]
+                slot = self._slot(act.slot)
                 if act.load_bits:
                     self._fill(act, key, ahead=False)
                     self.stats[act.kind] += 1
@@ -322,7 +378,7 @@ class ExpertStack:
             done = torch.cuda.Event()
             done.record(cs)
             for e, b in need:
-                self.slots[self.cache.resident((l, e))].last_use = done
+                self._slot(self.cache.resident((l, e))).last_use = done
             h = nxt
         self.trace.append(step_trace)
         self.predictions.append(step_pred)
@@ -341,9 +397,10 @@ class DecodeStack(ExpertStack):
     """One token per step (Sec. 4.2.2 importance, Eq. 8 prefetch)."""
 
     def __init__(self, ctx, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
-                 prefetch=True, transfer="bf16", alpha=0.125, device="cuda:0"):
+                 prefetch=True, transfer="bf16", alpha=0.125, device="cuda:0", budget_bytes=None):
         super().__init__(ctx, 1, "decode", H, F, E, k, routers, pool, slots, tier_count, tier_bits,
-                         floor_bits=floor_bits, prefetch=prefetch, transfer=transfer, alpha=alpha, device=device)
+                         floor_bits=floor_bits, prefetch=prefetch, transfer=transfer, alpha=alpha, device=device,
+                         budget_bytes=budget_bytes)
 
 
 class PrefillStack(ExpertStack):
@@ -351,7 +408,8 @@ class PrefillStack(ExpertStack):
     the predict_t most frequently predicted experts)."""
 
     def __init__(self, ctx, T, H, F, E, k, k_hh, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
-                 prefetch=True, predict_t=None, transfer="bf16", alpha=0.125, device="cuda:0"):
+                 prefetch=True, predict_t=None, transfer="bf16", alpha=0.125, device="cuda:0", budget_bytes=None):
         super().__init__(ctx, T, "prefill", H, F, E, k, routers, pool, slots, tier_count, tier_bits,
                          floor_bits=floor_bits, prefetch=prefetch, transfer=transfer, alpha=alpha, k_hh=k_hh,
-                         predict_t=predict_t if predict_t is not None else min(E, max(k, E // 2)), device=device)
+                         predict_t=predict_t if predict_t is not None else min(E, max(k, E // 2)), device=device,
+                         budget_bytes=budget_bytes)

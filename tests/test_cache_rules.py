@@ -15,8 +15,9 @@ def run(cache, script):
         # No Duplication: after any request every expert is resident exactly once
         locs = list(cache.where.values())
         assert len(locs) == len(set(locs))
-        held = [(b, i) for b in cache.pool for i, k in cache.pool[b].items() if k is not None]
-        assert sorted(held) == sorted(locs)
+        if hasattr(cache, "pool"):
+            held = [(b, i) for b in cache.pool for i, k in cache.pool[b].items() if k is not None]
+            assert sorted(held) == sorted(locs)
 
 
 def test_exact_hits_and_lru_eviction_within_a_pool():
@@ -90,3 +91,118 @@ def test_four_formats_form_one_ladder():
         ("a", 8, "hit", 16, None),
     ])
     assert c.resident("b") == (8, 0) and c.resident("a") == (16, 0)
+
+
+# ------------------------------------------------------------------ one byte budget (dymoe_cache_*)
+
+from paper_2603_19172_amd.cache import ByteBudgetCache
+
+MB = 1 << 20
+SIZES = {16: 352 * MB, 4: 99 * MB, 2: 55 * MB}      # a Mixtral expert: 1, 3 and 6 slots per 352 MB block
+
+
+def _consistent(c):
+    """No Duplication, and no two experts in one slot."""
+    locs = list(c.where.values())
+    assert len(locs) == len(set(locs))
+    assert c.bytes_resident() == sum(-(-SIZES[b] // 256) * 256 for b, _ in locs)
+    for (b, off) in locs:
+        assert off % 256 == 0 and off + SIZES[b] <= c.n_blocks * c.block_bytes
+
+
+def _cache(n_blocks):
+    c = ByteBudgetCache(n_blocks * 352 * MB + 1000, SIZES)
+    c.n_blocks = n_blocks
+    assert c.block_bytes == 352 * MB
+    return c
+
+
+def test_budget_cache_fills_blocks_format_by_format():
+    c = _cache(2)
+    a = c.request("a", 16)
+    assert (a.kind, a.slot, a.load_bits, a.evicted) == ("miss", (16, 0), 16, None)
+    offs = [c.request("q%d" % i, 4).slot[1] for i in range(3)]
+    assert offs == [352 * MB + i * 99 * MB for i in range(3)]         # three int4 experts share the second block
+    _consistent(c)
+    # both blocks are taken: a fourth int4 expert evicts the least recently used int4 one, not the newer bf16 block...
+    c.request("a", 16)
+    x = c.request("q3", 4)
+    assert x.kind == "miss" and x.evicted == ["q0"] and x.slot == (4, 352 * MB)
+    # ...and an int2 expert takes over the least recently used block as a whole (here the bf16 one is older)
+    c.request("q1", 4); c.request("q2", 4); c.request("q3", 4)
+    y = c.request("t0", 2)
+    assert y.evicted == ["a"] and y.slot == (2, 0)
+    assert [c.request("t%d" % i, 2).slot[1] for i in range(1, 6)] == [i * 55 * MB for i in range(1, 6)]
+    _consistent(c)
+    # a bf16 expert needs a whole block: the int4 block is the older one now and goes with all three residents
+    z = c.request("b", 16)
+    assert sorted(z.evicted) == ["q1", "q2", "q3"] and z.slot == (16, 352 * MB)
+    _consistent(c)
+
+
+def test_budget_cache_rules_and_protection():
+    c = _cache(2)
+    run(c, [
+        ("a", 4, "miss", 4, None),
+        ("a", 2, "hit", 4, None),          # Conservative Reuse
+        ("a", 16, "promote", 16, None),    # Precision Promotion into the free block; the int4 copy is dropped
+        ("a", 4, "hit", 16, None),
+    ])
+    assert c.resident("a") == (16, 352 * MB) and len(c.where) == 1
+    r = c.request("b", 2)
+    assert r.slot == (2, 0)                # the block the dropped int4 copy left
+    # protected experts stay: with both blocks protected nothing can make room for bf16
+    with pytest.raises(RuntimeError):
+        c.request("c", 16, protect=[c.resident("a"), c.resident("b")])
+    assert c.resident("a") == (16, 352 * MB) and c.resident("b") == (2, 0)       # unchanged
+    r = c.request("c", 16, protect=[c.resident("a")])
+    assert r.evicted == ["b"] and r.slot == (16, 0)
+    # promotion when the only room is the block the lower format itself sits in
+    d = _cache(1)
+    d.request("x", 2)
+    p = d.request("x", 16)
+    assert (p.kind, p.slot, p.dropped, p.evicted) == ("promote", (16, 0), (2, 0), None)
+    _consistent(d)
+
+
+def test_budget_cache_random_walk_keeps_its_invariants():
+    import random
+    rnd = random.Random(7)
+    c = _cache(3)
+    for step in range(3000):
+        key = rnd.randrange(40)
+        want = rnd.choice((16, 4, 4, 2, 2, 2))
+        before = c.resident(key)
+        a = c.request(key, want)
+        if before is not None and before[0] >= want:
+            assert a.kind == "hit" and a.slot == before and a.use_bits == before[0] and a.load_bits == 0
+        else:
+            assert a.kind == ("promote" if before is not None else "miss")
+            assert a.use_bits == want and a.load_bits == want and a.slot[0] == want
+            assert (a.dropped == before) if before is not None else a.dropped is None
+        assert c.resident(key) == a.slot
+        for k in a.evicted or ():
+            assert c.resident(k) is None and k != key
+        _consistent(c)
+    assert c.bytes_resident() <= 3 * 352 * MB
+
+
+def test_budget_cache_rejects_bad_arguments():
+    from paper_2603_19172_amd import binding as B
+    import ctypes as C
+    h = C.c_void_p()
+    fb = (C.c_int32 * 2)(16, 4)
+    sb = (C.c_size_t * 2)(1000, 100)
+    cr = B.lib.dymoe_cache_create
+    assert cr(C.byref(h), 999, 2, C.cast(fb, C.c_void_p), C.cast(sb, C.c_void_p)) == B.ENOSPC
+    assert cr(C.byref(h), 10000, 0, C.cast(fb, C.c_void_p), C.cast(sb, C.c_void_p)) == B.EINVAL
+    assert cr(C.byref(h), 10000, 2, C.cast((C.c_int32 * 2)(16, 16), C.c_void_p), C.cast(sb, C.c_void_p)) == B.EINVAL
+    assert cr(C.byref(h), 10000, 2, C.cast((C.c_int32 * 2)(16, 3), C.c_void_p), C.cast(sb, C.c_void_p)) == B.EINVAL
+    assert cr(C.byref(h), 1 << 20, 2, C.cast(fb, C.c_void_p), C.cast((C.c_size_t * 2)(65536, 256), C.c_void_p)) == B.ENOTSUP
+    assert cr(C.byref(h), 10000, 2, C.cast(fb, C.c_void_p), C.cast(sb, C.c_void_p)) == B.OK
+    act = B.CacheAction()
+    assert B.lib.dymoe_cache_request(h, 1, 8, None, 0, C.byref(act)) == B.EINVAL       # not a configured format
+    assert B.lib.dymoe_cache_request(h, 1, 4, None, 1, C.byref(act)) == B.EINVAL
+    assert B.lib.dymoe_cache_request(h, 1, 4, None, 0, C.byref(act)) == B.OK and act.kind == B.CACHE_MISS
+    assert B.lib.dymoe_cache_lookup(h, 1, None, None) == 1 and B.lib.dymoe_cache_lookup(h, 2, None, None) == 0
+    B.lib.dymoe_cache_destroy(h)

@@ -66,7 +66,7 @@ TIERS3 = ((1, 3, 4), (16, 4, 2))
 TIERS4 = ((1, 2, 2, 3), (16, 8, 4, 2))
 
 
-def _small_stack(ctx, L, slots, prefetch, seed0, transfer="bf16", pool=None, tiers=TIERS3):
+def _small_stack(ctx, L, slots, prefetch, seed0, transfer="bf16", pool=None, tiers=TIERS3, budget_bytes=None):
     H, F, E, k = 256, 512, 8, 2
     cfgs = [synth.scaled(synth.CONFIGS["tiny"], T=1, phase="decode", config_id=seed0 + l) for l in range(L)]
     routers_np = [synth.router(c)[0] for c in cfgs]
@@ -79,7 +79,8 @@ def _small_stack(ctx, L, slots, prefetch, seed0, transfer="bf16", pool=None, tie
             pool.add_quantised(ctx, DEV, formats=[b for b in tiers[1] if b != 16])
     floor = [4] + [0] * (L - 2) + [4]
     stack = DecodeStack(ctx, H, F, E, k, [to_bf16(r) for r in routers_np], pool, slots, tiers[0], tiers[1],
-                        floor_bits=floor, prefetch=prefetch, transfer=transfer, alpha=0.25, device=DEV)
+                        floor_bits=floor, prefetch=prefetch, transfer=transfer, alpha=0.25, device=DEV,
+                        budget_bytes=budget_bytes)
     expert_matrices = lambda l, e: mats[pool.entry(l, e)]
     return stack, routers_np, expert_matrices, floor, cfgs[0]
 
@@ -280,3 +281,33 @@ def test_prefill_stack_moving_the_assigned_format_in_tile_layout(ctx):
         for (ex, assigned, used) in step:
             assert all(u >= a for a, u in zip(assigned, used))
     _check_prefill_against_oracle(outs, stack, routers_np, expert_matrices, floor, k_hh, 4)
+
+
+@pytest.mark.parametrize("transfer", ["assigned", "bf16"])
+def test_stack_with_one_byte_budget_shared_by_the_formats(ctx, transfer):
+    """The library's byte-budget cache: blocks of the bf16 size change hands between the formats as the
+    demand shifts, slots are views of one arena, and a slot that takes over the memory of evicted experts
+    waits for their last use.  Results against the oracle as in the fixed-pool tests."""
+    L, steps = 4, 8
+    bf16_bytes = 6 * 256 * 512
+    budget = (5 if transfer == "assigned" else 6) * (bf16_bytes + 400 * 1024)     # few blocks: evictions all the time
+    stack, routers_np, expert_matrices, floor, cfg0 = _small_stack(ctx, L, None, True, 1500, transfer=transfer,
+                                                                   budget_bytes=budget)
+    outs = []
+    for s in range(steps):
+        x, _ = synth.activations(synth.scaled(cfg0, config_id=1600 + (s % 4)))
+        outs.append((x, stack.step(to_bf16(x)).clone()))
+    stack.close()
+    st = stack.stats
+    assert _uses(st) == L * 2 * steps
+    assert stack.cache.bytes_resident() <= stack.arena.numel()
+    # every resident expert sits in its own, non-overlapping piece of the arena
+    spans = sorted((off, off + stack._slot_bytes[b]) for (b, off) in stack.cache.where.values())
+    assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:])) and spans[-1][1] <= stack.arena.numel()
+    if transfer == "assigned":
+        assert st["copies_4"] + st["copies_2"] > 0
+        assert len({b for (b, _) in stack.slots}) >= 2                  # blocks served more than one format
+    for step in stack.trace:
+        for (ex, assigned, used) in step:
+            assert all(u >= a for a, u in zip(assigned, used))
+    _check_against_oracle(outs, stack.trace, routers_np, expert_matrices, floor)

@@ -156,6 +156,44 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// Reductions over the 64 lanes through the data-parallel primitives (no LDS
+// crossbar), returned in every lane.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_get(float v)
+{
+    // lanes whose row is masked out, or whose source lane does not exist, read 0
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, true));
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_get_or_self(float v)
+{
+    // lanes whose row is masked out, or whose source lane does not exist, read their own value
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+    v += dpp_get<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v += dpp_get<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v += dpp_get<0x141, 0xF>(v);   // row_half_mirror
+    v += dpp_get<0x140, 0xF>(v);   // row_mirror: every lane of a row holds the row's sum
+    v += dpp_get<0x142, 0xA>(v);   // row_bcast15 into rows 1 and 3
+    v += dpp_get<0x143, 0xC>(v);   // row_bcast31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+__device__ __forceinline__ float wave_max_dpp(float v)
+{
+    v = fmaxf(v, dpp_get_or_self<0xB1, 0xF>(v));
+    v = fmaxf(v, dpp_get_or_self<0x4E, 0xF>(v));
+    v = fmaxf(v, dpp_get_or_self<0x141, 0xF>(v));
+    v = fmaxf(v, dpp_get_or_self<0x140, 0xF>(v));
+    v = fmaxf(v, dpp_get_or_self<0x142, 0xA>(v));
+    v = fmaxf(v, dpp_get_or_self<0x143, 0xC>(v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 __device__ __forceinline__ float wave_max(float v)
 {
 #pragma unroll

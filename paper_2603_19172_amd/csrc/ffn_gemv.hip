@@ -32,27 +32,6 @@ namespace dymoe {
 constexpr int kGvThreads = 256;
 constexpr int kGvWaves = kGvThreads / kWave;
 
-// ------------------------------------------------------------------ reductions
-
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_get(float v)
-{
-    // lanes whose row is masked out, or whose source lane does not exist, read 0
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, true));
-}
-
-// sum over the 64 lanes, returned in every lane
-__device__ __forceinline__ float wave_sum_dpp(float v)
-{
-    v += dpp_get<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
-    v += dpp_get<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
-    v += dpp_get<0x141, 0xF>(v);   // row_half_mirror
-    v += dpp_get<0x140, 0xF>(v);   // row_mirror: every lane of a row holds the row's sum
-    v += dpp_get<0x142, 0xA>(v);   // row_bcast15 into rows 1 and 3
-    v += dpp_get<0x143, 0xC>(v);   // row_bcast31 into rows 2 and 3
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
-}
-
 // ------------------------------------------------------------------ activations
 
 // 32 activations of one lane (quantised layouts), as fp16 pairs ordered for

@@ -63,60 +63,128 @@ __device__ __forceinline__ void route_logits(const uint16_t* __restrict__ x,
     }
 }
 
-// Softmax and top-k of one token by one wavefront, from its logits in LDS (lg is
-// consumed).  A wavefront only touches its own LDS rows here; LDS operations of
-// one wavefront complete in order, so a wavefront-scope fence is all that the
-// lane-to-lane hand-offs need.  prob_sum (LDS, may be null): prob_sum[e] += p[e];
-// load_cnt (LDS, may be null): load_cnt[e] += 1 for the selected experts.
+// Softmax and top-k of TB tokens by one wavefront, from their logits in LDS.
+// Lane l keeps the logits of experts l, l + 64, ... of every token in registers
+// (NC per token, NC * 64 >= E); the k rounds of arg-max then run on registers
+// alone: the largest remaining logit through the data-parallel primitives, the
+// lowest expert index that holds it through a ballot, and the owner retires
+// the entry.  The TB tokens are independent chains of the same arithmetic,
+// written side by side so that their latencies overlap; every token's result
+// is what TB = 1 gives.
+// t[b] < 0: token b is padding (computed, nothing written to global memory).
+// selp[b]: k floats of LDS scratch per token.  prob_sum (LDS, may be null):
+// prob_sum[e] += p[e]; load_cnt (LDS, may be null): load_cnt[e] += 1 for the
+// selected experts.
+template <int TB, int NC>
+__device__ __forceinline__ void route_select_regs(float* const (&lg)[TB], float* const (&selp)[TB],
+                                                  const int (&t)[TB], int E, int k, int renorm,
+                                                  int32_t* __restrict__ idx, float* __restrict__ w,
+                                                  float* __restrict__ probs, float* prob_sum,
+                                                  int32_t* load_cnt)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    float v[TB][NC];
+    float mx[TB], den[TB], rden[TB], sel_sum[TB];
+#pragma unroll
+    for (int b = 0; b < TB; b++) {
+        mx[b] = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < NC; c++) {
+            const int e = c * kWave + lane;
+            v[b][c] = (e < E) ? lg[b][e] : -INFINITY;
+            mx[b] = fmaxf(mx[b], v[b][c]);
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < TB; b++) {
+        mx[b] = wave_max_dpp(mx[b]);
+        den[b] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NC; c++)
+            if (c * kWave + lane < E) den[b] += expf(v[b][c] - mx[b]);
+    }
+#pragma unroll
+    for (int b = 0; b < TB; b++) {
+        den[b] = wave_sum_dpp(den[b]);
+        rden[b] = 1.0f / den[b];
+        sel_sum[b] = 0.0f;
+    }
+    if (probs || prob_sum) {
+#pragma unroll
+        for (int b = 0; b < TB; b++)
+#pragma unroll
+            for (int c = 0; c < NC; c++) {
+                const int e = c * kWave + lane;
+                if (e < E && t[b] >= 0) {
+                    const float p = expf(v[b][c] - mx[b]) * rden[b];
+                    if (probs) probs[(size_t)t[b] * E + e] = p;
+                    if (prob_sum) prob_sum[e] += p;
+                }
+            }
+    }
+    for (int j = 0; j < k; j++) {
+#pragma unroll
+        for (int b = 0; b < TB; b++) {
+            // the largest remaining logit, then the lowest expert index that holds it
+            float bv = v[b][0];
+#pragma unroll
+            for (int c = 1; c < NC; c++) bv = fmaxf(bv, v[b][c]);
+            bv = wave_max_dpp(bv);
+            int bi = -1;
+#pragma unroll
+            for (int c = 0; c < NC; c++) {
+                const unsigned long long hit = __ballot(c * kWave + lane < E && v[b][c] == bv);
+                if (bi < 0 && hit) bi = c * kWave + __ffsll((long long)hit) - 1;
+            }
+            const float p = expf(bv - mx[b]) * rden[b];
+            sel_sum[b] += p;
+            if (lane == 0) {
+                if (t[b] >= 0) idx[(size_t)t[b] * k + j] = bi;
+                selp[b][j] = p;
+                if (load_cnt && t[b] >= 0) load_cnt[bi] += 1;
+            }
+#pragma unroll
+            for (int c = 0; c < NC; c++)
+                if (c * kWave + lane == bi) v[b][c] = -INFINITY;        // the owner retires the entry
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");      // selp: written by lane 0, read by all
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int b = 0; b < TB; b++) {
+        const float scale = renorm ? 1.0f / sel_sum[b] : 1.0f;
+        if (t[b] >= 0)
+            for (int j = lane; j < k; j += kWave) w[(size_t)t[b] * k + j] = selp[b][j] * scale;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// the same with NC chosen for E (E <= DYMOE_MAX_EXPERTS = 1024)
+template <int TB>
+__device__ __forceinline__ void route_select_batch(float* const (&lg)[TB], float* const (&selp)[TB],
+                                                   const int (&t)[TB], int E, int k, int renorm,
+                                                   int32_t* __restrict__ idx, float* __restrict__ w,
+                                                   float* __restrict__ probs, float* prob_sum,
+                                                   int32_t* load_cnt)
+{
+    if (E <= 64) route_select_regs<TB, 1>(lg, selp, t, E, k, renorm, idx, w, probs, prob_sum, load_cnt);
+    else if (E <= 128) route_select_regs<TB, 2>(lg, selp, t, E, k, renorm, idx, w, probs, prob_sum, load_cnt);
+    else if (E <= 256) route_select_regs<TB, 4>(lg, selp, t, E, k, renorm, idx, w, probs, prob_sum, load_cnt);
+    else if (E <= 512) route_select_regs<TB, 8>(lg, selp, t, E, k, renorm, idx, w, probs, prob_sum, load_cnt);
+    else route_select_regs<TB, 16>(lg, selp, t, E, k, renorm, idx, w, probs, prob_sum, load_cnt);
+}
+
+// one token
 __device__ __forceinline__ void route_select(float* lg, float* selp, int t, int E, int k, int renorm,
                                              int32_t* __restrict__ idx, float* __restrict__ w,
                                              float* __restrict__ probs, float* prob_sum,
                                              int32_t* load_cnt)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    float mx = -INFINITY;
-    for (int e = lane; e < E; e += kWave) mx = fmaxf(mx, lg[e]);
-    mx = wave_max(mx);
-    float den = 0.0f;
-    for (int e = lane; e < E; e += kWave) den += expf(lg[e] - mx);
-    den = wave_sum(den);
-    const float rden = 1.0f / den;
-    if (probs || prob_sum)
-        for (int e = lane; e < E; e += kWave) {
-            const float p = expf(lg[e] - mx) * rden;
-            if (probs) probs[(size_t)t * E + e] = p;
-            if (prob_sum) prob_sum[e] += p;
-        }
-    float sel_sum = 0.0f;
-    for (int j = 0; j < k; j++) {
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
-        for (int e = lane; e < E; e += kWave) {
-            const float v = lg[e];
-            if (v > bv || (v == bv && e < bi)) { bv = v; bi = e; }
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const float ov = __shfl_xor(bv, o, kWave);
-            const int oi = __shfl_xor(bi, o, kWave);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-        }
-        // bi is now the same in every lane; the owner retires the entry
-        const float p = expf(bv - mx) * rden;
-        sel_sum += p;
-        if (lane == 0) {
-            idx[(size_t)t * k + j] = bi;
-            selp[j] = p;
-            if (load_cnt) load_cnt[bi] += 1;
-        }
-        if ((bi & (kWave - 1)) == lane) lg[bi] = -INFINITY;
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-    }
-    const float scale = renorm ? 1.0f / sel_sum : 1.0f;
-    for (int j = lane; j < k; j += kWave) w[(size_t)t * k + j] = selp[j] * scale;
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    float* const lgs[1] = {lg};
+    float* const sps[1] = {selp};
+    const int ts[1] = {t};
+    route_select_batch<1>(lgs, sps, ts, E, k, renorm, idx, w, probs, prob_sum, load_cnt);
 }
 
 // A workgroup of NW wavefronts owns TW tokens: logits by all wavefronts, then
@@ -140,6 +208,119 @@ __global__ __launch_bounds__(NW* kWave) void route_kernel(
         const int t = t0 + tw;
         if (t >= T) break;
         route_select(logit + tw * E, selp, t, E, k, renorm, idx, w, probs, nullptr, nullptr);
+    }
+}
+
+// Gating of many tokens against many experts: the logits are a dense contraction
+// [T,H] x [H,E], done on the matrix cores.  A workgroup owns 32 tokens; experts are
+// taken 64 at a time (two 32-expert fragments; the four partial tiles and the logits of
+// all experts then fit in 64 KiB of LDS).  The reduction over H is split
+// between the four wavefronts (every fourth 32-column slice each), so that a
+// wavefront's chain of dependent loads is a quarter as long and the activations
+// are fetched once per workgroup; the four partial tiles meet in LDS.  Tiles are
+// computed transposed (experts down, tokens across): a lane then holds one
+// token's logits of 16 experts.  Softmax and top-k are route_select's.
+// Router rows and activations are read in MFMA operand order straight from
+// global memory (the router is small and stays in L2).
+constexpr int kRmTokens = 32;
+constexpr int kRmExperts = 64;
+constexpr int kRmFrags = kRmExperts / 32;
+constexpr int kRmDepth = 4;      // 32-column slices in flight per wavefront
+constexpr int kRmBatch = 4;      // tokens a wavefront takes through softmax and top-k side by side
+
+__global__ __launch_bounds__(4 * kWave) void route_mfma_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
+    const float* __restrict__ bias, int T, int H, int E, int k, int renorm,
+    int32_t* __restrict__ idx, float* __restrict__ w, float* __restrict__ probs)
+{
+    extern __shared__ float smem[];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int ln = lane & 31, kb = lane >> 5;
+    float* part = smem;                                             // [4 wavefronts][32 tokens][64 experts]
+    float* logit = smem + 4 * kRmTokens * kRmExperts;               // [32 tokens][E]
+    float* selp = logit + (size_t)kRmTokens * E + (size_t)wave * kRmBatch * k;   // [4 wavefronts][kRmBatch][k]
+    const int t0 = blockIdx.x * kRmTokens;
+    // lane (ln, kb): token ln (B operand) and expert ln of each fragment (A operand);
+    // of every 32-column slice the 16 bytes at columns 16 kb and 16 kb + 8
+    const uint16_t* xrow = x + (size_t)min(t0 + ln, T - 1) * H + kb * 16;
+    const int n_slices = H >> 5;
+    for (int e0 = 0; e0 < E; e0 += kRmExperts) {
+        const uint16_t* wrow[kRmFrags];
+#pragma unroll
+        for (int f = 0; f < kRmFrags; f++) wrow[f] = wg + (size_t)min(e0 + 32 * f + ln, E - 1) * H + kb * 16;
+        float16_t acc[kRmFrags];
+#pragma unroll
+        for (int f = 0; f < kRmFrags; f++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) acc[f][i] = 0.0f;
+        // kRmDepth slices in flight per wavefront, each register set refilled as soon as it has been used
+        struct Slice {
+            uint4 xv[2], wv[kRmFrags][2];
+        };
+        Slice ring[kRmDepth];
+        auto fetch = [&](int slice, Slice& sv) {
+            sv.xv[0] = load_global<uint4>(xrow + slice * 32);
+            sv.xv[1] = load_global<uint4>(xrow + slice * 32 + 8);
+#pragma unroll
+            for (int f = 0; f < kRmFrags; f++) {
+                sv.wv[f][0] = load_global<uint4>(wrow[f] + slice * 32);
+                sv.wv[f][1] = load_global<uint4>(wrow[f] + slice * 32 + 8);
+            }
+        };
+#pragma unroll
+        for (int i = 0; i < kRmDepth; i++) fetch(min(wave + 4 * i, n_slices - 1), ring[i]);
+        for (int sl = wave; sl < n_slices; sl += 4 * kRmDepth) {
+#pragma unroll
+            for (int i = 0; i < kRmDepth; i++) {
+                const int cur = sl + 4 * i;
+                if (cur < n_slices) {                          // the same in every lane
+#pragma unroll
+                    for (int f = 0; f < kRmFrags; f++) {
+                        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ring[i].wv[f][0]),
+                                                                        __builtin_bit_cast(bf16x8_t, ring[i].xv[0]), acc[f], 0, 0, 0);
+                        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ring[i].wv[f][1]),
+                                                                        __builtin_bit_cast(bf16x8_t, ring[i].xv[1]), acc[f], 0, 0, 0);
+                    }
+                    const int nx = cur + 4 * kRmDepth;         // past the end: re-read the current slice, never used
+                    fetch(nx < n_slices ? nx : cur, ring[i]);
+                }
+            }
+        }
+        // register i of fragment f: expert 32 f + 8 (i / 4) + 4 kb + i % 4, token ln
+        float* mine = part + ((size_t)wave * kRmTokens + ln) * kRmExperts;
+#pragma unroll
+        for (int f = 0; f < kRmFrags; f++)
+#pragma unroll
+            for (int g = 0; g < 4; g++)
+                *reinterpret_cast<float4*>(mine + 32 * f + 8 * g + 4 * kb) =
+                    make_float4(acc[f][4 * g], acc[f][4 * g + 1], acc[f][4 * g + 2], acc[f][4 * g + 3]);
+        __syncthreads();
+        for (int i = threadIdx.x; i < kRmTokens * kRmExperts; i += 4 * kWave) {
+            const int tok = i / kRmExperts, e = e0 + i % kRmExperts;
+            if (e < E) {
+                // the four quarters of the reduction, in wavefront order
+                const float v = ((part[i] + part[kRmTokens * kRmExperts + i]) + part[2 * kRmTokens * kRmExperts + i]) +
+                                part[3 * kRmTokens * kRmExperts + i];
+                logit[(size_t)tok * E + e] = v + (bias ? bias[e] : 0.0f);
+            }
+        }
+        __syncthreads();
+    }
+    // wavefront `wave` finishes tokens wave, wave + 4, ..., kRmBatch at a time
+    for (int first = wave; first < kRmTokens; first += 4 * kRmBatch) {
+        float* lgs[kRmBatch];
+        float* sps[kRmBatch];
+        int ts[kRmBatch];
+#pragma unroll
+        for (int b = 0; b < kRmBatch; b++) {
+            const int tw = first + 4 * b;
+            lgs[b] = logit + (size_t)tw * E;
+            sps[b] = selp + b * k;
+            ts[b] = (t0 + tw < T) ? t0 + tw : -1;      // rows past the last token hold a copy of it: computed, not stored
+        }
+        float* const (&lgc)[kRmBatch] = lgs;
+        float* const (&spc)[kRmBatch] = sps;
+        route_select_batch<kRmBatch>(lgc, spc, ts, E, k, renorm, idx, w, probs, nullptr, nullptr);
     }
 }
 
@@ -235,6 +416,16 @@ int dymoe_route_topk(dymoe_ctx* ctx, const void* x, const void* wg, const float*
     if (!ctx) return DYMOE_ENOCTX;
     if (T == 0) return DYMOE_OK;
     hipStream_t st = (hipStream_t)stream;
+    // many tokens and experts: a dense contraction, on the matrix cores (when its tiles fit in 64 KiB of LDS)
+    const size_t mfma_lds = (4 * (size_t)dymoe::kRmTokens * dymoe::kRmExperts + (size_t)dymoe::kRmTokens * E +
+                             4 * (size_t)dymoe::kRmBatch * k) * sizeof(float);
+    if (T >= 128 && E >= 32 && H % 128 == 0 && mfma_lds <= 65536) {
+        dymoe_launch(ctx, DYMOE_K_ROUTE, dymoe::route_mfma_kernel, dim3((unsigned)((T + dymoe::kRmTokens - 1) / dymoe::kRmTokens)),
+                     dim3(4 * dymoe::kWave), mfma_lds, st, (const uint16_t*)x, (const uint16_t*)wg, bias, T, H, E, k, renorm,
+                     idx, w, probs);
+        DYMOE_HIP_LAUNCH_CHECK();
+        return DYMOE_OK;
+    }
     // tokens per workgroup chosen so that their activations fit in 128 VGPRs;
     // few tokens: one per workgroup, its experts spread over 8 wavefronts
     if (H <= 4096 && T >= 1024)

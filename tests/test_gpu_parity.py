@@ -168,11 +168,23 @@ def test_route_topk_tiny_and_ragged(ctx):
 
 
 def test_route_topk_many_experts_multi_token_wavefronts(ctx):
-    # 128 experts top-8 with the Zipf bias; T >= 1024 takes the 4-tokens-per-wavefront kernel
+    # 128 experts top-8 with the Zipf bias, ragged last token tile: the matrix-core router
     c = synth.scaled(synth.CONFIGS["fine_grained"], T=1030)
     x, _ = synth.activations(c)
     wg, bias = synth.router(c)
     _check_route(ctx, x, wg, bias, c.k)
+    # the same kernel with a ragged last expert fragment (40 = 32 + 8), with its largest expert count, at its
+    # smallest token count
+    for T, E, H, k in ((128, 40, 256, 3), (300, 192, 384, 6), (129, 32, 128, 8)):
+        c1 = synth.scaled(synth.CONFIGS["fine_grained"], config_id=13, T=T, E=E, H=H, k=k)
+        x, _ = synth.activations(c1)
+        wg, _ = synth.router(c1)
+        _check_route(ctx, x, wg[:E], None, k)
+    # few experts, many tokens: four tokens per wavefront on the vector units
+    c3 = synth.scaled(synth.CONFIGS["tiny"], config_id=14, T=1030)
+    x, _ = synth.activations(c3)
+    wg, bias = synth.router(c3)
+    _check_route(ctx, x, wg, bias, c3.k)
     # wide rows (two and four register segments)
     for H in (8192, 16384):
         c2 = synth.scaled(synth.CONFIGS["tiny"], config_id=12, T=3, H=H)

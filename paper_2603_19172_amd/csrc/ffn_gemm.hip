@@ -59,60 +59,117 @@ __host__ __device__ inline PlanPtrs plan_ptrs(int32_t* base, int E, int P)
     return p;
 }
 
-__global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ idx,
-                                                    const uint8_t* __restrict__ bits, int P, int E,
-                                                    int tile_m, int max_tiles,
-                                                    int32_t* __restrict__ plan)
+// One workgroup of 16 wavefronts.  Counting and scattering go through one
+// histogram per wavefront when they fit in LDS (E <= kPlanPrivE), so that the
+// atomics of a popular expert do not queue up across the whole workgroup; a
+// pair's position is then (expert offset) + (pairs of the expert in earlier
+// wavefronts) + (its turn inside its wavefront).  Tiles are laid out by one
+// thread per expert after a scan of the per-expert tile counts, staged in LDS
+// when the list fits, and sorted by rank counting.
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanWaves = kPlanThreads / kWave;
+constexpr int kPlanPrivE = 256;        // 16 x 256 counters = 16 KiB
+constexpr int kPlanLdsTiles = 1024;    // 4 ints each = 16 KiB
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ idx,
+                                                            const uint8_t* __restrict__ bits, int P, int E,
+                                                            int tile_m, int max_tiles,
+                                                            int32_t* __restrict__ plan)
 {
     __shared__ int32_t s_count[DYMOE_MAX_EXPERTS];
     __shared__ int32_t s_off[DYMOE_MAX_EXPERTS + 1];
-    __shared__ int s_nt;
-    const PlanPtrs pp = plan_ptrs(plan, E, P);
-    int32_t* draft = pp.tiles + 4 * (size_t)max_tiles;   // tiles in expert order, before sorting
+    __shared__ int32_t s_tile0[DYMOE_MAX_EXPERTS + 1];       // first tile of each expert
+    __shared__ int32_t s_priv[kPlanWaves * kPlanPrivE];
+    __shared__ int32_t s_draft[4 * kPlanLdsTiles];
     __shared__ uint8_t s_bits[DYMOE_MAX_EXPERTS];
-    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+    const PlanPtrs pp = plan_ptrs(plan, E, P);
+    const int tid = threadIdx.x, wave = tid / kWave;
+    const bool priv = E <= kPlanPrivE;
+    // tiles in expert order, before sorting
+    int32_t* draft = (max_tiles <= kPlanLdsTiles) ? s_draft : pp.tiles + 4 * (size_t)max_tiles;
+    for (int e = tid; e < E; e += kPlanThreads) {
         s_count[e] = 0;
         s_bits[e] = bits[e];
     }
+    if (priv)
+        for (int i = tid; i < kPlanWaves * E; i += kPlanThreads) s_priv[i] = 0;
     __syncthreads();
-    for (int p = threadIdx.x; p < P; p += blockDim.x) {
-        const int e = idx[p];
-        if (e < 0 || e >= E) continue;
+    auto counted = [&](int p, int& e) {
+        e = idx[p];
+        if (e < 0 || e >= E) return false;
         const int b = s_bits[e];
-        if (b != 16 && b != 8 && b != 4 && b != 2) continue;
-        atomicAdd(&s_count[e], 1);
+        return b == 16 || b == 8 || b == 4 || b == 2;
+    };
+    for (int p = tid; p < P; p += kPlanThreads) {
+        int e;
+        if (counted(p, e)) atomicAdd(priv ? &s_priv[wave * E + e] : &s_count[e], 1);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0, nt = 0;
-        for (int e = 0; e < E; e++) {
-            s_off[e] = run;
-            const int c = s_count[e];
-            const int b = s_bits[e];
-            for (int m0 = 0; m0 < c; m0 += tile_m) {
-                const int rows = min(tile_m, c - m0);
-                draft[4 * nt + 0] = e;
-                draft[4 * nt + 1] = run + m0;
-                draft[4 * nt + 2] = rows;
-                // cost key, roughly the time a workgroup spends on the tile: streaming (bf16)
-                // or dequantising (int4, int2) the weights costs the same whatever the number
-                // of tokens; the MFMA work grows with the 32-token fragments
-                draft[4 * nt + 3] = (b == 16 ? 100 : (b == 2 ? 60 : 61)) + 10 * ((rows + 31) >> 5);
-                nt++;
+    if (priv) {
+        // per expert: total, and every wavefront's first position among the expert's pairs
+        for (int e = tid; e < E; e += kPlanThreads) {
+            int run = 0;
+            for (int wv = 0; wv < kPlanWaves; wv++) {
+                const int c = s_priv[wv * E + e];
+                s_priv[wv * E + e] = run;
+                run += c;
             }
-            run += c;
+            s_count[e] = run;
         }
-        s_off[E] = run;
-        pp.ntiles[0] = nt;
-        pp.ntiles[1] = run;
-        s_nt = nt;
+        __syncthreads();
+    }
+    // exclusive scans over the experts (pairs and tiles): E is at most 1024, one wavefront walks it in strides
+    if (wave == 0) {
+        const int lane = tid;
+        int run = 0, trun = 0;
+        for (int e0 = 0; e0 < E; e0 += kWave) {
+            const int e = e0 + lane;
+            const int c = (e < E) ? s_count[e] : 0;
+            const int nt_e = (c + tile_m - 1) / tile_m;
+            int incl = c, tincl = nt_e;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const int a = __shfl_up(incl, o, kWave), b2 = __shfl_up(tincl, o, kWave);
+                if (lane >= o) {
+                    incl += a;
+                    tincl += b2;
+                }
+            }
+            if (e < E) {
+                s_off[e] = run + incl - c;
+                s_tile0[e] = trun + tincl - nt_e;
+            }
+            run += __shfl(incl, kWave - 1, kWave);
+            trun += __shfl(tincl, kWave - 1, kWave);
+        }
+        if (lane == 0) {
+            s_off[E] = run;
+            s_tile0[E] = trun;
+            pp.ntiles[0] = trun;
+            pp.ntiles[1] = run;
+        }
     }
     __syncthreads();
+    const int nt_all = s_tile0[E];
+    for (int e = tid; e < E; e += kPlanThreads) {
+        const int c = s_count[e], b = s_bits[e];
+        int nt = s_tile0[e];
+        for (int m0 = 0; m0 < c; m0 += tile_m, nt++) {
+            const int rows = min(tile_m, c - m0);
+            draft[4 * nt + 0] = e;
+            draft[4 * nt + 1] = s_off[e] + m0;
+            draft[4 * nt + 2] = rows;
+            // cost key, roughly the time a workgroup spends on the tile: streaming (bf16)
+            // or dequantising (int4, int2) the weights costs the same whatever the number
+            // of tokens; the MFMA work grows with the 32-token fragments
+            draft[4 * nt + 3] = (b == 16 ? 100 : (b == 2 ? 60 : 61)) + 10 * ((rows + 31) >> 5);
+        }
+    }
+    __syncthreads();        // (workgroup-wide visibility also of the draft kept in global memory)
     // Longest first: workgroups are dispatched in tile order, so the cheap tiles
     // (few tokens) fill the end of the launch instead of stretching it.
     // Rank by counting, (key descending, position ascending): a permutation.
-    const int nt_all = s_nt;
-    for (int i = threadIdx.x; i < nt_all; i += blockDim.x) {
+    for (int i = tid; i < nt_all; i += kPlanThreads) {
         const int key = draft[4 * i + 3];
         int pos = 0;
         for (int j = 0; j < nt_all; j++) {
@@ -124,20 +181,19 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
         pp.tiles[4 * pos + 2] = draft[4 * i + 2];
         pp.tiles[4 * pos + 3] = key;
     }
-    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+    for (int e = tid; e < E; e += kPlanThreads) {
         pp.counts[e] = s_count[e];
         pp.offsets[e] = s_off[e];
-        s_count[e] = 0;  // reused as the scatter cursor
     }
-    if (threadIdx.x == 0) pp.offsets[E] = s_off[E];
+    if (tid == 0) pp.offsets[E] = s_off[E];
+    __syncthreads();
+    for (int e = tid; e < E; e += kPlanThreads) s_count[e] = 0;    // reused as the scatter cursor
     __syncthreads();
     // order inside an expert is arbitrary: every row of a tile is computed independently
-    for (int p = threadIdx.x; p < P; p += blockDim.x) {
-        const int e = idx[p];
-        if (e < 0 || e >= E) continue;
-        const int b = s_bits[e];
-        if (b != 16 && b != 8 && b != 4 && b != 2) continue;
-        const int pos = s_off[e] + atomicAdd(&s_count[e], 1);
+    for (int p = tid; p < P; p += kPlanThreads) {
+        int e;
+        if (!counted(p, e)) continue;
+        const int pos = s_off[e] + (priv ? atomicAdd(&s_priv[wave * E + e], 1) : atomicAdd(&s_count[e], 1));
         pp.perm[pos] = p;
     }
 }
@@ -844,7 +900,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     int32_t* plan = reinterpret_cast<int32_t*>(ws + L.plan);
     const uint16_t* xb = (const uint16_t*)x;
 
-    dymoe_launch(ctx, DYMOE_K_PLAN, plan_kernel, dim3(1), dim3(1024), 0, st, idx, bits, P, E, kGemmTileM, L.max_tiles, plan);
+    dymoe_launch(ctx, DYMOE_K_PLAN, plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, idx, bits, P, E, kGemmTileM, L.max_tiles, plan);
     DYMOE_HIP_LAUNCH_CHECK();
     const long n16 = (long)T * H / 16;
     hipLaunchKernelGGL(prep_x_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, xb, n16, xh4, xh2, xh8);

@@ -21,11 +21,17 @@ __global__ void zero_i32_kernel(int32_t* a, int32_t* b, int n)
 }
 
 // Prefill: a token is a heavy hitter when fewer than k_hh tokens precede it in
-// the order (score descending, token index ascending).  Each thread ranks one
-// token against all T scores staged through LDS (four per read), then adds its
-// k routed experts to the workgroup's LDS histograms (load and, if heavy,
-// importance); the workgroup adds its non-zero bins to the global ones, which
-// the caller has zeroed.  with_importance = 0: only the load histogram (decode).
+// the order (score descending, token index ascending).  kImpLanes adjacent
+// lanes share one token: all T scores pass through LDS in tiles, each lane
+// compares the token against its eighth of every tile (four scores per read),
+// and the partial counts are added across the lanes.  The token's first lane
+// then adds its k routed experts to the workgroup's LDS histograms (load and,
+// if heavy, importance); the workgroup adds its non-zero bins to the global
+// ones, which the caller has zeroed.  with_importance = 0: only the load
+// histogram (decode).
+constexpr int kImpLanes = 8;
+constexpr int kImpTokens = kImpThreads / kImpLanes;      // tokens per workgroup
+
 __global__ __launch_bounds__(kImpThreads) void importance_prefill_kernel(
     const int32_t* __restrict__ idx, const float* __restrict__ score, int T, int E, int k,
     int k_hh, int with_importance, int32_t* __restrict__ importance, int32_t* __restrict__ load)
@@ -37,18 +43,20 @@ __global__ __launch_bounds__(kImpThreads) void importance_prefill_kernel(
         s_load[e] = 0;
         s_imp[e] = 0;
     }
-    const int t = blockIdx.x * kImpThreads + threadIdx.x;
+    const int part = threadIdx.x % kImpLanes;
+    const int t = blockIdx.x * kImpTokens + threadIdx.x / kImpLanes;
     bool heavy = false;
     if (with_importance) {
         const float mine = (t < T) ? score[t] : 0.0f;
         int before = 0;
+        constexpr int kSpan = kImpThreads / kImpLanes;     // scores of a tile that one lane looks at
         for (int base = 0; base < T; base += kImpThreads) {
             const int u = base + threadIdx.x;
             // slots past the end hold -inf at an index past every token: never counted
             tile[threadIdx.x] = (u < T) ? score[u] : -INFINITY;
             __syncthreads();
-#pragma unroll 4
-            for (int j = 0; j < kImpThreads; j += 4) {
+#pragma unroll
+            for (int j = part * kSpan; j < (part + 1) * kSpan; j += 4) {
                 const float4 s4 = *reinterpret_cast<const float4*>(tile + j);
                 const int u0 = base + j;
                 before += (s4.x > mine || (s4.x == mine && u0 + 0 < t)) ? 1 : 0;
@@ -58,11 +66,13 @@ __global__ __launch_bounds__(kImpThreads) void importance_prefill_kernel(
             }
             __syncthreads();
         }
+#pragma unroll
+        for (int o = 1; o < kImpLanes; o <<= 1) before += __shfl_xor(before, o, kWave);
         heavy = (t < T) && before < k_hh;
     } else {
         __syncthreads();
     }
-    if (t < T) {
+    if (t < T && part == 0) {
         for (int s = 0; s < k; s++) {
             const int e = idx[(size_t)t * k + s];
             if (e < 0 || e >= E) continue;
@@ -199,7 +209,7 @@ int dymoe_expert_importance(dymoe_ctx* ctx, int phase, const int32_t* idx, const
                        prefill ? (int32_t*)importance : (int32_t*)nullptr, E);
     DYMOE_HIP_LAUNCH_CHECK();
     if (T > 0) {
-        const unsigned blocks = (unsigned)((T + dymoe::kImpThreads - 1) / dymoe::kImpThreads);
+        const unsigned blocks = (unsigned)((T + dymoe::kImpTokens - 1) / dymoe::kImpTokens);
         dymoe_launch(ctx, DYMOE_K_IMPORTANCE, dymoe::importance_prefill_kernel, dim3(blocks), dim3(dymoe::kImpThreads),
                            0, st, idx, token_score, T, E, k, k_hh, prefill ? 1 : 0,
                            (int32_t*)importance, load);

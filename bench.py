@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--stack-budget-gb", type=float, default=24.0,
                     help="device bytes set aside for expert slots in the stack run")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--fine-grained", action="store_true",
+                    help="also time the fine-grained layer (BASELINE configs[3]: 2048 tokens, 128 experts, top-8)")
     ap.add_argument("--prefill-steps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run dymoe_pack_tiles on a 1 GiB bf16 matrix: a permuting copy of known traffic "
@@ -275,6 +277,40 @@ def main():
             "workload": "512 tokens, 32 query / 8 key heads of 128, causal",
             "kernels_us": {n: round(v[0] / max(v[1], 1) * 1e3, 1) for n, v in ak_us.items()},
             "TFLOPs": round(a_flops / (a_us * 1e-6) / 1e12, 1) if a_us > 0 else None}
+
+    # ---------------------------------------------------------------- fine-grained layer (opt-in)
+    if args.fine_grained:
+        fcfg = synth.CONFIGS["fine_grained"]
+        fhw = synth.expert_weights_many(fcfg, range(fcfg.E), workers=16)
+        fstore = ExpertStore([[bf16(m) for m in fhw[e]] for e in range(fcfg.E)], fcfg.H, fcfg.F, dev, ctx=ctx)
+        fx_np, _ = synth.activations(fcfg)
+        fwg_np, fbias_np = synth.router(fcfg)
+        fx, fwg, fbias = bf16(fx_np), bf16(fwg_np), torch.from_numpy(fbias_np).to(dev)
+        flay = MoELayer(ctx, fcfg.T, fcfg.H, fcfg.F, fcfg.E, fcfg.k, "prefill", fcfg.tier_count, fcfg.tier_bits,
+                        k_hh=fcfg.k_hh, out_dtype=B.OUT_BF16, device=dev)
+        for _ in range(3):
+            flay.step(fx, fwg, fbias, fstore)
+        torch.cuda.synchronize()
+        fnames = ["route", "token_norm", "importance", "assign", "quantize", "plan", "gemm1", "gemm2", "gemm_combine"]
+        ctx.timing_enable(fnames)
+        t0 = time.perf_counter()
+        for _ in range(args.prefill_steps):
+            flay.step(fx, fwg, fbias, fstore)
+        torch.cuda.synchronize()
+        fdt = (time.perf_counter() - t0) / args.prefill_steps
+        fk = {n: ctx.timing_read(n) for n in fnames}
+        ctx.timing_enable(())
+        fg_us = (fk["gemm1"][0] / max(fk["gemm1"][1], 1) + fk["gemm2"][0] / max(fk["gemm2"][1], 1)) * 1e3
+        fflops = 2.0 * 3 * fcfg.H * fcfg.F * fcfg.T * fcfg.k
+        out["fine_grained_2048"] = {
+            "workload": "fine_grained (BASELINE configs[3]): 2048 tokens, 128 experts of 768, top-8, Zipf router bias, tiers 13/39/76",
+            "tokens_per_s_full_path": round(fcfg.T / fdt, 1), "us_per_step_full_path": round(fdt * 1e6, 1),
+            "experts_with_load": int((flay.load > 0).sum()), "max_load": int(flay.load.max()),
+            "grouped_gemm_us": round(fg_us, 1),
+            "grouped_gemm_frac_mfma_bf16_peak": round(fflops / (fg_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "kernels_us": {n: round(v[0] / max(v[1], 1) * 1e3, 1) for n, v in fk.items()}}
+        del fstore, flay
+        torch.cuda.empty_cache()
 
     # ---------------------------------------------------------------- CPU oracle on this host
     if not args.skip_cpu:

@@ -154,3 +154,12 @@ def test_create_without_gpu_reports_error():
     assert B.lib.dymoe_create(C.byref(h), 0) == B.EHIP and not h.value
     with pytest.raises(B.DymoeError):
         B.Context(0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""

@@ -80,7 +80,7 @@ def main():
     x_np, _ = synth.activations(cfg)
     wg_np, bias_np = synth.router(cfg)
     ctx = B.Context(0)
-    stores = [ExpertStore([[bf16(m) for m in host_w[e]] for e in range(E)], H, F, dev, ctx=ctx)]
+    stores = [ExpertStore([[bf16(m) for m in host_w[e]] for e in range(E)], H, F, dev, ctx=ctx, formats=(8, 4, 2))]
     for _ in range(LAYER_COPIES - 1):
         stores.append(stores[0].clone())
     x = bf16(x_np)
@@ -194,6 +194,34 @@ def main():
                           "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)})
         kernels_report[name] = entry
 
+    # ---------------------------------------------------------------- S5 alone with the active pair forced to each format
+    sweep = {}
+    st0 = B._stream(None)
+    only_active = torch.zeros((E,), dtype=torch.int32, device=dev)
+    only_active[active] = 1
+    for ba, bb in ((16, 16), (8, 8), (4, 4), (4, 2), (2, 2)):
+        forced = torch.full((E,), 2, dtype=torch.uint8, device=dev)
+        forced[active[0]], forced[active[1]] = ba, bb
+        for s_ in stores:
+            ctx.quantize_experts(s_.table, forced, only_active, E, H, F, layout=layer.layout)
+        layer.bits.copy_(forced)
+        for i in range(4):
+            layer.ffn(x, stores[i % len(stores)], st0)
+        torch.cuda.synchronize()
+        ctx.timing_enable(["gemv_phase1", "gemv_phase2", "gemv_combine"])
+        n_sw = 40
+        for i in range(n_sw):
+            layer.ffn(x, stores[i % len(stores)], st0)
+        torch.cuda.synchronize()
+        us = {n_: ctx.timing_read(n_)[0] / n_sw * 1e3 for n_ in ("gemv_phase1", "gemv_phase2", "gemv_combine")}
+        ctx.timing_enable(())
+        nbytes = 3.0 * H * F * (bytes_per_weight(ba) + bytes_per_weight(bb))
+        tot = sum(us.values())
+        sweep["%d+%d" % (ba, bb)] = {"algorithmic_bytes": nbytes, "kernels_us": {k_: round(v_, 1) for k_, v_ in us.items()},
+                                     "GBps": round(nbytes / (tot * 1e-6) / 1e9, 1),
+                                     "frac_hbm": round(nbytes / (tot * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+    layer.bits.copy_(torch.from_numpy(bits_host).to(dev))
+
     out = {
         "metric": "MoE-layer tokens/s, decode b=1, full hot path (route, importance, precision, quantize-pack, mixed FFN)",
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -211,6 +239,9 @@ def main():
                          "note": "all kernels of a step and the gaps between them over the step's algorithmic "
                                  "bytes; stream_copy_GBps is a plain 1 GiB copy (read + write bytes) on this GPU"},
         "kernels": kernels_report,
+        "decode_ffn_format_sweep": {"note": "S5 kernels alone (sum of their execution times, eager launches, 4 rotating weight "
+                                            "copies), the two active experts forced to the named bit-widths",
+                                    "pairs": sweep},
         "decode_ffn_only": {"tokens_per_s": round(cfg.T * args.steps / sec_ffn, 1),
                             "us_per_step": round(sec_ffn / args.steps * 1e6, 2),
                             "algorithmic_bytes": ffn_bytes,

@@ -47,6 +47,10 @@ def main():
     ap.add_argument("--stack-budget-gb", type=float, default=24.0,
                     help="device bytes set aside for expert slots in the stack run")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--format-sweep", action="store_true",
+                    help="also time the decode FFN kernels with the two active experts forced to bf16, int8, int4, "
+                         "int4+int2 and int2 (off by default: its extra launches would blur the per-kernel averages of a "
+                         "profiler run over the default workload)")
     ap.add_argument("--fine-grained", action="store_true",
                     help="also time the fine-grained layer (BASELINE configs[3]: 2048 tokens, 128 experts, top-8)")
     ap.add_argument("--prefill-steps", type=int, default=20)
@@ -80,7 +84,8 @@ def main():
     x_np, _ = synth.activations(cfg)
     wg_np, bias_np = synth.router(cfg)
     ctx = B.Context(0)
-    stores = [ExpertStore([[bf16(m) for m in host_w[e]] for e in range(E)], H, F, dev, ctx=ctx, formats=(8, 4, 2))]
+    stores = [ExpertStore([[bf16(m) for m in host_w[e]] for e in range(E)], H, F, dev, ctx=ctx,
+                          formats=(8, 4, 2) if args.format_sweep else (4, 2))]
     for _ in range(LAYER_COPIES - 1):
         stores.append(stores[0].clone())
     x = bf16(x_np)
@@ -199,7 +204,7 @@ def main():
     st0 = B._stream(None)
     only_active = torch.zeros((E,), dtype=torch.int32, device=dev)
     only_active[active] = 1
-    for ba, bb in ((16, 16), (8, 8), (4, 4), (4, 2), (2, 2)):
+    for ba, bb in (((16, 16), (8, 8), (4, 4), (4, 2), (2, 2)) if args.format_sweep else ()):
         forced = torch.full((E,), 2, dtype=torch.uint8, device=dev)
         forced[active[0]], forced[active[1]] = ba, bb
         for s_ in stores:
@@ -240,8 +245,8 @@ def main():
                                  "bytes; stream_copy_GBps is a plain 1 GiB copy (read + write bytes) on this GPU"},
         "kernels": kernels_report,
         "decode_ffn_format_sweep": {"note": "S5 kernels alone (sum of their execution times, eager launches, 4 rotating weight "
-                                            "copies), the two active experts forced to the named bit-widths",
-                                    "pairs": sweep},
+                                            "copies), the two active experts forced to the named bit-widths; --format-sweep",
+                                    "pairs": sweep} if args.format_sweep else None,
         "decode_ffn_only": {"tokens_per_s": round(cfg.T * args.steps / sec_ffn, 1),
                             "us_per_step": round(sec_ffn / args.steps * 1e6, 2),
                             "algorithmic_bytes": ffn_bytes,

@@ -119,6 +119,15 @@ __device__ __forceinline__ void store_global(void* p, T v)
     else *(DYMOE_GLOBAL T*)p = v;
 }
 
+// The same store marked non-temporal: written once, not read again by this kernel.
+template <typename T>
+__device__ __forceinline__ void store_global_nt(void* p, T v)
+{
+    if constexpr (sizeof(T) == 16) __builtin_nontemporal_store(__builtin_bit_cast(u32x4_t, v), (DYMOE_GLOBAL u32x4_t*)p);
+    else if constexpr (sizeof(T) == 8) __builtin_nontemporal_store(__builtin_bit_cast(u32x2_t, v), (DYMOE_GLOBAL u32x2_t*)p);
+    else __builtin_nontemporal_store(v, (DYMOE_GLOBAL T*)p);
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 __device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }

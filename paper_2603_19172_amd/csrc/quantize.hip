@@ -92,16 +92,16 @@ __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, l
         words[wd] = lo16 | hi16;
     }
     if constexpr (BITS == 8) {
-        store_global(codes + e0, make_uint4(words[0], words[1], words[2], words[3]));
-        store_global(codes + e0 + 16, make_uint4(words[4], words[5], words[6], words[7]));
+        store_global_nt(codes + e0, make_uint4(words[0], words[1], words[2], words[3]));
+        store_global_nt(codes + e0 + 16, make_uint4(words[4], words[5], words[6], words[7]));
     } else if constexpr (BITS == 4) {
-        store_global(codes + (e0 >> 1), make_uint4(words[0], words[1], words[2], words[3]));
+        store_global_nt(codes + (e0 >> 1), make_uint4(words[0], words[1], words[2], words[3]));
     } else {
-        store_global(codes + (e0 >> 2), make_uint2(words[0], words[1]));
+        store_global_nt(codes + (e0 >> 2), make_uint2(words[0], words[1]));
     }
     if ((lane & 1) == 0) {
-        store_global(scale + (e0 >> 6), (uint16_t)f16_bits(sh));
-        store_global(zero + (e0 >> 6), (uint16_t)f16_bits(zh));
+        store_global_nt(scale + (e0 >> 6), (uint16_t)f16_bits(sh));
+        store_global_nt(zero + (e0 >> 6), (uint16_t)f16_bits(zh));
     }
 }
 
@@ -183,16 +183,16 @@ __device__ __forceinline__ void quantize_tile(const uint16_t* __restrict__ w, lo
         uint8_t* dst = codes + tile * 4096 + lane * 16;
 #pragma unroll
         for (int c = 0; c < 4; c++)
-            store_global(dst + c * 1024, make_uint4(words[4 * c], words[4 * c + 1], words[4 * c + 2], words[4 * c + 3]));
+            store_global_nt(dst + c * 1024, make_uint4(words[4 * c], words[4 * c + 1], words[4 * c + 2], words[4 * c + 3]));
     } else if constexpr (BITS == 4) {
         uint8_t* dst = codes + tile * 2048 + lane * 16;
-        store_global(dst, make_uint4(words[0], words[1], words[2], words[3]));
-        store_global(dst + 1024, make_uint4(words[4], words[5], words[6], words[7]));
+        store_global_nt(dst, make_uint4(words[0], words[1], words[2], words[3]));
+        store_global_nt(dst + 1024, make_uint4(words[4], words[5], words[6], words[7]));
     } else {
-        store_global(codes + tile * 1024 + lane * 16, make_uint4(words[0], words[1], words[2], words[3]));
+        store_global_nt(codes + tile * 1024 + lane * 16, make_uint4(words[0], words[1], words[2], words[3]));
     }
-    store_global(scale + tile * 64 + lane, (uint16_t)f16_bits(sh));
-    store_global(zero + tile * 64 + lane, (uint16_t)f16_bits(zh));
+    store_global_nt(scale + tile * 64 + lane, (uint16_t)f16_bits(sh));
+    store_global_nt(zero + tile * 64 + lane, (uint16_t)f16_bits(zh));
 }
 
 // bf16 row-major -> bf16 tiles: thread = (tile, chunk j, lane)

@@ -119,6 +119,21 @@ __device__ __forceinline__ void store_global(void* p, T v)
     else *(DYMOE_GLOBAL T*)p = v;
 }
 
+// The same load marked non-temporal: data streamed through once.
+template <typename T>
+__device__ __forceinline__ T load_global_nt(const void* p)
+{
+    if constexpr (sizeof(T) == 16) {
+        const u32x4_t v = __builtin_nontemporal_load((const DYMOE_GLOBAL u32x4_t*)p);
+        return __builtin_bit_cast(T, v);
+    } else if constexpr (sizeof(T) == 8) {
+        const u32x2_t v = __builtin_nontemporal_load((const DYMOE_GLOBAL u32x2_t*)p);
+        return __builtin_bit_cast(T, v);
+    } else {
+        return __builtin_nontemporal_load((const DYMOE_GLOBAL T*)p);
+    }
+}
+
 // The same store marked non-temporal: written once, not read again by this kernel.
 template <typename T>
 __device__ __forceinline__ void store_global_nt(void* p, T v)

@@ -201,7 +201,7 @@ __device__ __forceinline__ void load_row(const ExpertMat& m, long row, int K, in
 #pragma unroll
             for (int j = 0; j < 4; j++) {
                 const int col = min((seg0 + s) * kSeg + (j * kWave + lane) * 8, K - 8);
-                rr.c[s][j] = load_global<uint4>(base + col);
+                rr.c[s][j] = load_global_nt<uint4>(base + col);
             }
     } else {
         const long G = K >> 6;
@@ -210,10 +210,10 @@ __device__ __forceinline__ void load_row(const ExpertMat& m, long row, int K, in
         for (int s = 0; s < NSEG; s++) {
             const int col0 = min((seg0 + s) * kSeg + 32 * lane, K - 32);
             if constexpr (BITS == 8) {
-                rr.c[s][0] = load_global<uint4>(codes + col0);
-                rr.c[s][1] = load_global<uint4>(codes + col0 + 16);
-            } else if constexpr (BITS == 4) rr.c[s] = load_global<uint4>(codes + (col0 >> 1));
-            else rr.c[s] = load_global<uint2>(codes + (col0 >> 2));
+                rr.c[s][0] = load_global_nt<uint4>(codes + col0);
+                rr.c[s][1] = load_global_nt<uint4>(codes + col0 + 16);
+            } else if constexpr (BITS == 4) rr.c[s] = load_global_nt<uint4>(codes + (col0 >> 1));
+            else rr.c[s] = load_global_nt<uint2>(codes + (col0 >> 2));
             rr.s[s] = load_global<uint16_t>(m.s + row * G + (col0 >> 6));
             rr.z[s] = load_global<uint16_t>(m.z + row * G + (col0 >> 6));
         }

@@ -100,8 +100,8 @@ __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, l
         store_global_nt(codes + (e0 >> 2), make_uint2(words[0], words[1]));
     }
     if ((lane & 1) == 0) {
-        store_global_nt(scale + (e0 >> 6), (uint16_t)f16_bits(sh));
-        store_global_nt(zero + (e0 >> 6), (uint16_t)f16_bits(zh));
+        store_global(scale + (e0 >> 6), (uint16_t)f16_bits(sh));
+        store_global(zero + (e0 >> 6), (uint16_t)f16_bits(zh));
     }
 }
 
@@ -191,8 +191,8 @@ __device__ __forceinline__ void quantize_tile(const uint16_t* __restrict__ w, lo
     } else {
         store_global_nt(codes + tile * 1024 + lane * 16, make_uint4(words[0], words[1], words[2], words[3]));
     }
-    store_global_nt(scale + tile * 64 + lane, (uint16_t)f16_bits(sh));
-    store_global_nt(zero + tile * 64 + lane, (uint16_t)f16_bits(zh));
+    store_global(scale + tile * 64 + lane, (uint16_t)f16_bits(sh));
+    store_global(zero + tile * 64 + lane, (uint16_t)f16_bits(zh));
 }
 
 // bf16 row-major -> bf16 tiles: thread = (tile, chunk j, lane)

@@ -190,6 +190,8 @@ template <int NSEG> struct RowRegs<8, NSEG> { uint4 c[NSEG][2]; uint16_t s[NSEG]
 
 // Issue the loads of row `row` (K columns).  Lanes past the end of the row
 // re-read its tail: finite weights against zero activations add nothing.
+// Weights are read once per step: where a load instruction covers whole cache
+// lines (consecutive lanes, consecutive 16 or 8 bytes) it is marked non-temporal.
 template <int BITS, int NSEG>
 __device__ __forceinline__ void load_row(const ExpertMat& m, long row, int K, int seg0, int lane,
                                          RowRegs<BITS, NSEG>& rr)
@@ -210,8 +212,10 @@ __device__ __forceinline__ void load_row(const ExpertMat& m, long row, int K, in
         for (int s = 0; s < NSEG; s++) {
             const int col0 = min((seg0 + s) * kSeg + 32 * lane, K - 32);
             if constexpr (BITS == 8) {
-                rr.c[s][0] = load_global_nt<uint4>(codes + col0);
-                rr.c[s][1] = load_global_nt<uint4>(codes + col0 + 16);
+                // (ordinary loads: the two pieces of a lane interleave with its neighbours', and only a
+                // cached line serves both)
+                rr.c[s][0] = load_global<uint4>(codes + col0);
+                rr.c[s][1] = load_global<uint4>(codes + col0 + 16);
             } else if constexpr (BITS == 4) rr.c[s] = load_global_nt<uint4>(codes + (col0 >> 1));
             else rr.c[s] = load_global_nt<uint2>(codes + (col0 >> 2));
             rr.s[s] = load_global<uint16_t>(m.s + row * G + (col0 >> 6));

@@ -593,3 +593,70 @@ def test_stream_copy_copies_every_byte(ctx, nbytes):
     sync()
     assert torch.equal(dst[:nbytes], src)
     assert int(dst[nbytes:].sum()) == 0        # nothing written past the end
+
+
+# ---------------------------------------------------------------- further edges
+
+def test_ffn_paths_agree_at_the_switch_over(ctx):
+    """AUTO takes the GEMV up to 4 tokens and the grouped GEMM above: both paths on the same 4- and 5-token
+    inputs agree with the oracle, hence with each other."""
+    for T in (4, 5):
+        cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=31, T=T)
+        x, _ = synth.activations(cfg)
+        idx, w = routed(cfg, x)
+        bits_np = np.array([16, 8, 4, 2, 16, 8, 4, 2], np.uint8)
+        outs = {}
+        for path in (B.PATH_GEMV, B.PATH_GEMM):
+            host, dev, table, keep = build_layer(cfg, bits_np, path=path)
+            ref = oracle_ffn(cfg, x, idx, w, bits_np, host)
+            outs[path] = run_ffn(ctx, cfg, x, idx, w, bits_np, table, path)
+            assert rel_err_per_token(outs[path], ref) <= FFN_TOL
+        assert rel_err_per_token(outs[B.PATH_GEMV], outs[B.PATH_GEMM]) <= FFN_TOL
+
+
+def test_route_one_expert_and_all_experts(ctx):
+    # E = 1: the only expert with weight 1; k = E = 24: a full ranking of the experts
+    c1 = synth.scaled(synth.CONFIGS["tiny"], config_id=32, T=9, E=1, k=1)
+    x, _ = synth.activations(c1)
+    wg, _ = synth.router(c1)
+    idx, w, p = _check_route(ctx, x, wg[:1], None, 1)
+    assert (idx.cpu().numpy() == 0).all() and np.allclose(w.cpu().numpy(), 1.0) and np.allclose(p.cpu().numpy(), 1.0)
+    c2 = synth.scaled(synth.CONFIGS["tiny"], config_id=33, T=6, H=512, E=24, k=24)
+    x, _ = synth.activations(c2)
+    wg, _ = synth.router(c2)
+    ridx, _, _, rl = O.route_topk(x, wg, None, 24)
+    if margin_ok(rl, 23).all():
+        idx, w, p = ctx.route_topk(to_bf16(x), to_bf16(wg), None, 24)
+        sync()
+        assert np.array_equal(idx.cpu().numpy(), ridx)
+        assert np.allclose(w.cpu().numpy().sum(axis=1), 1.0, rtol=1e-5)
+
+
+def test_decode_front_at_its_largest_step(ctx):
+    T, H, E, k = B.FRONT_MAX_TOKENS, 512, 16, 4
+    c = synth.scaled(synth.CONFIGS["tiny"], config_id=34, T=T, H=H, E=E, k=k)
+    x, _ = synth.activations(c)
+    wg, _ = synth.router(c)
+    tiers, tier_bits = (2, 4, 4, 6), (16, 8, 4, 2)
+    idx, w, p, imp, load, bits, rank = ctx.decode_front(to_bf16(x), to_bf16(wg), None, k, tiers, tier_bits)
+    sync()
+    ridx, rw, rp, rl = O.route_topk(x, wg, None, k)
+    ok = margin_ok(rl, k)
+    assert np.array_equal(idx.cpu().numpy()[ok], ridx[ok])
+    rload = np.bincount(idx.cpu().numpy().ravel(), minlength=E)
+    assert np.array_equal(load.cpu().numpy(), rload) and rload.sum() == T * k
+    assert np.allclose(imp.cpu().numpy(), rp.mean(axis=0), rtol=2e-4, atol=1e-7)
+    rbits, rrank = O.assign_precision(imp.cpu().numpy().astype(np.float64), rload.astype(np.int32), tiers, tier_bits)
+    assert np.array_equal(bits.cpu().numpy(), rbits) and np.array_equal(rank.cpu().numpy(), rrank)
+
+
+def test_quantize_pack_smallest_and_odd_sizes(ctx):
+    rng = np.random.default_rng(35)
+    for n, k in ((1, 64), (3, 64), (7, 192), (129, 320)):
+        w = synth.f32_to_bf16_bits((rng.standard_normal((n, k)) * 0.05).astype(np.float32))
+        for bits in (8, 4, 2):
+            _check_quant(ctx, w, bits)
+    # values at the edge of what fp16 scales and zeros can hold
+    w = synth.f32_to_bf16_bits((rng.standard_normal((4, 128)) * 8000.0).astype(np.float32))
+    for bits in (8, 4, 2):
+        _check_quant(ctx, w, bits)

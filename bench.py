@@ -438,11 +438,13 @@ def main():
                 stack.step(xs[0])                 # warm-up step (fills the slots it can)
                 torch.cuda.synchronize()
                 stack.stats.clear()
+                stack.measure_overlap = True
                 t0 = time.perf_counter()
                 for s in range(args.stack_steps):
                     stack.step(xs[s])
                 torch.cuda.synchronize()
                 dt = time.perf_counter() - t0
+                ovl = stack.overlap_report()
                 stack.close()
                 stt = stack.stats
                 results.append({"transfer": transfer, "tiers": tier_name, "slots": slots, "prefetch": prefetch,
@@ -453,7 +455,10 @@ def main():
                                 "hit_prefetched": stt["hit_prefetched"], "reused_higher": stt["reused_higher"],
                                 "prefetch_issued": stt["prefetch_issued"], "prefetch_wasted": stt["prefetch_wasted"],
                                 "GB_moved_per_step": round(stt["bytes_copied"] / args.stack_steps / 1e9, 2),
-                                "host_link_GBps": round(stt["bytes_copied"] / dt / 1e9, 1)})
+                                "host_link_GBps": round(stt["bytes_copied"] / dt / 1e9, 1),
+                                "copy_ms_per_step": round(ovl["copy_ms"] / args.stack_steps, 2),
+                                "compute_stream_waiting_ms_per_step": round(ovl["stall_ms"] / args.stack_steps, 2),
+                                "copy_time_hidden": None if ovl["copy_time_hidden"] is None else round(ovl["copy_time_hidden"], 3)})
                 del stack
                 torch.cuda.empty_cache()
         out["stack_decode"] = {"workload": "32 Mixtral-shaped layers, 1 token per step, experts in pinned host memory "

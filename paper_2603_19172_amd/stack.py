@@ -217,6 +217,8 @@ class ExpertStack:
         self.host_idx, self.host_load, self.host_bits = pin((T, k), torch.int32), pin((E,), torch.int32), pin((E,), torch.uint8)
         self.host_pidx, self.host_pload, self.host_pbits = pin((T, k), torch.int32), pin((E,), torch.int32), pin((E,), torch.uint8)
         self.stats = collections.Counter()
+        self.measure_overlap = False    # set True to time every copy and every wait of the compute stream (overlap_report)
+        self._copy_events, self._stall_events = [], []
         self.trace = []     # per step and layer: (experts, assigned bits, bits they were run at)
         self.predictions = []   # per step and layer (but the last): experts fetched ahead for the next layer
 
@@ -252,8 +254,14 @@ class ExpertStack:
             self.side.wait_event(slot.last_use)
         layer, e = key
         nbytes = self.pool.nbytes[act.load_bits]
+        if self.measure_overlap:
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c0.record(self.side)
         slot.copy_event = self.ctx.prefetch_submit(self.pool.host_ptr(layer, e, act.load_bits), slot.buf.data_ptr(),
                                                    nbytes, self.side.cuda_stream)
+        if self.measure_overlap:
+            c1.record(self.side)
+            self._copy_events.append((c0, c1))
         slot.prefetched = ahead
         self.stats["bytes_copied"] += nbytes
         self.stats["copies_%d" % act.load_bits] += 1
@@ -315,6 +323,9 @@ class ExpertStack:
                     protect.add(self.cache.resident((l, e)))
             used_bits = dict(zip(active, abits))
             override = False
+            if self.measure_overlap:
+                w0 = torch.cuda.Event(enable_timing=True)
+                w0.record(cs)
             for e, b in need:
                 key = (l, e)
                 act = self.cache.request(key, want(b), protect)
@@ -338,6 +349,10 @@ class ExpertStack:
                     used_bits[e] = act.use_bits
                     override = True
                     self.stats["reused_higher"] += 1
+            if self.measure_overlap:
+                w1 = torch.cuda.Event(enable_timing=True)
+                w1.record(cs)
+                self._stall_events.append((w0, w1))
             if override:
                 lay.bits.copy_(self.host_bits, non_blocking=True)
             step_trace.append((tuple(active), tuple(abits), tuple(used_bits[e] for e in active)))
@@ -384,6 +399,17 @@ class ExpertStack:
         self.predictions.append(step_pred)
         self.stats["steps"] += 1
         return h
+
+    def overlap_report(self):
+        """With measure_overlap: time the host link was busy, time the compute stream stood waiting for copies
+        (between the first and the last wait of each layer), and the share of the copy time that was hidden
+        behind compute.  Clears the recorded events."""
+        torch.cuda.synchronize()
+        copy_ms = sum(a.elapsed_time(b) for a, b in self._copy_events)
+        stall_ms = sum(a.elapsed_time(b) for a, b in self._stall_events)
+        self._copy_events, self._stall_events = [], []
+        hidden = 1.0 - stall_ms / copy_ms if copy_ms > 0 else None
+        return {"copy_ms": copy_ms, "stall_ms": stall_ms, "copy_time_hidden": hidden}
 
     def close(self):
         torch.cuda.synchronize()

@@ -311,3 +311,20 @@ def test_stack_with_one_byte_budget_shared_by_the_formats(ctx, transfer):
         for (ex, assigned, used) in step:
             assert all(u >= a for a, u in zip(assigned, used))
     _check_against_oracle(outs, stack.trace, routers_np, expert_matrices, floor)
+
+
+def test_stack_overlap_report_accounts_for_copy_and_waiting_time(ctx):
+    L, steps = 4, 3
+    rep = {}
+    for prefetch in (False, True):
+        stack, _, _, _, cfg0 = _small_stack(ctx, L, 4, prefetch, 1700)
+        stack.measure_overlap = True
+        for s in range(steps):
+            x, _ = synth.activations(synth.scaled(cfg0, config_id=1800 + s))
+            stack.step(to_bf16(x))
+        rep[prefetch] = stack.overlap_report()
+        stack.close()
+        assert rep[prefetch]["copy_ms"] > 0 and rep[prefetch]["stall_ms"] >= 0
+        assert rep[prefetch]["copy_time_hidden"] <= 1.0
+    # without look-ahead every copy is waited for in full (the waiting time holds the copy time)
+    assert rep[False]["stall_ms"] >= 0.8 * rep[False]["copy_ms"]

@@ -9,7 +9,8 @@
 // Both passes compute tiles of S^T = K Q^T (keys down, queries across) with
 // v_mfma_f32_32x32x16_bf16.  Queries and keys are [token][head][d] rows, so a
 // lane's 16-byte pieces of a row are at once the A operand (keys) and the B
-// operand (queries): nothing goes through LDS.  In the result a lane holds one
+// operand (queries): for short sequences nothing goes through LDS (long ones
+// share the streamed operand between wavefronts, see below).  In the result a lane holds one
 // query (column) and 16 keys (rows): the softmax statistics of a query and the
 // running per-key sums both stay inside a lane until the very end.
 #include "common.hpp"
@@ -18,6 +19,7 @@ namespace dymoe {
 
 constexpr int kAtThreads = 256;
 constexpr int kAtWaves = kAtThreads / kWave;
+constexpr int kAtWideFrags = 32;       // from this many 32-token fragments on (T > 992): the LDS-staged kernels
 
 // One lane's share of a 32-token fragment of one head (D columns): lane (ln, kb)
 // holds row ln; piece c covers columns 32 (c / 2) + 16 kb + 8 (c % 2) .. + 7, i.e.
@@ -202,6 +204,195 @@ __global__ __launch_bounds__(kAtThreads) void attn_colsum_kernel(
     }
 }
 
+// ----------------------------------------------------------------------------
+// Long sequences: the streamed operand goes through LDS.  A workgroup owns 128
+// tokens (one 32-token fragment per wavefront, kept in registers) and all four
+// wavefronts multiply against the same streamed fragment, which the workgroup
+// fetches once with whole-row coalesced loads and parks in LDS (two buffers;
+// 16-byte chunk c of row r at chunk position c ^ (r mod chunks-per-row), so that
+// the operand reads of 16 consecutive rows fall on different banks).  A quarter
+// of the global traffic of the short-sequence kernels, and no merge between
+// wavefronts: each owns its tokens' statistics or sums outright.
+template <int D>
+struct AtStage {
+    static constexpr int kPerThread = 32 * (D / 8) / kAtThreads;      // 2 (D = 128) or 1 (D = 64)
+    uint4 v[kPerThread];
+};
+
+template <int D>
+__device__ __forceinline__ void stage_fetch(const uint16_t* __restrict__ head_base, long row_stride, int row0, int T,
+                                            AtStage<D>& st)
+{
+    constexpr int CH = D / 8;
+#pragma unroll
+    for (int i = 0; i < AtStage<D>::kPerThread; i++) {
+        const int at = i * kAtThreads + threadIdx.x;
+        const int r = at / CH, c = at % CH;
+        st.v[i] = load_global<uint4>(head_base + (long)min(row0 + r, T - 1) * row_stride + c * 8);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void stage_store(char* buf, const AtStage<D>& st)
+{
+    constexpr int CH = D / 8;
+#pragma unroll
+    for (int i = 0; i < AtStage<D>::kPerThread; i++) {
+        const int at = i * kAtThreads + threadIdx.x;
+        const int r = at / CH, c = at % CH;
+        *reinterpret_cast<uint4*>(buf + r * (D * 2) + ((c ^ (r & (CH - 1))) << 4)) = st.v[i];
+    }
+}
+
+// the lane's share of the staged fragment, in the piece order of load_frag
+template <int D>
+__device__ __forceinline__ void frag_from_lds(const char* buf, int ln, int kb, AtFrag<D>& f)
+{
+    constexpr int CH = D / 8;
+#pragma unroll
+    for (int c = 0; c < D / 16; c++) {
+        const int ch = (c >> 1) * 4 + kb * 2 + (c & 1);
+        f.c[c] = *reinterpret_cast<const uint4*>(buf + ln * (D * 2) + ((ch ^ (ln & (CH - 1))) << 4));
+    }
+}
+
+// Pass 1, long sequences: wavefront w owns queries 128 blk + 32 w .. + 31; keys stream through LDS.
+template <int D>
+__global__ __launch_bounds__(kAtThreads) void attn_rowstats_wide_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int T, int n_heads, int group,
+    float scale_log2, int causal, float2* __restrict__ stats)
+{
+    __shared__ __attribute__((aligned(16))) char s_buf[2][32 * D * 2];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int ln = lane & 31, kb = lane >> 5;
+    const int nfrag = (T + 31) >> 5;
+    int blk, h;
+    fragment_and_head((nfrag + 3) >> 2, n_heads, blk, h);
+    const long q_stride = (long)n_heads * D, k_stride = (long)(n_heads / group) * D;
+    const uint16_t* qh = q + (long)h * D;
+    const uint16_t* kh = k + (long)(h / group) * D;
+    const int qf = 4 * blk + wave;
+    const int query = qf * 32 + ln;
+    AtFrag<D> fq, fk;
+    load_frag<D>(qh, q_stride, min(query, T - 1), kb, fq);
+    const int kf_last = causal ? min(4 * blk + 3, nfrag - 1) : nfrag - 1;
+    AtStage<D> st;
+    stage_fetch<D>(kh, k_stride, 0, T, st);
+    stage_store<D>(s_buf[0], st);
+    __syncthreads();
+    float m = kMasked, l = 0.0f;
+    for (int kf = 0; kf <= kf_last; kf++) {
+        const bool more = kf < kf_last;                         // the same in every thread
+        if (more) stage_fetch<D>(kh, k_stride, (kf + 1) * 32, T, st);
+        if (qf < nfrag && (!causal || kf <= qf)) {              // the same in every lane of the wavefront
+            frag_from_lds<D>(s_buf[kf & 1], ln, kb, fk);
+            const float16_t acc = logits_tile<D>(fk, fq);
+            if (kf * 32 + 31 < T && (!causal || kf < qf)) {
+                // nothing to mask (the rule for all but the diagonal and the last fragment): the scale is positive,
+                // so the maximum is taken over the raw logits and the scale rides in the exponent's multiply-add
+                float raw = acc[0];
+#pragma unroll
+                for (int i = 1; i < 16; i++) raw = fmaxf(raw, acc[i]);
+                const float mx = fmaxf(m, raw * scale_log2);
+                float add = 0.0f;
+#pragma unroll
+                for (int i = 0; i < 16; i++) add += __builtin_amdgcn_exp2f(fmaf(acc[i], scale_log2, -mx));
+                l = l * __builtin_amdgcn_exp2f(m - mx) + add;
+                m = mx;
+            } else {
+                float sv[16];
+                float mx = m;
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const int key = tile_key(kf, kb, i);
+                    const bool ok = key < T && (!causal || key <= query);
+                    sv[i] = ok ? acc[i] * scale_log2 : kMasked;
+                    mx = fmaxf(mx, sv[i]);
+                }
+                float add = 0.0f;
+#pragma unroll
+                for (int i = 0; i < 16; i++) add += (sv[i] > 0.5f * kMasked) ? __builtin_amdgcn_exp2f(sv[i] - mx) : 0.0f;
+                l = l * __builtin_amdgcn_exp2f(m - mx) + add;
+                m = mx;
+            }
+        }
+        if (more) stage_store<D>(s_buf[(kf + 1) & 1], st);
+        __syncthreads();
+    }
+    const float m2 = __shfl_xor(m, 32, kWave), l2 = __shfl_xor(l, 32, kWave);
+    const float M = fmaxf(m, m2);
+    const float L = l * __builtin_amdgcn_exp2f(m - M) + l2 * __builtin_amdgcn_exp2f(m2 - M);
+    // one number per query is all pass 2 needs: p = exp2(logit' - (m + log2 l))
+    if (kb == 0 && query < T) stats[(long)h * T + query] = make_float2(M + __builtin_amdgcn_logf(L), 0.0f);
+}
+
+// Pass 2, long sequences: wavefront w owns keys 128 blk + 32 w .. + 31; queries stream through LDS.
+template <int D>
+__global__ __launch_bounds__(kAtThreads) void attn_colsum_wide_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int T, int n_heads, int group,
+    float scale_log2, int causal, const float2* __restrict__ stats, float* __restrict__ partial)
+{
+    __shared__ __attribute__((aligned(16))) char s_buf[2][32 * D * 2];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int ln = lane & 31, kb = lane >> 5;
+    const int nfrag = (T + 31) >> 5;
+    int blk, h;
+    fragment_and_head((nfrag + 3) >> 2, n_heads, blk, h);
+    const long q_stride = (long)n_heads * D, k_stride = (long)(n_heads / group) * D;
+    const uint16_t* qh = q + (long)h * D;
+    const uint16_t* kh = k + (long)(h / group) * D;
+    const float2* sh = stats + (long)h * T;
+    const int kf = 4 * blk + wave;
+    AtFrag<D> fk, fq;
+    load_frag<D>(kh, k_stride, min(kf * 32 + ln, T - 1), kb, fk);
+    const int qf_first = causal ? 4 * blk : 0;
+    AtStage<D> st;
+    stage_fetch<D>(qh, q_stride, qf_first * 32, T, st);
+    stage_store<D>(s_buf[0], st);
+    __syncthreads();
+    float col[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) col[i] = 0.0f;
+    for (int qf = qf_first; qf < nfrag; qf++) {
+        const bool more = qf + 1 < nfrag;
+        if (more) stage_fetch<D>(qh, q_stride, (qf + 1) * 32, T, st);
+        if (kf < nfrag && (!causal || qf >= kf)) {
+            const int query = qf * 32 + ln;
+            const float shift = -sh[min(query, T - 1)].x;
+            frag_from_lds<D>(s_buf[(qf - qf_first) & 1], ln, kb, fq);
+            const float16_t acc = logits_tile<D>(fk, fq);
+            if (qf * 32 + 31 < T && kf * 32 + 31 < T && (!causal || kf < qf)) {
+#pragma unroll
+                for (int i = 0; i < 16; i++) col[i] += __builtin_amdgcn_exp2f(fmaf(acc[i], scale_log2, shift));
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const int key = tile_key(kf, kb, i);
+                    const bool ok = query < T && key < T && (!causal || key <= query);
+                    const float p = __builtin_amdgcn_exp2f(fmaf(acc[i], scale_log2, shift));
+                    col[i] += ok ? p : 0.0f;
+                }
+            }
+        }
+        if (more) stage_store<D>(s_buf[(qf + 1 - qf_first) & 1], st);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        float v = col[i];
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+        col[i] = v;
+    }
+    if (ln == 0 && kf < nfrag) {
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int key = tile_key(kf, kb, i);
+            if (key < T) partial[(long)h * T + key] = col[i];
+        }
+    }
+}
+
 // s[i] = (sum over heads, in head order) / (Hh T)
 __global__ __launch_bounds__(256) void attn_score_kernel(const float* __restrict__ partial, int T, int n_heads,
                                                          float inv, float* __restrict__ score)
@@ -249,20 +440,29 @@ int dymoe_token_score_attention(dymoe_ctx* ctx, const void* q, const void* k, in
     const float s = (scale > 0.0f) ? scale : 1.0f / sqrtf((float)head_dim);
     const float scale_log2 = s * 1.44269504088896340736f;
     const int nfrag = (T + 31) / 32;
-    const dim3 grid((unsigned)nfrag, (unsigned)n_heads);      // one workgroup per (32-token fragment, head)
-    if (head_dim == 64) {
-        dymoe_launch(ctx, DYMOE_K_ATTN_STATS, dymoe::attn_rowstats_kernel<64>, grid, dim3(dymoe::kAtThreads), 0, st,
-                     qb, kbp, T, n_heads, group, scale_log2, causal, stats);
-        DYMOE_HIP_LAUNCH_CHECK();
-        dymoe_launch(ctx, DYMOE_K_ATTN_COLSUM, dymoe::attn_colsum_kernel<64>, grid, dim3(dymoe::kAtThreads), 0, st,
-                     qb, kbp, T, n_heads, group, scale_log2, causal, (const float2*)stats, partial);
-    } else {
-        dymoe_launch(ctx, DYMOE_K_ATTN_STATS, dymoe::attn_rowstats_kernel<128>, grid, dim3(dymoe::kAtThreads), 0, st,
-                     qb, kbp, T, n_heads, group, scale_log2, causal, stats);
-        DYMOE_HIP_LAUNCH_CHECK();
-        dymoe_launch(ctx, DYMOE_K_ATTN_COLSUM, dymoe::attn_colsum_kernel<128>, grid, dim3(dymoe::kAtThreads), 0, st,
-                     qb, kbp, T, n_heads, group, scale_log2, causal, (const float2*)stats, partial);
-    }
+    // short sequences: a workgroup per 32-token fragment (many workgroups, operands straight from global memory);
+    // long ones: a workgroup per 128 tokens with the streamed operand shared through LDS
+    const bool wide = nfrag >= dymoe::kAtWideFrags;
+    const dim3 grid((unsigned)(wide ? (nfrag + 3) / 4 : nfrag), (unsigned)n_heads);
+#define DYMOE_ATTN_LAUNCH(D_)                                                                                          \
+    do {                                                                                                               \
+        if (wide) {                                                                                                    \
+            dymoe_launch(ctx, DYMOE_K_ATTN_STATS, dymoe::attn_rowstats_wide_kernel<D_>, grid, dim3(dymoe::kAtThreads), 0, st, \
+                         qb, kbp, T, n_heads, group, scale_log2, causal, stats);                                       \
+            DYMOE_HIP_LAUNCH_CHECK();                                                                                  \
+            dymoe_launch(ctx, DYMOE_K_ATTN_COLSUM, dymoe::attn_colsum_wide_kernel<D_>, grid, dim3(dymoe::kAtThreads), 0, st, \
+                         qb, kbp, T, n_heads, group, scale_log2, causal, (const float2*)stats, partial);               \
+        } else {                                                                                                       \
+            dymoe_launch(ctx, DYMOE_K_ATTN_STATS, dymoe::attn_rowstats_kernel<D_>, grid, dim3(dymoe::kAtThreads), 0, st,  \
+                         qb, kbp, T, n_heads, group, scale_log2, causal, stats);                                       \
+            DYMOE_HIP_LAUNCH_CHECK();                                                                                  \
+            dymoe_launch(ctx, DYMOE_K_ATTN_COLSUM, dymoe::attn_colsum_kernel<D_>, grid, dim3(dymoe::kAtThreads), 0, st,   \
+                         qb, kbp, T, n_heads, group, scale_log2, causal, (const float2*)stats, partial);               \
+        }                                                                                                              \
+    } while (0)
+    if (head_dim == 64) DYMOE_ATTN_LAUNCH(64);
+    else DYMOE_ATTN_LAUNCH(128);
+#undef DYMOE_ATTN_LAUNCH
     DYMOE_HIP_LAUNCH_CHECK();
     hipLaunchKernelGGL(dymoe::attn_score_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st,
                        (const float*)partial, T, n_heads, 1.0f / ((float)n_heads * (float)T), score);

@@ -28,6 +28,8 @@
  *                        precision), the rest low precision or 0-bit (skipped).
  *   prefetch frequency   Sec. 4.4.1 token-frequency count c_e (same histogram
  *                        as the total load returned by the importance step).
+ *   error-compensated   Sec. 5 (GPTQ as the base quantizer): see
+ *   quantizer            oracle_gptq_quantize_pack.
  * The paper leaves the quantizer (it uses an off-line one and says the base
  * algorithm is exchangeable) and the expert FFN form unstated; this build
  * uses asymmetric group-wise round-to-nearest with fp16 scale and fp16 zero
@@ -379,6 +381,83 @@ int oracle_quantize_pack(const uint16_t* w, long N, long K, int bits, int group,
             }
         }
     }
+    return 0;
+}
+
+/*
+ * Error-compensated variant of the quantizer (paper Sec. 5: the experts are
+ * quantised with GPTQ, "the basic quantization algorithm" of the paper's
+ * implementation; the published algorithm is followed, restated here).
+ *
+ * A row of W is quantised column by column.  What rounding takes away from
+ * column c is spread over the columns not yet quantised so that the layer
+ * output on the calibration inputs changes least: with H = X^T X (+ damping)
+ * the Hessian of that error and U the upper triangular factor of its inverse,
+ * H^-1 = U^T U, the correction of column j > c is  -e U[c,j],  e = (w_c -
+ * dequant(q_c)) / U[c,c].  Scale and zero of a group are fixed when its first
+ * column is reached, from the row's current (already corrected) values, by
+ * the same rule as the plain quantizer above; so are the codes.
+ *
+ * Like the plain quantizer this is an exact sequence of binary32 operations
+ * (each line one correctly rounded operation, the correction one fused
+ * multiply-add per column pair, columns c in ascending order):
+ *   v[0..K) = (float) w[n, :]
+ *   for each group g, columns base .. base + group - 1:
+ *     lo, hi = min, max of v over the group;   zero, scale, m, s, inv as above
+ *     for c in the group:
+ *       q  = clamp(rint((v[c] - m) * inv), 0, qmax)
+ *       dq = (float)q * s;  dq = dq + m
+ *       e  = (v[c] - dq) / U[c,c]
+ *       v[j] = fma(-e, U[c,j], v[j])   for j = c+1 .. K-1
+ * u [K,K] fp32 row-major (only the upper triangle is read).  Outputs as
+ * oracle_quantize_pack.
+ */
+int oracle_gptq_quantize_pack(const uint16_t* w, long N, long K, int bits, int group, const float* u,
+                              uint8_t* codes, uint16_t* scale, uint16_t* zero)
+{
+    if ((bits != 2 && bits != 4 && bits != 8) || group <= 0 || K % group != 0) return -1;
+    const int per_byte = 8 / bits;
+    if (group % per_byte != 0) return -1;
+    const int qmax = (1 << bits) - 1;
+    const long G = K / group;
+    float* v = (float*)malloc((size_t)K * sizeof(float));
+    if (!v) return -2;
+    memset(codes, 0, (size_t)(N * K * bits / 8));
+    for (long n = 0; n < N; n++) {
+        for (long j = 0; j < K; j++) v[j] = bf16_to_f32(w[n * K + j]);
+        for (long g = 0; g < G; g++) {
+            const long base = g * group;
+            float lo = v[base];
+            float hi = lo;
+            for (int i = 1; i < group; i++) {
+                if (v[base + i] < lo) lo = v[base + i];
+                if (v[base + i] > hi) hi = v[base + i];
+            }
+            uint16_t zh = f32_to_f16_rne(lo);
+            float range = hi - lo;
+            float step = range / (float)qmax;
+            uint16_t sh = f32_to_f16_rne(step);
+            float m = f16_to_f32(zh);
+            float s = f16_to_f32(sh);
+            float inv = (s > 0.0f) ? (1.0f / s) : 0.0f;
+            scale[n * G + g] = sh;
+            zero[n * G + g] = zh;
+            for (int i = 0; i < group; i++) {
+                const long c = base + i;
+                float d = v[c] - m;
+                float r = rintf(d * inv);
+                if (r < 0.0f) r = 0.0f;
+                if (r > (float)qmax) r = (float)qmax;
+                int q = (int)r;
+                codes[n * (K * bits / 8) + c / per_byte] |= (uint8_t)(q << (bits * (int)(c % per_byte)));
+                float dq = r * s;
+                dq = dq + m;
+                float e = (v[c] - dq) / u[c * K + c];
+                for (long j = c + 1; j < K; j++) v[j] = fmaf(-e, u[c * K + j], v[j]);
+            }
+        }
+    }
+    free(v);
     return 0;
 }
 

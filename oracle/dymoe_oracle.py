@@ -369,3 +369,111 @@ def token_score_attention(q_bits, k_bits, n_heads, n_kv_heads, causal=True, scal
         p /= p.sum(axis=1, keepdims=True)
         s += p.sum(axis=0)
     return s / (n_heads * T)
+
+
+# ---------------------------------------------------------------------------
+# Error-compensated quantizer (paper Sec. 5: GPTQ is the base quantizer of the
+# paper's implementation).  Hessian and its factor in fp64 with numpy's linear
+# algebra as library steps; the column sweep is the C function (binary32, the
+# sequence the GPU must reproduce), with an fp64 twin and the textbook
+# one-column-at-a-time form beside it for the pins.
+
+_lib.oracle_gptq_quantize_pack.restype = C.c_int
+_lib.oracle_gptq_quantize_pack.argtypes = [_u16p, C.c_long, C.c_long, C.c_int, C.c_int, _f32p, _u8p, _u16p, _u16p]
+
+
+def gptq_hessian(x_bits):
+    """H = X^T X over the calibration rows x [n, K] (bf16 bit patterns), fp64."""
+    x = _widen_bf16(x_bits).astype(np.float64)
+    return x.T @ x
+
+
+def gptq_damped(hess, damp=0.01):
+    """H + damp * mean(diag H) * I; a column that never saw an input (H[c,c] = 0) gets H[c,c] = 1 first."""
+    h = np.array(hess, dtype=np.float64, copy=True)
+    d = np.diagonal(h).copy()
+    d[d == 0.0] = 1.0
+    np.fill_diagonal(h, d)
+    h[np.diag_indices_from(h)] += damp * d.mean()
+    return h
+
+
+def gptq_factor(hess, damp=0.01):
+    """Upper triangular U with (damped H)^-1 = U^T U, positive diagonal."""
+    return np.linalg.cholesky(np.linalg.inv(gptq_damped(hess, damp))).T.copy()
+
+
+def gptq_quantize_pack(w_bits, u, bits, group=64):
+    """The binary32 sweep.  u [K,K] (rounded to fp32 here if it is not).  Returns codes, scale, zero."""
+    w = _c(w_bits, np.uint16)
+    N, K = w.shape
+    uf = _c(u, np.float32)
+    assert uf.shape == (K, K)
+    codes = np.zeros((N, K * bits // 8), np.uint8)
+    scale = np.zeros((N, K // group), np.uint16)
+    zero = np.zeros((N, K // group), np.uint16)
+    rc = _lib.oracle_gptq_quantize_pack(_ptr(w, _u16p), N, K, bits, group, _ptr(uf, _f32p), _ptr(codes, _u8p),
+                                        _ptr(scale, _u16p), _ptr(zero, _u16p))
+    if rc != 0:
+        raise ValueError("oracle_gptq_quantize_pack rc=%d" % rc)
+    return codes, scale, zero
+
+
+def _grid_f64(lo, hi, qmax):
+    """Scale and zero of a group as the quantizer stores them (fp16), as fp64 numbers."""
+    m = np.array([f16_to_f32(f32_to_f16(float(np.float32(v)))) for v in lo])
+    step = (np.float32(hi) - np.float32(lo)) / np.float32(qmax)
+    s = np.array([f16_to_f32(f32_to_f16(float(v))) for v in step])
+    return s, m
+
+
+def gptq_sweep_f64(w, u, bits, group=64):
+    """The same sweep in fp64 (group grids rounded to fp16 as stored).  Returns integer codes [N,K] and
+    the dequantised matrix."""
+    v = np.array(w, dtype=np.float64, copy=True)
+    N, K = v.shape
+    qmax = (1 << bits) - 1
+    q = np.zeros((N, K), np.int64)
+    deq = np.zeros((N, K))
+    for c in range(K):
+        if c % group == 0:
+            blk = v[:, c:c + group]
+            s, m = _grid_f64(blk.min(axis=1), blk.max(axis=1), qmax)
+            inv = np.where(s > 0, 1.0 / np.where(s > 0, s, 1.0), 0.0)
+        q[:, c] = np.clip(np.rint((v[:, c] - m) * inv), 0, qmax)
+        deq[:, c] = q[:, c] * s + m
+        e = (v[:, c] - deq[:, c]) / u[c, c]
+        v[:, c + 1:] -= np.outer(e, u[c, c + 1:])
+    return q, deq
+
+
+def gptq_sweep_textbook(w, hess_damped, bits, group=64):
+    """One column at a time, from the definition: quantise column c, move every remaining weight by
+    -(w_c - dq_c) / [H^-1]_cc * H^-1[c, :] (the minimiser of the output error with w_c pinned), then drop
+    column c from the problem (H^-1 of the remaining columns by eliminating row and column c)."""
+    v = np.array(w, dtype=np.float64, copy=True)
+    N, K = v.shape
+    qmax = (1 << bits) - 1
+    hinv = np.linalg.inv(hess_damped)
+    q = np.zeros((N, K), np.int64)
+    deq = np.zeros((N, K))
+    for c in range(K):
+        if c % group == 0:
+            blk = v[:, c:c + group]
+            s, m = _grid_f64(blk.min(axis=1), blk.max(axis=1), qmax)
+            inv = np.where(s > 0, 1.0 / np.where(s > 0, s, 1.0), 0.0)
+        q[:, c] = np.clip(np.rint((v[:, c] - m) * inv), 0, qmax)
+        deq[:, c] = q[:, c] * s + m
+        err = (v[:, c] - deq[:, c]) / hinv[c, c]
+        v[:, c + 1:] -= np.outer(err, hinv[c, c + 1:])
+        hinv = hinv - np.outer(hinv[:, c], hinv[c, :]) / hinv[c, c]
+        hinv[c, :] = 0.0
+        hinv[:, c] = 0.0
+        hinv[c, c] = 1.0                         # keeps the slot harmless; column c is never read again
+    return q, deq
+
+
+def output_error(w, deq, hess):
+    """sum over rows of (w - deq) H (w - deq)^T = || (W - What) X^T ||_F^2 on the calibration inputs."""
+    d = np.asarray(w, np.float64) - deq
+    return float(np.einsum("nk,kj,nj->", d, hess, d))

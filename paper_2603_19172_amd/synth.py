@@ -169,3 +169,22 @@ def attention_inputs(cfg: MoEConfig, n_heads: int, n_kv_heads: int, head_dim: in
     if heavy.size:
         k[heavy] += boost * u[None, :, :]
     return f32_to_bf16_bits(q), f32_to_bf16_bits(k), heavy
+
+
+_TID_CALIB = 3000
+
+
+def calibration_inputs(config_id: int, n: int, K: int, rank: int = 4, strength: float = 1.5) -> np.ndarray:
+    """Calibration activations [n, K] as bf16 bits for the error-compensated quantizer: unit Gaussians plus
+    `rank` shared directions of weight `strength` (trained models' activations are strongly correlated
+    across channels, which is what error compensation exploits), and per-channel magnitudes spread
+    log-uniformly over a factor 4 (a few loud channels)."""
+    rz = _rng(config_id, _TID_CALIB + 0)
+    ra = _rng(config_id, _TID_CALIB + 1)
+    rb = _rng(config_id, _TID_CALIB + 2)
+    rs = _rng(config_id, _TID_CALIB + 3)
+    x = rz.standard_normal((n, K), dtype=np.float32)
+    if rank > 0:
+        x += strength * (ra.standard_normal((n, rank), dtype=np.float32) @ rb.standard_normal((rank, K), dtype=np.float32))
+    x *= np.exp2(rs.uniform(-1.0, 1.0, size=(1, K))).astype(np.float32)
+    return f32_to_bf16_bits(x)

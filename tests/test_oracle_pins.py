@@ -609,3 +609,115 @@ def test_attention_inputs_make_the_heavy_hitters_score_highest():
     assert heavy.size == 13
     s = O.token_score_attention(q, k, 8, 2, causal=False)
     assert set(np.argsort(-s)[:13].tolist()) == set(heavy.tolist())
+
+
+# ------------------------------------------------- error-compensated quantizer (Sec. 5: GPTQ)
+
+def _calib_case(cid, N, K, n=384, sigma=0.02):
+    xb = synth.calibration_inputs(cid, n, K)
+    wb = synth.normal_bf16(cid, 77, (N, K), sigma)
+    return xb, wb, widen(wb)
+
+
+def test_gptq_hessian_brute_force():
+    xb = synth.calibration_inputs(911, 9, 6, rank=2)
+    x = widen(xb)
+    want = np.zeros((6, 6))
+    for s in range(9):
+        for i in range(6):
+            for j in range(6):
+                want[i, j] += x[s, i] * x[s, j]
+    got = O.gptq_hessian(xb)
+    assert np.allclose(got, want, rtol=1e-13, atol=0) and np.array_equal(got, got.T)
+
+
+def test_gptq_factor_closed_forms_and_definition():
+    # 2 x 2 without damping: H^-1 = [[c, -b], [-b, a]] / det  =>  U = [[sqrt(c/det), -b/sqrt(c det)], [0, 1/sqrt(c)]]
+    a, b, c = 5.0, 1.5, 2.0
+    det = a * c - b * b
+    U = O.gptq_factor(np.array([[a, b], [b, c]]), damp=0.0)
+    assert np.allclose(U, [[np.sqrt(c / det), -b / np.sqrt(c * det)], [0.0, 1.0 / np.sqrt(c)]], rtol=1e-13)
+    # diagonal H with damping: U = diag(1 / sqrt(h + damp mean h)); a dead column counts as h = 1
+    h = np.array([4.0, 0.0, 9.0, 1.0])
+    hd = np.array([4.0, 1.0, 9.0, 1.0])
+    U = O.gptq_factor(np.diag(h), damp=0.1)
+    assert np.allclose(U, np.diag(1.0 / np.sqrt(hd + 0.1 * hd.mean())), rtol=1e-13)
+    # general: upper triangular, positive diagonal, U^T U (H + damping) = I
+    xb, _, _ = _calib_case(912, 1, 192)
+    H = O.gptq_hessian(xb)
+    U = O.gptq_factor(H, damp=0.01)
+    assert np.array_equal(U, np.triu(U)) and (np.diag(U) > 0).all()
+    Hd = H + 0.01 * np.mean(np.diag(H)) * np.eye(192)
+    assert np.abs(U.T @ U @ Hd - np.eye(192)).max() < 1e-8
+
+
+def test_gptq_sweep_hand_example():
+    """One group of 4 columns, 2 bits: lo = 0, hi = 3, scale 1, zero 0.  Column 1 holds 0.375 -> code 0,
+    error 0.375, divided by U[1,1] = 0.5 -> e = 0.75; U[1,2] = -1 moves column 2 from 1.0 to 1.75 -> code 2
+    (plain rounding gives 1).  A flipped sign gives 0.25 -> 0, a transposed U or a dropped update gives 1,
+    a dropped division gives 1.375 -> 1."""
+    w = bf16(np.array([[0.0, 0.375, 1.0, 3.0]]))
+    U = np.eye(4)
+    U[1, 1] = 0.5
+    U[1, 2] = -1.0
+    codes, scale, zero = O.gptq_quantize_pack(w, U, 2, group=4)
+    assert O.f16_to_f32(int(scale[0, 0])) == 1.0 and O.f16_to_f32(int(zero[0, 0])) == 0.0
+    assert codes[0, 0] == (0 | 0 << 2 | 2 << 4 | 3 << 6)
+    plain, _, _ = O.quantize_pack(w, 2, group=4)
+    assert plain[0, 0] == (0 | 0 << 2 | 1 << 4 | 3 << 6)
+    # the same through the fp64 twin and the one-column-at-a-time form (H^-1 = U^T U)
+    q, _ = O.gptq_sweep_f64(widen(w), U, 2, group=4)
+    assert q.tolist() == [[0, 0, 2, 3]]
+    q, _ = O.gptq_sweep_textbook(widen(w), np.linalg.inv(U.T @ U), 2, group=4)
+    assert q.tolist() == [[0, 0, 2, 3]]
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_gptq_identity_factor_is_the_plain_quantizer(bits):
+    _, wb, _ = _calib_case(913, 24, 192)
+    got = O.gptq_quantize_pack(wb, np.eye(192), bits)
+    want = O.quantize_pack(wb, bits)
+    for g, r in zip(got, want):
+        assert np.array_equal(g, r)
+    # and a factor scaled by a power of two changes nothing (e / U[c,c] * U[c,j] is scale free)
+    xb, _, _ = _calib_case(913, 1, 192)
+    U = O.gptq_factor(O.gptq_hessian(xb)).astype(np.float32)
+    a = O.gptq_quantize_pack(wb, U, bits)
+    b = O.gptq_quantize_pack(wb, U * np.float32(4.0), bits)
+    for g, r in zip(a, b):
+        assert np.array_equal(g, r)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_gptq_factor_rows_equal_the_column_by_column_definition(bits):
+    """The sweep with rows of U is the textbook procedure (quantise a column, correct the rest with the
+    current inverse Hessian, eliminate the column): same codes, same corrected weights."""
+    xb, wb, w = _calib_case(914 + bits, 12, 192)
+    H = O.gptq_hessian(xb)
+    Hd = O.gptq_damped(H)
+    U = O.gptq_factor(H)
+    q1, d1 = O.gptq_sweep_f64(w, U, bits)
+    q2, d2 = O.gptq_sweep_textbook(w, Hd, bits)
+    assert np.array_equal(q1, q2) and np.abs(d1 - d2).max() < 1e-9
+    # binary32 sweep against the fp64 twin: a near-tie may flip a code here and there, nothing more
+    codes, sc, ze = O.gptq_quantize_pack(wb, U, bits)
+    d3 = O.dequantize(codes, sc, ze, bits)
+    assert (d3 == d1).mean() > 0.995
+    e1, e3 = O.output_error(w, d1, H), O.output_error(w, d3, H)
+    assert abs(e3 - e1) <= 0.02 * e1
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_gptq_lowers_the_output_error_on_correlated_inputs(bits):
+    xb, wb, w = _calib_case(920, 32, 256, n=512)
+    H = O.gptq_hessian(xb)
+    U = O.gptq_factor(H)
+    codes, sc, ze = O.gptq_quantize_pack(wb, U, bits)
+    plain = O.quantize_pack(wb, bits)
+    e_comp = O.output_error(w, O.dequantize(codes, sc, ze, bits), H)
+    e_plain = O.output_error(w, O.dequantize(*plain, bits), H)
+    # measured directly on the inputs, not through H: || (W - What) X^T ||^2
+    x = widen(xb)
+    direct = float((((w - O.dequantize(codes, sc, ze, bits)) @ x.T) ** 2).sum())
+    assert abs(direct - e_comp) <= 1e-9 * e_comp
+    assert e_comp < 0.5 * e_plain

@@ -254,6 +254,33 @@ int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits,
                         uint8_t* codes, void* scale, void* zero, void* stream);
 
 /*
+ * Error-compensated quantize-and-pack (the paper, Sec. 5, quantizes the experts
+ * with GPTQ as its base algorithm; the published algorithm, restated).  Same
+ * outputs and formats as dymoe_quantize_pack, row-major, so the FFN reads them
+ * unchanged.  A row is quantised column by column; with U the upper triangular
+ * factor of the inverse of the damped Hessian of the calibration inputs,
+ * H^-1 = U^T U, in binary32, one correctly rounded operation per step, columns
+ * c in ascending order, v the row widened to fp32:
+ *   at the first column of a group: lo, hi, zero, scale, m, s, inv from the
+ *     group's current values, as in dymoe_quantize_pack
+ *   q  = clamp(rint((v[c] - m) * inv), 0, 2^bits-1)
+ *   dq = (float)q * s;  dq = dq + m
+ *   e  = (v[c] - dq) / U[c,c]
+ *   v[j] = fma(-e, U[c,j], v[j])          for every j > c
+ * u [K,K] fp32 row-major, device, 16-byte aligned (only the upper triangle is
+ * read; U[c,c] > 0); from dymoe_gptq_factor or the caller's own.  The identity
+ * gives dymoe_quantize_pack's result.  workspace: dymoe_gptq_workspace_bytes(N,
+ * K) bytes of device memory, 256-byte aligned (an fp32 copy of the matrix and
+ * 64 errors per row); its contents are garbage afterwards.  Other arguments,
+ * limits and errors as dymoe_quantize_pack; DYMOE_ENOSPC if the workspace is
+ * too small.  Enqueues 2 K/64 launches on `stream`; never synchronises.
+ */
+size_t dymoe_gptq_workspace_bytes(long N, long K);
+int dymoe_gptq_quantize_pack(dymoe_ctx* ctx, const void* w, const float* u, long N, long K, int bits, int group,
+                             uint8_t* codes, void* scale, void* zero, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/*
  * Device-driven quantization of a layer's experts, so that the precision
  * decision never travels to the host: for each expert e with bits[e] in {2,4,8}
  * (and load[e] > 0 when load is given), quantize table[e].w[0..3) at bits[e]
@@ -399,9 +426,10 @@ size_t dymoe_cache_bytes_resident(const dymoe_cache* cache);
  * Per-kernel timing (diagnostic; the paper reports only end-to-end latency,
  * Sec. 6.1 "Key Metrics", so these serve the roofline accounting).
  * dymoe_timing_enable: launches of the kernels whose bit is set in kernel_mask
- * (bit i = kernel id i, ids 0..15 in the order route, token_norm, importance,
+ * (bit i = kernel id i, ids 0..17 in the order route, token_norm, importance,
  * assign, quantize, gemv_phase1, gemv_phase2, gemv_combine, plan, gemm1, gemm2,
- * gemm_combine, stream_copy, decode_front, attn_stats, attn_colsum) carry a start and a stop HIP event on the dispatch itself, so
+ * gemm_combine, stream_copy, decode_front, attn_stats, attn_colsum, gptq_group,
+ * gptq_trail) carry a start and a stop HIP event on the dispatch itself, so
  * the interval is the kernel's execution time on the launch stream; 0 switches
  * timing off.  Either way, records not yet read are dropped.
  * dymoe_timing_read: waits for the recorded launches of `kernel`, drops their records and returns

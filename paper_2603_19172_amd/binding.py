@@ -34,6 +34,7 @@ EXPORTS = [
     "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_attention_workspace_bytes",
     "dymoe_token_score_attention", "dymoe_expert_importance",
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
+    "dymoe_gptq_workspace_bytes", "dymoe_gptq_quantize_pack",
     "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_moe_ffn_mixed", "dymoe_stream_copy",
     "dymoe_decode_front", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
     "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
@@ -44,7 +45,7 @@ EXPORTS = [
 
 KERNELS = ["route", "token_norm", "importance", "assign", "quantize", "gemv_phase1",
            "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine", "stream_copy", "decode_front",
-           "attn_stats", "attn_colsum"]
+           "attn_stats", "attn_colsum", "gptq_group", "gptq_trail"]
 
 
 class ExpertFmt(C.Structure):
@@ -117,6 +118,10 @@ lib.dymoe_assign_precision.restype = _i
 lib.dymoe_assign_precision.argtypes = [_vp, _i, _vp, _vp, _i, _i, _vp, _vp, _i, _vp, _vp, _vp]
 lib.dymoe_quantize_pack.restype = _i
 lib.dymoe_quantize_pack.argtypes = [_vp, _vp, _l, _l, _i, _i, _vp, _vp, _vp, _vp]
+lib.dymoe_gptq_workspace_bytes.restype = _sz
+lib.dymoe_gptq_workspace_bytes.argtypes = [_l, _l]
+lib.dymoe_gptq_quantize_pack.restype = _i
+lib.dymoe_gptq_quantize_pack.argtypes = [_vp, _vp, _vp, _l, _l, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.dymoe_quantize_experts.restype = _i
 lib.dymoe_quantize_experts.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]
 lib.dymoe_pack_tiles.restype = _i
@@ -296,6 +301,25 @@ class Context:
                                        _ptr(codes, torch.uint8), _ptr(scale, torch.float16),
                                        _ptr(zero, torch.float16), _stream(stream)),
                "dymoe_quantize_pack")
+        return codes, scale, zero
+
+    def gptq_quantize_pack(self, w, u, bits, group=64, out=None, workspace=None, stream=None):
+        """Error-compensated quantize-and-pack of w [N,K] bf16 with the factor u [K,K] fp32."""
+        N, K = w.shape
+        dev = w.device
+        if out is None:
+            codes = torch.empty((N, K * bits // 8), dtype=torch.uint8, device=dev)
+            scale = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+            zero = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+        else:
+            codes, scale, zero = out
+        need = int(lib.dymoe_gptq_workspace_bytes(N, K))
+        if workspace is None:
+            workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+        _check(lib.dymoe_gptq_quantize_pack(self._h, _ptr(w, torch.bfloat16), _ptr(u, torch.float32), N, K, bits,
+                                            group, _ptr(codes, torch.uint8), _ptr(scale, torch.float16),
+                                            _ptr(zero, torch.float16), _ptr(workspace, torch.uint8),
+                                            workspace.numel(), _stream(stream)), "dymoe_gptq_quantize_pack")
         return codes, scale, zero
 
     def quantize_experts(self, table, bits, load, E, H, F, group=64, layout=LAYOUT_ROWMAJOR,

@@ -20,17 +20,16 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, 
           # no compiler-generated packed-fp32 arithmetic
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
-# quantize.hip must reproduce an exact sequence of binary32 operations
-PER_FILE = {"quantize.hip": ["-ffp-contract=off"]}
+# quantize.hip and gptq.hip must reproduce an exact sequence of binary32 operations
+PER_FILE = {"quantize.hip": ["-ffp-contract=off"], "gptq.hip": ["-ffp-contract=off"]}
 
 SOURCES = ["api.hip", "route.hip", "importance.hip", "quantize.hip", "ffn.hip", "ffn_gemv.hip",
-           "ffn_gemm.hip", "prefetch.hip", "attention.hip", "expert_cache.cpp"]
+           "ffn_gemm.hip", "prefetch.hip", "attention.hip", "gptq.hip", "expert_cache.cpp"]
 
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    extra = os.environ.get("DYMOE_EXTRA_HIPCC", "").split()      # e.g. -D knobs while tuning
-    cmd = ["hipcc", *COMMON, *PER_FILE.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *COMMON, *PER_FILE.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -130,6 +130,8 @@ const char* dymoe_kernel_name(int kernel)
     case DYMOE_K_DECODE_FRONT: return "decode_front_kernel";
     case DYMOE_K_ATTN_STATS: return "attn_rowstats_kernel";
     case DYMOE_K_ATTN_COLSUM: return "attn_colsum_kernel";
+    case DYMOE_K_GPTQ_GROUP: return "gptq_group_kernel";
+    case DYMOE_K_GPTQ_TRAIL: return "gptq_trail_kernel";
     default: return nullptr;
     }
 }

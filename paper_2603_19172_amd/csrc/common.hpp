@@ -27,6 +27,8 @@ enum {
     DYMOE_K_DECODE_FRONT,
     DYMOE_K_ATTN_STATS,
     DYMOE_K_ATTN_COLSUM,
+    DYMOE_K_GPTQ_GROUP,
+    DYMOE_K_GPTQ_TRAIL,
     DYMOE_K_COUNT
 };
 

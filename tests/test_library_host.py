@@ -125,6 +125,18 @@ def test_argument_validation_happens_before_any_device_work():
     assert ta(None, P + 2, P, 77, 8, 2, 128, 0.0, 1, P, P, aw, None) == B.EINVAL
     assert ta(None, P, P, 77, 8, 2, 128, 0.0, 1, None, P, aw, None) == B.EINVAL
     assert ta(None, None, None, 0, 8, 2, 128, 0.0, 1, None, None, 0, None) == B.ENOCTX   # T = 0 needs only a context
+    # error-compensated quantizer
+    gq = lib.dymoe_gptq_quantize_pack
+    gw = int(lib.dymoe_gptq_workspace_bytes(100, 256))
+    assert gw >= 100 * 256 * 4 + 64 * 128 * 4 and gw % 256 == 0 and lib.dymoe_gptq_workspace_bytes(0, 256) == 0
+    assert gq(None, P, P, 100, 256, 4, 64, P, P, P, P, gw, None) == B.ENOCTX
+    assert gq(None, P, P, 100, 256, 4, 64, P, P, P, P, gw - 1, None) == B.ENOSPC
+    assert gq(None, P, P, 100, 256, 3, 64, P, P, P, P, gw, None) == B.EINVAL
+    assert gq(None, P, P, 100, 250, 4, 64, P, P, P, P, gw, None) == B.EINVAL
+    assert gq(None, P, P, 100, 256, 4, 32, P, P, P, P, gw, None) == B.EINVAL
+    assert gq(None, P, None, 100, 256, 4, 64, P, P, P, P, gw, None) == B.EINVAL
+    assert gq(None, P, P + 4, 100, 256, 4, 64, P, P, P, P, gw, None) == B.EINVAL
+    assert gq(None, P, P, 100, 256, 4, 64, P, P, P, P + 16, gw, None) == B.EINVAL     # workspace alignment
     # stream copy
     assert lib.dymoe_stream_copy(None, P, 2 * P, 1024, None) == B.ENOCTX
     assert lib.dymoe_stream_copy(None, P, 2 * P, 1000, None) == B.EINVAL

@@ -275,6 +275,27 @@ int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits,
  * limits and errors as dymoe_quantize_pack; DYMOE_ENOSPC if the workspace is
  * too small.  Enqueues 2 K/64 launches on `stream`; never synchronises.
  */
+/*
+ * The two steps before it (GPTQ as published; Sec. 5 of the paper only names it).
+ * dymoe_gptq_hessian: hess (+)= X^T X over calibration inputs x [n, K] bf16 (rows
+ * = tokens entering the matrix), hess [K, K] fp32 row-major, both device, 16-byte
+ * aligned; accumulate = 0 overwrites, 1 adds to what hess holds (several batches).
+ * bf16 products are exact, sums are fp32 on the matrix cores.  K multiple of 8,
+ * K <= 65536.
+ * dymoe_gptq_factor: u = the upper triangular U with (H + lambda I)^-1 = U^T U,
+ * lambda = damp * mean(diag H); a diagonal entry that is exactly zero (a column
+ * no input ever reached) counts as 1 and becomes 1 (+ lambda).  fp32 throughout.
+ * hess is read only; u [K, K] fp32, fully written (zeros below the diagonal);
+ * workspace of dymoe_gptq_factor_workspace_bytes(K) bytes (two K x K fp32
+ * matrices and change), 256-byte aligned.  K multiple of 64, K <= 65536, damp >=
+ * 0 (the published default is 0.01).  H + lambda I must be positive definite in
+ * fp32 (a square root of a negative pivot gives NaNs in u, nothing is checked).
+ * Errors as elsewhere; both enqueue on `stream` and return without waiting.
+ */
+int dymoe_gptq_hessian(dymoe_ctx* ctx, const void* x, long n, long K, int accumulate, float* hess, void* stream);
+size_t dymoe_gptq_factor_workspace_bytes(long K);
+int dymoe_gptq_factor(dymoe_ctx* ctx, const float* hess, long K, float damp, float* u, void* workspace,
+                      size_t workspace_bytes, void* stream);
 size_t dymoe_gptq_workspace_bytes(long N, long K);
 int dymoe_gptq_quantize_pack(dymoe_ctx* ctx, const void* w, const float* u, long N, long K, int bits, int group,
                              uint8_t* codes, void* scale, void* zero, void* workspace, size_t workspace_bytes,
@@ -426,10 +447,10 @@ size_t dymoe_cache_bytes_resident(const dymoe_cache* cache);
  * Per-kernel timing (diagnostic; the paper reports only end-to-end latency,
  * Sec. 6.1 "Key Metrics", so these serve the roofline accounting).
  * dymoe_timing_enable: launches of the kernels whose bit is set in kernel_mask
- * (bit i = kernel id i, ids 0..17 in the order route, token_norm, importance,
+ * (bit i = kernel id i, ids 0..19 in the order route, token_norm, importance,
  * assign, quantize, gemv_phase1, gemv_phase2, gemv_combine, plan, gemm1, gemm2,
  * gemm_combine, stream_copy, decode_front, attn_stats, attn_colsum, gptq_group,
- * gptq_trail) carry a start and a stop HIP event on the dispatch itself, so
+ * gptq_trail, gptq_hessian, gptq_factor) carry a start and a stop HIP event on the dispatch itself, so
  * the interval is the kernel's execution time on the launch stream; 0 switches
  * timing off.  Either way, records not yet read are dropped.
  * dymoe_timing_read: waits for the recorded launches of `kernel`, drops their records and returns

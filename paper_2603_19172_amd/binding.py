@@ -34,7 +34,8 @@ EXPORTS = [
     "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_attention_workspace_bytes",
     "dymoe_token_score_attention", "dymoe_expert_importance",
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
-    "dymoe_gptq_workspace_bytes", "dymoe_gptq_quantize_pack",
+    "dymoe_gptq_workspace_bytes", "dymoe_gptq_quantize_pack", "dymoe_gptq_hessian",
+    "dymoe_gptq_factor_workspace_bytes", "dymoe_gptq_factor",
     "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_moe_ffn_mixed", "dymoe_stream_copy",
     "dymoe_decode_front", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
     "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
@@ -45,7 +46,7 @@ EXPORTS = [
 
 KERNELS = ["route", "token_norm", "importance", "assign", "quantize", "gemv_phase1",
            "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine", "stream_copy", "decode_front",
-           "attn_stats", "attn_colsum", "gptq_group", "gptq_trail"]
+           "attn_stats", "attn_colsum", "gptq_group", "gptq_trail", "gptq_hessian", "gptq_factor"]
 
 
 class ExpertFmt(C.Structure):
@@ -120,6 +121,12 @@ lib.dymoe_quantize_pack.restype = _i
 lib.dymoe_quantize_pack.argtypes = [_vp, _vp, _l, _l, _i, _i, _vp, _vp, _vp, _vp]
 lib.dymoe_gptq_workspace_bytes.restype = _sz
 lib.dymoe_gptq_workspace_bytes.argtypes = [_l, _l]
+lib.dymoe_gptq_hessian.restype = _i
+lib.dymoe_gptq_hessian.argtypes = [_vp, _vp, _l, _l, _i, _vp, _vp]
+lib.dymoe_gptq_factor_workspace_bytes.restype = _sz
+lib.dymoe_gptq_factor_workspace_bytes.argtypes = [_l]
+lib.dymoe_gptq_factor.restype = _i
+lib.dymoe_gptq_factor.argtypes = [_vp, _vp, _l, C.c_float, _vp, _vp, _sz, _vp]
 lib.dymoe_gptq_quantize_pack.restype = _i
 lib.dymoe_gptq_quantize_pack.argtypes = [_vp, _vp, _vp, _l, _l, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.dymoe_quantize_experts.restype = _i
@@ -302,6 +309,28 @@ class Context:
                                        _ptr(zero, torch.float16), _stream(stream)),
                "dymoe_quantize_pack")
         return codes, scale, zero
+
+    def gptq_hessian(self, x, out=None, accumulate=False, stream=None):
+        """hess (+)= X^T X for calibration inputs x [n, K] bf16; returns hess [K, K] fp32."""
+        n, K = x.shape
+        if out is None:
+            out = torch.empty((K, K), dtype=torch.float32, device=x.device)
+        _check(lib.dymoe_gptq_hessian(self._h, _ptr(x, torch.bfloat16), n, K, int(bool(accumulate)),
+                                      _ptr(out, torch.float32), _stream(stream)), "dymoe_gptq_hessian")
+        return out
+
+    def gptq_factor(self, hess, damp=0.01, out=None, workspace=None, stream=None):
+        """The upper triangular U with (H + damp mean(diag H) I)^-1 = U^T U."""
+        K = hess.shape[0]
+        if out is None:
+            out = torch.empty((K, K), dtype=torch.float32, device=hess.device)
+        if workspace is None:
+            workspace = torch.empty((int(lib.dymoe_gptq_factor_workspace_bytes(K)),), dtype=torch.uint8,
+                                    device=hess.device)
+        _check(lib.dymoe_gptq_factor(self._h, _ptr(hess, torch.float32), K, float(damp), _ptr(out, torch.float32),
+                                     _ptr(workspace, torch.uint8), workspace.numel(), _stream(stream)),
+               "dymoe_gptq_factor")
+        return out
 
     def gptq_quantize_pack(self, w, u, bits, group=64, out=None, workspace=None, stream=None):
         """Error-compensated quantize-and-pack of w [N,K] bf16 with the factor u [K,K] fp32."""

@@ -132,6 +132,8 @@ const char* dymoe_kernel_name(int kernel)
     case DYMOE_K_ATTN_COLSUM: return "attn_colsum_kernel";
     case DYMOE_K_GPTQ_GROUP: return "gptq_group_kernel";
     case DYMOE_K_GPTQ_TRAIL: return "gptq_trail_kernel";
+    case DYMOE_K_GPTQ_HESSIAN: return "gptq_hessian_kernel";
+    case DYMOE_K_GPTQ_FACTOR: return "gptq_chol_diag_kernel";
     default: return nullptr;
     }
 }

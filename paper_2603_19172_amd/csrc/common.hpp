@@ -29,6 +29,8 @@ enum {
     DYMOE_K_ATTN_COLSUM,
     DYMOE_K_GPTQ_GROUP,
     DYMOE_K_GPTQ_TRAIL,
+    DYMOE_K_GPTQ_HESSIAN,
+    DYMOE_K_GPTQ_FACTOR,
     DYMOE_K_COUNT
 };
 

@@ -51,101 +51,127 @@ __global__ __launch_bounds__(256) void gptq_widen_kernel(const uint16_t* __restr
     *reinterpret_cast<float4*>(v + i + 4) = b;
 }
 
-// err [64][n_pad]: e of column base + c for row r at err[c * n_pad + r].
+// Where the group kernel puts the 64 values e of a row: element (c, row) at p[c * c_stride + row * r_stride].
+struct GqOut {
+    float* p;
+    long c_stride, r_stride;
+};
+
+// One group of 64 columns for the rows [row_begin, row_end), a lane per row.
+//   BITS = 2, 4, 8   the quantizer: codes, scale and zero of the group are written, e is the scaled rounding error;
+//   BITS = 0         nothing is quantised and e = x[c] / D[c,c]: the row is solved against the upper triangular
+//                    diagonal block D (forward substitution; the factorisation below is built from this).
+// x: the rows' current values of the group's columns, x[row * ldx + c]; d: the 64 x 64 diagonal block, d[c * ldd + j].
+// `own` receives e for the rows of the range only; `pad` for every lane of the grid (rows rounded up to 64: a buffer
+// of that many rows, from which the trail kernel loads whole 64-row tiles).  Either may be null.
 template <int BITS>
 __global__ __launch_bounds__(kGqRows) void gptq_group_kernel(
-    const float* __restrict__ v, const float* __restrict__ u, long N, long K, long base, long n_pad,
-    uint8_t* __restrict__ codes, uint16_t* __restrict__ scale, uint16_t* __restrict__ zero,
-    float* __restrict__ err)
+    const float* __restrict__ x_in, long ldx, const float* __restrict__ d, long ldd, long row_begin, long row_end,
+    GqOut own, GqOut pad, uint8_t* __restrict__ codes, uint16_t* __restrict__ scale, uint16_t* __restrict__ zero,
+    long code_row_bytes, long groups_per_row)
 {
 #pragma clang fp contract(off)
-    constexpr int qmax = (1 << BITS) - 1;
-    constexpr int per_word = 32 / BITS;
-    constexpr int n_words = kGqGroup / per_word;    // 16 (int8), 8 (int4), 4 (int2)
-    const long slot = (long)blockIdx.x * kGqRows + threadIdx.x;   // < n_pad
-    const long row = min(slot, N - 1);              // lanes past the last row redo it and store nothing but their errors
+    const long slot = row_begin + (long)blockIdx.x * kGqRows + threadIdx.x;
+    const bool mine = slot < row_end;
+    const long row = min(slot, row_end - 1);        // lanes past the last row redo it and keep the result to themselves
     float x[kGqGroup];
 #pragma unroll
     for (int c = 0; c < kGqGroup / 4; c++) {
-        const float4 q = *reinterpret_cast<const float4*>(v + row * K + base + 4 * c);
+        const float4 q = *reinterpret_cast<const float4*>(x_in + row * ldx + 4 * c);
         x[4 * c + 0] = q.x; x[4 * c + 1] = q.y; x[4 * c + 2] = q.z; x[4 * c + 3] = q.w;
     }
-    float lo = x[0], hi = x[0];
+    constexpr int qmax = BITS ? (1 << BITS) - 1 : 1;
+    constexpr int per_word = BITS ? 32 / BITS : 32;
+    constexpr int n_words = BITS ? kGqGroup / per_word : 1;   // 16 (int8), 8 (int4), 4 (int2)
+    float m = 0.0f, s = 0.0f, inv = 0.0f;
+    _Float16 zh = (_Float16)0.0f, sh = (_Float16)0.0f;
+    if constexpr (BITS != 0) {
+        float lo = x[0], hi = x[0];
 #pragma unroll
-    for (int i = 1; i < kGqGroup; i++) {
-        lo = fminf(lo, x[i]);
-        hi = fmaxf(hi, x[i]);
+        for (int i = 1; i < kGqGroup; i++) {
+            lo = fminf(lo, x[i]);
+            hi = fmaxf(hi, x[i]);
+        }
+        zh = (_Float16)lo;                          // round to nearest even
+        const float range = hi - lo;
+        const float step = range / (float)qmax;     // correctly rounded division
+        sh = (_Float16)step;
+        m = (float)zh;
+        s = (float)sh;
+        inv = (s > 0.0f) ? (1.0f / s) : 0.0f;
     }
-    const _Float16 zh = (_Float16)lo;               // round to nearest even
-    const float range = hi - lo;
-    const float step = range / (float)qmax;         // correctly rounded division
-    const _Float16 sh = (_Float16)step;
-    const float m = (float)zh;
-    const float s = (float)sh;
-    const float inv = (s > 0.0f) ? (1.0f / s) : 0.0f;
-    const float* __restrict__ ub = u + base * K + base;      // the diagonal block: the same address in every lane
     uint32_t words[n_words];
 #pragma unroll
     for (int i = 0; i < n_words; i++) words[i] = 0u;
 #pragma unroll
     for (int i = 0; i < kGqGroup; i++) {
-        const float d = x[i] - m;
-        float r = __builtin_rintf(d * inv);
-        r = fminf(fmaxf(r, 0.0f), (float)qmax);
-        words[i / per_word] |= (uint32_t)(int)r << (BITS * (i % per_word));
-        float dq = r * s;
-        dq = dq + m;
-        const float e = (x[i] - dq) / ub[(long)i * K + i];
-        err[(long)i * n_pad + slot] = e;
+        float rest = x[i];
+        if constexpr (BITS != 0) {
+            const float t = x[i] - m;
+            float r = __builtin_rintf(t * inv);
+            r = fminf(fmaxf(r, 0.0f), (float)qmax);
+            words[i / per_word] |= (uint32_t)(int)r << (BITS * (i % per_word));
+            float dq = r * s;
+            dq = dq + m;
+            rest = x[i] - dq;
+        }
+        const float e = rest / d[(long)i * ldd + i];             // the same address in every lane: scalar loads
+        if (own.p && mine) own.p[(long)i * own.c_stride + row * own.r_stride] = e;
+        if (pad.p) pad.p[(long)i * pad.c_stride + slot * pad.r_stride] = e;
         const float ne = -e;
 #pragma unroll
-        for (int j = i + 1; j < kGqGroup; j++) x[j] = __builtin_fmaf(ne, ub[(long)i * K + j], x[j]);
+        for (int j = i + 1; j < kGqGroup; j++) x[j] = __builtin_fmaf(ne, d[(long)i * ldd + j], x[j]);
     }
-    if (slot < N) {
-        const long G = K / kGqGroup;
-        uint8_t* dst = codes + row * (K * BITS / 8) + base * BITS / 8;
+    if constexpr (BITS != 0) {
+        if (mine) {
+            uint8_t* dst = codes + row * code_row_bytes;
 #pragma unroll
-        for (int i = 0; i < n_words / 4; i++)
-            store_global(dst + 16 * i, make_uint4(words[4 * i], words[4 * i + 1], words[4 * i + 2], words[4 * i + 3]));
-        store_global(scale + row * G + base / kGqGroup, (uint16_t)f16_bits(sh));
-        store_global(zero + row * G + base / kGqGroup, (uint16_t)f16_bits(zh));
+            for (int i = 0; i < n_words / 4; i++)
+                store_global(dst + 16 * i, make_uint4(words[4 * i], words[4 * i + 1], words[4 * i + 2], words[4 * i + 3]));
+            store_global(scale + row * groups_per_row, (uint16_t)f16_bits(sh));
+            store_global(zero + row * groups_per_row, (uint16_t)f16_bits(zh));
+        }
     }
 }
 
-// v[r, j] = fma(-err[c][r], U[base + c, j], v[r, j]) for c = 0 .. 63 in order, all j >= base + 64.
+// v[r, j] = fma(-E[c, r], B[c, j], v[r, j]) for c = 0 .. 63 in that order, rows [row_begin, row_end) in tiles of
+// 64 from row_begin, columns [col_begin, col_end) in tiles of 128 from col_begin.  E[c, r] = e[c * lde + r] (whole
+// 64-row tiles are loaded: the buffer covers the rows rounded up), B[c, j] = b[c * ldb + j].  lower_only: tiles that
+// lie wholly above the diagonal (every row < every column) are left alone.
 __global__ __launch_bounds__(kGqTrailThreads) void gptq_trail_kernel(
-    float* __restrict__ v, const float* __restrict__ u, const float* __restrict__ err, long N, long K,
-    long base, long n_pad)
+    float* __restrict__ v, long ldv, const float* __restrict__ e, long lde, const float* __restrict__ b, long ldb,
+    long row_begin, long row_end, long col_begin, long col_end, int lower_only)
 {
     __shared__ __attribute__((aligned(16))) float s_e[kGqGroup][kGqRows];
     __shared__ __attribute__((aligned(16))) float s_u[kGqGroup][kGqTrailCols];
     const int tid = threadIdx.x;
-    const long col0 = base + kGqGroup + (long)blockIdx.x * kGqTrailCols;
-    const long row0 = (long)blockIdx.y * kGqRows;
+    const long col0 = col_begin + (long)blockIdx.x * kGqTrailCols;
+    const long row0 = row_begin + (long)blockIdx.y * kGqRows;
+    if (lower_only && row0 + kGqRows - 1 < col0) return;
 #pragma unroll
     for (int i = 0; i < kGqGroup * kGqRows / 4 / kGqTrailThreads; i++) {
         const int at = (i * kGqTrailThreads + tid) * 4;
         const int c = at / kGqRows, r = at % kGqRows;
-        *reinterpret_cast<float4*>(&s_e[c][r]) = *reinterpret_cast<const float4*>(err + (long)c * n_pad + row0 + r);
+        *reinterpret_cast<float4*>(&s_e[c][r]) = *reinterpret_cast<const float4*>(e + (long)c * lde + row0 + r);
     }
 #pragma unroll
     for (int i = 0; i < kGqGroup * kGqTrailCols / 4 / kGqTrailThreads; i++) {
         const int at = (i * kGqTrailThreads + tid) * 4;
         const int c = at / kGqTrailCols, n = at % kGqTrailCols;
         float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (col0 + n < K) q = *reinterpret_cast<const float4*>(u + (base + c) * K + col0 + n);
+        if (col0 + n < col_end) q = *reinterpret_cast<const float4*>(b + (long)c * ldb + col0 + n);
         *reinterpret_cast<float4*>(&s_u[c][n]) = q;
     }
     __syncthreads();
     const int tx = tid & 31, ty = tid >> 5;
     const long col = col0 + 4 * tx;
     const long row = row0 + 8 * ty;
-    if (col >= K) return;
+    if (col >= col_end) return;
     float4 acc[8];
 #pragma unroll
     for (int i = 0; i < 8; i++) {
         acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row + i < N) acc[i] = *reinterpret_cast<const float4*>(v + (row + i) * K + col);
+        if (row + i < row_end) acc[i] = *reinterpret_cast<const float4*>(v + (row + i) * ldv + col);
     }
 #pragma unroll 4
     for (int c = 0; c < kGqGroup; c++) {
@@ -163,7 +189,189 @@ __global__ __launch_bounds__(kGqTrailThreads) void gptq_trail_kernel(
     }
 #pragma unroll
     for (int i = 0; i < 8; i++)
-        if (row + i < N) *reinterpret_cast<float4*>(v + (row + i) * K + col) = acc[i];
+        if (row + i < row_end) *reinterpret_cast<float4*>(v + (row + i) * ldv + col) = acc[i];
+}
+
+// ---------------------------------------------------------------------------
+// Hessian of the calibration inputs: hess (+)= X^T X, x [n, K] bf16, fp32 sums on the matrix cores
+// (v_mfma_f32_32x32x16_bf16: the products of bf16 numbers are exact in fp32).  Both operands of a tile are
+// columns of X, which memory holds row by row: a thread fetches an 8-sample x 8-column block with eight
+// 16-byte loads, transposes it in registers and parks eight 16-byte pieces (one column, 8 samples) in LDS,
+// chunk position XOR-swizzled by column so that the operand reads of 8 neighbouring columns hit different
+// banks.  A workgroup owns a 128 x 128 tile on or above the diagonal (64 x 64 per wavefront) and writes the
+// mirror image as well.
+constexpr int kHsTile = 128;
+constexpr int kHsSamples = 64;
+constexpr int kHsThreads = 256;
+
+__global__ __launch_bounds__(kHsThreads) void gptq_hessian_kernel(const uint16_t* __restrict__ x, long n, long K,
+                                                                 int accumulate, float* __restrict__ hess)
+{
+    __shared__ uint4 s_op[2][kHsTile * (kHsSamples / 8)];      // [operand][column][chunk of 8 samples]
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int ln = lane & 31, kb = lane >> 5;
+    // block -> tile (ti, tj), tj >= ti, rows of the upper triangle one after the other
+    const int nt = (int)((K + kHsTile - 1) / kHsTile);
+    int ti = 0, left = (int)blockIdx.x;
+    while (left >= nt - ti) {
+        left -= nt - ti;
+        ti++;
+    }
+    const int tj = ti + left;
+    const long i0 = (long)ti * kHsTile, j0 = (long)tj * kHsTile;
+    // loading role: threads 0..127 the row operand's columns, 128..255 the column operand's
+    const int op = tid >> 7;
+    const int blk = tid & 127;
+    const int sgrp = blk >> 4;                      // which 8 samples of the step's 64
+    const int cgrp = blk & 15;                      // which 8 columns of the tile's 128
+    const long lcol = (op ? j0 : i0) + 8 * cgrp;
+    const int wi = wave >> 1, wj = wave & 1;
+    float16_t acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; a++)
+#pragma unroll
+        for (int b = 0; b < 2; b++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) acc[a][b][i] = 0.0f;
+    uint4 raw[8];
+    auto fetch = [&](long s0) {
+#pragma unroll
+        for (int r = 0; r < 8; r++) {
+            const long smp = s0 + 8 * sgrp + r;
+            raw[r] = make_uint4(0u, 0u, 0u, 0u);
+            if (smp < n && lcol < K) raw[r] = load_global<uint4>(x + smp * K + lcol);
+        }
+    };
+    fetch(0);
+    for (long s0 = 0; s0 < n; s0 += kHsSamples) {
+        // 8 x 8 transpose of 16-bit values: pair up the rows, split even and odd columns
+        uint4 out[8];
+#pragma unroll
+        for (int dw = 0; dw < 4; dw++) {
+            uint32_t even[4], odd[4];
+#pragma unroll
+            for (int pr = 0; pr < 4; pr++) {
+                const uint32_t a = reinterpret_cast<const uint32_t*>(&raw[2 * pr])[dw];
+                const uint32_t b = reinterpret_cast<const uint32_t*>(&raw[2 * pr + 1])[dw];
+                even[pr] = (a & 0xffffu) | (b << 16);
+                odd[pr] = (a >> 16) | (b & 0xffff0000u);
+            }
+            out[2 * dw] = make_uint4(even[0], even[1], even[2], even[3]);
+            out[2 * dw + 1] = make_uint4(odd[0], odd[1], odd[2], odd[3]);
+        }
+        __syncthreads();                            // the previous step's operand reads are done
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const int c = 8 * cgrp + i;
+            s_op[op][c * (kHsSamples / 8) + (sgrp ^ (c & 7))] = out[i];
+        }
+        __syncthreads();
+        if (s0 + kHsSamples < n) fetch(s0 + kHsSamples);          // in flight during the products
+#pragma unroll
+        for (int ks = 0; ks < kHsSamples / 16; ks++) {
+            const int chunk = 2 * ks + kb;
+            bf16x8_t fa[2], fb[2];
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const int ca = 64 * wi + 32 * h + ln, cb = 64 * wj + 32 * h + ln;
+                fa[h] = __builtin_bit_cast(bf16x8_t, s_op[0][ca * (kHsSamples / 8) + (chunk ^ (ca & 7))]);
+                fb[h] = __builtin_bit_cast(bf16x8_t, s_op[1][cb * (kHsSamples / 8) + (chunk ^ (cb & 7))]);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; a++)
+#pragma unroll
+                for (int b = 0; b < 2; b++)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+    }
+    // register i of lane (ln, kb): row 8 (i / 4) + 4 kb + i % 4 of the 32 x 32 tile, column ln
+#pragma unroll
+    for (int a = 0; a < 2; a++)
+#pragma unroll
+        for (int b = 0; b < 2; b++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const long r = i0 + 64 * wi + 32 * a + 8 * (i >> 2) + 4 * kb + (i & 3);
+                const long c = j0 + 64 * wj + 32 * b + ln;
+                if (r < K && c < K) {
+                    float val = acc[a][b][i];
+                    if (accumulate) val += hess[r * K + c];
+                    hess[r * K + c] = val;
+                    if (ti != tj) hess[c * K + r] = val;
+                }
+            }
+}
+
+// ---------------------------------------------------------------------------
+// Factor of the inverse Hessian: U upper triangular, (H + damping)^-1 = U^T U.
+// With J the order-reversing permutation and J (H + damping) J = R^T R (R upper triangular, plain Cholesky),
+// U = J R^-T J.  Both steps are built from the two kernels above:
+//   Cholesky, per block of 64 columns: the 64 x 64 diagonal block is factored by one wavefront; the rows
+//     below it are solved against that block (group kernel without quantisation: e = the new column block of
+//     L = R^T, stored as rows of R); the rest of the lower triangle loses L_panel L_panel^T (trail kernel with
+//     the panel, read from R, on both sides);
+//   inverse: the rows of R^-T come from forward substitution of the unit vectors against R, which is the
+//     quantizer's sweep with nothing quantised and the identity as the matrix; a row c only starts at its own
+//     column, so a step touches rows [0, base + 64) only.  e is written straight to U's mirrored position.
+
+// damping = damp * mean of the diagonal, a zero diagonal entry counting as (and becoming) 1
+__global__ __launch_bounds__(256) void gptq_damping_kernel(const float* __restrict__ hess, long K, float damp,
+                                                           float* __restrict__ lambda)
+{
+    __shared__ double s_part[256];
+    double acc = 0.0;
+    for (long i = threadIdx.x; i < K; i += 256) {
+        const float dgl = hess[i * K + i];
+        acc += (dgl == 0.0f) ? 1.0 : (double)dgl;
+    }
+    s_part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) s_part[threadIdx.x] += s_part[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *lambda = (float)((double)damp * s_part[0] / (double)K);
+}
+
+// v = J (H + damping) J
+__global__ __launch_bounds__(256) void gptq_reverse_kernel(const float* __restrict__ hess, long K,
+                                                           const float* __restrict__ lambda, float* __restrict__ v)
+{
+    const long at = (long)blockIdx.x * 256 + threadIdx.x;
+    if (at >= K * K) return;
+    const long i = at / K, j = at - i * K;
+    float val = hess[(K - 1 - i) * K + (K - 1 - j)];
+    if (i == j) val = ((val == 0.0f) ? 1.0f : val) + *lambda;
+    v[at] = val;
+}
+
+__global__ __launch_bounds__(256) void gptq_fill_kernel(float* __restrict__ m, long K, float diag)
+{
+    const long at = (long)blockIdx.x * 256 + threadIdx.x;
+    if (at >= K * K) return;
+    const long i = at / K, j = at - i * K;
+    m[at] = (i == j) ? diag : 0.0f;
+}
+
+// R_JJ^T R_JJ = A, A = the 64 x 64 diagonal block at (j0, j0) of v (its lower triangle is current), R_JJ
+// written to r[(j0 + c) * K + j0 + j] (zeros below the diagonal).  One wavefront, lane j holds column j.
+__global__ __launch_bounds__(kWave) void gptq_chol_diag_kernel(const float* __restrict__ v, long K, long j0,
+                                                               float* __restrict__ r)
+{
+    const int j = threadIdx.x;
+    float col[kGqGroup];                                          // A[i, j], read from the lower triangle
+#pragma unroll
+    for (int i = 0; i < kGqGroup; i++) col[i] = v[(j0 + max(i, j)) * K + j0 + min(i, j)];
+#pragma unroll
+    for (int c = 0; c < kGqGroup; c++) {
+        const float dcc = __shfl(col[c], c, kWave);
+        const float rd = sqrtf(dcc);
+        const float rj = (j >= c) ? col[c] / rd : 0.0f;           // R[c, j]
+        r[(j0 + c) * K + j0 + j] = rj;
+#pragma unroll
+        for (int i = c + 1; i < kGqGroup; i++) col[i] = __builtin_fmaf(-__shfl(rj, i, kWave), rj, col[i]);
+    }
 }
 
 }  // namespace dymoe
@@ -199,29 +407,117 @@ int dymoe_gptq_quantize_pack(dymoe_ctx* ctx, const void* w_bf16, const float* u,
                        (const uint16_t*)w_bf16, n_elems, v);
     DYMOE_HIP_LAUNCH_CHECK();
     const dim3 grid_a((unsigned)(n_pad / kGqRows));
+    const GqOut none{nullptr, 0, 0};
+    const GqOut pad{err, n_pad, 1};
+    const long G = K / kGqGroup;
     for (long base = 0; base < K; base += kGqGroup) {
+        const float* xg = v + base;
+        const float* dg = u + base * K + base;
+        uint8_t* cg = codes + base * bits / 8;
+        uint16_t* sg = (uint16_t*)scale + base / kGqGroup;
+        uint16_t* zg = (uint16_t*)zero + base / kGqGroup;
         switch (bits) {
         case 8:
-            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<8>, grid_a, dim3(kGqRows), 0, st, (const float*)v, u,
-                         N, K, base, n_pad, codes, (uint16_t*)scale, (uint16_t*)zero, err);
+            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<8>, grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
+                         0L, N, none, pad, cg, sg, zg, K * bits / 8, G);
             break;
         case 4:
-            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<4>, grid_a, dim3(kGqRows), 0, st, (const float*)v, u,
-                         N, K, base, n_pad, codes, (uint16_t*)scale, (uint16_t*)zero, err);
+            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<4>, grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
+                         0L, N, none, pad, cg, sg, zg, K * bits / 8, G);
             break;
         default:
-            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<2>, grid_a, dim3(kGqRows), 0, st, (const float*)v, u,
-                         N, K, base, n_pad, codes, (uint16_t*)scale, (uint16_t*)zero, err);
+            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<2>, grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
+                         0L, N, none, pad, cg, sg, zg, K * bits / 8, G);
             break;
         }
         DYMOE_HIP_LAUNCH_CHECK();
         const long rest = K - base - kGqGroup;
         if (rest > 0) {
             const dim3 grid_b((unsigned)((rest + kGqTrailCols - 1) / kGqTrailCols), (unsigned)(n_pad / kGqRows));
-            dymoe_launch(ctx, DYMOE_K_GPTQ_TRAIL, gptq_trail_kernel, grid_b, dim3(kGqTrailThreads), 0, st, v, u,
-                         (const float*)err, N, K, base, n_pad);
+            dymoe_launch(ctx, DYMOE_K_GPTQ_TRAIL, gptq_trail_kernel, grid_b, dim3(kGqTrailThreads), 0, st, v, K,
+                         (const float*)err, n_pad, u + base * K, K, 0L, N, base + kGqGroup, K, 0);
             DYMOE_HIP_LAUNCH_CHECK();
         }
+    }
+    return DYMOE_OK;
+}
+
+int dymoe_gptq_hessian(dymoe_ctx* ctx, const void* x_bf16, long n, long K, int accumulate, float* hess, void* stream)
+{
+    using namespace dymoe;
+    DYMOE_REQUIRE(x_bf16 && hess && n > 0 && K > 0 && K % 8 == 0 && (accumulate == 0 || accumulate == 1));
+    DYMOE_REQUIRE(K <= 65536 && dymoe_aligned(x_bf16, 16) && dymoe_aligned(hess, 16));
+    if (!ctx) return DYMOE_ENOCTX;
+    const long nt = (K + kHsTile - 1) / kHsTile;
+    dymoe_launch(ctx, DYMOE_K_GPTQ_HESSIAN, gptq_hessian_kernel, dim3((unsigned)(nt * (nt + 1) / 2)), dim3(kHsThreads), 0,
+                 (hipStream_t)stream, (const uint16_t*)x_bf16, n, K, accumulate, hess);
+    DYMOE_HIP_LAUNCH_CHECK();
+    return DYMOE_OK;
+}
+
+size_t dymoe_gptq_factor_workspace_bytes(long K)
+{
+    if (K <= 0) return 0;
+    // the reversed damped Hessian (later the substitution's right-hand sides), its Cholesky factor, 64 errors per row, damping
+    return 2 * dymoe::gq_round256((size_t)K * (size_t)K * 4) + dymoe::gq_round256((size_t)dymoe::kGqGroup * (size_t)K * 4) + 256;
+}
+
+int dymoe_gptq_factor(dymoe_ctx* ctx, const float* hess, long K, float damp, float* u, void* workspace,
+                      size_t workspace_bytes, void* stream)
+{
+    using namespace dymoe;
+    DYMOE_REQUIRE(hess && u && workspace && K > 0 && K % kGqGroup == 0 && K <= 65536 && damp >= 0.0f);
+    DYMOE_REQUIRE(dymoe_aligned(hess, 16) && dymoe_aligned(u, 16) && dymoe_aligned(workspace, 256));
+    DYMOE_REQUIRE((const void*)hess != (const void*)u);
+    if (workspace_bytes < dymoe_gptq_factor_workspace_bytes(K)) return DYMOE_ENOSPC;
+    if (!ctx) return DYMOE_ENOCTX;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t mat = gq_round256((size_t)K * (size_t)K * 4);
+    float* v = reinterpret_cast<float*>(workspace);
+    float* r = reinterpret_cast<float*>((char*)workspace + mat);
+    float* err = reinterpret_cast<float*>((char*)workspace + 2 * mat);
+    float* lambda = reinterpret_cast<float*>((char*)workspace + 2 * mat + gq_round256((size_t)kGqGroup * (size_t)K * 4));
+    const dim3 whole((unsigned)((K * K + 255) / 256));
+    const GqOut none{nullptr, 0, 0};
+    hipLaunchKernelGGL(gptq_damping_kernel, dim3(1), dim3(256), 0, st, hess, K, damp, lambda);
+    hipLaunchKernelGGL(gptq_reverse_kernel, whole, dim3(256), 0, st, hess, K, (const float*)lambda, v);
+    hipLaunchKernelGGL(gptq_fill_kernel, whole, dim3(256), 0, st, r, K, 0.0f);
+    DYMOE_HIP_LAUNCH_CHECK();
+    // J (H + damping) J = R^T R
+    for (long j0 = 0; j0 < K; j0 += kGqGroup) {
+        dymoe_launch(ctx, DYMOE_K_GPTQ_FACTOR, gptq_chol_diag_kernel, dim3(1), dim3(kWave), 0, st, (const float*)v, K, j0, r);
+        const long below = K - j0 - kGqGroup;
+        if (below > 0) {
+            const long rb = j0 + kGqGroup;
+            const GqOut panel{r + j0 * K, K, 1};                   // L[row, j0 + c] = R[j0 + c, row]
+            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<0>, dim3((unsigned)(below / kGqRows)), dim3(kGqRows), 0,
+                         st, (const float*)(v + j0), K, (const float*)(r + j0 * K + j0), K, rb, K, panel, none,
+                         (uint8_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, 0L, 0L);
+            const dim3 grid_b((unsigned)((below + kGqTrailCols - 1) / kGqTrailCols), (unsigned)(below / kGqRows));
+            dymoe_launch(ctx, DYMOE_K_GPTQ_TRAIL, gptq_trail_kernel, grid_b, dim3(kGqTrailThreads), 0, st, v, K,
+                         (const float*)(r + j0 * K), K, (const float*)(r + j0 * K), K, rb, K, rb, K, 1);
+        }
+        DYMOE_HIP_LAUNCH_CHECK();
+    }
+    // rows of R^-T by forward substitution of the unit vectors, mirrored into U
+    hipLaunchKernelGGL(gptq_fill_kernel, whole, dim3(256), 0, st, v, K, 1.0f);
+    hipLaunchKernelGGL(gptq_fill_kernel, whole, dim3(256), 0, st, u, K, 0.0f);
+    DYMOE_HIP_LAUNCH_CHECK();
+    for (long base = 0; base < K; base += kGqGroup) {
+        const long rows = base + kGqGroup;
+        // e of (row c, column base + i) is U[K - 1 - base - i, K - 1 - c]
+        const GqOut mirrored{u + (K - 1 - base) * K + (K - 1), -K, -1};
+        const GqOut pad{err, K, 1};
+        dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<0>, dim3((unsigned)(rows / kGqRows)), dim3(kGqRows), 0, st,
+                     (const float*)(v + base), K, (const float*)(r + base * K + base), K, 0L, rows, mirrored, pad,
+                     (uint8_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, 0L, 0L);
+        const long rest = K - rows;
+        if (rest > 0) {
+            const dim3 grid_b((unsigned)((rest + kGqTrailCols - 1) / kGqTrailCols), (unsigned)(rows / kGqRows));
+            dymoe_launch(ctx, DYMOE_K_GPTQ_TRAIL, gptq_trail_kernel, grid_b, dim3(kGqTrailThreads), 0, st, v, K,
+                         (const float*)err, K, (const float*)(r + base * K), K, 0L, rows, rows, K, 0);
+        }
+        DYMOE_HIP_LAUNCH_CHECK();
     }
     return DYMOE_OK;
 }

@@ -79,3 +79,62 @@ def test_gptq_reuses_a_dirty_workspace_and_lowers_the_output_error(ctx):
     deq = O.dequantize(first[0].cpu().numpy(), bits_of(first[1]), bits_of(first[2]), 4)
     plain = O.dequantize(*O.quantize_pack(wb, 4), 4)
     assert O.output_error(wf, deq, H) < 0.5 * O.output_error(wf, plain, H)
+
+
+# samples: fewer than a step's 64, ragged, several steps; columns: one tile, a ragged last tile, several tiles
+@pytest.mark.parametrize("n,K", [(9, 64), (300, 320), (1000, 512), (64, 1024)])
+def test_gptq_hessian_matches_the_oracle(ctx, n, K):
+    xb = synth.calibration_inputs(740 + K, n, K)
+    want = O.gptq_hessian(xb)
+    x = to_bf16(xb)
+    got = ctx.gptq_hessian(x)
+    torch.cuda.synchronize()
+    g = got.cpu().numpy().astype(np.float64)
+    scale = np.sqrt(np.outer(np.diag(want), np.diag(want)))
+    err = np.abs(g - want) / scale
+    print("n=%d K=%d: max |dH| / sqrt(Hii Hjj) = %.2e" % (n, K, err.max()))
+    assert err.max() < 1e-5 and np.array_equal(g, g.T)
+    # a second batch added on top
+    both = ctx.gptq_hessian(x, out=got, accumulate=True)
+    torch.cuda.synchronize()
+    assert np.abs(both.cpu().numpy() - 2.0 * want).max() <= 2e-5 * scale.max()
+
+
+@pytest.mark.parametrize("K", [64, 192, 1024])
+def test_gptq_factor_matches_the_oracle(ctx, K):
+    xb = synth.calibration_inputs(760 + K, 2 * K, K)
+    H = O.gptq_hessian(xb)
+    H[:, 5] = 0.0                      # a column no input reached
+    H[5, :] = 0.0
+    want = O.gptq_factor(H, damp=0.01)
+    got = ctx.gptq_factor(torch.from_numpy(H.astype(np.float32)).to(DEV), damp=0.01)
+    torch.cuda.synchronize()
+    U = got.cpu().numpy().astype(np.float64)
+    assert np.isfinite(U).all() and np.array_equal(U, np.triu(U)) and (np.diag(U) > 0).all()
+    rel = np.abs(U - want).max(axis=1) / np.abs(want).max(axis=1)
+    Hd = O.gptq_damped(H, 0.01)
+    resid = np.abs(U.T @ U @ Hd - np.eye(K)).max()
+    print("K=%d: max row-relative error %.2e, |U^T U Hd - I| = %.2e" % (K, rel.max(), resid))
+    assert rel.max() < 2e-4 and resid < 2e-3
+
+
+def test_gptq_chain_on_the_device(ctx):
+    """Hessian, factor and sweep all on the device; the result is as good as the oracle's own chain (the
+    factors differ in the last fp32 digits, so a code may differ here and there)."""
+    N, K = 128, 512
+    xb = synth.calibration_inputs(780, 1024, K)
+    wb = synth.normal_bf16(780, 77, (N, K), 0.02)
+    H = O.gptq_hessian(xb)
+    want = O.gptq_quantize_pack(wb, O.gptq_factor(H), 4)
+    hess = ctx.gptq_hessian(to_bf16(xb))
+    u = ctx.gptq_factor(hess)
+    got = ctx.gptq_quantize_pack(to_bf16(wb), u, 4)
+    torch.cuda.synchronize()
+    wf = synth.bf16_bits_to_f32(wb).astype(np.float64)
+    d_got = O.dequantize(got[0].cpu().numpy(), bits_of(got[1]), bits_of(got[2]), 4)
+    d_want = O.dequantize(*want, 4)
+    e_got, e_want = O.output_error(wf, d_got, H), O.output_error(wf, d_want, H)
+    e_plain = O.output_error(wf, O.dequantize(*O.quantize_pack(wb, 4), 4), H)
+    same = (d_got == d_want).mean()
+    print("same dequantised values %.4f; output error device %.4e oracle %.4e plain %.4e" % (same, e_got, e_want, e_plain))
+    assert same > 0.98 and abs(e_got - e_want) <= 0.02 * e_want and e_got < 0.5 * e_plain

@@ -137,6 +137,20 @@ def test_argument_validation_happens_before_any_device_work():
     assert gq(None, P, None, 100, 256, 4, 64, P, P, P, P, gw, None) == B.EINVAL
     assert gq(None, P, P + 4, 100, 256, 4, 64, P, P, P, P, gw, None) == B.EINVAL
     assert gq(None, P, P, 100, 256, 4, 64, P, P, P, P + 16, gw, None) == B.EINVAL     # workspace alignment
+    gh = lib.dymoe_gptq_hessian
+    assert gh(None, P, 300, 256, 0, P, None) == B.ENOCTX
+    assert gh(None, P, 300, 250, 0, P, None) == B.EINVAL
+    assert gh(None, P, 0, 256, 0, P, None) == B.EINVAL
+    assert gh(None, P, 300, 256, 2, P, None) == B.EINVAL
+    assert gh(None, P, 300, 256, 0, None, None) == B.EINVAL
+    gf = lib.dymoe_gptq_factor
+    fw = int(lib.dymoe_gptq_factor_workspace_bytes(256))
+    assert fw >= 2 * 256 * 256 * 4 + 64 * 256 * 4 and lib.dymoe_gptq_factor_workspace_bytes(0) == 0
+    assert gf(None, P, 256, 0.01, 2 * P, P, fw, None) == B.ENOCTX
+    assert gf(None, P, 256, 0.01, 2 * P, P, fw - 1, None) == B.ENOSPC
+    assert gf(None, P, 200, 0.01, 2 * P, P, fw, None) == B.EINVAL
+    assert gf(None, P, 256, -1.0, 2 * P, P, fw, None) == B.EINVAL
+    assert gf(None, P, 256, 0.01, P, P, fw, None) == B.EINVAL                           # in place
     # stream copy
     assert lib.dymoe_stream_copy(None, P, 2 * P, 1024, None) == B.ENOCTX
     assert lib.dymoe_stream_copy(None, P, 2 * P, 1000, None) == B.EINVAL

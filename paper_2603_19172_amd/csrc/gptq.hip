@@ -51,23 +51,21 @@ __global__ __launch_bounds__(256) void gptq_widen_kernel(const uint16_t* __restr
     *reinterpret_cast<float4*>(v + i + 4) = b;
 }
 
-// Where the group kernel puts the 64 values e of a row: element (c, row) at p[c * c_stride + row * r_stride].
-struct GqOut {
-    float* p;
-    long c_stride, r_stride;
-};
-
 // One group of 64 columns for the rows [row_begin, row_end), a lane per row.
 //   BITS = 2, 4, 8   the quantizer: codes, scale and zero of the group are written, e is the scaled rounding error;
 //   BITS = 0         nothing is quantised and e = x[c] / D[c,c]: the row is solved against the upper triangular
 //                    diagonal block D (forward substitution; the factorisation below is built from this).
 // x: the rows' current values of the group's columns, x[row * ldx + c]; d: the 64 x 64 diagonal block, d[c * ldd + j].
-// `own` receives e for the rows of the range only; `pad` for every lane of the grid (rows rounded up to 64: a buffer
-// of that many rows, from which the trail kernel loads whole 64-row tiles).  Either may be null.
-template <int BITS>
+// e of (column c, row) goes to own_p[c * own_cs + row * own_rs] (OWN; the row range must then be whole blocks of 64)
+// and to pad_p[c * pad_cs + slot * pad_rs] (PAD) for every lane of the grid, rows rounded up to 64: a buffer of that
+// many rows, from which the trail kernel loads whole 64-row tiles.  Which of the two are written is fixed at compile
+// time: with run-time tests around the stores the 64 unrolled columns fall apart into basic blocks and the scalar
+// registers holding the diagonal block spill.
+template <int BITS, bool OWN, bool PAD>
 __global__ __launch_bounds__(kGqRows) void gptq_group_kernel(
     const float* __restrict__ x_in, long ldx, const float* __restrict__ d, long ldd, long row_begin, long row_end,
-    GqOut own, GqOut pad, uint8_t* __restrict__ codes, uint16_t* __restrict__ scale, uint16_t* __restrict__ zero,
+    float* __restrict__ own_p, long own_cs, long own_rs, float* __restrict__ pad_p, long pad_cs, long pad_rs,
+    uint8_t* __restrict__ codes, uint16_t* __restrict__ scale, uint16_t* __restrict__ zero,
     long code_row_bytes, long groups_per_row)
 {
 #pragma clang fp contract(off)
@@ -116,8 +114,8 @@ __global__ __launch_bounds__(kGqRows) void gptq_group_kernel(
             rest = x[i] - dq;
         }
         const float e = rest / d[(long)i * ldd + i];             // the same address in every lane: scalar loads
-        if (own.p && mine) own.p[(long)i * own.c_stride + row * own.r_stride] = e;
-        if (pad.p) pad.p[(long)i * pad.c_stride + slot * pad.r_stride] = e;
+        if constexpr (OWN) own_p[(long)i * own_cs + slot * own_rs] = e;
+        if constexpr (PAD) pad_p[(long)i * pad_cs + slot * pad_rs] = e;
         const float ne = -e;
 #pragma unroll
         for (int j = i + 1; j < kGqGroup; j++) x[j] = __builtin_fmaf(ne, d[(long)i * ldd + j], x[j]);
@@ -407,8 +405,7 @@ int dymoe_gptq_quantize_pack(dymoe_ctx* ctx, const void* w_bf16, const float* u,
                        (const uint16_t*)w_bf16, n_elems, v);
     DYMOE_HIP_LAUNCH_CHECK();
     const dim3 grid_a((unsigned)(n_pad / kGqRows));
-    const GqOut none{nullptr, 0, 0};
-    const GqOut pad{err, n_pad, 1};
+    float* const none = nullptr;
     const long G = K / kGqGroup;
     for (long base = 0; base < K; base += kGqGroup) {
         const float* xg = v + base;
@@ -418,16 +415,16 @@ int dymoe_gptq_quantize_pack(dymoe_ctx* ctx, const void* w_bf16, const float* u,
         uint16_t* zg = (uint16_t*)zero + base / kGqGroup;
         switch (bits) {
         case 8:
-            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<8>, grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
-                         0L, N, none, pad, cg, sg, zg, K * bits / 8, G);
+            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<8, false, true>), grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
+                         0L, N, none, 0L, 0L, err, n_pad, 1L, cg, sg, zg, K * bits / 8, G);
             break;
         case 4:
-            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<4>, grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
-                         0L, N, none, pad, cg, sg, zg, K * bits / 8, G);
+            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<4, false, true>), grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
+                         0L, N, none, 0L, 0L, err, n_pad, 1L, cg, sg, zg, K * bits / 8, G);
             break;
         default:
-            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<2>, grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
-                         0L, N, none, pad, cg, sg, zg, K * bits / 8, G);
+            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<2, false, true>), grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
+                         0L, N, none, 0L, 0L, err, n_pad, 1L, cg, sg, zg, K * bits / 8, G);
             break;
         }
         DYMOE_HIP_LAUNCH_CHECK();
@@ -478,7 +475,7 @@ int dymoe_gptq_factor(dymoe_ctx* ctx, const float* hess, long K, float damp, flo
     float* err = reinterpret_cast<float*>((char*)workspace + 2 * mat);
     float* lambda = reinterpret_cast<float*>((char*)workspace + 2 * mat + gq_round256((size_t)kGqGroup * (size_t)K * 4));
     const dim3 whole((unsigned)((K * K + 255) / 256));
-    const GqOut none{nullptr, 0, 0};
+    float* const none = nullptr;
     hipLaunchKernelGGL(gptq_damping_kernel, dim3(1), dim3(256), 0, st, hess, K, damp, lambda);
     hipLaunchKernelGGL(gptq_reverse_kernel, whole, dim3(256), 0, st, hess, K, (const float*)lambda, v);
     hipLaunchKernelGGL(gptq_fill_kernel, whole, dim3(256), 0, st, r, K, 0.0f);
@@ -489,9 +486,9 @@ int dymoe_gptq_factor(dymoe_ctx* ctx, const float* hess, long K, float damp, flo
         const long below = K - j0 - kGqGroup;
         if (below > 0) {
             const long rb = j0 + kGqGroup;
-            const GqOut panel{r + j0 * K, K, 1};                   // L[row, j0 + c] = R[j0 + c, row]
-            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<0>, dim3((unsigned)(below / kGqRows)), dim3(kGqRows), 0,
-                         st, (const float*)(v + j0), K, (const float*)(r + j0 * K + j0), K, rb, K, panel, none,
+            // the panel of L goes into R as rows: L[row, j0 + c] = R[j0 + c, row]
+            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<0, true, false>), dim3((unsigned)(below / kGqRows)), dim3(kGqRows), 0,
+                         st, (const float*)(v + j0), K, (const float*)(r + j0 * K + j0), K, rb, K, r + j0 * K, K, 1L, none, 0L, 0L,
                          (uint8_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, 0L, 0L);
             const dim3 grid_b((unsigned)((below + kGqTrailCols - 1) / kGqTrailCols), (unsigned)(below / kGqRows));
             dymoe_launch(ctx, DYMOE_K_GPTQ_TRAIL, gptq_trail_kernel, grid_b, dim3(kGqTrailThreads), 0, st, v, K,
@@ -506,11 +503,9 @@ int dymoe_gptq_factor(dymoe_ctx* ctx, const float* hess, long K, float damp, flo
     for (long base = 0; base < K; base += kGqGroup) {
         const long rows = base + kGqGroup;
         // e of (row c, column base + i) is U[K - 1 - base - i, K - 1 - c]
-        const GqOut mirrored{u + (K - 1 - base) * K + (K - 1), -K, -1};
-        const GqOut pad{err, K, 1};
-        dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, gptq_group_kernel<0>, dim3((unsigned)(rows / kGqRows)), dim3(kGqRows), 0, st,
-                     (const float*)(v + base), K, (const float*)(r + base * K + base), K, 0L, rows, mirrored, pad,
-                     (uint8_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, 0L, 0L);
+        dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<0, true, true>), dim3((unsigned)(rows / kGqRows)), dim3(kGqRows), 0, st,
+                     (const float*)(v + base), K, (const float*)(r + base * K + base), K, 0L, rows,
+                     u + (K - 1 - base) * K + (K - 1), -K, -1L, err, K, 1L, (uint8_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, 0L, 0L);
         const long rest = K - rows;
         if (rest > 0) {
             const dim3 grid_b((unsigned)((rest + kGqTrailCols - 1) / kGqTrailCols), (unsigned)(rows / kGqRows));

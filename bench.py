@@ -53,6 +53,9 @@ def main():
                          "profiler run over the default workload)")
     ap.add_argument("--fine-grained", action="store_true",
                     help="also time the fine-grained layer (BASELINE configs[3]: 2048 tokens, 128 experts, top-8)")
+    ap.add_argument("--gptq", action="store_true",
+                    help="also time the error-compensated quantizer (Hessian, inverse factor, column sweep) on the three "
+                         "matrices of one Mixtral-shaped expert with 2048 synthetic calibration tokens")
     ap.add_argument("--prefill-steps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run dymoe_pack_tiles on a 1 GiB bf16 matrix: a permuting copy of known traffic "
@@ -361,6 +364,56 @@ def main():
             "kernels_us": {n: round(v[0] / max(v[1], 1) * 1e3, 1) for n, v in fk.items()}}
         del fstore, flay
         torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- error-compensated quantizer (opt-in)
+    if args.gptq:
+        gnames = ["gptq_hessian", "gptq_factor", "gptq_group", "gptq_trail"]
+        n_cal = 2048
+        res = {}
+        for label, (gN, gK) in (("W1/W3 [F,H]", (F, H)), ("W2 [H,F]", (H, F))):
+            gw = bf16(host_w[0][0 if gK == H else 2])
+            gx = bf16(synth.calibration_inputs(31, n_cal, gK))
+            hess = torch.empty((gK, gK), dtype=torch.float32, device=dev)
+            gu = torch.empty_like(hess)
+            fws = torch.empty((int(B.lib.dymoe_gptq_factor_workspace_bytes(gK)),), dtype=torch.uint8, device=dev)
+            sws = torch.empty((int(B.lib.dymoe_gptq_workspace_bytes(gN, gK)),), dtype=torch.uint8, device=dev)
+            gout = None
+            for rep in range(2):                        # the second pass is the one reported
+                ctx.timing_enable(gnames)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ctx.gptq_hessian(gx, out=hess)
+                ctx.gptq_factor(hess, out=gu, workspace=fws)
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                fac = {n_: ctx.timing_read(n_) for n_ in gnames}
+                gout = ctx.gptq_quantize_pack(gw, gu, 4, workspace=sws, out=gout)
+                torch.cuda.synchronize()
+                t2 = time.perf_counter()
+                swp = {n_: ctx.timing_read(n_) for n_ in gnames}
+                ctx.timing_enable(())
+            trail_flops = 2.0 * gN * gK * (gK - 64) / 2.0       # one FMA per (row, column pair c < j across groups)
+            res[label] = {
+                "N": gN, "K": gK, "calibration_tokens": n_cal,
+                "hessian_ms": round(fac["gptq_hessian"][0], 3),
+                "hessian_TFLOPs_bf16": round(2.0 * n_cal * gK * gK / 2 / (fac["gptq_hessian"][0] * 1e-3) / 1e12, 1),
+                "factor_ms_wall": round((t1 - t0) * 1e3 - fac["gptq_hessian"][0], 2),
+                "factor_kernels_ms": {"chol_diag": round(fac["gptq_factor"][0], 2), "group": round(fac["gptq_group"][0], 2),
+                                      "trail": round(fac["gptq_trail"][0], 2)},
+                "sweep_ms_wall": round((t2 - t1) * 1e3, 2),
+                "sweep_kernels_ms": {"group": round(swp["gptq_group"][0], 2), "trail": round(swp["gptq_trail"][0], 2)},
+                "sweep_trail_TFLOPs_fp32": round(trail_flops / (swp["gptq_trail"][0] * 1e-3) / 1e12, 1),
+                "sweep_trail_frac_fp32_vector_peak": round(trail_flops / (swp["gptq_trail"][0] * 1e-3) / 1e12 / 157.3, 3),
+                "finite": bool(torch.isfinite(gu).all())}
+            del hess, gu, fws, sws, gx, gw, gout
+            torch.cuda.empty_cache()
+        out["gptq_one_expert"] = {
+            "note": "int4, group 64; the factor of [F,H] serves W1 and W3; wall times include the launch gaps of the "
+                    "per-group launches (timed launches carry events, untimed runs are a little faster)",
+            "matrices": res,
+            "expert_total_ms": round(res["W1/W3 [F,H]"]["hessian_ms"] + res["W1/W3 [F,H]"]["factor_ms_wall"]
+                                     + 2 * res["W1/W3 [F,H]"]["sweep_ms_wall"] + res["W2 [H,F]"]["hessian_ms"]
+                                     + res["W2 [H,F]"]["factor_ms_wall"] + res["W2 [H,F]"]["sweep_ms_wall"], 1)}
 
     # ---------------------------------------------------------------- CPU oracle on this host
     if not args.skip_cpu:

@@ -138,3 +138,40 @@ def test_gptq_chain_on_the_device(ctx):
     same = (d_got == d_want).mean()
     print("same dequantised values %.4f; output error device %.4e oracle %.4e plain %.4e" % (same, e_got, e_want, e_plain))
     assert same > 0.98 and abs(e_got - e_want) <= 0.02 * e_want and e_got < 0.5 * e_plain
+
+
+def test_gptq_mixtral_sized_matrix(ctx):
+    """The first expert matrix of the Mixtral-shaped layer at full size (14336 x 4096), 1024 calibration
+    tokens.  Rows are independent in the sweep, so the oracle checks a seeded sample of them bit for bit;
+    the factor is compared in full."""
+    N, K, n = 14336, 4096, 1024
+    cfg = synth.CONFIGS["mixtral_decode"]
+    wb = synth.expert_matrix(cfg, 0, 0)
+    assert wb.shape == (N, K)
+    xb = synth.calibration_inputs(790, n, K)
+    H = O.gptq_hessian(xb)
+    U = O.gptq_factor(H)
+    x = to_bf16(xb)
+    hess = ctx.gptq_hessian(x)
+    u_dev = ctx.gptq_factor(hess)
+    torch.cuda.synchronize()
+    Ud = u_dev.cpu().numpy().astype(np.float64)
+    rel = np.abs(Ud - U).max(axis=1) / np.abs(U).max(axis=1)
+    print("factor K=%d: max row-relative error %.2e" % (K, rel.max()))
+    assert np.isfinite(Ud).all() and rel.max() < 5e-4
+    del Ud
+    # the sweep with the oracle's own factor, so that the comparison is bit for bit
+    U32 = U.astype(np.float32)
+    got = ctx.gptq_quantize_pack(to_bf16(wb), torch.from_numpy(U32).to(DEV), 4)
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(790).choice(N, size=24, replace=False))
+    rows[0], rows[-1] = 0, N - 1
+    want = O.gptq_quantize_pack(wb[rows], U32, 4)
+    assert np.array_equal(got[0].cpu().numpy()[rows], want[0])
+    assert np.array_equal(bits_of(got[1])[rows], want[1]) and np.array_equal(bits_of(got[2])[rows], want[2])
+    # the sampled rows' output error against the plain quantizer's
+    wf = synth.bf16_bits_to_f32(wb[rows]).astype(np.float64)
+    e_comp = O.output_error(wf, O.dequantize(*want, 4), H)
+    e_plain = O.output_error(wf, O.dequantize(*O.quantize_pack(wb[rows], 4), 4), H)
+    print("output error on 24 rows: compensated %.4e, plain %.4e" % (e_comp, e_plain))
+    assert e_comp < 0.7 * e_plain

@@ -175,3 +175,32 @@ def test_gptq_mixtral_sized_matrix(ctx):
     e_plain = O.output_error(wf, O.dequantize(*O.quantize_pack(wb[rows], 4), 4), H)
     print("output error on 24 rows: compensated %.4e, plain %.4e" % (e_comp, e_plain))
     assert e_comp < 0.7 * e_plain
+
+
+def test_gptq_experts_feed_the_mixed_ffn(ctx):
+    """The compensated quantizer writes the plain quantizer's formats: the FFN reads its experts unchanged.
+    Two experts (int4 and int2) quantised on the device with calibration inputs for [F,H] and [H,F]; the
+    FFN's output against the oracle's FFN over the oracle's own compensated codes."""
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=3, H=256, F=512, E=2, k=2, config_id=83)
+    x, _ = synth.activations(cfg)
+    hw = {e: synth.expert_weights(cfg, e) for e in range(cfg.E)}
+    cal = {cfg.H: synth.calibration_inputs(83, 1024, cfg.H), cfg.F: synth.calibration_inputs(84, 1024, cfg.F)}
+    U = {K: O.gptq_factor(O.gptq_hessian(cal[K])).astype(np.float32) for K in cal}
+    Ud = {K: torch.from_numpy(U[K]).to(DEV) for K in U}
+    bits_np = np.array([4, 2], dtype=np.uint8)
+    experts_dev, experts_ref = [], []
+    for e in range(cfg.E):
+        b = int(bits_np[e])
+        experts_dev.append({"q%d" % b: [ctx.gptq_quantize_pack(to_bf16(m), Ud[m.shape[1]], b) for m in hw[e]]})
+        experts_ref.append({"q": [O.gptq_quantize_pack(m, U[m.shape[1]], b) for m in hw[e]]})
+    table, keep = B.make_expert_table(experts_dev, DEV)
+    idx_np = np.array([[0, 1], [1, 0], [0, 1]], dtype=np.int32)
+    w_np = np.array([[0.6, 0.4], [0.3, 0.7], [0.5, 0.5]], dtype=np.float32)
+    y = ctx.moe_ffn_mixed(to_bf16(x), torch.from_numpy(idx_np).to(DEV), torch.from_numpy(w_np).to(DEV),
+                          torch.from_numpy(bits_np).to(DEV), table, cfg.F, out_dtype=B.OUT_F32)
+    torch.cuda.synchronize()
+    ref = O.moe_ffn_mixed(x, idx_np, w_np.astype(np.float64), bits_np, experts_ref)
+    rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))
+    err = float((np.abs(y.cpu().numpy() - ref) / rms).max())
+    print("FFN over compensated experts: max err / rms = %.2e" % err)
+    assert err <= 2e-2

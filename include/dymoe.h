@@ -323,6 +323,17 @@ int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const 
 int dymoe_pack_tiles(dymoe_ctx* ctx, const void* w, long N, long K, void* tiles, void* stream);
 
 /*
+ * The same for a quantised matrix: codes [N, K*bits/8] with scale and zero
+ * [N, K/64] as dymoe_quantize_pack and dymoe_gptq_quantize_pack write them ->
+ * the tile layout the GEMM path reads (what dymoe_quantize_experts writes with
+ * DYMOE_LAYOUT_TILE), so that an expert quantised off-line (Sec. 5) serves
+ * prefill as well.  A pure permutation.  bits in {2,4,8}; N multiple of 32, K
+ * multiple of 128; code buffers 16-byte aligned; source and destination distinct.
+ */
+int dymoe_pack_code_tiles(dymoe_ctx* ctx, const uint8_t* codes, const void* scale, const void* zero, long N, long K,
+                          int bits, uint8_t* t_codes, void* t_scale, void* t_zero, void* stream);
+
+/*
  * Mixed-precision SwiGLU expert FFN (paper Sec. 4.1: the executor runs the
  * layer on a unified mixed-precision weight set; Sec. 1: a 0-bit expert is
  * skipped):

@@ -36,7 +36,7 @@ EXPORTS = [
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
     "dymoe_gptq_workspace_bytes", "dymoe_gptq_quantize_pack", "dymoe_gptq_hessian",
     "dymoe_gptq_factor_workspace_bytes", "dymoe_gptq_factor",
-    "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_moe_ffn_mixed", "dymoe_stream_copy",
+    "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_pack_code_tiles", "dymoe_moe_ffn_mixed", "dymoe_stream_copy",
     "dymoe_decode_front", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
     "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
     "dymoe_cache_create", "dymoe_cache_destroy", "dymoe_cache_request", "dymoe_cache_lookup",
@@ -131,6 +131,8 @@ lib.dymoe_gptq_quantize_pack.restype = _i
 lib.dymoe_gptq_quantize_pack.argtypes = [_vp, _vp, _vp, _l, _l, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.dymoe_quantize_experts.restype = _i
 lib.dymoe_quantize_experts.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]
+lib.dymoe_pack_code_tiles.restype = _i
+lib.dymoe_pack_code_tiles.argtypes = [_vp, _vp, _vp, _vp, _l, _l, _i, _vp, _vp, _vp, _vp]
 lib.dymoe_pack_tiles.restype = _i
 lib.dymoe_pack_tiles.argtypes = [_vp, _vp, _l, _l, _vp, _vp]
 lib.dymoe_moe_ffn_mixed.restype = _i
@@ -356,6 +358,18 @@ class Context:
         _check(lib.dymoe_quantize_experts(self._h, _ptr(table), _ptr(bits, torch.uint8),
                                           _ptr(load, torch.int32), E, H, F, group, layout,
                                           _stream(stream)), "dymoe_quantize_experts")
+
+    def pack_code_tiles(self, trip, bits, stream=None):
+        """(codes, scale, zero) row-major -> the same in the tile layout (new tensors)."""
+        codes, scale, zero = trip
+        N = codes.shape[0]
+        K = codes.shape[1] * 8 // bits
+        out = (torch.empty_like(codes), torch.empty_like(scale), torch.empty_like(zero))
+        _check(lib.dymoe_pack_code_tiles(self._h, _ptr(codes, torch.uint8), _ptr(scale, torch.float16),
+                                         _ptr(zero, torch.float16), N, K, bits, _ptr(out[0], torch.uint8),
+                                         _ptr(out[1], torch.float16), _ptr(out[2], torch.float16), _stream(stream)),
+               "dymoe_pack_code_tiles")
+        return out
 
     def pack_tiles(self, w, stream=None):
         N, K = w.shape

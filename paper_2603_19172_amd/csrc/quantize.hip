@@ -212,6 +212,28 @@ __global__ __launch_bounds__(256) void pack_tiles_kernel(const uint16_t* __restr
     reinterpret_cast<uint4*>(tiles)[i] = *reinterpret_cast<const uint4*>(w + row * K + col);
 }
 
+// packed codes + scale + zero, row-major -> tile layout: thread = (tile, lane); a lane's group is contiguous in
+// both layouts (8 * bits bytes), so the move is bits / 2 16-byte copies and two 2-byte ones
+__global__ __launch_bounds__(256) void pack_code_tiles_kernel(
+    const uint8_t* __restrict__ codes, const uint16_t* __restrict__ scale, const uint16_t* __restrict__ zero, long N,
+    long K, int bits, uint8_t* __restrict__ t_codes, uint16_t* __restrict__ t_scale, uint16_t* __restrict__ t_zero)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= N * K / 64) return;                              // one group per thread
+    const long tile = i >> 6;
+    const int lane = (int)(i & 63);
+    const long KT = K >> 7;
+    const long nt = tile / KT;
+    const long kt = tile - nt * KT;
+    const long row = nt * 32 + (lane & 31);
+    const long grp = kt * 2 + (lane >> 5);
+    const uint8_t* src = codes + row * (K * bits / 8) + grp * (8 * bits);
+    uint8_t* dst = t_codes + tile * (512 * bits) + lane * 16;
+    for (int c = 0; c < bits / 2; c++) store_global(dst + c * 1024, load_global<uint4>(src + 16 * c));
+    t_scale[tile * 64 + lane] = scale[row * (K >> 6) + grp];
+    t_zero[tile * 64 + lane] = zero[row * (K >> 6) + grp];
+}
+
 // Worklist of a layer: the experts whose assigned width is 8, 4 or 2 bits (and
 // that have load, when load is given), in ascending order.  Every workgroup
 // builds its own copy in LDS with its first wavefront (ballot + prefix count),
@@ -349,6 +371,25 @@ int dymoe_pack_tiles(dymoe_ctx* ctx, const void* w, long N, long K, void* tiles,
     if (blocks > 0x7fffffffL) return DYMOE_ENOTSUP;
     hipLaunchKernelGGL(dymoe::pack_tiles_kernel, dim3((unsigned)blocks), dim3(256), 0,
                        (hipStream_t)stream, (const uint16_t*)w, N, K, (uint16_t*)tiles);
+    DYMOE_HIP_LAUNCH_CHECK();
+    return DYMOE_OK;
+}
+
+int dymoe_pack_code_tiles(dymoe_ctx* ctx, const uint8_t* codes, const void* scale, const void* zero, long N, long K,
+                          int bits, uint8_t* t_codes, void* t_scale, void* t_zero, void* stream)
+{
+    DYMOE_REQUIRE(N >= 0 && K > 0 && N % 32 == 0 && K % 128 == 0 && (bits == 2 || bits == 4 || bits == 8));
+    if (N == 0) return ctx ? DYMOE_OK : DYMOE_ENOCTX;
+    DYMOE_REQUIRE(codes && scale && zero && t_codes && t_scale && t_zero);
+    DYMOE_REQUIRE(codes != t_codes && scale != t_scale && zero != t_zero);
+    DYMOE_REQUIRE(dymoe_aligned(codes, 16) && dymoe_aligned(t_codes, 16) && dymoe_aligned(scale, 2) &&
+                  dymoe_aligned(zero, 2) && dymoe_aligned(t_scale, 2) && dymoe_aligned(t_zero, 2));
+    if (!ctx) return DYMOE_ENOCTX;
+    const long blocks = (N * K / 64 + 255) / 256;
+    if (blocks > 0x7fffffffL) return DYMOE_ENOTSUP;
+    hipLaunchKernelGGL(dymoe::pack_code_tiles_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, codes,
+                       (const uint16_t*)scale, (const uint16_t*)zero, N, K, bits, t_codes, (uint16_t*)t_scale,
+                       (uint16_t*)t_zero);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }

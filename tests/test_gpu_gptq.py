@@ -204,3 +204,52 @@ def test_gptq_experts_feed_the_mixed_ffn(ctx):
     err = float((np.abs(y.cpu().numpy() - ref) / rms).max())
     print("FFN over compensated experts: max err / rms = %.2e" % err)
     assert err <= 2e-2
+
+
+def test_code_tiles_from_rowmajor_equal_the_quantizers_own_tiles(ctx):
+    """dymoe_pack_code_tiles is the permutation between the two layouts the plain quantizer can write."""
+    from paper_2603_19172_amd.layer import ExpertStore
+    cfg = synth.scaled(synth.CONFIGS["tiny"], H=384, F=256, E=3, k=2, config_id=85)
+    hw = {e: synth.expert_weights(cfg, e) for e in range(cfg.E)}
+    store = ExpertStore([[to_bf16(m) for m in hw[e]] for e in range(cfg.E)], cfg.H, cfg.F, DEV, formats=(8, 4, 2))
+    bits = torch.tensor([8, 4, 2], dtype=torch.uint8, device=DEV)
+    ones = torch.ones((cfg.E,), dtype=torch.int32, device=DEV)
+    ctx.quantize_experts(store.table, bits, ones, cfg.E, cfg.H, cfg.F, layout=B.LAYOUT_TILE)
+    for e, b in enumerate((8, 4, 2)):
+        for i in range(3):
+            tiles = ctx.pack_code_tiles(ctx.quantize_pack(store.w[e][i], b), b)
+            torch.cuda.synchronize()
+            # scale and zero of a tile are 64 fp16 in lane order: compare as flat arrays
+            assert torch.equal(tiles[0].flatten(), store.q[b][e][i][0].flatten())
+            assert torch.equal(tiles[1].flatten(), store.q[b][e][i][1].flatten())
+            assert torch.equal(tiles[2].flatten(), store.q[b][e][i][2].flatten())
+
+
+def test_gptq_experts_feed_the_grouped_gemm(ctx):
+    """Compensated experts, re-packed into tiles, through the MFMA path (8 tokens) against the oracle's FFN."""
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=8, H=256, F=512, E=2, k=2, config_id=86)
+    x, _ = synth.activations(cfg)
+    hw = {e: synth.expert_weights(cfg, e) for e in range(cfg.E)}
+    cal = {cfg.H: synth.calibration_inputs(86, 1024, cfg.H), cfg.F: synth.calibration_inputs(87, 1024, cfg.F)}
+    U = {K: O.gptq_factor(O.gptq_hessian(cal[K])).astype(np.float32) for K in cal}
+    Ud = {K: torch.from_numpy(U[K]).to(DEV) for K in U}
+    bits_np = np.array([4, 2], dtype=np.uint8)
+    experts_dev, experts_ref = [], []
+    for e in range(cfg.E):
+        b = int(bits_np[e])
+        rm = [ctx.gptq_quantize_pack(to_bf16(m), Ud[m.shape[1]], b) for m in hw[e]]
+        experts_dev.append({"q%d" % b: [ctx.pack_code_tiles(t, b) for t in rm]})
+        experts_ref.append({"q": [O.gptq_quantize_pack(m, U[m.shape[1]], b) for m in hw[e]]})
+    table, keep = B.make_expert_table(experts_dev, DEV)
+    rng = np.random.default_rng(86)
+    idx_np = np.stack([rng.permutation(2) for _ in range(cfg.T)]).astype(np.int32)
+    w_np = rng.uniform(0.2, 0.8, size=(cfg.T, 1)).astype(np.float32)
+    w_np = np.concatenate([w_np, 1.0 - w_np], axis=1)
+    y = ctx.moe_ffn_mixed(to_bf16(x), torch.from_numpy(idx_np).to(DEV), torch.from_numpy(w_np).to(DEV),
+                          torch.from_numpy(bits_np).to(DEV), table, cfg.F, out_dtype=B.OUT_F32, path=B.PATH_GEMM)
+    torch.cuda.synchronize()
+    ref = O.moe_ffn_mixed(x, idx_np, w_np.astype(np.float64), bits_np, experts_ref)
+    rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))
+    err = float((np.abs(y.cpu().numpy() - ref) / rms).max())
+    print("grouped GEMM over compensated experts: max err / rms = %.2e" % err)
+    assert err <= 2e-2

@@ -102,6 +102,12 @@ def test_argument_validation_happens_before_any_device_work():
     assert lib.dymoe_pack_tiles(None, P, 48, 256, 2 * P, None) == B.EINVAL
     assert lib.dymoe_pack_tiles(None, P, 64, 192, 2 * P, None) == B.EINVAL
     assert lib.dymoe_pack_tiles(None, P, 64, 256, P, None) == B.EINVAL                          # in place
+    pc = lib.dymoe_pack_code_tiles
+    assert pc(None, P, P, P, 64, 256, 4, 2 * P, 2 * P, 2 * P, None) == B.ENOCTX
+    assert pc(None, P, P, P, 48, 256, 4, 2 * P, 2 * P, 2 * P, None) == B.EINVAL
+    assert pc(None, P, P, P, 64, 192, 4, 2 * P, 2 * P, 2 * P, None) == B.EINVAL
+    assert pc(None, P, P, P, 64, 256, 3, 2 * P, 2 * P, 2 * P, None) == B.EINVAL
+    assert pc(None, P, P, P, 64, 256, 4, P, 2 * P, 2 * P, None) == B.EINVAL                     # in place
     # fused decode front end
     df = lib.dymoe_decode_front
     assert df(None, P, P, None, 1, 256, 8, 2, 1, 3, tcp, tbp, 0, P, P, P, P, P, P, P, None) == B.ENOCTX

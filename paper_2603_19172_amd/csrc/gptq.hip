@@ -18,8 +18,8 @@
 //
 // Rows are independent, columns are not.  Per group of 64 columns two launches:
 //   group kernel   a lane owns a row: the group's 64 values in registers, the
-//                  64 x 64 diagonal block of U read through the scalar cache
-//                  (every lane needs the same value); quantises the 64 columns
+//                  64 x 64 diagonal block of U staged in LDS and read as
+//                  broadcasts (every lane needs the same value); quantises the 64 columns
 //                  in order, applies the corrections inside the group, writes
 //                  codes, scale, zero and the 64 errors e of the row;
 //   trail kernel   v[:, j] for all later columns j: 64 chained FMAs per element,
@@ -59,8 +59,8 @@ __global__ __launch_bounds__(256) void gptq_widen_kernel(const uint16_t* __restr
 // e of (column c, row) goes to own_p[c * own_cs + row * own_rs] (OWN; the row range must then be whole blocks of 64)
 // and to pad_p[c * pad_cs + slot * pad_rs] (PAD) for every lane of the grid, rows rounded up to 64: a buffer of that
 // many rows, from which the trail kernel loads whole 64-row tiles.  Which of the two are written is fixed at compile
-// time: with run-time tests around the stores the 64 unrolled columns fall apart into basic blocks and the scalar
-// registers holding the diagonal block spill.
+// time: with run-time tests around the stores the 64 unrolled columns fall apart into basic blocks, and the
+// values the compiler keeps across them spill.
 template <int BITS, bool OWN, bool PAD>
 __global__ __launch_bounds__(kGqRows) void gptq_group_kernel(
     const float* __restrict__ x_in, long ldx, const float* __restrict__ d, long ldd, long row_begin, long row_end,
@@ -98,6 +98,14 @@ __global__ __launch_bounds__(kGqRows) void gptq_group_kernel(
         s = (float)sh;
         inv = (s > 0.0f) ? (1.0f / s) : 0.0f;
     }
+    // The diagonal block goes through LDS: every lane needs every value, one row per column step, and fetched row
+    // by row from memory (the scalar cache's way) each step would wait out a full memory latency: 64 in a chain.
+    __shared__ __attribute__((aligned(16))) float s_d[kGqGroup][kGqGroup];
+#pragma unroll
+    for (int c = 0; c < kGqGroup / 4; c++)
+        *reinterpret_cast<float4*>(&s_d[threadIdx.x][4 * c]) =
+            *reinterpret_cast<const float4*>(d + (long)threadIdx.x * ldd + 4 * c);
+    __syncthreads();
     uint32_t words[n_words];
 #pragma unroll
     for (int i = 0; i < n_words; i++) words[i] = 0u;
@@ -113,12 +121,12 @@ __global__ __launch_bounds__(kGqRows) void gptq_group_kernel(
             dq = dq + m;
             rest = x[i] - dq;
         }
-        const float e = rest / d[(long)i * ldd + i];             // the same address in every lane: scalar loads
+        const float e = rest / s_d[i][i];
         if constexpr (OWN) own_p[(long)i * own_cs + slot * own_rs] = e;
         if constexpr (PAD) pad_p[(long)i * pad_cs + slot * pad_rs] = e;
         const float ne = -e;
 #pragma unroll
-        for (int j = i + 1; j < kGqGroup; j++) x[j] = __builtin_fmaf(ne, d[(long)i * ldd + j], x[j]);
+        for (int j = i + 1; j < kGqGroup; j++) x[j] = __builtin_fmaf(ne, s_d[i][j], x[j]);
     }
     if constexpr (BITS != 0) {
         if (mine) {
@@ -361,14 +369,18 @@ __global__ __launch_bounds__(kWave) void gptq_chol_diag_kernel(const float* __re
     float col[kGqGroup];                                          // A[i, j], read from the lower triangle
 #pragma unroll
     for (int i = 0; i < kGqGroup; i++) col[i] = v[(j0 + max(i, j)) * K + j0 + min(i, j)];
+    // row c of R is handed from lane to lane through LDS (one write, broadcast reads)
+    __shared__ __attribute__((aligned(16))) float s_row[2][kGqGroup];
 #pragma unroll
     for (int c = 0; c < kGqGroup; c++) {
         const float dcc = __shfl(col[c], c, kWave);
         const float rd = sqrtf(dcc);
         const float rj = (j >= c) ? col[c] / rd : 0.0f;           // R[c, j]
         r[(j0 + c) * K + j0 + j] = rj;
+        s_row[c & 1][j] = rj;
+        __syncthreads();                                          // one wavefront: orders the LDS write before the reads
 #pragma unroll
-        for (int i = c + 1; i < kGqGroup; i++) col[i] = __builtin_fmaf(-__shfl(rj, i, kWave), rj, col[i]);
+        for (int i = c + 1; i < kGqGroup; i++) col[i] = __builtin_fmaf(-s_row[c & 1][i], rj, col[i]);
     }
 }
 

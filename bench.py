@@ -403,7 +403,8 @@ def main():
                 "sweep_ms_wall": round((t2 - t1) * 1e3, 2),
                 "sweep_kernels_ms": {"group": round(swp["gptq_group"][0], 2), "trail": round(swp["gptq_trail"][0], 2)},
                 "sweep_trail_TFLOPs_fp32": round(trail_flops / (swp["gptq_trail"][0] * 1e-3) / 1e12, 1),
-                "sweep_trail_frac_fp32_vector_peak": round(trail_flops / (swp["gptq_trail"][0] * 1e-3) / 1e12 / 157.3, 3),
+                # 157.3 TFLOP/s is the packed-fp32 figure; one v_fma_f32 per lane (this build emits no packed fp32) peaks at half
+                "sweep_trail_frac_fp32_fma_peak_78p6": round(trail_flops / (swp["gptq_trail"][0] * 1e-3) / 1e12 / 78.65, 3),
                 "finite": bool(torch.isfinite(gu).all())}
             del hess, gu, fws, sws, gx, gw, gout
             torch.cuda.empty_cache()

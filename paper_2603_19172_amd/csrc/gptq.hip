@@ -140,62 +140,68 @@ __global__ __launch_bounds__(kGqRows) void gptq_group_kernel(
     }
 }
 
-// v[r, j] = fma(-E[c, r], B[c, j], v[r, j]) for c = 0 .. 63 in that order, rows [row_begin, row_end) in tiles of
+// v[r, j] = fma(-E[c, r], B[c, j], v[r, j]) for c = 0 .. 64 n_chunks - 1 in that order (one or two groups' worth of
+// corrections in one pass over v: the working copy is what this kernel streams), rows [row_begin, row_end) in tiles of
 // 64 from row_begin, columns [col_begin, col_end) in tiles of 128 from col_begin.  E[c, r] = e[c * lde + r] (whole
 // 64-row tiles are loaded: the buffer covers the rows rounded up), B[c, j] = b[c * ldb + j].  lower_only: tiles that
 // lie wholly above the diagonal (every row < every column) are left alone.
 __global__ __launch_bounds__(kGqTrailThreads) void gptq_trail_kernel(
     float* __restrict__ v, long ldv, const float* __restrict__ e, long lde, const float* __restrict__ b, long ldb,
-    long row_begin, long row_end, long col_begin, long col_end, int lower_only)
+    long row_begin, long row_end, long col_begin, long col_end, int n_chunks, int lower_only)
 {
     __shared__ __attribute__((aligned(16))) float s_e[kGqGroup][kGqRows];
     __shared__ __attribute__((aligned(16))) float s_u[kGqGroup][kGqTrailCols];
     const int tid = threadIdx.x;
     const long col0 = col_begin + (long)blockIdx.x * kGqTrailCols;
     const long row0 = row_begin + (long)blockIdx.y * kGqRows;
-    if (lower_only && row0 + kGqRows - 1 < col0) return;
-#pragma unroll
-    for (int i = 0; i < kGqGroup * kGqRows / 4 / kGqTrailThreads; i++) {
-        const int at = (i * kGqTrailThreads + tid) * 4;
-        const int c = at / kGqRows, r = at % kGqRows;
-        *reinterpret_cast<float4*>(&s_e[c][r]) = *reinterpret_cast<const float4*>(e + (long)c * lde + row0 + r);
-    }
-#pragma unroll
-    for (int i = 0; i < kGqGroup * kGqTrailCols / 4 / kGqTrailThreads; i++) {
-        const int at = (i * kGqTrailThreads + tid) * 4;
-        const int c = at / kGqTrailCols, n = at % kGqTrailCols;
-        float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (col0 + n < col_end) q = *reinterpret_cast<const float4*>(b + (long)c * ldb + col0 + n);
-        *reinterpret_cast<float4*>(&s_u[c][n]) = q;
-    }
-    __syncthreads();
+    if (lower_only && row0 + kGqRows - 1 < col0) return;        // the whole workgroup
     const int tx = tid & 31, ty = tid >> 5;
     const long col = col0 + 4 * tx;
     const long row = row0 + 8 * ty;
-    if (col >= col_end) return;
+    const bool in_cols = col < col_end;
     float4 acc[8];
 #pragma unroll
     for (int i = 0; i < 8; i++) {
         acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row + i < row_end) acc[i] = *reinterpret_cast<const float4*>(v + (row + i) * ldv + col);
+        if (in_cols && row + i < row_end) acc[i] = *reinterpret_cast<const float4*>(v + (row + i) * ldv + col);
     }
-#pragma unroll 4
-    for (int c = 0; c < kGqGroup; c++) {
-        const float4 e0 = *reinterpret_cast<const float4*>(&s_e[c][8 * ty]);
-        const float4 e1 = *reinterpret_cast<const float4*>(&s_e[c][8 * ty + 4]);
-        const float4 uu = *reinterpret_cast<const float4*>(&s_u[c][4 * tx]);
-        const float ne[8] = {-e0.x, -e0.y, -e0.z, -e0.w, -e1.x, -e1.y, -e1.z, -e1.w};
+    for (int ch = 0; ch < n_chunks; ch++) {
+        if (ch) __syncthreads();                    // the previous chunk's reads of LDS are done
+        const float* ec = e + (long)ch * kGqGroup * lde;
+        const float* bc = b + (long)ch * kGqGroup * ldb;
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            acc[i].x = __builtin_fmaf(ne[i], uu.x, acc[i].x);
-            acc[i].y = __builtin_fmaf(ne[i], uu.y, acc[i].y);
-            acc[i].z = __builtin_fmaf(ne[i], uu.z, acc[i].z);
-            acc[i].w = __builtin_fmaf(ne[i], uu.w, acc[i].w);
+        for (int i = 0; i < kGqGroup * kGqRows / 4 / kGqTrailThreads; i++) {
+            const int at = (i * kGqTrailThreads + tid) * 4;
+            const int c = at / kGqRows, r = at % kGqRows;
+            *reinterpret_cast<float4*>(&s_e[c][r]) = *reinterpret_cast<const float4*>(ec + (long)c * lde + row0 + r);
+        }
+#pragma unroll
+        for (int i = 0; i < kGqGroup * kGqTrailCols / 4 / kGqTrailThreads; i++) {
+            const int at = (i * kGqTrailThreads + tid) * 4;
+            const int c = at / kGqTrailCols, n = at % kGqTrailCols;
+            float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (col0 + n < col_end) q = *reinterpret_cast<const float4*>(bc + (long)c * ldb + col0 + n);
+            *reinterpret_cast<float4*>(&s_u[c][n]) = q;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int c = 0; c < kGqGroup; c++) {
+            const float4 e0 = *reinterpret_cast<const float4*>(&s_e[c][8 * ty]);
+            const float4 e1 = *reinterpret_cast<const float4*>(&s_e[c][8 * ty + 4]);
+            const float4 uu = *reinterpret_cast<const float4*>(&s_u[c][4 * tx]);
+            const float ne[8] = {-e0.x, -e0.y, -e0.z, -e0.w, -e1.x, -e1.y, -e1.z, -e1.w};
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                acc[i].x = __builtin_fmaf(ne[i], uu.x, acc[i].x);
+                acc[i].y = __builtin_fmaf(ne[i], uu.y, acc[i].y);
+                acc[i].z = __builtin_fmaf(ne[i], uu.z, acc[i].z);
+                acc[i].w = __builtin_fmaf(ne[i], uu.w, acc[i].w);
+            }
         }
     }
 #pragma unroll
     for (int i = 0; i < 8; i++)
-        if (row + i < row_end) *reinterpret_cast<float4*>(v + (row + i) * ldv + col) = acc[i];
+        if (in_cols && row + i < row_end) *reinterpret_cast<float4*>(v + (row + i) * ldv + col) = acc[i];
 }
 
 // ---------------------------------------------------------------------------
@@ -392,7 +398,7 @@ size_t dymoe_gptq_workspace_bytes(long N, long K)
 {
     if (N <= 0 || K <= 0) return 0;
     return dymoe::gq_round256((size_t)N * (size_t)K * 4) +
-           dymoe::gq_round256((size_t)dymoe::kGqGroup * (size_t)dymoe::gq_rows_padded(N) * 4);
+           dymoe::gq_round256(2 * (size_t)dymoe::kGqGroup * (size_t)dymoe::gq_rows_padded(N) * 4);
 }
 
 int dymoe_gptq_quantize_pack(dymoe_ctx* ctx, const void* w_bf16, const float* u, long N, long K, int bits, int group,
@@ -417,36 +423,49 @@ int dymoe_gptq_quantize_pack(dymoe_ctx* ctx, const void* w_bf16, const float* u,
                        (const uint16_t*)w_bf16, n_elems, v);
     DYMOE_HIP_LAUNCH_CHECK();
     const dim3 grid_a((unsigned)(n_pad / kGqRows));
-    float* const none = nullptr;
     const long G = K / kGqGroup;
-    for (long base = 0; base < K; base += kGqGroup) {
+    // one group of 64 columns: codes, scale, zero; its 64 errors per row go to err rows [64 * slot, 64 * slot + 64)
+    auto group_step = [&](long base, int slot) {
         const float* xg = v + base;
         const float* dg = u + base * K + base;
         uint8_t* cg = codes + base * bits / 8;
         uint16_t* sg = (uint16_t*)scale + base / kGqGroup;
         uint16_t* zg = (uint16_t*)zero + base / kGqGroup;
+        float* eg = err + (long)slot * kGqGroup * n_pad;
+        float* const none = nullptr;
         switch (bits) {
         case 8:
             dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<8, false, true>), grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
-                         0L, N, none, 0L, 0L, err, n_pad, 1L, cg, sg, zg, K * bits / 8, G);
+                         0L, N, none, 0L, 0L, eg, n_pad, 1L, cg, sg, zg, K * bits / 8, G);
             break;
         case 4:
             dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<4, false, true>), grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
-                         0L, N, none, 0L, 0L, err, n_pad, 1L, cg, sg, zg, K * bits / 8, G);
+                         0L, N, none, 0L, 0L, eg, n_pad, 1L, cg, sg, zg, K * bits / 8, G);
             break;
         default:
             dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<2, false, true>), grid_a, dim3(kGqRows), 0, st, xg, K, dg, K,
-                         0L, N, none, 0L, 0L, err, n_pad, 1L, cg, sg, zg, K * bits / 8, G);
+                         0L, N, none, 0L, 0L, eg, n_pad, 1L, cg, sg, zg, K * bits / 8, G);
             break;
         }
+    };
+    // corrections of `chunks` groups starting at column `base`, applied to the columns [col_begin, col_end)
+    auto trail_step = [&](long base, int chunks, long col_begin, long col_end) {
+        const dim3 grid_b((unsigned)((col_end - col_begin + kGqTrailCols - 1) / kGqTrailCols), (unsigned)(n_pad / kGqRows));
+        dymoe_launch(ctx, DYMOE_K_GPTQ_TRAIL, gptq_trail_kernel, grid_b, dim3(kGqTrailThreads), 0, st, v, K,
+                     (const float*)err, n_pad, u + base * K, K, 0L, N, col_begin, col_end, chunks, 0);
+    };
+    // Two groups per pass over the working copy: the first group's corrections reach the second group's 64 columns
+    // at once, the second group is quantised, and both groups' 128 corrections then go over the remaining columns
+    // together, in the same order as one group at a time (so the same roundings) at half the traffic.
+    for (long base = 0; base < K; base += 2 * kGqGroup) {
+        group_step(base, 0);
         DYMOE_HIP_LAUNCH_CHECK();
-        const long rest = K - base - kGqGroup;
-        if (rest > 0) {
-            const dim3 grid_b((unsigned)((rest + kGqTrailCols - 1) / kGqTrailCols), (unsigned)(n_pad / kGqRows));
-            dymoe_launch(ctx, DYMOE_K_GPTQ_TRAIL, gptq_trail_kernel, grid_b, dim3(kGqTrailThreads), 0, st, v, K,
-                         (const float*)err, n_pad, u + base * K, K, 0L, N, base + kGqGroup, K, 0);
-            DYMOE_HIP_LAUNCH_CHECK();
-        }
+        if (base + kGqGroup >= K) break;
+        trail_step(base, 1, base + kGqGroup, base + 2 * kGqGroup);
+        group_step(base + kGqGroup, 1);
+        DYMOE_HIP_LAUNCH_CHECK();
+        if (base + 2 * kGqGroup < K) trail_step(base, 2, base + 2 * kGqGroup, K);
+        DYMOE_HIP_LAUNCH_CHECK();
     }
     return DYMOE_OK;
 }
@@ -467,8 +486,8 @@ int dymoe_gptq_hessian(dymoe_ctx* ctx, const void* x_bf16, long n, long K, int a
 size_t dymoe_gptq_factor_workspace_bytes(long K)
 {
     if (K <= 0) return 0;
-    // the reversed damped Hessian (later the substitution's right-hand sides), its Cholesky factor, 64 errors per row, damping
-    return 2 * dymoe::gq_round256((size_t)K * (size_t)K * 4) + dymoe::gq_round256((size_t)dymoe::kGqGroup * (size_t)K * 4) + 256;
+    // the reversed damped Hessian (later the substitution's right-hand sides), its Cholesky factor, 128 errors per row, damping
+    return 2 * dymoe::gq_round256((size_t)K * (size_t)K * 4) + dymoe::gq_round256(2 * (size_t)dymoe::kGqGroup * (size_t)K * 4) + 256;
 }
 
 int dymoe_gptq_factor(dymoe_ctx* ctx, const float* hess, long K, float damp, float* u, void* workspace,
@@ -485,45 +504,65 @@ int dymoe_gptq_factor(dymoe_ctx* ctx, const float* hess, long K, float damp, flo
     float* v = reinterpret_cast<float*>(workspace);
     float* r = reinterpret_cast<float*>((char*)workspace + mat);
     float* err = reinterpret_cast<float*>((char*)workspace + 2 * mat);
-    float* lambda = reinterpret_cast<float*>((char*)workspace + 2 * mat + gq_round256((size_t)kGqGroup * (size_t)K * 4));
+    float* lambda = reinterpret_cast<float*>((char*)workspace + 2 * mat + gq_round256(2 * (size_t)kGqGroup * (size_t)K * 4));
     const dim3 whole((unsigned)((K * K + 255) / 256));
-    float* const none = nullptr;
     hipLaunchKernelGGL(gptq_damping_kernel, dim3(1), dim3(256), 0, st, hess, K, damp, lambda);
     hipLaunchKernelGGL(gptq_reverse_kernel, whole, dim3(256), 0, st, hess, K, (const float*)lambda, v);
     hipLaunchKernelGGL(gptq_fill_kernel, whole, dim3(256), 0, st, r, K, 0.0f);
     DYMOE_HIP_LAUNCH_CHECK();
+    float* const none = nullptr;
+    // (both loops take two blocks of 64 per pass over the trailing matrix, as the quantizer's sweep does)
+    auto trail = [&](long row_begin, long row_end, long col_begin, long col_end, const float* e, long lde, const float* b,
+                     int chunks, int lower_only) {
+        const dim3 grid_b((unsigned)((col_end - col_begin + kGqTrailCols - 1) / kGqTrailCols),
+                          (unsigned)((row_end - row_begin) / kGqRows));
+        dymoe_launch(ctx, DYMOE_K_GPTQ_TRAIL, gptq_trail_kernel, grid_b, dim3(kGqTrailThreads), 0, st, v, K, e, lde, b, K,
+                     row_begin, row_end, col_begin, col_end, chunks, lower_only);
+    };
     // J (H + damping) J = R^T R
-    for (long j0 = 0; j0 < K; j0 += kGqGroup) {
+    // diagonal block at j0, then the rows below it solved against it: the panel of L goes into R as rows,
+    // L[row, j0 + c] = R[j0 + c, row]
+    auto chol_block = [&](long j0) {
         dymoe_launch(ctx, DYMOE_K_GPTQ_FACTOR, gptq_chol_diag_kernel, dim3(1), dim3(kWave), 0, st, (const float*)v, K, j0, r);
         const long below = K - j0 - kGqGroup;
-        if (below > 0) {
-            const long rb = j0 + kGqGroup;
-            // the panel of L goes into R as rows: L[row, j0 + c] = R[j0 + c, row]
-            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<0, true, false>), dim3((unsigned)(below / kGqRows)), dim3(kGqRows), 0,
-                         st, (const float*)(v + j0), K, (const float*)(r + j0 * K + j0), K, rb, K, r + j0 * K, K, 1L, none, 0L, 0L,
-                         (uint8_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, 0L, 0L);
-            const dim3 grid_b((unsigned)((below + kGqTrailCols - 1) / kGqTrailCols), (unsigned)(below / kGqRows));
-            dymoe_launch(ctx, DYMOE_K_GPTQ_TRAIL, gptq_trail_kernel, grid_b, dim3(kGqTrailThreads), 0, st, v, K,
-                         (const float*)(r + j0 * K), K, (const float*)(r + j0 * K), K, rb, K, rb, K, 1);
-        }
+        if (below > 0)
+            dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<0, true, false>), dim3((unsigned)(below / kGqRows)),
+                         dim3(kGqRows), 0, st, (const float*)(v + j0), K, (const float*)(r + j0 * K + j0), K, j0 + kGqGroup, K,
+                         r + j0 * K, K, 1L, none, 0L, 0L, (uint8_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, 0L, 0L);
+    };
+    for (long j0 = 0; j0 < K; j0 += 2 * kGqGroup) {
+        const long j1 = j0 + kGqGroup, j2 = j0 + 2 * kGqGroup;
+        chol_block(j0);
+        DYMOE_HIP_LAUNCH_CHECK();
+        if (j1 >= K) break;
+        trail(j1, K, j1, j2, r + j0 * K, K, r + j0 * K, 1, 1);          // the next block's columns first
+        chol_block(j1);
+        DYMOE_HIP_LAUNCH_CHECK();
+        if (j2 < K) trail(j2, K, j2, K, r + j0 * K, K, r + j0 * K, 2, 1);  // then both panels over the rest of the lower triangle
         DYMOE_HIP_LAUNCH_CHECK();
     }
     // rows of R^-T by forward substitution of the unit vectors, mirrored into U
     hipLaunchKernelGGL(gptq_fill_kernel, whole, dim3(256), 0, st, v, K, 1.0f);
     hipLaunchKernelGGL(gptq_fill_kernel, whole, dim3(256), 0, st, u, K, 0.0f);
     DYMOE_HIP_LAUNCH_CHECK();
-    for (long base = 0; base < K; base += kGqGroup) {
-        const long rows = base + kGqGroup;
-        // e of (row c, column base + i) is U[K - 1 - base - i, K - 1 - c]
-        dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<0, true, true>), dim3((unsigned)(rows / kGqRows)), dim3(kGqRows), 0, st,
-                     (const float*)(v + base), K, (const float*)(r + base * K + base), K, 0L, rows,
-                     u + (K - 1 - base) * K + (K - 1), -K, -1L, err, K, 1L, (uint8_t*)nullptr, (uint16_t*)nullptr, (uint16_t*)nullptr, 0L, 0L);
-        const long rest = K - rows;
-        if (rest > 0) {
-            const dim3 grid_b((unsigned)((rest + kGqTrailCols - 1) / kGqTrailCols), (unsigned)(rows / kGqRows));
-            dymoe_launch(ctx, DYMOE_K_GPTQ_TRAIL, gptq_trail_kernel, grid_b, dim3(kGqTrailThreads), 0, st, v, K,
-                         (const float*)err, K, (const float*)(r + base * K), K, 0L, rows, rows, K, 0);
-        }
+    // one block of 64 columns for the rows [0, rows): e of (row c, column base + i) is U[K - 1 - base - i, K - 1 - c];
+    // rows that have not started yet (c >= base + 64) hold zeros there and give e = 0
+    auto subst_block = [&](long base, long rows, int slot) {
+        dymoe_launch(ctx, DYMOE_K_GPTQ_GROUP, (gptq_group_kernel<0, true, true>), dim3((unsigned)(rows / kGqRows)), dim3(kGqRows),
+                     0, st, (const float*)(v + base), K, (const float*)(r + base * K + base), K, 0L, rows,
+                     u + (K - 1 - base) * K + (K - 1), -K, -1L, err + (long)slot * kGqGroup * K, K, 1L, (uint8_t*)nullptr,
+                     (uint16_t*)nullptr, (uint16_t*)nullptr, 0L, 0L);
+    };
+    for (long base = 0; base < K; base += 2 * kGqGroup) {
+        const long b1 = base + kGqGroup, b2 = base + 2 * kGqGroup;
+        const long rows = (b2 < K) ? b2 : K;
+        subst_block(base, rows, 0);
+        DYMOE_HIP_LAUNCH_CHECK();
+        if (b1 >= K) break;
+        trail(0, b1, b1, b2, err, K, r + base * K, 1, 0);
+        subst_block(b1, rows, 1);
+        DYMOE_HIP_LAUNCH_CHECK();
+        if (b2 < K) trail(0, b2, b2, K, err, K, r + base * K, 2, 0);
         DYMOE_HIP_LAUNCH_CHECK();
     }
     return DYMOE_OK;

@@ -271,9 +271,9 @@ int dymoe_quantize_pack(dymoe_ctx* ctx, const void* w, long N, long K, int bits,
  * read; U[c,c] > 0); from dymoe_gptq_factor or the caller's own.  The identity
  * gives dymoe_quantize_pack's result.  workspace: dymoe_gptq_workspace_bytes(N,
  * K) bytes of device memory, 256-byte aligned (an fp32 copy of the matrix and
- * 64 errors per row); its contents are garbage afterwards.  Other arguments,
+ * 128 errors per row); its contents are garbage afterwards.  Other arguments,
  * limits and errors as dymoe_quantize_pack; DYMOE_ENOSPC if the workspace is
- * too small.  Enqueues 2 K/64 launches on `stream`; never synchronises.
+ * too small.  Enqueues about 2 K/64 launches on `stream`; never synchronises.
  */
 /*
  * The two steps before it (GPTQ as published; Sec. 5 of the paper only names it).

@@ -16,15 +16,18 @@
 // for the trailing update (it would round differently), but the same work as
 // a chain of fp32 FMAs in registers.
 //
-// Rows are independent, columns are not.  Per group of 64 columns two launches:
+// Rows are independent, columns are not.  Per group of 64 columns two kinds of launch:
 //   group kernel   a lane owns a row: the group's 64 values in registers, the
 //                  64 x 64 diagonal block of U staged in LDS and read as
 //                  broadcasts (every lane needs the same value); quantises the 64 columns
 //                  in order, applies the corrections inside the group, writes
 //                  codes, scale, zero and the 64 errors e of the row;
-//   trail kernel   v[:, j] for all later columns j: 64 chained FMAs per element,
-//                  a workgroup on a 64-row x 128-column tile with the errors and
-//                  the 64 x 128 block of U in LDS, 8 x 4 elements per thread.
+//   trail kernel   v[:, j] for later columns j: 64 chained FMAs per element and
+//                  group, a workgroup on a 64-row x 128-column tile with the
+//                  errors and the 64 x 128 block of U in LDS, 8 x 4 elements per
+//                  thread.  Groups go in pairs: the first group's corrections
+//                  reach the second group's columns at once, and both groups'
+//                  128 corrections then go over the remaining columns in one pass.
 // The working copy v of the matrix (fp32) lives in the caller's workspace.
 #include "common.hpp"
 

@@ -186,3 +186,39 @@ def test_mixtral_prefill_full(ctx):
 
 def test_fine_grained_prefill_full(ctx):
     _prefill_case(ctx, synth.CONFIGS["fine_grained"], n_sample=8, seed=2)
+
+
+@pytest.mark.parametrize("T", [1, 4])
+def test_fine_grained_decode_full(ctx, T):
+    """Decode on the fine-grained layer's shape (128 experts of 768, top-8, Zipf router bias): the
+    single-launch front end with 128 experts, then the GEMV path over 8 T (token, expert) pairs in three
+    formats (2 experts bf16, 3 int4, the rest int2)."""
+    cfg = synth.scaled(synth.CONFIGS["fine_grained"], T=T, phase="decode", k_hh=0, tier_count=(2, 3, 123),
+                       config_id=44 + T)
+    x, _ = synth.activations(cfg)
+    wg, bias = synth.router(cfg)
+    ridx, rw, rp, rl = O.route_topk(x, wg, bias, cfg.k)
+    assert margin_ok(rl, cfg.k).all()
+    need = set(int(e) for e in ridx.ravel())
+    host_w = synth.expert_weights_many(cfg, sorted(need), workers=6)
+    rimp = O.expert_importance_decode(rp)
+    rload = np.bincount(ridx.ravel(), minlength=cfg.E).astype(np.int32)
+    order = np.sort(rimp)[::-1]
+    assert (order[:6] - order[1:7] > 1e-6).all()     # the tier boundaries are decided well inside fp32
+    rbits, rrank = O.assign_precision(rimp, rload, cfg.tier_count, cfg.tier_bits)
+    store = _store(ctx, cfg, host_w, need)
+    layer = MoELayer(ctx, cfg.T, cfg.H, cfg.F, cfg.E, cfg.k, "decode", cfg.tier_count, cfg.tier_bits,
+                     out_dtype=B.OUT_F32, device=DEV)
+    assert layer.layout == B.LAYOUT_ROWMAJOR
+    y = layer.step(to_bf16(x), to_bf16(wg), torch.from_numpy(bias).to(DEV), store)
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.idx.cpu().numpy(), ridx)
+    assert np.array_equal(layer.load.cpu().numpy(), rload)
+    got_bits = layer.bits.cpu().numpy()
+    assert np.array_equal(got_bits[sorted(need)], rbits[sorted(need)])
+    assert sorted(set(int(rbits[e]) for e in need)) in ([2, 4, 16], [4, 16], [2, 16], [2, 4])
+    ref = O.moe_ffn_mixed(x, ridx, rw, _masked_bits(cfg, rbits, need), _oracle_experts(cfg, host_w, rbits, need))
+    err = rel_err_per_token(y.cpu().numpy().astype(np.float64), ref)
+    print("fine-grained decode T=%d, formats of the selected experts %s: err=%.3e"
+          % (T, sorted(int(rbits[e]) for e in need), err))
+    assert err <= FFN_TOL

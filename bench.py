@@ -362,7 +362,38 @@ def main():
             "grouped_gemm_us": round(fg_us, 1),
             "grouped_gemm_frac_mfma_bf16_peak": round(fflops / (fg_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
             "kernels_us": {n: round(v[0] / max(v[1], 1) * 1e3, 1) for n, v in fk.items()}}
-        del fstore, flay
+        # one decode token on the same layer (the selected experts rank first, so all eight run in bf16):
+        # 75 MB of weights, a step made of launch latencies rather than bandwidth
+        dcfg = synth.scaled(fcfg, T=1, phase="decode", k_hh=0, config_id=45)
+        dx = bf16(synth.activations(dcfg)[0])
+        dlay = MoELayer(ctx, 1, fcfg.H, fcfg.F, fcfg.E, fcfg.k, "decode", fcfg.tier_count, fcfg.tier_bits,
+                        out_dtype=B.OUT_BF16, device=dev)
+        drun = lambda: dlay.step(dx, fwg, fbias, fstore)
+        for _ in range(3):
+            drun()
+        torch.cuda.synchronize()
+        if not args.no_graph:
+            dgraph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(dgraph, stream=torch.cuda.Stream()):
+                drun()
+            drun = dgraph.replay
+        for _ in range(5):
+            drun()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(200):
+            drun()
+        torch.cuda.synchronize()
+        ddt = (time.perf_counter() - t0) / 200
+        dsel = dlay.idx.cpu().numpy().ravel()
+        dbits = dlay.bits.cpu().numpy()
+        dbytes = sum({16: 2.0, 8: 1.0625, 4: 0.5625, 2: 0.3125}[int(dbits[e])] * 3 * fcfg.H * fcfg.F for e in dsel)
+        out["fine_grained_2048"]["decode_1_token"] = {
+            "us_per_step_full_path": round(ddt * 1e6, 1), "tokens_per_s": round(1.0 / ddt, 1),
+            "selected_bits": [int(dbits[e]) for e in dsel], "weight_bytes": dbytes,
+            "GBps": round(dbytes / ddt / 1e9, 1),
+            "note": "same weights hot in the caches from step to step: a latency figure, not a bandwidth one"}
+        del fstore, flay, dlay
         torch.cuda.empty_cache()
 
     # ---------------------------------------------------------------- error-compensated quantizer (opt-in)

@@ -44,6 +44,9 @@ __device__ __forceinline__ void assign_one(int e, int E, const ImpT* s_imp, cons
     const ImpT mi = s_imp[e];
     const int32_t ml = s_load[e];
     int pos = 0;
+    // (unrolled so that the LDS reads of several experts are in flight together: one at a time, a read's
+    // latency per expert made this loop the longest part of the step for 128 experts)
+#pragma unroll 16
     for (int j = 0; j < E; j++) {
         const ImpT oi = s_imp[j];
         const int32_t ol = s_load[j];

@@ -541,8 +541,15 @@ int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const int P = T * k;
     const int nseg1 = (H + kSeg - 1) / kSeg;
     const int nseg2 = (F + kSeg - 1) / kSeg;
-    // rows per workgroup (measured on the Mixtral-shaped decode layer: 64/64 beat 16..128)
-    const int rows1 = 64, rows2 = 64;
+    // rows per workgroup: 64 / 64 on the Mixtral-shaped decode layer (measured: beat 16..128), which makes 448 and
+    // 896 workgroups; smaller layers get fewer rows per workgroup so that the launch still fills the chip
+    auto rows_for = [](long rows_total, long want_groups) {
+        int r = 64;
+        while (r > 8 && rows_total / r < want_groups) r >>= 1;
+        return r;
+    };
+    const int rows1 = rows_for((long)F * P, 384);
+    const int rows2 = rows_for((long)H * nseg2 * P, 512);
     const dim3 g1((unsigned)((F + rows1 - 1) / rows1), (unsigned)P);
     const uint16_t* xb = (const uint16_t*)x;
     {

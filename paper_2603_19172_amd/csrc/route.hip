@@ -34,31 +34,49 @@ __device__ __forceinline__ void route_logits(const uint16_t* __restrict__ x,
                 xr[tw][c] = *reinterpret_cast<const uint4*>(x + (size_t)(t0 + tw) * H + col);
         }
     }
-    for (int e = wave; e < E; e += NW) {
-        float acc[TW];
+    // A wavefront takes EB experts per round (all their rows requested before the first is used): with one token
+    // the loop is nothing but memory latency, one round trip per round.
+    constexpr int EB = (TW == 1) ? ((NCH <= 4) ? 4 : (NCH <= 8) ? 2 : 1) : 1;
+    for (int e0 = wave; e0 < E; e0 += NW * EB) {
+        uint4 wv[EB][NCH];
 #pragma unroll
-        for (int tw = 0; tw < TW; tw++) acc[tw] = 0.0f;
-        const uint16_t* row = wg + (size_t)e * H;
+        for (int i = 0; i < EB; i++) {
+            const int e = min(e0 + i * NW, E - 1);            // past the last expert: a copy of it, not stored
+            const uint16_t* row = wg + (size_t)e * H;
 #pragma unroll
-        for (int c = 0; c < NCH; c++) {
-            if (c * kWave * 8 < H) {  // uniform
-                // lanes past the end re-read the row's tail against zero activations
-                const int col = min((c * kWave + lane) * 8, H - 8);
-                const uint4 wv = *reinterpret_cast<const uint4*>(row + col);
-#pragma unroll
-                for (int tw = 0; tw < TW; tw++) {
-                    acc[tw] = dot2_bf16(wv.x, xr[tw][c].x, acc[tw]);
-                    acc[tw] = dot2_bf16(wv.y, xr[tw][c].y, acc[tw]);
-                    acc[tw] = dot2_bf16(wv.z, xr[tw][c].z, acc[tw]);
-                    acc[tw] = dot2_bf16(wv.w, xr[tw][c].w, acc[tw]);
+            for (int c = 0; c < NCH; c++) {
+                wv[i][c] = make_uint4(0, 0, 0, 0);
+                if (c * kWave * 8 < H) {  // uniform
+                    // lanes past the end re-read the row's tail against zero activations
+                    const int col = min((c * kWave + lane) * 8, H - 8);
+                    wv[i][c] = *reinterpret_cast<const uint4*>(row + col);
                 }
             }
         }
-        const float b = bias ? bias[e] : 0.0f;
 #pragma unroll
-        for (int tw = 0; tw < TW; tw++) {
-            const float s = wave_sum(acc[tw]);
-            if (lane == 0) logit[tw * E + e] = s + b;
+        for (int i = 0; i < EB; i++) {
+            const int e = e0 + i * NW;
+            float acc[TW];
+#pragma unroll
+            for (int tw = 0; tw < TW; tw++) acc[tw] = 0.0f;
+#pragma unroll
+            for (int c = 0; c < NCH; c++) {
+                if (c * kWave * 8 < H) {  // uniform
+#pragma unroll
+                    for (int tw = 0; tw < TW; tw++) {
+                        acc[tw] = dot2_bf16(wv[i][c].x, xr[tw][c].x, acc[tw]);
+                        acc[tw] = dot2_bf16(wv[i][c].y, xr[tw][c].y, acc[tw]);
+                        acc[tw] = dot2_bf16(wv[i][c].z, xr[tw][c].z, acc[tw]);
+                        acc[tw] = dot2_bf16(wv[i][c].w, xr[tw][c].w, acc[tw]);
+                    }
+                }
+            }
+            const float b = (bias && e < E) ? bias[e] : 0.0f;
+#pragma unroll
+            for (int tw = 0; tw < TW; tw++) {
+                const float s = wave_sum(acc[tw]);
+                if (lane == 0 && e < E) logit[tw * E + e] = s + b;
+            }
         }
     }
 }
@@ -185,6 +203,20 @@ __device__ __forceinline__ void route_select(float* lg, float* selp, int t, int 
     float* const sps[1] = {selp};
     const int ts[1] = {t};
     route_select_batch<1>(lgs, sps, ts, E, k, renorm, idx, w, probs, prob_sum, load_cnt);
+}
+
+// one token, the number of logits per lane fixed by the caller (E <= 64 NC): the single-workgroup front-end
+// kernels are launched once per step with cold instruction caches, and every select variant they carry but do
+// not run is code they still have to fetch past
+template <int NC>
+__device__ __forceinline__ void route_select_fixed(float* lg, float* selp, int t, int E, int k, int renorm,
+                                                   int32_t* __restrict__ idx, float* __restrict__ w,
+                                                   float* __restrict__ probs, float* prob_sum, int32_t* load_cnt)
+{
+    float* const lgs[1] = {lg};
+    float* const sps[1] = {selp};
+    const int ts[1] = {t};
+    route_select_regs<1, NC>(lgs, sps, ts, E, k, renorm, idx, w, probs, prob_sum, load_cnt);
 }
 
 // A workgroup of NW wavefronts owns TW tokens: logits by all wavefronts, then
@@ -328,7 +360,7 @@ __global__ __launch_bounds__(4 * kWave) void route_mfma_kernel(
 // gating of route_kernel<1, NCH, 8>, then the decode importance (mean gate
 // probability, summed in token order), the load histogram and the ranked
 // bit-width assignment, with the arithmetic of the stand-alone kernels.
-template <int NCH>
+template <int NCH, int NC>
 __global__ __launch_bounds__(8 * kWave) void decode_front_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
     const float* __restrict__ bias, int T, int H, int E, int k, int renorm,
@@ -349,9 +381,86 @@ __global__ __launch_bounds__(8 * kWave) void decode_front_kernel(
     for (int t = 0; t < T; t++) {
         route_logits<1, NCH, 8>(x, wg, bias, T, H, E, t, logit);
         __syncthreads();
-        if (wave == 0) route_select(logit, selp, t, E, k, renorm, idx, w, probs, s_imp, s_load);
+        if (wave == 0) route_select_fixed<NC>(logit, selp, t, E, k, renorm, idx, w, probs, s_imp, s_load);
         __syncthreads();
     }
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        const float g = s_imp[e];
+        const float v = (T <= 1) ? g : g / (float)T;
+        s_imp[e] = v;
+        importance[e] = v;
+        load[e] = s_load[e];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += blockDim.x)
+        assign_one<float>(e, E, s_imp, s_load, tiers, floor_bits, bits, rank);
+}
+
+// The same front end for many experts, in two launches.  With 128 router rows of 2048 (512 KiB) one workgroup
+// cannot keep enough loads in flight (a kilobyte per thread), so the logits take round after round of memory
+// latency.  Here a wavefront owns one router row, kept in registers, and meets every token with it (the row is
+// read once whatever T); the logits go to the probs buffer, and a single workgroup then does what is left.
+//   logit[t, e] -> probs[t * E + e]      (overwritten with the probabilities by the second launch)
+template <int NCH>
+__global__ __launch_bounds__(8 * kWave) void front_logits_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg, const float* __restrict__ bias, int T, int H,
+    int E, float* __restrict__ logit)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int e = blockIdx.x * 8 + threadIdx.x / kWave;
+    if (e >= E) return;
+    const uint16_t* row = wg + (size_t)e * H;
+    uint4 wv[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+        wv[c] = make_uint4(0, 0, 0, 0);
+        if (c * kWave * 8 < H) wv[c] = *reinterpret_cast<const uint4*>(row + min((c * kWave + lane) * 8, H - 8));
+    }
+    const float b = bias ? bias[e] : 0.0f;
+    for (int t = 0; t < T; t++) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NCH; c++) {
+            if (c * kWave * 8 < H) {  // uniform
+                const int col = (c * kWave + lane) * 8;
+                // lanes past the end meet the re-read tail of the row with zero activations
+                uint4 xv = make_uint4(0, 0, 0, 0);
+                if (col < H) xv = *reinterpret_cast<const uint4*>(x + (size_t)t * H + col);
+                acc = dot2_bf16(wv[c].x, xv.x, acc);
+                acc = dot2_bf16(wv[c].y, xv.y, acc);
+                acc = dot2_bf16(wv[c].z, xv.z, acc);
+                acc = dot2_bf16(wv[c].w, xv.w, acc);
+            }
+        }
+        const float s = wave_sum(acc);
+        if (lane == 0) logit[(size_t)t * E + e] = s + b;
+    }
+}
+
+template <int NC>
+__global__ __launch_bounds__(8 * kWave) void front_finish_kernel(
+    int T, int E, int k, int renorm, int32_t* __restrict__ idx, float* __restrict__ w, float* __restrict__ probs,
+    TierTable tiers, int floor_bits, float* __restrict__ importance, int32_t* __restrict__ load,
+    uint8_t* __restrict__ bits, int32_t* __restrict__ rank)
+{
+    extern __shared__ float smem[];
+    __shared__ float s_imp[DYMOE_MAX_EXPERTS];
+    __shared__ int32_t s_load[DYMOE_MAX_EXPERTS];
+    const int wave = threadIdx.x / kWave;
+    float* logit = smem;          // [E]
+    float* selp = smem + E;       // [k]
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        s_imp[e] = 0.0f;
+        s_load[e] = 0;
+    }
+    for (int t = 0; t < T; t++) {
+        __syncthreads();                            // the previous token's logits have been used
+        for (int e = threadIdx.x; e < E; e += blockDim.x) logit[e] = probs[(size_t)t * E + e];
+        __syncthreads();
+        // tokens in order by one wavefront: the importance is a sum in token order
+        if (wave == 0) route_select_fixed<NC>(logit, selp, t, E, k, renorm, idx, w, probs, s_imp, s_load);
+    }
+    __syncthreads();
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         const float g = s_imp[e];
         const float v = (T <= 1) ? g : g / (float)T;
@@ -454,15 +563,50 @@ int dymoe_decode_front(dymoe_ctx* ctx, const void* x, const void* wg, const floa
     const size_t smem = ((size_t)E + (size_t)k) * sizeof(float);
     const uint16_t* xb = (const uint16_t*)x;
     const uint16_t* wb = (const uint16_t*)wg;
-    if (H <= 4096)
-        dymoe_launch(ctx, DYMOE_K_DECODE_FRONT, (dymoe::decode_front_kernel<8>), dim3(1), dim3(8 * dymoe::kWave), smem, st,
-                     xb, wb, bias, T, H, E, k, renorm, idx, w, probs, tt, floor_bits, importance, load, bits, rank);
-    else if (H <= 8192)
-        dymoe_launch(ctx, DYMOE_K_DECODE_FRONT, (dymoe::decode_front_kernel<16>), dim3(1), dim3(8 * dymoe::kWave), smem, st,
-                     xb, wb, bias, T, H, E, k, renorm, idx, w, probs, tt, floor_bits, importance, load, bits, rank);
-    else
-        dymoe_launch(ctx, DYMOE_K_DECODE_FRONT, (dymoe::decode_front_kernel<32>), dim3(1), dim3(8 * dymoe::kWave), smem, st,
-                     xb, wb, bias, T, H, E, k, renorm, idx, w, probs, tt, floor_bits, importance, load, bits, rank);
+    // many experts (router of 256 KiB and more) and a probs buffer to pass the logits through: two launches
+    if (probs && (size_t)E * (size_t)H * 2 >= ((size_t)256 << 10)) {
+        const dim3 grid((unsigned)((E + 7) / 8));
+        if (H <= 2048)
+            dymoe_launch(ctx, DYMOE_K_ROUTE, (dymoe::front_logits_kernel<4>), grid, dim3(8 * dymoe::kWave), 0, st, xb, wb, bias,
+                         T, H, E, probs);
+        else if (H <= 4096)
+            dymoe_launch(ctx, DYMOE_K_ROUTE, (dymoe::front_logits_kernel<8>), grid, dim3(8 * dymoe::kWave), 0, st, xb, wb, bias,
+                         T, H, E, probs);
+        else if (H <= 8192)
+            dymoe_launch(ctx, DYMOE_K_ROUTE, (dymoe::front_logits_kernel<16>), grid, dim3(8 * dymoe::kWave), 0, st, xb, wb, bias,
+                         T, H, E, probs);
+        else
+            dymoe_launch(ctx, DYMOE_K_ROUTE, (dymoe::front_logits_kernel<32>), grid, dim3(8 * dymoe::kWave), 0, st, xb, wb, bias,
+                         T, H, E, probs);
+        DYMOE_HIP_LAUNCH_CHECK();
+#define DYMOE_FINISH(NC_)                                                                                              \
+    dymoe_launch(ctx, DYMOE_K_DECODE_FRONT, (dymoe::front_finish_kernel<NC_>), dim3(1), dim3(8 * dymoe::kWave), smem, st, T, E, \
+                 k, renorm, idx, w, probs, tt, floor_bits, importance, load, bits, rank)
+        if (E <= 64) DYMOE_FINISH(1);
+        else if (E <= 128) DYMOE_FINISH(2);
+        else if (E <= 256) DYMOE_FINISH(4);
+        else if (E <= 512) DYMOE_FINISH(8);
+        else DYMOE_FINISH(16);
+#undef DYMOE_FINISH
+        DYMOE_HIP_LAUNCH_CHECK();
+        return DYMOE_OK;
+    }
+#define DYMOE_FRONT(NCH_, NC_)                                                                                          \
+    dymoe_launch(ctx, DYMOE_K_DECODE_FRONT, (dymoe::decode_front_kernel<NCH_, NC_>), dim3(1), dim3(8 * dymoe::kWave), smem, st, \
+                 xb, wb, bias, T, H, E, k, renorm, idx, w, probs, tt, floor_bits, importance, load, bits, rank)
+#define DYMOE_FRONT_BY_E(NCH_)                 \
+    do {                                       \
+        if (E <= 64) DYMOE_FRONT(NCH_, 1);     \
+        else if (E <= 128) DYMOE_FRONT(NCH_, 2); \
+        else if (E <= 256) DYMOE_FRONT(NCH_, 4); \
+        else if (E <= 512) DYMOE_FRONT(NCH_, 8); \
+        else DYMOE_FRONT(NCH_, 16);            \
+    } while (0)
+    if (H <= 4096) DYMOE_FRONT_BY_E(8);
+    else if (H <= 8192) DYMOE_FRONT_BY_E(16);
+    else DYMOE_FRONT_BY_E(32);
+#undef DYMOE_FRONT_BY_E
+#undef DYMOE_FRONT
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }

@@ -35,24 +35,31 @@ inline int make_tier_table(int E, int n_tiers, const int32_t* tier_count, const 
 
 // Expert e counts the experts that precede it in the order (importance
 // descending, load descending, index ascending) -> rank -> tier -> bits.
-// s_imp / s_load: all E values (LDS).
-template <typename ImpT>
-__device__ __forceinline__ void assign_one(int e, int E, const ImpT* s_imp, const int32_t* s_load,
-                                           const TierTable& tiers, int floor_bits,
-                                           uint8_t* __restrict__ bits, int32_t* __restrict__ rank)
+// s_imp / s_load: all E values (LDS).  S adjacent lanes share an expert (S a
+// power of two up to 8, lane = e * S + part): each counts every S-th rival and
+// the counts are added across the S lanes; the lane with part 0 writes.  All
+// lanes of a wavefront must call (the cross-lane sum has no branches around it);
+// a lane whose e is past the end passes e >= E and writes nothing.
+template <typename ImpT, int S>
+__device__ __forceinline__ void assign_shared(int e, int part, int E, const ImpT* s_imp, const int32_t* s_load,
+                                              const TierTable& tiers, int floor_bits,
+                                              uint8_t* __restrict__ bits, int32_t* __restrict__ rank)
 {
-    const ImpT mi = s_imp[e];
-    const int32_t ml = s_load[e];
+    const int me = min(e, E - 1);
+    const ImpT mi = s_imp[me];
+    const int32_t ml = s_load[me];
     int pos = 0;
-    // (unrolled so that the LDS reads of several experts are in flight together: one at a time, a read's
-    // latency per expert made this loop the longest part of the step for 128 experts)
-#pragma unroll 16
-    for (int j = 0; j < E; j++) {
+    // (unrolled so that the LDS reads of several rivals are in flight together)
+#pragma unroll 8
+    for (int j = part; j < E; j += S) {
         const ImpT oi = s_imp[j];
         const int32_t ol = s_load[j];
-        const bool first = (oi > mi) || (oi == mi && (ol > ml || (ol == ml && j < e)));
+        const bool first = (oi > mi) || (oi == mi && (ol > ml || (ol == ml && j < me)));
         pos += first ? 1 : 0;
     }
+#pragma unroll
+    for (int o = 1; o < S; o <<= 1) pos += __shfl_xor(pos, o, kWave);
+    if (e >= E || part != 0) return;
     int tier = 0, upto = tiers.count[0];
     while (pos >= upto && tier + 1 < tiers.n) {
         tier++;
@@ -62,6 +69,25 @@ __device__ __forceinline__ void assign_one(int e, int E, const ImpT* s_imp, cons
     if (b < floor_bits) b = floor_bits;
     bits[e] = (uint8_t)b;
     if (rank) rank[e] = pos;
+}
+
+// All experts by a workgroup of `threads` threads (a multiple of 64; every thread must call).
+template <typename ImpT>
+__device__ __forceinline__ void assign_all(int threads, int E, const ImpT* s_imp, const int32_t* s_load,
+                                           const TierTable& tiers, int floor_bits,
+                                           uint8_t* __restrict__ bits, int32_t* __restrict__ rank)
+{
+    const int tid = threadIdx.x;
+    if (E * 8 <= threads) {
+        assign_shared<ImpT, 8>(tid >> 3, tid & 7, E, s_imp, s_load, tiers, floor_bits, bits, rank);
+    } else if (E * 4 <= threads) {
+        assign_shared<ImpT, 4>(tid >> 2, tid & 3, E, s_imp, s_load, tiers, floor_bits, bits, rank);
+    } else if (E * 2 <= threads) {
+        assign_shared<ImpT, 2>(tid >> 1, tid & 1, E, s_imp, s_load, tiers, floor_bits, bits, rank);
+    } else {
+        for (int e0 = 0; e0 < E; e0 += threads)
+            assign_shared<ImpT, 1>(e0 + tid, 0, E, s_imp, s_load, tiers, floor_bits, bits, rank);
+    }
 }
 
 }  // namespace dymoe

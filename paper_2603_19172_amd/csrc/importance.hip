@@ -159,7 +159,7 @@ __global__ void importance_decode_kernel(const float* __restrict__ probs, int T,
     importance[e] = (T == 1) ? s : s / (float)T;
 }
 
-// One workgroup; thread e ranks expert e.
+// One workgroup of 1024 threads: up to eight lanes share an expert's ranking.
 template <typename ImpT>
 __global__ __launch_bounds__(DYMOE_MAX_EXPERTS) void assign_precision_kernel(
     const ImpT* __restrict__ importance, const int32_t* __restrict__ load, int E, TierTable tiers,
@@ -167,14 +167,12 @@ __global__ __launch_bounds__(DYMOE_MAX_EXPERTS) void assign_precision_kernel(
 {
     __shared__ ImpT s_imp[DYMOE_MAX_EXPERTS];
     __shared__ int32_t s_load[DYMOE_MAX_EXPERTS];
-    const int e = threadIdx.x;
-    if (e < E) {
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
         s_imp[e] = importance[e];
         s_load[e] = load ? load[e] : 0;
     }
     __syncthreads();
-    if (e >= E) return;
-    assign_one<ImpT>(e, E, s_imp, s_load, tiers, floor_bits, bits, rank);
+    assign_all<ImpT>((int)blockDim.x, E, s_imp, s_load, tiers, floor_bits, bits, rank);
 }
 
 }  // namespace dymoe
@@ -237,7 +235,9 @@ int dymoe_assign_precision(dymoe_ctx* ctx, int phase, const void* importance,
     if (E > DYMOE_MAX_EXPERTS) return DYMOE_ENOTSUP;
     if (!ctx) return DYMOE_ENOCTX;
     hipStream_t st = (hipStream_t)stream;
-    const unsigned threads = (unsigned)(((E + 63) / 64) * 64);
+    // enough threads for eight lanes per expert, at most the 1024 of a workgroup
+    unsigned threads = (unsigned)(((E * 8 + 63) / 64) * 64);
+    if (threads > DYMOE_MAX_EXPERTS) threads = DYMOE_MAX_EXPERTS;
     if (phase == DYMOE_PHASE_PREFILL)
         dymoe_launch(ctx, DYMOE_K_ASSIGN, (dymoe::assign_precision_kernel<int32_t>), dim3(1), dim3(threads), 0, st,
                            (const int32_t*)importance, load, E, tt, floor_bits, bits, rank);

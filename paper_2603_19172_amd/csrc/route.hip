@@ -102,7 +102,9 @@ __device__ __forceinline__ void route_select_regs(float* const (&lg)[TB], float*
 {
     const int lane = threadIdx.x & (kWave - 1);
     float v[TB][NC];
-    float mx[TB], den[TB], rden[TB], sel_sum[TB];
+    float mx[TB], den[TB], rden[TB], sel_sum[TB], mine[TB];
+#pragma unroll
+    for (int b = 0; b < TB; b++) mine[b] = 0.0f;
 #pragma unroll
     for (int b = 0; b < TB; b++) {
         mx[b] = -INFINITY;
@@ -154,17 +156,31 @@ __device__ __forceinline__ void route_select_regs(float* const (&lg)[TB], float*
                 const unsigned long long hit = __ballot(c * kWave + lane < E && v[b][c] == bv);
                 if (bi < 0 && hit) bi = c * kWave + __ffsll((long long)hit) - 1;
             }
-            const float p = expf(bv - mx[b]) * rden[b];
+            const float p = expf(bv - mx[b]) * rden[b];      // the same in every lane
             sel_sum[b] += p;
+            if (k <= kWave) {
+                if (lane == j) mine[b] = p;                   // lane j keeps the j-th gate weight
+            } else if (lane == 0) {
+                selp[b][j] = p;
+            }
             if (lane == 0) {
                 if (t[b] >= 0) idx[(size_t)t[b] * k + j] = bi;
-                selp[b][j] = p;
                 if (load_cnt && t[b] >= 0) load_cnt[bi] += 1;
             }
 #pragma unroll
             for (int c = 0; c < NC; c++)
                 if (c * kWave + lane == bi) v[b][c] = -INFINITY;        // the owner retires the entry
         }
+    }
+    if (k <= kWave) {
+        // up to 64 selected experts: the weights never leave the registers (no LDS hand-over, and so no wait for
+        // the stores above, which the fences of the other branch imply)
+#pragma unroll
+        for (int b = 0; b < TB; b++) {
+            const float scale = renorm ? 1.0f / sel_sum[b] : 1.0f;
+            if (t[b] >= 0 && lane < k) w[(size_t)t[b] * k + lane] = mine[b] * scale;
+        }
+        return;
     }
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");      // selp: written by lane 0, read by all
     __builtin_amdgcn_wave_barrier();
@@ -392,8 +408,7 @@ __global__ __launch_bounds__(8 * kWave) void decode_front_kernel(
         load[e] = s_load[e];
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < E; e += blockDim.x)
-        assign_one<float>(e, E, s_imp, s_load, tiers, floor_bits, bits, rank);
+    assign_all<float>(8 * kWave, E, s_imp, s_load, tiers, floor_bits, bits, rank);
 }
 
 // The same front end for many experts, in two launches.  With 128 router rows of 2048 (512 KiB) one workgroup
@@ -469,8 +484,7 @@ __global__ __launch_bounds__(8 * kWave) void front_finish_kernel(
         load[e] = s_load[e];
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < E; e += blockDim.x)
-        assign_one<float>(e, E, s_imp, s_load, tiers, floor_bits, bits, rank);
+    assign_all<float>(8 * kWave, E, s_imp, s_load, tiers, floor_bits, bits, rank);
 }
 
 // s_t = sqrt(sum_h x[t,h]^2), one wavefront per token

@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--stack-steps", type=int, default=0,
                     help="also decode this many steps through a 32-layer stack with the experts in pinned host "
                          "memory (BASELINE configs[4]); off by default: the run is bound by the host link")
+    ap.add_argument("--stack-warmup", type=int, default=1,
+                    help="untimed steps of the stack before the timed ones, cycling through the same inputs (as many as "
+                         "--stack-steps with a large budget: every expert the timed steps need is then resident)")
     ap.add_argument("--stack-budget-gb", type=float, default=24.0,
                     help="device bytes set aside for expert slots in the stack run")
     ap.add_argument("--skip-cpu", action="store_true")
@@ -520,7 +523,8 @@ def main():
                 stack = DecodeStack(ctx, H, F, E, k, routers, pool, None if by_budget else slots, tcount, tbits,
                                     floor_bits=flr, prefetch=prefetch, transfer=transfer, alpha=0.125, device=dev,
                                     budget_bytes=int(budget * 1e9) if by_budget else None)
-                stack.step(xs[0])                 # warm-up step (fills the slots it can)
+                for s in range(max(1, args.stack_warmup)):      # warm-up (fills the slots it can)
+                    stack.step(xs[s % len(xs)])
                 torch.cuda.synchronize()
                 stack.stats.clear()
                 stack.measure_overlap = True
@@ -549,7 +553,8 @@ def main():
         out["stack_decode"] = {"workload": "32 Mixtral-shaped layers, 1 token per step, experts in pinned host memory "
                                            "(16 distinct experts shared by the 256 layer-experts), look-ahead of the next layer's 2 "
                                            "experts; the 1/3/4 tiers carry an int4 floor in the first and last 4 layers",
-                               "device_budget_GB": budget, "steps": args.stack_steps, "runs": results}
+                               "device_budget_GB": budget, "steps": args.stack_steps, "warmup_steps": max(1, args.stack_warmup),
+                               "runs": results}
     print(json.dumps(out))
 
 

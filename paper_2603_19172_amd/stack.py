@@ -213,9 +213,23 @@ class ExpertStack:
         self.h = [torch.empty((T, H), dtype=torch.bfloat16, device=device) for _ in range(2)]
         self.score = torch.empty((T,), dtype=torch.float32, device=device)
         self.side = torch.cuda.Stream(device=device)
-        pin = lambda shape, dt: torch.empty(shape, dtype=dt).pin_memory()
-        self.host_idx, self.host_load, self.host_bits = pin((T, k), torch.int32), pin((E,), torch.int32), pin((E,), torch.uint8)
-        self.host_pidx, self.host_pload, self.host_pbits = pin((T, k), torch.int32), pin((E,), torch.int32), pin((E,), torch.uint8)
+        # What the host reads back per layer (selected experts, loads, bit widths) sits in one device buffer per
+        # runner and travels in one copy: idx [T,k] int32 | load [E] int32 | bits [E] uint8.
+        n_idx, n_load = T * k * 4, E * 4
+        self._meta_tail = n_idx                 # T > 1: only load and bits travel
+
+        def views(buf):
+            return (buf[:n_idx].view(torch.int32).view(T, k), buf[n_idx:n_idx + n_load].view(torch.int32),
+                    buf[n_idx + n_load:n_idx + n_load + E])
+
+        def pack(lay):
+            lay.meta = torch.zeros((n_idx + n_load + (E + 3) // 4 * 4,), dtype=torch.uint8, device=device)
+            lay.idx, lay.load, lay.bits = views(lay.meta)
+            host = torch.zeros(lay.meta.shape, dtype=torch.uint8).pin_memory()
+            return (host,) + views(host)
+
+        self.host_meta, self.host_idx, self.host_load, self.host_bits = pack(self.layer)
+        self.host_pmeta, self.host_pidx, self.host_pload, self.host_pbits = pack(self.ahead)
         self.stats = collections.Counter()
         self.measure_overlap = False    # set True to time every copy and every wait of the compute stream (overlap_report)
         self._copy_events, self._stall_events = [], []
@@ -299,14 +313,10 @@ class ExpertStack:
             if look:     # Eq. 6: the next layer's router (and precision rule) on the current hidden states
                 nxt_lay.floor_bits, nxt_lay._tc = self.floor[l + 1], self.tier_arrays[l + 1]
                 self._front(nxt_lay, h, self.routers[l + 1], st)
-                if self.T == 1:
-                    self.host_pidx.copy_(nxt_lay.idx, non_blocking=True)
-                self.host_pload.copy_(nxt_lay.load, non_blocking=True)
-                self.host_pbits.copy_(nxt_lay.bits, non_blocking=True)
-            if self.T == 1:
-                self.host_idx.copy_(lay.idx, non_blocking=True)
-            self.host_load.copy_(lay.load, non_blocking=True)
-            self.host_bits.copy_(lay.bits, non_blocking=True)
+                a = 0 if self.T == 1 else self._meta_tail
+                self.host_pmeta[a:].copy_(nxt_lay.meta[a:], non_blocking=True)
+            a = 0 if self.T == 1 else self._meta_tail
+            self.host_meta[a:].copy_(lay.meta[a:], non_blocking=True)
             cs.synchronize()
             if self.T == 1:      # in routing order
                 active = [int(e) for e in self.host_idx[0].tolist()]

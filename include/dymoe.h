@@ -219,12 +219,15 @@ int dymoe_assign_precision(dymoe_ctx* ctx, int phase, const void* importance,
 /*
  * Decode-step front end: dymoe_route_topk, dymoe_expert_importance (decode
  * phase: importance = gate score, Sec. 4.2.2 Eq. 3) and dymoe_assign_precision
- * (Sec. 4.3, Sec. 5) in ONE launch, for steps of 1 <= T <= DYMOE_FRONT_MAX_TOKENS
+ * (Sec. 4.3, Sec. 5) in one launch, for steps of 1 <= T <= DYMOE_FRONT_MAX_TOKENS
  * tokens, where three dependent launches of microseconds each would cost more
  * than their work.  Arguments have the meaning, layout and limits they have in
  * the three calls (importance: [E] fp32; probs may be NULL; rank may be NULL;
  * tier_count / tier_bits: host arrays read before the launch), and every
- * output is bit for bit what the three calls in turn produce.
+ * output is bit for bit what the three calls in turn produce.  With a router
+ * of 256 KiB or more (E * H * 2 bytes) and a probs buffer, the logits are
+ * computed by a launch of their own over many workgroups and handed to the
+ * finishing launch through probs (two launches; same outputs).
  */
 int dymoe_decode_front(dymoe_ctx* ctx, const void* x, const void* wg, const float* bias,
                        int T, int H, int E, int k, int renorm, int n_tiers,

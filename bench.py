@@ -56,6 +56,9 @@ def main():
                          "profiler run over the default workload)")
     ap.add_argument("--fine-grained", action="store_true",
                     help="also time the fine-grained layer (BASELINE configs[3]: 2048 tokens, 128 experts, top-8)")
+    ap.add_argument("--attention-long", action="store_true",
+                    help="also time the attention-derived token score at 2048 and 8192 tokens (32 query / 8 key heads of "
+                         "128), causal and not: the sizes its LDS-staged kernels serve")
     ap.add_argument("--gptq", action="store_true",
                     help="also time the error-compensated quantizer (Hessian, inverse factor, column sweep) on the three "
                          "matrices of one Mixtral-shaped expert with 2048 synthetic calibration tokens")
@@ -319,6 +322,37 @@ def main():
             "workload": "512 tokens, 32 query / 8 key heads of 128, causal",
             "kernels_us": {n: round(v[0] / max(v[1], 1) * 1e3, 1) for n, v in ak_us.items()},
             "TFLOPs": round(a_flops / (a_us * 1e-6) / 1e12, 1) if a_us > 0 else None}
+
+    # ---------------------------------------------------------------- attention score, long sequences (opt-in)
+    if args.attention_long:
+        a_heads, a_kv, a_d = 32, 8, 128
+        rows = []
+        for aT in (2048, 8192):
+            acfg = synth.scaled(synth.CONFIGS["mixtral_prefill"], T=aT, k_hh=max(1, aT // 20), config_id=70)
+            aq_np, ak_np, _ = synth.attention_inputs(acfg, a_heads, a_kv, a_d)
+            aq = torch.from_numpy(aq_np.view(np.int16)).to(dev).view(torch.bfloat16)
+            ak = torch.from_numpy(ak_np.view(np.int16)).to(dev).view(torch.bfloat16)
+            a_ws = torch.empty((int(B.lib.dymoe_attention_workspace_bytes(aT, a_heads)),), dtype=torch.uint8, device=dev)
+            a_out = torch.empty((aT,), dtype=torch.float32, device=dev)
+            for causal in (True, False):
+                for _ in range(3):
+                    ctx.token_score_attention(aq, ak, causal=causal, out=a_out, workspace=a_ws)
+                torch.cuda.synchronize()
+                ctx.timing_enable(["attn_stats", "attn_colsum"])
+                for _ in range(args.prefill_steps):
+                    ctx.token_score_attention(aq, ak, causal=causal, out=a_out, workspace=a_ws)
+                torch.cuda.synchronize()
+                ak_us = {n: ctx.timing_read(n) for n in ("attn_stats", "attn_colsum")}
+                ctx.timing_enable(())
+                a_us = sum(v[0] / max(v[1], 1) for v in ak_us.values()) * 1e3
+                # two passes of T x T x d products per head; the causal mask leaves the 32-token tiles on or below the diagonal
+                a_flops = 2 * 2.0 * a_d * a_heads * (aT * (aT + 32) / 2 if causal else float(aT) * aT)
+                rows.append({"tokens": aT, "causal": causal,
+                             "kernels_us": {n: round(v[0] / max(v[1], 1) * 1e3, 1) for n, v in ak_us.items()},
+                             "TFLOPs": round(a_flops / (a_us * 1e-6) / 1e12, 1),
+                             "frac_mfma_bf16_peak": round(a_flops / (a_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)})
+            del aq, ak, a_ws
+        out["attention_token_score_long"] = {"workload": "32 query / 8 key heads of 128", "runs": rows}
 
     # ---------------------------------------------------------------- fine-grained layer (opt-in)
     if args.fine_grained:

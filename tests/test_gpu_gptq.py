@@ -253,3 +253,17 @@ def test_gptq_experts_feed_the_grouped_gemm(ctx):
     err = float((np.abs(y.cpu().numpy() - ref) / rms).max())
     print("grouped GEMM over compensated experts: max err / rms = %.2e" % err)
     assert err <= 2e-2
+
+
+def test_gptq_factor_with_fewer_samples_than_columns(ctx):
+    """64 calibration tokens for 512 columns: the Hessian has rank 64 and only the damping keeps it
+    positive definite (condition number about 1e4), the case fp32 Cholesky has least room for."""
+    K = 512
+    H = O.gptq_hessian(synth.calibration_inputs(864, 64, K))
+    want = O.gptq_factor(H)
+    got = ctx.gptq_factor(torch.from_numpy(H.astype(np.float32)).to(DEV))
+    torch.cuda.synchronize()
+    U = got.cpu().numpy().astype(np.float64)
+    rel = np.abs(U - want).max(axis=1) / np.abs(want).max(axis=1)
+    print("rank-deficient Hessian: max row-relative error %.2e" % rel.max())
+    assert np.isfinite(U).all() and rel.max() < 5e-4

@@ -64,14 +64,20 @@ class HostExpertPool:
             view[i, H * F:2 * H * F] = w3.reshape(-1).view("int16")
             view[i, 2 * H * F:] = w2.reshape(-1).view("int16")
 
-    def add_quantised(self, ctx, device, formats=(4, 2), layout=B.LAYOUT_ROWMAJOR):
+    def add_quantised(self, ctx, device, formats=(4, 2), layout=B.LAYOUT_ROWMAJOR, factors=None):
         """Quantised copies (by default int4 and int2) of every entry, made by the device quantiser and
         kept in pinned host memory, in the layout the FFN path that will read them expects (row-major for
-        the GEMV, tiles for the grouped GEMM)."""
+        the GEMV, tiles for the grouped GEMM).
+        factors: None for the plain quantiser, or {H: U_H, F: U_F}, the inverse-Hessian factors
+        (dymoe_gptq_factor) of the inputs of W1 / W3 and of W2: the error-compensated quantiser the paper
+        prepares its experts with (Sec. 5)."""
         H, F = self.H, self.F
         self.layout = layout
         wdev = torch.empty((self.elems,), dtype=torch.bfloat16, device=device)
         st = torch.cuda.current_stream().cuda_stream
+        if factors is not None:
+            self._add_compensated(ctx, device, formats, layout, factors, wdev)
+            return
         for b in formats:
             offs, total = quant_layout(H, F, b)
             self.nbytes[b] = total
@@ -87,6 +93,32 @@ class HostExpertPool:
                 wdev.view(torch.uint8).copy_(self.buf[16][i], non_blocking=True)
                 B._check(B.lib.dymoe_quantize_experts(ctx._h, table.data_ptr(), want.data_ptr(), None, 1, H, F, 64,
                                                       layout, st), "dymoe_quantize_experts")
+                self.buf[b][i].copy_(stage, non_blocking=True)
+            torch.cuda.synchronize()
+
+    def _add_compensated(self, ctx, device, formats, layout, factors, wdev):
+        H, F = self.H, self.F
+        shapes = ((F, H), (F, H), (H, F))
+        ws = {K: torch.empty((int(B.lib.dymoe_gptq_workspace_bytes(n, K)),), dtype=torch.uint8, device=device)
+              for n, K in ((F, H), (H, F))}
+        for b in formats:
+            offs, total = quant_layout(H, F, b)
+            self.nbytes[b] = total
+            self.buf[b] = torch.empty((self.n_pool, total), dtype=torch.uint8, pin_memory=True)
+            stage = torch.empty((total,), dtype=torch.uint8, device=device)
+            for i in range(self.n_pool):
+                wdev.view(torch.uint8).copy_(self.buf[16][i], non_blocking=True)
+                for m, (n, K) in enumerate(shapes):
+                    co, so, zo = offs[m]
+                    out = (stage[co:so].view(n, K * b // 8), stage[so:zo].view(torch.float16).view(n, K // 64),
+                           stage[zo:zo + n * (K // 64) * 2].view(torch.float16).view(n, K // 64))
+                    w = wdev[m * H * F:(m + 1) * H * F].view(n, K)
+                    if layout == B.LAYOUT_ROWMAJOR:
+                        ctx.gptq_quantize_pack(w, factors[K], b, out=out, workspace=ws[K])
+                    else:
+                        tiles = ctx.pack_code_tiles(ctx.gptq_quantize_pack(w, factors[K], b, workspace=ws[K]), b)
+                        for dst, src in zip(out, tiles):
+                            dst.copy_(src)
                 self.buf[b][i].copy_(stage, non_blocking=True)
             torch.cuda.synchronize()
 

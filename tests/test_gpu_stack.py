@@ -328,3 +328,44 @@ def test_stack_overlap_report_accounts_for_copy_and_waiting_time(ctx):
         assert rep[prefetch]["copy_time_hidden"] <= 1.0
     # without look-ahead every copy is waited for in full (the waiting time holds the copy time)
     assert rep[False]["stall_ms"] >= 0.8 * rep[False]["copy_ms"]
+
+
+@pytest.mark.parametrize("layout", [B.LAYOUT_ROWMAJOR, B.LAYOUT_TILE])
+def test_pool_prepared_with_the_compensated_quantizer(ctx, layout):
+    """The paper prepares its experts off line with GPTQ (Sec. 5): the pool's quantised formats made by
+    dymoe_gptq_quantize_pack hold the oracle's compensated codes, in either layout, and a stack runs on them."""
+    from paper_2603_19172_amd.stack import quant_layout
+    from gpu_helpers import rowmajor_from_tiles
+    H, F, E, n_pool = 256, 512, 8, 3
+    pool_cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=950)
+    mats = {i: synth.expert_weights(pool_cfg, i) for i in range(n_pool)}
+    U = {K: O.gptq_factor(O.gptq_hessian(synth.calibration_inputs(950 + K, 1024, K))).astype(np.float32) for K in (H, F)}
+    pool = HostExpertPool(H, F, E, n_pool, lambda i: mats[i])
+    pool.add_quantised(ctx, DEV, formats=(4, 2), layout=layout, factors={K: torch.from_numpy(U[K]).to(DEV) for K in U})
+    for b in (4, 2):
+        offs, total = quant_layout(H, F, b)
+        assert pool.nbytes[b] == total
+        for i in (0, n_pool - 1):
+            blob = pool.buf[b][i].numpy()
+            for m, (n, K) in enumerate(((F, H), (F, H), (H, F))):
+                co, so, zo = offs[m]
+                codes = blob[co:so].reshape(n, K * b // 8)
+                scale = blob[so:zo].view(np.uint16).reshape(n, K // 64)
+                zero = blob[zo:zo + n * (K // 64) * 2].view(np.uint16).reshape(n, K // 64)
+                if layout == B.LAYOUT_TILE:
+                    codes, scale, zero = rowmajor_from_tiles(codes, scale, zero, b)
+                want = O.gptq_quantize_pack(mats[i][m], U[K], b)
+                assert np.array_equal(codes, want[0]) and np.array_equal(scale, want[1]) and np.array_equal(zero, want[2])
+    if layout == B.LAYOUT_ROWMAJOR:
+        L = 3
+        cfgs = [synth.scaled(synth.CONFIGS["tiny"], T=1, phase="decode", config_id=960 + l) for l in range(L)]
+        routers = [to_bf16(synth.router(c)[0]) for c in cfgs]
+        stack = DecodeStack(ctx, H, F, E, 2, routers, pool, {4: 6, 2: 6}, (3, 5), (4, 2), prefetch=True,
+                            transfer="assigned", alpha=0.25, device=DEV)
+        for s in range(3):
+            x, _ = synth.activations(synth.scaled(cfgs[0], config_id=970 + s))
+            h = stack.step(to_bf16(x))
+            torch.cuda.synchronize()
+            assert torch.isfinite(h.float()).all()
+        stack.close()
+        assert stack.stats["copies_4"] + stack.stats["copies_2"] > 0

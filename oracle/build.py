@@ -17,12 +17,19 @@ FLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-We
 
 
 def build(force: bool = False) -> str:
-    stale = (not os.path.exists(LIB)) or os.path.getmtime(LIB) < os.path.getmtime(SRC)
+    # ORACLE_SANITIZE=undefined: a second library built with gcc's undefined-behaviour sanitizer (traps on the
+    # first finding), which the wrapper then loads instead; the pins run against it in tests/test_oracle_sanitized.py
+    san = os.environ.get("ORACLE_SANITIZE", "")
+    lib, flags = LIB, FLAGS
+    if san:
+        lib = os.path.join(HERE, "liboracle_%s.so" % san)
+        flags = [f for f in FLAGS if f != "-O2"] + ["-O1", "-g", "-fsanitize=" + san, "-fno-sanitize-recover=" + san]
+    stale = (not os.path.exists(lib)) or os.path.getmtime(lib) < os.path.getmtime(SRC)
     if force or stale:
-        tmp = LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", *FLAGS, SRC, "-o", tmp, "-lm"])
-        os.replace(tmp, LIB)
-    return LIB
+        tmp = lib + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", *flags, SRC, "-o", tmp, "-lm"])
+        os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":

@@ -267,3 +267,25 @@ def test_gptq_factor_with_fewer_samples_than_columns(ctx):
     rel = np.abs(U - want).max(axis=1) / np.abs(want).max(axis=1)
     print("rank-deficient Hessian: max row-relative error %.2e" % rel.max())
     assert np.isfinite(U).all() and rel.max() < 5e-4
+
+
+def test_gptq_sweep_edge_rows(ctx):
+    """One row; a group of equal weights (scale 0: every code 0, the whole value becomes error and is passed
+    on); a group of zeros; values at the top of the bf16 range the plain quantizer accepts."""
+    K = 256
+    _, wb, U = _case(741, 4, K)
+    w = synth.bf16_bits_to_f32(wb).copy()
+    w[1, 64:128] = 0.01953125          # one bf16 value through a whole group
+    w[2, 0:64] = 0.0
+    w[3, 128:192] *= 1.0e6             # ~2e4: near the fp16 range of scale and zero
+    wb = synth.f32_to_bf16_bits(w)
+    for rows in (slice(0, 1), slice(0, 4)):
+        for bits in (2, 4, 8):
+            want = O.gptq_quantize_pack(wb[rows], U, bits)
+            got = ctx.gptq_quantize_pack(to_bf16(wb[rows]), torch.from_numpy(U).to(DEV), bits)
+            assert _same(got, want)
+    # one calibration token
+    xb = synth.calibration_inputs(742, 1, 128)
+    h = ctx.gptq_hessian(to_bf16(xb))
+    torch.cuda.synchronize()
+    assert np.allclose(h.cpu().numpy(), O.gptq_hessian(xb), rtol=1e-6, atol=0)

@@ -37,7 +37,8 @@ def _run(ctx, q, k, causal, scale=0.0):
                                         (160, 8, 2, 128), (512, 32, 8, 128),
                                         # from 993 tokens on the streamed operand goes through LDS: ragged ends,
                                         # a head count the XCD mapping does not divide, both head sizes
-                                        (993, 8, 2, 128), (1100, 3, 3, 64), (1057, 5, 1, 128), (2048, 8, 8, 64)])
+                                        (993, 8, 2, 128), (1100, 3, 3, 64), (1057, 5, 1, 128), (2048, 8, 8, 64),
+                                        (4100, 2, 1, 128)])
 @pytest.mark.parametrize("causal", [True, False])
 def test_attention_score_matches_the_oracle(ctx, T, Hh, Hkv, d, causal):
     cfg = synth.scaled(synth.CONFIGS["mixtral_prefill"], T=T, k_hh=max(1, T // 20), config_id=60 + T)

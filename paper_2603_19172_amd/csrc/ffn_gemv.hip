@@ -368,7 +368,9 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
     const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table, int H, int F,
     int E, int k, int rows_per_block, float* __restrict__ hbuf)
 {
-    const int p = blockIdx.y;
+    // pairs in reverse: a token's later slots carry the less important experts, hence the narrower formats,
+    // whose workgroups are short and latency-bound; dispatched first they overlap the wide ones instead of forming the tail
+    const int p = (int)gridDim.y - 1 - (int)blockIdx.y;
     const int e = idx[p];
     if (e < 0 || e >= E) return;
     const int b = bits[e];
@@ -452,7 +454,7 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase2_kernel(
     const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table, int H, int F,
     int E, int rows_per_block, int nseg, float* __restrict__ part)
 {
-    const int p = blockIdx.z;
+    const int p = (int)gridDim.z - 1 - (int)blockIdx.z;       // narrow formats first, as in phase 1
     const int s = blockIdx.y;
     const int e = idx[p];
     if (e < 0 || e >= E) return;

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kGqRows) void gptq_group_kernel(
     }
     // The diagonal block goes through LDS: every lane needs every value, one row per column step, and fetched row
     // by row from memory (the scalar cache's way) each step would wait out a full memory latency: 64 in a chain.
-    __shared__ __attribute__((aligned(16))) float s_d[kGqGroup][kGqGroup];
+    __shared__ __attribute__((aligned(16))) float s_d[kGqGroup][kGqGroup + 4];   // + 4: the row-per-lane staging stores spread over the banks
 #pragma unroll
     for (int c = 0; c < kGqGroup / 4; c++)
         *reinterpret_cast<float4*>(&s_d[threadIdx.x][4 * c]) =
@@ -212,10 +212,16 @@ __global__ __launch_bounds__(kGqTrailThreads) void gptq_trail_kernel(
 // (v_mfma_f32_32x32x16_bf16: the products of bf16 numbers are exact in fp32).  Both operands of a tile are
 // columns of X, which memory holds row by row: a thread fetches an 8-sample x 8-column block with eight
 // 16-byte loads, transposes it in registers and parks eight 16-byte pieces (one column, 8 samples) in LDS,
-// chunk position XOR-swizzled by column so that the operand reads of 8 neighbouring columns hit different
-// banks.  A workgroup owns a 128 x 128 tile on or above the diagonal (64 x 64 per wavefront) and writes the
+// chunk position XOR-swizzled by column so that neither the operand reads nor the transposed stores
+// collide on banks.  A workgroup owns a 128 x 128 tile on or above the diagonal (64 x 64 per wavefront) and writes the
 // mirror image as well.
 constexpr int kHsTile = 128;
+// Chunk position of column c's 16-byte pieces in LDS: a column is 128 bytes (all 32 banks), so the bank of a
+// piece is its chunk position alone.  Eight neighbouring lanes must land on eight positions both when the
+// operands are read (lanes = 8 consecutive columns, one chunk) and when the transposed blocks are stored
+// (lanes = the same column-in-block of 8 consecutive blocks, one chunk): hence both the low bits and the
+// block bits of the column go into the XOR.
+__device__ __forceinline__ int hs_swizzle(int c) { return (c ^ (c >> 3)) & 7; }
 constexpr int kHsSamples = 64;
 constexpr int kHsThreads = 256;
 
@@ -279,7 +285,7 @@ __global__ __launch_bounds__(kHsThreads) void gptq_hessian_kernel(const uint16_t
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             const int c = 8 * cgrp + i;
-            s_op[op][c * (kHsSamples / 8) + (sgrp ^ (c & 7))] = out[i];
+            s_op[op][c * (kHsSamples / 8) + (sgrp ^ hs_swizzle(c))] = out[i];
         }
         __syncthreads();
         if (s0 + kHsSamples < n) fetch(s0 + kHsSamples);          // in flight during the products
@@ -290,8 +296,8 @@ __global__ __launch_bounds__(kHsThreads) void gptq_hessian_kernel(const uint16_t
 #pragma unroll
             for (int h = 0; h < 2; h++) {
                 const int ca = 64 * wi + 32 * h + ln, cb = 64 * wj + 32 * h + ln;
-                fa[h] = __builtin_bit_cast(bf16x8_t, s_op[0][ca * (kHsSamples / 8) + (chunk ^ (ca & 7))]);
-                fb[h] = __builtin_bit_cast(bf16x8_t, s_op[1][cb * (kHsSamples / 8) + (chunk ^ (cb & 7))]);
+                fa[h] = __builtin_bit_cast(bf16x8_t, s_op[0][ca * (kHsSamples / 8) + (chunk ^ hs_swizzle(ca))]);
+                fb[h] = __builtin_bit_cast(bf16x8_t, s_op[1][cb * (kHsSamples / 8) + (chunk ^ hs_swizzle(cb))]);
             }
 #pragma unroll
             for (int a = 0; a < 2; a++)

@@ -38,7 +38,7 @@ constexpr int kGvWaves = kGvThreads / kWave;
 // the code extraction below, plus the two per-lane constants.
 struct LaneX {
     uint32_t r[16];
-    float xsum;  // sum of the lane's 32 activations
+    float xsum;  // sum of the 64 activations of the lane's quantisation group (the lane's 32 and its partner's)
     float xoff;  // sum of 2^n_k * x_k
 };
 
@@ -55,7 +55,7 @@ __device__ __forceinline__ void arrange_lane_x(const float* v, LaneX& lx)
         hv[i] = (_Float16)v[i];
         sum += h2f(hv[i]);
     }
-    lx.xsum = sum;
+    lx.xsum = sum + dpp_get<0xB1, 0xF>(sum);       // quad_perm [1,0,3,2]: lanes 2i and 2i+1 share a group
     float off = 0.0f;
     if (BITS == 8) {
         // dword d holds codes 4d..4d+3, one per byte; pairs (b0,b1) and (b2,b3), all offset by 1024
@@ -184,9 +184,9 @@ __device__ __forceinline__ ExpertMat pick_mat(const dymoe_expert_fmt& ex, int ma
 // what one lane loads of one row: NSEG segments starting at column seg0 * 2048
 template <int BITS, int NSEG> struct RowRegs;
 template <int NSEG> struct RowRegs<16, NSEG> { uint4 c[NSEG][4]; };
-template <int NSEG> struct RowRegs<4, NSEG> { uint4 c[NSEG]; uint16_t s[NSEG], z[NSEG]; };
-template <int NSEG> struct RowRegs<2, NSEG> { uint2 c[NSEG]; uint16_t s[NSEG], z[NSEG]; };
-template <int NSEG> struct RowRegs<8, NSEG> { uint4 c[NSEG][2]; uint16_t s[NSEG], z[NSEG]; };
+template <int NSEG> struct RowRegs<4, NSEG> { uint4 c[NSEG]; uint16_t sz[NSEG]; };
+template <int NSEG> struct RowRegs<2, NSEG> { uint2 c[NSEG]; uint16_t sz[NSEG]; };
+template <int NSEG> struct RowRegs<8, NSEG> { uint4 c[NSEG][2]; uint16_t sz[NSEG]; };
 
 // Issue the loads of row `row` (K columns).  Lanes past the end of the row
 // re-read its tail: finite weights against zero activations add nothing.
@@ -218,8 +218,9 @@ __device__ __forceinline__ void load_row(const ExpertMat& m, long row, int K, in
                 rr.c[s][1] = load_global<uint4>(codes + col0 + 16);
             } else if constexpr (BITS == 4) rr.c[s] = load_global_nt<uint4>(codes + (col0 >> 1));
             else rr.c[s] = load_global_nt<uint2>(codes + (col0 >> 2));
-            rr.s[s] = load_global<uint16_t>(m.s + row * G + (col0 >> 6));
-            rr.z[s] = load_global<uint16_t>(m.z + row * G + (col0 >> 6));
+            // the two lanes of a group share its scale and zero: the even lane fetches the scale, the odd one the
+            // zero (one load instruction for both; dot_row_q puts the halves together)
+            rr.sz[s] = load_global<uint16_t>(((lane & 1) ? m.z : m.s) + row * G + (col0 >> 6));
         }
     }
 }
@@ -235,9 +236,12 @@ __device__ __forceinline__ float dot_row_q(const RowRegs<BITS, NSEG>& rr, const 
         if constexpr (BITS == 8) acc = dot_q8(rr.c[s][0], rr.c[s][1], lx[s]);
         else if constexpr (BITS == 4) acc = dot_q4(rr.c[s], lx[s]);
         else acc = dot_q2(rr.c[s], lx[s]);
-        const float sc = h2f(f16_from_bits(rr.s[s]));
-        const float zr = h2f(f16_from_bits(rr.z[s]));
-        part += sc * (acc - lx[s].xoff) + zr * lx[s].xsum;
+        // group total = scale * sum_k q_k x_k + zero * sum_k x_k over both lanes' halves: the even lane, which holds
+        // the scale, takes the first term (its partner's sum comes over by DPP), the odd lane the second
+        const float qx = acc - lx[s].xoff;
+        const float qx_group = qx + dpp_get<0xB1, 0xF>(qx);
+        const float coef = h2f(f16_from_bits(rr.sz[s]));
+        part += coef * ((threadIdx.x & 1) ? lx[s].xsum : qx_group);
     }
     return part;
 }

@@ -200,6 +200,16 @@ __device__ __forceinline__ float dpp_get_or_self(float v)
     return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
 }
 
+// (v & mask) | magic in one instruction.  With literal operands the compiler has
+// to emit two (the three-operand form takes no literals), so the mask is handed
+// over in a scalar register and the magic number in a vector register.
+__device__ __forceinline__ uint32_t and_or(uint32_t v, uint32_t mask, uint32_t magic)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "s"(mask), "v"(magic));
+    return r;
+}
+
 __device__ __forceinline__ float wave_sum_dpp(float v)
 {
     v += dpp_get<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]

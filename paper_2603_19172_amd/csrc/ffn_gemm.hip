@@ -278,16 +278,6 @@ __device__ __forceinline__ MatPtr mat_ptr(const dymoe_expert_fmt& ex, int mat, i
     return m;
 }
 
-// (v & mask) | magic in one instruction.  With literal operands the compiler has
-// to emit two (the three-operand form takes no literals), so the mask is handed
-// over in a scalar register and the magic number in a vector register.
-__device__ __forceinline__ uint32_t and_or(uint32_t v, uint32_t mask, uint32_t magic)
-{
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "s"(mask), "v"(magic));
-    return r;
-}
-
 __device__ __forceinline__ uint32_t deq_pair(uint32_t biased, uint32_t bias2, uint32_t s2, uint32_t m2)
 {
     const half2_t q = __builtin_bit_cast(half2_t, biased) - __builtin_bit_cast(half2_t, bias2);  // exact

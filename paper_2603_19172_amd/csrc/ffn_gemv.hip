@@ -105,10 +105,10 @@ __device__ __forceinline__ float dot_q4(const uint4 c, const LaneX& lx)
 #pragma unroll
     for (int d = 0; d < 4; d++) {
         const uint32_t v = w[d], v8 = w[d] >> 8;
-        acc = dot2_f16((v & 0x000F000Fu) | 0x64006400u, lx.r[4 * d + 0], acc);
-        acc = dot2_f16((v & 0x00F000F0u) | 0x54005400u, lx.r[4 * d + 1], acc);
-        acc = dot2_f16((v8 & 0x000F000Fu) | 0x64006400u, lx.r[4 * d + 2], acc);
-        acc = dot2_f16((v8 & 0x00F000F0u) | 0x54005400u, lx.r[4 * d + 3], acc);
+        acc = dot2_f16(and_or(v, 0x000F000Fu, 0x64006400u), lx.r[4 * d + 0], acc);
+        acc = dot2_f16(and_or(v, 0x00F000F0u, 0x54005400u), lx.r[4 * d + 1], acc);
+        acc = dot2_f16(and_or(v8, 0x000F000Fu, 0x64006400u), lx.r[4 * d + 2], acc);
+        acc = dot2_f16(and_or(v8, 0x00F000F0u, 0x54005400u), lx.r[4 * d + 3], acc);
     }
     return acc;
 }
@@ -121,14 +121,14 @@ __device__ __forceinline__ float dot_q2(const uint2 c, const LaneX& lx)
 #pragma unroll
     for (int d = 0; d < 2; d++) {
         const uint32_t v = w[d], v10 = w[d] >> 10;
-        acc = dot2_f16((v & 0x00030003u) | 0x64006400u, lx.r[8 * d + 0], acc);
-        acc = dot2_f16((v & 0x000C000Cu) | 0x5C005C00u, lx.r[8 * d + 1], acc);
-        acc = dot2_f16((v & 0x00300030u) | 0x54005400u, lx.r[8 * d + 2], acc);
-        acc = dot2_f16((v & 0x00C000C0u) | 0x4C004C00u, lx.r[8 * d + 3], acc);
-        acc = dot2_f16((v & 0x03000300u) | 0x44004400u, lx.r[8 * d + 4], acc);
-        acc = dot2_f16((v10 & 0x00030003u) | 0x64006400u, lx.r[8 * d + 5], acc);
-        acc = dot2_f16((v10 & 0x000C000Cu) | 0x5C005C00u, lx.r[8 * d + 6], acc);
-        acc = dot2_f16((v10 & 0x00300030u) | 0x54005400u, lx.r[8 * d + 7], acc);
+        acc = dot2_f16(and_or(v, 0x00030003u, 0x64006400u), lx.r[8 * d + 0], acc);
+        acc = dot2_f16(and_or(v, 0x000C000Cu, 0x5C005C00u), lx.r[8 * d + 1], acc);
+        acc = dot2_f16(and_or(v, 0x00300030u, 0x54005400u), lx.r[8 * d + 2], acc);
+        acc = dot2_f16(and_or(v, 0x00C000C0u, 0x4C004C00u), lx.r[8 * d + 3], acc);
+        acc = dot2_f16(and_or(v, 0x03000300u, 0x44004400u), lx.r[8 * d + 4], acc);
+        acc = dot2_f16(and_or(v10, 0x00030003u, 0x64006400u), lx.r[8 * d + 5], acc);
+        acc = dot2_f16(and_or(v10, 0x000C000Cu, 0x5C005C00u), lx.r[8 * d + 6], acc);
+        acc = dot2_f16(and_or(v10, 0x00300030u, 0x54005400u), lx.r[8 * d + 7], acc);
     }
     return acc;
 }

@@ -180,7 +180,7 @@ def main():
     ffn_bytes = sum(3.0 * H * F * bytes_per_weight(b) for b in active_bits)
 
     # ---------------------------------------------------------------- per-kernel timing (eager, HIP events)
-    kernels = ["decode_front", "quantize", "gemv_phase1", "gemv_phase2", "gemv_combine"]
+    kernels = ["decode_front", "quantize", "gemv_phase1", "gemv_phase2"]
     ctx.timing_enable(kernels)
     n_timed = min(args.steps, 100)
     for i in range(n_timed):
@@ -236,12 +236,12 @@ def main():
         for i in range(4):
             layer.ffn(x, stores[i % len(stores)], st0)
         torch.cuda.synchronize()
-        ctx.timing_enable(["gemv_phase1", "gemv_phase2", "gemv_combine"])
+        ctx.timing_enable(["gemv_phase1", "gemv_phase2"])
         n_sw = 40
         for i in range(n_sw):
             layer.ffn(x, stores[i % len(stores)], st0)
         torch.cuda.synchronize()
-        us = {n_: ctx.timing_read(n_)[0] / n_sw * 1e3 for n_ in ("gemv_phase1", "gemv_phase2", "gemv_combine")}
+        us = {n_: ctx.timing_read(n_)[0] / n_sw * 1e3 for n_ in ("gemv_phase1", "gemv_phase2")}
         ctx.timing_enable(())
         nbytes = 3.0 * H * F * (bytes_per_weight(ba) + bytes_per_weight(bb))
         tot = sum(us.values())

@@ -464,7 +464,8 @@ size_t dymoe_cache_bytes_resident(const dymoe_cache* cache);
  * (bit i = kernel id i, ids 0..19 in the order route, token_norm, importance,
  * assign, quantize, gemv_phase1, gemv_phase2, gemv_combine, plan, gemm1, gemm2,
  * gemm_combine, stream_copy, decode_front, attn_stats, attn_colsum, gptq_group,
- * gptq_trail, gptq_hessian, gptq_factor) carry a start and a stop HIP event on the dispatch itself, so
+ * gptq_trail, gptq_hessian, gptq_factor; gemv_combine is reserved: the decode path's second phase
+ * writes y itself and no launch carries that id) carry a start and a stop HIP event on the dispatch itself, so
  * the interval is the kernel's execution time on the launch stream; 0 switches
  * timing off.  Either way, records not yet read are dropped.
  * dymoe_timing_read: waits for the recorded launches of `kernel`, drops their records and returns

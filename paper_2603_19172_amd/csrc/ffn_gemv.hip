@@ -1,7 +1,9 @@
 // Decode path of the mixed-precision SwiGLU expert FFN: bandwidth-bound
-// dequant-fused GEMV, one (token, expert) pair per grid row.
+// dequant-fused GEMV in two launches: phase 1 (gate and up projections, SwiGLU;
+// one (token, expert) pair per grid row) and phase 2 (down projection of every
+// expert of a token, weighted by the gate and summed into y).
 //
-// A wavefront owns whole weight rows.  A row is cut into segments of 2048
+// A wavefront streams weight rows.  A row is cut into segments of 2048
 // columns; in a segment every lane owns a fixed set of 32 columns, so the
 // activations a lane needs never change while it streams rows: they are
 // loaded once into registers (packed pairs) and the weight stream is the only
@@ -411,10 +413,18 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
 }
 
 // ---------------------------------------------------------------- phase 2
-// part[p,s,j] = sum over segment s of W2[j,f] * h[p,f]
-// A wavefront takes R consecutive rows j per iteration.
+// y[t,j] = sum_slot w[t,slot] * sum_f W2_e[j,f] * h[p,f],  p = t*k + slot, e = idx[p]
+// A workgroup owns kP2Rows consecutive rows j of one token, over every slot and every 2048-column segment of F:
+// the (slot, segment) units are dealt out to its wavefronts.  A wavefront keeps the activations of its unit in
+// registers, streams the unit's piece of every row and adds gate * partial into per-lane, per-row accumulators;
+// only after its last unit are the accumulators summed over the lanes (once per row instead of once per row and
+// segment), then over the wavefronts through LDS in a fixed order, and y is written: no partial sums in memory
+// and no separate combining launch.
 
 template <int BITS> struct Phase2Rows { static constexpr int R = (BITS == 16 || BITS == 8) ? 4 : 8; };
+
+constexpr int kP2Rows = 16;
+constexpr int kP2MaxWaves = 8;
 
 // fp32 intermediate against bf16 weights
 struct LaneH {
@@ -435,126 +445,122 @@ __device__ __forceinline__ float dot_row_h(const RowRegs<16, 1>& rr, const LaneH
     return acc;
 }
 
+// one unit: segment `seg` of rows j_begin .. j_begin + kP2Rows - 1 (clamped to the last row H - 1)
 template <int BITS, typename XT, typename DotFn>
-__device__ __forceinline__ void phase2_rows(const ExpertMat& m2, int F, int seg, int j_begin,
-                                            int j_end, float* __restrict__ out, const XT& lx,
-                                            DotFn dot)
+__device__ __forceinline__ void phase2_unit(const ExpertMat& m2, int F, int seg, int j_begin, int H,
+                                            float gate, float (&tot)[kP2Rows], const XT& lx, DotFn dot)
 {
     constexpr int R = Phase2Rows<BITS>::R;
+    constexpr int NB = kP2Rows / R;                 // 4 or 2 batches of rows
+    static_assert(NB % 2 == 0, "batches come in pairs");
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
     RowRegs<BITS, 1> ra[R], rb[R];                  // used in turn, as in phase 1
-    int j = j_begin + wave * R;
-    if (j >= j_end) return;
-    constexpr int kStep = kGvWaves * R;
     auto fetch = [&](RowRegs<BITS, 1>(&dst)[R], int j0) {
 #pragma unroll
-        for (int i = 0; i < R; i++) load_row<BITS, 1>(m2, min(j0 + i, j_end - 1), F, seg, lane, dst[i]);
+        for (int i = 0; i < R; i++) load_row<BITS, 1>(m2, min(j0 + i, H - 1), F, seg, lane, dst[i]);
     };
-    auto finish = [&](const RowRegs<BITS, 1>(&src)[R], int j0) {
-        float acc[R];
+    fetch(ra, j_begin);
 #pragma unroll
-        for (int i = 0; i < R; i++) acc[i] = dot(src[i], lx);
+    for (int bt = 0; bt < NB; bt += 2) {
+        fetch(rb, j_begin + (bt + 1) * R);          // next batch first
 #pragma unroll
-        for (int i = 0; i < R; i++) acc[i] = wave_sum_dpp(acc[i]);
-        float o = 0.0f;
+        for (int i = 0; i < R; i++) tot[bt * R + i] = fmaf(gate, dot(ra[i], lx), tot[bt * R + i]);
+        if (bt + 2 < NB) fetch(ra, j_begin + (bt + 2) * R);
 #pragma unroll
-        for (int i = 0; i < R; i++)
-            if (lane == i) o = acc[i];
-        if (lane < R && j0 + lane < j_end) out[j0 + lane] = o;
-    };
-    fetch(ra, j);
-    for (; j < j_end; j += 2 * kStep) {
-        fetch(rb, j + kStep);
-        finish(ra, j);
-        if (j + kStep >= j_end) break;
-        fetch(ra, j + 2 * kStep);
-        finish(rb, j + kStep);
+        for (int i = 0; i < R; i++) tot[(bt + 1) * R + i] = fmaf(gate, dot(rb[i], lx), tot[(bt + 1) * R + i]);
     }
 }
 
-__global__ __launch_bounds__(kGvThreads) void gemv_phase2_kernel(
-    const float* __restrict__ hbuf, const int32_t* __restrict__ idx,
+__global__ __launch_bounds__(kP2MaxWaves * kWave) void gemv_phase2_kernel(
+    const float* __restrict__ hbuf, const int32_t* __restrict__ idx, const float* __restrict__ w,
     const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table, int H, int F,
-    int E, int rows_per_block, int nseg, float* __restrict__ part)
+    int E, int k, int nseg, int out_dtype, void* __restrict__ y)
 {
-    const int p = (int)gridDim.z - 1 - (int)blockIdx.z;       // narrow formats first, as in phase 1
-    const int s = blockIdx.y;
-    const int e = idx[p];
-    if (e < 0 || e >= E) return;
-    const int b = bits[e];
-    if (b != 16 && b != 8 && b != 4 && b != 2) return;
+    __shared__ float s_red[kP2MaxWaves][kP2Rows];
+    const int t = blockIdx.y;
+    const int j_begin = blockIdx.x * kP2Rows;
     const int lane = threadIdx.x & (kWave - 1);
-    const int j_begin = blockIdx.x * rows_per_block;
-    const int j_end = min(H, j_begin + rows_per_block);
-    const float* hrow = hbuf + (long)p * F;
-    float* out = part + ((long)p * nseg + s) * H;
-    const dymoe_expert_fmt ex = table[e];
-    if (b == 16) {
-        LaneH lh;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int nwaves = blockDim.x / kWave;
+    float tot[kP2Rows];
 #pragma unroll
-        for (int c = 0; c < 4; c++) {
-            const int col = s * kSeg + (c * kWave + lane) * 8;
-#pragma unroll
-            for (int i = 0; i < 8; i++) lh.v[c][i] = 0.0f;
-            if (col < F) {
-                const float4 lo = *reinterpret_cast<const float4*>(hrow + col);
-                const float4 hi = *reinterpret_cast<const float4*>(hrow + col + 4);
-                lh.v[c][0] = lo.x; lh.v[c][1] = lo.y; lh.v[c][2] = lo.z; lh.v[c][3] = lo.w;
-                lh.v[c][4] = hi.x; lh.v[c][5] = hi.y; lh.v[c][6] = hi.z; lh.v[c][7] = hi.w;
-            }
-        }
-        phase2_rows<16>(pick_mat(ex, 2, 16), F, s, j_begin, j_end, out, lh,
-                        [](const RowRegs<16, 1>& rr, const LaneH& l) { return dot_row_h(rr, l); });
-    } else {
-        const int col0 = s * kSeg + 32 * lane;
-        float v[32];
-#pragma unroll
-        for (int c = 0; c < 8; c++) {
-            float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (col0 < F) q = *reinterpret_cast<const float4*>(hrow + col0 + 4 * c);
-            v[4 * c + 0] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
-        }
-        LaneX lx[1];
-        if (b == 8) {
-            arrange_lane_x<8>(v, lx[0]);
-            phase2_rows<8>(pick_mat(ex, 2, 8), F, s, j_begin, j_end, out, lx,
-                           [](const RowRegs<8, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<8, 1>(rr, l); });
-        } else if (b == 4) {
-            arrange_lane_x<4>(v, lx[0]);
-            phase2_rows<4>(pick_mat(ex, 2, 4), F, s, j_begin, j_end, out, lx,
-                           [](const RowRegs<4, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<4, 1>(rr, l); });
-        } else {
-            arrange_lane_x<2>(v, lx[0]);
-            phase2_rows<2>(pick_mat(ex, 2, 2), F, s, j_begin, j_end, out, lx,
-                           [](const RowRegs<2, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<2, 1>(rr, l); });
-        }
-    }
-}
-
-// y[t,j] = sum_slot w[t,slot] * sum_s part[p,s,j]   (pairs of skipped experts omitted)
-__global__ __launch_bounds__(256) void gemv_combine_kernel(
-    const float* __restrict__ part, const int32_t* __restrict__ idx,
-    const float* __restrict__ w, const uint8_t* __restrict__ bits, int T, int H, int E, int k,
-    int nseg, int out_dtype, void* __restrict__ y)
-{
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (long)T * H) return;
-    const int t = (int)(i / H);
-    const int j = (int)(i - (long)t * H);
-    float acc = 0.0f;
-    for (int slot = 0; slot < k; slot++) {
+    for (int i = 0; i < kP2Rows; i++) tot[i] = 0.0f;
+    const int units = k * nseg;
+    const int rounds = (units + nwaves - 1) / nwaves;
+    // odd wavefronts take their units in reverse: the slots of a token differ in format (the later, the narrower),
+    // and a compute unit should at any time hold wavefronts on wide, bandwidth-bound rows beside wavefronts on
+    // narrow, instruction-bound ones instead of all of them on the same kind
+    for (int r = 0; r < rounds; r++) {
+        const int u = wave + nwaves * ((wave & 1) ? rounds - 1 - r : r);
+        if (u >= units) continue;
+        const int slot = u / nseg;
+        const int s = u - slot * nseg;
         const int p = t * k + slot;
         const int e = idx[p];
-        if (e < 0 || e >= E) continue;
+        if (e < 0 || e >= E) continue;              // pairs of skipped experts add nothing
         const int b = bits[e];
         if (b != 16 && b != 8 && b != 4 && b != 2) continue;
-        float o = 0.0f;
-        for (int s = 0; s < nseg; s++) o += part[((long)p * nseg + s) * H + j];
-        acc = fmaf(w[p], o, acc);
+        const float gate = w[p];
+        const float* hrow = hbuf + (long)p * F;
+        const dymoe_expert_fmt ex = table[e];
+        if (b == 16) {
+            LaneH lh;
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                const int col = s * kSeg + (c * kWave + lane) * 8;
+#pragma unroll
+                for (int i = 0; i < 8; i++) lh.v[c][i] = 0.0f;
+                if (col < F) {
+                    const float4 lo = *reinterpret_cast<const float4*>(hrow + col);
+                    const float4 hi = *reinterpret_cast<const float4*>(hrow + col + 4);
+                    lh.v[c][0] = lo.x; lh.v[c][1] = lo.y; lh.v[c][2] = lo.z; lh.v[c][3] = lo.w;
+                    lh.v[c][4] = hi.x; lh.v[c][5] = hi.y; lh.v[c][6] = hi.z; lh.v[c][7] = hi.w;
+                }
+            }
+            phase2_unit<16>(pick_mat(ex, 2, 16), F, s, j_begin, H, gate, tot, lh,
+                            [](const RowRegs<16, 1>& rr, const LaneH& l) { return dot_row_h(rr, l); });
+        } else {
+            const int col0 = s * kSeg + 32 * lane;
+            float v[32];
+#pragma unroll
+            for (int c = 0; c < 8; c++) {
+                float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (col0 < F) q = *reinterpret_cast<const float4*>(hrow + col0 + 4 * c);
+                v[4 * c + 0] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
+            }
+            LaneX lx[1];
+            if (b == 8) {
+                arrange_lane_x<8>(v, lx[0]);
+                phase2_unit<8>(pick_mat(ex, 2, 8), F, s, j_begin, H, gate, tot, lx,
+                               [](const RowRegs<8, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<8, 1>(rr, l); });
+            } else if (b == 4) {
+                arrange_lane_x<4>(v, lx[0]);
+                phase2_unit<4>(pick_mat(ex, 2, 4), F, s, j_begin, H, gate, tot, lx,
+                               [](const RowRegs<4, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<4, 1>(rr, l); });
+            } else {
+                arrange_lane_x<2>(v, lx[0]);
+                phase2_unit<2>(pick_mat(ex, 2, 2), F, s, j_begin, H, gate, tot, lx,
+                               [](const RowRegs<2, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<2, 1>(rr, l); });
+            }
+        }
     }
-    if (out_dtype == DYMOE_OUT_F32) reinterpret_cast<float*>(y)[i] = acc;
-    else reinterpret_cast<uint16_t*>(y)[i] = (uint16_t)f32_to_bf16_bits(acc);
+    // lanes, then wavefronts (in wavefront order: the result does not depend on timing)
+    float o = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kP2Rows; i++) {
+        const float r = wave_sum_dpp(tot[i]);
+        if (lane == i) o = r;
+    }
+    if (lane < kP2Rows) s_red[wave][lane] = o;
+    __syncthreads();
+    const int j = j_begin + (int)threadIdx.x;
+    if (threadIdx.x < kP2Rows && j < H) {
+        float acc = 0.0f;
+        for (int wv = 0; wv < nwaves; wv++) acc += s_red[wv][threadIdx.x];
+        const long i = (long)t * H + j;
+        if (out_dtype == DYMOE_OUT_F32) reinterpret_cast<float*>(y)[i] = acc;
+        else reinterpret_cast<uint16_t*>(y)[i] = (uint16_t)f32_to_bf16_bits(acc);
+    }
 }
 
 int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w,
@@ -563,19 +569,17 @@ int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
 {
     const FfnLayout L = ffn_layout(T, H, F, E, k);
     float* hbuf = reinterpret_cast<float*>((char*)workspace + L.hbuf);
-    float* part = reinterpret_cast<float*>((char*)workspace + L.part);
     const int P = T * k;
     const int nseg1 = (H + kSeg - 1) / kSeg;
     const int nseg2 = (F + kSeg - 1) / kSeg;
-    // rows per workgroup: 64 / 64 on the Mixtral-shaped decode layer (measured: beat 16..128), which makes 448 and
-    // 896 workgroups; smaller layers get fewer rows per workgroup so that the launch still fills the chip
+    // phase 1, rows per workgroup: 64 on the Mixtral-shaped decode layer (measured: beat 16..128), which makes 448
+    // workgroups; smaller layers get fewer rows per workgroup so that the launch still fills the chip
     auto rows_for = [](long rows_total, long want_groups) {
         int r = 64;
         while (r > 8 && rows_total / r < want_groups) r >>= 1;
         return r;
     };
     const int rows1 = rows_for((long)F * P, 384);
-    const int rows2 = rows_for((long)H * nseg2 * P, 512);
     const dim3 g1((unsigned)((F + rows1 - 1) / rows1), (unsigned)P);
     const uint16_t* xb = (const uint16_t*)x;
     {
@@ -588,15 +592,17 @@ int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
         }
     }
     DYMOE_HIP_LAUNCH_CHECK();
-    const dim3 g2((unsigned)((H + rows2 - 1) / rows2), (unsigned)nseg2, (unsigned)P);
+    // phase 2: as many wavefronts as (slot, segment) units, at most kP2MaxWaves; of the counts that need the
+    // fewest rounds the smallest, so that no wavefront idles through the last round
+    const int units = k * nseg2;
+    int nwaves = units < kP2MaxWaves ? units : kP2MaxWaves;
     {
-        dymoe_launch(ctx, DYMOE_K_GEMV_PHASE2, gemv_phase2_kernel, g2, dim3(kGvThreads), 0, st, hbuf, idx, bits, table, H,
-                           F, E, rows2, nseg2, part);
+        const int rounds = (units + nwaves - 1) / nwaves;
+        while (nwaves > 1 && (units + nwaves - 2) / (nwaves - 1) == rounds) nwaves--;
     }
-    DYMOE_HIP_LAUNCH_CHECK();
-    const long n = (long)T * H;
-    dymoe_launch(ctx, DYMOE_K_GEMV_COMBINE, gemv_combine_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part,
-                       idx, w, bits, T, H, E, k, nseg2, out_dtype, y);
+    const dim3 g2((unsigned)((H + kP2Rows - 1) / kP2Rows), (unsigned)T);
+    dymoe_launch(ctx, DYMOE_K_GEMV_PHASE2, gemv_phase2_kernel, g2, dim3((unsigned)(nwaves * kWave)), 0, st, hbuf, idx, w,
+                 bits, table, H, F, E, k, nseg2, out_dtype, y);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }

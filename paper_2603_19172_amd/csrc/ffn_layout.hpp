@@ -12,7 +12,7 @@ constexpr int kPlanTileMin = 32;  // sizing granularity of the tile list
 
 struct FfnLayout {
     size_t hbuf;    // [P,F] SwiGLU intermediate: fp32 (GEMV) or 16-bit (GEMM)
-    size_t part;    // GEMV: [P,nseg,H] fp32 partial sums; GEMM: [P,H] fp32 per-pair outputs
+    size_t part;    // GEMM: [P,H] fp32 per-pair outputs (the GEMV path keeps its partial sums on chip; the area is sized as before)
     size_t xh;      // GEMM: three [T,H] fp16 copies of the activations (int4 / int2 / natural column order)
     size_t plan;    // int32: counts[E], offsets[E+1], cursor[E], ntiles, perm[P], tiles[4*maxtiles], draft[4*maxtiles]
     size_t total;

@@ -460,7 +460,7 @@ def test_chained_layer_tiny(ctx):
     assert err <= FFN_TOL
 
 
-def test_ffn_gemv_combine_is_deterministic_over_many_launches(ctx):
+def test_ffn_gemv_is_deterministic_over_many_launches(ctx):
     """Partial sums of the segments and of the token's experts are added in a fixed
     order: every launch gives the same bits."""
     cfg = synth.scaled(synth.CONFIGS["tiny"], T=3, H=1024, F=4096, E=4, k=2, config_id=81)

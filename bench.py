@@ -598,6 +598,34 @@ def main():
                                 "copy_time_hidden": None if ovl["copy_time_hidden"] is None else round(ovl["copy_time_hidden"], 3)})
                 del stack
                 torch.cuda.empty_cache()
+        # the same stack with every format of every expert resident on the device: one HIP graph per step
+        from paper_2603_19172_amd.stack import ResidentDecodeStack
+        resident = []
+        for tier_name, tcount, tbits, flr in (("1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
+                                              ("4/2 with the cosine depth schedule", paper_tiers, (4, 2), None)):
+            for graph in (False, True):
+                rs = ResidentDecodeStack(ctx, H, F, E, k, routers, pool, tcount, tbits, floor_bits=flr, alpha=0.125,
+                                         device=dev, graph=graph)
+                for s in range(2):
+                    rs.step(xs[s % len(xs)])
+                torch.cuda.synchronize()
+                n_rs = max(args.stack_steps, 32)
+                t0 = time.perf_counter()
+                for s in range(n_rs):
+                    rs.step(xs[s % len(xs)])
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+                tr = rs.trace()
+                nbytes = sum(pool.nbytes[b] for (_, bts) in tr for b in bts)
+                resident.append({"tiers": tier_name, "launch": "hip_graph" if graph else "eager", "steps": n_rs,
+                                 "steps_per_s": round(n_rs / dt, 1), "us_per_layer": round(dt / n_rs / L * 1e6, 1),
+                                 "weight_GB_read_in_the_last_step": round(nbytes / 1e9, 3),
+                                 "GBps_last_step_bytes_at_mean_rate": round(nbytes / (dt / n_rs) / 1e9, 1)})
+                del rs
+                torch.cuda.empty_cache()
+        out["stack_decode_resident"] = {"workload": "the same 32 layers with every expert resident in device memory in every "
+                                                    "format its tiers may name: no copies, no host decisions, a step is "
+                                                    "128 launches replayed as one HIP graph", "runs": resident}
         out["stack_decode"] = {"workload": "32 Mixtral-shaped layers, 1 token per step, experts in pinned host memory "
                                            "(16 distinct experts shared by the 256 layer-experts), look-ahead of the next layer's 2 "
                                            "experts; the 1/3/4 tiers carry an int4 floor in the first and last 4 layers",

@@ -481,3 +481,96 @@ class PrefillStack(ExpertStack):
                          floor_bits=floor_bits, prefetch=prefetch, transfer=transfer, alpha=alpha, k_hh=k_hh,
                          predict_t=predict_t if predict_t is not None else min(E, max(k, E // 2)), device=device,
                          budget_bytes=budget_bytes)
+
+
+class ResidentDecodeStack:
+    """One token per step through a stack whose experts are all resident in DEVICE memory, in every format the
+    precision assignment may name (a 288 GB device holds a whole model of the paper's size, Sec. 6.1).
+
+    Nothing is copied and nothing is decided on the host: the importance of an expert and its bit width are still
+    chosen per token and layer on the device (Sec. 4.2.2, Sec. 4.3), and the FFN reads, through the layer's format
+    table, the format the assignment names.  A step is therefore a fixed chain of launches (per layer
+    dymoe_decode_front, dymoe_moe_ffn_mixed, dymoe_residual_rmsnorm) and is replayed as one HIP graph.
+
+    pool: a HostExpertPool holding every format in `tier_bits` and the floors (row-major codes); its entries are
+    copied to the device once.  tier_count: one tuple, or one per layer; floor_bits: per layer or None."""
+
+    def __init__(self, ctx, H, F, E, k, routers, pool, tier_count, tier_bits, floor_bits=None, alpha=0.125,
+                 device="cuda:0", graph=True):
+        self.ctx, self.H, self.F, self.E, self.k = ctx, H, F, E, k
+        self.L = L = len(routers)
+        self.routers, self.alpha, self.dev = routers, float(alpha), device
+        self.floor = [int(b) for b in floor_bits] if floor_bits is not None else [0] * L
+        per_layer = isinstance(tier_count[0], (tuple, list))
+        tiers = [tuple(tc) for tc in tier_count] if per_layer else [tuple(tier_count)] * L
+        if len(tiers) != L or any(len(tc) != len(tier_bits) for tc in tiers):
+            raise ValueError("tier_count: one tuple, or one per layer, as long as tier_bits")
+        self._tc = [(C.c_int32 * len(tc))(*[int(v) for v in tc]) for tc in tiers]
+        self._tb = (C.c_uint8 * len(tier_bits))(*[int(b) for b in tier_bits])
+        self._nt = len(tier_bits)
+        formats = sorted({int(b) for b in list(tier_bits) + self.floor if int(b) != 0})
+        missing = [b for b in formats if b not in pool.buf]
+        if missing:
+            raise ValueError("the pool holds no %s-bit format" % missing)
+        if any(b != 16 for b in formats) and pool.layout != B.LAYOUT_ROWMAJOR:
+            raise ValueError("the decode path reads row-major codes")
+        self.weights = {b: pool.buf[b].to(device) for b in formats}     # [n_pool, bytes of the format]
+        table = bytearray()
+        for l in range(L):
+            for e in range(E):
+                fmt, i = B.ExpertFmt(), pool.entry(l, e)
+                for b in formats:
+                    base = self.weights[b].data_ptr() + i * pool.nbytes[b]
+                    if b == 16:
+                        for m in range(3):
+                            fmt.w[m] = base + m * H * F * 2
+                    else:
+                        _Slot._point(fmt, b, base, quant_layout(H, F, b)[0])
+                table += bytes(fmt)
+        self.tables = torch.frombuffer(table, dtype=torch.uint8).to(device).view(L, E, FMT_BYTES)
+        i32 = lambda *s: torch.zeros(s, dtype=torch.int32, device=device)
+        f32 = lambda *s: torch.zeros(s, dtype=torch.float32, device=device)
+        self.idx, self.gate = i32(L, 1, k), f32(L, 1, k)                 # kept per layer: what `trace` reports
+        self.bits = torch.zeros((L, E), dtype=torch.uint8, device=device)
+        self.probs, self.imp, self.load, self.rank = f32(1, E), f32(E), i32(E), i32(E)
+        self.y = f32(1, H)
+        self.ws_bytes = B.workspace_bytes(1, H, F, E, k)
+        self.ws = torch.empty((self.ws_bytes,), dtype=torch.uint8, device=device)
+        self.h = [torch.zeros((1, H), dtype=torch.bfloat16, device=device) for _ in range(2)]
+        self._graph = None if graph else False
+
+    def _enqueue(self, st):
+        ctx, H, F, E, k = self.ctx._h, self.H, self.F, self.E, self.k
+        for l in range(self.L):
+            h, nxt = self.h[l % 2], self.h[(l + 1) % 2]
+            idx, gate, bits, table = self.idx[l].data_ptr(), self.gate[l].data_ptr(), self.bits[l].data_ptr(), \
+                self.tables[l].data_ptr()
+            B._check(B.lib.dymoe_decode_front(ctx, h.data_ptr(), self.routers[l].data_ptr(), None, 1, H, E, k, 1,
+                                              self._nt, C.cast(self._tc[l], C.c_void_p), C.cast(self._tb, C.c_void_p),
+                                              self.floor[l], idx, gate, self.probs.data_ptr(), self.imp.data_ptr(),
+                                              self.load.data_ptr(), bits, self.rank.data_ptr(), st),
+                     "dymoe_decode_front")
+            B._check(B.lib.dymoe_moe_ffn_mixed(ctx, h.data_ptr(), idx, gate, bits, table, 1, H, F, E, k, 64, B.OUT_F32,
+                                               B.PATH_GEMV, self.y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, st),
+                     "dymoe_moe_ffn_mixed")
+            B._check(B.lib.dymoe_residual_rmsnorm(ctx, h.data_ptr(), self.y.data_ptr(), B.OUT_F32, self.alpha, 1, H,
+                                                  nxt.data_ptr(), st), "dymoe_residual_rmsnorm")
+
+    def step(self, h0):
+        """h0: [1,H] bf16 on the device.  Returns the final hidden states (a buffer the next step overwrites)."""
+        self.h[0].copy_(h0)
+        if self._graph is False:
+            self._enqueue(torch.cuda.current_stream().cuda_stream)
+        else:
+            if self._graph is None:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=torch.cuda.Stream(device=self.dev)):
+                    self._enqueue(torch.cuda.current_stream().cuda_stream)
+                self._graph = g
+            self._graph.replay()
+        return self.h[self.L % 2]
+
+    def trace(self):
+        """Per layer of the last step: (selected experts in routing order, their assigned bit widths).  Synchronises."""
+        idx, bits = self.idx.cpu(), self.bits.cpu()
+        return [(tuple(int(e) for e in idx[l, 0]), tuple(int(bits[l, e]) for e in idx[l, 0])) for l in range(self.L)]

@@ -8,7 +8,7 @@ import torch
 from oracle import dymoe_oracle as O
 from paper_2603_19172_amd import binding as B
 from paper_2603_19172_amd import synth
-from paper_2603_19172_amd.stack import DecodeStack, HostExpertPool, PrefillStack
+from paper_2603_19172_amd.stack import DecodeStack, HostExpertPool, PrefillStack, ResidentDecodeStack
 from gpu_helpers import DEV, bits_of, margin_ok, to_bf16
 
 pytestmark = pytest.mark.gpu
@@ -369,3 +369,43 @@ def test_pool_prepared_with_the_compensated_quantizer(ctx, layout):
             assert torch.isfinite(h.float()).all()
         stack.close()
         assert stack.stats["copies_4"] + stack.stats["copies_2"] > 0
+
+
+@pytest.mark.parametrize("tiers,floor_rule", [(TIERS3, True), (((3, 5), (4, 2)), False), (TIERS4, True)])
+def test_resident_stack_replayed_as_a_graph_matches_eager_launches_and_the_oracle(ctx, tiers, floor_rule):
+    """Every expert in every format in device memory: no copies, no host decisions, a step is one HIP graph.  The
+    graph is replayed several times with other inputs, eager steps and synchronisations in between, and every
+    replay must give exactly what eager launches give; the chain itself is the oracle's (assigned precisions)."""
+    H, F, E, k, L = 256, 512, 8, 2, 5
+    cfgs = [synth.scaled(synth.CONFIGS["tiny"], T=1, phase="decode", config_id=2300 + l) for l in range(L)]
+    routers_np = [synth.router(c)[0] for c in cfgs]
+    n_pool = 12
+    pool_cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=2350)
+    mats = {i: synth.expert_weights(pool_cfg, i) for i in range(n_pool)}
+    pool = HostExpertPool(H, F, E, n_pool, lambda i: mats[i])
+    pool.add_quantised(ctx, DEV, formats=[b for b in tiers[1] if b != 16])
+    floor = ([4] + [0] * (L - 2) + [4]) if floor_rule else [0] * L
+    routers = [to_bf16(r) for r in routers_np]
+    make = lambda graph: ResidentDecodeStack(ctx, H, F, E, k, routers, pool, tiers[0], tiers[1], floor_bits=floor,
+                                             alpha=0.25, device=DEV, graph=graph)
+    eager, replayed = make(False), make(True)
+    outs, traces = [], []
+    for s in (0, 1, 2, 1, 0, 3):
+        x, _ = synth.activations(synth.scaled(cfgs[0], config_id=2400 + s))
+        a = eager.step(to_bf16(x)).clone()
+        torch.cuda.synchronize()
+        b = replayed.step(to_bf16(x)).clone()
+        assert torch.equal(a, b)
+        assert eager.trace() == replayed.trace()
+        outs.append((x, b))
+        traces.append([(ex, bts, bts) for (ex, bts) in replayed.trace()])
+    _check_against_oracle(outs, traces, routers_np, lambda l, e: mats[pool.entry(l, e)], floor, tiers=tiers)
+
+
+def test_resident_stack_refuses_a_pool_without_the_formats_it_may_need(ctx):
+    H, F, E, k = 256, 512, 8, 2
+    pool_cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=2350)
+    pool = HostExpertPool(H, F, E, 4, lambda i: synth.expert_weights(pool_cfg, i))
+    routers = [to_bf16(synth.router(synth.scaled(synth.CONFIGS["tiny"], T=1, phase="decode", config_id=2300))[0])]
+    with pytest.raises(ValueError):
+        ResidentDecodeStack(ctx, H, F, E, k, routers, pool, (1, 3, 4), (16, 4, 2), device=DEV)

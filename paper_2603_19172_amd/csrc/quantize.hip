@@ -115,14 +115,20 @@ __global__ __launch_bounds__(kQThreads) void quantize_pack_kernel(
 }
 
 // Tile-layout variant: a lane owns a whole group (row 32*nt + r, columns
-// 128*kt + 64*kb .. +64 of tile (nt, kt), lane l = 32*kb + r): eight 16-byte
-// loads from the row-major bf16 matrix, no cross-lane step, and the codes,
-// scale and zero go to the lane's slots of the tile.  One wavefront per tile.
+// 128*kt + 64*kb .. +64 of tile (nt, kt), lane l = 32*kb + r), no cross-lane
+// arithmetic, and the codes, scale and zero go to the lane's slots of the tile.
+// One wavefront per tile.  The tile's 32 row pieces of 256 bytes are fetched
+// with whole-line loads (16 lanes per row piece, 4 rows per instruction) and
+// turned through the wavefront's LDS stage into the lane-owns-a-group order;
+// rows of the stage are 272 bytes apart so that neither side has bank conflicts.
+constexpr int kTileStageRow = 272;
+constexpr int kTileStageBytes = 32 * kTileStageRow;
+
 template <int BITS>
 __device__ __forceinline__ void quantize_tile(const uint16_t* __restrict__ w, long K, long tile,
                                               uint8_t* __restrict__ codes,
                                               uint16_t* __restrict__ scale,
-                                              uint16_t* __restrict__ zero)
+                                              uint16_t* __restrict__ zero, uint8_t* stage)
 {
 #pragma clang fp contract(off)
     constexpr int qmax = (1 << BITS) - 1;
@@ -132,11 +138,22 @@ __device__ __forceinline__ void quantize_tile(const uint16_t* __restrict__ w, lo
     const long KT = K >> 7;
     const long nt = tile / KT;
     const long kt = tile - nt * KT;
-    const long row = nt * 32 + (lane & 31);
-    const long col = kt * 128 + 64 * (lane >> 5);
     uint4 raw[8];
+    {
+        const uint16_t* src = w + (nt * 32 + (lane >> 4)) * K + kt * 128 + (lane & 15) * 8;
 #pragma unroll
-    for (int c = 0; c < 8; c++) raw[c] = load_global<uint4>(w + row * K + col + 8 * c);
+        for (int c = 0; c < 8; c++) raw[c] = load_global_nt<uint4>(src + 4 * c * K);
+        uint8_t* put = stage + (lane >> 4) * kTileStageRow + (lane & 15) * 16;
+#pragma unroll
+        for (int c = 0; c < 8; c++) *reinterpret_cast<uint4*>(put + 4 * c * kTileStageRow) = raw[c];
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");      // the stage is the wavefront's own
+        __builtin_amdgcn_wave_barrier();
+        const uint8_t* get = stage + (lane & 31) * kTileStageRow + (lane >> 5) * 128;
+#pragma unroll
+        for (int c = 0; c < 8; c++) raw[c] = *reinterpret_cast<const uint4*>(get + 16 * c);
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");      // read before the next tile overwrites it
+        __builtin_amdgcn_wave_barrier();
+    }
     float v[64];
 #pragma unroll
     for (int c = 0; c < 8; c++) unpack8(raw[c], v + 8 * c);
@@ -272,6 +289,8 @@ __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
 {
     __shared__ int16_t list[DYMOE_MAX_EXPERTS];
     __shared__ int n_list;
+    __shared__ __attribute__((aligned(16))) uint8_t
+        stage[(LAYOUT == DYMOE_LAYOUT_TILE) ? (kQThreads / kWave) * kTileStageBytes : 16];
     const int n_work = build_worklist(bits, load, E, list, &n_list);
     const long n_elems = (long)H * (long)F;
     // row-major: 8192 elements per block; tiles: 4 tiles (one per wavefront) = 16384 elements
@@ -293,9 +312,10 @@ __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
             const long K = (mat == 2) ? F : H;
             const long tile = blk * 4 + (threadIdx.x >> 6);
             if (tile * 4096 < n_elems) {
-                if (b == 8) quantize_tile<8>(w, K, tile, q, sc, zr);
-                else if (b == 4) quantize_tile<4>(w, K, tile, q, sc, zr);
-                else quantize_tile<2>(w, K, tile, q, sc, zr);
+                uint8_t* mine = stage + (threadIdx.x >> 6) * kTileStageBytes;
+                if (b == 8) quantize_tile<8>(w, K, tile, q, sc, zr, mine);
+                else if (b == 4) quantize_tile<4>(w, K, tile, q, sc, zr, mine);
+                else quantize_tile<2>(w, K, tile, q, sc, zr, mine);
             }
         } else {
             if (b == 8) quantize_block<8>(w, n_elems, q, sc, zr, blk);

@@ -17,6 +17,8 @@ namespace dymoe {
 constexpr int kQThreads = 256;
 constexpr int kQElemsPerLane = 32;
 constexpr int kQElemsPerBlock = kQThreads * kQElemsPerLane;  // 8192 elements = 128 groups
+constexpr int kRowStageLane = 80;                            // bytes between two lanes' pieces of the LDS stage
+constexpr int kRowStageBytes = kWave * kRowStageLane;        // per wavefront
 
 __device__ __forceinline__ void unpack8(const uint4 raw, float* v)
 {
@@ -33,7 +35,7 @@ template <int BITS>
 __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, long n_elems,
                                                uint8_t* __restrict__ codes,
                                                uint16_t* __restrict__ scale,
-                                               uint16_t* __restrict__ zero, long block)
+                                               uint16_t* __restrict__ zero, long block, uint8_t* stage)
 {
 #pragma clang fp contract(off)
     constexpr int qmax = (1 << BITS) - 1;
@@ -41,11 +43,30 @@ __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, l
     constexpr int kMagicBits = 0x4B400000;
     const int lane = threadIdx.x & (kWave - 1);
     const long e0 = block * (long)kQElemsPerBlock + (long)threadIdx.x * kQElemsPerLane;
+    // The wavefront's 4 KiB come in with whole-line loads (lane l takes 16 bytes of each of four 1 KiB pieces) and
+    // are turned through the wavefront's LDS stage into 32 consecutive weights per lane; a lane's 64 bytes of the
+    // stage start 80 bytes apart so that the 16-byte reads meet no bank conflict.
+    uint4 raw[4];
+    {
+        const long wave0 = e0 - (long)lane * kQElemsPerLane;      // first element of the wavefront
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            const long at = wave0 + (long)(c * kWave + lane) * 8;
+            raw[c] = make_uint4(0, 0, 0, 0);
+            if (at < n_elems) raw[c] = load_global_nt<uint4>(w + at);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; c++)
+            *reinterpret_cast<uint4*>(stage + (16 * c + (lane >> 2)) * kRowStageLane + (lane & 3) * 16) = raw[c];
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");      // the stage is the wavefront's own
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int c = 0; c < 4; c++) raw[c] = *reinterpret_cast<const uint4*>(stage + lane * kRowStageLane + 16 * c);
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");      // read before the next block overwrites it
+        __builtin_amdgcn_wave_barrier();
+    }
     // a group's two lanes are in or out together (n_elems is a multiple of 64)
     if (e0 >= n_elems) return;
-    uint4 raw[4];
-#pragma unroll
-    for (int c = 0; c < 4; c++) raw[c] = load_global<uint4>(w + e0 + 8 * c);
     float v[32];
 #pragma unroll
     for (int c = 0; c < 4; c++) unpack8(raw[c], v + 8 * c);
@@ -109,9 +130,11 @@ __global__ __launch_bounds__(kQThreads) void quantize_pack_kernel(
     const uint16_t* __restrict__ w, long n_elems, int bits,
     uint8_t* __restrict__ codes, uint16_t* __restrict__ scale, uint16_t* __restrict__ zero)
 {
-    if (bits == 8) quantize_block<8>(w, n_elems, codes, scale, zero, blockIdx.x);
-    else if (bits == 4) quantize_block<4>(w, n_elems, codes, scale, zero, blockIdx.x);
-    else quantize_block<2>(w, n_elems, codes, scale, zero, blockIdx.x);
+    __shared__ __attribute__((aligned(16))) uint8_t stage[(kQThreads / kWave) * kRowStageBytes];
+    uint8_t* mine = stage + (threadIdx.x / kWave) * kRowStageBytes;
+    if (bits == 8) quantize_block<8>(w, n_elems, codes, scale, zero, blockIdx.x, mine);
+    else if (bits == 4) quantize_block<4>(w, n_elems, codes, scale, zero, blockIdx.x, mine);
+    else quantize_block<2>(w, n_elems, codes, scale, zero, blockIdx.x, mine);
 }
 
 // Tile-layout variant: a lane owns a whole group (row 32*nt + r, columns
@@ -290,7 +313,7 @@ __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
     __shared__ int16_t list[DYMOE_MAX_EXPERTS];
     __shared__ int n_list;
     __shared__ __attribute__((aligned(16))) uint8_t
-        stage[(LAYOUT == DYMOE_LAYOUT_TILE) ? (kQThreads / kWave) * kTileStageBytes : 16];
+        stage[(kQThreads / kWave) * ((LAYOUT == DYMOE_LAYOUT_TILE) ? kTileStageBytes : kRowStageBytes)];
     const int n_work = build_worklist(bits, load, E, list, &n_list);
     const long n_elems = (long)H * (long)F;
     // row-major: 8192 elements per block; tiles: 4 tiles (one per wavefront) = 16384 elements
@@ -318,9 +341,10 @@ __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
                 else quantize_tile<2>(w, K, tile, q, sc, zr, mine);
             }
         } else {
-            if (b == 8) quantize_block<8>(w, n_elems, q, sc, zr, blk);
-            else if (b == 4) quantize_block<4>(w, n_elems, q, sc, zr, blk);
-            else quantize_block<2>(w, n_elems, q, sc, zr, blk);
+            uint8_t* mine = stage + (threadIdx.x >> 6) * kRowStageBytes;
+            if (b == 8) quantize_block<8>(w, n_elems, q, sc, zr, blk, mine);
+            else if (b == 4) quantize_block<4>(w, n_elems, q, sc, zr, blk, mine);
+            else quantize_block<2>(w, n_elems, q, sc, zr, blk, mine);
         }
     }
 }

@@ -338,7 +338,8 @@ def test_ffn_tiny_every_precision(ctx, path):
 
 def test_ffn_gemv_ragged_shapes(ctx):
     # row lengths that leave lanes idle and need several segments; odd token count
-    for T, H, F, E, k in ((5, 320, 192, 4, 2), (3, 4160, 2112, 3, 2), (1, 8192, 128, 2, 1)):
+    # (the last: 18 (slot, segment) units of the second phase over 6 wavefronts and 3 rounds, a short last segment)
+    for T, H, F, E, k in ((5, 320, 192, 4, 2), (3, 4160, 2112, 3, 2), (1, 8192, 128, 2, 1), (2, 320, 10304, 4, 3)):
         cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=21, T=T, H=H, F=F, E=E, k=k,
                            tier_count=(E,))
         x, _ = synth.activations(cfg)

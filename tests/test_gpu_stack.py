@@ -43,7 +43,7 @@ def test_prefetch_copy_is_ordered_before_the_compute_stream(ctx):
     ctx.prefetch_release(ev)
 
 
-@pytest.mark.parametrize("T,H,alpha", [(1, 256, 1.0), (5, 4096, 0.125), (3, 264, 0.5)])
+@pytest.mark.parametrize("T,H,alpha", [(1, 256, 1.0), (5, 4096, 0.125), (3, 264, 0.5), (2, 250, 0.5), (3, 6152, 0.25)])
 def test_residual_rmsnorm_against_the_oracle(ctx, T, H, alpha):
     rng = np.random.default_rng(3)
     h = synth.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))

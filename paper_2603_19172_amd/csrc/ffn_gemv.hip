@@ -471,6 +471,45 @@ __device__ __forceinline__ void phase2_unit(const ExpertMat& m2, int F, int seg,
     }
 }
 
+// Two units of narrow formats (int4, int2) side by side: a wavefront's start-up chain (pair -> expert -> bit width ->
+// table entry -> activations -> first rows) is a string of dependent latencies, and with 16 rows of int4 or int2
+// there is little streaming to hide the second unit's chain behind.  Taken together, both chains run at once.
+template <int BA, int BB>
+__device__ __forceinline__ void phase2_two_units(const ExpertMat& ma, const ExpertMat& mb, int F, int sa, int sb,
+                                                 int j_begin, int H, float ga, float gb,
+                                                 float (&tot)[kP2Rows], const LaneX (&la)[1], const LaneX (&lb)[1])
+{
+    constexpr int R = (BA == 2 && BB == 2) ? 8 : 4;
+    constexpr int NB = kP2Rows / R;
+    static_assert(NB % 2 == 0, "batches come in pairs");
+    const int lane = threadIdx.x & (kWave - 1);
+    RowRegs<BA, 1> a0[R], a1[R];
+    RowRegs<BB, 1> b0[R], b1[R];
+    auto fetch = [&](RowRegs<BA, 1>(&da)[R], RowRegs<BB, 1>(&db)[R], int j0) {
+#pragma unroll
+        for (int i = 0; i < R; i++) {
+            const int row = min(j0 + i, H - 1);
+            load_row<BA, 1>(ma, row, F, sa, lane, da[i]);
+            load_row<BB, 1>(mb, row, F, sb, lane, db[i]);
+        }
+    };
+    auto finish = [&](const RowRegs<BA, 1>(&da)[R], const RowRegs<BB, 1>(&db)[R], int bt) {
+#pragma unroll
+        for (int i = 0; i < R; i++) {
+            float acc = fmaf(ga, dot_row_q<BA, 1>(da[i], la), tot[bt * R + i]);
+            tot[bt * R + i] = fmaf(gb, dot_row_q<BB, 1>(db[i], lb), acc);
+        }
+    };
+    fetch(a0, b0, j_begin);
+#pragma unroll
+    for (int bt = 0; bt < NB; bt += 2) {
+        fetch(a1, b1, j_begin + (bt + 1) * R);
+        finish(a0, b0, bt);
+        if (bt + 2 < NB) fetch(a0, b0, j_begin + (bt + 2) * R);
+        finish(a1, b1, bt + 1);
+    }
+}
+
 __global__ __launch_bounds__(kP2MaxWaves * kWave) void gemv_phase2_kernel(
     const float* __restrict__ hbuf, const int32_t* __restrict__ idx, const float* __restrict__ w,
     const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table, int H, int F,
@@ -490,16 +529,35 @@ __global__ __launch_bounds__(kP2MaxWaves * kWave) void gemv_phase2_kernel(
     // odd wavefronts take their units in reverse: the slots of a token differ in format (the later, the narrower),
     // and a compute unit should at any time hold wavefronts on wide, bandwidth-bound rows beside wavefronts on
     // narrow, instruction-bound ones instead of all of them on the same kind
-    for (int r = 0; r < rounds; r++) {
+    struct Unit {
+        int valid, p, s, e, b;
+    };
+    auto unit_of = [&](int r) {
+        Unit un = {0, 0, 0, 0, 0};
+        if (r >= rounds) return un;
         const int u = wave + nwaves * ((wave & 1) ? rounds - 1 - r : r);
-        if (u >= units) continue;
+        if (u >= units) return un;
         const int slot = u / nseg;
-        const int s = u - slot * nseg;
-        const int p = t * k + slot;
-        const int e = idx[p];
-        if (e < 0 || e >= E) continue;              // pairs of skipped experts add nothing
-        const int b = bits[e];
-        if (b != 16 && b != 8 && b != 4 && b != 2) continue;
+        un.s = u - slot * nseg;
+        un.p = t * k + slot;
+        un.e = idx[un.p];
+        if (un.e < 0 || un.e >= E) return un;       // pairs of skipped experts add nothing
+        un.b = bits[un.e];
+        un.valid = (un.b == 16 || un.b == 8 || un.b == 4 || un.b == 2);
+        return un;
+    };
+    auto quant_x = [&](const Unit& un, float (&v)[32]) {
+        const float* hrow = hbuf + (long)un.p * F;
+        const int col0 = un.s * kSeg + 32 * lane;
+#pragma unroll
+        for (int c = 0; c < 8; c++) {
+            float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (col0 < F) q = *reinterpret_cast<const float4*>(hrow + col0 + 4 * c);
+            v[4 * c + 0] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
+        }
+    };
+    auto one_unit = [&](const Unit& un) {
+        const int p = un.p, s = un.s, e = un.e, b = un.b;
         const float gate = w[p];
         const float* hrow = hbuf + (long)p * F;
         const dymoe_expert_fmt ex = table[e];
@@ -520,14 +578,8 @@ __global__ __launch_bounds__(kP2MaxWaves * kWave) void gemv_phase2_kernel(
             phase2_unit<16>(pick_mat(ex, 2, 16), F, s, j_begin, H, gate, tot, lh,
                             [](const RowRegs<16, 1>& rr, const LaneH& l) { return dot_row_h(rr, l); });
         } else {
-            const int col0 = s * kSeg + 32 * lane;
             float v[32];
-#pragma unroll
-            for (int c = 0; c < 8; c++) {
-                float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (col0 < F) q = *reinterpret_cast<const float4*>(hrow + col0 + 4 * c);
-                v[4 * c + 0] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
-            }
+            quant_x(un, v);
             LaneX lx[1];
             if (b == 8) {
                 arrange_lane_x<8>(v, lx[0]);
@@ -542,6 +594,37 @@ __global__ __launch_bounds__(kP2MaxWaves * kWave) void gemv_phase2_kernel(
                 phase2_unit<2>(pick_mat(ex, 2, 2), F, s, j_begin, H, gate, tot, lx,
                                [](const RowRegs<2, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<2, 1>(rr, l); });
             }
+        }
+    };
+    for (int r = 0; r < rounds; r += 2) {
+        const Unit ua = unit_of(r), ub = unit_of(r + 1);
+        if (ua.valid && ub.valid && (ua.b == 4 || ua.b == 2) && (ub.b == 4 || ub.b == 2)) {
+            const float ga = w[ua.p], gb = w[ub.p];
+            const ExpertMat ma = pick_mat(table[ua.e], 2, ua.b), mb = pick_mat(table[ub.e], 2, ub.b);
+            LaneX la[1], lb[1];
+            {
+                float v[32];
+                quant_x(ua, v);
+                if (ua.b == 4) arrange_lane_x<4>(v, la[0]);
+                else arrange_lane_x<2>(v, la[0]);
+            }
+            {
+                float v[32];
+                quant_x(ub, v);
+                if (ub.b == 4) arrange_lane_x<4>(v, lb[0]);
+                else arrange_lane_x<2>(v, lb[0]);
+            }
+            if (ua.b == 4 && ub.b == 4)
+                phase2_two_units<4, 4>(ma, mb, F, ua.s, ub.s, j_begin, H, ga, gb, tot, la, lb);
+            else if (ua.b == 4)
+                phase2_two_units<4, 2>(ma, mb, F, ua.s, ub.s, j_begin, H, ga, gb, tot, la, lb);
+            else if (ub.b == 4)
+                phase2_two_units<2, 4>(ma, mb, F, ua.s, ub.s, j_begin, H, ga, gb, tot, la, lb);
+            else
+                phase2_two_units<2, 2>(ma, mb, F, ua.s, ub.s, j_begin, H, ga, gb, tot, la, lb);
+        } else {
+            if (ua.valid) one_unit(ua);
+            if (ub.valid) one_unit(ub);
         }
     }
     // lanes, then wavefronts (in wavefront order: the result does not depend on timing)

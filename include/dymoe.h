@@ -352,6 +352,8 @@ int dymoe_pack_code_tiles(dymoe_ctx* ctx, const uint8_t* codes, const void* scal
  * contents are scratch.  Limits: group = 64; H, F multiples of 64;
  * GEMV path H <= 8192; GEMM path H, F multiples of 128; E <= DYMOE_MAX_EXPERTS.
  * Activations and the SwiGLU intermediate must stay inside fp16 range.
+ * Every sum is taken in a fixed order (no atomics): the same inputs give the
+ * same bits from launch to launch, on either path.
  */
 int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w,
                         const uint8_t* bits, const dymoe_expert_fmt* table,

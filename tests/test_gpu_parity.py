@@ -489,6 +489,20 @@ def test_ffn_gemv_is_deterministic_over_many_launches(ctx):
     assert rel_err_per_token(first.cpu().numpy(), ref) <= FFN_TOL
 
 
+def test_ffn_gemm_is_deterministic_over_many_launches(ctx):
+    """The grouped GEMM orders an expert's tokens with atomics, but no sum depends on that order, and the split-K
+    slabs are added in a fixed order: every launch gives the same bits."""
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=300, H=256, F=1024, E=4, k=2, config_id=83, tier_count=(4,))
+    x, _ = synth.activations(cfg)
+    idx, w = routed(cfg, x)
+    bits_np = np.array([16, 4, 2, 8], dtype=np.uint8)
+    host, dev, table, keep = build_layer(cfg, bits_np, path=B.PATH_GEMM)
+    first = run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM)
+    for _ in range(40):
+        assert np.array_equal(run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM), first)
+    assert rel_err_per_token(first, oracle_ffn(cfg, x, idx, w, bits_np, host)) <= FFN_TOL
+
+
 # ------------------------------------------------------------------ the paper's own modes
 
 @pytest.mark.parametrize("low_bits", [2, 0])

@@ -120,7 +120,27 @@ __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, l
     } else {
         store_global_nt(codes + (e0 >> 2), make_uint2(words[0], words[1]));
     }
-    if ((lane & 1) == 0) {
+    // The wavefront's 32 scales and 32 zeros leave as 16-byte non-temporal stores: lane 16 i gathers the scales of
+    // the eight groups held by lanes 16 i .. 16 i + 15, lane 16 i + 1 their zeros (a wavefront whose tail lies past
+    // the end of the matrix has returned above as a whole or holds only whole groups of eight: n_elems is a
+    // multiple of 64, and a wavefront covers 32 groups, so a partial one is handled by the plain stores below).
+    const uint32_t mine = (lane & 1) ? 0u : ((uint32_t)(uint16_t)f16_bits(sh) | ((uint32_t)(uint16_t)f16_bits(zh) << 16));
+    const long wave_e0 = e0 - (long)lane * kQElemsPerLane;
+    if (wave_e0 + (long)kWave * kQElemsPerLane <= n_elems && (((uintptr_t)scale | (uintptr_t)zero) & 15) == 0) {
+        const int base = lane & ~15;
+        uint32_t g[8];
+#pragma unroll
+        for (int i = 0; i < 8; i++) g[i] = (uint32_t)__shfl((int)mine, base + 2 * i, kWave);
+        const int which = lane & 15;                 // 0: scales, 1: zeros of this run of eight groups
+        if (which < 2) {
+            uint32_t h[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) h[i] = which ? (g[i] >> 16) : (g[i] & 0xffffu);
+            const uint4 out = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            uint16_t* dst = (which ? zero : scale) + (wave_e0 >> 6) + (lane >> 4) * 8;
+            store_global_nt(dst, out);
+        }
+    } else if ((lane & 1) == 0) {
         store_global(scale + (e0 >> 6), (uint16_t)f16_bits(sh));
         store_global(zero + (e0 >> 6), (uint16_t)f16_bits(zh));
     }
@@ -231,8 +251,26 @@ __device__ __forceinline__ void quantize_tile(const uint16_t* __restrict__ w, lo
     } else {
         store_global_nt(codes + tile * 1024 + lane * 16, make_uint4(words[0], words[1], words[2], words[3]));
     }
-    store_global(scale + tile * 64 + lane, (uint16_t)f16_bits(sh));
-    store_global(zero + tile * 64 + lane, (uint16_t)f16_bits(zh));
+    // the tile's 64 scales and 64 zeros (128 bytes each) leave as 16-byte non-temporal stores: lane 8 i gathers the
+    // scales of lanes 8 i .. 8 i + 7, lane 8 i + 1 their zeros
+    if ((((uintptr_t)scale | (uintptr_t)zero) & 15) == 0) {
+        const uint32_t mine = (uint32_t)(uint16_t)f16_bits(sh) | ((uint32_t)(uint16_t)f16_bits(zh) << 16);
+        const int base = lane & ~7;
+        uint32_t g[8];
+#pragma unroll
+        for (int i = 0; i < 8; i++) g[i] = (uint32_t)__shfl((int)mine, base + i, kWave);
+        const int which = lane & 7;                  // 0: scales, 1: zeros of this run of eight groups
+        if (which < 2) {
+            uint32_t h[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) h[i] = which ? (g[i] >> 16) : (g[i] & 0xffffu);
+            const uint4 out = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            store_global_nt((which ? zero : scale) + tile * 64 + base, out);
+        }
+    } else {
+        store_global(scale + tile * 64 + lane, (uint16_t)f16_bits(sh));
+        store_global(zero + tile * 64 + lane, (uint16_t)f16_bits(zh));
+    }
 }
 
 // bf16 row-major -> bf16 tiles: thread = (tile, chunk j, lane)

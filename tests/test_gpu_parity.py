@@ -64,6 +64,29 @@ def test_quantize_pack_bit_exact(ctx, bits):
     _check_quant(ctx, synth.f32_to_bf16_bits(w), bits)
 
 
+@pytest.mark.parametrize("bits", [4, 2])
+def test_quantize_pack_into_scale_and_zero_buffers_that_are_only_2_byte_aligned(ctx, bits):
+    """Whole wavefronts write their scales and zeros 16 bytes at a time when the buffers allow it; buffers that
+    start on an odd element take the element-wise stores and must give the same bits."""
+    rng = np.random.default_rng(40 + bits)
+    n, k = 300, 448                                   # 16.4 blocks: whole wavefronts and a partial one
+    w = synth.f32_to_bf16_bits((rng.standard_normal((n, k)) * 0.02).astype(np.float32))
+    rc, rs, rz = O.quantize_pack(w, bits)
+    g = k // 64
+    for off in (0, 1, 3):
+        codes = torch.empty((n, k * bits // 8), dtype=torch.uint8, device=DEV)
+        sbuf = torch.zeros((n * g + 8,), dtype=torch.float16, device=DEV)
+        zbuf = torch.zeros((n * g + 8,), dtype=torch.float16, device=DEV)
+        out = (codes, sbuf[off:off + n * g].view(n, g), zbuf[off:off + n * g].view(n, g))
+        ctx.quantize_pack(to_bf16(w), bits, out=out)
+        sync()
+        assert np.array_equal(codes.cpu().numpy(), rc)
+        assert np.array_equal(bits_of(out[1]), rs) and np.array_equal(bits_of(out[2]), rz)
+        # nothing written outside the views
+        assert (bits_of(sbuf[:off]) == 0).all() and (bits_of(sbuf[off + n * g:]) == 0).all()
+        assert (bits_of(zbuf[:off]) == 0).all() and (bits_of(zbuf[off + n * g:]) == 0).all()
+
+
 def test_quantize_pack_empty_and_deterministic(ctx):
     w = torch.zeros((0, 128), dtype=torch.bfloat16, device=DEV)
     cd, sc, zr = ctx.quantize_pack(w, 4)

@@ -17,7 +17,7 @@ namespace dymoe {
 constexpr int kQThreads = 256;
 constexpr int kQElemsPerLane = 32;
 constexpr int kQElemsPerBlock = kQThreads * kQElemsPerLane;  // 8192 elements = 128 groups
-constexpr int kRowStageLane = 80;                            // bytes between two lanes' pieces of the LDS stage
+constexpr int kRowStageLane = 64;                            // bytes of a lane's 32 weights in the LDS stage
 constexpr int kRowStageBytes = kWave * kRowStageLane;        // per wavefront
 
 __device__ __forceinline__ void unpack8(const uint4 raw, float* v)
@@ -44,8 +44,9 @@ __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, l
     const int lane = threadIdx.x & (kWave - 1);
     const long e0 = block * (long)kQElemsPerBlock + (long)threadIdx.x * kQElemsPerLane;
     // The wavefront's 4 KiB come in with whole-line loads (lane l takes 16 bytes of each of four 1 KiB pieces) and
-    // are turned through the wavefront's LDS stage into 32 consecutive weights per lane; a lane's 64 bytes of the
-    // stage start 80 bytes apart so that the 16-byte reads meet no bank conflict.
+    // are turned through the wavefront's LDS stage into 32 consecutive weights per lane.  Within a lane's 64 bytes
+    // the four 16-byte pieces are stored in the order piece ^ ((lane >> 2) & 3): lanes 4 apart, whose 64 bytes
+    // start in the same banks, then read different quarters, and neither the writes nor the reads conflict.
     uint4 raw[4];
     {
         const long wave0 = e0 - (long)lane * kQElemsPerLane;      // first element of the wavefront
@@ -57,11 +58,13 @@ __device__ __forceinline__ void quantize_block(const uint16_t* __restrict__ w, l
         }
 #pragma unroll
         for (int c = 0; c < 4; c++)
-            *reinterpret_cast<uint4*>(stage + (16 * c + (lane >> 2)) * kRowStageLane + (lane & 3) * 16) = raw[c];
+            *reinterpret_cast<uint4*>(stage + (16 * c + (lane >> 2)) * kRowStageLane +
+                                      (((lane & 3) ^ ((lane >> 4) & 3)) * 16)) = raw[c];   // owner lane 16 c + lane / 4
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");      // the stage is the wavefront's own
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int c = 0; c < 4; c++) raw[c] = *reinterpret_cast<const uint4*>(stage + lane * kRowStageLane + 16 * c);
+        for (int c = 0; c < 4; c++)
+            raw[c] = *reinterpret_cast<const uint4*>(stage + lane * kRowStageLane + ((c ^ ((lane >> 2) & 3)) * 16));
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");      // read before the next block overwrites it
         __builtin_amdgcn_wave_barrier();
     }

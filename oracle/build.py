@@ -17,13 +17,16 @@ FLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-We
 
 
 def build(force: bool = False) -> str:
-    # ORACLE_SANITIZE=undefined: a second library built with gcc's undefined-behaviour sanitizer (traps on the
-    # first finding), which the wrapper then loads instead; the pins run against it in tests/test_oracle_sanitized.py
+    # ORACLE_SANITIZE=undefined | address | address,undefined: a second library built with gcc's sanitizers (stops at
+    # the first finding), which the wrapper then loads instead; the pins run against it in
+    # tests/test_oracle_sanitized.py.  An address-sanitized library needs the sanitizer's runtime loaded first
+    # (LD_PRELOAD of `gcc -print-file-name=libasan.so`); that test arranges it.
     san = os.environ.get("ORACLE_SANITIZE", "")
     lib, flags = LIB, FLAGS
     if san:
-        lib = os.path.join(HERE, "liboracle_%s.so" % san)
-        flags = [f for f in FLAGS if f != "-O2"] + ["-O1", "-g", "-fsanitize=" + san, "-fno-sanitize-recover=" + san]
+        lib = os.path.join(HERE, "liboracle_%s.so" % san.replace(",", "_"))
+        flags = [f for f in FLAGS if f != "-O2"] + ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=" + san,
+                                                     "-fno-sanitize-recover=all"]
     stale = (not os.path.exists(lib)) or os.path.getmtime(lib) < os.path.getmtime(SRC)
     if force or stale:
         tmp = lib + ".tmp.%d" % os.getpid()

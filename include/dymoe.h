@@ -361,6 +361,31 @@ int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t* idx, const
                         void* y, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * dymoe_moe_ffn_mixed for callers that cannot allocate device memory or hand in
+ * a workspace (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc).  Same arguments, results, limits and errors, minus the
+ * workspace: its scratch is a fixed array of DYMOE_STATIC_SCRATCH_BYTES that the
+ * library keeps in each GPU's memory from the moment it is loaded until the
+ * process ends.  The call allocates and frees nothing, on the device or through
+ * any allocating runtime routine, and records no timing events (per-kernel
+ * timing is off for its launches).
+ *  - DYMOE_ENOSPC when dymoe_workspace_bytes(T,H,F,E,k) exceeds
+ *    DYMOE_STATIC_SCRATCH_BYTES (8 MiB: a Mixtral-shaped decode step of up to 16
+ *    tokens takes 5.5 MiB; prefill batches need the workspace form).
+ *  - Every call on a GPU shares that GPU's array: calls that overlap in time on
+ *    one GPU (different streams, different threads) race; calls on one stream do
+ *    not.  Nothing in it has to start at zero (each launch writes what it later
+ *    reads), so the previous call's contents are harmless.
+ *  - The array's address is taken once per device in dymoe_create; the context
+ *    must have been created for the device the call runs on.
+ */
+#define DYMOE_STATIC_SCRATCH_BYTES (8u << 20)
+int dymoe_moe_ffn_mixed_noalloc(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w,
+                                const uint8_t* bits, const dymoe_expert_fmt* table,
+                                int T, int H, int F, int E, int k, int group, int out_dtype, int path,
+                                void* y, void* stream);
+
+/*
  * Host-resident experts (Sec. 4.4.1, Phase-Adaptive Prefetcher): the weights a
  * later layer is predicted to need are copied from pinned host memory into
  * device buffers on a side stream while the compute stream works on the current

@@ -36,7 +36,8 @@ EXPORTS = [
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
     "dymoe_gptq_workspace_bytes", "dymoe_gptq_quantize_pack", "dymoe_gptq_hessian",
     "dymoe_gptq_factor_workspace_bytes", "dymoe_gptq_factor",
-    "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_pack_code_tiles", "dymoe_moe_ffn_mixed", "dymoe_stream_copy",
+    "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_pack_code_tiles", "dymoe_moe_ffn_mixed", "dymoe_moe_ffn_mixed_noalloc",
+    "dymoe_stream_copy",
     "dymoe_decode_front", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
     "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
     "dymoe_cache_create", "dymoe_cache_destroy", "dymoe_cache_request", "dymoe_cache_lookup",
@@ -138,6 +139,9 @@ lib.dymoe_pack_tiles.argtypes = [_vp, _vp, _l, _l, _vp, _vp]
 lib.dymoe_moe_ffn_mixed.restype = _i
 lib.dymoe_moe_ffn_mixed.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i,
                                     _vp, _vp, _sz, _vp]
+STATIC_SCRATCH_BYTES = 8 << 20
+lib.dymoe_moe_ffn_mixed_noalloc.restype = _i
+lib.dymoe_moe_ffn_mixed_noalloc.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _i, _vp, _vp]
 
 
 lib.dymoe_timing_enable.restype = _i

@@ -23,6 +23,9 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restric
         if (i + 256 * u < n16) dst[i + 256 * u] = v[u];
 }
 
+int ffn_static_scratch_address(void** out);
+int ffn_gemm_init();
+
 }  // namespace dymoe
 
 extern "C" {
@@ -55,6 +58,21 @@ int dymoe_create(dymoe_ctx** out, int device)
     c->device = device;
     c->num_cu = prop.multiProcessorCount;
     c->timing_mask = 0;
+    c->static_scratch = nullptr;
+    // per-device set-up, with that device current: the address of its copy of the static scratch array, and the
+    // dynamic-LDS limit of the grouped-GEMM kernels (so that no later call has anything left to configure)
+    int prev = 0;
+    int rc = DYMOE_OK;
+    if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(device) != hipSuccess) rc = DYMOE_EHIP;
+    if (rc == DYMOE_OK) {
+        rc = dymoe::ffn_static_scratch_address(&c->static_scratch);
+        if (rc == DYMOE_OK) rc = dymoe::ffn_gemm_init();
+        if (hipSetDevice(prev) != hipSuccess) rc = DYMOE_EHIP;
+    }
+    if (rc != DYMOE_OK) {
+        delete c;
+        return rc;
+    }
     *out = c;
     return DYMOE_OK;
 }

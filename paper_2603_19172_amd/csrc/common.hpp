@@ -42,6 +42,7 @@ struct dymoe_timed_launch {
 struct dymoe_ctx {
     int device;
     int num_cu;
+    void* static_scratch;                    // device address of this GPU's scratch array (dymoe_moe_ffn_mixed_noalloc)
     unsigned timing_mask;                    // bit i set: time launches of kernel i
     std::vector<dymoe_timed_launch> timed;   // recorded, not yet read
 };

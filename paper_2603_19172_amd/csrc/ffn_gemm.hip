@@ -873,14 +873,36 @@ __global__ __launch_bounds__(256) void gemm_combine_kernel(
     }
 }
 
+constexpr size_t kGemmLdsBytes = 2 * (size_t)kXsBufBytes;     // two token-tile buffers
+
+// Once per device, at context creation, with that device current: the kernels use more dynamic LDS than the default limit.
+int ffn_gemm_init()
+{
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<1>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes) != hipSuccess)
+        return DYMOE_EHIP;
+    return DYMOE_OK;
+}
+
+// Limits of the launch shapes below, checked by the entry point before anything is enqueued: the tile index is a
+// grid's y dimension, and the token-tile copies address a row through an unsigned 32-bit byte offset.
+bool ffn_gemm_fits(int T, int H, int F, int E, int k)
+{
+    const size_t P = (size_t)T * (size_t)k;
+    if (P / kGemmTileM + (size_t)E > 65535) return false;
+    if ((size_t)T * H * 2 >= ((size_t)1 << 32) || P * (size_t)F * 2 >= ((size_t)1 << 32)) return false;
+    return true;
+}
+
 int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w, const uint8_t* bits,
                     const dymoe_expert_fmt* table, int T, int H, int F, int E, int k,
                     int out_dtype, void* y, void* workspace, hipStream_t st)
 {
     const FfnLayout L = ffn_layout(T, H, F, E, k);
     const int P = T * k;
-    // the token-tile copies address a row through an unsigned 32-bit byte offset
-    if ((size_t)T * H * 2 >= ((size_t)1 << 32) || (size_t)P * F * 2 >= ((size_t)1 << 32)) return DYMOE_ENOTSUP;
+    if (!ffn_gemm_fits(T, H, F, E, k)) return DYMOE_ENOTSUP;
     char* ws = (char*)workspace;
     uint16_t* hbuf = reinterpret_cast<uint16_t*>(ws + L.hbuf);   // [P,F] 16-bit
     uint16_t* xh4 = reinterpret_cast<uint16_t*>(ws + L.xh);      // [T,H] fp16, int4 column order
@@ -895,17 +917,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const long n16 = (long)T * H / 16;
     hipLaunchKernelGGL(prep_x_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, xb, n16, xh4, xh2, xh8);
     DYMOE_HIP_LAUNCH_CHECK();
-    // two token-tile buffers in LDS
-    constexpr size_t kLdsBytes = 2 * (size_t)kXsBufBytes;
-    static bool lds_attr_set = false;
-    if (!lds_attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes) != hipSuccess)
-            return DYMOE_EHIP;
-        lds_attr_set = true;
-    }
+    constexpr size_t kLdsBytes = kGemmLdsBytes;
     const int max_tiles = P / kGemmTileM + E;
     const int cols1 = 32 * kGmWaves, cols2 = 64 * kGmWaves;
     const dim3 g1((unsigned)((F + cols1 - 1) / cols1), (unsigned)max_tiles);

@@ -176,6 +176,17 @@ def test_argument_validation_happens_before_any_device_work():
     ws2 = B.workspace_bytes(16, 192, 512, 8, 2)
     assert ffn(None, P, P, P, P, P, 16, 192, 512, 8, 2, 64, 0, 2, P, P, ws2, None) == B.ENOTSUP
     assert ffn(None, P, P, P, P, P, 16, 192, 512, 8, 2, 64, 0, 0, P, P, ws2, None) == B.ENOCTX
+    # more tiles than a grid's y dimension holds: refused before anything is launched (H = F = 128, 2 M tokens x 4)
+    big = B.workspace_bytes(1 << 21, 128, 128, 8, 4)
+    assert ffn(None, P, P, P, P, P, 1 << 21, 128, 128, 8, 4, 64, 0, 2, P, P, big, None) == B.ENOTSUP
+    # the form with the static scratch: same checks, and a fixed capacity instead of a workspace size
+    ffn_na = lib.dymoe_moe_ffn_mixed_noalloc
+    assert ffn_na(None, P, P, P, P, P, 16, 256, 512, 8, 2, 64, 0, 0, P, None) == B.ENOCTX
+    assert ffn_na(None, P, P, P, P, P, 16, 256, 512, 8, 2, 64, 5, 0, P, None) == B.EINVAL
+    assert ffn_na(None, P, P, P, None, P, 16, 256, 512, 8, 2, 64, 0, 0, P, None) == B.EINVAL
+    assert B.workspace_bytes(16, 4096, 14336, 8, 2) <= B.STATIC_SCRATCH_BYTES < B.workspace_bytes(512, 4096, 14336, 8, 2)
+    assert ffn_na(None, P, P, P, P, P, 16, 4096, 14336, 8, 2, 64, 0, 0, P, None) == B.ENOCTX
+    assert ffn_na(None, P, P, P, P, P, 512, 4096, 14336, 8, 2, 64, 0, 0, P, None) == B.ENOSPC
 
 
 def test_create_without_gpu_reports_error():

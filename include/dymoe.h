@@ -361,6 +361,17 @@ int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t* idx, const
                         void* y, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Diagnostic (tests, profiling): where the grouped-GEMM path of dymoe_moe_ffn_mixed leaves its token
+ * grouping in the workspace, so that a caller can see which (token, slot) pair went to which row of which
+ * tile (paper Sec. 4.2.1: the per-expert token lists Tokens_j).  Returns the byte offset of an int32 array
+ * laid out as counts[E] | offsets[E+1] | (E ints, unused) | ntiles, pairs (+6 unused) | perm[T*k]:
+ * counts[e] = pairs routed to expert e at a non-zero precision, offsets = their exclusive prefix sums,
+ * perm[offsets[e] + i] = the i-th pair (token * k + slot) of expert e, in the order the GEMM's tiles take
+ * them (rows [128 j, 128 j + 128) of an expert form its j-th tile).  Pure host function; 0 for invalid sizes.
+ */
+size_t dymoe_ffn_plan_offset(int T, int H, int F, int E, int k);
+
+/*
  * dymoe_moe_ffn_mixed for callers that cannot allocate device memory or hand in
  * a workspace (code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc).  Same arguments, results, limits and errors, minus the

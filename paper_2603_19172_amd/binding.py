@@ -30,7 +30,7 @@ LAYOUT_ROWMAJOR, LAYOUT_TILE = 0, 1
 
 # every symbol include/dymoe.h declares
 EXPORTS = [
-    "dymoe_create", "dymoe_destroy", "dymoe_strerror", "dymoe_workspace_bytes",
+    "dymoe_create", "dymoe_destroy", "dymoe_strerror", "dymoe_workspace_bytes", "dymoe_ffn_plan_offset",
     "dymoe_route_topk", "dymoe_token_score_norm", "dymoe_attention_workspace_bytes",
     "dymoe_token_score_attention", "dymoe_expert_importance",
     "dymoe_depth_schedule", "dymoe_assign_precision", "dymoe_quantize_pack",
@@ -89,6 +89,8 @@ lib.dymoe_strerror.restype = C.c_char_p
 lib.dymoe_strerror.argtypes = [_i]
 lib.dymoe_workspace_bytes.restype = _sz
 lib.dymoe_workspace_bytes.argtypes = [_i] * 5
+lib.dymoe_ffn_plan_offset.restype = _sz
+lib.dymoe_ffn_plan_offset.argtypes = [_i] * 5
 lib.dymoe_decode_front.restype = _i
 lib.dymoe_decode_front.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _i,
                                    _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
@@ -188,6 +190,15 @@ def _stream(stream):
 
 def workspace_bytes(T, H, F, E, k) -> int:
     return int(lib.dymoe_workspace_bytes(T, H, F, E, k))
+
+
+def read_ffn_plan(ws, T, H, F, E, k):
+    """The token grouping a GEMM-path call left in workspace `ws` (uint8 tensor): (counts [E], offsets [E+1],
+    perm [T*k]) as host int32 arrays; perm[offsets[e] + i] is the i-th (token * k + slot) pair of expert e."""
+    off = int(lib.dymoe_ffn_plan_offset(T, H, F, E, k))
+    n = 3 * E + 1 + 8 + T * k
+    ints = ws[off:off + 4 * n].view(torch.int32).cpu().numpy()
+    return ints[:E].copy(), ints[E:2 * E + 1].copy(), ints[3 * E + 9:3 * E + 9 + T * k].copy()
 
 
 def depth_schedule(layer, n_layers, lam, M) -> int:

@@ -175,6 +175,12 @@ size_t dymoe_workspace_bytes(int T, int H, int F, int E, int k)
     return dymoe::ffn_layout(T, H, F, E, k).total;
 }
 
+size_t dymoe_ffn_plan_offset(int T, int H, int F, int E, int k)
+{
+    if (T < 0 || H <= 0 || F <= 0 || E <= 0 || k <= 0 || k > E) return 0;
+    return dymoe::ffn_layout(T, H, F, E, k).plan;
+}
+
 // Paper Sec. 4.3: cosine retention ratio, then the ceiling.  The product is
 // lowered by 1e-9 before the ceiling so that an exactly integral r(l)*M that
 // evaluates one ulp high (cos(pi/3) = 0.5000000000000001) is not rounded up.

@@ -774,33 +774,52 @@ __global__ __launch_bounds__(kGmThreads, 2) void gemm_kernel(
     const uint16_t* __restrict__ hbuf_in,
     const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table,
     const int32_t* __restrict__ plan, int P, int E, int k_route, int H, int F,
-    uint16_t* __restrict__ hbuf_out, float* __restrict__ opair)
+    uint16_t* __restrict__ hbuf_out, float* __restrict__ opair, int max_tiles, int splits)
 {
     // two token-tile buffers; the swizzle and the buffer toggle work on address bits
     extern __shared__ __attribute__((aligned(65536))) uint16_t xs_raw[];
     const uint32_t xs = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)xs_raw;
     const PlanPtrs pp = plan_ptrs(const_cast<int32_t*>(plan), E, P);
-    const int tile = blockIdx.y;
+    const int K = (MODE == 1) ? H : F;
+    const int N = (MODE == 1) ? F : H;
+    // Which (column block, tile, K split) this workgroup takes.  The first GEMM's grid is (column block, tile).  The
+    // second GEMM's launch is one-dimensional: workgroups go to the 8 XCDs (each with an L2 of its own) in turn by
+    // launch index, and the column blocks of a unit (one tile's rows over one K split) all read the same rows of the
+    // intermediate, so a unit is kept on one XCD: launch index L -> XCD L % 8, place j = L / 8 in that XCD's sequence,
+    // unit (j / nblk) * 8 + L % 8, column block j % nblk.  Units are numbered tile-major (all K splits of the longest
+    // tile first), so the longest-first order of the tile list survives.
+    int tile, bx, bz;
+    if (MODE == 2) {
+        const int nblk = (N + 64 * kGmWaves - 1) / (64 * kGmWaves);
+        const int L = blockIdx.x, j = L >> 3;
+        const int unit = (j / nblk) * 8 + (L & 7);
+        bx = j % nblk;
+        tile = unit / splits;
+        bz = unit - tile * splits;
+        if (tile >= max_tiles) return;
+    } else {
+        tile = blockIdx.y;
+        bx = blockIdx.x;
+        bz = 0;
+    }
     if (tile >= pp.ntiles[0]) return;
     const int e = pp.tiles[4 * tile + 0];
     const int row0 = pp.tiles[4 * tile + 1];
     const int rows = pp.tiles[4 * tile + 2];
     const int b = bits[e];
     const dymoe_expert_fmt ex = table[e];
-    const int K = (MODE == 1) ? H : F;
-    const int N = (MODE == 1) ? F : H;
-    // split-K (MODE 2 only): blockIdx.z takes K-tiles [z*per, (z+1)*per) and its own output slab
+    // split-K (second GEMM only): split bz takes K-tiles [bz*per, (bz+1)*per) and its own output slab
     const int nkt = K / kBK;
-    const int per = (nkt + (int)gridDim.z - 1) / (int)gridDim.z;
-    const int kt_begin = (int)blockIdx.z * per;
+    const int per = (nkt + splits - 1) / splits;
+    const int kt_begin = bz * per;
     const int kt_end = min(nkt, kt_begin + per);
-    float* oz = opair + (size_t)blockIdx.z * (size_t)P * (size_t)N;
+    float* oz = opair + (size_t)bz * (size_t)P * (size_t)N;
     if (kt_begin >= kt_end) {
         // a split with no K-tiles still owns its slab: write zeros
         if (MODE == 2) {
             const int cols = 64 * kGmWaves;     // columns of this workgroup
             for (int i = threadIdx.x; i < rows * (cols / 4); i += kGmThreads) {
-                const int r = i / (cols / 4), c = blockIdx.x * cols + (i % (cols / 4)) * 4;
+                const int r = i / (cols / 4), c = bx * cols + (i % (cols / 4)) * 4;
                 if (c < N)
                     *reinterpret_cast<float4*>(oz + (size_t)pp.perm[row0 + r] * N + c) = make_float4(0.f, 0.f, 0.f, 0.f);
             }
@@ -813,7 +832,7 @@ __global__ __launch_bounds__(kGmThreads, 2) void gemm_kernel(
     // accumulators then sit in fixed registers for the whole K loop
 #define DYMOE_TILE(BITS_, NTF_)                                                                      \
     gemm_tile<MODE, BITS_, NTF_>(act, pp.perm, k_route, ex, K, N, kt_begin, kt_end, row0, rows,      \
-                                 blockIdx.x, hbuf_out, oz, xs)
+                                 bx, hbuf_out, oz, xs)
 #define DYMOE_TILE_NTF(BITS_)                     \
     switch (ntf) {                                \
     case 1: DYMOE_TILE(BITS_, 1); break;          \
@@ -922,21 +941,25 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const int cols1 = 32 * kGmWaves, cols2 = 64 * kGmWaves;
     const dim3 g1((unsigned)((F + cols1 - 1) / cols1), (unsigned)max_tiles);
     dymoe_launch(ctx, DYMOE_K_GEMM1, (gemm_kernel<1>), g1, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2, xh8,
-                 (const uint16_t*)nullptr, bits, table, plan, P, E, k, H, F, hbuf, (float*)nullptr);
+                 (const uint16_t*)nullptr, bits, table, plan, P, E, k, H, F, hbuf, (float*)nullptr, max_tiles, 1);
     DYMOE_HIP_LAUNCH_CHECK();
-    // The down projection has few output tiles: split K so that the launch
-    // still covers the chip.  Each split writes its own slab of per-pair
-    // outputs; the combine kernel adds the slabs in a fixed order.
+    // The down projection has few output tiles: split K so that the launch still covers the chip (two workgroups per
+    // compute unit, about one and a half rounds of them; measured on the Mixtral prefill: 2 to 7 splits lie within
+    // 7 % of each other, 4 is best).  Each split writes its own slab of per-pair outputs and the combine kernel adds
+    // the slabs in a fixed order, so every extra split also costs a slab of traffic each way.  The number of tiles is
+    // only known on the device; from the sizes: every expert with tokens has one, and P / 128 more at most.
     const int nblk2 = (H + cols2 - 1) / cols2;
-    const long est_blocks = (long)nblk2 * ((long)P / kGemmTileM + (E < P ? E : P) / 2 + 1);
-    int splits = (int)((4L * ctx->num_cu + est_blocks - 1) / est_blocks);
+    const long est_tiles = (E < P ? E : P) + (long)P / (2 * kGemmTileM);
+    const long est_blocks = (long)nblk2 * est_tiles;
+    int splits = (int)(3L * ctx->num_cu / est_blocks);
     const int max_splits = (F + kSeg - 1) / kSeg;     // slabs the workspace holds
     if (splits > max_splits) splits = max_splits;
     if (splits > 8) splits = 8;
     if (splits < 1) splits = 1;
-    const dim3 g2((unsigned)nblk2, (unsigned)max_tiles, (unsigned)splits);
+    const int units = max_tiles * splits;
+    const dim3 g2((unsigned)(8 * nblk2 * ((units + 7) / 8)));
     dymoe_launch(ctx, DYMOE_K_GEMM2, (gemm_kernel<2>), g2, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2, xh8, hbuf,
-                 bits, table, plan, P, E, k, H, F, (uint16_t*)nullptr, opair);
+                 bits, table, plan, P, E, k, H, F, (uint16_t*)nullptr, opair, max_tiles, splits);
     DYMOE_HIP_LAUNCH_CHECK();
     const long n4 = (long)T * (H / 4);
     dymoe_launch(ctx, DYMOE_K_GEMM_COMBINE, gemm_combine_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, opair,

@@ -162,30 +162,61 @@ def _prefill_case(ctx, cfg, n_sample, seed):
             cd, sc, zr = store.q[b][e][i]
             got = rowmajor_from_tiles(cd.cpu().numpy(), bits_of(sc), bits_of(zr), b)
             assert np.array_equal(got[0], rc) and np.array_equal(got[1], rs) and np.array_equal(got[2], rz)
-    # FFN on a seeded sample of token rows (heavy hitters included)
+    # FFN against the oracle on a sample of token rows: seeded picks, two heavy hitters, and, for every expert with
+    # more tokens than one 128-row tile holds, two tokens from beyond its 128th row (the token order inside an expert
+    # comes out of the grouping kernel, so it is read back from the workspace)
+    counts, offsets, perm = B.read_ffn_plan(layer.ws, cfg.T, cfg.H, cfg.F, cfg.E, cfg.k)
+    assert np.array_equal(counts, rload) and offsets[-1] == cfg.T * cfg.k
+    assert sorted(perm.tolist()) == list(range(cfg.T * cfg.k))           # every pair is in exactly one tile row
+    for e in range(cfg.E):
+        assert (gidx.ravel()[perm[offsets[e]:offsets[e + 1]]] == e).all()
     rng = np.random.default_rng(seed)
-    sample = rng.choice(cfg.T, n_sample, replace=False)
+    sample = list(rng.choice(cfg.T, n_sample, replace=False))
     if heavy.size:
         sample[:2] = heavy[:2]
-    sample = np.unique(sample)
+    beyond = 0
+    for e in np.argsort(-counts)[:8]:
+        if counts[e] > 128:
+            late = perm[offsets[e] + 128:offsets[e + 1]]
+            picks = late[[0, len(late) - 1]] // cfg.k
+            sample.extend(int(t) for t in picks)
+            beyond += 2
+    sample = np.unique(np.array(sample))
     gw = layer.gate.cpu().numpy().astype(np.float64)
     need_s = set(int(e) for e in gidx[sample].ravel())
     experts = _oracle_experts(cfg, host_w, rbits, need_s)
     ref = O.moe_ffn_mixed(x[sample], gidx[sample], gw[sample], _masked_bits(cfg, rbits, need_s), experts)
     got = y.cpu().numpy().astype(np.float64)[sample]
     err = rel_err_per_token(got, ref)
-    print("%s: FFN err over %d sampled rows = %.3e" % (cfg.name, len(sample), err))
-    assert err <= FFN_TOL
-    # every row was written with finite values
+    print("%s: FFN err over %d sampled rows (%d of them beyond an expert's 128th row) = %.3e"
+          % (cfg.name, len(sample), beyond, err))
+    assert len(sample) >= 32 and err <= FFN_TOL
+    # every row: the grouped GEMM against the GEMV path of the same library on the same inputs (row-major codes of
+    # the same weights, fp32 accumulation of exact products; itself within 3e-4 of the oracle on the decode tests)
+    store_rm = ExpertStore(store.w, cfg.H, cfg.F, DEV)
+    st = B._stream(None)
+    B._check(B.lib.dymoe_quantize_experts(ctx._h, store_rm.table.data_ptr(), layer.bits.data_ptr(),
+                                          layer.load.data_ptr(), cfg.E, cfg.H, cfg.F, 64, B.LAYOUT_ROWMAJOR, st),
+             "dymoe_quantize_experts")
+    y2 = torch.empty_like(y)
+    xd = to_bf16(x)
+    B._check(B.lib.dymoe_moe_ffn_mixed(ctx._h, xd.data_ptr(), layer.idx.data_ptr(), layer.gate.data_ptr(),
+                                       layer.bits.data_ptr(), store_rm.table.data_ptr(), cfg.T, cfg.H, cfg.F, cfg.E,
+                                       cfg.k, 64, B.OUT_F32, B.PATH_GEMV, y2.data_ptr(), layer.ws.data_ptr(),
+                                       layer.ws_bytes, st), "dymoe_moe_ffn_mixed")
+    torch.cuda.synchronize()
+    both = rel_err_per_token(y.cpu().numpy().astype(np.float64), y2.cpu().numpy().astype(np.float64))
+    print("%s: grouped GEMM against the GEMV path, all %d rows: %.3e" % (cfg.name, cfg.T, both))
+    assert both <= FFN_TOL
     assert torch.isfinite(y).all()
 
 
 def test_mixtral_prefill_full(ctx):
-    _prefill_case(ctx, synth.CONFIGS["mixtral_prefill"], n_sample=8, seed=1)
+    _prefill_case(ctx, synth.CONFIGS["mixtral_prefill"], n_sample=32, seed=1)
 
 
 def test_fine_grained_prefill_full(ctx):
-    _prefill_case(ctx, synth.CONFIGS["fine_grained"], n_sample=8, seed=2)
+    _prefill_case(ctx, synth.CONFIGS["fine_grained"], n_sample=32, seed=2)
 
 
 @pytest.mark.parametrize("T", [1, 4])
@@ -214,8 +245,9 @@ def test_fine_grained_decode_full(ctx, T):
     torch.cuda.synchronize()
     assert np.array_equal(layer.idx.cpu().numpy(), ridx)
     assert np.array_equal(layer.load.cpu().numpy(), rload)
-    got_bits = layer.bits.cpu().numpy()
-    assert np.array_equal(got_bits[sorted(need)], rbits[sorted(need)])
+    # every expert's bit width, selected or not: only the two tier boundaries (ranks 1|2 and 4|5) decide a width, and
+    # their importance gaps were just checked to be far above fp32 noise
+    assert np.array_equal(layer.bits.cpu().numpy(), rbits)
     assert sorted(set(int(rbits[e]) for e in need)) in ([2, 4, 16], [4, 16], [2, 16], [2, 4])
     ref = O.moe_ffn_mixed(x, ridx, rw, _masked_bits(cfg, rbits, need), _oracle_experts(cfg, host_w, rbits, need))
     err = rel_err_per_token(y.cpu().numpy().astype(np.float64), ref)

@@ -6,11 +6,16 @@ A step is one pass of the whole hot path over one batch: router gating + top-k
 the assignment sends to int4 / int2 -> dequant-fused SwiGLU expert FFN.
 
 Headline (`value`): tokens/s of that full step on the Mixtral-8x7B-shaped decode
-layer (batch 1).  The same JSON line also carries the FFN alone with the
-selected formats already resident, the 512-token prefill of the same layer, the
-roofline of the dominant kernel (timed with HIP events attached to its
-dispatches by the library's per-kernel timers, over the same steps launched
-eagerly right after the timed region) and the CPU oracle timed on this host.
+layer (batch 1, BASELINE configs[1]).  The same JSON line also carries, each under
+its own key: the FFN alone with the selected formats already resident and the two
+active experts forced to each pair of formats; the 512-token prefill of the same
+layer (configs[2]); the fine-grained 128-expert layer (configs[3]); the 32-layer
+decode stack with the experts in pinned host memory, 64 steps (configs[4]); the
+roofline of the dominant kernel of the timed step and of the two paths the targets
+are stated on (timed with HIP events attached to the dispatches by the library's
+per-kernel timers, over the same steps launched eagerly right after the timed
+region); the matrix rate and copy rate this machine sustains; and the CPU oracle
+timed on this host for the decode step and for a sample of the prefill.
 
   python bench.py --gpus 1 --steps 200 --warmup 20
 """
@@ -41,21 +46,26 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--skip-prefill", action="store_true")
-    ap.add_argument("--stack-steps", type=int, default=0,
-                    help="also decode this many steps through a 32-layer stack with the experts in pinned host "
-                         "memory (BASELINE configs[4]); off by default: the run is bound by the host link")
+    ap.add_argument("--stack-steps", type=int, default=64,
+                    help="decode steps through the 32-layer stack with the experts in pinned host memory "
+                         "(BASELINE configs[4] names 64); 0 skips the stack")
+    ap.add_argument("--stack-plans", default="literal,budget,paper",
+                    help="which plans of the host-resident stack to run, each with look-ahead off and on: literal (bf16 "
+                         "travels and is quantised on arrival, as configs[4] words it), pools (the assigned format "
+                         "travels, fixed pools per format), budget (the assigned format, one byte budget), paper "
+                         "(4/2 tiers with the cosine depth schedule, one byte budget), paper-pools")
     ap.add_argument("--stack-warmup", type=int, default=1,
                     help="untimed steps of the stack before the timed ones, cycling through the same inputs (as many as "
                          "--stack-steps with a large budget: every expert the timed steps need is then resident)")
     ap.add_argument("--stack-budget-gb", type=float, default=24.0,
                     help="device bytes set aside for expert slots in the stack run")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--format-sweep", action="store_true",
-                    help="also time the decode FFN kernels with the two active experts forced to bf16, int8, int4, "
-                         "int4+int2 and int2 (off by default: its extra launches would blur the per-kernel averages of a "
-                         "profiler run over the default workload)")
-    ap.add_argument("--fine-grained", action="store_true",
-                    help="also time the fine-grained layer (BASELINE configs[3]: 2048 tokens, 128 experts, top-8)")
+    ap.add_argument("--no-format-sweep", action="store_true",
+                    help="skip the pass that times the decode FFN kernels with the two active experts forced to bf16, "
+                         "int8, int4, int4+int2 and int2 (for a profiler run over the default workload: its extra "
+                         "launches would blur the per-kernel averages)")
+    ap.add_argument("--skip-fine-grained", action="store_true",
+                    help="skip the fine-grained layer (BASELINE configs[3]: 2048 tokens, 128 experts, top-8)")
     ap.add_argument("--attention-long", action="store_true",
                     help="also time the attention-derived token score at 2048 and 8192 tokens (32 query / 8 key heads of "
                          "128), causal and not: the sizes its LDS-staged kernels serve")
@@ -68,6 +78,8 @@ def main():
                          "(1 GiB read in 32-byte pieces, 1 GiB written), a second reference for a profiler's "
                          "byte counters beside the plain stream copy that every run makes")
     args = ap.parse_args()
+    args.format_sweep = not args.no_format_sweep
+    args.fine_grained = not args.skip_fine_grained
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
@@ -115,6 +127,18 @@ def main():
     ms, n = ctx.timing_read("stream_copy")
     ctx.timing_enable([])
     copy_gbps = 2.0 * src.numel() * n / (ms * 1e-3) / 1e9
+    # register-only bf16 MFMA loop: the matrix rate this machine sustains (about 50 ms of it, so that the clock
+    # settles where it stays under that load), one and two wavefronts per SIMD
+    sink = torch.empty((1 << 18,), dtype=torch.float32, device=dev)
+    mfma_rate = {}
+    for wps in (1, 2):
+        ctx.mfma_peak(2000, wps, sink)
+        ctx.timing_enable(["mfma_peak"])
+        fl = sum(ctx.mfma_peak(20000, wps, sink) for _ in range(6))
+        ms, n = ctx.timing_read("mfma_peak")
+        ctx.timing_enable([])
+        mfma_rate[wps] = fl / (ms * 1e-3) / 1e12
+    mfma_measured = max(mfma_rate.values())
     if args.calibrate_copy:
         src2 = src.view(torch.bfloat16).view(32768, 16384)
         for _ in range(3):
@@ -204,15 +228,31 @@ def main():
     # HBM bytes per launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by the
     # same counters' reading for a copy kernel of known size); written down from the
     # profiling runs documented under profiles/, null when no such file is there
-    traffic = None
+    traffic_all = {}
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get("mixtral_decode", {}).get(kname)
+            traffic_all = json.load(f)
+    traffic = traffic_all.get("mixtral_decode", {}).get(kname)
+    # the longest kernel of the timed step (the quantiser: it reads bf16 and writes codes, so it says nothing
+    # about running on packed weights; that is `roofline_decode_packed` below)
     roofline = {"kernel": kname,
                 "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "algorithmic_bytes_per_launch": alg_bytes[dominant], "avg_launch_us": round(dom_us, 2)}
+                "algorithmic_bytes_per_launch": alg_bytes[dominant], "avg_launch_us": round(dom_us, 2),
+                "note": "dominant kernel of the timed step by duration"}
+    # decode on packed weights: the two dequant GEMV launches together
+    gemv_us = kt["gemv_phase1"][0] + kt["gemv_phase2"][0]
+    gemv_bytes = alg_bytes["gemv_phase1"] + alg_bytes["gemv_phase2"]
+    gemv_gbs = gemv_bytes / (gemv_us * 1e-6) / 1e9 if gemv_us > 0 else 0.0
+    gemv_traffic = [traffic_all.get("mixtral_decode", {}).get(n_) for n_ in ("gemv_phase1_kernel", "gemv_phase2_kernel")]
+    roofline_decode = {"kernels": ["gemv_phase1_kernel", "gemv_phase2_kernel"], "bound": "hbm",
+                       "achieved": round(gemv_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": round(gemv_gbs / HBM_PEAK_GBS, 4),
+                       "traffic": sum(gemv_traffic) if all(v is not None for v in gemv_traffic) else None,
+                       "algorithmic_bytes_per_step": gemv_bytes, "sum_of_launch_us": round(gemv_us, 2),
+                       "note": "S5 on packed weights (bf16 + int4 expert), kernel time only; the step-level figure, "
+                               "gaps and front end included, is decode_ffn_only.frac_hbm"}
     kernels_report = {}
     for name in kernels:
         entry = {"avg_us": round(kt[name][0], 2), "launches": kt[name][1]}
@@ -260,6 +300,13 @@ def main():
                    "active_experts": active, "active_bits": active_bits, "launch": launch_mode,
                    "weight_copies_rotated": LAYER_COPIES, "setup_s": round(setup_s, 1)},
         "roofline": roofline,
+        "roofline_decode_packed": roofline_decode,
+        "machine": {"stream_copy_GBps": round(copy_gbps, 1),
+                    "mfma_bf16_TFLOPs_register_loop": {"one_wave_per_simd": round(mfma_rate[1], 1),
+                                                       "two_waves_per_simd": round(mfma_rate[2], 1)},
+                    "note": "what this GPU sustains on the library's two measurement aids (dymoe_stream_copy: 1 GiB read + "
+                            "1 GiB written; dymoe_mfma_peak: v_mfma_f32_32x32x16_bf16 on registers only): the practical "
+                            "ceilings beside the data sheet's 8 TB/s and 2.5 PFLOP/s that every fraction here is priced against"},
         "hot_path_hbm": {"algorithmic_bytes_per_step": sum(alg_bytes.values()),
                          "GBps": round(sum(alg_bytes.values()) / (ms_per_step * 1e-3) / 1e9, 1),
                          "frac_hbm": round(sum(alg_bytes.values()) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -268,7 +315,7 @@ def main():
                                  "bytes; stream_copy_GBps is a plain 1 GiB copy (read + write bytes) on this GPU"},
         "kernels": kernels_report,
         "decode_ffn_format_sweep": {"note": "S5 kernels alone (sum of their execution times, eager launches, 4 rotating weight "
-                                            "copies), the two active experts forced to the named bit-widths; --format-sweep",
+                                            "copies), the two active experts forced to the named bit-widths",
                                     "pairs": sweep} if args.format_sweep else None,
         "decode_ffn_only": {"tokens_per_s": round(cfg.T * args.steps / sec_ffn, 1),
                             "us_per_step": round(sec_ffn / args.steps * 1e6, 2),
@@ -312,8 +359,50 @@ def main():
             "grouped_gemm_us": round(g_us, 1),
             "grouped_gemm_TFLOPs": round(flops / (g_us * 1e-6) / 1e12, 1) if g_us > 0 else None,
             "grouped_gemm_frac_mfma_bf16_peak": round(flops / (g_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4) if g_us > 0 else None,
+            "grouped_gemm_frac_of_measured_mfma_rate": round(flops / (g_us * 1e-6) / 1e12 / mfma_measured, 4) if g_us > 0 else None,
             "kernels_us": {n: round(v[0] / max(v[1], 1) * 1e3, 1) for n, v in pk.items()},
         }
+        gt = traffic_all.get("mixtral_prefill", {})
+        out["roofline_prefill_gemm"] = {
+            "kernels": ["gemm_kernel<1>", "gemm_kernel<2>"], "bound": "mfma",
+            "achieved": round(flops / (g_us * 1e-6) / 1e12, 1) if g_us > 0 else None, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(flops / (g_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4) if g_us > 0 else None,
+            "traffic": (gt.get("gemm_kernel<1>", 0) + gt.get("gemm_kernel<2>", 0)) or None,
+            "algorithmic_flops_per_step": flops, "algorithmic_weight_bytes_per_step": wbytes,
+            "sum_of_launch_us": round(g_us, 1),
+            "note": "2*3*H*F flops per (token, expert) pair over the two GEMM launches of one 512-token step"}
+        # the oracle on a seeded sample of the same step: routing, importance and assignment in full, the FFN on
+        # a few token rows; its time per (token, expert) pair extrapolated to the 1024 pairs of the step
+        if not args.skip_cpu:
+            from oracle import dymoe_oracle as O
+            t0 = time.perf_counter()
+            ridx, rw, rp, _ = O.route_topk(px_np, pwg_np, None, k)
+            rimp, rload, _ = O.expert_importance_prefill(ridx, O.token_score_norm(px_np), E, pcfg.k_hh)
+            rbits, _ = O.assign_precision(rimp, rload, pcfg.tier_count, pcfg.tier_bits)
+            t_front = time.perf_counter() - t0
+            rows = np.random.default_rng(5).choice(pcfg.T, 4, replace=False)
+            need = sorted(set(int(e) for e in ridx[rows].ravel()))
+            t0 = time.perf_counter()
+            ex = [({"w": host_w[e]} if rbits[e] == 16 else {"q": [O.quantize_pack(m, int(rbits[e])) for m in host_w[e]]})
+                  if e in need else {} for e in range(E)]
+            t_quant = time.perf_counter() - t0
+            mb = np.array([rbits[e] if e in need else 0 for e in range(E)], np.uint8)
+            t0 = time.perf_counter()
+            pref = O.moe_ffn_mixed(px_np[rows], ridx[rows], rw[rows], mb, ex)
+            t_ffn = time.perf_counter() - t0
+            n_q = sum(1 for e in need if rbits[e] != 16)
+            n_q_all = int(sum(1 for e in range(E) if rload[e] > 0 and rbits[e] != 16))
+            est = t_front + t_quant / max(n_q, 1) * n_q_all + t_ffn / (len(rows) * k) * (pcfg.T * k)
+            got = play.y.float().cpu().numpy().astype(np.float64)[rows]
+            prms = np.sqrt((pref ** 2).mean(axis=1, keepdims=True))
+            out["prefill_512"]["cpu_baseline"] = {
+                "value": round(pcfg.T / est, 4), "unit": "tokens/s", "cores": 1, "kind": "oracle", "extrapolated": True,
+                "sample": "route + importance + assignment of all 512 tokens (%.2f s), quantize-pack of %d of the %d "
+                          "quantised experts (%.1f s), FFN of %d token rows = %d (token, expert) pairs (%.1f s); the step's "
+                          "time is extrapolated from these: quantize-pack per expert x %d, FFN per pair x %d"
+                          % (t_front, n_q, n_q_all, t_quant, len(rows), len(rows) * k, t_ffn, n_q_all, pcfg.T * k),
+                "seconds_per_step_extrapolated": round(est, 1),
+                "ffn_max_err_over_rms_on_the_sample_bf16_out": round(float((np.abs(got - pref) / prms).max()), 5)}
         # the attention-derived token score of the same 512 tokens (32 query heads, 8 key heads of 128)
         a_heads, a_kv, a_d = 32, 8, 128
         aq_np, ak_np, _ = synth.attention_inputs(pcfg, a_heads, a_kv, a_d)
@@ -540,6 +629,7 @@ def main():
                                    "ffn_max_err_over_rms_bf16_out": round(err, 5)}
     # ---------------------------------------------------------------- 32-layer stack, experts in host memory
     if args.stack_steps > 0:
+        t_stack = time.perf_counter()
         from paper_2603_19172_amd.stack import DecodeStack, HostExpertPool
         L, n_pool = 32, 16
         del stores[1:]
@@ -557,13 +647,15 @@ def main():
         # byte-budget cache, whose blocks change hands between the formats as the demand shifts
         # the paper's "4/2" mode: t_l Critical experts in 4 bits (cosine depth schedule, lambda = 0.5), the rest in 2
         paper_tiers = [(B.depth_schedule(l, L, 0.5, E), E - B.depth_schedule(l, L, 0.5, E)) for l in range(L)]
-        plans = [("bf16", int(budget / (gb[16] + gb[4] + gb[2])), "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
-                 ("assigned", {16: int(0.25 * budget / gb[16]), 4: int(0.5 * budget / gb[4]),
-                               2: int(0.25 * budget / gb[2])}, "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
-                 ("assigned", "budget", "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
-                 ("assigned", {4: int(0.75 * budget / gb[4]), 2: int(0.25 * budget / gb[2])},
-                  "4/2 with the cosine depth schedule", paper_tiers, (4, 2), None),
-                 ("assigned", "budget", "4/2 with the cosine depth schedule", paper_tiers, (4, 2), None)]
+        all_plans = {
+            "literal": ("bf16", int(budget / (gb[16] + gb[4] + gb[2])), "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
+            "pools": ("assigned", {16: int(0.25 * budget / gb[16]), 4: int(0.5 * budget / gb[4]),
+                                   2: int(0.25 * budget / gb[2])}, "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
+            "budget": ("assigned", "budget", "1/3/4 bf16/int4/int2", cfg.tier_count, cfg.tier_bits, floor),
+            "paper-pools": ("assigned", {4: int(0.75 * budget / gb[4]), 2: int(0.25 * budget / gb[2])},
+                            "4/2 with the cosine depth schedule", paper_tiers, (4, 2), None),
+            "paper": ("assigned", "budget", "4/2 with the cosine depth schedule", paper_tiers, (4, 2), None)}
+        plans = [all_plans[n_.strip()] for n_ in args.stack_plans.split(",") if n_.strip()]
         results = []
         for transfer, slots, tier_name, tcount, tbits, flr in plans:
             for prefetch in (False, True):
@@ -630,7 +722,18 @@ def main():
                                            "(16 distinct experts shared by the 256 layer-experts), look-ahead of the next layer's 2 "
                                            "experts; the 1/3/4 tiers carry an int4 floor in the first and last 4 layers",
                                "device_budget_GB": budget, "steps": args.stack_steps, "warmup_steps": max(1, args.stack_warmup),
+                               "host_pool_GB": round(sum(pool.buf[b].numel() for b in pool.buf) / 1e9, 2),
+                               "section_wall_s": round(time.perf_counter() - t_stack, 1),
                                "runs": results}
+    # the two acceptance figures of the benchmark spec, side by side with what was measured in this run
+    pg = out.get("prefill_512", {}).get("grouped_gemm_frac_mfma_bf16_peak")
+    out["targets"] = {
+        "decode_frac_hbm_on_packed_weights": {"target": 0.70, "kernels_only": roofline_decode["frac"],
+                                              "step_level_formats_resident": out["decode_ffn_only"]["frac_hbm"],
+                                              "step_level_full_hot_path": out["hot_path_hbm"]["frac_hbm"],
+                                              "met": bool(out["decode_ffn_only"]["frac_hbm"] >= 0.70)},
+        "prefill_grouped_gemm_frac_mfma_bf16_peak": {"target": 0.50, "measured": pg,
+                                                     "met": bool(pg is not None and pg >= 0.50)}}
     print(json.dumps(out))
 
 

@@ -447,6 +447,21 @@ int dymoe_residual_rmsnorm(dymoe_ctx* ctx, const void* h, const void* y, int y_d
 int dymoe_stream_copy(dymoe_ctx* ctx, const void* src, void* dst, size_t bytes, void* stream);
 
 /*
+ * Measurement aid, not a step of the method: a register-only loop of
+ * v_mfma_f32_32x32x16_bf16, `iters` rounds of four independent accumulators in
+ * every wavefront, one (waves_per_simd = 1) or two wavefronts on every SIMD of
+ * the chip, no memory traffic but one float per thread at the end (sink: device,
+ * at least 512 * compute units floats; sink_floats its length).  *flops (host
+ * pointer, may be NULL) receives the floating-point operations of the launch;
+ * time it with dymoe_timing_enable (kernel id 20).  The rate it sustains is the
+ * matrix rate the chip reaches at the clock it holds under that load: the
+ * practical ceiling of the prefill GEMM beside the data sheet's 2.5 PFLOP/s
+ * (the paper gives no kernel-level figure, Sec. 6.1 "Key Metrics").
+ */
+int dymoe_mfma_peak(dymoe_ctx* ctx, int iters, int waves_per_simd, float* sink, size_t sink_floats, double* flops,
+                    void* stream);
+
+/*
  * Mixed-precision expert cache with one byte budget (paper Sec. 4.4.2): host-side
  * bookkeeping for a caller that keeps experts in an arena of device memory.  No
  * GPU call is made and no device memory is touched; all pointers are host pointers.
@@ -499,10 +514,10 @@ size_t dymoe_cache_bytes_resident(const dymoe_cache* cache);
  * Per-kernel timing (diagnostic; the paper reports only end-to-end latency,
  * Sec. 6.1 "Key Metrics", so these serve the roofline accounting).
  * dymoe_timing_enable: launches of the kernels whose bit is set in kernel_mask
- * (bit i = kernel id i, ids 0..19 in the order route, token_norm, importance,
+ * (bit i = kernel id i, ids 0..20 in the order route, token_norm, importance,
  * assign, quantize, gemv_phase1, gemv_phase2, gemv_combine, plan, gemm1, gemm2,
  * gemm_combine, stream_copy, decode_front, attn_stats, attn_colsum, gptq_group,
- * gptq_trail, gptq_hessian, gptq_factor; gemv_combine is reserved: the decode path's second phase
+ * gptq_trail, gptq_hessian, gptq_factor, mfma_peak; gemv_combine is reserved: the decode path's second phase
  * writes y itself and no launch carries that id) carry a start and a stop HIP event on the dispatch itself, so
  * the interval is the kernel's execution time on the launch stream; 0 switches
  * timing off.  Either way, records not yet read are dropped.

@@ -37,7 +37,7 @@ EXPORTS = [
     "dymoe_gptq_workspace_bytes", "dymoe_gptq_quantize_pack", "dymoe_gptq_hessian",
     "dymoe_gptq_factor_workspace_bytes", "dymoe_gptq_factor",
     "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_pack_code_tiles", "dymoe_moe_ffn_mixed", "dymoe_moe_ffn_mixed_noalloc",
-    "dymoe_stream_copy",
+    "dymoe_stream_copy", "dymoe_mfma_peak",
     "dymoe_decode_front", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
     "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
     "dymoe_cache_create", "dymoe_cache_destroy", "dymoe_cache_request", "dymoe_cache_lookup",
@@ -47,7 +47,7 @@ EXPORTS = [
 
 KERNELS = ["route", "token_norm", "importance", "assign", "quantize", "gemv_phase1",
            "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine", "stream_copy", "decode_front",
-           "attn_stats", "attn_colsum", "gptq_group", "gptq_trail", "gptq_hessian", "gptq_factor"]
+           "attn_stats", "attn_colsum", "gptq_group", "gptq_trail", "gptq_hessian", "gptq_factor", "mfma_peak"]
 
 
 class ExpertFmt(C.Structure):
@@ -108,6 +108,8 @@ lib.dymoe_attention_workspace_bytes.restype = _sz
 lib.dymoe_attention_workspace_bytes.argtypes = [_i, _i]
 lib.dymoe_token_score_attention.restype = _i
 lib.dymoe_token_score_attention.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, C.c_float, _i, _vp, _vp, _sz, _vp]
+lib.dymoe_mfma_peak.restype = _i
+lib.dymoe_mfma_peak.argtypes = [_vp, _i, _i, _vp, _sz, C.POINTER(_d), _vp]
 lib.dymoe_stream_copy.restype = _i
 lib.dymoe_stream_copy.argtypes = [_vp, _vp, _vp, _sz, _vp]
 lib.dymoe_route_topk.restype = _i
@@ -443,6 +445,13 @@ class Context:
             raise ValueError("stream_copy: byte counts differ")
         _check(lib.dymoe_stream_copy(self._h, _ptr(src), _ptr(dst), n, _stream(stream)), "dymoe_stream_copy")
         return dst
+
+    def mfma_peak(self, iters, waves_per_simd, sink, stream=None):
+        """Register-only bf16 MFMA loop (measurement aid); returns the floating-point operations of the launch."""
+        fl = _d(0.0)
+        _check(lib.dymoe_mfma_peak(self._h, int(iters), int(waves_per_simd), _ptr(sink, torch.float32), sink.numel(),
+                                   C.byref(fl), _stream(stream)), "dymoe_mfma_peak")
+        return fl.value
 
     # -- S5
     def moe_ffn_mixed(self, x, idx, w, bits, table, F, out_dtype=OUT_BF16, path=PATH_AUTO,

@@ -23,6 +23,30 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restric
         if (i + 256 * u < n16) dst[i + 256 * u] = v[u];
 }
 
+// Register-only loop of bf16 matrix instructions: every wavefront keeps four independent accumulators busy with
+// v_mfma_f32_32x32x16_bf16 and touches no memory until the end.  What it sustains is the matrix rate this chip
+// reaches at the clock it holds under that load, the practical ceiling beside the data sheet's figure.
+__global__ __launch_bounds__(256) void mfma_peak_kernel(float* __restrict__ sink, int iters)
+{
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    typedef float f32x16 __attribute__((ext_vector_type(16)));
+    const int tid = blockIdx.x * 256 + threadIdx.x;
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        a[i] = (__bf16)(float)((tid + i) & 7) * (__bf16)0.125f;
+        b[i] = (__bf16)(float)((tid + 3 * i) & 3) * (__bf16)0.25f;
+    }
+    f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+    for (int it = 0; it < iters; it++) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    }
+    sink[tid] = c0[0] + c1[5] + c2[10] + c3[15];
+}
+
 int ffn_static_scratch_address(void** out);
 int ffn_gemm_init();
 
@@ -42,6 +66,20 @@ int dymoe_stream_copy(dymoe_ctx* ctx, const void* src, void* dst, size_t bytes, 
     dymoe_launch(ctx, DYMOE_K_STREAM_COPY, dymoe::stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0,
                  (hipStream_t)stream, (const uint4*)src, (uint4*)dst, n16);
     DYMOE_HIP_LAUNCH_CHECK();
+    return DYMOE_OK;
+}
+
+int dymoe_mfma_peak(dymoe_ctx* ctx, int iters, int waves_per_simd, float* sink, size_t sink_floats, double* flops,
+                    void* stream)
+{
+    DYMOE_REQUIRE(iters > 0 && (waves_per_simd == 1 || waves_per_simd == 2) && sink != nullptr);
+    if (!ctx) return DYMOE_ENOCTX;
+    const unsigned blocks = (unsigned)(ctx->num_cu * waves_per_simd);     // four wavefronts each, one per SIMD
+    DYMOE_REQUIRE(sink_floats >= (size_t)blocks * 256);
+    dymoe_launch(ctx, DYMOE_K_MFMA_PEAK, dymoe::mfma_peak_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, sink,
+                 iters);
+    DYMOE_HIP_LAUNCH_CHECK();
+    if (flops) *flops = (double)blocks * 4.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
     return DYMOE_OK;
 }
 
@@ -152,6 +190,7 @@ const char* dymoe_kernel_name(int kernel)
     case DYMOE_K_GPTQ_TRAIL: return "gptq_trail_kernel";
     case DYMOE_K_GPTQ_HESSIAN: return "gptq_hessian_kernel";
     case DYMOE_K_GPTQ_FACTOR: return "gptq_chol_diag_kernel";
+    case DYMOE_K_MFMA_PEAK: return "mfma_peak_kernel";
     default: return nullptr;
     }
 }

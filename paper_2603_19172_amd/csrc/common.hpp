@@ -31,6 +31,7 @@ enum {
     DYMOE_K_GPTQ_TRAIL,
     DYMOE_K_GPTQ_HESSIAN,
     DYMOE_K_GPTQ_FACTOR,
+    DYMOE_K_MFMA_PEAK,
     DYMOE_K_COUNT
 };
 

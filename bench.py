@@ -662,7 +662,7 @@ def main():
                 by_budget = slots == "budget"
                 stack = DecodeStack(ctx, H, F, E, k, routers, pool, None if by_budget else slots, tcount, tbits,
                                     floor_bits=flr, prefetch=prefetch, transfer=transfer, alpha=0.125, device=dev,
-                                    budget_bytes=int(budget * 1e9) if by_budget else None)
+                                    budget_bytes=int(budget * 1e9) if by_budget else None, lookahead="expected")
                 for s in range(max(1, args.stack_warmup)):      # warm-up (fills the slots it can)
                     stack.step(xs[s % len(xs)])
                 torch.cuda.synchronize()
@@ -683,6 +683,10 @@ def main():
                                 "miss": stt["miss"], "promote": stt["promote"], "hit_resident": stt["hit_resident"],
                                 "hit_prefetched": stt["hit_prefetched"], "reused_higher": stt["reused_higher"],
                                 "prefetch_issued": stt["prefetch_issued"], "prefetch_wasted": stt["prefetch_wasted"],
+                                "prefetch_declined": stt["prefetch_declined"],
+                                "predictions_right": round(stack._pred_right / stack._pred_seen, 3) if prefetch else None,
+                                "layer_compute_ms": None if stack.layer_ms is None else round(stack.layer_ms, 3),
+                                "link_GBps_one_copy": round(stack.link_gbps, 1),
                                 "GB_moved_per_step": round(stt["bytes_copied"] / args.stack_steps / 1e9, 2),
                                 "host_link_GBps": round(stt["bytes_copied"] / dt / 1e9, 1),
                                 "copy_ms_per_step": round(ovl["copy_ms"] / args.stack_steps, 2),
@@ -720,7 +724,9 @@ def main():
                                                     "128 launches replayed as one HIP graph", "runs": resident}
         out["stack_decode"] = {"workload": "32 Mixtral-shaped layers, 1 token per step, experts in pinned host memory "
                                            "(16 distinct experts shared by the 256 layer-experts), look-ahead of the next layer's 2 "
-                                           "experts; the 1/3/4 tiers carry an int4 floor in the first and last 4 layers",
+                                           "experts on a copy stream of its own, issued when p * min(c, t) >= (1 - p) * c (p share of "
+                                           "right predictions, c the copy's time, t a layer's compute time); the 1/3/4 tiers carry "
+                                           "an int4 floor in the first and last 4 layers",
                                "device_budget_GB": budget, "steps": args.stack_steps, "warmup_steps": max(1, args.stack_warmup),
                                "host_pool_GB": round(sum(pool.buf[b].numel() for b in pool.buf) / 1e9, 2),
                                "section_wall_s": round(time.perf_counter() - t_stack, 1),

@@ -485,6 +485,10 @@ int dymoe_mfma_peak(dymoe_ctx* ctx, int iters, int waves_per_simd, float* sink, 
  *   protect[0..n_protect) are never evicted.  DYMOE_ENOSPC: nothing evictable;
  *   the cache is then unchanged.
  * dymoe_cache_lookup: 1 and the resident format / offset, or 0.
+ * dymoe_cache_create_pools: the same rules over a fixed partition instead of one budget: slot_counts[i] >= 1 slots
+ *   of format_bits[i], laid out format after format (offsets are into an arena of dymoe_cache_block_bytes bytes,
+ *   slot j of format i after all slots of the formats before it); a slot never serves another format, so room for a
+ *   request comes from free or least recently used unprotected slots of its own format only.
  */
 typedef struct dymoe_cache dymoe_cache;
 #define DYMOE_CACHE_MAX_FORMATS 4
@@ -503,6 +507,8 @@ typedef struct {
 } dymoe_cache_action;
 int dymoe_cache_create(dymoe_cache** out, size_t budget_bytes, int n_formats, const int32_t* format_bits,
                        const size_t* slot_bytes);
+int dymoe_cache_create_pools(dymoe_cache** out, int n_formats, const int32_t* format_bits, const size_t* slot_bytes,
+                             const int32_t* slot_counts);
 void dymoe_cache_destroy(dymoe_cache* cache);
 int dymoe_cache_request(dymoe_cache* cache, int64_t key, int want_bits, const int64_t* protect, int n_protect,
                         dymoe_cache_action* out);

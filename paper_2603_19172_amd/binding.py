@@ -40,7 +40,7 @@ EXPORTS = [
     "dymoe_stream_copy", "dymoe_mfma_peak",
     "dymoe_decode_front", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
     "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
-    "dymoe_cache_create", "dymoe_cache_destroy", "dymoe_cache_request", "dymoe_cache_lookup",
+    "dymoe_cache_create", "dymoe_cache_create_pools", "dymoe_cache_destroy", "dymoe_cache_request", "dymoe_cache_lookup",
     "dymoe_cache_block_bytes", "dymoe_cache_bytes_resident",
     "dymoe_timing_enable", "dymoe_timing_read", "dymoe_kernel_name",
 ]
@@ -71,6 +71,8 @@ class CacheAction(C.Structure):
 _vp, _i, _l, _sz, _d = C.c_void_p, C.c_int, C.c_long, C.c_size_t, C.c_double
 lib.dymoe_cache_create.restype = _i
 lib.dymoe_cache_create.argtypes = [C.POINTER(_vp), _sz, _i, _vp, _vp]
+lib.dymoe_cache_create_pools.restype = _i
+lib.dymoe_cache_create_pools.argtypes = [C.POINTER(_vp), _i, _vp, _vp, _vp]
 lib.dymoe_cache_destroy.restype = None
 lib.dymoe_cache_destroy.argtypes = [_vp]
 lib.dymoe_cache_request.restype = _i

@@ -1,12 +1,7 @@
-"""Mixed-precision expert cache (paper Sec. 4.4.2): host-side bookkeeping only.
+"""Mixed-precision expert cache (paper Sec. 4.4.2): thin wrappers of the library's host-side
+bookkeeping (dymoe_cache_*; no GPU call is made there or here).
 
-Two managers with the same interface: `MixedPrecisionCache` below divides the
-device memory into a fixed number of slots per format; `ByteBudgetCache` wraps
-the library's dymoe_cache_*, which shares one byte budget between the formats.
-
-The device memory set aside for experts is divided into slots of three sizes,
-one pool per stored format (16, 8, 4 or 2 bits per weight); each pool is kept in
-least-recently-used order.  The three rules of the paper:
+The three rules of the paper:
 
   No Duplication        an expert is resident in at most one format;
   Precision Promotion   asked for a higher precision than the resident one:
@@ -15,11 +10,16 @@ least-recently-used order.  The three rules of the paper:
   Conservative Reuse    asked for a lower precision than the resident one:
                         a hit; the resident (higher) format is used.
 
+Two ways of dividing the device memory set aside for experts, one interface:
+`MixedPrecisionCache` gives every stored format (16, 8, 4 or 2 bits per weight) a fixed
+number of slots (dymoe_cache_create_pools), `ByteBudgetCache` shares one byte budget
+between the formats (dymoe_cache_create).  Either keeps least-recently-used order.
+
 `request` returns what the caller has to do (nothing, or copy the expert's
 `load_bits` format into slot `slot`) and which precision the layer then runs
-the expert at.  No GPU call is made here.
+the expert at.  A request that cannot be served raises and leaves the cache as it was.
 """
-import collections
+import ctypes as C
 
 FORMATS = (16, 8, 4, 2)
 
@@ -29,11 +29,11 @@ class Action:
 
     def __init__(self, kind, slot, use_bits, load_bits=0, evicted=None, dropped=None, freed=()):
         self.kind = kind            # "hit", "miss" or "promote"
-        self.slot = slot            # (format, index) holding the expert after the request
+        self.slot = slot            # name of the slot holding the expert after the request
         self.use_bits = use_bits    # precision the expert is run at
         self.load_bits = load_bits  # format to copy into `slot` (0: nothing to copy)
-        self.evicted = evicted      # key that lost `slot`, if any
-        self.dropped = dropped      # (format, index) freed by a promotion, if any
+        self.evicted = evicted      # what lost its slot, if anything (one key for fixed pools, a list for a budget)
+        self.dropped = dropped      # slot freed by a promotion, if any
         self.freed = tuple(freed)   # slots other than `slot` whose contents were given up and whose memory `slot` may overlap
 
     def __repr__(self):
@@ -41,81 +41,20 @@ class Action:
             self.kind, self.slot, self.use_bits, self.load_bits, self.evicted, self.dropped)
 
 
-class MixedPrecisionCache:
-    def __init__(self, slots):
-        """slots: {16: n16, 8: n8, 4: n4, 2: n2} slot counts per format (missing: none)."""
-        self.capacity = {b: int(slots.get(b, 0)) for b in FORMATS}
-        # per format: slot index -> key (None when free), least recently used first
-        self.pool = {b: collections.OrderedDict((i, None) for i in range(self.capacity[b])) for b in FORMATS}
-        self.where = {}      # key -> (format, index)
+class _NativeCache:
+    """What the two managers share: keys of any hashable type mapped to the library's int64 ids, the mirror of
+    who is where, and the request itself.  Subclasses create the handle and name the slots."""
 
-    def resident(self, key):
-        """(format, index) of the expert, or None."""
-        return self.where.get(key)
-
-    def covers(self, key, want_bits):
-        """True when a request for `want_bits` would be a hit."""
-        loc = self.where.get(key)
-        return loc is not None and loc[0] >= want_bits
-
-    def _take(self, fmt, protect):
-        """A slot of pool `fmt`: a free one, else the least recently used one not in `protect`."""
-        pool = self.pool[fmt]
-        for i, k in pool.items():
-            if k is None:
-                return i, None
-        for i, k in pool.items():
-            if (fmt, i) not in protect:
-                return i, k
-        raise RuntimeError("no evictable %d-bit slot" % fmt)
-
-    def request(self, key, want_bits, protect=()):
-        if want_bits not in FORMATS:
-            raise ValueError("want_bits must be one of %s" % (FORMATS,))
-        if self.capacity[want_bits] == 0 and not self.covers(key, want_bits):
-            raise ValueError("no %d-bit slots configured" % want_bits)
-        loc = self.where.get(key)
-        if loc is not None and loc[0] >= want_bits:          # Conservative Reuse (or an exact hit)
-            self.pool[loc[0]].move_to_end(loc[1])
-            return Action("hit", loc, loc[0])
-        dropped = None
-        if loc is not None:                                  # Precision Promotion: the lower format goes
-            self.pool[loc[0]][loc[1]] = None
-            self.pool[loc[0]].move_to_end(loc[1], last=False)
-            del self.where[key]
-            dropped = loc
-        i, old = self._take(want_bits, protect)
-        if old is not None:
-            del self.where[old]
-        self.pool[want_bits][i] = key
-        self.pool[want_bits].move_to_end(i)
-        self.where[key] = (want_bits, i)
-        return Action("promote" if dropped else "miss", (want_bits, i), want_bits, want_bits, old, dropped)
-
-
-class ByteBudgetCache:
-    """The library's byte-budget cache (dymoe_cache_*) behind the interface of MixedPrecisionCache.
-    A slot is named (format, byte offset into the caller's arena).  Keys may be any hashable values."""
-
-    def __init__(self, budget_bytes, slot_bytes):
-        """slot_bytes: {bits: bytes of one expert in that format}."""
-        import ctypes as C
+    def _init(self, handle):
         from . import binding as B
-        self._B, self._C = B, C
-        self.formats = tuple(sorted(slot_bytes, reverse=True))
-        fb = (C.c_int32 * len(self.formats))(*self.formats)
-        sb = (C.c_size_t * len(self.formats))(*[int(slot_bytes[b]) for b in self.formats])
-        h = C.c_void_p()
-        B._check(B.lib.dymoe_cache_create(C.byref(h), int(budget_bytes), len(self.formats), C.cast(fb, C.c_void_p),
-                                          C.cast(sb, C.c_void_p)), "dymoe_cache_create")
-        self._h = h
-        self.block_bytes = int(B.lib.dymoe_cache_block_bytes(h))
+        self._B = B
+        self._h = handle
         self._id, self._key = {}, {}       # key <-> int64 id
-        self.where = {}                    # key -> (format, offset), mirrored for inspection
-        self._at = {}                      # slot -> key
+        self.where = {}                    # key -> slot name, mirrored for inspection
+        self._at = {}                      # slot name -> key
 
     def close(self):
-        if self._h is not None and self._B.lib is not None:
+        if getattr(self, "_h", None) is not None and self._B.lib is not None:
             self._B.lib.dymoe_cache_destroy(self._h)
         self._h = None
 
@@ -129,19 +68,24 @@ class ByteBudgetCache:
             self._key[i] = key
         return i
 
+    def _name(self, bits, offset):
+        return (bits, int(offset))
+
     def resident(self, key):
+        """Name of the slot the expert is in, or None."""
         return self.where.get(key)
 
     def covers(self, key, want_bits):
+        """True when a request for `want_bits` would be a hit."""
         loc = self.where.get(key)
         return loc is not None and loc[0] >= want_bits
 
     def bytes_resident(self):
         return int(self._B.lib.dymoe_cache_bytes_resident(self._h))
 
-    def request(self, key, want_bits, protect=()):
-        """protect: slots (format, offset) whose experts must stay."""
-        C, B = self._C, self._B
+    def _request(self, key, want_bits, protect):
+        """protect: slot names whose experts must stay."""
+        B = self._B
         keep = [self._ident(self._at[s]) for s in protect if s in self._at]
         arr = (C.c_int64 * max(len(keep), 1))(*keep)
         act = B.CacheAction()
@@ -149,6 +93,8 @@ class ByteBudgetCache:
                                        C.byref(act))
         if rc == B.ENOSPC:
             raise RuntimeError("no evictable room for a %d-bit expert" % want_bits)
+        if rc == B.EINVAL:
+            raise ValueError("no %d-bit slots configured" % want_bits)
         B._check(rc, "dymoe_cache_request")
         evicted = [self._key[act.evicted[i]] for i in range(act.n_evicted)]
         freed = []
@@ -160,9 +106,66 @@ class ByteBudgetCache:
             dropped = self.where.pop(key)
             self._at.pop(dropped, None)
             freed.append(dropped)
-        slot = (act.use_bits, int(act.offset))
+        slot = self._name(act.use_bits, act.offset)
         self.where[key] = slot
         self._at[slot] = key
         kind = ("hit", "miss", "promote")[act.kind]
-        return Action(kind, slot, act.use_bits, act.load_bits, evicted if evicted else None, dropped,
-                      [f for f in freed if f != slot])
+        return kind, slot, act, evicted, dropped, [f for f in freed if f != slot]
+
+
+class MixedPrecisionCache(_NativeCache):
+    """A fixed number of slots per format.  A slot is named (format, index)."""
+
+    def __init__(self, slots):
+        """slots: {16: n16, 8: n8, 4: n4, 2: n2} slot counts per format (missing or 0: none)."""
+        from . import binding as B
+        self.capacity = {b: int(slots.get(b, 0)) for b in FORMATS}
+        fmts = [b for b in FORMATS if self.capacity[b] > 0]
+        if not fmts:
+            raise ValueError("no slots configured")
+        # only the order of the slots matters here: the caller owns the memory, one buffer per slot
+        self._unit = 256
+        fb = (C.c_int32 * len(fmts))(*fmts)
+        sb = (C.c_size_t * len(fmts))(*[self._unit] * len(fmts))
+        nb = (C.c_int32 * len(fmts))(*[self.capacity[b] for b in fmts])
+        h = C.c_void_p()
+        B._check(B.lib.dymoe_cache_create_pools(C.byref(h), len(fmts), C.cast(fb, C.c_void_p), C.cast(sb, C.c_void_p),
+                                                C.cast(nb, C.c_void_p)), "dymoe_cache_create_pools")
+        self._init(h)
+        self._base, pos = {}, 0
+        for b in fmts:
+            self._base[b] = pos
+            pos += self.capacity[b] * self._unit
+
+    def _name(self, bits, offset):
+        return (bits, (int(offset) - self._base[bits]) // self._unit)
+
+    def held(self, bits):
+        """Keys resident in the pool of this format."""
+        return [k for k, (b, _) in self.where.items() if b == bits]
+
+    def request(self, key, want_bits, protect=()):
+        if want_bits not in FORMATS:
+            raise ValueError("want_bits must be one of %s" % (FORMATS,))
+        kind, slot, act, evicted, dropped, freed = self._request(key, want_bits, protect)
+        return Action(kind, slot, act.use_bits, act.load_bits, evicted[0] if evicted else None, dropped)
+
+
+class ByteBudgetCache(_NativeCache):
+    """One byte budget shared by the formats.  A slot is named (format, byte offset into the caller's arena)."""
+
+    def __init__(self, budget_bytes, slot_bytes):
+        """slot_bytes: {bits: bytes of one expert in that format}."""
+        from . import binding as B
+        self.formats = tuple(sorted(slot_bytes, reverse=True))
+        fb = (C.c_int32 * len(self.formats))(*self.formats)
+        sb = (C.c_size_t * len(self.formats))(*[int(slot_bytes[b]) for b in self.formats])
+        h = C.c_void_p()
+        B._check(B.lib.dymoe_cache_create(C.byref(h), int(budget_bytes), len(self.formats), C.cast(fb, C.c_void_p),
+                                          C.cast(sb, C.c_void_p)), "dymoe_cache_create")
+        self._init(h)
+        self.block_bytes = int(B.lib.dymoe_cache_block_bytes(h))
+
+    def request(self, key, want_bits, protect=()):
+        kind, slot, act, evicted, dropped, freed = self._request(key, want_bits, protect)
+        return Action(kind, slot, act.use_bits, act.load_bits, evicted if evicted else None, dropped, freed)

@@ -19,6 +19,10 @@
 //       block being as recent as its most recently used resident,
 // (a) on equal age.  Evicting a block frees all its slots and hands the block
 // over to the requesting format.
+//
+// The same rules over a FIXED partition (dymoe_cache_create_pools): so many
+// slots per format, each slot a block of its own that never changes hands; room
+// for a request then comes from its own format's pool alone.
 #include "dymoe.h"
 
 #include <stdint.h>
@@ -40,6 +44,8 @@ struct Resident {
 struct Block {
     int fmt = -1;                 // -1: free
     int used = 0;
+    int pin = -1;                 // fixed partition: the only format this block ever serves (-1: any)
+    size_t base = 0;              // byte offset of the block in the arena
     std::vector<int64_t> keys;    // per slot: resident key, or kNoKey
 };
 
@@ -64,7 +70,7 @@ struct dymoe_cache {
     }
     int64_t offset_of(const Resident& r) const
     {
-        return (int64_t)((size_t)r.block * block_bytes + (size_t)r.slot * slot_bytes[r.fmt]);
+        return (int64_t)(blocks[r.block].base + (size_t)r.slot * slot_bytes[r.fmt]);
     }
     void release(int64_t key)
     {
@@ -89,7 +95,7 @@ struct dymoe_cache {
         }
         for (size_t i = 0; i < blocks.size(); i++) {
             Block& b = blocks[i];
-            if (b.fmt != -1) continue;
+            if (b.fmt != -1 || (b.pin >= 0 && b.pin != f)) continue;
             b.fmt = f;
             b.used = 0;
             b.keys.assign((size_t)slots_per_block[f], kNoKey);
@@ -138,6 +144,41 @@ int dymoe_cache_create(dymoe_cache** out, size_t budget_bytes, int n_formats, co
         return DYMOE_ENOSPC;
     }
     c->blocks.resize(n_blocks);
+    for (size_t i = 0; i < n_blocks; i++) c->blocks[i].base = i * largest;
+    *out = c;
+    return DYMOE_OK;
+}
+
+int dymoe_cache_create_pools(dymoe_cache** out, int n_formats, const int32_t* format_bits, const size_t* slot_bytes,
+                             const int32_t* slot_counts)
+{
+    if (!out || !format_bits || !slot_bytes || !slot_counts) return DYMOE_EINVAL;
+    if (n_formats < 1 || n_formats > DYMOE_CACHE_MAX_FORMATS) return DYMOE_EINVAL;
+    dymoe_cache* c = new (std::nothrow) dymoe_cache;
+    if (!c) return DYMOE_EHIP;
+    size_t total = 0, pos = 0;
+    for (int i = 0; i < n_formats; i++) {
+        const int b = format_bits[i];
+        bool dup = false;
+        for (int j = 0; j < i; j++) dup = dup || format_bits[j] == b;
+        if (!(b == 2 || b == 4 || b == 8 || b == 16) || dup || slot_bytes[i] == 0 || slot_counts[i] < 1) {
+            delete c;
+            return DYMOE_EINVAL;
+        }
+        c->bits.push_back(b);
+        c->slot_bytes.push_back((slot_bytes[i] + 255) / 256 * 256);
+        c->slots_per_block.push_back(1);
+        total += (size_t)slot_counts[i];
+    }
+    c->blocks.resize(total);
+    size_t n = 0;
+    for (int i = 0; i < n_formats; i++)
+        for (int j = 0; j < slot_counts[i]; j++, n++) {
+            c->blocks[n].pin = i;
+            c->blocks[n].base = pos;
+            pos += c->slot_bytes[i];
+        }
+    c->block_bytes = pos;       // the whole arena: what dymoe_cache_block_bytes reports for a fixed partition
     *out = c;
     return DYMOE_OK;
 }
@@ -205,7 +246,7 @@ int dymoe_cache_request(dymoe_cache* c, int64_t key, int want_bits, const int64_
         uint64_t other_tick = UINT64_MAX;
         for (size_t i = 0; i < c->blocks.size(); i++) {
             const Block& b = c->blocks[i];
-            if (b.fmt < 0 || b.fmt == f) continue;
+            if (b.fmt < 0 || b.fmt == f || b.pin >= 0) continue;      // (a pinned block serves its own format only)
             uint64_t newest = 0;
             bool ok = true;
             for (int64_t k : b.keys) {

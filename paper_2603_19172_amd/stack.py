@@ -8,7 +8,13 @@ layer's router applied to the current hidden states (Sec. 4.4.1 Eq. 6) names the
 experts to prefetch (decode: the token's own predicted experts, Eq. 8; prefill:
 the experts most tokens are predicted to ask for, Eq. 7), which are copied on a
 side stream (dymoe_prefetch_submit / dymoe_prefetch_wait) while the current
-layer computes.
+layer computes.  Copies a layer is waiting for and copies made on a prediction
+travel on two different streams, so that a miss never queues behind speculation,
+and a speculative copy is only issued when it is expected to pay: with p the
+measured share of right predictions, a copy of c milliseconds hides at most the
+layer's compute time t when it is right and occupies the link for c when it is
+wrong, so it is issued when p * min(c, t) >= (1 - p) * c (`lookahead="expected"`;
+"always" issues every predicted copy).
 
 Two ways of moving an expert:
   transfer="bf16"      the bf16 weights travel and are quantised on the device
@@ -186,7 +192,7 @@ class _Slot:
 class ExpertStack:
     def __init__(self, ctx, T, phase, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
                  prefetch=True, transfer="bf16", alpha=0.125, k_hh=0, predict_t=None, device="cuda:0",
-                 budget_bytes=None):
+                 budget_bytes=None, lookahead="always"):
         """T tokens per step; phase "decode" (gate-score importance, Eq. 3; the k experts the next layer is
         predicted to route the token to are fetched ahead, Eq. 8 with t = k) or "prefill" (heavy-hitter
         importance over the k_hh highest-norm tokens, Eq. 2; the predict_t experts of highest predicted
@@ -199,6 +205,9 @@ class ExpertStack:
         layer, or a list of per-layer tuples (e.g. (t_l, E - t_l) from the depth schedule of Sec. 4.3)."""
         if transfer not in ("bf16", "assigned"):
             raise ValueError("transfer must be 'bf16' or 'assigned'")
+        if lookahead not in ("always", "expected"):
+            raise ValueError("lookahead must be 'always' or 'expected'")
+        self.lookahead = lookahead
         if phase not in ("decode", "prefill"):
             raise ValueError("phase must be 'decode' or 'prefill'")
         self.ctx, self.T, self.phase, self.H, self.F, self.E, self.k = ctx, T, phase, H, F, E, k
@@ -244,29 +253,70 @@ class ExpertStack:
         self.table_slot = {}                    # (layer, e) -> slot written in the table
         self.h = [torch.empty((T, H), dtype=torch.bfloat16, device=device) for _ in range(2)]
         self.score = torch.empty((T,), dtype=torch.float32, device=device)
-        self.side = torch.cuda.Stream(device=device)
-        # What the host reads back per layer (selected experts, loads, bit widths) sits in one device buffer per
-        # runner and travels in one copy: idx [T,k] int32 | load [E] int32 | bits [E] uint8.
-        n_idx, n_load = T * k * 4, E * 4
-        self._meta_tail = n_idx                 # T > 1: only load and bits travel
+        self.side = torch.cuda.Stream(device=device)       # copies a layer is waiting for
+        self.spec = torch.cuda.Stream(device=device)       # copies made on a prediction (same priority)
+        # what the look-ahead rule goes by: the link's rate (one timed copy), a layer's compute time (timed over the
+        # first steps) and the share of right predictions so far (a prior of 3 in 4 until there is evidence)
+        self.link_gbps = self._measure_link()
+        self.layer_ms = None
+        self._layer_events = []
+        self._pred_seen, self._pred_right = 4, 3
+        self._last_pred = None
+        self._idle_lookahead, self._probe_now = False, True
+        # What the host reads back per layer sits in one device buffer per runner and travels in one copy:
+        # idx [T,k] int32 | load [E] int32 | rank [E] int32 | bits [E] uint8 | mark [E] uint8.  rank and mark are the
+        # look-ahead runner's Eq. 7 selection (position of every expert by predicted frequency; 16 for the
+        # predict_t most frequent, 0 for the rest), written by dymoe_assign_precision with tiers (t, E - t).
+        n_idx, n_load, n_e = T * k * 4, E * 4, (E + 3) // 4 * 4
+        self._meta_tail = n_idx                 # T > 1: idx stays on the device
 
         def views(buf):
+            o = n_idx + 2 * n_load
             return (buf[:n_idx].view(torch.int32).view(T, k), buf[n_idx:n_idx + n_load].view(torch.int32),
-                    buf[n_idx + n_load:n_idx + n_load + E])
+                    buf[n_idx + n_load:o].view(torch.int32), buf[o:o + E], buf[o + n_e:o + n_e + E])
 
         def pack(lay):
-            lay.meta = torch.zeros((n_idx + n_load + (E + 3) // 4 * 4,), dtype=torch.uint8, device=device)
-            lay.idx, lay.load, lay.bits = views(lay.meta)
+            lay.meta = torch.zeros((n_idx + 2 * n_load + 2 * n_e,), dtype=torch.uint8, device=device)
+            lay.idx, lay.load, lay.sel_rank, lay.bits, lay.sel_mark = views(lay.meta)
             host = torch.zeros(lay.meta.shape, dtype=torch.uint8).pin_memory()
             return (host,) + views(host)
 
-        self.host_meta, self.host_idx, self.host_load, self.host_bits = pack(self.layer)
-        self.host_pmeta, self.host_pidx, self.host_pload, self.host_pbits = pack(self.ahead)
+        self.host_meta, self.host_idx, self.host_load, _, self.host_bits, _ = pack(self.layer)
+        self.host_pmeta, self.host_pidx, self.host_pload, self.host_prank, self.host_pbits, self.host_pmark = pack(self.ahead)
+        t_sel = min(self.predict_t, E)
+        self._sel_tc = (C.c_int32 * 2)(t_sel, E - t_sel)
+        self._sel_tb = (C.c_uint8 * 2)(16, 0)
         self.stats = collections.Counter()
         self.measure_overlap = False    # set True to time every copy and every wait of the compute stream (overlap_report)
         self._copy_events, self._stall_events = [], []
         self.trace = []     # per step and layer: (experts, assigned bits, bits they were run at)
         self.predictions = []   # per step and layer (but the last): experts fetched ahead for the next layer
+
+    def _measure_link(self):
+        """Host link rate in GB/s from one copy out of the pool (64 MiB at most), on the demand stream."""
+        fmt = 16 if 16 in self.pool.buf else sorted(self.pool.buf)[-1]
+        n = min(self.pool.nbytes[fmt], 64 << 20)
+        dst = torch.empty((n,), dtype=torch.uint8, device=self.dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        rates = []
+        for _ in range(2):                       # the second copy is the one that counts
+            e0.record(self.side)
+            ev = self.ctx.prefetch_submit(self.pool.buf[fmt].data_ptr(), dst.data_ptr(), n, self.side.cuda_stream)
+            e1.record(self.side)
+            e1.synchronize()
+            self.ctx.prefetch_release(ev)
+            rates.append(n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        return rates[-1]
+
+    def _worth_fetching_ahead(self, nbytes):
+        """The expected-value rule of the module's header."""
+        if self.lookahead == "always":
+            return True
+        if self.layer_ms is None:                # no compute time measured yet: wait for it
+            return False
+        p = self._pred_right / self._pred_seen
+        c = nbytes / (self.link_gbps * 1e6)      # ms
+        return p * min(c, self.layer_ms) >= (1.0 - p) * c
 
     def _slot(self, name):
         slot = self.slots.get(name)
@@ -277,36 +327,38 @@ class ExpertStack:
         return slot
 
     def _fill(self, act, key, ahead):
-        """Copy the format `act.load_bits` of expert `key` into the slot the cache chose, on the side stream."""
+        """Copy the format `act.load_bits` of expert `key` into the slot the cache chose: on the demand stream, or
+        (ahead) on the stream of speculative copies."""
+        stream = self.spec if ahead else self.side
         slot = self._slot(act.slot)
-        for name in act.freed:                    # slots given up whose memory the new one may overlap
-            old = self.slots.get(name)
-            if old is None:
-                continue
+
+        def settle(old):
+            """Order the new copy behind whatever still touches the memory `old` names."""
             if old.prefetched:
                 self.stats["prefetch_wasted"] += 1
                 old.prefetched = False
-            if old.copy_event is not None:        # same stream: the old copy is ordered before the new one
+            if old.copy_event is not None:        # an unused earlier copy, possibly on the other stream
+                self.ctx.prefetch_wait(old.copy_event, stream.cuda_stream)
                 self.ctx.prefetch_release(old.copy_event)
                 old.copy_event = None
-            if old.last_use is not None:
-                self.side.wait_event(old.last_use)
+            if old.last_use is not None:          # the compute stream may still be reading the old content
+                stream.wait_event(old.last_use)
                 old.last_use = None
-        if slot.prefetched:
-            self.stats["prefetch_wasted"] += 1
-        if slot.copy_event is not None:           # an unused earlier copy: same stream, ordered before this one
-            self.ctx.prefetch_release(slot.copy_event)
-        if slot.last_use is not None:             # the compute stream may still be reading the old content
-            self.side.wait_event(slot.last_use)
+
+        for name in act.freed:                    # slots given up whose memory the new one may overlap
+            old = self.slots.get(name)
+            if old is not None:
+                settle(old)
+        settle(slot)
         layer, e = key
         nbytes = self.pool.nbytes[act.load_bits]
         if self.measure_overlap:
             c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            c0.record(self.side)
+            c0.record(stream)
         slot.copy_event = self.ctx.prefetch_submit(self.pool.host_ptr(layer, e, act.load_bits), slot.buf.data_ptr(),
-                                                   nbytes, self.side.cuda_stream)
+                                                   nbytes, stream.cuda_stream)
         if self.measure_overlap:
-            c1.record(self.side)
+            c1.record(stream)
             self._copy_events.append((c0, c1))
         slot.prefetched = ahead
         self.stats["bytes_copied"] += nbytes
@@ -338,13 +390,23 @@ class ExpertStack:
                 B._check(B.lib.dymoe_token_score_norm(ctx._h, h.data_ptr(), self.T, self.H, self.score.data_ptr(), st),
                          "dymoe_token_score_norm")
         step_trace, step_pred = [], []
+        # when the rule turned every copy of the last step down, the prediction itself (a router launch per layer) is
+        # only made every 8th step, to keep the share of right predictions current
+        self._probe_now = not self._idle_lookahead or self.stats["steps"] % 8 == 0
+        declined0, issued0 = self.stats["prefetch_declined"], self.stats["prefetch_issued"]
         for l in range(self.L):
             lay.floor_bits, lay._tc = self.floor[l], self.tier_arrays[l]
             self._front(lay, h, self.routers[l], st)
-            look = self.prefetch and l + 1 < self.L
+            look = self.prefetch and l + 1 < self.L and self._probe_now
             if look:     # Eq. 6: the next layer's router (and precision rule) on the current hidden states
                 nxt_lay.floor_bits, nxt_lay._tc = self.floor[l + 1], self.tier_arrays[l + 1]
                 self._front(nxt_lay, h, self.routers[l + 1], st)
+                if self.T > 1:   # Eq. 7: the predict_t experts of highest predicted frequency, chosen on the device
+                    B._check(B.lib.dymoe_assign_precision(ctx._h, B.PHASE_PREFILL, nxt_lay.load.data_ptr(), None, self.E,
+                                                          2, C.cast(self._sel_tc, C.c_void_p),
+                                                          C.cast(self._sel_tb, C.c_void_p), 0,
+                                                          nxt_lay.sel_mark.data_ptr(), nxt_lay.sel_rank.data_ptr(), st),
+                             "dymoe_assign_precision")
                 a = 0 if self.T == 1 else self._meta_tail
                 self.host_pmeta[a:].copy_(nxt_lay.meta[a:], non_blocking=True)
             a = 0 if self.T == 1 else self._meta_tail
@@ -355,6 +417,10 @@ class ExpertStack:
             else:                # every expert some token was routed to
                 active = [e for e, c in enumerate(self.host_load.tolist()) if c > 0]
             abits = [int(self.host_bits[e]) for e in active]
+            if self._last_pred is not None:       # how the look-ahead of the layer before did
+                self._pred_seen += len(self._last_pred)
+                self._pred_right += sum(1 for e in self._last_pred if e in active)
+                self._last_pred = None
             want = lambda b: 16 if self.transfer == "bf16" else b
             need = [(e, b) for e, b in zip(active, abits) if b != 0]
             # this layer's experts: resident, arriving, or fetched now (what is already resident is
@@ -402,11 +468,11 @@ class ExpertStack:
             if look:
                 if self.T == 1:      # Eq. 8: the token's own predicted experts
                     ahead = [int(v) for v in self.host_pidx[0].tolist()][:self.predict_t]
-                else:                # Eq. 7: the experts most tokens are predicted to ask for
-                    freq = self.host_pload.tolist()
-                    order = sorted(range(self.E), key=lambda e: (-freq[e], e))
-                    ahead = [e for e in order[:self.predict_t] if freq[e] > 0]
+                else:                # Eq. 7: the experts most tokens are predicted to ask for (nobody's are left out)
+                    mark, rank, freq = self.host_pmark.tolist(), self.host_prank.tolist(), self.host_pload.tolist()
+                    ahead = sorted((e for e in range(self.E) if mark[e] and freq[e] > 0), key=lambda e: rank[e])
                 step_pred.append(tuple(ahead))
+                self._last_pred = tuple(ahead)
                 for e in ahead:
                     pb = int(self.host_pbits[e])
                     key = (l + 1, e)
@@ -415,11 +481,18 @@ class ExpertStack:
                     if self.cache.covers(key, want(pb)):
                         protect.add(self.cache.resident(key))
                         continue
+                    if not self._worth_fetching_ahead(self.pool.nbytes[want(pb)]):
+                        self.stats["prefetch_declined"] += 1
+                        continue
                     act = self.cache.request(key, want(pb), protect)
                     protect.add(act.slot)
                     self._fill(act, key, ahead=True)
                     self.stats["prefetch_issued"] += 1
             table = self.tables[l]
+            timing = self.layer_ms is None
+            if timing:
+                t0 = torch.cuda.Event(enable_timing=True)
+                t0.record(cs)
             if self.transfer == "bf16":      # S4 on arrival
                 B._check(B.lib.dymoe_quantize_experts(ctx._h, table.data_ptr(), lay.bits.data_ptr(),
                                                       lay.load.data_ptr(), self.E, self.H, self.F, 64,
@@ -432,11 +505,22 @@ class ExpertStack:
             B._check(B.lib.dymoe_residual_rmsnorm(ctx._h, h.data_ptr(), lay.y.data_ptr(), B.OUT_F32,
                                                   float(self.alpha), self.T, self.H, nxt.data_ptr(), st),
                      "dymoe_residual_rmsnorm")
+            if timing:
+                t1 = torch.cuda.Event(enable_timing=True)
+                t1.record(cs)
+                self._layer_events.append((t0, t1))
             done = torch.cuda.Event()
             done.record(cs)
             for e, b in need:
                 self._slot(self.cache.resident((l, e))).last_use = done
             h = nxt
+        self._last_pred = None
+        if self._probe_now and self.lookahead == "expected" and self.layer_ms is not None:
+            self._idle_lookahead = (self.stats["prefetch_issued"] == issued0 and self.stats["prefetch_declined"] > declined0)
+        if self.layer_ms is None and self.stats["steps"] >= 1:      # the second step on: a layer's compute time is known
+            cs.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in self._layer_events[self.L:])
+            self.layer_ms, self._layer_events = ms[len(ms) // 2], []
         self.trace.append(step_trace)
         self.predictions.append(step_pred)
         self.stats["steps"] += 1
@@ -465,10 +549,10 @@ class DecodeStack(ExpertStack):
     """One token per step (Sec. 4.2.2 importance, Eq. 8 prefetch)."""
 
     def __init__(self, ctx, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
-                 prefetch=True, transfer="bf16", alpha=0.125, device="cuda:0", budget_bytes=None):
+                 prefetch=True, transfer="bf16", alpha=0.125, device="cuda:0", budget_bytes=None, lookahead="always"):
         super().__init__(ctx, 1, "decode", H, F, E, k, routers, pool, slots, tier_count, tier_bits,
                          floor_bits=floor_bits, prefetch=prefetch, transfer=transfer, alpha=alpha, device=device,
-                         budget_bytes=budget_bytes)
+                         budget_bytes=budget_bytes, lookahead=lookahead)
 
 
 class PrefillStack(ExpertStack):
@@ -476,11 +560,12 @@ class PrefillStack(ExpertStack):
     the predict_t most frequently predicted experts)."""
 
     def __init__(self, ctx, T, H, F, E, k, k_hh, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
-                 prefetch=True, predict_t=None, transfer="bf16", alpha=0.125, device="cuda:0", budget_bytes=None):
+                 prefetch=True, predict_t=None, transfer="bf16", alpha=0.125, device="cuda:0", budget_bytes=None,
+                 lookahead="always"):
         super().__init__(ctx, T, "prefill", H, F, E, k, routers, pool, slots, tier_count, tier_bits,
                          floor_bits=floor_bits, prefetch=prefetch, transfer=transfer, alpha=alpha, k_hh=k_hh,
                          predict_t=predict_t if predict_t is not None else min(E, max(k, E // 2)), device=device,
-                         budget_bytes=budget_bytes)
+                         budget_bytes=budget_bytes, lookahead=lookahead)
 
 
 class ResidentDecodeStack:

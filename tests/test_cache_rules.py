@@ -1,6 +1,7 @@
 """Table-driven CPU tests of the mixed-precision expert cache (paper Sec. 4.4.2):
 No Duplication, Precision Promotion, Conservative Reuse, and least-recently-used
-eviction inside each format's pool.  Host logic only; no GPU."""
+eviction, over a fixed partition (dymoe_cache_create_pools) and over one byte budget
+(dymoe_cache_create).  Host logic of the library only; no GPU."""
 import pytest
 
 from paper_2603_19172_amd.cache import MixedPrecisionCache
@@ -15,9 +16,8 @@ def run(cache, script):
         # No Duplication: after any request every expert is resident exactly once
         locs = list(cache.where.values())
         assert len(locs) == len(set(locs))
-        if hasattr(cache, "pool"):
-            held = [(b, i) for b in cache.pool for i, k in cache.pool[b].items() if k is not None]
-            assert sorted(held) == sorted(locs)
+        if hasattr(cache, "capacity"):        # fixed pools: nobody sits outside its pool
+            assert all(0 <= i < cache.capacity[b] for b, i in locs)
 
 
 def test_exact_hits_and_lru_eviction_within_a_pool():
@@ -41,7 +41,7 @@ def test_conservative_reuse_serves_a_lower_request_from_the_higher_format():
         ("b", 2, "hit", 4, None),
     ])
     assert c.resident("a") == (16, 0) and c.resident("b") == (4, 0)
-    assert all(k is None for k in c.pool[2].values())       # the int2 pool was never touched
+    assert c.held(2) == []                                  # the int2 pool was never touched
 
 
 def test_precision_promotion_is_a_miss_that_drops_the_lower_format():
@@ -71,6 +71,26 @@ def test_protected_slots_are_not_evicted():
         c.request("e", 16)               # no bf16 slots configured
     with pytest.raises(ValueError):
         c.request("e", 8)
+
+
+def test_a_promotion_that_finds_no_room_leaves_the_cache_as_it_was():
+    """One slot per format; A resident at 2 bits, B protected in the only int4 slot: asking for A at 4 bits cannot be
+    served, and A must still be resident at 2 bits afterwards (both managers)."""
+    c = MixedPrecisionCache({4: 1, 2: 1})
+    c.request("A", 2)
+    b = c.request("B", 4)
+    with pytest.raises(RuntimeError):
+        c.request("A", 4, protect={b.slot})
+    assert c.resident("A") == (2, 0) and c.resident("B") == (4, 0) and c.covers("A", 2)
+    assert c.request("A", 2).kind == "hit"
+    from paper_2603_19172_amd.cache import ByteBudgetCache
+    d = ByteBudgetCache(2 * 1024, {4: 1024, 2: 512})        # two blocks of one int4 or two int2 experts
+    d.request("A", 2)
+    b = d.request("B", 4)
+    x = d.request("X", 2)                                   # shares A's block
+    with pytest.raises(RuntimeError):
+        d.request("A", 4, protect={b.slot, x.slot})         # B's block is protected, A's own block holds X
+    assert d.resident("A") == (2, 0) and d.request("A", 2).kind == "hit" and d.resident("X") is not None
 
 
 def test_covers_predicts_the_outcome_of_a_request():

@@ -95,17 +95,25 @@ def _check_against_oracle(outs, trace, routers_np, expert_matrices, floor, tiers
         run_bits = [dict(zip(ex, used)) for (ex, _, used) in trace[s]]
         ref_h, log, _ = O.decode_stack(x, routers_np, expert_matrices, 2, tiers[0], tiers[1], floor, 0.25,
                                        run_bits=run_bits)
-        if not all(margin_ok(lg, 2).all() for (_, _, lg, _) in log):
-            continue                     # a near tie somewhere in the stack: decisions may legitimately differ
-        checked += 1
-        for l, (idx, bts, _, _) in enumerate(log):
+        # decisions are compared layer by layer up to the first near tie of the oracle's logits (from there on the
+        # two sides may legitimately part); the hidden state only when no layer had one
+        clear = 0
+        for l, (idx, bts, lg, _) in enumerate(log):
+            if not margin_ok(lg, 2).all():
+                break
             assert trace[s][l][0] == tuple(int(v) for v in idx[0])
             assert trace[s][l][1] == tuple(int(v) for v in bts)            # the assignment itself
+            clear += 1
+        if clear < len(log):
+            continue
+        checked += 1
         got = synth.bf16_bits_to_f32(bits_of(h_dev)).astype(np.float64)
         want = synth.bf16_bits_to_f32(ref_h).astype(np.float64)
         # unit-RMS rows; the FFN tolerance (2e-2 of a row's RMS, scaled by alpha) accumulates over the layers
         assert np.abs(got - want).max() <= 2e-2
-    assert checked >= 1
+    # the seeded inputs are fixed: near ties (a gap under 1e-4 somewhere in L layers x top-3 logits) may take out a
+    # third of a run's steps at most
+    assert checked >= max(1, (2 * len(outs)) // 3), (checked, len(outs))
 
 
 def test_stack_decode_matches_the_oracle_and_prefetch_changes_nothing(ctx):
@@ -129,6 +137,32 @@ def test_stack_decode_matches_the_oracle_and_prefetch_changes_nothing(ctx):
     assert stats[True]["prefetch_issued"] > 0
     assert stats[True]["miss"] <= stats[False]["miss"]
     _check_against_oracle(outs[True], traces[True], routers_np, expert_matrices, floor)
+
+
+def test_stack_lookahead_by_the_expected_value_rule_changes_nothing_but_the_copies(ctx):
+    """lookahead="expected": no speculative copy before a layer's compute time has been measured (two steps), then
+    copies whose expected gain covers their expected cost; the hidden states are those of the run without look-ahead."""
+    L, steps = 4, 6
+    outs, stats = {}, {}
+    for mode in ("off", "expected"):
+        H, F, E, k = 256, 512, 8, 2
+        stack, routers_np, expert_matrices, floor, cfg0 = _small_stack(ctx, L, 6, mode != "off", 2100)
+        stack.lookahead = "expected"
+        hs = []
+        for s in range(steps):
+            x, _ = synth.activations(synth.scaled(cfg0, config_id=2200 + s))
+            hs.append(stack.step(to_bf16(x)).clone())
+        stack.close()
+        outs[mode], stats[mode] = hs, dict(stack.stats)
+        if mode == "expected":
+            assert stack.layer_ms is not None and stack.layer_ms > 0 and stack.link_gbps > 0
+            assert 0.0 < stack._pred_right / stack._pred_seen <= 1.0
+    for a, b in zip(outs["off"], outs["expected"]):
+        assert torch.equal(a, b)
+    st = stats["expected"]
+    assert st.get("prefetch_declined", 0) > 0                       # the first two steps at least
+    assert st.get("prefetch_issued", 0) + st.get("prefetch_declined", 0) > 0
+    assert _uses(st) == L * 2 * steps
 
 
 def test_stack_with_room_for_everything_copies_each_expert_once(ctx):
@@ -326,8 +360,7 @@ def test_stack_overlap_report_accounts_for_copy_and_waiting_time(ctx):
         stack.close()
         assert rep[prefetch]["copy_ms"] > 0 and rep[prefetch]["stall_ms"] >= 0
         assert rep[prefetch]["copy_time_hidden"] <= 1.0
-    # without look-ahead every copy is waited for in full (the waiting time holds the copy time)
-    assert rep[False]["stall_ms"] >= 0.8 * rep[False]["copy_ms"]
+    # (how much of the copy time the look-ahead hides is a measurement: bench.py reports it per plan)
 
 
 @pytest.mark.parametrize("layout", [B.LAYOUT_ROWMAJOR, B.LAYOUT_TILE])

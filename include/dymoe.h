@@ -361,6 +361,27 @@ int dymoe_moe_ffn_mixed(dymoe_ctx* ctx, const void* x, const int32_t* idx, const
                         void* y, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * A whole decode step on resident formats in two launches: dymoe_decode_front
+ * (Sec. 4.2.2 Eq. 3 importance, Sec. 4.3 assignment) and dymoe_moe_ffn_mixed on its
+ * GEMV path (Sec. 4.1: the executor on the mixed-precision weight set), with the
+ * front end worked out by every workgroup of the FFN's first launch for itself
+ * instead of by a launch of its own: a decode layer is a few tens of microseconds
+ * of weight streaming, and a launch boundary plus the front end's own chain of
+ * memory latencies is a tenth of that.  Arguments, layouts, limits and errors are
+ * those of the two calls; every output (idx, w, probs, importance, load, bits,
+ * rank, y) holds bit for bit what dymoe_decode_front followed by
+ * dymoe_moe_ffn_mixed(path = DYMOE_PATH_GEMV) writes.  The formats the assignment
+ * may name must already be materialised in `table` (row-major codes).
+ * DYMOE_ENOTSUP outside T <= 4, E <= 64, k <= 8, H a multiple of 64 up to 8192:
+ * the caller then makes the two calls.
+ */
+int dymoe_decode_step(dymoe_ctx* ctx, const void* x, const void* wg, const float* bias, int T, int H, int F,
+                      int E, int k, int renorm, int n_tiers, const int32_t* tier_count, const uint8_t* tier_bits,
+                      int floor_bits, const dymoe_expert_fmt* table, int group, int out_dtype, int32_t* idx,
+                      float* w, float* probs, float* importance, int32_t* load, uint8_t* bits, int32_t* rank,
+                      void* y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Diagnostic (tests, profiling): where the grouped-GEMM path of dymoe_moe_ffn_mixed leaves its token
  * grouping in the workspace, so that a caller can see which (token, slot) pair went to which row of which
  * tile (paper Sec. 4.2.1: the per-expert token lists Tokens_j).  Returns the byte offset of an int32 array

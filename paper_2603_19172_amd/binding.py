@@ -38,7 +38,7 @@ EXPORTS = [
     "dymoe_gptq_factor_workspace_bytes", "dymoe_gptq_factor",
     "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_pack_code_tiles", "dymoe_moe_ffn_mixed", "dymoe_moe_ffn_mixed_noalloc",
     "dymoe_stream_copy", "dymoe_mfma_peak",
-    "dymoe_decode_front", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
+    "dymoe_decode_front", "dymoe_decode_step", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
     "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
     "dymoe_cache_create", "dymoe_cache_create_pools", "dymoe_cache_destroy", "dymoe_cache_request", "dymoe_cache_lookup",
     "dymoe_cache_block_bytes", "dymoe_cache_bytes_resident",
@@ -96,6 +96,9 @@ lib.dymoe_ffn_plan_offset.argtypes = [_i] * 5
 lib.dymoe_decode_front.restype = _i
 lib.dymoe_decode_front.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _i,
                                    _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.dymoe_decode_step.restype = _i
+lib.dymoe_decode_step.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _vp, _i, _i,
+                                  _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.dymoe_prefetch_submit.restype = _i
 lib.dymoe_prefetch_submit.argtypes = [_vp, _vp, _vp, _sz, _vp, C.POINTER(_vp)]
 lib.dymoe_prefetch_wait.restype = _i

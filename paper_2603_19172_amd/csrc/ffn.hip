@@ -1,6 +1,7 @@
 // dymoe_moe_ffn_mixed: argument checks and the choice between the decode
 // (GEMV) and prefill (grouped GEMM) paths.
 #include "common.hpp"
+#include "assign.hpp"
 #include "ffn_layout.hpp"
 
 // Scratch of the entry point that allocates nothing.  One copy per GPU the library runs on, held until the
@@ -25,6 +26,11 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
                     const dymoe_expert_fmt* table, int T, int H, int F, int E, int k,
                     int out_dtype, void* y, void* workspace, hipStream_t st);
 bool ffn_gemm_fits(int T, int H, int F, int E, int k);
+bool decode_fused_fits(int T, int H, int E, int k);
+int decode_fused_launch(dymoe_ctx* ctx, const void* x, const void* wg, const float* bias, const TierTable& tt,
+                        int floor_bits, const dymoe_expert_fmt* table, int T, int H, int F, int E, int k, int renorm,
+                        int out_dtype, int32_t* idx, float* w, float* probs, float* importance, int32_t* load,
+                        uint8_t* bits, int32_t* rank, void* y, void* workspace, hipStream_t st);
 }  // namespace dymoe
 
 // Argument checks shared by the two entry points; on DYMOE_OK *path holds the path that will run.
@@ -89,4 +95,27 @@ extern "C" int dymoe_moe_ffn_mixed_noalloc(dymoe_ctx* ctx, const void* x, const 
         : dymoe::ffn_gemm_launch(ctx, x, idx, w, bits, table, T, H, F, E, k, out_dtype, y, ws, (hipStream_t)stream);
     ctx->timing_mask = mask;
     return out;
+}
+
+extern "C" int dymoe_decode_step(dymoe_ctx* ctx, const void* x, const void* wg, const float* bias, int T, int H, int F,
+                                 int E, int k, int renorm, int n_tiers, const int32_t* tier_count,
+                                 const uint8_t* tier_bits, int floor_bits, const dymoe_expert_fmt* table, int group,
+                                 int out_dtype, int32_t* idx, float* w, float* probs, float* importance,
+                                 int32_t* load, uint8_t* bits, int32_t* rank, void* y, void* workspace,
+                                 size_t workspace_bytes, void* stream)
+{
+    // the front end's checks, then the FFN's
+    DYMOE_REQUIRE(T >= 1 && H > 0 && F > 0 && E > 0 && k > 0 && k <= E && H % 8 == 0);
+    DYMOE_REQUIRE(x && wg && idx && w && importance && load && bits);
+    DYMOE_REQUIRE(dymoe_aligned(x, 16) && dymoe_aligned(wg, 16));
+    DYMOE_REQUIRE(floor_bits == 0 || floor_bits == 2 || floor_bits == 4 || floor_bits == 8 || floor_bits == 16);
+    dymoe::TierTable tt;
+    DYMOE_REQUIRE(dymoe::make_tier_table(E, n_tiers, tier_count, tier_bits, tt) == DYMOE_OK);
+    int path = DYMOE_PATH_GEMV;
+    const int rc = ffn_check(x, idx, w, bits, table, T, H, F, E, k, group, out_dtype, &path, y, workspace, workspace_bytes);
+    if (rc != DYMOE_OK) return rc;
+    if (!dymoe::decode_fused_fits(T, H, E, k)) return DYMOE_ENOTSUP;
+    if (!ctx) return DYMOE_ENOCTX;
+    return dymoe::decode_fused_launch(ctx, x, wg, bias, tt, floor_bits, table, T, H, F, E, k, renorm, out_dtype, idx, w,
+                                      probs, importance, load, bits, rank, y, workspace, (hipStream_t)stream);
 }

@@ -27,7 +27,9 @@
 #include <math.h>
 
 #include "common.hpp"
+#include "assign.hpp"
 #include "ffn_layout.hpp"
+#include "route_device.hpp"
 
 namespace dymoe {
 
@@ -382,19 +384,12 @@ __device__ __forceinline__ void phase1_bf16(const ExpertMat& m1, const ExpertMat
                           });
 }
 
+// One (token, expert) pair p: rows [f_begin, f_end) of W1 and W3 of expert e at b bits.
 template <int NSEG>
-__global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
-    const uint16_t* __restrict__ x, const int32_t* __restrict__ idx,
-    const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table, int H, int F,
-    int E, int k, int rows_per_block, float* __restrict__ hbuf)
+__device__ __forceinline__ void phase1_pair(const uint16_t* __restrict__ x, const dymoe_expert_fmt* __restrict__ table,
+                                            int p, int e, int b, int H, int F, int k, int rows_per_block,
+                                            float* __restrict__ hbuf)
 {
-    // pairs in reverse: a token's later slots carry the less important experts, hence the narrower formats,
-    // whose workgroups are short and latency-bound; dispatched first they overlap the wide ones instead of forming the tail
-    const int p = (int)gridDim.y - 1 - (int)blockIdx.y;
-    const int e = idx[p];
-    if (e < 0 || e >= E) return;
-    const int b = bits[e];
-    if (b != 16 && b != 8 && b != 4 && b != 2) return;
     const int t = p / k;
     const int f_begin = blockIdx.x * rows_per_block;
     const int f_end = min(F, f_begin + rows_per_block);
@@ -410,6 +405,87 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
     } else {
         phase1_quant<2, NSEG>(pick_mat(ex, 0, 2), pick_mat(ex, 1, 2), xrow, H, f_begin, f_end, hrow);
     }
+}
+
+template <int NSEG>
+__global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
+    const uint16_t* __restrict__ x, const int32_t* __restrict__ idx,
+    const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table, int H, int F,
+    int E, int k, int rows_per_block, float* __restrict__ hbuf)
+{
+    // pairs in reverse: a token's later slots carry the less important experts, hence the narrower formats,
+    // whose workgroups are short and latency-bound; dispatched first they overlap the wide ones instead of forming the tail
+    const int p = (int)gridDim.y - 1 - (int)blockIdx.y;
+    const int e = idx[p];
+    if (e < 0 || e >= E) return;
+    const int b = bits[e];
+    if (b != 16 && b != 8 && b != 4 && b != 2) return;
+    phase1_pair<NSEG>(x, table, p, e, b, H, F, k, rows_per_block, hbuf);
+}
+
+// The first phase with the decode step's front end in front of it (router gating and top-k, decode importance,
+// bit-width assignment: the arithmetic of dymoe_decode_front, same device functions, same order of every sum, so the
+// same bits).  Every workgroup works the front end out for itself, in LDS, from the router (64 KiB for 8 experts of
+// 4096: read from L2 by all but the first workgroups) and goes on to its rows without a launch boundary and without
+// the chain of dependent loads (pair -> expert -> bit width) the stand-alone kernel starts with; workgroup (0, 0)
+// also writes the front end's outputs to memory for the second phase and for the caller.
+// Limits (checked by the launcher): T <= kFusedMaxTokens, E <= 64, k <= kFusedMaxK.
+constexpr int kFusedMaxTokens = 4, kFusedMaxK = 8, kFusedMaxE = 64;
+
+template <int NSEG, int NCH>
+__global__ __launch_bounds__(kGvThreads) void decode_fused_phase1_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg, const float* __restrict__ bias,
+    const dymoe_expert_fmt* __restrict__ table, int T, int H, int F, int E, int k, int renorm, TierTable tiers,
+    int floor_bits, int rows_per_block, int32_t* __restrict__ idx, float* __restrict__ w, float* __restrict__ probs,
+    float* __restrict__ importance, int32_t* __restrict__ load, uint8_t* __restrict__ bits,
+    int32_t* __restrict__ rank, float* __restrict__ hbuf)
+{
+    __shared__ float s_logit[kFusedMaxE];
+    __shared__ float s_selp[kFusedMaxK];
+    __shared__ float s_imp[kFusedMaxE];
+    __shared__ int32_t s_load[kFusedMaxE];
+    __shared__ int32_t s_idx[kFusedMaxTokens * kFusedMaxK];
+    __shared__ float s_w[kFusedMaxTokens * kFusedMaxK];
+    __shared__ float s_probs[kFusedMaxTokens * kFusedMaxE];
+    __shared__ uint8_t s_bits[kFusedMaxE];
+    __shared__ int32_t s_rank[kFusedMaxE];
+    const int wave = threadIdx.x / kWave;
+    for (int e = threadIdx.x; e < E; e += kGvThreads) {
+        s_imp[e] = 0.0f;
+        s_load[e] = 0;
+    }
+    for (int t = 0; t < T; t++) {
+        route_logits<1, NCH, kGvWaves>(x, wg, bias, T, H, E, t, s_logit);
+        __syncthreads();
+        if (wave == 0) route_select_fixed<1>(s_logit, s_selp, t, E, k, renorm, s_idx, s_w, s_probs, s_imp, s_load);
+        __syncthreads();
+    }
+    for (int e = threadIdx.x; e < E; e += kGvThreads) {
+        const float g = s_imp[e];
+        s_imp[e] = (T <= 1) ? g : g / (float)T;
+    }
+    __syncthreads();
+    assign_all<float>(kGvThreads, E, s_imp, s_load, tiers, floor_bits, s_bits, s_rank);
+    __syncthreads();
+    if (blockIdx.x == 0 && blockIdx.y == 0) {
+        for (int i = threadIdx.x; i < T * k; i += kGvThreads) {
+            idx[i] = s_idx[i];
+            w[i] = s_w[i];
+        }
+        if (probs)
+            for (int i = threadIdx.x; i < T * E; i += kGvThreads) probs[i] = s_probs[i];
+        for (int e = threadIdx.x; e < E; e += kGvThreads) {
+            importance[e] = s_imp[e];
+            load[e] = s_load[e];
+            bits[e] = s_bits[e];
+            if (rank) rank[e] = s_rank[e];
+        }
+    }
+    const int p = (int)gridDim.y - 1 - (int)blockIdx.y;
+    const int e = s_idx[p];
+    const int b = s_bits[e];
+    if (b != 16 && b != 8 && b != 4 && b != 2) return;
+    phase1_pair<NSEG>(x, table, p, e, b, H, F, k, rows_per_block, hbuf);
 }
 
 // ---------------------------------------------------------------- phase 2
@@ -646,6 +722,35 @@ __global__ __launch_bounds__(kP2MaxWaves * kWave) void gemv_phase2_kernel(
     }
 }
 
+// rows per workgroup of the first phase: 64 on the Mixtral-shaped decode layer (measured: beat 16..128), which makes 448
+// workgroups; smaller layers get fewer rows per workgroup so that the launch still fills the chip
+static int phase1_rows_per_block(long rows_total)
+{
+    int r = 64;
+    while (r > 8 && rows_total / r < 384) r >>= 1;
+    return r;
+}
+
+static int phase2_launch(dymoe_ctx* ctx, const float* hbuf, const int32_t* idx, const float* w, const uint8_t* bits,
+                         const dymoe_expert_fmt* table, int T, int H, int F, int E, int k, int out_dtype, void* y,
+                         hipStream_t st)
+{
+    // as many wavefronts as (slot, segment) units, at most kP2MaxWaves; of the counts that need the
+    // fewest rounds the smallest, so that no wavefront idles through the last round
+    const int nseg2 = (F + kSeg - 1) / kSeg;
+    const int units = k * nseg2;
+    int nwaves = units < kP2MaxWaves ? units : kP2MaxWaves;
+    {
+        const int rounds = (units + nwaves - 1) / nwaves;
+        while (nwaves > 1 && (units + nwaves - 2) / (nwaves - 1) == rounds) nwaves--;
+    }
+    const dim3 g2((unsigned)((H + kP2Rows - 1) / kP2Rows), (unsigned)T);
+    dymoe_launch(ctx, DYMOE_K_GEMV_PHASE2, gemv_phase2_kernel, g2, dim3((unsigned)(nwaves * kWave)), 0, st, hbuf, idx, w,
+                 bits, table, H, F, E, k, nseg2, out_dtype, y);
+    DYMOE_HIP_LAUNCH_CHECK();
+    return DYMOE_OK;
+}
+
 int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const float* w,
                     const uint8_t* bits, const dymoe_expert_fmt* table, int T, int H, int F, int E,
                     int k, int out_dtype, void* y, void* workspace, hipStream_t st)
@@ -654,15 +759,7 @@ int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     float* hbuf = reinterpret_cast<float*>((char*)workspace + L.hbuf);
     const int P = T * k;
     const int nseg1 = (H + kSeg - 1) / kSeg;
-    const int nseg2 = (F + kSeg - 1) / kSeg;
-    // phase 1, rows per workgroup: 64 on the Mixtral-shaped decode layer (measured: beat 16..128), which makes 448
-    // workgroups; smaller layers get fewer rows per workgroup so that the launch still fills the chip
-    auto rows_for = [](long rows_total, long want_groups) {
-        int r = 64;
-        while (r > 8 && rows_total / r < want_groups) r >>= 1;
-        return r;
-    };
-    const int rows1 = rows_for((long)F * P, 384);
+    const int rows1 = phase1_rows_per_block((long)F * P);
     const dim3 g1((unsigned)((F + rows1 - 1) / rows1), (unsigned)P);
     const uint16_t* xb = (const uint16_t*)x;
     {
@@ -675,19 +772,42 @@ int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
         }
     }
     DYMOE_HIP_LAUNCH_CHECK();
-    // phase 2: as many wavefronts as (slot, segment) units, at most kP2MaxWaves; of the counts that need the
-    // fewest rounds the smallest, so that no wavefront idles through the last round
-    const int units = k * nseg2;
-    int nwaves = units < kP2MaxWaves ? units : kP2MaxWaves;
-    {
-        const int rounds = (units + nwaves - 1) / nwaves;
-        while (nwaves > 1 && (units + nwaves - 2) / (nwaves - 1) == rounds) nwaves--;
+    return phase2_launch(ctx, hbuf, idx, w, bits, table, T, H, F, E, k, out_dtype, y, st);
+}
+
+// Whether the fused decode step covers these sizes.
+bool decode_fused_fits(int T, int H, int E, int k)
+{
+    return T >= 1 && T <= kFusedMaxTokens && E <= kFusedMaxE && k <= kFusedMaxK && H % 64 == 0 && H <= 4 * kSeg;
+}
+
+int decode_fused_launch(dymoe_ctx* ctx, const void* x, const void* wg, const float* bias, const TierTable& tt,
+                        int floor_bits, const dymoe_expert_fmt* table, int T, int H, int F, int E, int k, int renorm,
+                        int out_dtype, int32_t* idx, float* w, float* probs, float* importance, int32_t* load,
+                        uint8_t* bits, int32_t* rank, void* y, void* workspace, hipStream_t st)
+{
+    const FfnLayout L = ffn_layout(T, H, F, E, k);
+    float* hbuf = reinterpret_cast<float*>((char*)workspace + L.hbuf);
+    const int P = T * k;
+    const int nseg1 = (H + kSeg - 1) / kSeg;
+    const int rows1 = phase1_rows_per_block((long)F * P);
+    const dim3 g1((unsigned)((F + rows1 - 1) / rows1), (unsigned)P);
+    const uint16_t* xb = (const uint16_t*)x;
+    const uint16_t* wb = (const uint16_t*)wg;
+    // NCH: 16-byte chunks of an activation row per lane, as in dymoe_decode_front (8 up to 4096 columns, then 16)
+#define DYMOE_FUSED(NSEG_, NCH_)                                                                                        \
+    dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (decode_fused_phase1_kernel<NSEG_, NCH_>), g1, dim3(kGvThreads), 0, st, xb, wb,  \
+                 bias, table, T, H, F, E, k, renorm, tt, floor_bits, rows1, idx, w, probs, importance, load, bits, rank, hbuf)
+    switch (nseg1) {
+    case 1: DYMOE_FUSED(1, 8); break;
+    case 2: DYMOE_FUSED(2, 8); break;
+    case 3: DYMOE_FUSED(3, 16); break;
+    case 4: DYMOE_FUSED(4, 16); break;
+    default: return DYMOE_ENOTSUP;
     }
-    const dim3 g2((unsigned)((H + kP2Rows - 1) / kP2Rows), (unsigned)T);
-    dymoe_launch(ctx, DYMOE_K_GEMV_PHASE2, gemv_phase2_kernel, g2, dim3((unsigned)(nwaves * kWave)), 0, st, hbuf, idx, w,
-                 bits, table, H, F, E, k, nseg2, out_dtype, y);
+#undef DYMOE_FUSED
     DYMOE_HIP_LAUNCH_CHECK();
-    return DYMOE_OK;
+    return phase2_launch(ctx, hbuf, idx, w, bits, table, T, H, F, E, k, out_dtype, y, st);
 }
 
 }  // namespace dymoe

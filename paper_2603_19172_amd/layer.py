@@ -117,11 +117,28 @@ class MoELayer:
                                           self.imp.data_ptr(), self.load.data_ptr(), self.bits.data_ptr(),
                                           self.rank.data_ptr(), st), "dymoe_decode_front")
 
+    def decode_step(self, x, wg, bias, store, st):
+        """S1 + S2 + S3 + S5 of a small decode step on resident formats in two launches; False when the sizes are
+        outside what the fused step covers (the caller then makes the separate calls)."""
+        rc = B.lib.dymoe_decode_step(self.ctx._h, x.data_ptr(), wg.data_ptr(), bias.data_ptr() if bias is not None else None,
+                                     self.T, self.H, self.F, self.E, self.k, 1, self._nt, C.cast(self._tc, C.c_void_p),
+                                     C.cast(self._tb, C.c_void_p), self.floor_bits, store.table.data_ptr(), self.group,
+                                     self.out_dtype, self.idx.data_ptr(), self.gate.data_ptr(), self.probs.data_ptr(),
+                                     self.imp.data_ptr(), self.load.data_ptr(), self.bits.data_ptr(),
+                                     self.rank.data_ptr(), self.y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, st)
+        if rc == B.ENOTSUP:
+            return False
+        B._check(rc, "dymoe_decode_step")
+        return True
+
     def step(self, x, wg, bias, store, quantize=True, stream=None, fused_front=True):
         """The whole hot path for one batch.  quantize=False assumes the formats
         the assignment selects are already materialised in `store`.  Small decode
         steps take the single-launch front end unless fused_front is False."""
         st = B._stream(stream)
+        if (fused_front and not quantize and self.phase == B.PHASE_DECODE and self.path != B.PATH_GEMM
+                and self.layout == B.LAYOUT_ROWMAJOR and self.decode_step(x, wg, bias, store, st)):
+            return self.y
         if fused_front and self.phase == B.PHASE_DECODE and self.T <= B.FRONT_MAX_TOKENS:
             self.front(x, wg, bias, st)
         else:

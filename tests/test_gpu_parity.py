@@ -1,6 +1,8 @@
 """GPU parity: every entry point of libdymoe.so against the CPU oracle, element
 by element, on the same seeded inputs.  Sizes span several tiles and ragged
 tails; the oracle finishes each case in seconds."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -618,6 +620,64 @@ def test_decode_front_equals_the_three_calls_and_the_oracle(ctx, T, H, E, k, tie
     rbits, rrank = O.assign_precision(imp.cpu().numpy().astype(np.float64), rload, tiers, tier_bits)
     assert np.array_equal(bits.cpu().numpy(), rbits)
     assert np.array_equal(rank.cpu().numpy(), rrank)
+
+
+# ------------------------------------------------------------------ the decode step in two launches
+
+@pytest.mark.parametrize("T,H,F,E,k,tiers,tier_bits,floor", [
+    (1, 256, 512, 8, 2, (2, 3, 3), (16, 4, 2), 0),            # the tiny layer, one token
+    (4, 320, 704, 8, 2, (1, 3, 4), (16, 4, 2), 4),            # ragged widths, a floor, four tokens
+    (2, 512, 256, 64, 8, (8, 16, 16, 24), (16, 8, 4, 2), 0),  # 64 experts, top-8, the four-format ladder
+    (1, 4096, 1024, 8, 2, (1, 3, 4), (16, 4, 2), 0),          # the decode layer's hidden size (two segments)
+    (3, 6144, 256, 16, 4, (4, 4, 8), (16, 4, 0), 0),          # three segments, skipped experts
+])
+def test_decode_step_equals_the_front_end_and_the_ffn_call_by_call(ctx, T, H, F, E, k, tiers, tier_bits, floor):
+    """dymoe_decode_step: every output bit for bit what dymoe_decode_front followed by dymoe_moe_ffn_mixed (GEMV
+    path) writes; the FFN result against the oracle as well."""
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=T, H=H, F=F, E=E, k=k, phase="decode", config_id=3100 + H + T)
+    x, _ = synth.activations(cfg)
+    wg, _ = synth.router(cfg)
+    bias = np.linspace(-0.2, 0.2, E).astype(np.float32) if E > 8 else None
+    mats = [synth.expert_weights(cfg, e) for e in range(E)]
+    store = ExpertStore([[to_bf16(m) for m in mats[e]] for e in range(E)], H, F, DEV, formats=(8, 4, 2))
+    xd, wgd = to_bf16(x), to_bf16(wg)
+    bd = torch.from_numpy(bias).to(DEV) if bias is not None else None
+    # every format of every expert, so that whatever the assignment names is there
+    for b in (8, 4, 2):
+        forced = torch.full((E,), b, dtype=torch.uint8, device=DEV)
+        ctx.quantize_experts(store.table, forced, None, E, H, F, layout=B.LAYOUT_ROWMAJOR)
+    lay_a = MoELayer(ctx, T, H, F, E, k, "decode", tiers, tier_bits, floor_bits=floor, out_dtype=B.OUT_F32, device=DEV)
+    lay_b = MoELayer(ctx, T, H, F, E, k, "decode", tiers, tier_bits, floor_bits=floor, out_dtype=B.OUT_F32, device=DEV)
+    st = B._stream(None)
+    lay_a.y.fill_(float("nan"))
+    assert lay_a.decode_step(xd, wgd, bd, store, st)
+    lay_b.front(xd, wgd, bd, st)
+    lay_b.path = B.PATH_GEMV
+    lay_b.ffn(xd, store, st)
+    sync()
+    for name in ("idx", "gate", "probs", "imp", "load", "bits", "rank"):
+        assert torch.equal(getattr(lay_a, name), getattr(lay_b, name)), name
+    assert torch.equal(lay_a.y.view(torch.int32), lay_b.y.view(torch.int32))
+    # the oracle, told the GPU's own decisions
+    gidx, gw, gbits = lay_a.idx.cpu().numpy(), lay_a.gate.cpu().numpy().astype(np.float64), lay_a.bits.cpu().numpy()
+    need = set(int(e) for e in gidx.ravel())
+    experts = [({"w": mats[e]} if gbits[e] == 16 else {"q": oracle_quantize_expert(mats[e], int(gbits[e]))})
+               if (e in need and gbits[e] != 0) else {} for e in range(E)]
+    mb = np.array([gbits[e] if e in need else 0 for e in range(E)], np.uint8)
+    if mb.any():
+        ref = O.moe_ffn_mixed(x, gidx, gw, mb, experts)
+        assert rel_err_per_token(lay_a.y.cpu().numpy().astype(np.float64), ref) <= FFN_TOL
+
+
+def test_decode_step_declines_what_it_does_not_cover(ctx):
+    one = torch.zeros((4096,), dtype=torch.uint8, device=DEV)
+    tc, tb = (ctypes.c_int32 * 1)(80), (ctypes.c_uint8 * 1)(16)
+    args = lambda T, E, k: (ctx._h, one.data_ptr(), one.data_ptr(), None, T, 256, 512, E, k, 1, 1, tc, tb, 0, one.data_ptr(),
+                            64, B.OUT_F32) + (one.data_ptr(),) * 8 + (one.data_ptr(), 1 << 30, B._stream(None))
+    tc[0] = 8
+    assert B.lib.dymoe_decode_step(*args(5, 8, 2)) == B.ENOTSUP          # more than four tokens
+    tc[0] = 80
+    assert B.lib.dymoe_decode_step(*args(1, 80, 2)) == B.ENOTSUP         # more than 64 experts
 
 
 # ------------------------------------------------------------------ measurement aid

@@ -47,6 +47,9 @@ extern "C" {
 #define DYMOE_ENOTSUP (-4) /* valid in principle, outside what the kernels cover */
 #define DYMOE_ENOCTX (-5)  /* context is NULL (checked after the other arguments) */
 
+/* bits of the per-device condition word (dymoe_device_flags) */
+#define DYMOE_FLAG_FORMAT_MISSING 1u /* an expert with tokens was assigned a precision its table entry does not hold */
+
 #define DYMOE_PHASE_PREFILL 0
 #define DYMOE_PHASE_DECODE 1
 
@@ -80,7 +83,14 @@ typedef struct dymoe_ctx dymoe_ctx;
  * paper's precision spectrum, Sec. 1).  wt: optional copy of w in the tile layout
  * (dymoe_pack_tiles), read by the GEMM path for 16-bit experts; when NULL that
  * path reads w row by row (slower).
- * Entries for precisions that are never selected may be NULL.
+ * Entries for precisions that are never selected may be NULL.  The precisions are
+ * chosen on the device, so no host check can know which entries a launch will read:
+ * dymoe_moe_ffn_mixed, dymoe_decode_step and dymoe_quantize_experts test the pointers
+ * of the selected format (for 16 bits w, for 8 / 4 / 2 the codes, scales and zeros,
+ * of all three matrices; for the quantiser also its source w) before the first
+ * access, leave the expert out as if it had been assigned 0 bits when one is NULL
+ * (the quantiser writes nothing for it), and raise DYMOE_FLAG_FORMAT_MISSING in the
+ * device's condition word (dymoe_device_flags).  A non-NULL pointer is trusted.
  * The table lives in device memory ([E] of these).
  *
  * Two layouts of a packed [N,K] matrix exist, with the same bytes in a
@@ -116,6 +126,26 @@ typedef struct {
 /* Create / destroy a context bound to HIP device `device`.  Host calls. */
 int dymoe_create(dymoe_ctx** out, int device);
 void dymoe_destroy(dymoe_ctx* ctx);
+
+/*
+ * Conditions the kernels met and went on from since the last call of this function
+ * on the context's device (DYMOE_FLAG_*): waits for `stream`, copies the device's
+ * condition word to *flags and clears it when it was not zero.  One word per device
+ * and process, shared by every context on that device.  A host call that
+ * synchronises: not for use during stream capture, and not needed on the hot path
+ * (a caller whose tables hold every format its tiers and floors can name never
+ * sees a bit set).  Errors: DYMOE_EINVAL (flags NULL), DYMOE_ENOCTX, DYMOE_EHIP.
+ */
+int dymoe_device_flags(dymoe_ctx* ctx, unsigned* flags, void* stream);
+
+/*
+ * The test the kernels apply to a table entry before running its expert at `bits`
+ * (see dymoe_expert_fmt), on a HOST copy of the entry: 1 when every pointer of that
+ * format is non-NULL, 0 otherwise (also for a NULL entry or a bit width other than
+ * 16, 8, 4, 2).  Pure host function; lets a caller check a table against the
+ * precisions its tiers and floors can name before uploading it.
+ */
+int dymoe_format_present(const dymoe_expert_fmt* entry, int bits);
 
 /* Static, human-readable text of an error code. */
 const char* dymoe_strerror(int code);
@@ -385,7 +415,7 @@ int dymoe_decode_step(dymoe_ctx* ctx, const void* x, const void* wg, const float
  * Diagnostic (tests, profiling): where the grouped-GEMM path of dymoe_moe_ffn_mixed leaves its token
  * grouping in the workspace, so that a caller can see which (token, slot) pair went to which row of which
  * tile (paper Sec. 4.2.1: the per-expert token lists Tokens_j).  Returns the byte offset of an int32 array
- * laid out as counts[E] | offsets[E+1] | (E ints, unused) | ntiles, pairs (+6 unused) | perm[T*k]:
+ * laid out as counts[E] | offsets[E+1] | (E ints: the first E bytes hold the bit width each expert is run at) | ntiles, pairs (+6 unused) | perm[T*k]:
  * counts[e] = pairs routed to expert e at a non-zero precision, offsets = their exclusive prefix sums,
  * perm[offsets[e] + i] = the i-th pair (token * k + slot) of expert e, in the order the GEMM's tiles take
  * them (rows [128 j, 128 j + 128) of an expert form its j-th tile).  Pure host function; 0 for invalid sizes.

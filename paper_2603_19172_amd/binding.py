@@ -24,6 +24,7 @@ lib = C.CDLL(LIB_PATH)
 OK, EINVAL, ENOSPC, EHIP, ENOTSUP, ENOCTX = 0, -1, -2, -3, -4, -5
 PHASE_PREFILL, PHASE_DECODE = 0, 1
 FRONT_MAX_TOKENS = 16
+FLAG_FORMAT_MISSING = 1
 OUT_BF16, OUT_F32 = 0, 1
 PATH_AUTO, PATH_GEMV, PATH_GEMM = 0, 1, 2
 LAYOUT_ROWMAJOR, LAYOUT_TILE = 0, 1
@@ -37,7 +38,7 @@ EXPORTS = [
     "dymoe_gptq_workspace_bytes", "dymoe_gptq_quantize_pack", "dymoe_gptq_hessian",
     "dymoe_gptq_factor_workspace_bytes", "dymoe_gptq_factor",
     "dymoe_quantize_experts", "dymoe_pack_tiles", "dymoe_pack_code_tiles", "dymoe_moe_ffn_mixed", "dymoe_moe_ffn_mixed_noalloc",
-    "dymoe_stream_copy", "dymoe_mfma_peak",
+    "dymoe_stream_copy", "dymoe_mfma_peak", "dymoe_device_flags", "dymoe_format_present",
     "dymoe_decode_front", "dymoe_decode_step", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
     "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
     "dymoe_cache_create", "dymoe_cache_create_pools", "dymoe_cache_destroy", "dymoe_cache_request", "dymoe_cache_lookup",
@@ -113,6 +114,10 @@ lib.dymoe_attention_workspace_bytes.restype = _sz
 lib.dymoe_attention_workspace_bytes.argtypes = [_i, _i]
 lib.dymoe_token_score_attention.restype = _i
 lib.dymoe_token_score_attention.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, C.c_float, _i, _vp, _vp, _sz, _vp]
+lib.dymoe_device_flags.restype = _i
+lib.dymoe_device_flags.argtypes = [_vp, C.POINTER(C.c_uint), _vp]
+lib.dymoe_format_present.restype = _i
+lib.dymoe_format_present.argtypes = [_vp, _i]
 lib.dymoe_mfma_peak.restype = _i
 lib.dymoe_mfma_peak.argtypes = [_vp, _i, _i, _vp, _sz, C.POINTER(_d), _vp]
 lib.dymoe_stream_copy.restype = _i
@@ -197,6 +202,11 @@ def _stream(stream):
 
 def workspace_bytes(T, H, F, E, k) -> int:
     return int(lib.dymoe_workspace_bytes(T, H, F, E, k))
+
+
+def format_present(entry, bits) -> bool:
+    """Whether a host ExpertFmt holds every pointer that running its expert at `bits` reads (the kernels' own test)."""
+    return bool(lib.dymoe_format_present(C.byref(entry), int(bits)))
 
 
 def read_ffn_plan(ws, T, H, F, E, k):
@@ -450,6 +460,12 @@ class Context:
             raise ValueError("stream_copy: byte counts differ")
         _check(lib.dymoe_stream_copy(self._h, _ptr(src), _ptr(dst), n, _stream(stream)), "dymoe_stream_copy")
         return dst
+
+    def device_flags(self, stream=None) -> int:
+        """Conditions the kernels met and went on from since the last read (FLAG_*); waits for the stream, clears."""
+        v = C.c_uint(0)
+        _check(lib.dymoe_device_flags(self._h, C.byref(v), _stream(stream)), "dymoe_device_flags")
+        return int(v.value)
 
     def mfma_peak(self, iters, waves_per_simd, sink, stream=None):
         """Register-only bf16 MFMA loop (measurement aid); returns the floating-point operations of the launch."""

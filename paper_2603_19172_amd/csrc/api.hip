@@ -48,6 +48,7 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(float* __restrict__ sink
 }
 
 int ffn_static_scratch_address(void** out);
+int ffn_device_flags_address(unsigned** out);
 int ffn_gemm_init();
 
 }  // namespace dymoe
@@ -97,6 +98,7 @@ int dymoe_create(dymoe_ctx** out, int device)
     c->num_cu = prop.multiProcessorCount;
     c->timing_mask = 0;
     c->static_scratch = nullptr;
+    c->device_flags = nullptr;
     // per-device set-up, with that device current: the address of its copy of the static scratch array, and the
     // dynamic-LDS limit of the grouped-GEMM kernels (so that no later call has anything left to configure)
     int prev = 0;
@@ -104,6 +106,7 @@ int dymoe_create(dymoe_ctx** out, int device)
     if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(device) != hipSuccess) rc = DYMOE_EHIP;
     if (rc == DYMOE_OK) {
         rc = dymoe::ffn_static_scratch_address(&c->static_scratch);
+        if (rc == DYMOE_OK) rc = dymoe::ffn_device_flags_address(&c->device_flags);
         if (rc == DYMOE_OK) rc = dymoe::ffn_gemm_init();
         if (hipSetDevice(prev) != hipSuccess) rc = DYMOE_EHIP;
     }
@@ -113,6 +116,29 @@ int dymoe_create(dymoe_ctx** out, int device)
     }
     *out = c;
     return DYMOE_OK;
+}
+
+int dymoe_device_flags(dymoe_ctx* ctx, unsigned* flags, void* stream)
+{
+    DYMOE_REQUIRE(flags != nullptr);
+    if (!ctx) return DYMOE_ENOCTX;
+    if (!ctx->device_flags) return DYMOE_EHIP;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned v = 0;
+    if (hipMemcpyAsync(&v, ctx->device_flags, sizeof(v), hipMemcpyDeviceToHost, st) != hipSuccess) return DYMOE_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return DYMOE_EHIP;
+    if (v != 0) {
+        if (hipMemsetAsync(ctx->device_flags, 0, sizeof(v), st) != hipSuccess) return DYMOE_EHIP;
+        if (hipStreamSynchronize(st) != hipSuccess) return DYMOE_EHIP;
+    }
+    *flags = v;
+    return DYMOE_OK;
+}
+
+int dymoe_format_present(const dymoe_expert_fmt* entry, int bits)
+{
+    if (!entry) return 0;
+    return dymoe_fmt_present(*entry, bits) ? 1 : 0;
 }
 
 static void drop_timed(dymoe_ctx* ctx)

@@ -44,6 +44,7 @@ struct dymoe_ctx {
     int device;
     int num_cu;
     void* static_scratch;                    // device address of this GPU's scratch array (dymoe_moe_ffn_mixed_noalloc)
+    unsigned* device_flags;                  // device address of this GPU's condition word (dymoe_device_flags)
     unsigned timing_mask;                    // bit i set: time launches of kernel i
     std::vector<dymoe_timed_launch> timed;   // recorded, not yet read
 };
@@ -83,6 +84,24 @@ inline void dymoe_launch(dymoe_ctx* ctx, int kernel_id, void (*kernel)(KArgs...)
     } while (0)
 
 static inline bool dymoe_aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// Whether a table entry holds every pointer that running its expert at b bits reads: the three bf16 matrices for 16,
+// codes, scales and zeros of the three matrices for 8 / 4 / 2.  The bit widths are chosen on the device, so the host
+// cannot know which formats a launch will touch; the kernels ask this before the first access and leave out an
+// expert whose selected format is absent (raising DYMOE_FLAG_FORMAT_MISSING) instead of reading through NULL.
+// (Written out field by field: selecting one of the member arrays by a run-time index would force the entry into
+// private memory.)
+__host__ __device__ inline bool dymoe_fmt_present(const dymoe_expert_fmt& ex, int b)
+{
+    if (b == 16) return ex.w[0] && ex.w[1] && ex.w[2];
+    if (b == 8)
+        return ex.q8[0] && ex.q8[1] && ex.q8[2] && ex.s8[0] && ex.s8[1] && ex.s8[2] && ex.z8[0] && ex.z8[1] && ex.z8[2];
+    if (b == 4)
+        return ex.q4[0] && ex.q4[1] && ex.q4[2] && ex.s4[0] && ex.s4[1] && ex.s4[2] && ex.z4[0] && ex.z4[1] && ex.z4[2];
+    if (b == 2)
+        return ex.q2[0] && ex.q2[1] && ex.q2[2] && ex.s2[0] && ex.s2[1] && ex.s2[2] && ex.z2[0] && ex.z2[1] && ex.z2[2];
+    return false;
+}
 
 namespace dymoe {
 

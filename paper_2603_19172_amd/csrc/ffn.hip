@@ -9,6 +9,10 @@
 // device address comes from hipGetSymbolAddress (ffn_static_scratch_address) and is what every launch is given.
 static __device__ __align__(256) unsigned char scratch[DYMOE_STATIC_SCRATCH_BYTES];
 
+// Conditions the kernels met and went on from (DYMOE_FLAG_*), one word per GPU; read and cleared by
+// dymoe_device_flags.  Handled like the scratch array: launches are given the address, never the name.
+static __device__ unsigned device_flags;
+
 namespace dymoe {
 // Device address of this GPU's scratch array; the device must be current.
 int ffn_static_scratch_address(void** out)
@@ -16,6 +20,15 @@ int ffn_static_scratch_address(void** out)
     void* p = nullptr;
     if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return DYMOE_EHIP;
     *out = p;
+    return DYMOE_OK;
+}
+
+// Device address of this GPU's condition word; the device must be current.
+int ffn_device_flags_address(unsigned** out)
+{
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(device_flags)) != hipSuccess || p == nullptr) return DYMOE_EHIP;
+    *out = static_cast<unsigned*>(p);
     return DYMOE_OK;
 }
 

@@ -38,6 +38,8 @@ constexpr int kXsBufBytes = kGemmTileM * kBK * 2;   // one token tile in LDS: 12
 // ----------------------------------------------------------------------------
 // plan: counting sort of the (token, slot) pairs by expert + tile list
 // ints: counts[E] | offsets[E+1] | cursor[E] | ntiles (8 ints) | perm[P] | tiles[4*max_tiles] | draft[4*max_tiles]
+// (cursor: its first E BYTES hold the bit width every expert is run at, which is bits[e] unless the table lacks that
+// format, then 0; the GEMM and combine kernels read these instead of bits[])
 struct PlanPtrs {
     int32_t* counts;
     int32_t* offsets;
@@ -72,9 +74,10 @@ constexpr int kPlanPrivE = 256;        // 16 x 256 counters = 16 KiB
 constexpr int kPlanLdsTiles = 1024;    // 4 ints each = 16 KiB
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ idx,
-                                                            const uint8_t* __restrict__ bits, int P, int E,
+                                                            const uint8_t* __restrict__ bits,
+                                                            const dymoe_expert_fmt* __restrict__ table, int P, int E,
                                                             int tile_m, int max_tiles,
-                                                            int32_t* __restrict__ plan)
+                                                            int32_t* __restrict__ plan, unsigned* __restrict__ flags)
 {
     __shared__ int32_t s_count[DYMOE_MAX_EXPERTS];
     __shared__ int32_t s_off[DYMOE_MAX_EXPERTS + 1];
@@ -89,7 +92,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     int32_t* draft = (max_tiles <= kPlanLdsTiles) ? s_draft : pp.tiles + 4 * (size_t)max_tiles;
     for (int e = tid; e < E; e += kPlanThreads) {
         s_count[e] = 0;
-        s_bits[e] = bits[e];
+        int b = bits[e];
+        if (b == 16 || b == 8 || b == 4 || b == 2) {
+            // a format the table does not hold: the expert is left out, as at 0 bits.  Whether it had pairs is not
+            // known yet, but the decode path reports the same condition only for routed experts: checked below.
+            if (!dymoe_fmt_present(table[e], b)) b = 0x80 | b;
+        } else {
+            b = 0;
+        }
+        s_bits[e] = (uint8_t)b;
     }
     if (priv)
         for (int i = tid; i < kPlanWaves * E; i += kPlanThreads) s_priv[i] = 0;
@@ -98,7 +109,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
         e = idx[p];
         if (e < 0 || e >= E) return false;
         const int b = s_bits[e];
-        return b == 16 || b == 8 || b == 4 || b == 2;
+        if (b & 0x80) {                       // routed to, selected format absent: say so, leave the pair out
+            atomicOr(flags, DYMOE_FLAG_FORMAT_MISSING);
+            return false;
+        }
+        return b != 0;
     };
     for (int p = tid; p < P; p += kPlanThreads) {
         int e;
@@ -184,6 +199,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     for (int e = tid; e < E; e += kPlanThreads) {
         pp.counts[e] = s_count[e];
         pp.offsets[e] = s_off[e];
+        reinterpret_cast<uint8_t*>(pp.cursor)[e] = (s_bits[e] & 0x80) ? 0 : s_bits[e];
     }
     if (tid == 0) pp.offsets[E] = s_off[E];
     __syncthreads();
@@ -931,7 +947,10 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     int32_t* plan = reinterpret_cast<int32_t*>(ws + L.plan);
     const uint16_t* xb = (const uint16_t*)x;
 
-    dymoe_launch(ctx, DYMOE_K_PLAN, plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, idx, bits, P, E, kGemmTileM, L.max_tiles, plan);
+    dymoe_launch(ctx, DYMOE_K_PLAN, plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, idx, bits, table, P, E, kGemmTileM,
+                 L.max_tiles, plan, ctx->device_flags);
+    // what the kernels after the plan take as the bit widths: the plan's copy, 0 where the table lacks the format
+    const uint8_t* run_bits = reinterpret_cast<const uint8_t*>(plan_ptrs(plan, E, P).cursor);
     DYMOE_HIP_LAUNCH_CHECK();
     const long n16 = (long)T * H / 16;
     hipLaunchKernelGGL(prep_x_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, xb, n16, xh4, xh2, xh8);
@@ -941,7 +960,7 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const int cols1 = 32 * kGmWaves, cols2 = 64 * kGmWaves;
     const dim3 g1((unsigned)((F + cols1 - 1) / cols1), (unsigned)max_tiles);
     dymoe_launch(ctx, DYMOE_K_GEMM1, (gemm_kernel<1>), g1, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2, xh8,
-                 (const uint16_t*)nullptr, bits, table, plan, P, E, k, H, F, hbuf, (float*)nullptr, max_tiles, 1);
+                 (const uint16_t*)nullptr, run_bits, table, plan, P, E, k, H, F, hbuf, (float*)nullptr, max_tiles, 1);
     DYMOE_HIP_LAUNCH_CHECK();
     // The down projection has few output tiles: split K so that the launch still covers the chip (two workgroups per
     // compute unit, about one and a half rounds of them; measured on the Mixtral prefill: 2 to 7 splits lie within
@@ -959,11 +978,11 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const int units = max_tiles * splits;
     const dim3 g2((unsigned)(8 * nblk2 * ((units + 7) / 8)));
     dymoe_launch(ctx, DYMOE_K_GEMM2, (gemm_kernel<2>), g2, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2, xh8, hbuf,
-                 bits, table, plan, P, E, k, H, F, (uint16_t*)nullptr, opair, max_tiles, splits);
+                 run_bits, table, plan, P, E, k, H, F, (uint16_t*)nullptr, opair, max_tiles, splits);
     DYMOE_HIP_LAUNCH_CHECK();
     const long n4 = (long)T * (H / 4);
     dymoe_launch(ctx, DYMOE_K_GEMM_COMBINE, gemm_combine_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, opair,
-                 idx, w, bits, T, H, E, k, splits, out_dtype, y);
+                 idx, w, run_bits, T, H, E, k, splits, out_dtype, y);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }

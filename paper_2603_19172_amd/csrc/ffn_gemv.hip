@@ -185,6 +185,13 @@ __device__ __forceinline__ ExpertMat pick_mat(const dymoe_expert_fmt& ex, int ma
     return m;
 }
 
+// Whether the table held the pointers of this matrix at b bits.  The bit widths are chosen on the device, so only the
+// kernels can tell that an assigned format is absent; they test exactly the pointers they are about to read through.
+__device__ __forceinline__ bool mat_present(const ExpertMat& m, int b)
+{
+    return (b == 16) ? (m.w != nullptr) : (m.q != nullptr && m.s != nullptr && m.z != nullptr);
+}
+
 // what one lane loads of one row: NSEG segments starting at column seg0 * 2048
 template <int BITS, int NSEG> struct RowRegs;
 template <int NSEG> struct RowRegs<16, NSEG> { uint4 c[NSEG][4]; };
@@ -335,10 +342,10 @@ __device__ __forceinline__ void phase1_rows(const ExpertMat& m1, const ExpertMat
     }
 }
 
-template <int BITS, int NSEG>
+template <int BITS, int NSEG, typename Missing>
 __device__ __forceinline__ void phase1_quant(const ExpertMat& m1, const ExpertMat& m3,
                                              const uint16_t* __restrict__ xrow, int H, int f_begin,
-                                             int f_end, float* __restrict__ hrow)
+                                             int f_end, float* __restrict__ hrow, Missing missing)
 {
     const int lane = threadIdx.x & (kWave - 1);
     LaneX lx[NSEG];
@@ -357,16 +364,18 @@ __device__ __forceinline__ void phase1_quant(const ExpertMat& m1, const ExpertMa
         }
         arrange_lane_x<BITS>(v, lx[s]);
     }
+    // (tested here and not before the loads above: the table's pointers and the activations then arrive together)
+    if (!mat_present(m1, BITS) || !mat_present(m3, BITS)) return missing();
     phase1_rows<BITS, NSEG>(m1, m3, H, f_begin, f_end, hrow, lx,
                             [](const RowRegs<BITS, NSEG>& rr, const LaneX (&l)[NSEG]) {
                                 return dot_row_q<BITS, NSEG>(rr, l);
                             });
 }
 
-template <int NSEG>
+template <int NSEG, typename Missing>
 __device__ __forceinline__ void phase1_bf16(const ExpertMat& m1, const ExpertMat& m3,
                                             const uint16_t* __restrict__ xrow, int H, int f_begin,
-                                            int f_end, float* __restrict__ hrow)
+                                            int f_end, float* __restrict__ hrow, Missing missing)
 {
     const int lane = threadIdx.x & (kWave - 1);
     LaneXB<NSEG> lx;
@@ -378,6 +387,7 @@ __device__ __forceinline__ void phase1_bf16(const ExpertMat& m1, const ExpertMat
             lx.r[s][j] = make_uint4(0, 0, 0, 0);
             if (col < H) lx.r[s][j] = *reinterpret_cast<const uint4*>(xrow + col);
         }
+    if (!mat_present(m1, 16) || !mat_present(m3, 16)) return missing();
     phase1_rows<16, NSEG>(m1, m3, H, f_begin, f_end, hrow, lx,
                           [](const RowRegs<16, NSEG>& rr, const LaneXB<NSEG>& l) {
                               return dot_row_b<NSEG>(rr, l);
@@ -388,7 +398,7 @@ __device__ __forceinline__ void phase1_bf16(const ExpertMat& m1, const ExpertMat
 template <int NSEG>
 __device__ __forceinline__ void phase1_pair(const uint16_t* __restrict__ x, const dymoe_expert_fmt* __restrict__ table,
                                             int p, int e, int b, int H, int F, int k, int rows_per_block,
-                                            float* __restrict__ hbuf)
+                                            float* __restrict__ hbuf, unsigned* __restrict__ flags)
 {
     const int t = p / k;
     const int f_begin = blockIdx.x * rows_per_block;
@@ -396,14 +406,20 @@ __device__ __forceinline__ void phase1_pair(const uint16_t* __restrict__ x, cons
     const uint16_t* xrow = x + (long)t * H;
     float* hrow = hbuf + (long)p * F;
     const dymoe_expert_fmt ex = table[e];
+    // The assigned format may be absent from the table: the pair then contributes nothing.  Its rows of the
+    // intermediate are set to zero, so that the second phase adds nothing for it even where it finds the down projection.
+    auto missing = [&]() {
+        for (int f = f_begin + (int)threadIdx.x; f < f_end; f += kGvThreads) hrow[f] = 0.0f;
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(flags, DYMOE_FLAG_FORMAT_MISSING);
+    };
     if (b == 16) {
-        phase1_bf16<NSEG>(pick_mat(ex, 0, 16), pick_mat(ex, 1, 16), xrow, H, f_begin, f_end, hrow);
+        phase1_bf16<NSEG>(pick_mat(ex, 0, 16), pick_mat(ex, 1, 16), xrow, H, f_begin, f_end, hrow, missing);
     } else if (b == 8) {
-        phase1_quant<8, NSEG>(pick_mat(ex, 0, 8), pick_mat(ex, 1, 8), xrow, H, f_begin, f_end, hrow);
+        phase1_quant<8, NSEG>(pick_mat(ex, 0, 8), pick_mat(ex, 1, 8), xrow, H, f_begin, f_end, hrow, missing);
     } else if (b == 4) {
-        phase1_quant<4, NSEG>(pick_mat(ex, 0, 4), pick_mat(ex, 1, 4), xrow, H, f_begin, f_end, hrow);
+        phase1_quant<4, NSEG>(pick_mat(ex, 0, 4), pick_mat(ex, 1, 4), xrow, H, f_begin, f_end, hrow, missing);
     } else {
-        phase1_quant<2, NSEG>(pick_mat(ex, 0, 2), pick_mat(ex, 1, 2), xrow, H, f_begin, f_end, hrow);
+        phase1_quant<2, NSEG>(pick_mat(ex, 0, 2), pick_mat(ex, 1, 2), xrow, H, f_begin, f_end, hrow, missing);
     }
 }
 
@@ -411,7 +427,7 @@ template <int NSEG>
 __global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
     const uint16_t* __restrict__ x, const int32_t* __restrict__ idx,
     const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table, int H, int F,
-    int E, int k, int rows_per_block, float* __restrict__ hbuf)
+    int E, int k, int rows_per_block, float* __restrict__ hbuf, unsigned* __restrict__ flags)
 {
     // pairs in reverse: a token's later slots carry the less important experts, hence the narrower formats,
     // whose workgroups are short and latency-bound; dispatched first they overlap the wide ones instead of forming the tail
@@ -420,7 +436,7 @@ __global__ __launch_bounds__(kGvThreads) void gemv_phase1_kernel(
     if (e < 0 || e >= E) return;
     const int b = bits[e];
     if (b != 16 && b != 8 && b != 4 && b != 2) return;
-    phase1_pair<NSEG>(x, table, p, e, b, H, F, k, rows_per_block, hbuf);
+    phase1_pair<NSEG>(x, table, p, e, b, H, F, k, rows_per_block, hbuf, flags);
 }
 
 // The first phase with the decode step's front end in front of it (router gating and top-k, decode importance,
@@ -438,7 +454,7 @@ __global__ __launch_bounds__(kGvThreads) void decode_fused_phase1_kernel(
     const dymoe_expert_fmt* __restrict__ table, int T, int H, int F, int E, int k, int renorm, TierTable tiers,
     int floor_bits, int rows_per_block, int32_t* __restrict__ idx, float* __restrict__ w, float* __restrict__ probs,
     float* __restrict__ importance, int32_t* __restrict__ load, uint8_t* __restrict__ bits,
-    int32_t* __restrict__ rank, float* __restrict__ hbuf)
+    int32_t* __restrict__ rank, float* __restrict__ hbuf, unsigned* __restrict__ flags)
 {
     __shared__ float s_logit[kFusedMaxE];
     __shared__ float s_selp[kFusedMaxK];
@@ -485,7 +501,7 @@ __global__ __launch_bounds__(kGvThreads) void decode_fused_phase1_kernel(
     const int e = s_idx[p];
     const int b = s_bits[e];
     if (b != 16 && b != 8 && b != 4 && b != 2) return;
-    phase1_pair<NSEG>(x, table, p, e, b, H, F, k, rows_per_block, hbuf);
+    phase1_pair<NSEG>(x, table, p, e, b, H, F, k, rows_per_block, hbuf, flags);
 }
 
 // ---------------------------------------------------------------- phase 2
@@ -589,7 +605,7 @@ __device__ __forceinline__ void phase2_two_units(const ExpertMat& ma, const Expe
 __global__ __launch_bounds__(kP2MaxWaves * kWave) void gemv_phase2_kernel(
     const float* __restrict__ hbuf, const int32_t* __restrict__ idx, const float* __restrict__ w,
     const uint8_t* __restrict__ bits, const dymoe_expert_fmt* __restrict__ table, int H, int F,
-    int E, int k, int nseg, int out_dtype, void* __restrict__ y)
+    int E, int k, int nseg, int out_dtype, void* __restrict__ y, unsigned* __restrict__ flags)
 {
     __shared__ float s_red[kP2MaxWaves][kP2Rows];
     const int t = blockIdx.y;
@@ -637,7 +653,12 @@ __global__ __launch_bounds__(kP2MaxWaves * kWave) void gemv_phase2_kernel(
         const float gate = w[p];
         const float* hrow = hbuf + (long)p * F;
         const dymoe_expert_fmt ex = table[e];
+        auto missing = [&]() {                 // format not in the table: the pair is left out
+            if (blockIdx.x == 0 && lane == 0) atomicOr(flags, DYMOE_FLAG_FORMAT_MISSING);
+        };
         if (b == 16) {
+            const ExpertMat m2 = pick_mat(ex, 2, 16);
+            if (!mat_present(m2, 16)) return missing();
             LaneH lh;
 #pragma unroll
             for (int c = 0; c < 4; c++) {
@@ -651,32 +672,40 @@ __global__ __launch_bounds__(kP2MaxWaves * kWave) void gemv_phase2_kernel(
                     lh.v[c][4] = hi.x; lh.v[c][5] = hi.y; lh.v[c][6] = hi.z; lh.v[c][7] = hi.w;
                 }
             }
-            phase2_unit<16>(pick_mat(ex, 2, 16), F, s, j_begin, H, gate, tot, lh,
+            phase2_unit<16>(m2, F, s, j_begin, H, gate, tot, lh,
                             [](const RowRegs<16, 1>& rr, const LaneH& l) { return dot_row_h(rr, l); });
         } else {
+            const ExpertMat m2 = (b == 8) ? pick_mat(ex, 2, 8) : (b == 4) ? pick_mat(ex, 2, 4) : pick_mat(ex, 2, 2);
+            if (!mat_present(m2, b)) return missing();
             float v[32];
             quant_x(un, v);
             LaneX lx[1];
             if (b == 8) {
                 arrange_lane_x<8>(v, lx[0]);
-                phase2_unit<8>(pick_mat(ex, 2, 8), F, s, j_begin, H, gate, tot, lx,
+                phase2_unit<8>(m2, F, s, j_begin, H, gate, tot, lx,
                                [](const RowRegs<8, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<8, 1>(rr, l); });
             } else if (b == 4) {
                 arrange_lane_x<4>(v, lx[0]);
-                phase2_unit<4>(pick_mat(ex, 2, 4), F, s, j_begin, H, gate, tot, lx,
+                phase2_unit<4>(m2, F, s, j_begin, H, gate, tot, lx,
                                [](const RowRegs<4, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<4, 1>(rr, l); });
             } else {
                 arrange_lane_x<2>(v, lx[0]);
-                phase2_unit<2>(pick_mat(ex, 2, 2), F, s, j_begin, H, gate, tot, lx,
+                phase2_unit<2>(m2, F, s, j_begin, H, gate, tot, lx,
                                [](const RowRegs<2, 1>& rr, const LaneX (&l)[1]) { return dot_row_q<2, 1>(rr, l); });
             }
         }
     };
     for (int r = 0; r < rounds; r += 2) {
         const Unit ua = unit_of(r), ub = unit_of(r + 1);
-        if (ua.valid && ub.valid && (ua.b == 4 || ua.b == 2) && (ub.b == 4 || ub.b == 2)) {
+        bool both = ua.valid && ub.valid && (ua.b == 4 || ua.b == 2) && (ub.b == 4 || ub.b == 2);
+        ExpertMat ma = {}, mb = {};
+        if (both) {
+            ma = pick_mat(table[ua.e], 2, ua.b);
+            mb = pick_mat(table[ub.e], 2, ub.b);
+            both = mat_present(ma, ua.b) && mat_present(mb, ub.b);   // (if not: one by one, each tested again)
+        }
+        if (both) {
             const float ga = w[ua.p], gb = w[ub.p];
-            const ExpertMat ma = pick_mat(table[ua.e], 2, ua.b), mb = pick_mat(table[ub.e], 2, ub.b);
             LaneX la[1], lb[1];
             {
                 float v[32];
@@ -746,7 +775,7 @@ static int phase2_launch(dymoe_ctx* ctx, const float* hbuf, const int32_t* idx, 
     }
     const dim3 g2((unsigned)((H + kP2Rows - 1) / kP2Rows), (unsigned)T);
     dymoe_launch(ctx, DYMOE_K_GEMV_PHASE2, gemv_phase2_kernel, g2, dim3((unsigned)(nwaves * kWave)), 0, st, hbuf, idx, w,
-                 bits, table, H, F, E, k, nseg2, out_dtype, y);
+                 bits, table, H, F, E, k, nseg2, out_dtype, y, ctx->device_flags);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }
@@ -764,10 +793,10 @@ int ffn_gemv_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     const uint16_t* xb = (const uint16_t*)x;
     {
         switch (nseg1) {
-        case 1: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<1>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
-        case 2: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<2>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
-        case 3: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<3>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
-        case 4: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<4>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf); break;
+        case 1: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<1>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf, ctx->device_flags); break;
+        case 2: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<2>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf, ctx->device_flags); break;
+        case 3: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<3>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf, ctx->device_flags); break;
+        case 4: dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (gemv_phase1_kernel<4>), g1, dim3(kGvThreads), 0, st, xb, idx, bits, table, H, F, E, k, rows1, hbuf, ctx->device_flags); break;
         default: return DYMOE_ENOTSUP;
         }
     }
@@ -797,7 +826,8 @@ int decode_fused_launch(dymoe_ctx* ctx, const void* x, const void* wg, const flo
     // NCH: 16-byte chunks of an activation row per lane, as in dymoe_decode_front (8 up to 4096 columns, then 16)
 #define DYMOE_FUSED(NSEG_, NCH_)                                                                                        \
     dymoe_launch(ctx, DYMOE_K_GEMV_PHASE1, (decode_fused_phase1_kernel<NSEG_, NCH_>), g1, dim3(kGvThreads), 0, st, xb, wb,  \
-                 bias, table, T, H, F, E, k, renorm, tt, floor_bits, rows1, idx, w, probs, importance, load, bits, rank, hbuf)
+                 bias, table, T, H, F, E, k, renorm, tt, floor_bits, rows1, idx, w, probs, importance, load, bits, rank, hbuf,  \
+                 ctx->device_flags)
     switch (nseg1) {
     case 1: DYMOE_FUSED(1, 8); break;
     case 2: DYMOE_FUSED(2, 8); break;

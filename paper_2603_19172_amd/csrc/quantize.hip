@@ -349,7 +349,7 @@ __device__ __forceinline__ int build_worklist(const uint8_t* __restrict__ bits,
 template <int LAYOUT>
 __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
     const dymoe_expert_fmt* __restrict__ table, const uint8_t* __restrict__ bits,
-    const int32_t* __restrict__ load, int E, int H, int F)
+    const int32_t* __restrict__ load, int E, int H, int F, unsigned* __restrict__ flags)
 {
     __shared__ int16_t list[DYMOE_MAX_EXPERTS];
     __shared__ int n_list;
@@ -372,6 +372,10 @@ __global__ __launch_bounds__(kQThreads) void quantize_experts_kernel(
         uint8_t* q = (b == 8) ? ex->q8[mat] : (b == 4) ? ex->q4[mat] : ex->q2[mat];
         uint16_t* sc = reinterpret_cast<uint16_t*>((b == 8) ? ex->s8[mat] : (b == 4) ? ex->s4[mat] : ex->s2[mat]);
         uint16_t* zr = reinterpret_cast<uint16_t*>((b == 8) ? ex->z8[mat] : (b == 4) ? ex->z4[mat] : ex->z2[mat]);
+        if (!w || !q || !sc || !zr) {         // no source, or nowhere to write the selected format: nothing is written
+            if (blk == 0 && threadIdx.x == 0) atomicOr(flags, DYMOE_FLAG_FORMAT_MISSING);
+            continue;                          // (the same for every thread of the workgroup)
+        }
         if constexpr (LAYOUT == DYMOE_LAYOUT_TILE) {
             const long K = (mat == 2) ? F : H;
             const long tile = blk * 4 + (threadIdx.x >> 6);
@@ -436,10 +440,10 @@ int dymoe_quantize_experts(dymoe_ctx* ctx, const dymoe_expert_fmt* table, const 
     if (grid > cap) grid = cap;
     if (layout == DYMOE_LAYOUT_TILE)
         dymoe_launch(ctx, DYMOE_K_QUANTIZE, dymoe::quantize_experts_kernel<DYMOE_LAYOUT_TILE>,
-                     dim3((unsigned)grid), dim3(dymoe::kQThreads), 0, st, table, bits, load, E, H, F);
+                     dim3((unsigned)grid), dim3(dymoe::kQThreads), 0, st, table, bits, load, E, H, F, ctx->device_flags);
     else
         dymoe_launch(ctx, DYMOE_K_QUANTIZE, dymoe::quantize_experts_kernel<DYMOE_LAYOUT_ROWMAJOR>,
-                     dim3((unsigned)grid), dim3(dymoe::kQThreads), 0, st, table, bits, load, E, H, F);
+                     dim3((unsigned)grid), dim3(dymoe::kQThreads), 0, st, table, bits, load, E, H, F, ctx->device_flags);
     DYMOE_HIP_LAUNCH_CHECK();
     return DYMOE_OK;
 }

@@ -67,6 +67,8 @@ class MoELayer:
         self.layout = B.LAYOUT_TILE if gemm else B.LAYOUT_ROWMAJOR
         self.ws_bytes = B.workspace_bytes(T, H, F, E, k)
         self.ws = torch.empty((self.ws_bytes,), dtype=torch.uint8, device=dev)
+        # a decode step on resident formats: dymoe_decode_step (two launches) instead of front end + FFN (three)
+        self.use_decode_step = True
 
     # the individual steps; each is one C call
     def route(self, x, wg, bias, st):
@@ -136,8 +138,9 @@ class MoELayer:
         the assignment selects are already materialised in `store`.  Small decode
         steps take the single-launch front end unless fused_front is False."""
         st = B._stream(stream)
-        if (fused_front and not quantize and self.phase == B.PHASE_DECODE and self.path != B.PATH_GEMM
-                and self.layout == B.LAYOUT_ROWMAJOR and self.decode_step(x, wg, bias, store, st)):
+        if (fused_front and self.use_decode_step and not quantize and self.phase == B.PHASE_DECODE
+                and self.path != B.PATH_GEMM and self.layout == B.LAYOUT_ROWMAJOR
+                and self.decode_step(x, wg, bias, store, st)):
             return self.y
         if fused_front and self.phase == B.PHASE_DECODE and self.T <= B.FRONT_MAX_TOKENS:
             self.front(x, wg, bias, st)

@@ -575,14 +575,16 @@ class ResidentDecodeStack:
     Nothing is copied and nothing is decided on the host: the importance of an expert and its bit width are still
     chosen per token and layer on the device (Sec. 4.2.2, Sec. 4.3), and the FFN reads, through the layer's format
     table, the format the assignment names.  A step is therefore a fixed chain of launches (per layer
-    dymoe_decode_front, dymoe_moe_ffn_mixed, dymoe_residual_rmsnorm) and is replayed as one HIP graph.
+    dymoe_decode_step, or dymoe_decode_front and dymoe_moe_ffn_mixed with fused=False, then dymoe_residual_rmsnorm),
+    enqueued one by one or (graph=True) replayed as one HIP graph.
 
     pool: a HostExpertPool holding every format in `tier_bits` and the floors (row-major codes); its entries are
     copied to the device once.  tier_count: one tuple, or one per layer; floor_bits: per layer or None."""
 
     def __init__(self, ctx, H, F, E, k, routers, pool, tier_count, tier_bits, floor_bits=None, alpha=0.125,
-                 device="cuda:0", graph=True):
+                 device="cuda:0", graph=True, fused=True):
         self.ctx, self.H, self.F, self.E, self.k = ctx, H, F, E, k
+        self.fused = bool(fused)
         self.L = L = len(routers)
         self.routers, self.alpha, self.dev = routers, float(alpha), device
         self.floor = [int(b) for b in floor_bits] if floor_bits is not None else [0] * L
@@ -630,14 +632,24 @@ class ResidentDecodeStack:
             h, nxt = self.h[l % 2], self.h[(l + 1) % 2]
             idx, gate, bits, table = self.idx[l].data_ptr(), self.gate[l].data_ptr(), self.bits[l].data_ptr(), \
                 self.tables[l].data_ptr()
-            B._check(B.lib.dymoe_decode_front(ctx, h.data_ptr(), self.routers[l].data_ptr(), None, 1, H, E, k, 1,
-                                              self._nt, C.cast(self._tc[l], C.c_void_p), C.cast(self._tb, C.c_void_p),
-                                              self.floor[l], idx, gate, self.probs.data_ptr(), self.imp.data_ptr(),
-                                              self.load.data_ptr(), bits, self.rank.data_ptr(), st),
-                     "dymoe_decode_front")
-            B._check(B.lib.dymoe_moe_ffn_mixed(ctx, h.data_ptr(), idx, gate, bits, table, 1, H, F, E, k, 64, B.OUT_F32,
-                                               B.PATH_GEMV, self.y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, st),
-                     "dymoe_moe_ffn_mixed")
+            rc = B.ENOTSUP
+            if self.fused:       # front end and FFN in two launches; sizes it does not cover take the separate calls
+                rc = B.lib.dymoe_decode_step(ctx, h.data_ptr(), self.routers[l].data_ptr(), None, 1, H, F, E, k, 1,
+                                             self._nt, C.cast(self._tc[l], C.c_void_p), C.cast(self._tb, C.c_void_p),
+                                             self.floor[l], table, 64, B.OUT_F32, idx, gate, self.probs.data_ptr(),
+                                             self.imp.data_ptr(), self.load.data_ptr(), bits, self.rank.data_ptr(),
+                                             self.y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, st)
+                if rc != B.ENOTSUP:
+                    B._check(rc, "dymoe_decode_step")
+            if rc == B.ENOTSUP:
+                B._check(B.lib.dymoe_decode_front(ctx, h.data_ptr(), self.routers[l].data_ptr(), None, 1, H, E, k, 1,
+                                                  self._nt, C.cast(self._tc[l], C.c_void_p), C.cast(self._tb, C.c_void_p),
+                                                  self.floor[l], idx, gate, self.probs.data_ptr(), self.imp.data_ptr(),
+                                                  self.load.data_ptr(), bits, self.rank.data_ptr(), st),
+                         "dymoe_decode_front")
+                B._check(B.lib.dymoe_moe_ffn_mixed(ctx, h.data_ptr(), idx, gate, bits, table, 1, H, F, E, k, 64, B.OUT_F32,
+                                                   B.PATH_GEMV, self.y.data_ptr(), self.ws.data_ptr(), self.ws_bytes, st),
+                         "dymoe_moe_ffn_mixed")
             B._check(B.lib.dymoe_residual_rmsnorm(ctx, h.data_ptr(), self.y.data_ptr(), B.OUT_F32, self.alpha, 1, H,
                                                   nxt.data_ptr(), st), "dymoe_residual_rmsnorm")
 

@@ -680,6 +680,96 @@ def test_decode_step_declines_what_it_does_not_cover(ctx):
     assert B.lib.dymoe_decode_step(*args(1, 80, 2)) == B.ENOTSUP         # more than 64 experts
 
 
+# ------------------------------------------------------------------ formats the table does not hold
+
+@pytest.mark.parametrize("path", [B.PATH_GEMV, B.PATH_GEMM])
+def test_ffn_leaves_out_an_expert_whose_selected_format_is_not_in_the_table(ctx, path):
+    """The precisions are chosen on the device, so the kernels test the table's pointers themselves: an expert
+    assigned a format its entry does not hold is left out exactly as at 0 bits and the device's condition word says
+    so; an entry that is NULL for an expert no token is routed to changes nothing and raises nothing."""
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=1 if path == B.PATH_GEMV else 48, config_id=3300 + path)
+    x, _ = synth.activations(cfg)
+    idx, w = routed(cfg, x)
+    bits_np = np.array([16, 4, 2, 8, 4, 2, 16, 4], np.uint8)
+    need = set(int(e) for e in idx.ravel())
+    assert len(need) < cfg.E or cfg.T > 1
+    host, dev, table, keep = build_layer(cfg, bits_np, experts_needed=need, path=path)
+    assert ctx.device_flags() == 0
+    y_full = run_ffn(ctx, cfg, x, idx, w, bits_np, table, path)
+    assert ctx.device_flags() == 0                    # unrouted experts' entries are NULL: not touched, no flag
+    ref = oracle_ffn(cfg, x, idx, w, bits_np, host)
+    assert rel_err_per_token(y_full, ref) <= FFN_TOL
+    for miss in sorted(need)[:3]:
+        dev2 = [({} if e == miss else d) for e, d in enumerate(dev)]
+        table2, keep2 = B.make_expert_table(dev2, DEV)
+        y_miss = run_ffn(ctx, cfg, x, idx, w, bits_np, table2, path)
+        assert ctx.device_flags() == B.FLAG_FORMAT_MISSING
+        assert ctx.device_flags() == 0                # a read clears the word
+        skipped = bits_np.copy()
+        skipped[miss] = 0
+        y_skip = run_ffn(ctx, cfg, x, idx, w, skipped, table, path)
+        assert ctx.device_flags() == 0
+        assert np.array_equal(y_miss, y_skip)
+        # one pointer of the format missing is enough (here: the zeros of the down projection, or W3)
+        d3 = dict(dev[miss])
+        if bits_np[miss] == 16:
+            d3["w"] = [d3["w"][0], None, d3["w"][2]]
+        else:
+            key = "q%d" % bits_np[miss]
+            q = [tuple(t) for t in d3[key]]
+            q[2] = (q[2][0], q[2][1], None)
+            d3[key] = q
+        table3, keep3 = B.make_expert_table([(d3 if e == miss else d) for e, d in enumerate(dev)], DEV)
+        y_part = run_ffn(ctx, cfg, x, idx, w, bits_np, table3, path)
+        assert ctx.device_flags() == B.FLAG_FORMAT_MISSING
+        assert np.array_equal(y_part, y_skip)
+
+
+def test_decode_step_and_quantizer_with_a_format_the_store_does_not_hold(ctx):
+    """Tiers that name int8 over a store without int8 buffers: the fused decode step leaves those experts out and
+    raises the flag; the quantiser writes nothing for them (and nothing for an expert whose bf16 source is NULL)."""
+    T, H, F, E, k = 1, 256, 512, 8, 2
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=T, phase="decode", config_id=3400)
+    x, _ = synth.activations(cfg)
+    wg, _ = synth.router(cfg)
+    mats = [synth.expert_weights(cfg, e) for e in range(E)]
+    store = ExpertStore([[to_bf16(m) for m in mats[e]] for e in range(E)], H, F, DEV, formats=(4,))
+    for e in range(E):
+        for cd, sc, zr in store.q[4][e]:
+            cd.fill_(0xAB)
+    lay = MoELayer(ctx, T, H, F, E, k, "decode", (1, 7), (8, 4), out_dtype=B.OUT_F32, device=DEV)
+    xd, wgd = to_bf16(x), to_bf16(wg)
+    st = B._stream(None)
+    lay.front(xd, wgd, None, st)
+    lay.quantize(store, st)                          # int4 for the experts at 4 bits; the int8 one has no buffers
+    assert ctx.device_flags() == B.FLAG_FORMAT_MISSING
+    bits = lay.bits.cpu().numpy()
+    sel = [int(e) for e in lay.idx.cpu().numpy().ravel()]
+    assert sorted(bits[sel].tolist()) == [4, 8]
+    for e in range(E):
+        written = all(not bool((cd == 0xAB).all()) for cd, _, _ in store.q[4][e])
+        assert written == (e in sel and bits[e] == 4)
+    lay.y.fill_(float("nan"))
+    assert lay.decode_step(xd, wgd, None, store, st)
+    assert ctx.device_flags() == B.FLAG_FORMAT_MISSING
+    only4 = torch.from_numpy(np.where(bits == 8, 0, bits).astype(np.uint8)).to(DEV)
+    y_ref = ctx.moe_ffn_mixed(xd, lay.idx, lay.gate, only4, store.table, F, out_dtype=B.OUT_F32, path=B.PATH_GEMV)
+    assert ctx.device_flags() == 0
+    assert torch.equal(lay.y.view(torch.int32), y_ref.view(torch.int32))
+    # quantiser: the bf16 source of a selected expert missing
+    experts = [{"w": [to_bf16(m) for m in mats[e]], "q4": empty_q(F, H, 4)} for e in range(2)]
+    experts[1]["w"] = [experts[1]["w"][0], None, experts[1]["w"][2]]
+    for ex in experts:
+        for cd, sc, zr in ex["q4"]:
+            cd.fill_(0xAB)
+    table, keep = B.make_expert_table(experts, DEV)
+    ctx.quantize_experts(table, torch.tensor([4, 4], dtype=torch.uint8, device=DEV), None, 2, H, F)
+    assert ctx.device_flags() == B.FLAG_FORMAT_MISSING
+    for i in range(3):
+        assert not bool((experts[0]["q4"][i][0] == 0xAB).all())
+        assert bool((experts[1]["q4"][i][0] == 0xAB).all()) == (i == 1)
+
+
 # ------------------------------------------------------------------ measurement aid
 
 @pytest.mark.parametrize("nbytes", [0, 16, 16 * 1024 * 3 + 48, 8 << 20])

@@ -419,9 +419,9 @@ def test_resident_stack_replayed_as_a_graph_matches_eager_launches_and_the_oracl
     pool.add_quantised(ctx, DEV, formats=[b for b in tiers[1] if b != 16])
     floor = ([4] + [0] * (L - 2) + [4]) if floor_rule else [0] * L
     routers = [to_bf16(r) for r in routers_np]
-    make = lambda graph: ResidentDecodeStack(ctx, H, F, E, k, routers, pool, tiers[0], tiers[1], floor_bits=floor,
-                                             alpha=0.25, device=DEV, graph=graph)
-    eager, replayed = make(False), make(True)
+    make = lambda graph, fused=True: ResidentDecodeStack(ctx, H, F, E, k, routers, pool, tiers[0], tiers[1],
+                                                         floor_bits=floor, alpha=0.25, device=DEV, graph=graph, fused=fused)
+    eager, replayed, separate = make(False), make(True), make(False, fused=False)
     outs, traces = [], []
     for s in (0, 1, 2, 1, 0, 3):
         x, _ = synth.activations(synth.scaled(cfgs[0], config_id=2400 + s))
@@ -430,6 +430,8 @@ def test_resident_stack_replayed_as_a_graph_matches_eager_launches_and_the_oracl
         b = replayed.step(to_bf16(x)).clone()
         assert torch.equal(a, b)
         assert eager.trace() == replayed.trace()
+        c = separate.step(to_bf16(x)).clone()      # front end and FFN as separate calls: the same bits
+        assert torch.equal(a, c) and eager.trace() == separate.trace()
         outs.append((x, b))
         traces.append([(ex, bts, bts) for (ex, bts) in replayed.trace()])
     _check_against_oracle(outs, traces, routers_np, lambda l, e: mats[pool.entry(l, e)], floor, tiers=tiers)

@@ -189,6 +189,45 @@ def test_argument_validation_happens_before_any_device_work():
     assert ffn_na(None, P, P, P, P, P, 512, 4096, 14336, 8, 2, 64, 0, 0, P, None) == B.ENOSPC
 
 
+def test_format_presence_test_the_kernels_apply_to_a_table_entry():
+    """The kernels run an expert at b bits only if its table entry holds every pointer of that format (the bit
+    widths are chosen on the device, so a NULL must never be read through).  The same inline test, on the host:
+    a format is present exactly when all of its pointers for the three matrices are set; any one NULL removes it,
+    other formats' pointers never matter, and the optional tile copy of the bf16 weights is not required."""
+    fields = {16: ("w",), 8: ("q8", "s8", "z8"), 4: ("q4", "s4", "z4"), 2: ("q2", "s2", "z2")}
+    empty = B.ExpertFmt()
+    for b in (16, 8, 4, 2, 0, 3, 1, 32, -4):
+        assert not B.format_present(empty, b)
+    assert B.lib.dymoe_format_present(None, 16) == 0
+    for b, names in fields.items():
+        full = B.ExpertFmt()
+        for n in names:
+            for m in range(3):
+                getattr(full, n)[m] = 0x1000 * (m + 1)
+        assert B.format_present(full, b)
+        for other in fields:
+            if other != b:
+                assert not B.format_present(full, other)        # only this format was filled in
+        for n in names:                                          # any single pointer missing: absent
+            for m in range(3):
+                one = B.ExpertFmt.from_buffer_copy(bytes(full))
+                getattr(one, n)[m] = None
+                assert not B.format_present(one, b), (b, n, m)
+        assert not B.format_present(full, 0) and not B.format_present(full, 5)
+    # everything set: every width present
+    allset = B.ExpertFmt()
+    for n, _ in B.ExpertFmt._fields_:
+        for m in range(3):
+            getattr(allset, n)[m] = 0x40
+    assert all(B.format_present(allset, b) for b in (16, 8, 4, 2))
+    for m in range(3):
+        allset.wt[m] = None
+    assert B.format_present(allset, 16)
+    u = C.c_uint(7)
+    assert B.lib.dymoe_device_flags(None, C.byref(u), None) == B.ENOCTX
+    assert B.lib.dymoe_device_flags(None, None, None) == B.EINVAL
+
+
 def test_create_without_gpu_reports_error():
     import torch
     if torch.cuda.is_available():

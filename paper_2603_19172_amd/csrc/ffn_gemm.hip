@@ -33,7 +33,22 @@ namespace dymoe {
 constexpr int kGmThreads = 256;
 constexpr int kGmWaves = 4;         // one per SIMD; two workgroups share a compute unit
 constexpr int kBK = 128;            // K-tile
-constexpr int kXsBufBytes = kGemmTileM * kBK * 2;   // one token tile in LDS: 128 rows x 256 bytes, no padding
+constexpr int kXsBufBytes = kGemmTileTall * kBK * 2;   // one token tile in LDS: up to 160 rows x 256 bytes, no padding
+
+// Tiles of one expert with c pairs at b bits: 128 rows each, the last one shorter.  For the int4 and int2 formats a
+// last remainder of 1..32 rows is attached to the tile before it instead (5 fragments of 32 tokens, 160 rows): a
+// remainder tile streams and dequantises the expert's whole weight matrices once more for a handful of tokens, which
+// costs a third to a half of a full tile's time and all of its memory traffic.  (bf16 and int8 strips leave no
+// registers for a fifth pair of accumulators.)
+__device__ __forceinline__ bool plan_tall(int c, int b)
+{
+    const int r = c % kGemmTileM;
+    return (b == 4 || b == 2) && c > kGemmTileM && r >= 1 && r <= kGemmTileTall - kGemmTileM;
+}
+__device__ __forceinline__ int plan_tiles_of(int c, int b)
+{
+    return (c + kGemmTileM - 1) / kGemmTileM - (plan_tall(c, b) ? 1 : 0);
+}
 
 // ----------------------------------------------------------------------------
 // plan: counting sort of the (token, slot) pairs by expert + tile list
@@ -140,7 +155,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
         for (int e0 = 0; e0 < E; e0 += kWave) {
             const int e = e0 + lane;
             const int c = (e < E) ? s_count[e] : 0;
-            const int nt_e = (c + tile_m - 1) / tile_m;
+            const int nt_e = (e < E) ? plan_tiles_of(c, s_bits[e]) : 0;
             int incl = c, tincl = nt_e;
 #pragma unroll
             for (int o = 1; o < kWave; o <<= 1) {
@@ -169,8 +184,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     for (int e = tid; e < E; e += kPlanThreads) {
         const int c = s_count[e], b = s_bits[e];
         int nt = s_tile0[e];
-        for (int m0 = 0; m0 < c; m0 += tile_m, nt++) {
-            const int rows = min(tile_m, c - m0);
+        const int nt_end = nt + plan_tiles_of(c, b);
+        for (int m0 = 0; nt < nt_end; m0 += tile_m, nt++) {
+            const int rows = (nt == nt_end - 1) ? c - m0 : tile_m;     // (the last tile: up to 160 rows when tall)
             draft[4 * nt + 0] = e;
             draft[4 * nt + 1] = s_off[e] + m0;
             draft[4 * nt + 2] = rows;
@@ -376,11 +392,11 @@ __device__ __forceinline__ StripSrc strip_src(const MatPtr& m, long nt, int K, i
 {
     StripSrc src;
     const long tile_row = nt * (K >> 7);
-    src.s = m.s + tile_row * 64 + lane;
-    src.z = m.z + tile_row * 64 + lane;
+    src.s = m.s + tile_row * 64 + (uint32_t)lane;
+    src.z = m.z + tile_row * 64 + (uint32_t)lane;
     if constexpr (BITS == 16) {
         if (m.wt) {          // tiles: chunk c of every lane sits in one 1 KiB run
-            src.p = m.wt + tile_row * 8192 + lane * 16;
+            src.p = m.wt + tile_row * 8192 + (uint32_t)(lane * 16);
             src.kt_stride = 8192;
             src.c_stride = 1024;
         } else {             // rows: the lane's 64 columns are contiguous
@@ -389,7 +405,7 @@ __device__ __forceinline__ StripSrc strip_src(const MatPtr& m, long nt, int K, i
             src.c_stride = 16;
         }
     } else {
-        src.p = m.q + tile_row * (512 * BITS) + lane * 16;      // 32 x 128 codes of BITS bits: 512 * BITS bytes per tile
+        src.p = m.q + tile_row * (512 * BITS) + (uint32_t)(lane * 16);      // 32 x 128 codes of BITS bits: 512 * BITS bytes per tile
         src.kt_stride = 512 * BITS;
         src.c_stride = 1024;
     }
@@ -478,6 +494,19 @@ __device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>
         strip_frags<BITS>(rb, jj, b0, b1);
 #pragma unroll
         for (int tf = 0; tf < NTF; tf++) {
+            if constexpr (NTF == 5) {
+                // five fragments: 160 accumulator registers leave no room for a second pair of operands, so a step
+                // reads its own (the other wavefront of the SIMD covers the LDS latency)
+                const uint32_t x0 = (xa ^ (uint32_t)(jj << 5)) + tf * (32 * kBK * 2);
+                ops.t0 = lds_read16(x0);
+                ops.t1 = lds_read16(x0 ^ 16u);
+                __builtin_amdgcn_sched_barrier(kStepMask);
+                acc[0][tf] = mfma16<BITS>(a0, ops.t0, acc[0][tf]);
+                acc[1][tf] = mfma16<BITS>(b0, ops.t0, acc[1][tf]);
+                acc[0][tf] = mfma16<BITS>(a1, ops.t1, acc[0][tf]);
+                acc[1][tf] = mfma16<BITS>(b1, ops.t1, acc[1][tf]);
+                __builtin_amdgcn_sched_barrier(kStepMask);
+            } else {
             // next step: next fragment, else next quarter (nothing after the tile's last step)
             const bool wrap = (tf == NTF - 1);
             const bool last = wrap && jj == 3;
@@ -496,6 +525,7 @@ __device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>
             acc[1][tf] = mfma16<BITS>(b1, ops.t1, acc[1][tf]);
             ops = nxt;
             __builtin_amdgcn_sched_barrier(kStepMask);
+            }
         }
         if constexpr (BITS == 16) {
             ra.r[2 * jj] = load_chunk<16>(sa, kt_next, 2 * jj);
@@ -507,6 +537,14 @@ __device__ __forceinline__ void compute_ktile(StripRaw<BITS>& ra, StripRaw<BITS>
             ra.r[jj] = load_chunk<8>(sa, kt_next, jj);
             rb.r[jj] = load_chunk<8>(sb, kt_next, jj);
             __builtin_amdgcn_sched_barrier(kStepMask);
+        } else if constexpr (NTF == 5 && BITS == 4) {
+            // five fragments: no second register set; each 16-byte chunk of codes serves two quarters and is
+            // refilled when the second is done, half a tile before the next tile needs it
+            if (jj & 1) {
+                ra.r[jj >> 1] = load_chunk<4>(sa, kt_next, jj >> 1);
+                rb.r[jj >> 1] = load_chunk<4>(sb, kt_next, jj >> 1);
+                __builtin_amdgcn_sched_barrier(kStepMask);
+            }
         }
     }
 }
@@ -587,7 +625,7 @@ __device__ __forceinline__ void gemm_tile(
 {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);     // (the same in every lane: addresses built from it stay scalar)
     const int ln = lane & 31;
     const int kb = lane >> 5;
 
@@ -658,7 +696,8 @@ __device__ __forceinline__ void gemm_tile(
         const int kn = min(kt + 1, kt_end - 1);
         copy_tile<NTF>(stage, kn, buf ^ 1);
         StripRaw<BITS> na, nb;
-        if constexpr (BITS != 16 && BITS != 8) {
+        constexpr bool kSecondSet = (BITS == 2) || (BITS == 4 && NTF != 5);    // next tile's codes in registers of their own
+        if constexpr (kSecondSet) {
             load_strip<BITS>(sa, kn, na);
             load_strip<BITS>(sb, kn, nb);
             __builtin_amdgcn_sched_barrier(0);   // keep the requests up here, a whole tile ahead of their use
@@ -666,7 +705,7 @@ __device__ __forceinline__ void gemm_tile(
         XOps ops;             // operands of the first step
         ops.t0 = lds_read16(xa);
         ops.t1 = lds_read16(xa ^ 16u);
-        if constexpr (BITS == 8) {
+        if constexpr (BITS == 8 || (BITS == 4 && NTF == 5)) {
             // the next tile's scale and zero are requested after the first quarter's
             // refills: a wait for a refilled register then never reaches back to
             // the copies issued at the top of the tile before a quarter has passed
@@ -683,7 +722,7 @@ __device__ __forceinline__ void gemm_tile(
         } else {
             compute_ktile<BITS, NTF, 0, 4>(ra, rb, sa, sb, kn, xa, ops, acc);
         }
-        if constexpr (BITS != 16 && BITS != 8) {
+        if constexpr (kSecondSet) {
             adopt_strip<BITS>(ra, na);
             adopt_strip<BITS>(rb, nb);
             // finish the hand-over here, not after the next tile's requests
@@ -693,7 +732,7 @@ __device__ __forceinline__ void gemm_tile(
         wait_tile_copies<ktile_loads<BITS>()>();
         __syncthreads();
         buf ^= 1;
-        xa ^= (uint32_t)kXsBufBytes;
+        xa = xa0 + (uint32_t)(buf * kXsBufBytes);
     }
 
     // epilogue.  D layout: lane (ln, kb), register i -> weight row 8*(i/4) + 4*kb + i%4, token ln
@@ -792,8 +831,8 @@ __global__ __launch_bounds__(kGmThreads, 2) void gemm_kernel(
     const int32_t* __restrict__ plan, int P, int E, int k_route, int H, int F,
     uint16_t* __restrict__ hbuf_out, float* __restrict__ opair, int max_tiles, int splits)
 {
-    // two token-tile buffers; the swizzle and the buffer toggle work on address bits
-    extern __shared__ __attribute__((aligned(65536))) uint16_t xs_raw[];
+    // two token-tile buffers; the swizzle works on the address bits inside a row
+    extern __shared__ __attribute__((aligned(1024))) uint16_t xs_raw[];
     const uint32_t xs = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)xs_raw;
     const PlanPtrs pp = plan_ptrs(const_cast<int32_t*>(plan), E, P);
     const int K = (MODE == 1) ? H : F;
@@ -854,7 +893,14 @@ __global__ __launch_bounds__(kGmThreads, 2) void gemm_kernel(
     case 1: DYMOE_TILE(BITS_, 1); break;          \
     case 2: DYMOE_TILE(BITS_, 2); break;          \
     case 3: DYMOE_TILE(BITS_, 3); break;          \
-    default: DYMOE_TILE(BITS_, 4); break;         \
+    case 4: DYMOE_TILE(BITS_, 4); break;          \
+    default:                                      \
+        if constexpr (BITS_ == 4 || BITS_ == 2) { \
+            DYMOE_TILE(BITS_, 5);                 \
+        } else {                                  \
+            DYMOE_TILE(BITS_, 4);                 \
+        }                                         \
+        break;                                    \
     }
     if (b == 16) {
         DYMOE_TILE_NTF(16)

@@ -8,6 +8,7 @@ namespace dymoe {
 
 constexpr int kSeg = 2048;        // columns one wavefront covers per GEMV row segment
 constexpr int kGemmTileM = 128;   // token rows per grouped-GEMM tile
+constexpr int kGemmTileTall = 160; // the last tile of an int4 / int2 expert also takes a remainder of up to 32 rows
 constexpr int kPlanTileMin = 32;  // sizing granularity of the tile list
 
 struct FfnLayout {

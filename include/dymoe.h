@@ -415,7 +415,7 @@ int dymoe_decode_step(dymoe_ctx* ctx, const void* x, const void* wg, const float
  * Diagnostic (tests, profiling): where the grouped-GEMM path of dymoe_moe_ffn_mixed leaves its token
  * grouping in the workspace, so that a caller can see which (token, slot) pair went to which row of which
  * tile (paper Sec. 4.2.1: the per-expert token lists Tokens_j).  Returns the byte offset of an int32 array
- * laid out as counts[E] | offsets[E+1] | (E ints: the first E bytes hold the bit width each expert is run at) | ntiles, pairs (+6 unused) | perm[T*k]:
+ * laid out as counts[E] | offsets[E+1] | (E ints: the first E bytes hold the bit width each expert is run at) | ntiles, pairs, experts with tiles (+5 unused) | perm[T*k]:
  * counts[e] = pairs routed to expert e at a non-zero precision, offsets = their exclusive prefix sums,
  * perm[offsets[e] + i] = the i-th pair (token * k + slot) of expert e, in the order the GEMM's tiles take
  * them (rows [128 j, 128 j + 128) of an expert form its j-th tile).  Pure host function; 0 for invalid sizes.

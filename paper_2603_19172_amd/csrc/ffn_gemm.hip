@@ -151,7 +151,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     // exclusive scans over the experts (pairs and tiles): E is at most 1024, one wavefront walks it in strides
     if (wave == 0) {
         const int lane = tid;
-        int run = 0, trun = 0;
+        int run = 0, trun = 0, with_tiles = 0;
         for (int e0 = 0; e0 < E; e0 += kWave) {
             const int e = e0 + lane;
             const int c = (e < E) ? s_count[e] : 0;
@@ -171,12 +171,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
             }
             run += __shfl(incl, kWave - 1, kWave);
             trun += __shfl(tincl, kWave - 1, kWave);
+            with_tiles += __popcll(__ballot(nt_e > 0));
         }
         if (lane == 0) {
             s_off[E] = run;
             s_tile0[E] = trun;
             pp.ntiles[0] = trun;
             pp.ntiles[1] = run;
+            pp.ntiles[2] = with_tiles;      // experts with at least one tile (the GEMM launches pick their XCD mapping by it)
         }
     }
     __syncthreads();
@@ -837,25 +839,44 @@ __global__ __launch_bounds__(kGmThreads, 2) void gemm_kernel(
     const PlanPtrs pp = plan_ptrs(const_cast<int32_t*>(plan), E, P);
     const int K = (MODE == 1) ? H : F;
     const int N = (MODE == 1) ? F : H;
-    // Which (column block, tile, K split) this workgroup takes.  The first GEMM's grid is (column block, tile).  The
-    // second GEMM's launch is one-dimensional: workgroups go to the 8 XCDs (each with an L2 of its own) in turn by
-    // launch index, and the column blocks of a unit (one tile's rows over one K split) all read the same rows of the
-    // intermediate, so a unit is kept on one XCD: launch index L -> XCD L % 8, place j = L / 8 in that XCD's sequence,
-    // unit (j / nblk) * 8 + L % 8, column block j % nblk.  Units are numbered tile-major (all K splits of the longest
-    // tile first), so the longest-first order of the tile list survives.
+    // Which (column block, tile, K split) this workgroup takes.  Both launches are one-dimensional: workgroups go to the
+    // 8 XCDs (each with an L2 of its own) in turn by launch index, L -> XCD c = L % 8, place j = L / 8 in that XCD's
+    // sequence, and the units (a tile's rows over one K split) are handed out 8 at a time, all their column blocks,
+    // before the next 8 (so the longest-first order of the tile list survives).  Inside such a group of 8 units x nblk
+    // column blocks one of two things can be shared through an XCD's L2, and the plan says which pays:
+    //  * the token rows (second GEMM): the column blocks of a unit all read the same rows of the intermediate.  XCD c
+    //    takes unit c of the group in every column block.  Right when an expert has one tile, as in the Mixtral prefill
+    //    (the second GEMM read 1.9 x its operands before);
+    //  * the weights: tiles of ONE expert are neighbours in the list (equal cost keys keep the expert order) and read the
+    //    same weight strips column block by column block.  The group's 8 x nblk (unit, column block) pairs are numbered
+    //    column block first, q = 8 * column block + unit, and XCD c takes q in [c * nblk, (c + 1) * nblk): a column
+    //    block's strips are then read by at most two XCDs instead of eight.  Right when experts have many tiles (routing
+    //    with a few popular experts: the first GEMM of the 128-expert layer streamed 3.4 x its weights, at 5.9 TB/s).
+    // The plan counts tiles and experts with tiles; weights are shared when there are at least twice as many tiles.
     int tile, bx, bz;
-    if (MODE == 2) {
-        const int nblk = (N + 64 * kGmWaves - 1) / (64 * kGmWaves);
-        const int L = blockIdx.x, j = L >> 3;
-        const int unit = (j / nblk) * 8 + (L & 7);
-        bx = j % nblk;
+    {
+        const int cols = (MODE == 1) ? 32 * kGmWaves : 64 * kGmWaves;
+        const int nblk = (N + cols - 1) / cols;
+        const int L = blockIdx.x, c = L & 7, j = L >> 3;
+        const int g = j / nblk, sq = j - g * nblk;
+        const bool share_weights = pp.ntiles[0] >= 2 * pp.ntiles[2];
+        int unit;
+        if (share_weights) {
+            const int q = c * nblk + sq;
+            bx = q >> 3;
+            unit = 8 * g + (q & 7);
+        } else if (MODE == 2) {
+            bx = sq;
+            unit = 8 * g + c;
+        } else {
+            // (first GEMM, one tile per expert: a tile per XCD would give each XCD one format, and the formats differ in
+            // cost per tile; the tile's column blocks go round all XCDs instead, launch index = tile * nblk + column block)
+            unit = L / nblk;
+            bx = L - unit * nblk;
+        }
         tile = unit / splits;
         bz = unit - tile * splits;
         if (tile >= max_tiles) return;
-    } else {
-        tile = blockIdx.y;
-        bx = blockIdx.x;
-        bz = 0;
     }
     if (tile >= pp.ntiles[0]) return;
     const int e = pp.tiles[4 * tile + 0];
@@ -972,7 +993,11 @@ int ffn_gemm_init()
 bool ffn_gemm_fits(int T, int H, int F, int E, int k)
 {
     const size_t P = (size_t)T * (size_t)k;
-    if (P / kGemmTileM + (size_t)E > 65535) return false;
+    const size_t tiles = P / kGemmTileM + (size_t)E;
+    if (tiles > 65535) return false;
+    // both launches are one-dimensional: 8 * column blocks * ceil(units / 8) workgroups, units <= 8 * tiles
+    const size_t nblk = ((size_t)(F > H ? F : H) + 32 * kGmWaves - 1) / (32 * kGmWaves);
+    if (8 * nblk * (tiles + 1) >= ((size_t)1 << 31)) return false;
     if ((size_t)T * H * 2 >= ((size_t)1 << 32) || P * (size_t)F * 2 >= ((size_t)1 << 32)) return false;
     return true;
 }
@@ -1004,7 +1029,8 @@ int ffn_gemm_launch(dymoe_ctx* ctx, const void* x, const int32_t* idx, const flo
     constexpr size_t kLdsBytes = kGemmLdsBytes;
     const int max_tiles = P / kGemmTileM + E;
     const int cols1 = 32 * kGmWaves, cols2 = 64 * kGmWaves;
-    const dim3 g1((unsigned)((F + cols1 - 1) / cols1), (unsigned)max_tiles);
+    const int nblk1 = (F + cols1 - 1) / cols1;
+    const dim3 g1((unsigned)(8 * nblk1 * ((max_tiles + 7) / 8)));
     dymoe_launch(ctx, DYMOE_K_GEMM1, (gemm_kernel<1>), g1, dim3(kGmThreads), kLdsBytes, st, xb, xh4, xh2, xh8,
                  (const uint16_t*)nullptr, run_bits, table, plan, P, E, k, H, F, hbuf, (float*)nullptr, max_tiles, 1);
     DYMOE_HIP_LAUNCH_CHECK();

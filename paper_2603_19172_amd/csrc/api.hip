@@ -50,6 +50,7 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(float* __restrict__ sink
 int ffn_static_scratch_address(void** out);
 int ffn_device_flags_address(unsigned** out);
 int ffn_gemm_init();
+int route_init();
 
 }  // namespace dymoe
 
@@ -100,7 +101,7 @@ int dymoe_create(dymoe_ctx** out, int device)
     c->static_scratch = nullptr;
     c->device_flags = nullptr;
     // per-device set-up, with that device current: the address of its copy of the static scratch array, and the
-    // dynamic-LDS limit of the grouped-GEMM kernels (so that no later call has anything left to configure)
+    // dynamic-LDS limits of the grouped-GEMM and matrix-core router kernels (so that no later call has anything left to configure)
     int prev = 0;
     int rc = DYMOE_OK;
     if (hipGetDevice(&prev) != hipSuccess || hipSetDevice(device) != hipSuccess) rc = DYMOE_EHIP;
@@ -108,6 +109,7 @@ int dymoe_create(dymoe_ctx** out, int device)
         rc = dymoe::ffn_static_scratch_address(&c->static_scratch);
         if (rc == DYMOE_OK) rc = dymoe::ffn_device_flags_address(&c->device_flags);
         if (rc == DYMOE_OK) rc = dymoe::ffn_gemm_init();
+        if (rc == DYMOE_OK) rc = dymoe::route_init();
         if (hipSetDevice(prev) != hipSuccess) rc = DYMOE_EHIP;
     }
     if (rc != DYMOE_OK) {

@@ -65,108 +65,106 @@ __global__ __launch_bounds__(NW* kWave) void route_kernel(
 }
 
 // Gating of many tokens against many experts: the logits are a dense contraction
-// [T,H] x [H,E], done on the matrix cores.  A workgroup owns 32 tokens; experts are
-// taken 64 at a time (two 32-expert fragments; the four partial tiles and the logits of
-// all experts then fit in 64 KiB of LDS).  The reduction over H is split
-// between the four wavefronts (every fourth 32-column slice each), so that a
-// wavefront's chain of dependent loads is a quarter as long and the activations
-// are fetched once per workgroup; the four partial tiles meet in LDS.  Tiles are
-// computed transposed (experts down, tokens across): a lane then holds one
-// token's logits of 16 experts.  Softmax and top-k are route_select's.
-// Router rows and activations are read in MFMA operand order straight from
-// global memory (the router is small and stays in L2).
+// [T,H] x [H,E], done on the matrix cores.  A workgroup of eight wavefronts owns 32
+// tokens and takes the experts 128 at a time (four 32-expert fragments).  Both
+// operands are rows of length H in memory, and an MFMA operand wants a lane per row:
+// read that way every load instruction touches 32 or 64 different cache lines for a
+// few bytes of each, and the texture path, which works a line at a time, becomes the
+// limit (measured: 33 of the kernel's 50 us).  So the operands go through LDS: per
+// K-tile of 128 columns the workgroup reads 32 token rows and 128 router rows with
+// 16 lanes per row (a wavefront instruction covers 4 rows x 256 contiguous bytes),
+// one K-tile ahead into registers, and stores them with the 16-byte chunk c of row r
+// at chunk position c ^ (r & 15), so that the operand reads (a lane per row, fixed c)
+// fall on all banks once.  Wavefront w multiplies expert fragment w % 4 over half
+// w / 4 of each K-tile's eight 16-column steps; the two halves meet in LDS and are
+// added in that order.  Tiles are computed transposed (experts down, tokens across):
+// a lane then holds one token's logits of 16 experts.  Softmax and top-k are
+// route_select's, four tokens side by side per wavefront.
 constexpr int kRmTokens = 32;
-constexpr int kRmExperts = 64;
-constexpr int kRmFrags = kRmExperts / 32;
-constexpr int kRmDepth = 4;      // 32-column slices in flight per wavefront
+constexpr int kRmExperts = 128;
+constexpr int kRmWaves = 8;
+constexpr int kRmThreads = kRmWaves * kWave;
+constexpr int kRmBK = 128;       // columns per K-tile
 constexpr int kRmBatch = 4;      // tokens a wavefront takes through softmax and top-k side by side
+constexpr int kRmWChunks = kRmExperts * (kRmBK / 8) / kRmThreads;      // 16-byte chunks of router rows per thread and K-tile
 
-__global__ __launch_bounds__(4 * kWave) void route_mfma_kernel(
+__global__ __launch_bounds__(kRmThreads) void route_mfma_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
     const float* __restrict__ bias, int T, int H, int E, int k, int renorm,
     int32_t* __restrict__ idx, float* __restrict__ w, float* __restrict__ probs)
 {
-    extern __shared__ float smem[];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    extern __shared__ __attribute__((aligned(1024))) float smem[];
+    static_assert(kRmTokens * (kRmBK / 8) == kRmThreads, "one chunk of the token tile per thread");
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int ln = lane & 31, kb = lane >> 5;
-    float* part = smem;                                             // [4 wavefronts][32 tokens][64 experts]
-    float* logit = smem + 4 * kRmTokens * kRmExperts;               // [32 tokens][E]
-    float* selp = logit + (size_t)kRmTokens * E + (size_t)wave * kRmBatch * k;   // [4 wavefronts][kRmBatch][k]
+    char* xs = reinterpret_cast<char*>(smem);                       // [32 rows][256 bytes], swizzled
+    char* ws = xs + kRmTokens * kRmBK * 2;                          // [128 rows][256 bytes], swizzled
+    float* part = reinterpret_cast<float*>(ws + kRmExperts * kRmBK * 2);   // [2 halves][32 tokens][128 experts]
+    float* logit = part + 2 * kRmTokens * kRmExperts;               // [32 tokens][E]
+    float* selp = logit + (size_t)kRmTokens * E + (size_t)wave * kRmBatch * k;   // [8 wavefronts][kRmBatch][k]
     const int t0 = blockIdx.x * kRmTokens;
-    // lane (ln, kb): token ln (B operand) and expert ln of each fragment (A operand);
-    // of every 32-column slice the 16 bytes at columns 16 kb and 16 kb + 8
-    const uint16_t* xrow = x + (size_t)min(t0 + ln, T - 1) * H + kb * 16;
-    const int n_slices = H >> 5;
+    const int n_kt = H / kRmBK;
+    // staging role: chunk (tid % 16) of row (tid / 16) of the token tile, and of router rows tid / 16 + 32 u
+    const int s_row = tid >> 4, s_chunk = tid & 15;
+    const uint16_t* x_src = x + (size_t)min(t0 + s_row, T - 1) * H + s_chunk * 8;
+    const uint32_t s_off = (uint32_t)(s_row * (kRmBK * 2) + ((s_chunk ^ (s_row & 15)) << 4));   // the same swizzle for rows 32 u apart
+    // operand role: fragment f, K half h; lane (ln, kb) reads row ln (token) or 32 f + ln (expert), chunk 2 j + kb
+    const int f = wave & 3, h = wave >> 2;
+    const uint32_t a_off = (uint32_t)((32 * f + ln) * (kRmBK * 2));
+    const uint32_t b_off = (uint32_t)(ln * (kRmBK * 2));
+    const uint32_t sw = (uint32_t)(ln & 15);
     for (int e0 = 0; e0 < E; e0 += kRmExperts) {
-        const uint16_t* wrow[kRmFrags];
+        const uint16_t* w_src[kRmWChunks];
 #pragma unroll
-        for (int f = 0; f < kRmFrags; f++) wrow[f] = wg + (size_t)min(e0 + 32 * f + ln, E - 1) * H + kb * 16;
-        float16_t acc[kRmFrags];
+        for (int u = 0; u < kRmWChunks; u++) w_src[u] = wg + (size_t)min(e0 + s_row + 32 * u, E - 1) * H + s_chunk * 8;
+        float16_t acc;
 #pragma unroll
-        for (int f = 0; f < kRmFrags; f++)
+        for (int i = 0; i < 16; i++) acc[i] = 0.0f;
+        uint4 xr, wr[kRmWChunks];
+        xr = load_global<uint4>(x_src);
 #pragma unroll
-            for (int i = 0; i < 16; i++) acc[f][i] = 0.0f;
-        // kRmDepth slices in flight per wavefront, each register set refilled as soon as it has been used
-        struct Slice {
-            uint4 xv[2], wv[kRmFrags][2];
-        };
-        Slice ring[kRmDepth];
-        auto fetch = [&](int slice, Slice& sv) {
-            sv.xv[0] = load_global<uint4>(xrow + slice * 32);
-            sv.xv[1] = load_global<uint4>(xrow + slice * 32 + 8);
+        for (int u = 0; u < kRmWChunks; u++) wr[u] = load_global<uint4>(w_src[u]);
+        for (int kt = 0; kt < n_kt; kt++) {
+            __syncthreads();                    // the previous tile has been read by every wavefront
+            *reinterpret_cast<uint4*>(xs + s_off) = xr;
 #pragma unroll
-            for (int f = 0; f < kRmFrags; f++) {
-                sv.wv[f][0] = load_global<uint4>(wrow[f] + slice * 32);
-                sv.wv[f][1] = load_global<uint4>(wrow[f] + slice * 32 + 8);
-            }
-        };
+            for (int u = 0; u < kRmWChunks; u++) *reinterpret_cast<uint4*>(ws + s_off + u * (32 * kRmBK * 2)) = wr[u];
+            // the next K-tile's rows, in flight while this one is multiplied (past the end: the last one again, unused)
+            const int kn = min(kt + 1, n_kt - 1);
+            xr = load_global<uint4>(x_src + kn * kRmBK);
 #pragma unroll
-        for (int i = 0; i < kRmDepth; i++) fetch(min(wave + 4 * i, n_slices - 1), ring[i]);
-        for (int sl = wave; sl < n_slices; sl += 4 * kRmDepth) {
+            for (int u = 0; u < kRmWChunks; u++) wr[u] = load_global<uint4>(w_src[u] + kn * kRmBK);
+            __syncthreads();
 #pragma unroll
-            for (int i = 0; i < kRmDepth; i++) {
-                const int cur = sl + 4 * i;
-                if (cur < n_slices) {                          // the same in every lane
-#pragma unroll
-                    for (int f = 0; f < kRmFrags; f++) {
-                        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ring[i].wv[f][0]),
-                                                                        __builtin_bit_cast(bf16x8_t, ring[i].xv[0]), acc[f], 0, 0, 0);
-                        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ring[i].wv[f][1]),
-                                                                        __builtin_bit_cast(bf16x8_t, ring[i].xv[1]), acc[f], 0, 0, 0);
-                    }
-                    const int nx = cur + 4 * kRmDepth;         // past the end: re-read the current slice, never used
-                    fetch(nx < n_slices ? nx : cur, ring[i]);
-                }
+            for (int j = 4 * h; j < 4 * h + 4; j++) {
+                const uint32_t c = ((uint32_t)(2 * j + kb) ^ sw) << 4;
+                const uint4 av = *reinterpret_cast<const uint4*>(ws + a_off + c);
+                const uint4 bv = *reinterpret_cast<const uint4*>(xs + b_off + c);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, bv),
+                                                             acc, 0, 0, 0);
             }
         }
-        // register i of fragment f: expert 32 f + 8 (i / 4) + 4 kb + i % 4, token ln
-        float* mine = part + ((size_t)wave * kRmTokens + ln) * kRmExperts;
+        // register i: expert 32 f + 8 (i / 4) + 4 kb + i % 4, token ln
+        float* mine = part + ((size_t)h * kRmTokens + ln) * kRmExperts + 32 * f;
 #pragma unroll
-        for (int f = 0; f < kRmFrags; f++)
-#pragma unroll
-            for (int g = 0; g < 4; g++)
-                *reinterpret_cast<float4*>(mine + 32 * f + 8 * g + 4 * kb) =
-                    make_float4(acc[f][4 * g], acc[f][4 * g + 1], acc[f][4 * g + 2], acc[f][4 * g + 3]);
+        for (int g = 0; g < 4; g++)
+            *reinterpret_cast<float4*>(mine + 8 * g + 4 * kb) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
         __syncthreads();
-        for (int i = threadIdx.x; i < kRmTokens * kRmExperts; i += 4 * kWave) {
+        for (int i = tid; i < kRmTokens * kRmExperts; i += kRmThreads) {
             const int tok = i / kRmExperts, e = e0 + i % kRmExperts;
-            if (e < E) {
-                // the four quarters of the reduction, in wavefront order
-                const float v = ((part[i] + part[kRmTokens * kRmExperts + i]) + part[2 * kRmTokens * kRmExperts + i]) +
-                                part[3 * kRmTokens * kRmExperts + i];
-                logit[(size_t)tok * E + e] = v + (bias ? bias[e] : 0.0f);
-            }
+            if (e < E) logit[(size_t)tok * E + e] = (part[i] + part[kRmTokens * kRmExperts + i]) + (bias ? bias[e] : 0.0f);
         }
         __syncthreads();
     }
-    // wavefront `wave` finishes tokens wave, wave + 4, ..., kRmBatch at a time
-    for (int first = wave; first < kRmTokens; first += 4 * kRmBatch) {
+    // wavefront `wave` finishes tokens wave, wave + 8, wave + 16, wave + 24, side by side
+    {
         float* lgs[kRmBatch];
         float* sps[kRmBatch];
         int ts[kRmBatch];
 #pragma unroll
         for (int b = 0; b < kRmBatch; b++) {
-            const int tw = first + 4 * b;
+            const int tw = wave + kRmWaves * b;
             lgs[b] = logit + (size_t)tw * E;
             sps[b] = selp + b * k;
             ts[b] = (t0 + tw < T) ? t0 + tw : -1;      // rows past the last token hold a copy of it: computed, not stored
@@ -328,6 +326,18 @@ static int launch_route(dymoe_ctx* ctx, const void* x, const void* wg, const flo
     return DYMOE_OK;
 }
 
+constexpr size_t kRouteMfmaMaxLds = 128 * 1024;
+
+// Once per device, at context creation, with that device current: the matrix-core router asks for more dynamic LDS than
+// the default limit (operand tiles, two partial tiles and the logits of 32 tokens).
+int route_init()
+{
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&route_mfma_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)kRouteMfmaMaxLds) != hipSuccess)
+        return DYMOE_EHIP;
+    return DYMOE_OK;
+}
+
 }  // namespace dymoe
 
 extern "C" {
@@ -344,12 +354,13 @@ int dymoe_route_topk(dymoe_ctx* ctx, const void* x, const void* wg, const float*
     if (!ctx) return DYMOE_ENOCTX;
     if (T == 0) return DYMOE_OK;
     hipStream_t st = (hipStream_t)stream;
-    // many tokens and experts: a dense contraction, on the matrix cores (when its tiles fit in 64 KiB of LDS)
-    const size_t mfma_lds = (4 * (size_t)dymoe::kRmTokens * dymoe::kRmExperts + (size_t)dymoe::kRmTokens * E +
-                             4 * (size_t)dymoe::kRmBatch * k) * sizeof(float);
-    if (T >= 128 && E >= 32 && H % 128 == 0 && mfma_lds <= 65536) {
+    // many tokens and experts: a dense contraction, on the matrix cores (when its tiles fit in the LDS it may ask for)
+    const size_t mfma_lds = (size_t)(dymoe::kRmTokens + dymoe::kRmExperts) * dymoe::kRmBK * 2 +
+                            (2 * (size_t)dymoe::kRmTokens * dymoe::kRmExperts + (size_t)dymoe::kRmTokens * E +
+                             (size_t)dymoe::kRmWaves * dymoe::kRmBatch * k) * sizeof(float);
+    if (T >= 128 && E >= 32 && H % 128 == 0 && mfma_lds <= dymoe::kRouteMfmaMaxLds) {
         dymoe_launch(ctx, DYMOE_K_ROUTE, dymoe::route_mfma_kernel, dim3((unsigned)((T + dymoe::kRmTokens - 1) / dymoe::kRmTokens)),
-                     dim3(4 * dymoe::kWave), mfma_lds, st, (const uint16_t*)x, (const uint16_t*)wg, bias, T, H, E, k, renorm,
+                     dim3(dymoe::kRmThreads), mfma_lds, st, (const uint16_t*)x, (const uint16_t*)wg, bias, T, H, E, k, renorm,
                      idx, w, probs);
         DYMOE_HIP_LAUNCH_CHECK();
         return DYMOE_OK;

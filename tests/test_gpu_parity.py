@@ -414,10 +414,12 @@ def test_ffn_gemm_ragged_tiles(ctx):
 
 
 @pytest.mark.parametrize("loads,fmts", [((160, 129, 33, 8), (4, 2, 4, 2)), ((161, 1, 0, 168), (2, 16, 4, 4)),
-                                        ((320, 5, 150, 140), (4, 4, 8, 16))])
+                                        ((320, 5, 150, 140), (4, 4, 8, 16)), ((276, 159, 130, 257), (4, 2, 2, 4))])
 def test_ffn_gemm_tile_boundaries(ctx, loads, fmts):
-    """Expert loads around the 128-token tile size: full tiles, remainders of 1, 5, 22, 32 and 33 tokens, an
-    expert with no token, in every format."""
+    """Expert loads around the 128-token tile size: full tiles, remainders of 1, 2, 5, 12, 20, 22, 31, 32, 33, 40 and 64
+    tokens, an expert with no token, in every format.  For int4 and int2 experts a remainder of up to 32 tokens rides
+    in the tile before it (129, 130, 159, 160 tokens: one tile of five fragments; 257 and 276: a full tile and one of
+    five fragments); 33 and more, and every remainder of a bf16 or int8 expert, make a tile of their own."""
     T = sum(loads)
     cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=23, T=T, H=256, F=384, E=4, k=1, tier_count=(4,))
     x, _ = synth.activations(cfg)

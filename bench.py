@@ -667,11 +667,13 @@ def main():
         plans = [all_plans[n_.strip()] for n_ in args.stack_plans.split(",") if n_.strip()]
         results = []
         for transfer, slots, tier_name, tcount, tbits, flr in plans:
-            for prefetch in (False, True):
+            # look-ahead off and on under the paper's least-recently-used eviction, then eviction by the layer schedule
+            for prefetch, eviction in ((False, "lru"), (True, "lru"), (False, "cyclic")):
                 by_budget = slots == "budget"
                 stack = DecodeStack(ctx, H, F, E, k, routers, pool, None if by_budget else slots, tcount, tbits,
                                     floor_bits=flr, prefetch=prefetch, transfer=transfer, alpha=0.125, device=dev,
-                                    budget_bytes=int(budget * 1e9) if by_budget else None, lookahead="expected")
+                                    budget_bytes=int(budget * 1e9) if by_budget else None, lookahead="expected",
+                                    eviction=eviction)
                 for s in range(max(1, args.stack_warmup)):      # warm-up (fills the slots it can)
                     stack.step(xs[s % len(xs)])
                 torch.cuda.synchronize()
@@ -686,6 +688,7 @@ def main():
                 stack.close()
                 stt = stack.stats
                 results.append({"transfer": transfer, "tiers": tier_name, "slots": slots, "prefetch": prefetch,
+                                "eviction": eviction,
                                 "steps_per_s": round(args.stack_steps / dt, 3),
                                 "ms_per_layer": round(dt / args.stack_steps / L * 1e3, 3),
                                 "expert_uses": stt["miss"] + stt["promote"] + stt["hit_resident"] + stt["hit_prefetched"],
@@ -732,7 +735,8 @@ def main():
                                                     "format its tiers may name: no copies, no host decisions, a step is "
                                                     "128 launches replayed as one HIP graph", "runs": resident}
         out["stack_decode"] = {"workload": "32 Mixtral-shaped layers, 1 token per step, experts in pinned host memory "
-                                           "(16 distinct experts shared by the 256 layer-experts), look-ahead of the next layer's 2 "
+                                           "(16 distinct experts shared by the 256 layer-experts), every step a different token; eviction 'lru' is the "
+                                           "paper's least-recently-used order, 'cyclic' evicts the expert whose layer comes up last; look-ahead of the next layer's 2 "
                                            "experts on a copy stream of its own, issued when p * min(c, t) >= (1 - p) * c (p share of "
                                            "right predictions, c the copy's time, t a layer's compute time); the 1/3/4 tiers carry "
                                            "an int4 floor in the first and last 4 layers",

@@ -536,6 +536,17 @@ int dymoe_mfma_peak(dymoe_ctx* ctx, int iters, int waves_per_simd, float* sink, 
  *   protect[0..n_protect) are never evicted.  DYMOE_ENOSPC: nothing evictable;
  *   the cache is then unchanged.
  * dymoe_cache_lookup: 1 and the resident format / offset, or 0.
+ * dymoe_cache_set_cyclic, dymoe_cache_request_at: an eviction order for callers whose requests walk a cyclic
+ *   schedule of n_positions positions (the layers of a decoder stack, visited 0 .. L-1 in every step).  The paper
+ *   extends the standard LRU cache; when one pass of the schedule asks for more experts than the cache holds, LRU
+ *   order evicts every entry shortly before its position comes round again.  With n_positions > 0 the request says
+ *   at which position it is made (0 <= position < n_positions), every resident remembers the position it was last
+ *   asked for at, and "least recently used" is replaced by "its position comes up last, counted from the request's"
+ *   (a resident of the request's own position that is not being asked for is a whole cycle away; least recently
+ *   used among equals), for residents and for blocks alike (a block ranks with the resident of its that would go
+ *   last).  The three rules, protection and the unchanged-on-failure guarantee are the same.  n_positions = 0
+ *   (the default) restores LRU order; dymoe_cache_request is dymoe_cache_request_at at the position of the request
+ *   before it.  DYMOE_EINVAL: negative n_positions, position out of range.
  * dymoe_cache_create_pools: the same rules over a fixed partition instead of one budget: slot_counts[i] >= 1 slots
  *   of format_bits[i], laid out format after format (offsets are into an arena of dymoe_cache_block_bytes bytes,
  *   slot j of format i after all slots of the formats before it); a slot never serves another format, so room for a
@@ -563,6 +574,9 @@ int dymoe_cache_create_pools(dymoe_cache** out, int n_formats, const int32_t* fo
 void dymoe_cache_destroy(dymoe_cache* cache);
 int dymoe_cache_request(dymoe_cache* cache, int64_t key, int want_bits, const int64_t* protect, int n_protect,
                         dymoe_cache_action* out);
+int dymoe_cache_set_cyclic(dymoe_cache* cache, int n_positions);
+int dymoe_cache_request_at(dymoe_cache* cache, int64_t key, int want_bits, const int64_t* protect, int n_protect,
+                           int position, dymoe_cache_action* out);
 int dymoe_cache_lookup(const dymoe_cache* cache, int64_t key, int32_t* bits, int64_t* offset);
 size_t dymoe_cache_block_bytes(const dymoe_cache* cache);
 size_t dymoe_cache_bytes_resident(const dymoe_cache* cache);

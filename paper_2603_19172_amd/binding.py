@@ -41,7 +41,8 @@ EXPORTS = [
     "dymoe_stream_copy", "dymoe_mfma_peak", "dymoe_device_flags", "dymoe_format_present",
     "dymoe_decode_front", "dymoe_decode_step", "dymoe_prefetch_submit", "dymoe_prefetch_wait", "dymoe_prefetch_done",
     "dymoe_prefetch_release", "dymoe_residual_rmsnorm",
-    "dymoe_cache_create", "dymoe_cache_create_pools", "dymoe_cache_destroy", "dymoe_cache_request", "dymoe_cache_lookup",
+    "dymoe_cache_create", "dymoe_cache_create_pools", "dymoe_cache_destroy", "dymoe_cache_request", "dymoe_cache_request_at",
+    "dymoe_cache_set_cyclic", "dymoe_cache_lookup",
     "dymoe_cache_block_bytes", "dymoe_cache_bytes_resident",
     "dymoe_timing_enable", "dymoe_timing_read", "dymoe_kernel_name",
 ]
@@ -72,6 +73,10 @@ class CacheAction(C.Structure):
 _vp, _i, _l, _sz, _d = C.c_void_p, C.c_int, C.c_long, C.c_size_t, C.c_double
 lib.dymoe_cache_create.restype = _i
 lib.dymoe_cache_create.argtypes = [C.POINTER(_vp), _sz, _i, _vp, _vp]
+lib.dymoe_cache_set_cyclic.restype = _i
+lib.dymoe_cache_set_cyclic.argtypes = [_vp, _i]
+lib.dymoe_cache_request_at.restype = _i
+lib.dymoe_cache_request_at.argtypes = [_vp, C.c_int64, _i, _vp, _i, _i, C.POINTER(CacheAction)]
 lib.dymoe_cache_create_pools.restype = _i
 lib.dymoe_cache_create_pools.argtypes = [C.POINTER(_vp), _i, _vp, _vp, _vp]
 lib.dymoe_cache_destroy.restype = None

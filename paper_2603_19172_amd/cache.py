@@ -13,7 +13,8 @@ The three rules of the paper:
 Two ways of dividing the device memory set aside for experts, one interface:
 `MixedPrecisionCache` gives every stored format (16, 8, 4 or 2 bits per weight) a fixed
 number of slots (dymoe_cache_create_pools), `ByteBudgetCache` shares one byte budget
-between the formats (dymoe_cache_create).  Either keeps least-recently-used order.
+between the formats (dymoe_cache_create).  Either keeps least-recently-used order, or, told the length of a cyclic
+schedule (`set_cyclic(L)`, requests then carry `position=`), evicts what the schedule comes back to last.
 
 `request` returns what the caller has to do (nothing, or copy the expert's
 `load_bits` format into slot `slot`) and which precision the layer then runs
@@ -83,18 +84,27 @@ class _NativeCache:
     def bytes_resident(self):
         return int(self._B.lib.dymoe_cache_bytes_resident(self._h))
 
-    def _request(self, key, want_bits, protect):
+    def set_cyclic(self, n_positions):
+        """Requests walk a cyclic schedule of n_positions positions (0: back to least-recently-used order)."""
+        self._B._check(self._B.lib.dymoe_cache_set_cyclic(self._h, int(n_positions)), "dymoe_cache_set_cyclic")
+        self._cyclic = int(n_positions)
+
+    def _request(self, key, want_bits, protect, position=None):
         """protect: slot names whose experts must stay."""
         B = self._B
         keep = [self._ident(self._at[s]) for s in protect if s in self._at]
         arr = (C.c_int64 * max(len(keep), 1))(*keep)
         act = B.CacheAction()
-        rc = B.lib.dymoe_cache_request(self._h, self._ident(key), int(want_bits), C.cast(arr, C.c_void_p), len(keep),
-                                       C.byref(act))
+        if position is None:
+            rc = B.lib.dymoe_cache_request(self._h, self._ident(key), int(want_bits), C.cast(arr, C.c_void_p), len(keep),
+                                           C.byref(act))
+        else:
+            rc = B.lib.dymoe_cache_request_at(self._h, self._ident(key), int(want_bits), C.cast(arr, C.c_void_p),
+                                              len(keep), int(position), C.byref(act))
         if rc == B.ENOSPC:
             raise RuntimeError("no evictable room for a %d-bit expert" % want_bits)
         if rc == B.EINVAL:
-            raise ValueError("no %d-bit slots configured" % want_bits)
+            raise ValueError("no %d-bit slots configured, or a position outside the cyclic schedule" % want_bits)
         B._check(rc, "dymoe_cache_request")
         evicted = [self._key[act.evicted[i]] for i in range(act.n_evicted)]
         freed = []
@@ -144,10 +154,10 @@ class MixedPrecisionCache(_NativeCache):
         """Keys resident in the pool of this format."""
         return [k for k, (b, _) in self.where.items() if b == bits]
 
-    def request(self, key, want_bits, protect=()):
+    def request(self, key, want_bits, protect=(), position=None):
         if want_bits not in FORMATS:
             raise ValueError("want_bits must be one of %s" % (FORMATS,))
-        kind, slot, act, evicted, dropped, freed = self._request(key, want_bits, protect)
+        kind, slot, act, evicted, dropped, freed = self._request(key, want_bits, protect, position)
         return Action(kind, slot, act.use_bits, act.load_bits, evicted[0] if evicted else None, dropped)
 
 
@@ -166,6 +176,6 @@ class ByteBudgetCache(_NativeCache):
         self._init(h)
         self.block_bytes = int(B.lib.dymoe_cache_block_bytes(h))
 
-    def request(self, key, want_bits, protect=()):
-        kind, slot, act, evicted, dropped, freed = self._request(key, want_bits, protect)
+    def request(self, key, want_bits, protect=(), position=None):
+        kind, slot, act, evicted, dropped, freed = self._request(key, want_bits, protect, position)
         return Action(kind, slot, act.use_bits, act.load_bits, evicted if evicted else None, dropped, freed)

@@ -20,6 +20,12 @@
 // (a) on equal age.  Evicting a block frees all its slots and hands the block
 // over to the requesting format.
 //
+// Which resident goes first is least-recently-used order (the paper extends the standard LRU cache), or, when the
+// caller says that requests walk a cyclic schedule of positions (dymoe_cache_set_cyclic: the layers of a decoder,
+// visited 0, 1, ..., L-1, 0, ...), the resident whose position comes up last: a stack of layers touches every layer's
+// experts once per step, and when a step's working set exceeds the cache, LRU order evicts each entry shortly before
+// its layer comes round again and never hits, while "farthest next visit first" keeps the layers just ahead.
+//
 // The same rules over a FIXED partition (dymoe_cache_create_pools): so many
 // slots per format, each slot a block of its own that never changes hands; room
 // for a request then comes from its own format's pool alone.
@@ -39,6 +45,7 @@ struct Resident {
     int block;
     int slot;
     uint64_t tick;  // time of last use
+    int pos;        // position of the cyclic schedule it was last asked for at (0 without a schedule)
 };
 
 struct Block {
@@ -61,6 +68,20 @@ struct dymoe_cache {
     std::vector<Block> blocks;
     std::unordered_map<int64_t, Resident> where;
     uint64_t clock = 0;
+    int n_pos = 0;                     // length of the cyclic schedule (0: none, least recently used goes first)
+    int cur_pos = 0;                   // position of the request being served
+
+    // What goes first has the LARGEST value.  Without a schedule: the oldest use.  With one: the position that comes up
+    // last counted from the request's (a resident of the request's own position was not wanted this time round and
+    // is a whole cycle away), the older use among equals.
+    uint64_t evict_rank(const Resident& r) const
+    {
+        const uint64_t age = clock - r.tick;                 // < 2^40 in any run that finishes
+        if (n_pos <= 0) return age;
+        int d = (r.pos - cur_pos) % n_pos;
+        if (d <= 0) d += n_pos;
+        return ((uint64_t)d << 40) | (age & ((1ull << 40) - 1));
+    }
 
     int format_of(int b) const
     {
@@ -205,18 +226,35 @@ int dymoe_cache_lookup(const dymoe_cache* c, int64_t key, int32_t* bits, int64_t
     return 1;
 }
 
+int dymoe_cache_set_cyclic(dymoe_cache* c, int n_positions)
+{
+    if (!c || n_positions < 0) return DYMOE_EINVAL;
+    c->n_pos = n_positions;
+    c->cur_pos = 0;
+    return DYMOE_OK;
+}
+
 int dymoe_cache_request(dymoe_cache* c, int64_t key, int want_bits, const int64_t* protect, int n_protect,
                         dymoe_cache_action* out)
 {
+    return dymoe_cache_request_at(c, key, want_bits, protect, n_protect, c ? c->cur_pos : 0, out);
+}
+
+int dymoe_cache_request_at(dymoe_cache* c, int64_t key, int want_bits, const int64_t* protect, int n_protect,
+                           int position, dymoe_cache_action* out)
+{
     if (!c || !out || n_protect < 0 || (n_protect > 0 && !protect) || key == kNoKey) return DYMOE_EINVAL;
+    if (position < 0 || (c->n_pos > 0 && position >= c->n_pos)) return DYMOE_EINVAL;
     const int f = c->format_of(want_bits);
     if (f < 0) return DYMOE_EINVAL;
+    c->cur_pos = position;
     out->n_evicted = 0;
     out->dropped_offset = -1;
     c->clock++;
     auto it = c->where.find(key);
     if (it != c->where.end() && c->bits[it->second.fmt] >= want_bits) {      // Conservative Reuse, or an exact hit
         it->second.tick = c->clock;
+        it->second.pos = position;
         out->kind = DYMOE_CACHE_HIT;
         out->use_bits = c->bits[it->second.fmt];
         out->load_bits = 0;
@@ -232,35 +270,40 @@ int dymoe_cache_request(dymoe_cache* c, int64_t key, int want_bits, const int64_
     const bool promote = it != c->where.end();
     // Room is found before anything is changed, so that a request that cannot be served leaves the cache as it was.
     if (!c->take_free(f, block, slot)) {
-        // (a) least recently used unprotected resident of the requested format
+        // (a) the unprotected resident of the requested format that goes first (evict_rank: least recently used, or
+        //     farthest next visit under a cyclic schedule)
         int64_t own = kNoKey;
-        uint64_t own_tick = UINT64_MAX;
+        uint64_t own_rank = 0;
         for (const auto& kv : c->where)
-            if (kv.second.fmt == f && kv.first != key && kv.second.tick < own_tick && !is_protected(kv.first)) {
-                own = kv.first;
-                own_tick = kv.second.tick;
+            if (kv.second.fmt == f && kv.first != key && !is_protected(kv.first)) {
+                const uint64_t rk = c->evict_rank(kv.second);
+                if (own == kNoKey || rk > own_rank || (rk == own_rank && kv.first < own)) {
+                    own = kv.first;
+                    own_rank = rk;
+                }
             }
-        // (b) least recently used block of another format without a protected resident (nor the expert being promoted:
-        //     its slot is released below, by the promotion itself)
+        // (b) the block of another format without a protected resident that goes first, a block ranking with the
+        //     resident of its that goes LAST (the expert being promoted does not count: its slot is released below, by
+        //     the promotion itself)
         int other = -1;
-        uint64_t other_tick = UINT64_MAX;
+        uint64_t other_rank = 0;
         for (size_t i = 0; i < c->blocks.size(); i++) {
             const Block& b = c->blocks[i];
             if (b.fmt < 0 || b.fmt == f || b.pin >= 0) continue;      // (a pinned block serves its own format only)
-            uint64_t newest = 0;
+            uint64_t keep = UINT64_MAX;          // the smallest rank among the block's residents
             bool ok = true;
             for (int64_t k : b.keys) {
                 if (k == kNoKey) continue;
                 if (k != key && is_protected(k)) ok = false;
-                if (k != key) newest = std::max(newest, c->where[k].tick);
+                if (k != key) keep = std::min(keep, c->evict_rank(c->where[k]));
             }
-            if (ok && newest < other_tick) {
+            if (ok && (other < 0 || keep > other_rank)) {
                 other = (int)i;
-                other_tick = newest;
+                other_rank = keep;
             }
         }
         if (own == kNoKey && other < 0) return DYMOE_ENOSPC;
-        if (own != kNoKey && own_tick <= other_tick) {
+        if (own != kNoKey && (other < 0 || own_rank >= other_rank)) {
             const Resident r = c->where[own];
             out->evicted[out->n_evicted++] = own;
             c->release(own);
@@ -298,7 +341,7 @@ int dymoe_cache_request(dymoe_cache* c, int64_t key, int want_bits, const int64_
     Block& b = c->blocks[block];
     b.keys[slot] = key;
     b.used++;
-    Resident r{f, block, slot, c->clock};
+    Resident r{f, block, slot, c->clock, position};
     c->where[key] = r;
     out->kind = promote ? DYMOE_CACHE_PROMOTE : DYMOE_CACHE_MISS;
     out->use_bits = want_bits;

@@ -192,7 +192,7 @@ class _Slot:
 class ExpertStack:
     def __init__(self, ctx, T, phase, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
                  prefetch=True, transfer="bf16", alpha=0.125, k_hh=0, predict_t=None, device="cuda:0",
-                 budget_bytes=None, lookahead="always"):
+                 budget_bytes=None, lookahead="always", eviction="lru"):
         """T tokens per step; phase "decode" (gate-score importance, Eq. 3; the k experts the next layer is
         predicted to route the token to are fetched ahead, Eq. 8 with t = k) or "prefill" (heavy-hitter
         importance over the k_hh highest-norm tokens, Eq. 2; the predict_t experts of highest predicted
@@ -238,6 +238,13 @@ class ExpertStack:
             self.arena = torch.empty((n_blocks * self.cache.block_bytes,), dtype=torch.uint8, device=device)
             self._slot_bytes = sizes
             self.slots = {}                         # (format, offset) -> _Slot, made when first handed out
+        # eviction order of the expert cache: least recently used (the paper's), or "cyclic": the layers are visited in
+        # the same order in every step, so what goes first is the resident whose layer comes up last
+        if eviction not in ("lru", "cyclic"):
+            raise ValueError("eviction: 'lru' or 'cyclic'")
+        self.eviction = eviction
+        if eviction == "cyclic":
+            self.cache.set_cyclic(self.L)
         per_layer = isinstance(tier_count[0], (tuple, list))
         self.tiers = [tuple(tc) for tc in tier_count] if per_layer else [tuple(tier_count)] * self.L
         if len(self.tiers) != self.L or any(len(tc) != len(tier_bits) for tc in self.tiers):
@@ -436,7 +443,7 @@ class ExpertStack:
                 w0.record(cs)
             for e, b in need:
                 key = (l, e)
-                act = self.cache.request(key, want(b), protect)
+                act = self.cache.request(key, want(b), protect, position=l if self.eviction == "cyclic" else None)
                 protect.add(act.slot)
                 slot = self._slot(act.slot)
                 if act.load_bits:
@@ -484,7 +491,7 @@ class ExpertStack:
                     if not self._worth_fetching_ahead(self.pool.nbytes[want(pb)]):
                         self.stats["prefetch_declined"] += 1
                         continue
-                    act = self.cache.request(key, want(pb), protect)
+                    act = self.cache.request(key, want(pb), protect, position=l + 1 if self.eviction == "cyclic" else None)
                     protect.add(act.slot)
                     self._fill(act, key, ahead=True)
                     self.stats["prefetch_issued"] += 1
@@ -549,10 +556,11 @@ class DecodeStack(ExpertStack):
     """One token per step (Sec. 4.2.2 importance, Eq. 8 prefetch)."""
 
     def __init__(self, ctx, H, F, E, k, routers, pool, slots, tier_count, tier_bits, floor_bits=None,
-                 prefetch=True, transfer="bf16", alpha=0.125, device="cuda:0", budget_bytes=None, lookahead="always"):
+                 prefetch=True, transfer="bf16", alpha=0.125, device="cuda:0", budget_bytes=None, lookahead="always",
+                 eviction="lru"):
         super().__init__(ctx, 1, "decode", H, F, E, k, routers, pool, slots, tier_count, tier_bits,
                          floor_bits=floor_bits, prefetch=prefetch, transfer=transfer, alpha=alpha, device=device,
-                         budget_bytes=budget_bytes, lookahead=lookahead)
+                         budget_bytes=budget_bytes, lookahead=lookahead, eviction=eviction)
 
 
 class PrefillStack(ExpertStack):

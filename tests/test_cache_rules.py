@@ -226,3 +226,82 @@ def test_budget_cache_rejects_bad_arguments():
     assert B.lib.dymoe_cache_request(h, 1, 4, None, 0, C.byref(act)) == B.OK and act.kind == B.CACHE_MISS
     assert B.lib.dymoe_cache_lookup(h, 1, None, None) == 1 and B.lib.dymoe_cache_lookup(h, 2, None, None) == 0
     B.lib.dymoe_cache_destroy(h)
+
+
+# ------------------------------------------------------------------ eviction order under a cyclic schedule
+
+def _cycle_misses(cache, n_pos, per_pos, cycles, position_arg):
+    """Every position asks for its `per_pos` keys in every cycle; returns the misses of the last cycle."""
+    misses = 0
+    for c in range(cycles):
+        misses = 0
+        for pos in range(n_pos):
+            for j in range(per_pos):
+                a = cache.request((pos, j), 4, position=pos if position_arg else None)
+                misses += a.kind != "hit"
+    return misses
+
+
+def test_cyclic_schedule_keeps_what_comes_up_next_where_lru_keeps_nothing():
+    """Four positions visited in a circle, one key each, three slots: least-recently-used order evicts every key
+    just before its turn (four misses per cycle, for ever); told the schedule, the cache evicts the key whose
+    position comes up last and misses once per cycle, which is the least any policy can (Belady)."""
+    lru = MixedPrecisionCache({4: 3})
+    assert _cycle_misses(lru, 4, 1, 6, position_arg=False) == 4
+    cyc = MixedPrecisionCache({4: 3})
+    cyc.set_cyclic(4)
+    assert _cycle_misses(cyc, 4, 1, 6, position_arg=True) == 1
+    # the same under one byte budget
+    b = ByteBudgetCache(3 * 1024, {4: 1024})
+    b.set_cyclic(4)
+    assert _cycle_misses(b, 4, 1, 6, position_arg=True) == 1
+    b.set_cyclic(0)                                     # back to least recently used
+    assert _cycle_misses(b, 4, 1, 6, position_arg=False) == 4
+
+
+def test_cyclic_order_step_by_step_and_its_arguments():
+    c = MixedPrecisionCache({4: 3})
+    c.set_cyclic(4)
+    seq = [(("k0", 0), "miss", None), (("k1", 1), "miss", None), (("k2", 2), "miss", None),
+           # at position 3 the residents come up in 1 (k0), 2 (k1) and 3 (k2) positions: k2, used last, goes first
+           (("k3", 3), "miss", "k2"),
+           (("k0", 0), "hit", None), (("k1", 1), "hit", None),
+           # at position 2: k3 comes up next, k0 in 2, k1 in 3
+           (("k2", 2), "miss", "k1"),
+           (("k3", 3), "hit", None), (("k0", 0), "hit", None),
+           # a key that is not asked for at its own position is a whole cycle away: at position 1, k0 (position 0) is 3
+           # away, k2 1 away, k3 2 away, so k0 goes; a second key at position 1 then finds ... k1 itself protected
+           (("k1", 1), "miss", "k0")]
+    for (key, pos), kind, evicted in seq:
+        a = c.request(key, 4, position=pos)
+        assert (a.kind, a.evicted) == (kind, evicted), (key, pos, a)
+    a = c.request("other", 4, protect=[c.resident("k1")], position=1)     # k2 comes up next, k3 after it: k3 goes
+    assert a.evicted == "k3"
+    with pytest.raises(ValueError):
+        c.request("k9", 4, position=4)                  # outside the schedule
+    with pytest.raises(ValueError):
+        c.request("k9", 4, position=-1)
+    from paper_2603_19172_amd import binding as B
+    assert B.lib.dymoe_cache_set_cyclic(None, 4) == B.EINVAL and B.lib.dymoe_cache_set_cyclic(c._h, -1) == B.EINVAL
+
+
+def test_cyclic_order_random_walk_keeps_the_rules():
+    """The three rules, protection and consistency do not depend on the eviction order."""
+    import random
+    rnd = random.Random(11)
+    c = _cache(3)
+    c.set_cyclic(5)
+    for step in range(3000):
+        pos = step % 5
+        key = (pos, rnd.randrange(8))
+        want = rnd.choice((16, 4, 4, 2, 2, 2))
+        before = c.resident(key)
+        a = c.request(key, want, position=pos)
+        if before is not None and before[0] >= want:
+            assert a.kind == "hit" and a.slot == before and a.load_bits == 0
+        else:
+            assert a.kind == ("promote" if before is not None else "miss") and a.use_bits == want
+        assert c.resident(key) == a.slot
+        for k in a.evicted or ():
+            assert c.resident(k) is None and k != key
+        _consistent(c)

@@ -66,7 +66,8 @@ TIERS3 = ((1, 3, 4), (16, 4, 2))
 TIERS4 = ((1, 2, 2, 3), (16, 8, 4, 2))
 
 
-def _small_stack(ctx, L, slots, prefetch, seed0, transfer="bf16", pool=None, tiers=TIERS3, budget_bytes=None):
+def _small_stack(ctx, L, slots, prefetch, seed0, transfer="bf16", pool=None, tiers=TIERS3, budget_bytes=None,
+                 eviction="lru"):
     H, F, E, k = 256, 512, 8, 2
     cfgs = [synth.scaled(synth.CONFIGS["tiny"], T=1, phase="decode", config_id=seed0 + l) for l in range(L)]
     routers_np = [synth.router(c)[0] for c in cfgs]
@@ -80,7 +81,7 @@ def _small_stack(ctx, L, slots, prefetch, seed0, transfer="bf16", pool=None, tie
     floor = [4] + [0] * (L - 2) + [4]
     stack = DecodeStack(ctx, H, F, E, k, [to_bf16(r) for r in routers_np], pool, slots, tiers[0], tiers[1],
                         floor_bits=floor, prefetch=prefetch, transfer=transfer, alpha=0.25, device=DEV,
-                        budget_bytes=budget_bytes)
+                        budget_bytes=budget_bytes, eviction=eviction)
     expert_matrices = lambda l, e: mats[pool.entry(l, e)]
     return stack, routers_np, expert_matrices, floor, cfgs[0]
 
@@ -163,6 +164,49 @@ def test_stack_lookahead_by_the_expected_value_rule_changes_nothing_but_the_copi
     assert st.get("prefetch_declined", 0) > 0                       # the first two steps at least
     assert st.get("prefetch_issued", 0) + st.get("prefetch_declined", 0) > 0
     assert _uses(st) == L * 2 * steps
+
+
+def test_stack_eviction_by_the_layer_schedule_changes_the_copies_not_the_results(ctx):
+    """eviction="cyclic": the cache is told that the layers come round in order and evicts the expert whose layer
+    comes up last.  With bf16 travelling, what is run does not depend on what is resident, so every hidden state and
+    decision is what the least-recently-used order gives; with fewer slots than a step's experts LRU order never hits,
+    the schedule order does."""
+    L, steps = 4, 10
+    outs, stats, traces = {}, {}, {}
+    for ev in ("lru", "cyclic"):
+        stack, routers_np, expert_matrices, floor, cfg0 = _small_stack(ctx, L, 5, False, 2600, eviction=ev)
+        hs = []
+        for s in range(steps):
+            x, _ = synth.activations(synth.scaled(cfg0, config_id=2700 + s % 3))     # three tokens in turn: some reuse
+            hs.append(stack.step(to_bf16(x)).clone())
+        stack.close()
+        outs[ev], stats[ev], traces[ev] = hs, dict(stack.stats), list(stack.trace)
+    assert traces["lru"] == traces["cyclic"]
+    for a, b in zip(outs["lru"], outs["cyclic"]):
+        assert torch.equal(a, b)
+    assert _uses(stats["lru"]) == _uses(stats["cyclic"]) == L * 2 * steps
+    # 5 slots, 8 expert uses per step
+    assert stats["lru"].get("hit_resident", 0) == 0 and stats["cyclic"].get("hit_resident", 0) > 0
+    assert stats["cyclic"]["bytes_copied"] < stats["lru"]["bytes_copied"]
+
+
+def test_stack_eviction_by_the_layer_schedule_under_one_budget_keeps_the_cache_rules(ctx):
+    """The same order with the assigned formats under one byte budget: what is run may differ from the LRU run (an
+    expert found resident at a higher precision is run at it), so the check is the oracle told what was run."""
+    L, steps = 4, 6
+    budget = 5 * (6 * 256 * 512 + 400 * 1024)           # five blocks of the bf16 size: evictions all the time
+    stack, routers_np, expert_matrices, floor, cfg0 = _small_stack(ctx, L, None, False, 2800, transfer="assigned",
+                                                                   budget_bytes=budget, eviction="cyclic")
+    outs = []
+    for s in range(steps):
+        x, _ = synth.activations(synth.scaled(cfg0, config_id=2900 + s % 3))
+        outs.append((x, stack.step(to_bf16(x)).clone()))
+    stack.close()
+    assert _uses(stack.stats) == L * 2 * steps
+    for step in stack.trace:
+        for (ex, assigned, used) in step:
+            assert all(u >= a for a, u in zip(assigned, used))      # never below the assigned precision
+    _check_against_oracle(outs, stack.trace, routers_np, expert_matrices, floor)
 
 
 def test_stack_with_room_for_everything_copies_each_expert_once(ctx):

@@ -413,6 +413,30 @@ def test_ffn_gemm_ragged_tiles(ctx):
     assert err <= FFN_TOL
 
 
+def test_ffn_gemm_many_tiles_per_expert_and_two_k_splits(ctx):
+    """Two experts with 700 tokens each (six tiles apiece: the launches then share weight strips, not token rows,
+    between the workgroups of an XCD) and an F of two 2048-column segments (two K splits in the second GEMM): 48
+    sampled rows against the oracle, every row against the GEMV path."""
+    cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=24, T=700, H=512, F=4096, E=2, k=2, tier_count=(2,))
+    x, _ = synth.activations(cfg)
+    idx, w = routed(cfg, x)
+    assert sorted(idx[0].tolist()) == [0, 1]
+    bits_np = np.array([4, 16], np.uint8)
+    host, dev, table, keep = build_layer(cfg, bits_np, path=B.PATH_GEMM)
+    y = run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM)
+    rows = np.random.default_rng(24).choice(cfg.T, 48, replace=False)
+    rows[:4] = (0, 127, 128, cfg.T - 1)
+    sub = synth.scaled(cfg, T=len(rows))
+    ref = oracle_ffn(sub, x[rows], idx[rows], w[rows], bits_np, host)
+    err = rel_err_per_token(y[rows], ref)
+    host_r, dev_r, table_r, keep_r = build_layer(cfg, bits_np, path=B.PATH_GEMV)
+    y_gemv = run_ffn(ctx, cfg, x, idx, w, bits_np, table_r, B.PATH_GEMV)
+    gap = rel_err_per_token(y, y_gemv)
+    print("gemm many tiles per expert: err vs oracle %.3e on %d rows, vs GEMV %.3e on all rows" % (err, len(rows), gap))
+    assert err <= FFN_TOL and gap <= FFN_TOL
+    assert np.array_equal(y, run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM))     # and the same bits again
+
+
 @pytest.mark.parametrize("loads,fmts", [((160, 129, 33, 8), (4, 2, 4, 2)), ((161, 1, 0, 168), (2, 16, 4, 4)),
                                         ((320, 5, 150, 140), (4, 4, 8, 16)), ((276, 159, 130, 257), (4, 2, 2, 4))])
 def test_ffn_gemm_tile_boundaries(ctx, loads, fmts):

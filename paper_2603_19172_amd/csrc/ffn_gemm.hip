@@ -484,6 +484,34 @@ __device__ __forceinline__ uint4 lds_read16(uint32_t addr)
     return __builtin_bit_cast(uint4, v);
 }
 
+__device__ __forceinline__ void lds_write16(uint32_t addr, const uint4 v)
+{
+    *(__attribute__((address_space(3))) u32x4_t*)(uintptr_t)addr = __builtin_bit_cast(u32x4_t, v);
+}
+
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void lds_write8(uint32_t addr, const uint2 v)
+{
+    *(__attribute__((address_space(3))) u32x2_t*)(uintptr_t)addr = __builtin_bit_cast(u32x2_t, v);
+}
+
+__device__ __forceinline__ uint32_t lds_read4(uint32_t addr)
+{
+    return *(const __attribute__((address_space(3))) uint32_t*)(uintptr_t)addr;
+}
+
+__device__ __forceinline__ void lds_write4(uint32_t addr, uint32_t v)
+{
+    *(__attribute__((address_space(3))) uint32_t*)(uintptr_t)addr = v;
+}
+
+// second GEMM's epilogue: a wavefront's own LDS area, 32 rows of 256 bytes + 16 of padding
+constexpr uint32_t kEpiRowBytes = 272;
+constexpr uint32_t kEpiWaveBytes = 32 * kEpiRowBytes;
+static_assert(kGmWaves * kEpiWaveBytes <= (uint32_t)kXsBufBytes, "the epilogue areas fit in the first token-tile buffer");
+static_assert(kGemmTileTall * kEpiRowBytes <= 2 * (uint32_t)kXsBufBytes, "the first GEMM's output rows fit in the two buffers");
+
 // The token operands of one MFMA step (two 16-byte chunks of one row).
 struct XOps {
     uint4 t0, t1;
@@ -758,15 +786,55 @@ __device__ __forceinline__ void gemm_tile(
     }
 
     // epilogue.  D layout: lane (ln, kb), register i -> weight row 8*(i/4) + 4*kb + i%4, token ln
+    if constexpr (MODE == 2) {
+        // Down projection: a lane holds, of its token's row, 4 consecutive outputs per register group: stored as they
+        // are, one instruction would touch 32 rows with 32 bytes each.  The wavefront turns each fragment round in LDS
+        // instead (the token tiles are done with: the loop's last barrier follows the last tile's arithmetic and the
+        // last copy's wait): 32 rows of its 64 columns, 256 bytes + 16 of padding per row (the padding keeps both the
+        // lane-per-row writes and the 16-lanes-per-row reads free of bank conflicts, and holds the row's pair index),
+        // read back so that 16 lanes store one row's 256 contiguous bytes.  A wavefront's LDS accesses execute in
+        // order, and the area is its own: no barrier.
+        const uint32_t ebase = xs_base + (uint32_t)wave * kEpiWaveBytes;
+        const long jbase = ((long)nblock * kGmWaves + wave) * 64;
+        const int rsub = lane >> 4, chunk = lane & 15;
+        const bool col_ok = strip_ok[chunk >> 3];
+        const uint32_t wr = ebase + (uint32_t)ln * kEpiRowBytes + (uint32_t)kb * 16u;
+#pragma unroll
+        for (int tf = 0; tf < NTF; tf++) {
+            const int trow = 32 * tf + ln;
+            const int pair_w = (trow < rows) ? perm[row0 + trow] : -1;
+#pragma unroll
+            for (int s = 0; s < 2; s++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    uint4 o;
+                    o.x = __float_as_uint(acc[s][tf][4 * g + 0]);
+                    o.y = __float_as_uint(acc[s][tf][4 * g + 1]);
+                    o.z = __float_as_uint(acc[s][tf][4 * g + 2]);
+                    o.w = __float_as_uint(acc[s][tf][4 * g + 3]);
+                    lds_write16(wr + (uint32_t)(s * 128 + g * 32), o);
+                }
+            if (kb == 0) lds_write4(ebase + (uint32_t)ln * kEpiRowBytes + 256u, (uint32_t)pair_w);
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const uint32_t ra = ebase + (uint32_t)(rsub + 4 * j) * kEpiRowBytes;
+                const int pair = (int)lds_read4(ra + 256u);
+                const uint4 v = lds_read16(ra + (uint32_t)chunk * 16u);
+                if (pair >= 0 && col_ok)
+                    *reinterpret_cast<uint4*>(oout + (long)pair * N + jbase + 4 * chunk) = v;
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int tf = 0; tf < NTF; tf++) {
         const int trow = 32 * tf + ln;
-        const bool row_ok = trow < rows;
         if (MODE == 1) {
             // SwiGLU; the 16-bit intermediate is written in the column order the
             // down projection of this expert reads (see perm8 / perm16)
-            const long f0 = nt_a * 32;
-            uint16_t* dst = hout + (long)(row0 + min(trow, rows - 1)) * N + f0;
+            // The workgroup's four strips are 128 adjacent features: every wavefront writes its 64 bytes of each
+            // row into LDS (272 bytes per row), and after one barrier the rows go out whole, 16 lanes per row.
+            const uint32_t dst = xs_base + (uint32_t)trow * kEpiRowBytes + (uint32_t)wave * 64u;
             uint32_t pk[4][2];
 #pragma unroll
             for (int g = 0; g < 4; g++) {
@@ -787,11 +855,8 @@ __device__ __forceinline__ void gemm_tile(
             }
             if constexpr (BITS == 16 || BITS == 8) {
                 // features f0 + 8g + 4kb .. +4, natural order
-                if (row_ok && strip_ok[0]) {
 #pragma unroll
-                    for (int g = 0; g < 4; g++)
-                        *reinterpret_cast<uint2*>(dst + 8 * g + 4 * kb) = make_uint2(pk[g][0], pk[g][1]);
-                }
+                for (int g = 0; g < 4; g++) lds_write8(dst + (uint32_t)(2 * (8 * g + 4 * kb)), make_uint2(pk[g][0], pk[g][1]));
             } else if constexpr (BITS == 4) {
                 // group of 8 features e0..e7: this lane holds e(4kb..4kb+3); stored order is
                 // e0,e4,e1,e5 | e2,e6,e3,e7: the two kb lanes trade one packed pair
@@ -803,13 +868,12 @@ __device__ __forceinline__ void gemm_tile(
                     const uint32_t hi = kb ? pk[g][1] : got;                 // kb0: (e4,e5)  kb1: (e6,e7)
                     const uint32_t o0 = (lo & 0xffffu) | (hi << 16);
                     const uint32_t o1 = (lo >> 16) | (hi & 0xffff0000u);
-                    if (row_ok && strip_ok[0])
-                        *reinterpret_cast<uint2*>(dst + 8 * g + 4 * kb) = make_uint2(o0, o1);
+                    lds_write8(dst + (uint32_t)(2 * (8 * g + 4 * kb)), make_uint2(o0, o1));
                 }
             } else {
                 // group of 16 features = register groups (g, g+1), g even: this lane holds
                 // e(4kb+i) and e(8+4kb+i); stored order interleaves them at 8kb .. 8kb+7
-                if (row_ok && strip_ok[0]) {
+                {
 #pragma unroll
                     for (int g = 0; g < 4; g += 2) {
                         const uint32_t a01 = pk[g][0], a23 = pk[g][1], b01 = pk[g + 1][0], b23 = pk[g + 1][1];
@@ -818,28 +882,20 @@ __device__ __forceinline__ void gemm_tile(
                         o.y = (a01 >> 16) | (b01 & 0xffff0000u);
                         o.z = (a23 & 0xffffu) | (b23 << 16);
                         o.w = (a23 >> 16) | (b23 & 0xffff0000u);
-                        *reinterpret_cast<uint4*>(dst + 8 * g + 8 * kb) = o;
+                        lds_write16(dst + (uint32_t)(2 * (8 * g + 8 * kb)), o);
                     }
                 }
             }
-        } else if (row_ok) {
-            const int pair = perm[row0 + trow];
-#pragma unroll
-            for (int s = 0; s < 2; s++) {
-                if (strip_ok[s]) {
-                    const long j0 = (s ? nt_b : nt_a) * 32;
-                    float* dst = oout + (long)pair * N + j0 + 4 * kb;
-#pragma unroll
-                    for (int g = 0; g < 4; g++) {
-                        float4 o;
-                        o.x = acc[s][tf][4 * g + 0];
-                        o.y = acc[s][tf][4 * g + 1];
-                        o.z = acc[s][tf][4 * g + 2];
-                        o.w = acc[s][tf][4 * g + 3];
-                        *reinterpret_cast<float4*>(dst + 8 * g) = o;
-                    }
-                }
-            }
+        }
+    }
+    if (MODE == 1) {
+        __syncthreads();
+        const long f0 = (long)nblock * (32 * kGmWaves);
+        const int chunk = tid & 15;                        // 8 features
+        const bool col_ok = f0 + 8 * chunk < N;
+        for (int r = tid >> 4; r < rows; r += kGmThreads / 16) {
+            const uint4 v = lds_read16(xs_base + (uint32_t)r * kEpiRowBytes + (uint32_t)chunk * 16u);
+            if (col_ok) *reinterpret_cast<uint4*>(hout + (long)(row0 + r) * N + f0 + 8 * chunk) = v;
         }
     }
 }

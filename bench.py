@@ -510,7 +510,7 @@ def main():
         # throughput: the step in either launch mode, the faster one reported, as for the other workloads
         fdt, fmode, f_launch_us = time_call(lambda: flay.step(fx, fwg, fbias, fstore), args.prefill_steps, 3)
         # per-kernel times: eager launches with events on the dispatches
-        fnames = ["route", "token_norm", "importance", "assign", "quantize", "plan", "gemm1", "gemm2", "gemm_combine"]
+        fnames = ["route", "route_select", "token_norm", "importance", "assign", "quantize", "plan", "gemm1", "gemm2", "gemm_combine"]
         ctx.timing_enable(fnames)
         for _ in range(args.prefill_steps):
             flay.step(fx, fwg, fbias, fstore)

@@ -585,11 +585,12 @@ size_t dymoe_cache_bytes_resident(const dymoe_cache* cache);
  * Per-kernel timing (diagnostic; the paper reports only end-to-end latency,
  * Sec. 6.1 "Key Metrics", so these serve the roofline accounting).
  * dymoe_timing_enable: launches of the kernels whose bit is set in kernel_mask
- * (bit i = kernel id i, ids 0..20 in the order route, token_norm, importance,
+ * (bit i = kernel id i, ids 0..21 in the order route, token_norm, importance,
  * assign, quantize, gemv_phase1, gemv_phase2, gemv_combine, plan, gemm1, gemm2,
  * gemm_combine, stream_copy, decode_front, attn_stats, attn_colsum, gptq_group,
- * gptq_trail, gptq_hessian, gptq_factor, mfma_peak; gemv_combine is reserved: the decode path's second phase
- * writes y itself and no launch carries that id) carry a start and a stop HIP event on the dispatch itself, so
+ * gptq_trail, gptq_hessian, gptq_factor, mfma_peak, route_select; gemv_combine is reserved: the decode path's
+ * second phase writes y itself and no launch carries that id; route_select is the second of the two launches
+ * dymoe_route_topk makes when it cuts the logits by experts as well as by tokens, route then names the first) carry a start and a stop HIP event on the dispatch itself, so
  * the interval is the kernel's execution time on the launch stream; 0 switches
  * timing off.  Either way, records not yet read are dropped.
  * dymoe_timing_read: waits for the recorded launches of `kernel`, drops their records and returns

@@ -49,7 +49,7 @@ EXPORTS = [
 
 KERNELS = ["route", "token_norm", "importance", "assign", "quantize", "gemv_phase1",
            "gemv_phase2", "gemv_combine", "plan", "gemm1", "gemm2", "gemm_combine", "stream_copy", "decode_front",
-           "attn_stats", "attn_colsum", "gptq_group", "gptq_trail", "gptq_hessian", "gptq_factor", "mfma_peak"]
+           "attn_stats", "attn_colsum", "gptq_group", "gptq_trail", "gptq_hessian", "gptq_factor", "mfma_peak", "route_select"]
 
 
 class ExpertFmt(C.Structure):

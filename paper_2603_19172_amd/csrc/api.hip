@@ -219,6 +219,7 @@ const char* dymoe_kernel_name(int kernel)
     case DYMOE_K_GPTQ_HESSIAN: return "gptq_hessian_kernel";
     case DYMOE_K_GPTQ_FACTOR: return "gptq_chol_diag_kernel";
     case DYMOE_K_MFMA_PEAK: return "mfma_peak_kernel";
+    case DYMOE_K_ROUTE_SELECT: return "route_select_kernel";
     default: return nullptr;
     }
 }

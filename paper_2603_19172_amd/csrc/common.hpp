@@ -32,6 +32,7 @@ enum {
     DYMOE_K_GPTQ_HESSIAN,
     DYMOE_K_GPTQ_FACTOR,
     DYMOE_K_MFMA_PEAK,
+    DYMOE_K_ROUTE_SELECT,
     DYMOE_K_COUNT
 };
 

@@ -18,7 +18,7 @@ template <int TB>
 __device__ __forceinline__ void route_select_batch(float* const (&lg)[TB], float* const (&selp)[TB],
                                                    const int (&t)[TB], int E, int k, int renorm,
                                                    int32_t* __restrict__ idx, float* __restrict__ w,
-                                                   float* __restrict__ probs, float* prob_sum,
+                                                   float* probs, float* prob_sum,
                                                    int32_t* load_cnt)
 {
     if (E <= 64) route_select_regs<TB, 1>(lg, selp, t, E, k, renorm, idx, w, probs, prob_sum, load_cnt);
@@ -31,7 +31,7 @@ __device__ __forceinline__ void route_select_batch(float* const (&lg)[TB], float
 // one token
 __device__ __forceinline__ void route_select(float* lg, float* selp, int t, int E, int k, int renorm,
                                              int32_t* __restrict__ idx, float* __restrict__ w,
-                                             float* __restrict__ probs, float* prob_sum,
+                                             float* probs, float* prob_sum,
                                              int32_t* load_cnt)
 {
     float* const lgs[1] = {lg};
@@ -173,6 +173,128 @@ __global__ __launch_bounds__(kRmThreads) void route_mfma_kernel(
         float* const (&spc)[kRmBatch] = sps;
         route_select_batch<kRmBatch>(lgc, spc, ts, E, k, renorm, idx, w, probs, nullptr, nullptr);
     }
+}
+
+// The same gating when the token tiles are fewer than the compute units (2048 tokens make 64): cut by experts
+// as well.  route_logits_kernel: a workgroup of four wavefronts takes 32 tokens x 32 experts (a quarter of the
+// router rows per workgroup instead of all of them: the rows a workgroup has to pull in, not the arithmetic, are what
+// the one-kernel form spends its time on), each wavefront a quarter of every K-tile's 16-column steps; the four
+// partial tiles meet in LDS, in the operand tile's place, and are added in wavefront order; logits (+ bias) go to
+// memory.  route_select_kernel: softmax and top-k of 32 tokens per workgroup from those logits, as above.
+constexpr int kRlWaves = 4;
+constexpr int kRlThreads = kRlWaves * kWave;
+#ifndef DYMOE_RL_BK
+#define DYMOE_RL_BK 256
+#endif
+constexpr int kRlBK = DYMOE_RL_BK;       // columns per K-tile
+
+template <int BK>
+__global__ __launch_bounds__(kRlThreads) void route_logits_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg, const float* __restrict__ bias,
+    int T, int H, int E, float* __restrict__ logit)
+{
+    // rows 0..31: tokens, 32..63: router rows; 2 BK bytes each, 16-byte chunk c of row r at chunk position c ^ (r & 15)
+    constexpr int kRowBytes = 2 * BK, kRowChunks = BK / 8;
+    constexpr int kRowsPerPass = kRlThreads / kRowChunks, kPasses = 64 / kRowsPerPass;
+    __shared__ __attribute__((aligned(1024))) char tiles[64 * kRowBytes];
+    static_assert(sizeof(tiles) >= kRlWaves * 32 * 32 * sizeof(float), "the partial tiles fit in the operand tile");
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int ln = lane & 31, kb = lane >> 5;
+    const int t0 = blockIdx.x * 32, e0 = blockIdx.y * 32;
+    const int n_kt = H / BK;
+    // staging role: chunk tid % kRowChunks of rows tid / kRowChunks + kRowsPerPass u
+    const int s_row = tid / kRowChunks, s_chunk = tid % kRowChunks;
+    const uint16_t* src[kPasses];
+    uint32_t s_off[kPasses];
+#pragma unroll
+    for (int u = 0; u < kPasses; u++) {
+        const int row = s_row + kRowsPerPass * u;
+        src[u] = ((row < 32) ? x + (size_t)min(t0 + row, T - 1) * H : wg + (size_t)min(e0 + row - 32, E - 1) * H) + s_chunk * 8;
+        s_off[u] = (uint32_t)(row * kRowBytes + ((s_chunk ^ (row & 15)) << 4));
+    }
+    const uint32_t a_off = (uint32_t)((32 + ln) * kRowBytes);
+    const uint32_t b_off = (uint32_t)(ln * kRowBytes);
+    const uint32_t sw = (uint32_t)(ln & 15);
+    constexpr int kSteps = BK / 16 / kRlWaves;      // 16-column MFMA steps per wavefront and K-tile
+    float16_t acc;
+#pragma unroll
+    for (int i = 0; i < 16; i++) acc[i] = 0.0f;
+    uint4 r[kPasses];
+#pragma unroll
+    for (int u = 0; u < kPasses; u++) r[u] = load_global<uint4>(src[u]);
+    for (int kt = 0; kt < n_kt; kt++) {
+        __syncthreads();                    // the previous tile has been read by every wavefront
+#pragma unroll
+        for (int u = 0; u < kPasses; u++) *reinterpret_cast<uint4*>(tiles + s_off[u]) = r[u];
+        // the next K-tile's rows, in flight while this one is multiplied (past the end: the last one again, unused)
+        const int kn = min(kt + 1, n_kt - 1);
+#pragma unroll
+        for (int u = 0; u < kPasses; u++) r[u] = load_global<uint4>(src[u] + kn * BK);
+        __syncthreads();
+#pragma unroll
+        for (int j = kSteps * wave; j < kSteps * wave + kSteps; j++) {
+            const uint32_t c = ((uint32_t)(2 * j + kb) ^ sw) << 4;
+            const uint4 av = *reinterpret_cast<const uint4*>(tiles + a_off + c);
+            const uint4 bv = *reinterpret_cast<const uint4*>(tiles + b_off + c);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, bv),
+                                                         acc, 0, 0, 0);
+        }
+    }
+    __syncthreads();                        // the last tile has been read: its place takes the partial tiles
+    // register i: expert 8 (i / 4) + 4 kb + i % 4, token ln
+    float* part = reinterpret_cast<float*>(tiles);              // [4 wavefronts][32 tokens][32 experts]
+    float* mine = part + ((size_t)wave * 32 + ln) * 32;
+#pragma unroll
+    for (int g = 0; g < 4; g++)
+        *reinterpret_cast<float4*>(mine + 8 * g + 4 * kb) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+    __syncthreads();
+    // thread: token tid / 8, experts 4 (tid % 8) .. + 3: 128 contiguous bytes of a row of the logits per 8 lanes
+    const int tok = tid >> 3, ec = 4 * (tid & 7);
+    if (t0 + tok < T) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int e = e0 + ec + i;
+            if (e < E) {
+                const int o = tok * 32 + ec + i;
+                const float v = ((part[o] + part[1024 + o]) + part[2048 + o]) + part[3072 + o];
+                logit[(size_t)(t0 + tok) * E + e] = v + (bias ? bias[e] : 0.0f);
+            }
+        }
+    }
+}
+
+#ifndef DYMOE_RS_TB
+#define DYMOE_RS_TB 1
+#endif
+constexpr int kRsBatch = DYMOE_RS_TB;      // tokens per wavefront
+constexpr int kRsWaves = 4;
+constexpr int kRsThreads = kRsWaves * kWave;
+
+// Softmax and top-k from logits in memory.  The selection is a chain of cross-lane reductions, k rounds long, that one
+// wavefront cannot overlap with anything but itself: what shortens the pass is more wavefronts, so each takes kRsBatch
+// tokens only and reads their logits straight from memory (a lane holds every 64th expert).
+__global__ __launch_bounds__(kRsThreads) void route_select_kernel(
+    int T, int E, int k, int renorm, int32_t* __restrict__ idx, float* __restrict__ w,
+    float* probs /* in: logits, out: probabilities */)
+{
+    extern __shared__ float smem[];                                  // [4 wavefronts][kRsBatch][k], used when k > 64
+    const int wave = threadIdx.x / kWave;
+    const int t0 = (blockIdx.x * kRsWaves + wave) * kRsBatch;
+    if (t0 >= T) return;
+    float* lgs[kRsBatch];
+    float* sps[kRsBatch];
+    int ts[kRsBatch];
+#pragma unroll
+    for (int b = 0; b < kRsBatch; b++) {
+        const int t = min(t0 + b, T - 1);
+        lgs[b] = probs + (size_t)t * E;
+        sps[b] = smem + ((size_t)wave * kRsBatch + b) * k;
+        ts[b] = (t0 + b < T) ? t0 + b : -1;
+    }
+    float* const (&lgc)[kRsBatch] = lgs;
+    float* const (&spc)[kRsBatch] = sps;
+    route_select_batch<kRsBatch>(lgc, spc, ts, E, k, renorm, idx, w, probs, nullptr, nullptr);
 }
 
 // Decode step front end in one workgroup: for each of the (few) tokens the
@@ -358,6 +480,19 @@ int dymoe_route_topk(dymoe_ctx* ctx, const void* x, const void* wg, const float*
     const size_t mfma_lds = (size_t)(dymoe::kRmTokens + dymoe::kRmExperts) * dymoe::kRmBK * 2 +
                             (2 * (size_t)dymoe::kRmTokens * dymoe::kRmExperts + (size_t)dymoe::kRmTokens * E +
                              (size_t)dymoe::kRmWaves * dymoe::kRmBatch * k) * sizeof(float);
+    // few token tiles: cut by experts too and select in a second pass (the logits wait in the probs array)
+    const int token_tiles = (T + dymoe::kRmTokens - 1) / dymoe::kRmTokens;
+    const size_t select_lds = (size_t)dymoe::kRsWaves * dymoe::kRsBatch * k * sizeof(float);
+    if (T >= 128 && E >= 64 && H % dymoe::kRlBK == 0 && probs && 2 * token_tiles <= ctx->num_cu) {
+        dymoe_launch(ctx, DYMOE_K_ROUTE, dymoe::route_logits_kernel<dymoe::kRlBK>, dim3((unsigned)token_tiles, (unsigned)((E + 31) / 32)),
+                     dim3(dymoe::kRlThreads), 0, st, (const uint16_t*)x, (const uint16_t*)wg, bias, T, H, E, probs);
+        DYMOE_HIP_LAUNCH_CHECK();
+        const int per_wg = dymoe::kRsWaves * dymoe::kRsBatch;
+        dymoe_launch(ctx, DYMOE_K_ROUTE_SELECT, dymoe::route_select_kernel, dim3((unsigned)((T + per_wg - 1) / per_wg)),
+                     dim3(dymoe::kRsThreads), select_lds, st, T, E, k, renorm, idx, w, probs);
+        DYMOE_HIP_LAUNCH_CHECK();
+        return DYMOE_OK;
+    }
     if (T >= 128 && E >= 32 && H % 128 == 0 && mfma_lds <= dymoe::kRouteMfmaMaxLds) {
         dymoe_launch(ctx, DYMOE_K_ROUTE, dymoe::route_mfma_kernel, dim3((unsigned)((T + dymoe::kRmTokens - 1) / dymoe::kRmTokens)),
                      dim3(dymoe::kRmThreads), mfma_lds, st, (const uint16_t*)x, (const uint16_t*)wg, bias, T, H, E, k, renorm,

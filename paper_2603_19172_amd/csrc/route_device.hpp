@@ -92,7 +92,7 @@ template <int TB, int NC>
 __device__ __forceinline__ void route_select_regs(float* const (&lg)[TB], float* const (&selp)[TB],
                                                   const int (&t)[TB], int E, int k, int renorm,
                                                   int32_t* __restrict__ idx, float* __restrict__ w,
-                                                  float* __restrict__ probs, float* prob_sum,
+                                                  float* probs, float* prob_sum,
                                                   int32_t* load_cnt)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -195,7 +195,7 @@ __device__ __forceinline__ void route_select_regs(float* const (&lg)[TB], float*
 template <int NC>
 __device__ __forceinline__ void route_select_fixed(float* lg, float* selp, int t, int E, int k, int renorm,
                                                    int32_t* __restrict__ idx, float* __restrict__ w,
-                                                   float* __restrict__ probs, float* prob_sum, int32_t* load_cnt)
+                                                   float* probs, float* prob_sum, int32_t* load_cnt)
 {
     float* const lgs[1] = {lg};
     float* const sps[1] = {selp};

@@ -159,14 +159,14 @@ def test_tile_layout_helpers_and_pack_tiles(ctx):
 
 # --------------------------------------------------------------------- route
 
-def _check_route(ctx, x, wg, bias, k, renorm=True):
+def _check_route(ctx, x, wg, bias, k, renorm=True, min_ok=0.97):
     xt, wt = to_bf16(x), to_bf16(wg)
     bt = torch.from_numpy(bias).to(DEV) if bias is not None else None
     idx, w, p = ctx.route_topk(xt, wt, bt, k, renorm=renorm)
     sync()
     ridx, rw, rp, rl = O.route_topk(x, wg, bias, k, renorm=renorm)
     ok = margin_ok(rl, k)
-    assert ok.mean() > 0.97
+    assert ok.mean() > min_ok
     gi = idx.cpu().numpy()
     assert np.array_equal(gi[ok], ridx[ok])
     # inside the margin the order may differ; the chosen experts must still be valid
@@ -205,6 +205,16 @@ def test_route_topk_many_experts_multi_token_wavefronts(ctx):
         x, _ = synth.activations(c1)
         wg, _ = synth.router(c1)
         _check_route(ctx, x, wg[:E], None, k)
+    # logits cut by experts as well, selection as a second pass (few token tiles, H a multiple of 256): a ragged
+    # last group of experts, rows of the logits that are not 16-byte aligned, more than 64 selected experts; and
+    # the one-kernel form again where the token tiles alone fill the chip
+    for T, E, H, k, with_bias in ((200, 70, 512, 5, False), (128, 100, 256, 7, True), (130, 96, 256, 70, False),
+                                  (8200, 64, 256, 4, True)):
+        c1 = synth.scaled(synth.CONFIGS["fine_grained"], config_id=15, T=T, E=E, H=H, k=k)
+        x, _ = synth.activations(c1)
+        wg, bias = synth.router(c1)
+        # (71 adjacent gaps all above the margin: about half of the tokens)
+        _check_route(ctx, x, wg[:E], bias[:E] if with_bias else None, k, min_ok=0.3 if k > 64 else 0.97)
     # few experts, many tokens: four tokens per wavefront on the vector units
     c3 = synth.scaled(synth.CONFIGS["tiny"], config_id=14, T=1030)
     x, _ = synth.activations(c3)

@@ -165,6 +165,9 @@ size_t dymoe_workspace_bytes(int T, int H, int F, int E, int k);
  * x [T,H] bf16, wg [E,H] bf16, bias [E] fp32 or NULL,
  * idx [T,k] int32, w [T,k] fp32, probs [T,E] fp32 or NULL.
  * Limits: 1 <= k <= E <= DYMOE_MAX_EXPERTS, H multiple of 8, H <= 16384.
+ * One or two kernel launches on `stream`, by size; with two, probs holds the
+ * logits between them (its contents are undefined until the call's work is done,
+ * as for any output).
  */
 int dymoe_route_topk(dymoe_ctx* ctx, const void* x, const void* wg, const float* bias,
                      int T, int H, int E, int k, int renorm,

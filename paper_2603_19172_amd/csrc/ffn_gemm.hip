@@ -87,6 +87,7 @@ constexpr int kPlanThreads = 1024;
 constexpr int kPlanWaves = kPlanThreads / kWave;
 constexpr int kPlanPrivE = 256;        // 16 x 256 counters = 16 KiB
 constexpr int kPlanLdsTiles = 1024;    // 4 ints each = 16 KiB
+constexpr int kPlanRankStrides = 4;    // tile lists of up to 4 x 64 entries are ranked from registers
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __restrict__ idx,
                                                             const uint8_t* __restrict__ bits,
@@ -98,13 +99,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     __shared__ int32_t s_off[DYMOE_MAX_EXPERTS + 1];
     __shared__ int32_t s_tile0[DYMOE_MAX_EXPERTS + 1];       // first tile of each expert
     __shared__ int32_t s_priv[kPlanWaves * kPlanPrivE];
-    __shared__ int32_t s_draft[4 * kPlanLdsTiles];
+    __shared__ __attribute__((aligned(16))) int32_t s_draft[4 * kPlanLdsTiles];
     __shared__ uint8_t s_bits[DYMOE_MAX_EXPERTS];
     const PlanPtrs pp = plan_ptrs(plan, E, P);
     const int tid = threadIdx.x, wave = tid / kWave;
     const bool priv = E <= kPlanPrivE;
-    // tiles in expert order, before sorting
-    int32_t* draft = (max_tiles <= kPlanLdsTiles) ? s_draft : pp.tiles + 4 * (size_t)max_tiles;
     for (int e = tid; e < E; e += kPlanThreads) {
         s_count[e] = 0;
         int b = bits[e];
@@ -122,7 +121,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     __syncthreads();
     // (the expert indices of a batch of pairs are requested together and looked at afterwards: one pair at a time, every
     // iteration waited a memory latency for its own index, 16 latencies per pass on the 128-expert layer)
-    constexpr int kPlanBatch = 8;
+    constexpr int kPlanBatch = 16;
+    // up to 16 x 1024 pairs: a thread's indices stay in registers from the counting pass to the scattering pass
+    const bool one_pass = P <= kPlanBatch * kPlanThreads;
+    int es[kPlanBatch];
     auto counted = [&](int e) {
         if (e < 0 || e >= E) return false;
         const int b = s_bits[e];
@@ -132,8 +134,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
         }
         return b != 0;
     };
-    for (int p0 = tid; p0 < P; p0 += kPlanBatch * kPlanThreads) {
-        int es[kPlanBatch];
+    for (int p0 = tid; p0 < P || p0 == tid; p0 += kPlanBatch * kPlanThreads) {
 #pragma unroll
         for (int u = 0; u < kPlanBatch; u++) {
             const int p = p0 + u * kPlanThreads;
@@ -192,39 +193,68 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     }
     __syncthreads();
     const int nt_all = s_tile0[E];
-    for (int e = tid; e < E; e += kPlanThreads) {
-        const int c = s_count[e], b = s_bits[e];
-        int nt = s_tile0[e];
-        const int nt_end = nt + plan_tiles_of(c, b);
-        for (int m0 = 0; nt < nt_end; m0 += tile_m, nt++) {
-            const int rows = (nt == nt_end - 1) ? c - m0 : tile_m;     // (the last tile: up to 160 rows when tall)
-            draft[4 * nt + 0] = e;
-            draft[4 * nt + 1] = s_off[e] + m0;
-            draft[4 * nt + 2] = rows;
-            // cost key, roughly the time a workgroup spends on the tile: streaming (bf16)
-            // or dequantising (int4, int2) the weights costs the same whatever the number
-            // of tokens; the MFMA work grows with the 32-token fragments
-            draft[4 * nt + 3] = (b == 16 ? 100 : (b == 2 ? 60 : 61)) + 10 * ((rows + 31) >> 5);
+    // (written once for a draft in LDS and once for a draft in memory, so that neither is reached through flat accesses)
+    auto lay_out_and_rank = [&](int32_t* draft) {
+        for (int e = tid; e < E; e += kPlanThreads) {
+            const int c = s_count[e], b = s_bits[e];
+            int nt = s_tile0[e];
+            const int nt_end = nt + plan_tiles_of(c, b);
+            for (int m0 = 0; nt < nt_end; m0 += tile_m, nt++) {
+                const int rows = (nt == nt_end - 1) ? c - m0 : tile_m;     // (the last tile: up to 160 rows when tall)
+                draft[4 * nt + 0] = e;
+                draft[4 * nt + 1] = s_off[e] + m0;
+                draft[4 * nt + 2] = rows;
+                // cost key, roughly the time a workgroup spends on the tile: streaming (bf16)
+                // or dequantising (int4, int2) the weights costs the same whatever the number
+                // of tokens; the MFMA work grows with the 32-token fragments
+                draft[4 * nt + 3] = (b == 16 ? 100 : (b == 2 ? 60 : 61)) + 10 * ((rows + 31) >> 5);
+            }
         }
-    }
-    __syncthreads();        // (workgroup-wide visibility also of the draft kept in global memory)
-    // Longest first: workgroups are dispatched in tile order, so the cheap tiles
-    // (few tokens) fill the end of the launch instead of stretching it.
-    // Rank by counting, (key descending, position ascending): a permutation.
-    // A wavefront per tile: its lanes share the comparisons against all tiles and add up (one thread per tile walked
-    // the whole list alone, a dependent LDS read per step: 9 us for the 174 tiles of the 128-expert layer).
-    for (int i = wave; i < nt_all; i += kPlanWaves) {
+        __syncthreads();        // (workgroup-wide visibility also of the draft kept in global memory)
+        // Longest first: workgroups are dispatched in tile order, so the cheap tiles
+        // (few tokens) fill the end of the launch instead of stretching it.
+        // Rank by counting, (key descending, position ascending): a permutation.
+        // A wavefront per tile: its lanes share the comparisons against all tiles (one thread per tile walked the
+        // whole list alone, a dependent LDS read per step: 9 us for the 174 tiles of the 128-expert layer).
         const int lane = tid & (kWave - 1);
-        const int key = draft[4 * i + 3];
-        int pos = 0;
-        for (int j = lane; j < nt_all; j += kWave) {
-            const int kj = draft[4 * j + 3];
-            pos += (kj > key || (kj == key && j < i)) ? 1 : 0;
-        }
+        if (nt_all <= kPlanRankStrides * kWave) {
+            // up to 256 tiles: a lane keeps the keys of tiles lane, 64 + lane, ... in registers, counts on the vector
+            // unit and the counts meet through DPP: a trip of the loop is one LDS read long (with the keys re-read
+            // and a ballot per stride counted on the scalar unit a trip was a chain of five dependent LDS reads and
+            // as many vector-to-scalar hand-overs: 8.2 us for the 197 tiles of the 128-expert layer)
+            int keys[kPlanRankStrides];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) pos += __shfl_xor(pos, o, kWave);
-        if (lane < 4) pp.tiles[4 * pos + lane] = draft[4 * i + lane];
-    }
+            for (int u = 0; u < kPlanRankStrides; u++) {
+                const int j = u * kWave + lane;
+                keys[u] = (j < nt_all) ? draft[4 * j + 3] : -1;          // (-1: below every key)
+            }
+            for (int i = wave; i < nt_all; i += kPlanWaves) {
+                const int rec = draft[4 * i + (lane & 3)];
+                const int key = __builtin_amdgcn_readlane(rec, 3);
+                int cnt = 0;
+#pragma unroll
+                for (int u = 0; u < kPlanRankStrides; u++) {
+                    const int j = u * kWave + lane;
+                    cnt += (keys[u] > key || (keys[u] == key && j < i)) ? 1 : 0;
+                }
+                const int pos = wave_sum_dpp_i32(cnt);
+                if (lane < 4) pp.tiles[4 * pos + lane] = rec;
+            }
+        } else {
+            for (int i = wave; i < nt_all; i += kPlanWaves) {
+                const int key = draft[4 * i + 3];
+                int pos = 0;        // the same in every lane: each stride of 64 tiles adds the number of its lanes that precede i
+                for (int j0 = 0; j0 < nt_all; j0 += kWave) {
+                    const int j = j0 + lane;
+                    const int kj = (j < nt_all) ? draft[4 * j + 3] : -1;
+                    pos += __popcll(__ballot(j < nt_all && (kj > key || (kj == key && j < i))));
+                }
+                if (lane < 4) pp.tiles[4 * pos + lane] = draft[4 * i + lane];
+            }
+        }
+    };
+    if (max_tiles <= kPlanLdsTiles) lay_out_and_rank(s_draft);
+    else lay_out_and_rank(pp.tiles + 4 * (size_t)max_tiles);
     for (int e = tid; e < E; e += kPlanThreads) {
         pp.counts[e] = s_count[e];
         pp.offsets[e] = s_off[e];
@@ -235,12 +265,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const int32_t* __res
     for (int e = tid; e < E; e += kPlanThreads) s_count[e] = 0;    // reused as the scatter cursor
     __syncthreads();
     // order inside an expert is arbitrary: every row of a tile is computed independently
-    for (int p0 = tid; p0 < P; p0 += kPlanBatch * kPlanThreads) {
-        int es[kPlanBatch];
+    for (int p0 = tid; p0 < P || p0 == tid; p0 += kPlanBatch * kPlanThreads) {
+        if (!one_pass) {
 #pragma unroll
-        for (int u = 0; u < kPlanBatch; u++) {
-            const int p = p0 + u * kPlanThreads;
-            es[u] = (p < P) ? idx[p] : -1;
+            for (int u = 0; u < kPlanBatch; u++) {
+                const int p = p0 + u * kPlanThreads;
+                es[u] = (p < P) ? idx[p] : -1;
+            }
         }
 #pragma unroll
         for (int u = 0; u < kPlanBatch; u++) {

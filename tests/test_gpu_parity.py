@@ -447,6 +447,33 @@ def test_ffn_gemm_many_tiles_per_expert_and_two_k_splits(ctx):
     assert np.array_equal(y, run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM))     # and the same bits again
 
 
+@pytest.mark.parametrize("loads", [(8500, 8500, 8500, 8500), (8192, 8192, 8192, 8064)])
+def test_ffn_gemm_long_tile_lists(ctx, loads):
+    """More than 16 x 1024 pairs (the plan counts and scatters in several trips), a tile list that does not fit the
+    plan's LDS staging (kept in the workspace instead), ranked from registers (255 tiles) or in strides (268 tiles):
+    64 sampled rows against the oracle, every row against the GEMV path."""
+    T = sum(loads)
+    cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=25, T=T, H=128, F=128, E=4, k=1, tier_count=(4,))
+    x, _ = synth.activations(cfg)
+    rng = np.random.default_rng(25)
+    idx = np.repeat(np.arange(4, dtype=np.int32), loads)
+    rng.shuffle(idx)
+    idx = idx.reshape(T, 1)
+    w = (0.5 + rng.random((T, 1))).astype(np.float32)
+    bits_np = np.array((4, 16, 2, 8), np.uint8)
+    host, dev, table, keep = build_layer(cfg, bits_np, path=B.PATH_GEMM)
+    y = run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM)
+    rows = rng.choice(T, 64, replace=False)
+    rows[:2] = (0, T - 1)
+    sub = synth.scaled(cfg, T=len(rows))
+    ref = oracle_ffn(sub, x[rows], idx[rows], w[rows], bits_np, host)
+    err = rel_err_per_token(y[rows], ref)
+    host_r, dev_r, table_r, keep_r = build_layer(cfg, bits_np, path=B.PATH_GEMV)
+    gap = rel_err_per_token(y, run_ffn(ctx, cfg, x, idx, w, bits_np, table_r, B.PATH_GEMV))
+    print("gemm long tile list loads=%s: err vs oracle %.3e on %d rows, vs GEMV %.3e on all rows" % (loads, err, len(rows), gap))
+    assert err <= FFN_TOL and gap <= FFN_TOL
+
+
 @pytest.mark.parametrize("loads,fmts", [((160, 129, 33, 8), (4, 2, 4, 2)), ((161, 1, 0, 168), (2, 16, 4, 4)),
                                         ((320, 5, 150, 140), (4, 4, 8, 16)), ((276, 159, 130, 257), (4, 2, 2, 4))])
 def test_ffn_gemm_tile_boundaries(ctx, loads, fmts):

@@ -8,7 +8,7 @@
 
 namespace dymoe {
 
-constexpr int kImpThreads = 256;
+constexpr int kImpThreads = 1024;
 
 // zero-fill without hipMemsetAsync (the calls may be captured into a graph)
 __global__ void zero_i32_kernel(int32_t* a, int32_t* b, int n)
@@ -22,21 +22,26 @@ __global__ void zero_i32_kernel(int32_t* a, int32_t* b, int n)
 
 // Prefill: a token is a heavy hitter when fewer than k_hh tokens precede it in
 // the order (score descending, token index ascending).  kImpLanes adjacent
-// lanes share one token: all T scores pass through LDS in tiles, each lane
-// compares the token against its eighth of every tile (four scores per read),
-// and the partial counts are added across the lanes.  The token's first lane
+// lanes share one token: all T scores pass through LDS, 2048 per trip (a
+// thread's two requested together), each lane compares the token against its
+// share of every 1024 of them (four scores per read), and the partial counts
+// are added across the lanes.  (32 lanes per token and 1024 threads: with 8
+// lanes and 256 threads the 2048 tokens of the 128-expert layer kept 256
+// wavefronts busy on a chip of 1024 SIMDs, a memory latency per 256 scores,
+// and four times as many workgroups queued up at the E global counters.)  The token's first lane
 // then adds its k routed experts to the workgroup's LDS histograms (load and,
 // if heavy, importance); the workgroup adds its non-zero bins to the global
 // ones, which the caller has zeroed.  with_importance = 0: only the load
 // histogram (decode).
-constexpr int kImpLanes = 8;
+constexpr int kImpLanes = 32;
 constexpr int kImpTokens = kImpThreads / kImpLanes;      // tokens per workgroup
+constexpr int kImpStage = 2 * kImpThreads;               // scores in LDS per trip
 
 __global__ __launch_bounds__(kImpThreads) void importance_prefill_kernel(
     const int32_t* __restrict__ idx, const float* __restrict__ score, int T, int E, int k,
     int k_hh, int with_importance, int32_t* __restrict__ importance, int32_t* __restrict__ load)
 {
-    __shared__ __attribute__((aligned(16))) float tile[kImpThreads];
+    __shared__ __attribute__((aligned(16))) float tile[kImpStage];
     __shared__ int32_t s_load[DYMOE_MAX_EXPERTS];
     __shared__ int32_t s_imp[DYMOE_MAX_EXPERTS];
     for (int e = threadIdx.x; e < E; e += kImpThreads) {
@@ -50,21 +55,32 @@ __global__ __launch_bounds__(kImpThreads) void importance_prefill_kernel(
         const float mine = (t < T) ? score[t] : 0.0f;
         int before = 0;
         constexpr int kSpan = kImpThreads / kImpLanes;     // scores of a tile that one lane looks at
-        for (int base = 0; base < T; base += kImpThreads) {
-            const int u = base + threadIdx.x;
-            // slots past the end hold -inf at an index past every token: never counted
-            tile[threadIdx.x] = (u < T) ? score[u] : -INFINITY;
-            __syncthreads();
+        for (int base = 0; base < T; base += kImpStage) {
+            // a thread's eight scores of this trip are requested together (one at a time, every 256 scores cost a
+            // memory latency: eight of them for the 2048 tokens of the 128-expert layer)
+            float v[kImpStage / kImpThreads];
 #pragma unroll
-            for (int j = part * kSpan; j < (part + 1) * kSpan; j += 4) {
-                const float4 s4 = *reinterpret_cast<const float4*>(tile + j);
-                const int u0 = base + j;
-                before += (s4.x > mine || (s4.x == mine && u0 + 0 < t)) ? 1 : 0;
-                before += (s4.y > mine || (s4.y == mine && u0 + 1 < t)) ? 1 : 0;
-                before += (s4.z > mine || (s4.z == mine && u0 + 2 < t)) ? 1 : 0;
-                before += (s4.w > mine || (s4.w == mine && u0 + 3 < t)) ? 1 : 0;
+            for (int u = 0; u < kImpStage / kImpThreads; u++) {
+                const int i = base + u * kImpThreads + (int)threadIdx.x;
+                // slots past the end hold -inf at an index past every token: never counted
+                v[u] = (i < T) ? score[i] : -INFINITY;
             }
+            __syncthreads();                               // the previous trip's scores have been read
+#pragma unroll
+            for (int u = 0; u < kImpStage / kImpThreads; u++) tile[u * kImpThreads + threadIdx.x] = v[u];
             __syncthreads();
+            const int pieces = min(kImpStage / kImpThreads, (T - base + kImpThreads - 1) / kImpThreads);
+            for (int piece = 0; piece < pieces; piece++) {
+#pragma unroll
+                for (int j = part * kSpan; j < (part + 1) * kSpan; j += 4) {
+                    const float4 s4 = *reinterpret_cast<const float4*>(tile + piece * kImpThreads + j);
+                    const int u0 = base + piece * kImpThreads + j;
+                    before += (s4.x > mine || (s4.x == mine && u0 + 0 < t)) ? 1 : 0;
+                    before += (s4.y > mine || (s4.y == mine && u0 + 1 < t)) ? 1 : 0;
+                    before += (s4.z > mine || (s4.z == mine && u0 + 2 < t)) ? 1 : 0;
+                    before += (s4.w > mine || (s4.w == mine && u0 + 3 < t)) ? 1 : 0;
+                }
+            }
         }
 #pragma unroll
         for (int o = 1; o < kImpLanes; o <<= 1) before += __shfl_xor(before, o, kWave);

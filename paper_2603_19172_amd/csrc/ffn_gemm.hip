@@ -23,6 +23,10 @@
 //    compute unit: the two wavefronts of a SIMD belong to different workgroups,
 //    so one's barrier, waits, prologue and epilogue are covered by the other's
 //    MFMA work.
+//  * Results leave through LDS: in the MFMA result layout a lane holds a few
+//    outputs of one token's row, so stores made from it would touch 32 rows per
+//    instruction; the token-tile buffers, free after the K loop, turn the
+//    rows round so that 16 lanes store 256 contiguous bytes of one row.
 #include <math.h>
 
 #include "common.hpp"

@@ -228,6 +228,24 @@ def test_route_topk_many_experts_multi_token_wavefronts(ctx):
         _check_route(ctx, x, wg, None, 2)
 
 
+def test_route_topk_without_probabilities_takes_the_one_kernel_form_and_agrees(ctx):
+    """The two-pass router keeps its logits in the caller's probs array; a caller that passes none gets the
+    one-kernel form.  Same experts (outside the margin) and the same gate weights either way."""
+    c = synth.scaled(synth.CONFIGS["fine_grained"], config_id=16, T=700)
+    x, _ = synth.activations(c)
+    wg, bias = synth.router(c)
+    xt, wt, bt = to_bf16(x), to_bf16(wg), torch.from_numpy(bias).to(DEV)
+    idx2, w2, p2 = ctx.route_topk(xt, wt, bt, c.k)
+    idx1, w1, p1 = ctx.route_topk(xt, wt, bt, c.k, probs=False)
+    sync()
+    assert p1 is None and p2 is not None
+    _, _, _, rl = O.route_topk(x, wg, bias, c.k)
+    ok = margin_ok(rl, c.k)
+    assert ok.mean() > 0.97
+    assert np.array_equal(idx1.cpu().numpy()[ok], idx2.cpu().numpy()[ok])
+    assert np.allclose(w1.cpu().numpy()[ok], w2.cpu().numpy()[ok], rtol=2e-4, atol=1e-7)
+
+
 def test_route_empty(ctx):
     x = torch.zeros((0, 256), dtype=torch.bfloat16, device=DEV)
     wg = torch.zeros((8, 256), dtype=torch.bfloat16, device=DEV)

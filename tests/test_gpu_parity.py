@@ -465,6 +465,27 @@ def test_ffn_gemm_many_tiles_per_expert_and_two_k_splits(ctx):
     assert np.array_equal(y, run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM))     # and the same bits again
 
 
+def test_ffn_gemm_partial_column_blocks(ctx):
+    """H = 384: the down projection's second column block has two wavefronts with strips and two without; F = 640:
+    five column blocks in the up projections, five K-tiles in the down projection.  Every format, ragged loads."""
+    loads = (150, 97, 64, 131, 40)
+    T = sum(loads)
+    cfg = synth.scaled(synth.CONFIGS["tiny"], config_id=26, T=T, H=384, F=640, E=5, k=1, tier_count=(5,))
+    x, _ = synth.activations(cfg)
+    rng = np.random.default_rng(26)
+    idx = np.repeat(np.arange(5, dtype=np.int32), loads)
+    rng.shuffle(idx)
+    idx = idx.reshape(T, 1)
+    w = (0.5 + rng.random((T, 1))).astype(np.float32)
+    bits_np = np.array((2, 16, 8, 4, 16), np.uint8)
+    host, dev, table, keep = build_layer(cfg, bits_np, path=B.PATH_GEMM)
+    ref = oracle_ffn(cfg, x, idx, w, bits_np, host)
+    y = run_ffn(ctx, cfg, x, idx, w, bits_np, table, B.PATH_GEMM)
+    err = rel_err_per_token(y, ref)
+    print("gemm partial column blocks: err=%.3e" % err)
+    assert err <= FFN_TOL
+
+
 @pytest.mark.parametrize("loads", [(8500, 8500, 8500, 8500), (8192, 8192, 8192, 8064)])
 def test_ffn_gemm_long_tile_lists(ctx, loads):
     """More than 16 x 1024 pairs (the plan counts and scatters in several trips), a tile list that does not fit the

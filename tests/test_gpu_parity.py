@@ -265,8 +265,9 @@ def test_token_score_norm(ctx):
 
 def test_importance_prefill_bit_exact(ctx):
     rng = np.random.default_rng(4)
-    for T, E, k, k_hh in ((16, 8, 2, 1), (700, 128, 8, 35), (513, 8, 2, 513), (300, 16, 4, 0),
-                           (2048, 128, 8, 103), (5000, 16, 4, 250)):   # the last one takes the multi-workgroup kernels
+    # up to 32 tokens: one workgroup, one launch; beyond: zero-fill and the many-workgroup kernel
+    for T, E, k, k_hh in ((16, 8, 2, 1), (32, 8, 2, 3), (33, 8, 2, 3), (200, 16, 4, 10), (700, 128, 8, 35),
+                           (513, 8, 2, 513), (300, 16, 4, 0), (2048, 128, 8, 103), (5000, 16, 4, 250)):
         idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
         score = (rng.standard_normal(T) ** 2).astype(np.float32)
         score[T // 2] = score[T // 3]          # an exact tie
@@ -280,7 +281,7 @@ def test_importance_prefill_bit_exact(ctx):
 
 def test_importance_decode(ctx):
     rng = np.random.default_rng(6)
-    for T in (1, 3):
+    for T in (1, 3, 40):
         p = rng.random((T, 8)).astype(np.float32)
         p /= p.sum(1, keepdims=True)
         idx = np.argsort(-p, axis=1)[:, :2].astype(np.int32)
